@@ -1,0 +1,264 @@
+"""CPU oracle for decode attention over a low-rank latent KV-cache (Palu).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain, obviously-correct
+definition that the HIP kernels are checked against.  Only the tests, the
+smoke check and the benchmark's CPU-baseline leg may import it; the product
+package never does, and nothing here imports the product package.
+
+Everything is numpy in float64 except the quantizer, which the paper defines
+as an integer-valued function and which is therefore evaluated in IEEE float32
+so that its integer decisions are reproducible bit for bit.
+
+Conventions (row-vector form used by the paper everywhere except one display):
+    h = x . A          latent, A in R^{d x r}               (Sec. 3.1)
+    y = h . B          reconstruction, B in R^{r x (s*d_h)} (Sec. 3.2.3)
+    head u of group j owns columns [u*d_h, (u+1)*d_h) of y.
+
+Parity status of each function is given in its docstring.  The paper prints no
+worked numeric example of latents, scores or outputs, so the attention output
+values themselves are pinned only through special cases, identities and brute
+force (see tests/test_oracle_pins.py), not through printed numbers.
+"""
+
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "rope_inv_freq", "rope_rotate", "unpack_int4", "pack_int4",
+    "dequant_latent", "quant_latent", "encode", "reconstruct",
+    "attn_decode", "attn_decode_scores", "softmax_rows",
+    "storage_ratio", "kv_cache_bytes", "reconstruction_macs_per_token",
+]
+
+
+# --------------------------------------------------------------------------
+# RoPE (Sec. 3.1.2 says only "RoPE"; the model family is Llama via the
+# Huggingface library (Sec. 4.1), whose convention pairs feature f with
+# feature f + d_h/2 and uses frequency theta^(-2f/d_h)).
+# --------------------------------------------------------------------------
+
+def rope_inv_freq(d_head: int, theta: float) -> np.ndarray:
+    """Angular frequency of pair f, f = 0 .. d_head/2 - 1 (float64)."""
+    f = np.arange(d_head // 2, dtype=np.float64)
+    return np.float64(theta) ** (-2.0 * f / np.float64(d_head))
+
+
+def rope_rotate(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
+    """Rotate the last axis of x (length d_head) by the angles of `pos`.
+
+    x   [..., d_head] float64
+    pos broadcastable to x.shape[:-1], integer positions
+    Pair (x[f], x[f + d_head/2]) is rotated by angle pos * inv_freq[f].
+    theta <= 0 disables the rotation (non-RoPE attention, Sec. 3.1.2 last
+    paragraph).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    if theta <= 0:
+        return x.copy()
+    d = x.shape[-1]
+    half = d // 2
+    phi = np.asarray(pos, dtype=np.float64)[..., None] * rope_inv_freq(d, theta)
+    c, s = np.cos(phi), np.sin(phi)
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+# --------------------------------------------------------------------------
+# int4 latents (Appendix A: asymmetric uniform quantization, B = 4 bits)
+# --------------------------------------------------------------------------
+
+def unpack_int4(packed: np.ndarray) -> np.ndarray:
+    """[..., n] uint8 -> [..., 2n] uint8 codes; low nibble = even channel."""
+    packed = np.asarray(packed, dtype=np.uint8)
+    out = np.empty(packed.shape[:-1] + (packed.shape[-1] * 2,), dtype=np.uint8)
+    out[..., 0::2] = packed & 0x0F
+    out[..., 1::2] = packed >> 4
+    return out
+
+
+def pack_int4(codes: np.ndarray) -> np.ndarray:
+    """[..., 2n] codes in 0..15 -> [..., n] uint8; low nibble = even channel."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    assert codes.shape[-1] % 2 == 0
+    assert codes.max(initial=0) <= 15
+    return (codes[..., 0::2] | (codes[..., 1::2] << 4)).astype(np.uint8)
+
+
+def dequant_latent(packed, scale, zero, block: int = 128) -> np.ndarray:
+    """Dequantize packed int4 latents to float64.
+
+    packed [..., R/2] uint8, scale/zero [..., R/block] (float16 values).
+    h[c] = (code[c] - zero[c // block]) * scale[c // block], evaluated in
+    float64 from the stored float16 scale and zero-point (Appendix A read
+    backwards; the benchmark configuration fixes one (scale, zero) per token
+    per `block` channels).
+    """
+    codes = unpack_int4(packed).astype(np.float64)
+    s = np.repeat(np.asarray(scale, dtype=np.float64), block, axis=-1)
+    z = np.repeat(np.asarray(zero, dtype=np.float64), block, axis=-1)
+    return (codes - z) * s
+
+
+def quant_latent(h: np.ndarray, block: int = 128):
+    """Asymmetric uniform 4-bit quantization of latents (Appendix A).
+
+    h [..., R] with values exactly representable in float16/bfloat16 (they are
+    converted to float32 exactly).  Per (row, block of `block` channels):
+
+        s  = (max - min) / 15                  float32, then rounded to float16
+             (s == 0 -> s = 1: a constant block quantizes to code 0 + z)
+        z  = round(-min / s)                   round-half-even, float32 divide,
+             clamped to +-65504 and rounded to float16 (the storage format);
+             the *stored* z is the one used for the codes
+        q  = clamp(round(x / s) + z, 0, 15)
+
+    Returns (packed [..., R/2] uint8, scale [..., R/block] float16,
+             zero [..., R/block] float16).
+    Every step is a single correctly-rounded IEEE float32 operation, so a GPU
+    doing the same steps in float32 must agree bit for bit.
+    """
+    h32 = np.asarray(h, dtype=np.float32)
+    R = h32.shape[-1]
+    assert R % block == 0 and block % 2 == 0
+    hb = h32.reshape(h32.shape[:-1] + (R // block, block))
+    mn = hb.min(axis=-1)
+    mx = hb.max(axis=-1)
+    s32 = (mx - mn) / np.float32(15.0)
+    s16 = s32.astype(np.float16)
+    s16 = np.where(s16 == 0, np.float16(1.0), s16).astype(np.float16)
+    sf = s16.astype(np.float32)
+    z = np.rint((-mn) / sf)
+    z = np.clip(z, np.float32(-65504.0), np.float32(65504.0))
+    z16 = z.astype(np.float16)
+    zf = z16.astype(np.float32)
+    q = np.rint(hb / sf[..., None]) + zf[..., None]
+    q = np.clip(q, np.float32(0.0), np.float32(15.0))
+    codes = q.astype(np.uint8).reshape(h32.shape)
+    return pack_int4(codes), s16, z16
+
+
+# --------------------------------------------------------------------------
+# Encode: h = x . A  (Sec. 3.1, first display; Sec. 3.2.3 for the grouped A)
+# --------------------------------------------------------------------------
+
+def encode(x: np.ndarray, A: np.ndarray) -> np.ndarray:
+    """Latent h = x . A in float64 (the caller rounds to the cache dtype).
+
+    x [T, d], A [d, R]; group j's A_gj occupies columns rank_off[j]..rank_off[j+1]
+    of A, so the grouped down-projection is a single matrix product.
+    """
+    return np.asarray(x, dtype=np.float64) @ np.asarray(A, dtype=np.float64)
+
+
+# --------------------------------------------------------------------------
+# Reconstruction y = h . B  (Sec. 3.2.3 display) and attention (Sec. 2.1)
+# --------------------------------------------------------------------------
+
+def _group_matrix(B_flat, j, group_head_off, rank_off, d_head):
+    """View of group j's reconstruction matrix [r_j, s_j*d_head] inside the
+    concatenated buffer (group j starts at sum_{i<j} r_i*s_i*d_head)."""
+    off = 0
+    for i in range(j):
+        off += (rank_off[i + 1] - rank_off[i]) * (group_head_off[i + 1] - group_head_off[i]) * d_head
+    r = rank_off[j + 1] - rank_off[j]
+    w = (group_head_off[j + 1] - group_head_off[j]) * d_head
+    return np.asarray(B_flat).reshape(-1)[off:off + r * w].reshape(r, w)
+
+
+def reconstruct(H: np.ndarray, B_flat, group_head_off, rank_off, d_head: int) -> np.ndarray:
+    """Full-width states from latents: [y_{j,1} .. y_{j,s}] = h_gj . B_gj.
+
+    H [L, R] float64 latents of one sequence, returns [L, n_heads*d_head].
+    """
+    H = np.asarray(H, dtype=np.float64)
+    n_groups = len(group_head_off) - 1
+    n_heads = group_head_off[-1]
+    Y = np.empty((H.shape[0], n_heads * d_head), dtype=np.float64)
+    for j in range(n_groups):
+        Bj = _group_matrix(B_flat, j, group_head_off, rank_off, d_head).astype(np.float64)
+        cols = slice(rank_off[j], rank_off[j + 1])
+        h0, h1 = group_head_off[j], group_head_off[j + 1]
+        Y[:, h0 * d_head:h1 * d_head] = H[:, cols] @ Bj
+    return Y
+
+
+def softmax_rows(s: np.ndarray) -> np.ndarray:
+    """Softmax over the last axis, max-subtracted, float64."""
+    s = np.asarray(s, dtype=np.float64)
+    e = np.exp(s - s.max(axis=-1, keepdims=True))
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attn_decode_scores(q, q_pos, Hk, Bk, group_head_off, k_rank_off, d_head,
+                       rope_theta, k_pos=None, seq_lens=None):
+    """Pre-softmax scores q'_i . K'_{i,t} / sqrt(d_h) as a list over batch of
+    [n_heads, L_b] float64 arrays (Eq. 2 numerator with RoPE on q and K,
+    Sec. 3.1.2)."""
+    q = np.asarray(q, dtype=np.float64)
+    Bsz, n_heads, _ = q.shape
+    out = []
+    for b in range(Bsz):
+        L = int(seq_lens[b]) if seq_lens is not None else Hk.shape[1]
+        pos = np.arange(L) if k_pos is None else np.asarray(k_pos)[:L]
+        K = reconstruct(np.asarray(Hk[b, :L], dtype=np.float64), Bk, group_head_off, k_rank_off, d_head)
+        K = rope_rotate(K.reshape(L, n_heads, d_head), pos[:, None], rope_theta)      # [L, n, d_h]
+        qr = rope_rotate(q[b], np.full((n_heads,), int(np.asarray(q_pos)[b])), rope_theta)  # [n, d_h]
+        out.append(np.einsum("lnd,nd->nl", K, qr) / np.sqrt(np.float64(d_head)))
+    return out
+
+
+def attn_decode(q, q_pos, Hk, Hv, Bk, Bv, group_head_off, k_rank_off, v_rank_off,
+                d_head: int, rope_theta: float, k_pos=None, seq_lens=None) -> np.ndarray:
+    """One decode step of attention over the latent cache, by the definition.
+
+    q   [B, n_heads, d_head]  pre-RoPE query (Sec. 4.5.2 times the kernel from
+        the pre-RoPE query)
+    q_pos [B] position of the query token
+    Hk  [B, Lmax, R_k], Hv [B, Lmax, R_v]  latents (already dequantized when
+        the cache is int4: the caller passes dequant_latent(...))
+    Bk, Bv  concatenated per-group reconstruction matrices
+    k_pos [Lmax] or None (token t sits at position t)
+    seq_lens [B] or None (all Lmax rows are attended)
+
+    Steps, in the paper's order: K = H_k B_k and V = H_v B_v fully materialised
+    (Sec. 3.2.3), RoPE on K rows and on q (Sec. 3.1.2), p = softmax(q K^T /
+    sqrt(d_h)), a = p V (Eq. 2).  Returns [B, n_heads, d_head] float64.
+    No causal mask: every cached row up to seq_lens[b] is attended.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    Bsz, n_heads, _ = q.shape
+    scores = attn_decode_scores(q, q_pos, Hk, Bk, group_head_off, k_rank_off, d_head,
+                                rope_theta, k_pos, seq_lens)
+    out = np.empty((Bsz, n_heads, d_head), dtype=np.float64)
+    for b in range(Bsz):
+        L = scores[b].shape[1]
+        V = reconstruct(np.asarray(Hv[b, :L], dtype=np.float64), Bv, group_head_off, v_rank_off, d_head)
+        V = V.reshape(L, n_heads, d_head)
+        p = softmax_rows(scores[b])                       # [n, L]
+        out[b] = np.einsum("nl,lnd->nd", p, V)
+    return out
+
+
+# --------------------------------------------------------------------------
+# Closed forms the paper prints (used as pins and by the benchmark's counters)
+# --------------------------------------------------------------------------
+
+def storage_ratio(m: float, n: float, r: float) -> float:
+    """(m r + r n) / (m n): size of A and B relative to W (Sec. 2.2)."""
+    return (m * r + r * n) / (m * n)
+
+
+def kv_cache_bytes(n_layers: int, seq_len: int, hidden: int, keep_fraction: float, bits: float) -> float:
+    """Bytes of K plus V cache: 2 * layers * L * (hidden * keep) * bits / 8
+    (Table 2's size column; scale and zero-point overhead not counted)."""
+    return 2.0 * n_layers * seq_len * hidden * keep_fraction * bits / 8.0
+
+
+def reconstruction_macs_per_token(group_head_off, rank_off, d_head: int) -> int:
+    """Multiply-accumulates to rebuild all heads of one token:
+    sum_j r_j * s_j * d_h  (Sec. 3.2.2 'High Inference Overhead', Sec. 3.2.3)."""
+    total = 0
+    for j in range(len(group_head_off) - 1):
+        total += (rank_off[j + 1] - rank_off[j]) * (group_head_off[j + 1] - group_head_off[j]) * d_head
+    return int(total)
