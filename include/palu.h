@@ -1,0 +1,173 @@
+/*
+ * palu.h - C ABI of the MI355X (gfx950) decode-attention library for a
+ * low-rank latent KV-cache (Palu, arXiv 2407.21118).
+ *
+ * Notation follows the paper: n heads of width d_h, groups of s heads
+ * (Sec. 3.2.3); per group j a down-projection A_gj in R^{d x r_j} and a
+ * reconstruction matrix B_gj in R^{r_j x (s_j d_h)}; the cache holds latents
+ * h = x A (Sec. 3.1) instead of keys and values; row-vector convention
+ * (h = x A, y = h B) throughout.
+ *
+ * Conventions common to every entry point
+ *   - plain C, every function returns a status (PALU_OK or a negative code),
+ *     never throws, never aborts;
+ *   - pointers marked DEVICE are HBM addresses on the current HIP device and
+ *     stay owned by the caller; pointers marked HOST are ordinary memory read
+ *     during the call;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising;
+ *   - the library allocates no device memory: scratch space comes from a
+ *     caller-provided workspace whose size is obtained from the matching
+ *     *_workspace_bytes query;
+ *   - arguments are validated on the host before anything is launched; on an
+ *     error nothing is enqueued and outputs are untouched.
+ */
+#ifndef PALU_H
+#define PALU_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  PALU_OK = 0,
+  PALU_ERR_INVALID_ARG = -1,        /* NULL / negative / inconsistent argument            */
+  PALU_ERR_UNSUPPORTED = -2,        /* valid request this build has no kernel for         */
+  PALU_ERR_WORKSPACE_TOO_SMALL = -3,
+  PALU_ERR_HIP = -4                 /* a HIP runtime call failed (launch, attribute query) */
+};
+
+enum { PALU_F16 = 0, PALU_BF16 = 1, PALU_I4 = 2 };
+
+/* Limits of this build. */
+enum {
+  PALU_MAX_HEADS = 256,
+  PALU_MAX_GROUPS = 64,
+  PALU_D_HEAD = 128,          /* only head width supported                                */
+  PALU_RANK_MULTIPLE = 32,    /* every group rank must be a multiple of this              */
+  PALU_MAX_RANK = 2048        /* per group                                                */
+};
+
+/*
+ * One compressed attention layer (Sec. 3.2.3, G-LRD; group size 1 is M-LRD,
+ * one group of all heads is J-LRD).
+ *   group j owns heads  [group_head_off[j], group_head_off[j+1])  - contiguous -
+ *   and latent columns  [k_rank_off[j], k_rank_off[j+1]) of a key-latent row,
+ *                       [v_rank_off[j], v_rank_off[j+1]) of a value-latent row.
+ *   Head u of group j (u counted inside the group) owns columns
+ *   [u d_h, (u+1) d_h) of B_gj.
+ * The three offset arrays are HOST arrays of n_groups+1 int32, starting at 0.
+ */
+typedef struct palu_layer_desc {
+  int32_t n_heads;
+  int32_t d_head;
+  int32_t n_groups;
+  const int32_t* group_head_off;   /* HOST [n_groups+1] */
+  const int32_t* k_rank_off;       /* HOST [n_groups+1] */
+  const int32_t* v_rank_off;       /* HOST [n_groups+1] */
+  int32_t act_dtype;               /* PALU_F16 | PALU_BF16: q, x, A, B_k, B_v, unquantized latents */
+  int32_t k_latent_dtype;          /* act_dtype or PALU_I4 */
+  int32_t v_latent_dtype;          /* act_dtype or PALU_I4 */
+  int32_t quant_block;             /* channels per (scale, zero) pair; 128 */
+  float rope_theta;                /* RoPE base, e.g. 10000; <= 0: no rotation */
+} palu_layer_desc;
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char* palu_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int palu_version(void);
+
+/*
+ * RoPE angle table (Sec. 3.1.2: RoPE acts on queries and keys before their
+ * product).  For position p and pair f < d_h/2 the table stores, as float16,
+ * cos(p w_f) and sin(p w_f) with w_f = theta^(-2f/d_h), computed in float64;
+ * the pairing is (f, f + d_h/2) as in the Huggingface Llama implementation the
+ * paper builds on (Sec. 4.1).  The row order inside a position is private to
+ * the library.  One table serves every layer and step of a model; build it
+ * once for the longest position that will occur.  theta <= 0 fills the table
+ * with cos = 1, sin = 0.
+ *   n_pos     number of positions 0 .. n_pos-1
+ *   table     DEVICE, palu_rope_table_bytes(...) bytes, 256-byte aligned
+ */
+int palu_rope_table_bytes(int32_t d_head, int32_t n_pos, size_t* out_bytes);
+int palu_rope_table_init(float rope_theta, int32_t d_head, int32_t n_pos, void* table, void* stream);
+
+/*
+ * Down-projection h = x A of new tokens into the latent cache (Sec. 3.1,
+ * first display; grouped A of Sec. 3.2.3: group j is columns rank_off[j].. of
+ * A, so all groups are one product).
+ *   which       0 = key side (k_rank_off), 1 = value side (v_rank_off)
+ *   x           DEVICE [n_tok, n_heads*d_head] act_dtype, row-major
+ *   A           DEVICE [n_heads*d_head, R] act_dtype, row-major, R = rank_off[n_groups]
+ *   latent      DEVICE base of the cache, act_dtype; token t is written to
+ *               latent + dst_row[t]*row_stride_elems, R contiguous elements
+ *   dst_row     DEVICE int32 [n_tok] row index per token (lets several
+ *               sequences append in one call), or NULL for row t
+ *   workspace   DEVICE scratch of palu_encode_workspace_bytes(...) bytes
+ * Accumulates in float32, rounds once to act_dtype.  Writes only the rows named.
+ */
+int palu_encode_workspace_bytes(const palu_layer_desc* desc, int which, int32_t n_tok, size_t* out_bytes);
+int palu_encode(const palu_layer_desc* desc, int which, const void* x, int32_t n_tok, const void* A,
+                void* latent, int64_t row_stride_elems, const int32_t* dst_row,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Asymmetric uniform 4-bit quantization of latent rows (Appendix A with B = 4),
+ * one (scale, zero) pair per token per quant_block channels:
+ *     s = fp16((max - min) / 15), s == 0 -> 1;   z = fp16(clamp(rint(-min / s), +-65504));
+ *     code = clamp(rint(x / s) + z, 0, 15)        (float32 arithmetic, ties to even)
+ *   latent      DEVICE act_dtype, token t at latent + t*row_stride_elems, R elements
+ *   codes       DEVICE uint8 [n_tok, R/2]; byte c/2 holds channel c (c even) in its
+ *               low nibble and channel c+1 in its high nibble
+ *   scale,zero  DEVICE float16 [n_tok, R/quant_block]
+ * R must be a multiple of quant_block.
+ */
+int palu_quant_latent(const palu_layer_desc* desc, int which, const void* latent, int64_t row_stride_elems,
+                      int32_t n_tok, uint8_t* codes, void* scale, void* zero, void* stream);
+
+/*
+ * One decode step of attention over the latent cache for `batch` sequences
+ * (Sec. 2.1 Eq. 2 with K = RoPE(H_k B_k) rebuilt on the fly, Sec. 3.1.2 and
+ * Appendix B; values contracted in latent space first, (p H_v) B_v, Eq. 4):
+ *     out[b,i] = softmax_t( RoPE(q[b,i], q_pos[b]) . RoPE(H_k[b,t] B_k, k_pos[t])_i / sqrt(d_h) ) H_v[b] B_v |_i
+ * over t in [0, seq_lens[b]).  No causal mask: every cached row is attended.
+ *
+ *   q          DEVICE [batch, n_heads, d_head] act_dtype, before RoPE (Sec. 4.5.2)
+ *   q_pos      DEVICE int32 [batch] position of each query token
+ *   hk, hv     DEVICE latents [batch, max_seq, R] act_dtype, or packed codes
+ *              [batch, max_seq, R/2] uint8 when the side is PALU_I4; sequence b
+ *              starts at b*max_seq rows
+ *   h*_scale, h*_zero   DEVICE float16 [batch, max_seq, R/quant_block] (PALU_I4 side), else NULL
+ *   k_pos      DEVICE int32 [max_seq] position of cached row t, or NULL (row t is position t).
+ *              Positions must lie in [0, rope_table_len); the kernels clamp to that
+ *              range to stay in bounds, results for out-of-range positions are undefined
+ *   seq_lens   DEVICE int32 [batch] rows to attend per sequence, each in [1, seq_len],
+ *              or NULL (all seq_len rows)
+ *   seq_len    upper bound of rows attended (1 <= seq_len <= max_seq)
+ *   Bk, Bv     DEVICE act_dtype; group j at element offset sum_{i<j} r_i s_i d_h,
+ *              row-major [r_j, s_j d_h]
+ *   rope_table DEVICE table from palu_rope_table_init (same theta, d_head),
+ *              rope_table_len positions; with k_pos == NULL needs rope_table_len >= seq_len
+ *   out        DEVICE float32 [batch, n_heads, d_head]
+ *   workspace  DEVICE scratch, at least palu_attn_decode_workspace_bytes(desc, batch, max_seq)
+ *              bytes, 256-byte aligned; contents need not be preserved between calls.
+ *              Calls sharing a workspace must be ordered on one stream.
+ */
+int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch, int32_t max_seq, size_t* out_bytes);
+int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                     const void* q, const int32_t* q_pos,
+                     const void* hk, const void* hk_scale, const void* hk_zero,
+                     const void* hv, const void* hv_scale, const void* hv_zero,
+                     const int32_t* k_pos, const int32_t* seq_lens,
+                     const void* Bk, const void* Bv,
+                     const void* rope_table, int32_t rope_table_len,
+                     float* out, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PALU_H */

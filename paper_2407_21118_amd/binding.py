@@ -1,0 +1,216 @@
+"""ctypes binding of include/palu.h: argument marshalling only.
+
+Functions carry the names of the C entry points.  Tensors are torch tensors
+on the GPU; the binding passes their data pointers and the current HIP
+stream.  There is no fallback: if the shared library is missing the import of
+a symbol raises, and a non-zero status raises PaluError.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+PALU_F16, PALU_BF16, PALU_I4 = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libpalu_hip.so"
+_lib = None
+
+
+class PaluError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        try:
+            text = load_library().palu_status_string(status).decode()
+        except Exception:
+            text = "?"
+        super().__init__(f"{where} failed with status {status} ({text})")
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [
+        ("n_heads", ctypes.c_int32), ("d_head", ctypes.c_int32), ("n_groups", ctypes.c_int32),
+        ("group_head_off", ctypes.POINTER(ctypes.c_int32)),
+        ("k_rank_off", ctypes.POINTER(ctypes.c_int32)),
+        ("v_rank_off", ctypes.POINTER(ctypes.c_int32)),
+        ("act_dtype", ctypes.c_int32), ("k_latent_dtype", ctypes.c_int32), ("v_latent_dtype", ctypes.c_int32),
+        ("quant_block", ctypes.c_int32), ("rope_theta", ctypes.c_float),
+    ]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """Load libpalu_hip.so (built in-tree by paper_2407_21118_amd.build).  torch
+    is imported first so that the library binds to the HIP runtime torch uses."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    import torch  # noqa: F401  (loads the HIP runtime the streams and tensors belong to)
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2407_21118_amd.build`")
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    dp = ctypes.POINTER(_Desc)
+    szp = ctypes.POINTER(ctypes.c_size_t)
+    lib.palu_status_string.restype = ctypes.c_char_p
+    lib.palu_status_string.argtypes = [ctypes.c_int]
+    lib.palu_version.restype = ctypes.c_int
+    lib.palu_version.argtypes = []
+    lib.palu_rope_table_bytes.argtypes = [i32, i32, szp]
+    lib.palu_rope_table_init.argtypes = [ctypes.c_float, i32, i32, vp, vp]
+    lib.palu_encode_workspace_bytes.argtypes = [dp, ctypes.c_int, i32, szp]
+    lib.palu_encode.argtypes = [dp, ctypes.c_int, vp, i32, vp, vp, i64, vp, vp, sz, vp]
+    lib.palu_quant_latent.argtypes = [dp, ctypes.c_int, vp, i64, i32, vp, vp, vp, vp]
+    lib.palu_attn_decode_workspace_bytes.argtypes = [dp, i32, i32, szp]
+    lib.palu_attn_decode.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                     vp, i32, vp, vp, sz, vp]
+    for name in ("palu_rope_table_bytes", "palu_rope_table_init", "palu_encode_workspace_bytes", "palu_encode",
+                 "palu_quant_latent", "palu_attn_decode_workspace_bytes", "palu_attn_decode"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+class LayerDesc:
+    """Owns a palu_layer_desc and the host offset arrays it points to."""
+
+    def __init__(self, n_heads: int, d_head: int, group_head_off: Sequence[int], k_rank_off: Sequence[int],
+                 v_rank_off: Sequence[int], act_dtype: int = PALU_F16, k_latent_dtype: Optional[int] = None,
+                 v_latent_dtype: Optional[int] = None, quant_block: int = 128, rope_theta: float = 10000.0):
+        n_groups = len(group_head_off) - 1
+        arr = ctypes.c_int32 * (n_groups + 1)
+        self._gho = arr(*[int(v) for v in group_head_off])
+        self._kro = arr(*[int(v) for v in k_rank_off])
+        self._vro = arr(*[int(v) for v in v_rank_off])
+        self.n_heads, self.d_head, self.n_groups = int(n_heads), int(d_head), n_groups
+        self.group_head_off = [int(v) for v in group_head_off]
+        self.k_rank_off = [int(v) for v in k_rank_off]
+        self.v_rank_off = [int(v) for v in v_rank_off]
+        self.act_dtype = act_dtype
+        self.k_latent_dtype = act_dtype if k_latent_dtype is None else k_latent_dtype
+        self.v_latent_dtype = act_dtype if v_latent_dtype is None else v_latent_dtype
+        self.quant_block = quant_block
+        self.rope_theta = float(rope_theta)
+        self.c = _Desc(self.n_heads, self.d_head, n_groups, self._gho, self._kro, self._vro, act_dtype,
+                       self.k_latent_dtype, self.v_latent_dtype, quant_block, self.rope_theta)
+
+    @property
+    def R_k(self) -> int:
+        return self.k_rank_off[-1]
+
+    @property
+    def R_v(self) -> int:
+        return self.v_rank_off[-1]
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise PaluError(status, where)
+
+
+def _need_cuda(*tensors) -> None:
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("device tensors required")
+        if t is not None and not t.is_contiguous():
+            raise ValueError("contiguous tensors required")
+
+
+def palu_status_string(status: int) -> str:
+    return load_library().palu_status_string(int(status)).decode()
+
+
+def palu_version() -> int:
+    return int(load_library().palu_version())
+
+
+def palu_rope_table_bytes(d_head: int, n_pos: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().palu_rope_table_bytes(d_head, n_pos, ctypes.byref(out)), "palu_rope_table_bytes")
+    return int(out.value)
+
+
+def palu_rope_table_init(rope_theta: float, d_head: int, n_pos: int, table=None, stream=None):
+    """Fills (allocating with torch when `table` is None) and returns the table tensor."""
+    import torch
+    if table is None:
+        table = torch.empty(palu_rope_table_bytes(d_head, n_pos), dtype=torch.uint8, device="cuda")
+    _need_cuda(table)
+    _check(load_library().palu_rope_table_init(float(rope_theta), d_head, n_pos, _ptr(table), _stream(stream)),
+           "palu_rope_table_init")
+    return table
+
+
+def palu_encode_workspace_bytes(desc: LayerDesc, which: int, n_tok: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().palu_encode_workspace_bytes(desc.ref(), which, n_tok, ctypes.byref(out)),
+           "palu_encode_workspace_bytes")
+    return int(out.value)
+
+
+def palu_encode(desc: LayerDesc, which: int, x, A, latent, row_stride_elems: int, dst_row=None,
+                workspace=None, stream=None):
+    import torch
+    n_tok = int(x.shape[0])
+    if workspace is None:
+        workspace = torch.empty(palu_encode_workspace_bytes(desc, which, n_tok), dtype=torch.uint8, device=x.device)
+    _need_cuda(x, A, latent, dst_row, workspace)
+    _check(load_library().palu_encode(desc.ref(), which, _ptr(x), n_tok, _ptr(A), _ptr(latent),
+                                      int(row_stride_elems), _ptr(dst_row), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream(stream)), "palu_encode")
+    return latent
+
+
+def palu_quant_latent(desc: LayerDesc, which: int, latent, row_stride_elems: int, n_tok: int,
+                      codes, scale, zero, stream=None):
+    _need_cuda(latent, codes, scale, zero)
+    _check(load_library().palu_quant_latent(desc.ref(), which, _ptr(latent), int(row_stride_elems), int(n_tok),
+                                            _ptr(codes), _ptr(scale), _ptr(zero), _stream(stream)),
+           "palu_quant_latent")
+    return codes, scale, zero
+
+
+def palu_attn_decode_workspace_bytes(desc: LayerDesc, batch: int, max_seq: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().palu_attn_decode_workspace_bytes(desc.ref(), batch, max_seq, ctypes.byref(out)),
+           "palu_attn_decode_workspace_bytes")
+    return int(out.value)
+
+
+def palu_attn_decode(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, q, q_pos, hk, hv, Bk, Bv,
+                     rope_table, rope_table_len: int, out=None, workspace=None, k_pos=None, seq_lens=None,
+                     hk_scale=None, hk_zero=None, hv_scale=None, hv_zero=None, stream=None):
+    import torch
+    if out is None:
+        out = torch.empty((batch, desc.n_heads, desc.d_head), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(palu_attn_decode_workspace_bytes(desc, batch, max_seq), dtype=torch.uint8,
+                                device=q.device)
+    _need_cuda(q, q_pos, hk, hv, Bk, Bv, rope_table, out, workspace, k_pos, seq_lens, hk_scale, hk_zero,
+               hv_scale, hv_zero)
+    _check(load_library().palu_attn_decode(
+        desc.ref(), batch, seq_len, max_seq, _ptr(q), _ptr(q_pos), _ptr(hk), _ptr(hk_scale), _ptr(hk_zero),
+        _ptr(hv), _ptr(hv_scale), _ptr(hv_zero), _ptr(k_pos), _ptr(seq_lens), _ptr(Bk), _ptr(Bv),
+        _ptr(rope_table), int(rope_table_len), _ptr(out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)), "palu_attn_decode")
+    return out

@@ -1,0 +1,540 @@
+// Host side of the C ABI declared in include/palu.h: argument validation,
+// launch geometry, workspace carving.  No device memory is allocated here.
+
+#include "encode_quant.hip"
+#include "rope_fold.hip"
+#include "score.hip"
+#include "value.hip"
+
+#include <atomic>
+#include <cmath>
+#include <cstring>
+
+using namespace palu;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+int device_cu_count() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int v = cached[dev].load(std::memory_order_relaxed);
+  if (v > 0) return v;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+  cached[dev].store(v, std::memory_order_relaxed);
+  return v;
+}
+
+// ---- descriptor validation -------------------------------------------------
+int check_desc(const palu_layer_desc* d, Meta* m) {
+  if (!d || !d->group_head_off || !d->k_rank_off || !d->v_rank_off) return PALU_ERR_INVALID_ARG;
+  if (d->n_heads <= 0 || d->n_groups <= 0 || d->d_head <= 0) return PALU_ERR_INVALID_ARG;
+  if (d->act_dtype != PALU_F16 && d->act_dtype != PALU_BF16) return PALU_ERR_INVALID_ARG;
+  for (int side = 0; side < 2; ++side) {
+    const int ld = side ? d->v_latent_dtype : d->k_latent_dtype;
+    if (ld != d->act_dtype && ld != PALU_I4) return PALU_ERR_INVALID_ARG;
+  }
+  if (d->group_head_off[0] != 0 || d->k_rank_off[0] != 0 || d->v_rank_off[0] != 0) return PALU_ERR_INVALID_ARG;
+  for (int j = 0; j < d->n_groups; ++j) {
+    if (d->group_head_off[j + 1] <= d->group_head_off[j]) return PALU_ERR_INVALID_ARG;
+    for (const int32_t* off : {d->k_rank_off, d->v_rank_off}) {
+      const int r = off[j + 1] - off[j];
+      if (r <= 0 || r % PALU_RANK_MULTIPLE != 0) return PALU_ERR_INVALID_ARG;
+    }
+  }
+  if (d->group_head_off[d->n_groups] != d->n_heads) return PALU_ERR_INVALID_ARG;
+  const bool any_i4 = d->k_latent_dtype == PALU_I4 || d->v_latent_dtype == PALU_I4;
+  if (any_i4) {
+    if (d->quant_block <= 0) return PALU_ERR_INVALID_ARG;
+    for (int side = 0; side < 2; ++side) {
+      if ((side ? d->v_latent_dtype : d->k_latent_dtype) != PALU_I4) continue;
+      const int32_t* off = side ? d->v_rank_off : d->k_rank_off;
+      for (int j = 0; j <= d->n_groups; ++j)
+        if (off[j] % d->quant_block != 0) return PALU_ERR_INVALID_ARG;
+    }
+  }
+  // limits of this build
+  if (d->d_head != PALU_D_HEAD) return PALU_ERR_UNSUPPORTED;
+  if (d->n_heads > PALU_MAX_HEADS || d->n_groups > PALU_MAX_GROUPS) return PALU_ERR_UNSUPPORTED;
+  if (any_i4 && (d->quant_block != 128 || d->act_dtype != PALU_F16)) return PALU_ERR_UNSUPPORTED;
+  for (int j = 0; j < d->n_groups; ++j) {
+    if (d->k_rank_off[j + 1] - d->k_rank_off[j] > PALU_MAX_RANK) return PALU_ERR_UNSUPPORTED;
+    if (d->v_rank_off[j + 1] - d->v_rank_off[j] > PALU_MAX_RANK) return PALU_ERR_UNSUPPORTED;
+  }
+  if (m) {
+    std::memset(m, 0, sizeof(*m));
+    m->n_heads = d->n_heads;
+    m->n_groups = d->n_groups;
+    int bk = 0, bv = 0;
+    for (int j = 0; j <= d->n_groups; ++j) {
+      m->head_off[j] = d->group_head_off[j];
+      m->k_off[j] = d->k_rank_off[j];
+      m->v_off[j] = d->v_rank_off[j];
+      m->bk_off[j] = bk;
+      m->bv_off[j] = bv;
+      if (j < d->n_groups) {
+        const int s = d->group_head_off[j + 1] - d->group_head_off[j];
+        bk += (d->k_rank_off[j + 1] - d->k_rank_off[j]) * s * PALU_D_HEAD;
+        bv += (d->v_rank_off[j + 1] - d->v_rank_off[j]) * s * PALU_D_HEAD;
+        for (int h = d->group_head_off[j]; h < d->group_head_off[j + 1]; ++h) m->group_of_head[h] = (uint8_t)j;
+      }
+    }
+  }
+  return PALU_OK;
+}
+
+// ---- score-path work units ----------------------------------------------------
+// Rank classes of the weight-stationary score kernel: the rank decides how many
+// k-steps of 16 a wavefront keeps in registers and whether it owns a whole head.
+enum { kClsKs4 = 0, kClsKs8, kClsKs16, kClsKs32Half, kNumScoreCls };
+constexpr int kScoreMaxWidth = 512;      // latent columns one workgroup stages per token
+
+int score_class(int r) {
+  if (r <= 64) return kClsKs4;
+  if (r <= 128) return kClsKs8;
+  if (r <= 256) return kClsKs16;
+  if (r <= 512) return kClsKs32Half;
+  return -1;
+}
+
+struct ScorePlan {
+  Units units[kNumScoreCls];
+  int max_width[kNumScoreCls];    // widest latent column range staged by a unit of the class
+  int total_units;
+  bool two_parts[PALU_MAX_HEADS];
+};
+
+int plan_score(const Meta& m, ScorePlan* p) {
+  std::memset(p, 0, sizeof(*p));
+  int h = 0;
+  while (h < m.n_heads) {
+    const int j0 = m.group_of_head[h];
+    const int cls = score_class(m.k_off[j0 + 1] - m.k_off[j0]);
+    if (cls < 0) return PALU_ERR_UNSUPPORTED;
+    const int max_heads = cls == kClsKs32Half ? 2 : 4;
+    int nh = 1;
+    while (h + nh < m.n_heads && nh < max_heads) {
+      const int jn = m.group_of_head[h + nh];
+      if (score_class(m.k_off[jn + 1] - m.k_off[jn]) != cls) break;
+      if (m.k_off[jn + 1] - m.k_off[j0] > kScoreMaxWidth) break;
+      ++nh;
+    }
+    Units& u = p->units[cls];
+    if (u.n_units >= kMaxUnits) return PALU_ERR_UNSUPPORTED;
+    u.h0[u.n_units] = (uint16_t)h;
+    u.nh[u.n_units] = (uint8_t)nh;
+    ++u.n_units;
+    ++p->total_units;
+    p->max_width[cls] = std::max(p->max_width[cls], m.k_off[m.group_of_head[h + nh - 1] + 1] - m.k_off[j0]);
+    if (cls == kClsKs32Half)
+      for (int x = 0; x < nh; ++x) p->two_parts[h + x] = true;
+    h += nh;
+  }
+  return PALU_OK;
+}
+
+// ---- value-path work units -----------------------------------------------------
+enum { kVal1 = 0, kVal2, kVal4, kNumValCls };
+
+struct ValuePlan {
+  Units units[kNumValCls];
+  int total_units;
+};
+
+int plan_value(const Meta& m, ValuePlan* p) {
+  std::memset(p, 0, sizeof(*p));
+  for (int j = 0; j < m.n_groups; ++j) {
+    const int s = m.head_off[j + 1] - m.head_off[j];
+    if (m.v_off[j + 1] - m.v_off[j] > 2048) return PALU_ERR_UNSUPPORTED;
+    for (int u0 = 0; u0 < s; u0 += 4) {
+      const int nh = std::min(4, s - u0);
+      const int cls = s == 1 ? kVal1 : (s == 2 ? kVal2 : kVal4);
+      Units& u = p->units[cls];
+      if (u.n_units >= kMaxUnits) return PALU_ERR_UNSUPPORTED;
+      u.h0[u.n_units] = (uint16_t)(m.head_off[j] + u0);
+      u.nh[u.n_units] = (uint8_t)nh;
+      ++u.n_units;
+      ++p->total_units;
+    }
+  }
+  return PALU_OK;
+}
+
+// Tokens per value split and number of splits for a given attended length.
+void split_geometry(int total_units, int batch, int seq_len, int* split_tokens, int* n_split) {
+  const int target = std::max(1, ceil_div(4 * device_cu_count(), std::max(1, total_units * batch)));
+  int st = ceil_div(ceil_div(seq_len, target), 32) * 32;
+  st = std::min(std::max(st, 64), kSplitMax);
+  *split_tokens = st;
+  *n_split = ceil_div(seq_len, st);
+}
+int split_bound(int total_units, int batch, int max_seq) {
+  const int target = std::max(1, ceil_div(4 * device_cu_count(), std::max(1, total_units * batch)));
+  return std::max(target, ceil_div(max_seq, kSplitMax)) + 1;
+}
+
+struct Workspace {
+  size_t mfold, scores, o_part, ml_part, total;
+  int lpad, o_stride;
+  long long mfold_bstride, part_stride;
+};
+
+int carve(const Meta& m, int batch, int max_seq, int n_split_cap, Workspace* w) {
+  w->lpad = ceil_div(max_seq, 32) * 32;
+  w->mfold_bstride = m.bk_off[m.n_groups];
+  w->o_stride = m.bv_off[m.n_groups] / PALU_D_HEAD;
+  w->part_stride = (long long)batch * m.n_heads * w->lpad;
+  size_t off = 0;
+  w->mfold = off;   off = align_up(off + (size_t)batch * w->mfold_bstride * 2);
+  w->scores = off;  off = align_up(off + (size_t)2 * w->part_stride * 4);
+  w->o_part = off;  off = align_up(off + (size_t)batch * n_split_cap * w->o_stride * 4);
+  w->ml_part = off; off = align_up(off + (size_t)batch * n_split_cap * m.n_heads * 2 * 4);
+  w->total = off;
+  return PALU_OK;
+}
+
+template <typename K>
+int allow_lds(K kernel, size_t bytes) {
+  if (bytes <= 64 * 1024) return PALU_OK;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)bytes) == hipSuccess ? PALU_OK : PALU_ERR_HIP;
+}
+
+using ScoreFn = void (*)(ScoreArgs);
+ScoreFn score_fn(int act, bool i4, int cls) {
+  if (act == PALU_F16 && !i4) {
+    switch (cls) {
+      case kClsKs4: return score_kernel<F16, 4, 4, false>;
+      case kClsKs8: return score_kernel<F16, 8, 4, false>;
+      case kClsKs16: return score_kernel<F16, 16, 4, false>;
+      default: return score_kernel<F16, 32, 2, false>;
+    }
+  }
+  if (act == PALU_F16 && i4) {
+    switch (cls) {
+      case kClsKs4: return score_kernel<F16, 4, 4, true>;
+      case kClsKs8: return score_kernel<F16, 8, 4, true>;
+      case kClsKs16: return score_kernel<F16, 16, 4, true>;
+      default: return score_kernel<F16, 32, 2, true>;
+    }
+  }
+  switch (cls) {
+    case kClsKs4: return score_kernel<BF16, 4, 4, false>;
+    case kClsKs8: return score_kernel<BF16, 8, 4, false>;
+    case kClsKs16: return score_kernel<BF16, 16, 4, false>;
+    default: return score_kernel<BF16, 32, 2, false>;
+  }
+}
+
+using ValueFn = void (*)(ValueArgs);
+ValueFn value_fn(int act, bool i4, int cls) {
+  if (act == PALU_F16 && !i4) {
+    switch (cls) {
+      case kVal1: return value_kernel<F16, 1, false>;
+      case kVal2: return value_kernel<F16, 2, false>;
+      default: return value_kernel<F16, 4, false>;
+    }
+  }
+  if (act == PALU_F16 && i4) {
+    switch (cls) {
+      case kVal1: return value_kernel<F16, 1, true>;
+      case kVal2: return value_kernel<F16, 2, true>;
+      default: return value_kernel<F16, 4, true>;
+    }
+  }
+  switch (cls) {
+    case kVal1: return value_kernel<BF16, 1, false>;
+    case kVal2: return value_kernel<BF16, 2, false>;
+    default: return value_kernel<BF16, 4, false>;
+  }
+}
+
+inline int launch_ok() { return hipGetLastError() == hipSuccess ? PALU_OK : PALU_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* palu_status_string(int status) {
+  switch (status) {
+    case PALU_OK: return "ok";
+    case PALU_ERR_INVALID_ARG: return "invalid argument";
+    case PALU_ERR_UNSUPPORTED: return "unsupported configuration";
+    case PALU_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case PALU_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int palu_version(void) { return 100; }
+
+int palu_rope_table_bytes(int32_t d_head, int32_t n_pos, size_t* out_bytes) {
+  if (!out_bytes || n_pos <= 0 || d_head <= 0) return PALU_ERR_INVALID_ARG;
+  if (d_head != PALU_D_HEAD) return PALU_ERR_UNSUPPORTED;
+  *out_bytes = (size_t)n_pos * PALU_D_HEAD * 2;
+  return PALU_OK;
+}
+
+int palu_rope_table_init(float rope_theta, int32_t d_head, int32_t n_pos, void* table, void* stream) {
+  if (!table || n_pos <= 0 || d_head <= 0) return PALU_ERR_INVALID_ARG;
+  if (d_head != PALU_D_HEAD) return PALU_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(table) & 15) != 0) return PALU_ERR_INVALID_ARG;
+  const long long items = (long long)n_pos * kHalf;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<uint16_t*>(table), n_pos, rope_theta);
+  return launch_ok();
+}
+
+// ------------------------------------------------------------------ encode
+int palu_encode_workspace_bytes(const palu_layer_desc* desc, int which, int32_t n_tok, size_t* out_bytes) {
+  Meta m;
+  const int st = check_desc(desc, &m);
+  if (st != PALU_OK) return st;
+  if (!out_bytes || n_tok <= 0 || (which != 0 && which != 1)) return PALU_ERR_INVALID_ARG;
+  const int R = which ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
+  const int d = m.n_heads * PALU_D_HEAD;
+  *out_bytes = align_up((size_t)(d / kEncRows) * n_tok * R * 4);
+  return PALU_OK;
+}
+
+int palu_encode(const palu_layer_desc* desc, int which, const void* x, int32_t n_tok, const void* A,
+                void* latent, int64_t row_stride_elems, const int32_t* dst_row,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  Meta m;
+  const int st = check_desc(desc, &m);
+  if (st != PALU_OK) return st;
+  if (!x || !A || !latent || !workspace || n_tok <= 0 || (which != 0 && which != 1)) return PALU_ERR_INVALID_ARG;
+  const int R = which ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
+  const int d = m.n_heads * PALU_D_HEAD;
+  if (row_stride_elems < R || (row_stride_elems & 1)) return PALU_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(A) & 15) || (reinterpret_cast<uintptr_t>(latent) & 3) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 15))
+    return PALU_ERR_INVALID_ARG;
+  size_t need = 0;
+  palu_encode_workspace_bytes(desc, which, n_tok, &need);
+  if (workspace_bytes < need) return PALU_ERR_WORKSPACE_TOO_SMALL;
+
+  EncodeArgs a;
+  a.x = static_cast<const uint16_t*>(x);
+  a.A = static_cast<const uint16_t*>(A);
+  a.partial = static_cast<float*>(workspace);
+  a.latent = static_cast<uint16_t*>(latent);
+  a.dst_row = dst_row;
+  a.row_stride = row_stride_elems;
+  a.n_tok = n_tok;
+  a.d = d;
+  a.R = R;
+  a.k_splits = d / kEncRows;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dim3 g1((unsigned)ceil_div(R, kEncCols), (unsigned)a.k_splits);
+  const unsigned g2 = (unsigned)(((long long)n_tok * (R / 2) + 255) / 256);
+  if (desc->act_dtype == PALU_F16) {
+    hipLaunchKernelGGL(encode_partial_kernel<F16>, g1, dim3(256), 0, s, a);
+    hipLaunchKernelGGL(encode_finish_kernel<F16>, dim3(g2), dim3(256), 0, s, a);
+  } else {
+    hipLaunchKernelGGL(encode_partial_kernel<BF16>, g1, dim3(256), 0, s, a);
+    hipLaunchKernelGGL(encode_finish_kernel<BF16>, dim3(g2), dim3(256), 0, s, a);
+  }
+  return launch_ok();
+}
+
+// ------------------------------------------------------------------ quantize
+int palu_quant_latent(const palu_layer_desc* desc, int which, const void* latent, int64_t row_stride_elems,
+                      int32_t n_tok, uint8_t* codes, void* scale, void* zero, void* stream) {
+  Meta m;
+  const int st = check_desc(desc, &m);
+  if (st != PALU_OK) return st;
+  if (!latent || !codes || !scale || !zero || n_tok <= 0 || (which != 0 && which != 1)) return PALU_ERR_INVALID_ARG;
+  if (desc->quant_block <= 0) return PALU_ERR_INVALID_ARG;
+  if (desc->quant_block != 128) return PALU_ERR_UNSUPPORTED;
+  const int R = which ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
+  if (R % desc->quant_block != 0) return PALU_ERR_INVALID_ARG;
+  if (row_stride_elems < R || (row_stride_elems & 1) || (reinterpret_cast<uintptr_t>(latent) & 3))
+    return PALU_ERR_INVALID_ARG;
+  QuantArgs a;
+  a.latent = static_cast<const uint16_t*>(latent);
+  a.codes = codes;
+  a.scale = static_cast<uint16_t*>(scale);
+  a.zero = static_cast<uint16_t*>(zero);
+  a.row_stride = row_stride_elems;
+  a.n_tok = n_tok;
+  a.R = R;
+  a.n_blocks = R / 128;
+  const long long items = (long long)n_tok * a.n_blocks;
+  const dim3 g((unsigned)((items + 3) / 4));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (desc->act_dtype == PALU_F16) hipLaunchKernelGGL(quant_kernel<F16>, g, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(quant_kernel<BF16>, g, dim3(256), 0, s, a);
+  return launch_ok();
+}
+
+// ------------------------------------------------------------------ decode
+int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch, int32_t max_seq, size_t* out_bytes) {
+  Meta m;
+  int st = check_desc(desc, &m);
+  if (st != PALU_OK) return st;
+  if (!out_bytes || batch <= 0 || max_seq <= 0) return PALU_ERR_INVALID_ARG;
+  ScorePlan sp;
+  ValuePlan vp;
+  if ((st = plan_score(m, &sp)) != PALU_OK) return st;
+  if ((st = plan_value(m, &vp)) != PALU_OK) return st;
+  Workspace w;
+  carve(m, batch, max_seq, split_bound(vp.total_units, batch, max_seq), &w);
+  *out_bytes = w.total;
+  return PALU_OK;
+}
+
+int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                     const void* q, const int32_t* q_pos,
+                     const void* hk, const void* hk_scale, const void* hk_zero,
+                     const void* hv, const void* hv_scale, const void* hv_zero,
+                     const int32_t* k_pos, const int32_t* seq_lens,
+                     const void* Bk, const void* Bv,
+                     const void* rope_table, int32_t rope_table_len,
+                     float* out, void* workspace, size_t workspace_bytes, void* stream) {
+  Meta m;
+  int st = check_desc(desc, &m);
+  if (st != PALU_OK) return st;
+  if (batch <= 0 || seq_len <= 0 || max_seq < seq_len) return PALU_ERR_INVALID_ARG;
+  if (!q || !q_pos || !hk || !hv || !Bk || !Bv || !rope_table || !out || !workspace) return PALU_ERR_INVALID_ARG;
+  const bool k_i4 = desc->k_latent_dtype == PALU_I4, v_i4 = desc->v_latent_dtype == PALU_I4;
+  if (k_i4 && (!hk_scale || !hk_zero)) return PALU_ERR_INVALID_ARG;
+  if (v_i4 && (!hv_scale || !hv_zero)) return PALU_ERR_INVALID_ARG;
+  if (rope_table_len <= 0 || (!k_pos && rope_table_len < seq_len)) return PALU_ERR_INVALID_ARG;
+  for (const void* p : {hk, hv, Bk, Bv, rope_table, (const void*)workspace})
+    if (reinterpret_cast<uintptr_t>(p) & 15) return PALU_ERR_INVALID_ARG;
+  const int Rk = m.k_off[m.n_groups], Rv = m.v_off[m.n_groups];
+  if ((Rk % 8) || (Rv % 8)) return PALU_ERR_INVALID_ARG;
+
+  ScorePlan sp;
+  ValuePlan vp;
+  if ((st = plan_score(m, &sp)) != PALU_OK) return st;
+  if ((st = plan_value(m, &vp)) != PALU_OK) return st;
+  int split_tokens, n_split;
+  split_geometry(vp.total_units, batch, seq_len, &split_tokens, &n_split);
+  if (n_split > kMaxSplits) return PALU_ERR_UNSUPPORTED;
+  const int n_split_cap = split_bound(vp.total_units, batch, max_seq);
+  Workspace w;
+  carve(m, batch, max_seq, n_split_cap, &w);
+  if (n_split > n_split_cap) return PALU_ERR_INVALID_ARG;
+  if (workspace_bytes < w.total) return PALU_ERR_WORKSPACE_TOO_SMALL;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const int act = desc->act_dtype;
+
+  // 1. fold the rotated query into B_k
+  {
+    FoldArgs a;
+    a.q = static_cast<const uint16_t*>(q);
+    a.q_pos = q_pos;
+    a.Bk = static_cast<const uint16_t*>(Bk);
+    a.mfold = reinterpret_cast<uint16_t*>(ws + w.mfold);
+    a.mfold_bstride = w.mfold_bstride;
+    a.theta = desc->rope_theta;
+    a.meta = m;
+    const dim3 g((unsigned)m.n_heads, (unsigned)batch);
+    if (act == PALU_F16) hipLaunchKernelGGL(fold_kernel<F16>, g, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
+    if ((st = launch_ok()) != PALU_OK) return st;
+  }
+
+  // 2. scores
+  {
+    ScoreArgs a;
+    a.hk = hk;
+    a.hk_scale = static_cast<const uint16_t*>(hk_scale);
+    a.hk_zero = static_cast<const uint16_t*>(hk_zero);
+    a.mfold = reinterpret_cast<const uint16_t*>(ws + w.mfold);
+    a.rope = static_cast<const uint16_t*>(rope_table);
+    a.k_pos = k_pos;
+    a.seq_lens = seq_lens;
+    a.scores = reinterpret_cast<float*>(ws + w.scores);
+    a.mfold_bstride = w.mfold_bstride;
+    a.row_elems = Rk;
+    a.max_seq = max_seq;
+    a.seq_len = seq_len;
+    a.lpad = w.lpad;
+    a.batch = batch;
+    a.rope_len = rope_table_len;
+    a.quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
+    a.n_blocks_q = Rk / a.quant_block;
+    a.scale = 1.4426950408889634f / std::sqrt((float)PALU_D_HEAD);
+    a.meta = m;
+    const int tiles = ceil_div(seq_len, kTile);
+    int n_chunks = std::max(1, std::min(tiles, (int)std::lround((double)device_cu_count() / (sp.total_units * batch))));
+    const int chunk_tiles = ceil_div(tiles, n_chunks);
+    a.chunk_tokens = chunk_tiles * kTile;
+    a.n_chunks = ceil_div(tiles, chunk_tiles);
+    for (int cls = 0; cls < kNumScoreCls; ++cls) {
+      if (sp.units[cls].n_units == 0) continue;
+      a.units = sp.units[cls];
+      const size_t lds = (size_t)2 * kTile * (sp.max_width[cls] * 2 + kRowPad);
+      ScoreFn fn = score_fn(act, k_i4, cls);
+      if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
+      const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
+      hipLaunchKernelGGL(fn, dim3(grid), dim3(256), lds, s, a);
+      if ((st = launch_ok()) != PALU_OK) return st;
+    }
+  }
+
+  // 3. softmax partials and P.H_v per split
+  {
+    ValueArgs a;
+    a.hv = hv;
+    a.hv_scale = static_cast<const uint16_t*>(hv_scale);
+    a.hv_zero = static_cast<const uint16_t*>(hv_zero);
+    a.scores = reinterpret_cast<const float*>(ws + w.scores);
+    a.seq_lens = seq_lens;
+    a.o_part = reinterpret_cast<float*>(ws + w.o_part);
+    a.ml_part = reinterpret_cast<float*>(ws + w.ml_part);
+    a.row_elems = Rv;
+    a.max_seq = max_seq;
+    a.part_stride = w.part_stride;
+    a.seq_len = seq_len;
+    a.lpad = w.lpad;
+    a.batch = batch;
+    a.split_tokens = split_tokens;
+    a.n_split = n_split;
+    a.o_stride = w.o_stride;
+    a.quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
+    a.n_blocks_q = Rv / a.quant_block;
+    std::memset(a.parts_mask_lo, 0, sizeof(a.parts_mask_lo));
+    for (int h = 0; h < m.n_heads; ++h)
+      if (sp.two_parts[h]) a.parts_mask_lo[h >> 5] |= 1u << (h & 31);
+    a.meta = m;
+    for (int cls = 0; cls < kNumValCls; ++cls) {
+      if (vp.units[cls].n_units == 0) continue;
+      a.units = vp.units[cls];
+      const unsigned grid = (unsigned)(a.units.n_units * n_split * batch);
+      hipLaunchKernelGGL(value_fn(act, v_i4, cls), dim3(grid), dim3(256), 0, s, a);
+      if ((st = launch_ok()) != PALU_OK) return st;
+    }
+  }
+
+  // 4. merge splits, normalise, apply B_v
+  {
+    CombineArgs a;
+    a.o_part = reinterpret_cast<const float*>(ws + w.o_part);
+    a.ml_part = reinterpret_cast<const float*>(ws + w.ml_part);
+    a.Bv = static_cast<const uint16_t*>(Bv);
+    a.seq_lens = seq_lens;
+    a.out = out;
+    a.n_split = n_split;
+    a.split_tokens = split_tokens;
+    a.seq_len = seq_len;
+    a.o_stride = w.o_stride;
+    a.meta = m;
+    const dim3 g((unsigned)m.n_heads, (unsigned)batch);
+    if (act == PALU_F16) hipLaunchKernelGGL(combine_kernel<F16>, g, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(combine_kernel<BF16>, g, dim3(256), 0, s, a);
+    if ((st = launch_ok()) != PALU_OK) return st;
+  }
+  return PALU_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,165 @@
+// Cache-append side: down-projection h = x A (Sec. 3.1) for a handful of new
+// tokens, and the 4-bit asymmetric quantizer of Appendix A.
+//
+// At decode time the projection reads all of A (d x R) for n_tok = batch
+// tokens: a weight-streaming problem (HBM-bound, 2*n_tok FLOP per weight
+// element), so it is a split-K float32 FMA kernel on 16-byte coalesced loads
+// followed by a small reduction that rounds once and scatters the rows.
+
+#include "palu_dev.h"
+
+namespace palu {
+
+constexpr int kEncRows = 64;      // rows of A per workgroup (16 per wavefront)
+constexpr int kEncCols = 512;     // columns of A per workgroup (8 per lane)
+constexpr int kEncTok = 8;        // tokens accumulated per pass over the weights
+
+struct EncodeArgs {
+  const uint16_t* x;       // [n_tok, d]
+  const uint16_t* A;       // [d, R]
+  float* partial;          // [k_splits][n_tok][R]
+  uint16_t* latent;
+  const int32_t* dst_row;
+  long long row_stride;
+  int n_tok, d, R, k_splits;
+};
+
+// grid (ceil(R / 512), d / 64), 256 threads.
+template <typename T>
+__global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
+  __shared__ float xs[kEncTok][kEncRows];
+  __shared__ float red[3][kEncTok][kEncCols];     // wavefronts 1..3 hand their sums to wavefront 0
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int c0 = blockIdx.x * kEncCols + lane * 8;
+  const int k0 = blockIdx.y * kEncRows;
+  const bool col_ok = c0 < a.R;                   // R is a multiple of 32, so 8 columns are all in or all out
+
+  for (int tb = 0; tb < a.n_tok; tb += kEncTok) {
+    const int nt = min(kEncTok, a.n_tok - tb);
+    __syncthreads();
+    for (int i = tid; i < kEncTok * kEncRows; i += 256) {
+      const int t = i / kEncRows, k = i - t * kEncRows;
+      xs[t][k] = t < nt ? T::to_float(a.x[(size_t)(tb + t) * a.d + k0 + k]) : 0.f;
+    }
+    __syncthreads();
+    float acc[kEncTok][8];
+#pragma unroll
+    for (int t = 0; t < kEncTok; ++t)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[t][e] = 0.f;
+    if (col_ok) {
+#pragma unroll 4
+      for (int kk = 0; kk < 16; ++kk) {
+        const int k = wave * 16 + kk;
+        const uint4v raw = *reinterpret_cast<const uint4v*>(a.A + (size_t)(k0 + k) * a.R + c0);
+        float wv[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          wv[2 * e] = T::to_float((uint16_t)(raw[e] & 0xffffu));
+          wv[2 * e + 1] = T::to_float((uint16_t)(raw[e] >> 16));
+        }
+#pragma unroll
+        for (int t = 0; t < kEncTok; ++t) {
+          const float xv = xs[t][k];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(xv, wv[e], acc[t][e]);
+        }
+      }
+    }
+    if (wave > 0) {
+#pragma unroll
+      for (int t = 0; t < kEncTok; ++t)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[wave - 1][t][e * 64 + lane] = acc[t][e];
+    }
+    __syncthreads();
+    if (wave == 0 && col_ok) {
+#pragma unroll
+      for (int t = 0; t < kEncTok; ++t) {
+        if (t >= nt) break;
+        float* dst = a.partial + ((size_t)blockIdx.y * a.n_tok + tb + t) * a.R + c0;
+        float4v o0, o1;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float s = acc[t][e] + red[0][t][e * 64 + lane] + red[1][t][e * 64 + lane] + red[2][t][e * 64 + lane];
+          if (e < 4) o0[e] = s; else o1[e - 4] = s;
+        }
+        *reinterpret_cast<float4v*>(dst) = o0;
+        *reinterpret_cast<float4v*>(dst + 4) = o1;
+      }
+    }
+  }
+}
+
+// One thread per (token, pair of columns): sums the split-K partials in a fixed
+// order, rounds once, scatters.
+template <typename T>
+__global__ __launch_bounds__(256) void encode_finish_kernel(EncodeArgs a) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int pairs = a.R / 2;
+  if (idx >= a.n_tok * pairs) return;
+  const int t = idx / pairs, c = (idx - t * pairs) * 2;
+  float s0 = 0.f, s1 = 0.f;
+  for (int ks = 0; ks < a.k_splits; ++ks) {
+    const float* p = a.partial + ((size_t)ks * a.n_tok + t) * a.R + c;
+    s0 += p[0];
+    s1 += p[1];
+  }
+  const long long row = a.dst_row ? a.dst_row[t] : t;
+  uint32_t* dst = reinterpret_cast<uint32_t*>(a.latent + row * a.row_stride + c);
+  *dst = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
+}
+
+struct QuantArgs {
+  const uint16_t* latent;
+  uint8_t* codes;
+  uint16_t* scale;
+  uint16_t* zero;
+  long long row_stride;
+  int n_tok, R, n_blocks;     // n_blocks = R / 128
+};
+
+// One wavefront per (token, 128-channel block); lane l owns channels 2l, 2l+1.
+// Every arithmetic step is a single IEEE float32 operation so the integer
+// codes are reproducible bit for bit (Appendix A: s = (max-min)/(2^B-1),
+// z = round(-min/s), code = clamp(round(x/s) + z, 0, 2^B-1), B = 4).
+template <typename T>
+__global__ __launch_bounds__(256) void quant_kernel(QuantArgs a) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const long long item = (long long)blockIdx.x * 4 + wave;
+  if (item >= (long long)a.n_tok * a.n_blocks) return;
+  const int t = (int)(item / a.n_blocks), blk = (int)(item - (long long)t * a.n_blocks);
+  const uint32_t raw = *reinterpret_cast<const uint32_t*>(a.latent + (size_t)t * a.row_stride + blk * 128 + lane * 2);
+  const float x0 = T::to_float((uint16_t)(raw & 0xffffu));
+  const float x1 = T::to_float((uint16_t)(raw >> 16));
+  float mn = fminf(x0, x1), mx = fmaxf(x0, x1);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    mn = fminf(mn, __shfl_xor(mn, off, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  }
+  const float s32 = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
+  uint16_t s16 = F16::from_float(s32);
+  if ((s16 & 0x7fffu) == 0) s16 = 0x3c00u;                    // s == 0 -> 1
+  const float sf = F16::to_float(s16);
+  float z = rintf(__fdiv_rn(-mn, sf));
+  z = fminf(fmaxf(z, -65504.0f), 65504.0f);
+  const uint16_t z16 = F16::from_float(z);
+  const float zf = F16::to_float(z16);
+  const float q0 = fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x0, sf)), zf), 0.0f), 15.0f);
+  const float q1 = fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x1, sf)), zf), 0.0f), 15.0f);
+  a.codes[(size_t)t * (a.R / 2) + blk * 64 + lane] = (uint8_t)((uint32_t)q0 | ((uint32_t)q1 << 4));
+  if (lane == 0) {
+    a.scale[(size_t)t * a.n_blocks + blk] = s16;
+    a.zero[(size_t)t * a.n_blocks + blk] = z16;
+  }
+}
+
+template __global__ void encode_partial_kernel<F16>(EncodeArgs);
+template __global__ void encode_partial_kernel<BF16>(EncodeArgs);
+template __global__ void encode_finish_kernel<F16>(EncodeArgs);
+template __global__ void encode_finish_kernel<BF16>(EncodeArgs);
+template __global__ void quant_kernel<F16>(QuantArgs);
+template __global__ void quant_kernel<BF16>(QuantArgs);
+
+}  // namespace palu

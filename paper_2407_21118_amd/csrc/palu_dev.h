@@ -1,0 +1,169 @@
+// Device-side shared definitions for the gfx950 kernels (not part of the public ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/palu.h"
+
+namespace palu {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+
+constexpr int kDHead = PALU_D_HEAD;        // 128
+constexpr int kHalf = kDHead / 2;          // 64 rotation pairs
+constexpr int kTile = 32;                  // tokens per MFMA tile (N of the 32x32x16 instruction)
+constexpr int kMaxUnits = 128;             // work units (head blocks) per launch
+
+// Layer metadata passed by value in the kernel arguments.
+struct Meta {
+  int n_heads;
+  int n_groups;
+  int head_off[PALU_MAX_GROUPS + 1];
+  int k_off[PALU_MAX_GROUPS + 1];
+  int v_off[PALU_MAX_GROUPS + 1];
+  int bk_off[PALU_MAX_GROUPS + 1];   // element offset of group j inside the concatenated B_k
+  int bv_off[PALU_MAX_GROUPS + 1];
+  uint8_t group_of_head[PALU_MAX_HEADS];
+};
+
+// A work unit of the score or value kernel: `nh` consecutive heads starting at h0.
+struct Units {
+  int n_units;
+  uint16_t h0[kMaxUnits];
+  uint8_t nh[kMaxUnits];
+};
+
+// Storage type helpers: the activation dtype is either IEEE half or bfloat16,
+// both 16 bits wide; kernels are templated on a tag.
+struct F16 {
+  using vec8 = half8;
+  static __device__ __forceinline__ float to_float(uint16_t bits) {
+    return (float)__builtin_bit_cast(_Float16, bits);
+  }
+  static __device__ __forceinline__ uint16_t from_float(float v) {
+    return __builtin_bit_cast(uint16_t, (_Float16)v);
+  }
+  static __device__ __forceinline__ float16v mfma(vec8 a, vec8 b, float16v c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+};
+
+struct BF16 {
+  using vec8 = bf16x8;
+  static __device__ __forceinline__ float to_float(uint16_t bits) {
+    return __builtin_bit_cast(float, (uint32_t)bits << 16);
+  }
+  static __device__ __forceinline__ uint16_t from_float(float v) {   // round to nearest even
+    uint32_t u = __builtin_bit_cast(uint32_t, v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+  }
+  static __device__ __forceinline__ float16v mfma(vec8 a, vec8 b, float16v c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+};
+
+// Position of accumulator element i of a 32x32 MFMA tile: the lane holds
+// column n = lane % 32 and rows 8*(i/4) + 4*(lane/32) + (i%4), i = 0..15.
+__device__ __forceinline__ int mfma_row(int i, int lane_hi) { return 8 * (i >> 2) + 4 * lane_hi + (i & 3); }
+
+// Index of feature c' (0..127: 0..63 pair with cos, 64..127 with sin) inside a
+// rope-table row, arranged so that lane-half `hi` of a wave finds the 64
+// values its accumulators need contiguously: [hi][row tile][i].
+__host__ __device__ __forceinline__ int rope_slot(int cprime) {
+  const int rt = cprime >> 5, rr = cprime & 31;
+  const int hi = (rr >> 2) & 1;
+  const int i = ((rr >> 3) << 2) | (rr & 3);
+  return hi * 64 + rt * 16 + i;
+}
+
+struct ScoreArgs {
+  const void* hk;            // latents or packed codes
+  const uint16_t* hk_scale;  // fp16 bits (int4 only)
+  const uint16_t* hk_zero;
+  const uint16_t* mfold;     // folded query-weights, per batch stride mfold_bstride elements
+  const uint16_t* rope;      // table
+  const int32_t* k_pos;
+  const int32_t* seq_lens;
+  float* scores;             // [parts][batch][n_heads][lpad]
+  long long mfold_bstride;
+  long long row_elems;       // R_k: elements per latent row
+  long long max_seq;
+  int seq_len;
+  int lpad;                  // row pitch of the score buffer (floats)
+  int batch;
+  int chunk_tokens;          // tokens per workgroup (multiple of kTile)
+  int n_chunks;
+  int rope_len;
+  int n_blocks_q;            // R_k / quant_block (int4 only)
+  int quant_block;
+  float scale;               // log2(e) / sqrt(d_h)
+  Meta meta;
+  Units units;
+};
+
+struct FoldArgs {
+  const uint16_t* q;         // [batch, n_heads, 128]
+  const int32_t* q_pos;
+  const uint16_t* Bk;
+  uint16_t* mfold;
+  long long mfold_bstride;
+  float theta;
+  Meta meta;
+};
+
+struct ValueArgs {
+  const void* hv;
+  const uint16_t* hv_scale;
+  const uint16_t* hv_zero;
+  const float* scores;       // [parts][batch][n_heads][lpad]
+  const int32_t* seq_lens;
+  float* o_part;             // [batch][n_split][sum_h r_v(h)]
+  float* ml_part;            // [batch][n_split][n_heads][2]  (max, sum) in the log2 domain
+  long long row_elems;       // R_v
+  long long max_seq;
+  long long part_stride;     // floats between score parts
+  int seq_len;
+  int lpad;
+  int batch;
+  int split_tokens;
+  int n_split;
+  int o_stride;              // sum_h r_v(group(h)): floats per (batch, split)
+  int quant_block;
+  int n_blocks_q;
+  unsigned parts_mask_lo[PALU_MAX_HEADS / 32];   // bit h set: head h has two score parts
+  Meta meta;
+  Units units;
+};
+
+struct CombineArgs {
+  const float* o_part;
+  const float* ml_part;
+  const uint16_t* Bv;
+  const int32_t* seq_lens;
+  float* out;                // [batch, n_heads, 128]
+  int n_split;
+  int split_tokens;
+  int seq_len;
+  int o_stride;
+  Meta meta;
+};
+
+// Per-head offset of its value-latent accumulator inside an o_part row:
+// heads are laid out in order, head h taking r_v(group(h)) floats.
+__device__ __forceinline__ int o_head_off(const Meta& m, int h) {
+  const int j = m.group_of_head[h];
+  // heads before group j take sum_{i<j} s_i r_i floats = bv_off[j] / 128
+  return m.bv_off[j] / kDHead + (h - m.head_off[j]) * (m.v_off[j + 1] - m.v_off[j]);
+}
+
+}  // namespace palu

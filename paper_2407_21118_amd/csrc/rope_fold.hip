@@ -1,0 +1,92 @@
+// RoPE angle table and the per-step fold of the rotated query into B_k.
+//
+// Score identity used by the whole score path (RoPE pairs feature f with
+// f + 64, angle phi_f(t) = pos_t * theta^(-2f/128); Sec. 3.1.2):
+//   q' . RoPE(k, t) = sum_f cos(phi_f(t)) (q'_f k_f + q'_{f+64} k_{f+64})
+//                         + sin(phi_f(t)) (q'_{f+64} k_f - q'_f k_{f+64})
+// and with k = h B (Sec. 3.2.3) every bracket is h . (a column built from q' and B):
+//   u_f = q'_f B[:,f] + q'_{f+64} B[:,f+64],   w_f = q'_{f+64} B[:,f] - q'_f B[:,f+64].
+// The fold kernel writes M = [u_0..u_63 | w_0..w_63] (r x 128 per head) in the
+// register layout of the MFMA A operand, so that the score kernel's contraction
+// H_k . M is the reconstruction GEMM itself (same r x 128 MACs per token and
+// head) and RoPE reduces to one cos/sin-weighted sum per accumulator.
+
+#include "palu_dev.h"
+
+namespace palu {
+
+// table[p][slot(c')] = fp16(cos(p w_c')) for c' < 64, fp16(sin(p w_{c'-64})) otherwise.
+__global__ __launch_bounds__(256) void rope_table_kernel(uint16_t* table, int n_pos, float theta) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;      // one (position, pair) per thread
+  const int p = idx >> 6, f = idx & 63;
+  if (p >= n_pos) return;
+  double c = 1.0, s = 0.0;
+  if (theta > 0.f) {
+    const double w = pow((double)theta, -2.0 * (double)f / (double)kDHead);
+    sincos((double)p * w, &s, &c);
+  }
+  uint16_t* row = table + (size_t)p * kDHead;
+  row[rope_slot(f)] = F16::from_float((float)c);
+  row[rope_slot(f + kHalf)] = F16::from_float((float)s);
+}
+
+// grid (n_heads, batch), 256 threads.
+template <typename T>
+__global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
+  __shared__ float qr[kDHead];
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x;
+  const Meta& m = a.meta;
+  const int j = m.group_of_head[h];
+  const int u = h - m.head_off[j];
+  const int r = m.k_off[j + 1] - m.k_off[j];
+  const int width = (m.head_off[j + 1] - m.head_off[j]) * kDHead;
+
+  if (tid < kHalf) {
+    const uint16_t* qp = a.q + ((size_t)b * m.n_heads + h) * kDHead;
+    const double x0 = (double)T::to_float(qp[tid]);
+    const double x1 = (double)T::to_float(qp[tid + kHalf]);
+    double c = 1.0, s = 0.0;
+    if (a.theta > 0.f) {
+      const double w = pow((double)a.theta, -2.0 * (double)tid / (double)kDHead);
+      sincos((double)a.q_pos[b] * w, &s, &c);
+    }
+    qr[tid] = (float)(x0 * c - x1 * s);
+    qr[tid + kHalf] = (float)(x1 * c + x0 * s);
+  }
+  __syncthreads();
+
+  const uint16_t* B = a.Bk + m.bk_off[j] + u * kDHead;                 // row k at B + k*width
+  uint16_t* out = a.mfold + (size_t)b * a.mfold_bstride + m.bk_off[j] + (size_t)u * r * kDHead;
+  const int n_items = (r / 16) * 256;           // (k-step, row tile, lane) triples, 8 k-values each
+  for (int it = tid; it < n_items; it += 256) {
+    const int lane = it & 63;
+    const int rt = (it >> 6) & 3;
+    const int ks = it >> 8;
+    const int cp = 32 * rt + (lane & 31);       // feature c' of this A-operand row
+    const int f = cp & 63;
+    const bool is_w = cp >= kHalf;
+    const float qa = qr[f], qb = qr[f + kHalf];
+    const int k0 = 16 * ks + 8 * (lane >> 5);
+    uint16_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint16_t* row = B + (size_t)(k0 + e) * width;
+      const float b1 = T::to_float(row[f]);
+      const float b2 = T::to_float(row[f + kHalf]);
+      const float val = is_w ? (qb * b1 - qa * b2) : (qa * b1 + qb * b2);
+      v[e] = T::from_float(val);
+    }
+    uint4v pk;
+    pk.x = v[0] | ((uint32_t)v[1] << 16);
+    pk.y = v[2] | ((uint32_t)v[3] << 16);
+    pk.z = v[4] | ((uint32_t)v[5] << 16);
+    pk.w = v[6] | ((uint32_t)v[7] << 16);
+    *reinterpret_cast<uint4v*>(out + (size_t)it * 8) = pk;
+  }
+}
+
+template __global__ void fold_kernel<F16>(FoldArgs);
+template __global__ void fold_kernel<BF16>(FoldArgs);
+
+}  // namespace palu

@@ -1,0 +1,75 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol the
+header declares, and validates arguments on the host (no kernel is launched)."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2407_21118_amd as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "palu.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(palu_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = P.load_library()
+    names = declared_symbols()
+    assert {"palu_encode", "palu_attn_decode", "palu_quant_latent"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings_and_version():
+    assert P.palu_version() >= 100
+    assert P.palu_status_string(0) == "ok"
+    for s in (-1, -2, -3, -4, -99):
+        assert P.palu_status_string(s)
+
+
+def desc(**kw):
+    a = dict(n_heads=8, d_head=128, group_head_off=[0, 4, 8], k_rank_off=[0, 64, 128], v_rank_off=[0, 64, 128])
+    a.update(kw)
+    return P.LayerDesc(**a)
+
+
+def test_workspace_queries_are_host_only():
+    d = desc()
+    assert P.palu_attn_decode_workspace_bytes(d, 2, 1000) > 0
+    assert P.palu_encode_workspace_bytes(d, 0, 3) > 0
+    assert P.palu_rope_table_bytes(128, 1000) == 1000 * 128 * 2
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(k_rank_off=[0, 60, 128]), -1),                 # rank not a multiple of 32
+    (dict(group_head_off=[0, 4, 7]), -1),                # heads do not add up
+    (dict(group_head_off=[0, 8, 8]), -1),                # empty group
+    (dict(d_head=64), -2),                               # unsupported head width
+    (dict(act_dtype=5), -1),
+    (dict(k_latent_dtype=P.PALU_I4, k_rank_off=[0, 64, 128]), -1),   # int4 needs ranks in multiples of the block
+    (dict(k_rank_off=[0, 4096, 8192]), -2),              # rank above the build limit
+])
+def test_descriptor_validation(kw, status):
+    with pytest.raises(P.PaluError) as e:
+        P.palu_attn_decode_workspace_bytes(desc(**kw), 1, 128)
+    assert e.value.status == status
+
+
+def test_null_and_range_arguments():
+    lib = P.load_library()
+    d = desc()
+    out = ctypes.c_size_t(0)
+    assert lib.palu_attn_decode_workspace_bytes(None, 1, 1, ctypes.byref(out)) == -1
+    assert lib.palu_attn_decode_workspace_bytes(d.ref(), 0, 1, ctypes.byref(out)) == -1
+    assert lib.palu_attn_decode_workspace_bytes(d.ref(), 1, 1, None) == -1
+    assert lib.palu_rope_table_bytes(128, 0, ctypes.byref(out)) == -1
+    assert lib.palu_rope_table_init(10000.0, 128, 16, None, None) == -1
+    assert lib.palu_encode(d.ref(), 2, None, 1, None, None, 128, None, None, 0, None) == -1
+    assert lib.palu_quant_latent(d.ref(), 0, None, 128, 1, None, None, None, None) == -1
+    assert lib.palu_attn_decode(d.ref(), 1, 8, 8, *([None] * 13), 8, None, None, 0, None) == -1

@@ -1,0 +1,100 @@
+"""GPU parity: HIP path through the C ABI vs the CPU oracle, element by element,
+on seeded inputs at sizes the oracle finishes in seconds.  Shapes span several
+32-token tiles, several sequence splits and a ragged tail."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import palu_oracle as O
+from workloads import synth
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import TOL_FP, TOL_I4, rel_err, run_hip, run_oracle, say  # noqa: E402
+
+
+def check(case, tol, **kw):
+    say(f"[parity] {case.name} dtype={case.dtype} B={case.batch} L={case.seq} "
+        f"groups={case.layer.n_groups} Rk={case.layer.R_k} kw={ {k: v for k, v in kw.items() if k != 'quant'} }")
+    got = run_hip(case, **kw)
+    ref = run_oracle(case, **{k: v for k, v in kw.items() if k in ("quant", "k_i4", "v_i4")})
+    assert np.isfinite(got).all()
+    whole, rows = rel_err(got, ref)
+    say(f"         rel err whole={whole:.3e} worst row={rows:.3e} (tol {tol})")
+    assert whole <= tol and rows <= tol
+    return whole
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_config1_tiny_full_size(dtype):
+    """Configuration 1 at full size: 8 heads, 2 groups of 4, rank 128, L = 1024."""
+    layer = synth.config_layer("1")
+    case = synth.make_case_orthonormal(layer, 1, 1024, seed=0, dtype=dtype)
+    case.name = "cfg1"
+    check(case, TOL_FP)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_config2_shape_reduced_length(dtype):
+    """7B shape (32 heads, 8 groups of 4, rank 256), two sequences of different
+    length, ragged tail (777 = 24 tiles + 9)."""
+    layer = synth.config_layer("2")
+    case = synth.make_case_svd(layer, 2, 777, seed=0, dtype=dtype)
+    case.seq_lens = np.array([777, 300], np.int32)
+    case.q_pos = np.array([776, 299], np.int32)
+    case.name = "cfg2-reduced"
+    check(case, TOL_FP)
+
+
+def test_config3_ragged_ranks_reduced_length():
+    layer = synth.config_layer("3")
+    assert max(np.diff(layer.k_rank_off)) > 256 and min(np.diff(layer.k_rank_off)) < 256
+    case = synth.make_case_svd(layer, 2, 500, seed=0)
+    case.name = "cfg3-reduced"
+    check(case, TOL_FP)
+
+
+@pytest.mark.parametrize("k_i4,v_i4", [(True, True), (False, True)])
+def test_config4_int4_reduced_length(k_i4, v_i4):
+    layer = synth.config_layer("4")
+    case = synth.make_case_svd(layer, 2, 400, seed=0, rotate=True)
+    case.name = "cfg4-reduced"
+    quant = {"k": O.quant_latent(case.Hk), "v": O.quant_latent(case.Hv)}
+    check(case, TOL_I4, k_i4=k_i4, v_i4=v_i4, quant=quant)
+
+
+def test_config5a_group_size_1_reduced_length():
+    layer = synth.config_layer("5a")
+    case = synth.make_case_svd(layer, 2, 333, seed=0)
+    case.name = "cfg5a-reduced"
+    check(case, TOL_FP)
+
+
+def test_custom_positions_and_single_token():
+    layer = synth.uniform_layer(8, 4, 64)
+    case = synth.make_case_orthonormal(layer, 2, 70, seed=3)
+    case.k_pos = (np.arange(70) * 37 + 5).astype(np.int32)
+    case.q_pos = np.array([4000, 17], np.int32)
+    case.name = "custom-pos"
+    check(case, TOL_FP)
+    one = synth.make_case_orthonormal(layer, 1, 1, seed=4)
+    one.name = "L=1"
+    check(one, TOL_FP)
+
+
+def test_no_rope():
+    """rope_theta <= 0: scores are (q B_k^T) H_k^T / sqrt(d_h) (Eq. 5)."""
+    layer = synth.uniform_layer(8, 2, 96, rope_theta=0.0)
+    case = synth.make_case_orthonormal(layer, 1, 200, seed=5)
+    case.name = "no-rope"
+    check(case, TOL_FP)
+
+
+def test_peaked_softmax_and_large_logits():
+    """Scaled-up queries give logits of order +-40: the running-max softmax must not overflow."""
+    layer = synth.uniform_layer(8, 4, 128)
+    case = synth.make_case_orthonormal(layer, 1, 600, seed=6)
+    case.q = synth.round_to(case.q * 12.0, "f16")
+    case.name = "peaked"
+    check(case, TOL_FP)
