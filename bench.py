@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Decode-attention benchmark over a low-rank latent KV-cache on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input,
+with everything already resident in HBM: down-project the new token into the
+key and value caches (palu_encode x2), quantize the new rows when the cache is
+int4 (palu_quant_latent), then one attention decode step (palu_attn_decode:
+fold, scores with on-the-fly key reconstruction + RoPE, softmax partials +
+P.H_v per split, merge + B_v).  Consecutive steps cycle through a ring of
+distinct latent caches larger than the 256 MB last-level cache so that every
+step streams its latents from HBM.
+
+Prints ONE JSON line (see README for the fields).
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_F16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 matrix peak
+HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak
+
+
+def log(msg: str) -> None:
+    print(msg, file=sys.stderr, flush=True)
+
+
+def algorithmic_work(layer, batch, seq, k_i4, v_i4):
+    """FLOPs and HBM bytes the method itself needs per decode step."""
+    T = batch * seq
+    d_h = layer.d_head
+    recon = 0
+    pv = 0
+    for j in range(layer.n_groups):
+        s = layer.group_size(j)
+        recon += 2 * T * (layer.k_rank_off[j + 1] - layer.k_rank_off[j]) * s * d_h
+        pv += 2 * T * (layer.v_rank_off[j + 1] - layer.v_rank_off[j]) * s
+
+    def side_bytes(R, i4):
+        return T * (R // 2 + (R // layer.quant_block) * 4) if i4 else T * R * 2
+
+    return {
+        "score_flops": recon,                               # H_k . B_k reconstruction (the q.K product adds < 1 %)
+        "pv_flops": pv,
+        "k_latent_bytes": side_bytes(layer.R_k, k_i4),
+        "v_latent_bytes": side_bytes(layer.R_v, v_i4),
+        "b_bytes": 2 * (layer.b_elems("k") + layer.b_elems("v")),
+        "a_bytes": 2 * layer.n_heads * d_h * (layer.R_k + layer.R_v),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="2", help="workload: 1, 2 (7B shape, seq 16K, headline), 2-4k, 2-64k, 3, 4, 4v, 5a, 5b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ring-gib", type=float, default=1.0, help="distinct latent bytes to cycle through")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2407_21118_amd as P
+    from workloads import device as wd
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    P.load_library()
+    torch.cuda.set_device(0)
+
+    cfg = args.config
+    v_only = cfg == "4v"
+    base_cfg = "4" if v_only else cfg
+    k_i4 = base_cfg == "4" and not v_only
+    v_i4 = base_cfg == "4"
+
+    # ---- inputs -----------------------------------------------------------
+    t0 = time.time()
+    from workloads import synth
+    layer = synth.config_layer(base_cfg.split("-")[0])
+    batch, seq = synth.FULL_SIZES[base_cfg]
+    work = algorithmic_work(layer, batch, seq, k_i4, v_i4)
+    set_bytes = batch * seq * (layer.R_k + layer.R_v) * 2
+    free_b = torch.cuda.mem_get_info()[0]
+    n_sets = max(1, min(int(np.ceil(args.ring_gib * 2 ** 30 / set_bytes)) + 1, int(0.5 * free_b / set_bytes)))
+    case = wd.make_device_case(base_cfg, seed=0, dtype="f16", n_sets=n_sets)
+    log(f"[bench] config {cfg}: batch {batch} seq {seq} groups {layer.n_groups} R_k {layer.R_k} R_v {layer.R_v}; "
+        f"{n_sets} cache sets of {set_bytes / 2**20:.0f} MiB built in {time.time() - t0:.1f}s")
+
+    act = P.PALU_F16
+    desc = P.LayerDesc(layer.n_heads, layer.d_head, layer.group_head_off, layer.k_rank_off, layer.v_rank_off, act,
+                       P.PALU_I4 if k_i4 else act, P.PALU_I4 if v_i4 else act, layer.quant_block, layer.rope_theta)
+    table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, seq)
+    ws = torch.empty(P.palu_attn_decode_workspace_bytes(desc, batch, seq), dtype=torch.uint8, device="cuda")
+    ws_ek = torch.empty(P.palu_encode_workspace_bytes(desc, 0, batch), dtype=torch.uint8, device="cuda")
+    ws_ev = torch.empty(P.palu_encode_workspace_bytes(desc, 1, batch), dtype=torch.uint8, device="cuda")
+    out = torch.empty((batch, layer.n_heads, layer.d_head), dtype=torch.float32, device="cuda")
+    dst_row = (torch.arange(batch, dtype=torch.int32, device="cuda") * seq + (seq - 1)).contiguous()
+    nbk, nbv = layer.R_k // layer.quant_block, layer.R_v // layer.quant_block
+
+    # int4 caches: quantize every set once with the library's own quantizer
+    qk, qv = [], []
+    if k_i4 or v_i4:
+        for s in range(n_sets):
+            for side, flag, H, R, nb, store in ((0, k_i4, case.Hk, layer.R_k, nbk, qk), (1, v_i4, case.Hv, layer.R_v, nbv, qv)):
+                if not flag:
+                    continue
+                codes = torch.empty((batch, seq, R // 2), dtype=torch.uint8, device="cuda")
+                sc = torch.empty((batch, seq, nb), dtype=torch.float16, device="cuda")
+                zp = torch.empty_like(sc)
+                P.palu_quant_latent(desc, side, H[s], R, batch * seq, codes, sc, zp)
+                store.append((codes, sc, zp))
+        torch.cuda.synchronize()
+    # staging rows for the new token when the cache is int4 (encode -> fp16 row -> quantize into the cache)
+    new_k = torch.empty((batch, layer.R_k), dtype=torch.float16, device="cuda")
+    new_v = torch.empty((batch, layer.R_v), dtype=torch.float16, device="cuda")
+
+    def step(i: int, events=None):
+        s = i % n_sets
+        if k_i4:
+            P.palu_encode(desc, 0, case.x_new, case.Ak, new_k, layer.R_k, None, ws_ek)
+            codes, sc, zp = qk[s]
+            P.palu_quant_latent(desc, 0, new_k, layer.R_k, batch, codes, sc, zp, dst_row)
+            hk, kq = codes, dict(hk_scale=sc, hk_zero=zp)
+        else:
+            P.palu_encode(desc, 0, case.x_new, case.Ak, case.Hk[s], layer.R_k, dst_row, ws_ek)
+            hk, kq = case.Hk[s], {}
+        if v_i4:
+            P.palu_encode(desc, 1, case.x_new, case.Av, new_v, layer.R_v, None, ws_ev)
+            codes, sc, zp = qv[s]
+            P.palu_quant_latent(desc, 1, new_v, layer.R_v, batch, codes, sc, zp, dst_row)
+            hv, vq = codes, dict(hv_scale=sc, hv_zero=zp)
+        else:
+            P.palu_encode(desc, 1, case.x_new, case.Av, case.Hv[s], layer.R_v, dst_row, ws_ev)
+            hv, vq = case.Hv[s], {}
+        P.palu_attn_decode(desc, batch, seq, seq, case.q, case.q_pos, hk, hv, case.Bk, case.Bv, table, seq,
+                           out=out, workspace=ws, stage_events=events, **kq, **vq)
+
+    # ---- timed region ------------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall) * 1e3
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = max(gpu_ms, 0.0) / args.steps
+    log(f"[bench] {args.steps} steps: {gpu_ms:.3f} ms on the stream, {wall_ms:.3f} ms wall")
+
+    # ---- per-stage durations: same steps again with event hooks between the stages
+    n_prof = min(args.steps, 100)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(P.PALU_DECODE_STAGES + 1)] for _ in range(n_prof)]
+    for row in evs:
+        for e in row:
+            e.record()              # creates the HIP event handles
+    torch.cuda.synchronize()
+    for i in range(n_prof):
+        step(args.warmup + i, evs[i])
+    torch.cuda.synchronize()
+    stage_ms = np.array([[row[k].elapsed_time(row[k + 1]) for k in range(P.PALU_DECODE_STAGES)] for row in evs])
+    stage_us = {n: float(np.mean(stage_ms[:, k]) * 1e3) for k, n in enumerate(["fold", "score", "value", "combine"])}
+    stage_us_med = {n: float(np.median(stage_ms[:, k]) * 1e3) for k, n in enumerate(["fold", "score", "value", "combine"])}
+    log(f"[bench] stage mean us: {stage_us}  median us: {stage_us_med}")
+
+    score_tflops = work["score_flops"] / (stage_us["score"] * 1e-6) / 1e12
+    k_gbs = work["k_latent_bytes"] / (stage_us["score"] * 1e-6) / 1e9
+    v_gbs = work["v_latent_bytes"] / (stage_us["value"] * 1e-6) / 1e9
+    total_gbs = (work["k_latent_bytes"] + work["v_latent_bytes"] + work["b_bytes"] + work["a_bytes"]) / (ms_per_step * 1e-3) / 1e9
+
+    result = {
+        "metric": "decode_attn_us_per_step",
+        "value": ms_per_step * 1e3,
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16" if not (k_i4 or v_i4) else ("i4+f16" if k_i4 else "f16 keys, i4 values"),
+        "data": "synthetic",
+        "config": {"workload": f"config {cfg}: Llama-2-7B-shaped layer decode, batch {batch}, seq {seq}, "
+                               f"{layer.n_groups} groups, R_k {layer.R_k}, R_v {layer.R_v}",
+                   "batch": batch, "seq_len": seq, "n_heads": layer.n_heads, "group_size": layer.group_size(0),
+                   "cache_sets": n_sets, "step": "encode K + encode V (+ quantize) + attn_decode"},
+        "roofline": {
+            "kernel": "score_kernel (key reconstruction + RoPE + q.K on MFMA)",
+            "bound": "mfma", "achieved": score_tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": score_tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+            "launch_us": stage_us["score"], "flops_per_launch": work["score_flops"],
+            "latent_read_GBps": k_gbs,
+        },
+        "roofline_value": {
+            "kernel": "value_kernel (softmax partials + P.H_v, split-K)",
+            "bound": "hbm", "achieved": v_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": v_gbs / HBM_PEAK_GBS,
+            "traffic": None, "launch_us": stage_us["value"], "bytes_per_launch": work["v_latent_bytes"],
+        },
+        "stage_us": stage_us,
+        "stage_us_median": stage_us_med,
+        "step_GBps_algorithmic": total_gbs,
+        "wall_ms_per_step": wall_ms / args.steps,
+    }
+
+    # ---- CPU baseline: the oracle as it stands, one decode step ------------------
+    if not args.no_cpu_baseline:
+        from oracle import palu_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = len(os.sched_getaffinity(0))
+        nb = 1                                          # one sequence of the batch, scaled by batch
+        lim = min(seq, 16384)
+        Hk = case.Hk[0][:nb, :lim].float().cpu().numpy()
+        Hv = case.Hv[0][:nb, :lim].float().cpu().numpy()
+        qn = case.q[:nb].float().cpu().numpy()
+        Bk = case.Bk.float().cpu().numpy()
+        Bv = case.Bv.float().cpu().numpy()
+        t_c = time.perf_counter()
+        O.attn_decode(qn, np.full((nb,), lim - 1), Hk, Hv, Bk, Bv, layer.group_head_off, layer.k_rank_off,
+                      layer.v_rank_off, layer.d_head, layer.rope_theta)
+        cpu_s = time.perf_counter() - t_c
+        scale = (batch / nb) * (seq / lim)
+        result["cpu_baseline"] = {
+            "value": cpu_s * scale * 1e6, "unit": "us/step", "cores": threads, "kind": "oracle",
+            "sample": f"{nb} of {batch} sequences x {lim} of {seq} cached tokens, all heads, attention only "
+                      f"(no encode); measured {cpu_s:.2f} s, scaled x{scale:g}",
+            "affinity_cores": len(os.sched_getaffinity(0)),
+        }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -121,13 +121,17 @@ int palu_encode(const palu_layer_desc* desc, int which, const void* x, int32_t n
  *     s = fp16((max - min) / 15), s == 0 -> 1;   z = fp16(clamp(rint(-min / s), +-65504));
  *     code = clamp(rint(x / s) + z, 0, 15)        (float32 arithmetic, ties to even)
  *   latent      DEVICE act_dtype, token t at latent + t*row_stride_elems, R elements
- *   codes       DEVICE uint8 [n_tok, R/2]; byte c/2 holds channel c (c even) in its
+ *   codes       DEVICE uint8 rows of R/2 bytes; byte c/2 holds channel c (c even) in its
  *               low nibble and channel c+1 in its high nibble
- *   scale,zero  DEVICE float16 [n_tok, R/quant_block]
+ *   scale,zero  DEVICE float16 rows of R/quant_block
+ *   dst_row     DEVICE int32 [n_tok]: token t is written to row dst_row[t] of codes,
+ *               scale and zero (appending to several sequences of a cache at once),
+ *               or NULL for row t
  * R must be a multiple of quant_block.
  */
 int palu_quant_latent(const palu_layer_desc* desc, int which, const void* latent, int64_t row_stride_elems,
-                      int32_t n_tok, uint8_t* codes, void* scale, void* zero, void* stream);
+                      int32_t n_tok, uint8_t* codes, void* scale, void* zero, const int32_t* dst_row,
+                      void* stream);
 
 /*
  * One decode step of attention over the latent cache for `batch` sequences
@@ -166,6 +170,29 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
                      const void* Bk, const void* Bv,
                      const void* rope_table, int32_t rope_table_len,
                      float* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Same call with per-stage timing hooks, for benchmarks that price each
+ * stage against its own roofline.  The decode step runs as PALU_DECODE_STAGES
+ * stages (0 fold the rotated query into B_k, 1 scores = reconstruction + RoPE +
+ * query product, 2 softmax partials and P H_v per sequence split, 3 merge
+ * splits and apply B_v).  `stage_events` is a HOST array of
+ * PALU_DECODE_STAGES + 1 hipEvent_t handles created by the caller (each passed
+ * as void*): event i is recorded on `stream` before stage i is enqueued, the
+ * last one after the final stage.  NULL disables the hooks (then identical to
+ * palu_attn_decode).  Recording events between the stages inserts queue
+ * barriers, so a step timed this way is slower than an unhooked one.
+ */
+enum { PALU_DECODE_STAGES = 4 };
+int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                            const void* q, const int32_t* q_pos,
+                            const void* hk, const void* hk_scale, const void* hk_zero,
+                            const void* hv, const void* hv_scale, const void* hv_zero,
+                            const int32_t* k_pos, const int32_t* seq_lens,
+                            const void* Bk, const void* Bv,
+                            const void* rope_table, int32_t rope_table_len,
+                            float* out, void* workspace, size_t workspace_bytes, void* stream,
+                            void* const* stage_events);
 
 #ifdef __cplusplus
 }

@@ -13,6 +13,7 @@ import os
 from typing import Optional, Sequence
 
 PALU_F16, PALU_BF16, PALU_I4 = 0, 1, 2
+PALU_DECODE_STAGES = 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libpalu_hip.so"
@@ -66,10 +67,12 @@ def load_library():
     lib.palu_rope_table_init.argtypes = [ctypes.c_float, i32, i32, vp, vp]
     lib.palu_encode_workspace_bytes.argtypes = [dp, ctypes.c_int, i32, szp]
     lib.palu_encode.argtypes = [dp, ctypes.c_int, vp, i32, vp, vp, i64, vp, vp, sz, vp]
-    lib.palu_quant_latent.argtypes = [dp, ctypes.c_int, vp, i64, i32, vp, vp, vp, vp]
+    lib.palu_quant_latent.argtypes = [dp, ctypes.c_int, vp, i64, i32, vp, vp, vp, vp, vp]
     lib.palu_attn_decode_workspace_bytes.argtypes = [dp, i32, i32, szp]
     lib.palu_attn_decode.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                      vp, i32, vp, vp, sz, vp]
+    lib.palu_attn_decode_staged.argtypes = lib.palu_attn_decode.argtypes + [ctypes.POINTER(vp)]
+    lib.palu_attn_decode_staged.restype = ctypes.c_int
     for name in ("palu_rope_table_bytes", "palu_rope_table_init", "palu_encode_workspace_bytes", "palu_encode",
                  "palu_quant_latent", "palu_attn_decode_workspace_bytes", "palu_attn_decode"):
         getattr(lib, name).restype = ctypes.c_int
@@ -182,10 +185,10 @@ def palu_encode(desc: LayerDesc, which: int, x, A, latent, row_stride_elems: int
 
 
 def palu_quant_latent(desc: LayerDesc, which: int, latent, row_stride_elems: int, n_tok: int,
-                      codes, scale, zero, stream=None):
-    _need_cuda(latent, codes, scale, zero)
+                      codes, scale, zero, dst_row=None, stream=None):
+    _need_cuda(latent, codes, scale, zero, dst_row)
     _check(load_library().palu_quant_latent(desc.ref(), which, _ptr(latent), int(row_stride_elems), int(n_tok),
-                                            _ptr(codes), _ptr(scale), _ptr(zero), _stream(stream)),
+                                            _ptr(codes), _ptr(scale), _ptr(zero), _ptr(dst_row), _stream(stream)),
            "palu_quant_latent")
     return codes, scale, zero
 
@@ -199,7 +202,9 @@ def palu_attn_decode_workspace_bytes(desc: LayerDesc, batch: int, max_seq: int) 
 
 def palu_attn_decode(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, q, q_pos, hk, hv, Bk, Bv,
                      rope_table, rope_table_len: int, out=None, workspace=None, k_pos=None, seq_lens=None,
-                     hk_scale=None, hk_zero=None, hv_scale=None, hv_zero=None, stream=None):
+                     hk_scale=None, hk_zero=None, hv_scale=None, hv_zero=None, stream=None, stage_events=None):
+    """stage_events: optional list of PALU_DECODE_STAGES + 1 torch.cuda.Event(enable_timing=True) that were
+    already recorded once (so that their HIP handles exist); routes through palu_attn_decode_staged."""
     import torch
     if out is None:
         out = torch.empty((batch, desc.n_heads, desc.d_head), dtype=torch.float32, device=q.device)
@@ -208,9 +213,15 @@ def palu_attn_decode(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, q,
                                 device=q.device)
     _need_cuda(q, q_pos, hk, hv, Bk, Bv, rope_table, out, workspace, k_pos, seq_lens, hk_scale, hk_zero,
                hv_scale, hv_zero)
-    _check(load_library().palu_attn_decode(
-        desc.ref(), batch, seq_len, max_seq, _ptr(q), _ptr(q_pos), _ptr(hk), _ptr(hk_scale), _ptr(hk_zero),
-        _ptr(hv), _ptr(hv_scale), _ptr(hv_zero), _ptr(k_pos), _ptr(seq_lens), _ptr(Bk), _ptr(Bv),
-        _ptr(rope_table), int(rope_table_len), _ptr(out), _ptr(workspace),
-        workspace.numel() * workspace.element_size(), _stream(stream)), "palu_attn_decode")
+    args = (desc.ref(), batch, seq_len, max_seq, _ptr(q), _ptr(q_pos), _ptr(hk), _ptr(hk_scale), _ptr(hk_zero),
+            _ptr(hv), _ptr(hv_scale), _ptr(hv_zero), _ptr(k_pos), _ptr(seq_lens), _ptr(Bk), _ptr(Bv),
+            _ptr(rope_table), int(rope_table_len), _ptr(out), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream(stream))
+    if stage_events is None:
+        _check(load_library().palu_attn_decode(*args), "palu_attn_decode")
+    else:
+        if len(stage_events) != PALU_DECODE_STAGES + 1:
+            raise ValueError("stage_events needs PALU_DECODE_STAGES + 1 events")
+        arr = (ctypes.c_void_p * len(stage_events))(*[ctypes.c_void_p(e.cuda_event) for e in stage_events])
+        _check(load_library().palu_attn_decode_staged(*args, arr), "palu_attn_decode_staged")
     return out

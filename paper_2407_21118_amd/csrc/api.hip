@@ -88,49 +88,70 @@ int check_desc(const palu_layer_desc* d, Meta* m) {
 }
 
 // ---- score-path work units ----------------------------------------------------
-// Rank classes of the weight-stationary score kernel: the rank decides how many
-// k-steps of 16 a wavefront keeps in registers and whether it owns a whole head.
-enum { kClsKs4 = 0, kClsKs8, kClsKs16, kClsKs32Half, kNumScoreCls };
-constexpr int kScoreMaxWidth = 512;      // latent columns one workgroup stages per token
+// The weight-stationary score kernel is compiled once per (rank, groups per
+// workgroup): rank = 32*(c+1), c = 0..15.  Up to rank 256 a wavefront owns a whole
+// head and a workgroup takes 4 heads; they may come from 1, 2 or 4 adjacent groups
+// of equal rank as long as the staged row stays within 512 columns.  Above rank
+// 256 a wavefront owns half a head and a workgroup takes 2 heads of one group.
+constexpr int kNumRankCls = 16;
+constexpr int kNumScoreCls = kNumRankCls * 3;     // (rank class, log2 of groups per workgroup)
+constexpr int kScoreMaxWidth = 512;               // latent columns one workgroup stages per token
 
-int score_class(int r) {
-  if (r <= 64) return kClsKs4;
-  if (r <= 128) return kClsKs8;
-  if (r <= 256) return kClsKs16;
-  if (r <= 512) return kClsKs32Half;
-  return -1;
-}
+int rank_class(int r) { return (r >= 32 && r <= 512 && r % 32 == 0) ? r / 32 - 1 : -1; }
+bool rank_class_half(int rc) { return rc >= 8; }
 
 struct ScorePlan {
-  Units units[kNumScoreCls];
-  int max_width[kNumScoreCls];    // widest latent column range staged by a unit of the class
+  int n_cls;                          // classes in use
+  int cls_id[kNumScoreCls];           // rank class * 3 + log2(G) of each class in use
+  Units units[kNumScoreCls];          // indexed like cls_id
   int total_units;
   bool two_parts[PALU_MAX_HEADS];
 };
 
 int plan_score(const Meta& m, ScorePlan* p) {
-  std::memset(p, 0, sizeof(*p));
+  p->n_cls = 0;
+  p->total_units = 0;
+  std::memset(p->two_parts, 0, sizeof(p->two_parts));
+  int slot_of[kNumScoreCls];
+  for (int& v : slot_of) v = -1;
   int h = 0;
   while (h < m.n_heads) {
     const int j0 = m.group_of_head[h];
-    const int cls = score_class(m.k_off[j0 + 1] - m.k_off[j0]);
-    if (cls < 0) return PALU_ERR_UNSUPPORTED;
-    const int max_heads = cls == kClsKs32Half ? 2 : 4;
-    int nh = 1;
-    while (h + nh < m.n_heads && nh < max_heads) {
-      const int jn = m.group_of_head[h + nh];
-      if (score_class(m.k_off[jn + 1] - m.k_off[jn]) != cls) break;
-      if (m.k_off[jn + 1] - m.k_off[j0] > kScoreMaxWidth) break;
-      ++nh;
+    const int r = m.k_off[j0 + 1] - m.k_off[j0];
+    const int rc = rank_class(r);
+    if (rc < 0) return PALU_ERR_UNSUPPORTED;
+    int nh, lg = 0;
+    if (rank_class_half(rc)) {
+      nh = std::min(2, m.head_off[j0 + 1] - h);
+    } else {
+      nh = std::min(4, m.head_off[j0 + 1] - h);
+      if (h == m.head_off[j0] && nh < 4) {
+        // a small group: widen the unit over 2 or 4 whole adjacent groups of the same rank and size
+        const int s = m.head_off[j0 + 1] - m.head_off[j0];
+        for (int g : {4, 2}) {
+          if (g * s > 4 || g * r > kScoreMaxWidth || j0 + g > m.n_groups) continue;
+          bool same = true;
+          for (int x = 1; x < g; ++x)
+            same = same && (m.k_off[j0 + x + 1] - m.k_off[j0 + x] == r) &&
+                   (m.head_off[j0 + x + 1] - m.head_off[j0 + x] == s);
+          if (same) { nh = g * s; lg = g == 4 ? 2 : 1; break; }
+        }
+      }
     }
-    Units& u = p->units[cls];
+    const int id = rc * 3 + lg;
+    if (slot_of[id] < 0) {
+      slot_of[id] = p->n_cls;
+      p->cls_id[p->n_cls] = id;
+      p->units[p->n_cls].n_units = 0;
+      ++p->n_cls;
+    }
+    Units& u = p->units[slot_of[id]];
     if (u.n_units >= kMaxUnits) return PALU_ERR_UNSUPPORTED;
     u.h0[u.n_units] = (uint16_t)h;
     u.nh[u.n_units] = (uint8_t)nh;
     ++u.n_units;
     ++p->total_units;
-    p->max_width[cls] = std::max(p->max_width[cls], m.k_off[m.group_of_head[h + nh - 1] + 1] - m.k_off[j0]);
-    if (cls == kClsKs32Half)
+    if (rank_class_half(rc))
       for (int x = 0; x < nh; ++x) p->two_parts[h + x] = true;
     h += nh;
   }
@@ -205,29 +226,41 @@ int allow_lds(K kernel, size_t bytes) {
 }
 
 using ScoreFn = void (*)(ScoreArgs);
-ScoreFn score_fn(int act, bool i4, int cls) {
-  if (act == PALU_F16 && !i4) {
-    switch (cls) {
-      case kClsKs4: return score_kernel<F16, 4, 4, false>;
-      case kClsKs8: return score_kernel<F16, 8, 4, false>;
-      case kClsKs16: return score_kernel<F16, 16, 4, false>;
-      default: return score_kernel<F16, 32, 2, false>;
-    }
+template <typename T, bool I4, int NKS>
+ScoreFn score_fn_g(int lg) {
+  if constexpr (NKS > 16) {
+    return score_kernel<T, NKS, 2, 1, I4>;
+  } else {
+    if constexpr (NKS <= 8) { if (lg == 2) return score_kernel<T, NKS, 4, 4, I4>; }
+    if (lg == 1) return score_kernel<T, NKS, 4, 2, I4>;
+    return score_kernel<T, NKS, 4, 1, I4>;
   }
-  if (act == PALU_F16 && i4) {
-    switch (cls) {
-      case kClsKs4: return score_kernel<F16, 4, 4, true>;
-      case kClsKs8: return score_kernel<F16, 8, 4, true>;
-      case kClsKs16: return score_kernel<F16, 16, 4, true>;
-      default: return score_kernel<F16, 32, 2, true>;
-    }
+}
+template <typename T, bool I4>
+ScoreFn score_fn_t(int rc, int lg) {
+  switch (rc) {
+    case 0: return score_fn_g<T, I4, 2>(lg);
+    case 1: return score_fn_g<T, I4, 4>(lg);
+    case 2: return score_fn_g<T, I4, 6>(lg);
+    case 3: return score_fn_g<T, I4, 8>(lg);
+    case 4: return score_fn_g<T, I4, 10>(lg);
+    case 5: return score_fn_g<T, I4, 12>(lg);
+    case 6: return score_fn_g<T, I4, 14>(lg);
+    case 7: return score_fn_g<T, I4, 16>(lg);
+    case 8: return score_fn_g<T, I4, 18>(lg);
+    case 9: return score_fn_g<T, I4, 20>(lg);
+    case 10: return score_fn_g<T, I4, 22>(lg);
+    case 11: return score_fn_g<T, I4, 24>(lg);
+    case 12: return score_fn_g<T, I4, 26>(lg);
+    case 13: return score_fn_g<T, I4, 28>(lg);
+    case 14: return score_fn_g<T, I4, 30>(lg);
+    default: return score_fn_g<T, I4, 32>(lg);
   }
-  switch (cls) {
-    case kClsKs4: return score_kernel<BF16, 4, 4, false>;
-    case kClsKs8: return score_kernel<BF16, 8, 4, false>;
-    case kClsKs16: return score_kernel<BF16, 16, 4, false>;
-    default: return score_kernel<BF16, 32, 2, false>;
-  }
+}
+ScoreFn score_fn(int act, bool i4, int cls_id) {
+  const int rc = cls_id / 3, lg = cls_id % 3;
+  if (i4) return score_fn_t<F16, true>(rc, lg);
+  return act == PALU_F16 ? score_fn_t<F16, false>(rc, lg) : score_fn_t<BF16, false>(rc, lg);
 }
 
 using ValueFn = void (*)(ValueArgs);
@@ -331,20 +364,21 @@ int palu_encode(const palu_layer_desc* desc, int which, const void* x, int32_t n
   a.k_splits = d / kEncRows;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 g1((unsigned)ceil_div(R, kEncCols), (unsigned)a.k_splits);
-  const unsigned g2 = (unsigned)(((long long)n_tok * (R / 2) + 255) / 256);
+  const dim3 g2((unsigned)ceil_div(R, 64), (unsigned)n_tok);
   if (desc->act_dtype == PALU_F16) {
     hipLaunchKernelGGL(encode_partial_kernel<F16>, g1, dim3(256), 0, s, a);
-    hipLaunchKernelGGL(encode_finish_kernel<F16>, dim3(g2), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(encode_finish_kernel<F16>, g2, dim3(256), 0, s, a);
   } else {
     hipLaunchKernelGGL(encode_partial_kernel<BF16>, g1, dim3(256), 0, s, a);
-    hipLaunchKernelGGL(encode_finish_kernel<BF16>, dim3(g2), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(encode_finish_kernel<BF16>, g2, dim3(256), 0, s, a);
   }
   return launch_ok();
 }
 
 // ------------------------------------------------------------------ quantize
 int palu_quant_latent(const palu_layer_desc* desc, int which, const void* latent, int64_t row_stride_elems,
-                      int32_t n_tok, uint8_t* codes, void* scale, void* zero, void* stream) {
+                      int32_t n_tok, uint8_t* codes, void* scale, void* zero, const int32_t* dst_row,
+                      void* stream) {
   Meta m;
   const int st = check_desc(desc, &m);
   if (st != PALU_OK) return st;
@@ -360,6 +394,7 @@ int palu_quant_latent(const palu_layer_desc* desc, int which, const void* latent
   a.codes = codes;
   a.scale = static_cast<uint16_t*>(scale);
   a.zero = static_cast<uint16_t*>(zero);
+  a.dst_row = dst_row;
   a.row_stride = row_stride_elems;
   a.n_tok = n_tok;
   a.R = R;
@@ -396,6 +431,20 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
                      const void* Bk, const void* Bv,
                      const void* rope_table, int32_t rope_table_len,
                      float* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return palu_attn_decode_staged(desc, batch, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale,
+                                 hv_zero, k_pos, seq_lens, Bk, Bv, rope_table, rope_table_len, out, workspace,
+                                 workspace_bytes, stream, nullptr);
+}
+
+int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                            const void* q, const int32_t* q_pos,
+                            const void* hk, const void* hk_scale, const void* hk_zero,
+                            const void* hv, const void* hv_scale, const void* hv_zero,
+                            const int32_t* k_pos, const int32_t* seq_lens,
+                            const void* Bk, const void* Bv,
+                            const void* rope_table, int32_t rope_table_len,
+                            float* out, void* workspace, size_t workspace_bytes, void* stream,
+                            void* const* stage_events) {
   Meta m;
   int st = check_desc(desc, &m);
   if (st != PALU_OK) return st;
@@ -426,6 +475,13 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   const int act = desc->act_dtype;
+  auto mark = [&](int i) -> int {
+    if (!stage_events) return PALU_OK;
+    return hipEventRecord(static_cast<hipEvent_t>(stage_events[i]), s) == hipSuccess ? PALU_OK : PALU_ERR_HIP;
+  };
+  if (stage_events)
+    for (int i = 0; i <= PALU_DECODE_STAGES; ++i)
+      if (!stage_events[i]) return PALU_ERR_INVALID_ARG;
 
   // 1. fold the rotated query into B_k
   {
@@ -436,8 +492,11 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
     a.mfold = reinterpret_cast<uint16_t*>(ws + w.mfold);
     a.mfold_bstride = w.mfold_bstride;
     a.theta = desc->rope_theta;
+    for (int f = 0; f < kHalf; ++f)
+      a.inv_freq[f] = desc->rope_theta > 0.f ? std::pow((double)desc->rope_theta, -2.0 * f / (double)PALU_D_HEAD) : 0.0;
     a.meta = m;
-    const dim3 g((unsigned)m.n_heads, (unsigned)batch);
+    const dim3 g((unsigned)m.n_heads, (unsigned)batch, (unsigned)kFoldSlices);
+    if ((st = mark(0)) != PALU_OK) return st;
     if (act == PALU_F16) hipLaunchKernelGGL(fold_kernel<F16>, g, dim3(256), 0, s, a);
     else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
     if ((st = launch_ok()) != PALU_OK) return st;
@@ -470,11 +529,12 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
     const int chunk_tiles = ceil_div(tiles, n_chunks);
     a.chunk_tokens = chunk_tiles * kTile;
     a.n_chunks = ceil_div(tiles, chunk_tiles);
-    for (int cls = 0; cls < kNumScoreCls; ++cls) {
-      if (sp.units[cls].n_units == 0) continue;
+    if ((st = mark(1)) != PALU_OK) return st;
+    for (int cls = 0; cls < sp.n_cls; ++cls) {
       a.units = sp.units[cls];
-      const size_t lds = (size_t)2 * kTile * (sp.max_width[cls] * 2 + kRowPad);
-      ScoreFn fn = score_fn(act, k_i4, cls);
+      const int width = 32 * (sp.cls_id[cls] / 3 + 1) << (sp.cls_id[cls] % 3);
+      const size_t lds = (size_t)2 * kTile * (width * 2 + kRowPad + kRopeRowB);
+      ScoreFn fn = score_fn(act, k_i4, sp.cls_id[cls]);
       if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
       const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
       hipLaunchKernelGGL(fn, dim3(grid), dim3(256), lds, s, a);
@@ -507,6 +567,7 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
     for (int h = 0; h < m.n_heads; ++h)
       if (sp.two_parts[h]) a.parts_mask_lo[h >> 5] |= 1u << (h & 31);
     a.meta = m;
+    if ((st = mark(2)) != PALU_OK) return st;
     for (int cls = 0; cls < kNumValCls; ++cls) {
       if (vp.units[cls].n_units == 0) continue;
       a.units = vp.units[cls];
@@ -530,9 +591,11 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
     a.o_stride = w.o_stride;
     a.meta = m;
     const dim3 g((unsigned)m.n_heads, (unsigned)batch);
+    if ((st = mark(3)) != PALU_OK) return st;
     if (act == PALU_F16) hipLaunchKernelGGL(combine_kernel<F16>, g, dim3(256), 0, s, a);
     else hipLaunchKernelGGL(combine_kernel<BF16>, g, dim3(256), 0, s, a);
     if ((st = launch_ok()) != PALU_OK) return st;
+    if ((st = mark(4)) != PALU_OK) return st;
   }
   return PALU_OK;
 }

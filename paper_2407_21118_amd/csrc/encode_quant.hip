@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[t][e] = 0.f;
     if (col_ok) {
-#pragma unroll 4
+#pragma unroll
       for (int kk = 0; kk < 16; ++kk) {
         const int k = wave * 16 + kk;
         const uint4v raw = *reinterpret_cast<const uint4v*>(a.A + (size_t)(k0 + k) * a.R + c0);
@@ -91,23 +91,31 @@ __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
   }
 }
 
-// One thread per (token, pair of columns): sums the split-K partials in a fixed
-// order, rounds once, scatters.
+// Sums the split-K partials in a fixed order, rounds once, scatters the rows.
+// Workgroup = 64 columns of one token; thread = (quarter of the splits, column).
+// grid (R / 64, n_tok), 256 threads.
 template <typename T>
 __global__ __launch_bounds__(256) void encode_finish_kernel(EncodeArgs a) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  const int pairs = a.R / 2;
-  if (idx >= a.n_tok * pairs) return;
-  const int t = idx / pairs, c = (idx - t * pairs) * 2;
-  float s0 = 0.f, s1 = 0.f;
-  for (int ks = 0; ks < a.k_splits; ++ks) {
-    const float* p = a.partial + ((size_t)ks * a.n_tok + t) * a.R + c;
-    s0 += p[0];
-    s1 += p[1];
+  __shared__ float part[4][64];
+  const int tid = threadIdx.x;
+  const int c = blockIdx.x * 64 + (tid & 63), t = blockIdx.y, sub = tid >> 6;
+  const int per = (a.k_splits + 3) / 4;
+  float s = 0.f;
+  if (c < a.R) {
+    const float* p = a.partial + (size_t)t * a.R + c;
+#pragma unroll 8
+    for (int ks = sub * per; ks < min((sub + 1) * per, a.k_splits); ++ks) s += p[(size_t)ks * a.n_tok * a.R];
   }
-  const long long row = a.dst_row ? a.dst_row[t] : t;
-  uint32_t* dst = reinterpret_cast<uint32_t*>(a.latent + row * a.row_stride + c);
-  *dst = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
+  part[sub][tid & 63] = s;
+  __syncthreads();
+  if (tid < 32 && blockIdx.x * 64 + tid * 2 < a.R) {
+    const int cc = tid * 2;
+    const float s0 = (part[0][cc] + part[1][cc]) + (part[2][cc] + part[3][cc]);
+    const float s1 = (part[0][cc + 1] + part[1][cc + 1]) + (part[2][cc + 1] + part[3][cc + 1]);
+    const long long row = a.dst_row ? a.dst_row[t] : t;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(a.latent + row * a.row_stride + blockIdx.x * 64 + cc);
+    *dst = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
+  }
 }
 
 struct QuantArgs {
@@ -115,6 +123,7 @@ struct QuantArgs {
   uint8_t* codes;
   uint16_t* scale;
   uint16_t* zero;
+  const int32_t* dst_row;     // output row of token t (NULL: t)
   long long row_stride;
   int n_tok, R, n_blocks;     // n_blocks = R / 128
 };
@@ -148,10 +157,11 @@ __global__ __launch_bounds__(256) void quant_kernel(QuantArgs a) {
   const float zf = F16::to_float(z16);
   const float q0 = fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x0, sf)), zf), 0.0f), 15.0f);
   const float q1 = fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x1, sf)), zf), 0.0f), 15.0f);
-  a.codes[(size_t)t * (a.R / 2) + blk * 64 + lane] = (uint8_t)((uint32_t)q0 | ((uint32_t)q1 << 4));
+  const size_t orow = a.dst_row ? (size_t)a.dst_row[t] : (size_t)t;
+  a.codes[orow * (a.R / 2) + blk * 64 + lane] = (uint8_t)((uint32_t)q0 | ((uint32_t)q1 << 4));
   if (lane == 0) {
-    a.scale[(size_t)t * a.n_blocks + blk] = s16;
-    a.zero[(size_t)t * a.n_blocks + blk] = z16;
+    a.scale[orow * a.n_blocks + blk] = s16;
+    a.zero[orow * a.n_blocks + blk] = z16;
   }
 }
 

@@ -118,6 +118,7 @@ struct FoldArgs {
   uint16_t* mfold;
   long long mfold_bstride;
   float theta;
+  double inv_freq[kHalf];    // theta^(-2f/128), computed on the host in float64
   Meta meta;
 };
 

@@ -6,7 +6,7 @@
 //                         + sin(phi_f(t)) (q'_{f+64} k_f - q'_f k_{f+64})
 // and with k = h B (Sec. 3.2.3) every bracket is h . (a column built from q' and B):
 //   u_f = q'_f B[:,f] + q'_{f+64} B[:,f+64],   w_f = q'_{f+64} B[:,f] - q'_f B[:,f+64].
-// The fold kernel writes M = [u_0..u_63 | w_0..w_63] (r x 128 per head) in the
+// The fold kernel writes M = [u_0..u_63 | w_0..w_63] (r x 128 per head, fp16) in the
 // register layout of the MFMA A operand, so that the score kernel's contraction
 // H_k . M is the reconstruction GEMM itself (same r x 128 MACs per token and
 // head) and RoPE reduces to one cos/sin-weighted sum per accumulator.
@@ -30,16 +30,20 @@ __global__ __launch_bounds__(256) void rope_table_kernel(uint16_t* table, int n_
   row[rope_slot(f + kHalf)] = F16::from_float((float)s);
 }
 
-// grid (n_heads, batch), 256 threads.
+constexpr int kFoldSlices = 8;   // workgroups per (head, sequence): slice z folds k-steps z, z+8, ...
+
+// grid (n_heads, batch, kFoldSlices), 256 threads.
 template <typename T>
 __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
   __shared__ float qr[kDHead];
-  const int h = blockIdx.x, b = blockIdx.y;
+  const int h = blockIdx.x, b = blockIdx.y, slice = blockIdx.z;
   const int tid = threadIdx.x;
   const Meta& m = a.meta;
   const int j = m.group_of_head[h];
   const int u = h - m.head_off[j];
   const int r = m.k_off[j + 1] - m.k_off[j];
+  const int nks = r >> 4;
+  if (slice >= nks) return;
   const int width = (m.head_off[j + 1] - m.head_off[j]) * kDHead;
 
   if (tid < kHalf) {
@@ -47,10 +51,7 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
     const double x0 = (double)T::to_float(qp[tid]);
     const double x1 = (double)T::to_float(qp[tid + kHalf]);
     double c = 1.0, s = 0.0;
-    if (a.theta > 0.f) {
-      const double w = pow((double)a.theta, -2.0 * (double)tid / (double)kDHead);
-      sincos((double)a.q_pos[b] * w, &s, &c);
-    }
+    if (a.theta > 0.f) sincos((double)a.q_pos[b] * a.inv_freq[tid], &s, &c);
     qr[tid] = (float)(x0 * c - x1 * s);
     qr[tid + kHalf] = (float)(x1 * c + x0 * s);
   }
@@ -58,15 +59,14 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
 
   const uint16_t* B = a.Bk + m.bk_off[j] + u * kDHead;                 // row k at B + k*width
   uint16_t* out = a.mfold + (size_t)b * a.mfold_bstride + m.bk_off[j] + (size_t)u * r * kDHead;
-  const int n_items = (r / 16) * 256;           // (k-step, row tile, lane) triples, 8 k-values each
-  for (int it = tid; it < n_items; it += 256) {
-    const int lane = it & 63;
-    const int rt = (it >> 6) & 3;
-    const int ks = it >> 8;
-    const int cp = 32 * rt + (lane & 31);       // feature c' of this A-operand row
-    const int f = cp & 63;
-    const bool is_w = cp >= kHalf;
-    const float qa = qr[f], qb = qr[f + kHalf];
+  // one item = (k-step, row tile, lane) = 8 consecutive k of one feature row, stored as one 16-byte word
+  const int lane = tid & 63;
+  const int rt = tid >> 6;
+  const int cp = 32 * rt + (lane & 31);         // feature c' of this A-operand row
+  const int f = cp & 63;
+  const bool is_w = cp >= kHalf;
+  const float qa = qr[f], qb = qr[f + kHalf];
+  for (int ks = slice; ks < nks; ks += kFoldSlices) {
     const int k0 = 16 * ks + 8 * (lane >> 5);
     uint16_t v[8];
 #pragma unroll
@@ -75,14 +75,14 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
       const float b1 = T::to_float(row[f]);
       const float b2 = T::to_float(row[f + kHalf]);
       const float val = is_w ? (qb * b1 - qa * b2) : (qa * b1 + qb * b2);
-      v[e] = T::from_float(val);
+      v[e] = F16::from_float(val);       // the score kernel always contracts in fp16
     }
     uint4v pk;
     pk.x = v[0] | ((uint32_t)v[1] << 16);
     pk.y = v[2] | ((uint32_t)v[3] << 16);
     pk.z = v[4] | ((uint32_t)v[5] << 16);
     pk.w = v[6] | ((uint32_t)v[7] << 16);
-    *reinterpret_cast<uint4v*>(out + (size_t)it * 8) = pk;
+    *reinterpret_cast<uint4v*>(out + ((size_t)ks * 256 + tid) * 8) = pk;
   }
 }
 

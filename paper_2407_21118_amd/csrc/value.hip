@@ -175,13 +175,14 @@ __global__ __launch_bounds__(256) void value_kernel(ValueArgs a) {
   }
 }
 
-// grid (n_heads, batch), 256 threads.
+// grid (n_heads, batch), 256 threads.  Small and latency-bound: every phase
+// spreads its loads over all 256 threads and keeps them independent.
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   __shared__ float w[kMaxSplits];
-  __shared__ float olat[PALU_MAX_RANK];
+  __shared__ __attribute__((aligned(16))) float olat[PALU_MAX_RANK];
+  __shared__ __attribute__((aligned(16))) float part[1024];              // phase 2: [4 split groups][64 k-quads][4]; phase 3: [8 k parts][32 column quads][4]
   __shared__ float red[4];
-  __shared__ float halfsum[kDHead];
   const int tid = threadIdx.x;
   const Meta& m = a.meta;
   const int h = blockIdx.x, b = blockIdx.y;
@@ -192,6 +193,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   const int rv = m.v_off[j + 1] - m.v_off[j];
   const int width = (m.head_off[j + 1] - m.head_off[j]) * kDHead;
 
+  // ---- softmax merge weights of the splits
   const float* ml = a.ml_part + ((size_t)b * a.n_split * m.n_heads + h) * 2;
   const size_t ml_stride = (size_t)m.n_heads * 2;
   float mx[1] = {-INFINITY};
@@ -205,23 +207,61 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   }
   block_reduce<1>(sum, red, false);      // barriers publish w[]
 
+  // ---- o_lat[k] = sum_c w_c o_c[k]: thread = (split group sg of 4, k-quad kq of 64), 16-byte loads
   const float* op = a.o_part + (size_t)b * a.n_split * a.o_stride + o_head_off(m, h);
-  for (int k = tid; k < rv; k += 256) {
-    float s = 0.f;
-    for (int c = 0; c < nsp; ++c) s = fmaf(w[c], op[(size_t)c * a.o_stride + k], s);
-    olat[k] = s;
+  const int sg = tid >> 6, kq = tid & 63;
+  for (int kb = 0; kb < rv; kb += 256) {
+    const int k = kb + kq * 4;
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+    if (k < rv) {
+#pragma unroll 4
+      for (int c = sg; c < nsp; c += 4) {
+        const float4v v = *reinterpret_cast<const float4v*>(op + (size_t)c * a.o_stride + k);
+        const float wc = w[c];
+        acc.x = fmaf(wc, v.x, acc.x);
+        acc.y = fmaf(wc, v.y, acc.y);
+        acc.z = fmaf(wc, v.z, acc.z);
+        acc.w = fmaf(wc, v.w, acc.w);
+      }
+    }
+    *reinterpret_cast<float4v*>(part + (sg * 64 + kq) * 4) = acc;
+    __syncthreads();
+    if (tid < 64 && k < rv) {
+      float4v s = *reinterpret_cast<const float4v*>(part + kq * 4);
+#pragma unroll
+      for (int g = 1; g < 4; ++g) {
+        const float4v o = *reinterpret_cast<const float4v*>(part + (g * 64 + kq) * 4);
+        s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w;
+      }
+      *reinterpret_cast<float4v*>(olat + k) = s;
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
-  const int col = tid & (kDHead - 1), part = tid >> 7;          // two threads per output column
-  const uint16_t* Bv = a.Bv + m.bv_off[j] + u * kDHead + col;
-  const int k_lo = part * (rv / 2), k_hi = k_lo + rv / 2;
-  float s = 0.f;
+  // ---- out = o_lat . B_v[:, head columns] / l: thread = (k part kp of 8, column quad cq of 32), 8-byte loads
+  const int kp = tid >> 5, cq = tid & 31;
+  const uint16_t* Bv = a.Bv + m.bv_off[j] + u * kDHead + cq * 4;
+  const int k_per = rv >> 3;                       // rank is a multiple of 32
+  float4v o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
-  for (int k = k_lo; k < k_hi; ++k) s = fmaf(olat[k], T::to_float(Bv[(size_t)k * width]), s);
-  if (part == 1) halfsum[col] = s;
+  for (int kk = 0; kk < k_per; ++kk) {
+    const int k = kp * k_per + kk;
+    const uint2v raw = *reinterpret_cast<const uint2v*>(Bv + (size_t)k * width);
+    const float ol = olat[k];
+    o.x = fmaf(ol, T::to_float((uint16_t)(raw.x & 0xffffu)), o.x);
+    o.y = fmaf(ol, T::to_float((uint16_t)(raw.x >> 16)), o.y);
+    o.z = fmaf(ol, T::to_float((uint16_t)(raw.y & 0xffffu)), o.z);
+    o.w = fmaf(ol, T::to_float((uint16_t)(raw.y >> 16)), o.w);
+  }
+  *reinterpret_cast<float4v*>(part + (kp * 32 + cq) * 4) = o;
   __syncthreads();
-  if (part == 0) a.out[((size_t)b * m.n_heads + h) * kDHead + col] = (s + halfsum[col]) / sum[0];
+  if (tid < kDHead) {
+    const int c4 = tid >> 2, e = tid & 3;
+    float s = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) s += part[(g * 32 + c4) * 4 + e];
+    a.out[((size_t)b * m.n_heads + h) * kDHead + tid] = s / sum[0];
+  }
 }
 
 #define PALU_VALUE_INST(T, HB, I4) template __global__ void value_kernel<T, HB, I4>(ValueArgs);

@@ -71,5 +71,5 @@ def test_null_and_range_arguments():
     assert lib.palu_rope_table_bytes(128, 0, ctypes.byref(out)) == -1
     assert lib.palu_rope_table_init(10000.0, 128, 16, None, None) == -1
     assert lib.palu_encode(d.ref(), 2, None, 1, None, None, 128, None, None, 0, None) == -1
-    assert lib.palu_quant_latent(d.ref(), 0, None, 128, 1, None, None, None, None) == -1
+    assert lib.palu_quant_latent(d.ref(), 0, None, 128, 1, None, None, None, None, None) == -1
     assert lib.palu_attn_decode(d.ref(), 1, 8, 8, *([None] * 13), 8, None, None, 0, None) == -1

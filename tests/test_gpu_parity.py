@@ -92,9 +92,12 @@ def test_no_rope():
 
 
 def test_peaked_softmax_and_large_logits():
-    """Scaled-up queries give logits of order +-40: the running-max softmax must not overflow."""
+    """Queries scaled by 12 give logits of order +-40: the max-subtracted softmax
+    must not overflow.  The folded weights and the cos/sin table are fp16, so a
+    logit carries an absolute error proportional to its own scale (about 3e-4
+    of the logit spread); the output tolerance is scaled by the same factor."""
     layer = synth.uniform_layer(8, 4, 128)
     case = synth.make_case_orthonormal(layer, 1, 600, seed=6)
     case.q = synth.round_to(case.q * 12.0, "f16")
     case.name = "peaked"
-    check(case, TOL_FP)
+    check(case, TOL_FP * 12.0)
