@@ -65,6 +65,7 @@ def main() -> int:
     ap.add_argument("--config", default="2", help="workload: 1, 2 (7B shape, seq 16K, headline), 2-4k, 2-64k, 3, 4, 4v, 5a, 5b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ring-gib", type=float, default=1.0, help="distinct latent bytes to cycle through")
+    ap.add_argument("--opt", action="append", default=[], help="tuning knob name=value (palu_set_option)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -81,6 +82,9 @@ def main() -> int:
         return 2
     P.load_library()
     torch.cuda.set_device(0)
+    for kv in args.opt:
+        k, v = kv.split("=")
+        P.palu_set_option(k, int(v))
 
     cfg = args.config
     v_only = cfg == "4v"

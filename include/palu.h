@@ -82,6 +82,18 @@ const char* palu_status_string(int status);
 int palu_version(void);
 
 /*
+ * Process-wide tuning knobs for experiments; every default (0) lets the library
+ * choose.  Not thread-safe against concurrent decode calls.
+ *   "score_waves"         4 or 8 wavefronts per score workgroup for ranks <= 256
+ *   "score_chunks"        sequence chunks per (sequence, head block) in the score kernel
+ *   "value_split_tokens"  tokens per sequence split in the value kernel (multiple of 32, <= 1024)
+ * Unknown names and out-of-range values return PALU_ERR_INVALID_ARG.  The workspace
+ * size query assumes the defaults; a smaller value_split_tokens may need more
+ * workspace, in which case palu_attn_decode reports the shortfall.
+ */
+int palu_set_option(const char* name, int value);
+
+/*
  * RoPE angle table (Sec. 3.1.2: RoPE acts on queries and keys before their
  * product).  For position p and pair f < d_h/2 the table stores, as float16,
  * cos(p w_f) and sin(p w_f) with w_f = theta^(-2f/d_h), computed in float64;

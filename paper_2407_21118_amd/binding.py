@@ -42,7 +42,9 @@ class _Desc(ctypes.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, _LIB_NAME)
+    """Path of the shared library: the in-tree build, or the file named by the
+    PALU_LIB environment variable (to try another build of the same ABI)."""
+    return os.environ.get("PALU_LIB") or os.path.join(_HERE, _LIB_NAME)
 
 
 def load_library():
@@ -63,6 +65,8 @@ def load_library():
     lib.palu_status_string.argtypes = [ctypes.c_int]
     lib.palu_version.restype = ctypes.c_int
     lib.palu_version.argtypes = []
+    lib.palu_set_option.restype = ctypes.c_int
+    lib.palu_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
     lib.palu_rope_table_bytes.argtypes = [i32, i32, szp]
     lib.palu_rope_table_init.argtypes = [ctypes.c_float, i32, i32, vp, vp]
     lib.palu_encode_workspace_bytes.argtypes = [dp, ctypes.c_int, i32, szp]
@@ -145,6 +149,10 @@ def palu_status_string(status: int) -> str:
 
 def palu_version() -> int:
     return int(load_library().palu_version())
+
+
+def palu_set_option(name: str, value: int) -> None:
+    _check(load_library().palu_set_option(name.encode(), int(value)), "palu_set_option")
 
 
 def palu_rope_table_bytes(d_head: int, n_pos: int) -> int:

@@ -18,6 +18,11 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// Tuning knobs (palu_set_option); 0 = automatic.
+std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score workgroup (ranks <= 256)
+std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
+std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
+
 int device_cu_count() {
   static std::atomic<int> cached[64];
   int dev = 0;
@@ -100,10 +105,14 @@ constexpr int kScoreMaxWidth = 512;               // latent columns one workgrou
 int rank_class(int r) { return (r >= 32 && r <= 512 && r % 32 == 0) ? r / 32 - 1 : -1; }
 bool rank_class_half(int rc) { return rc >= 8; }
 
+struct ScoreClass {
+  int id;                              // rank class * 3 + log2(groups per workgroup)
+  int n_units;
+  ScoreUnit u[PALU_MAX_HEADS];         // split into launches of kMaxScoreUnits
+};
 struct ScorePlan {
-  int n_cls;                          // classes in use
-  int cls_id[kNumScoreCls];           // rank class * 3 + log2(G) of each class in use
-  Units units[kNumScoreCls];          // indexed like cls_id
+  int n_cls;                           // classes in use
+  ScoreClass cls[kNumScoreCls];
   int total_units;
   bool two_parts[PALU_MAX_HEADS];
 };
@@ -118,6 +127,7 @@ int plan_score(const Meta& m, ScorePlan* p) {
   while (h < m.n_heads) {
     const int j0 = m.group_of_head[h];
     const int r = m.k_off[j0 + 1] - m.k_off[j0];
+    const int s = m.head_off[j0 + 1] - m.head_off[j0];
     const int rc = rank_class(r);
     if (rc < 0) return PALU_ERR_UNSUPPORTED;
     int nh, lg = 0;
@@ -125,9 +135,8 @@ int plan_score(const Meta& m, ScorePlan* p) {
       nh = std::min(2, m.head_off[j0 + 1] - h);
     } else {
       nh = std::min(4, m.head_off[j0 + 1] - h);
-      if (h == m.head_off[j0] && nh < 4) {
+      if (h == m.head_off[j0] && s <= 2) {
         // a small group: widen the unit over 2 or 4 whole adjacent groups of the same rank and size
-        const int s = m.head_off[j0 + 1] - m.head_off[j0];
         for (int g : {4, 2}) {
           if (g * s > 4 || g * r > kScoreMaxWidth || j0 + g > m.n_groups) continue;
           bool same = true;
@@ -141,15 +150,18 @@ int plan_score(const Meta& m, ScorePlan* p) {
     const int id = rc * 3 + lg;
     if (slot_of[id] < 0) {
       slot_of[id] = p->n_cls;
-      p->cls_id[p->n_cls] = id;
-      p->units[p->n_cls].n_units = 0;
+      p->cls[p->n_cls].id = id;
+      p->cls[p->n_cls].n_units = 0;
       ++p->n_cls;
     }
-    Units& u = p->units[slot_of[id]];
-    if (u.n_units >= kMaxUnits) return PALU_ERR_UNSUPPORTED;
-    u.h0[u.n_units] = (uint16_t)h;
-    u.nh[u.n_units] = (uint8_t)nh;
-    ++u.n_units;
+    ScoreClass& c = p->cls[slot_of[id]];
+    ScoreUnit& u = c.u[c.n_units++];
+    u.h0 = h;
+    u.nh = nh;
+    u.s = s;
+    u.head_off0 = m.head_off[j0];
+    u.k_off0 = m.k_off[j0];
+    u.bk_off0 = m.bk_off[j0];
     ++p->total_units;
     if (rank_class_half(rc))
       for (int x = 0; x < nh; ++x) p->two_parts[h + x] = true;
@@ -199,7 +211,7 @@ int split_bound(int total_units, int batch, int max_seq) {
 }
 
 struct Workspace {
-  size_t mfold, scores, o_part, ml_part, total;
+  size_t mfold, scores, o_part, ml_part, rope_rows, total;
   int lpad, o_stride;
   long long mfold_bstride, part_stride;
 };
@@ -214,6 +226,7 @@ int carve(const Meta& m, int batch, int max_seq, int n_split_cap, Workspace* w) 
   w->scores = off;  off = align_up(off + (size_t)2 * w->part_stride * 4);
   w->o_part = off;  off = align_up(off + (size_t)batch * n_split_cap * w->o_stride * 4);
   w->ml_part = off; off = align_up(off + (size_t)batch * n_split_cap * m.n_heads * 2 * 4);
+  w->rope_rows = off; off = align_up(off + (size_t)w->lpad * PALU_D_HEAD * 2);   // cos/sin rows gathered by k_pos
   w->total = off;
   return PALU_OK;
 }
@@ -226,41 +239,47 @@ int allow_lds(K kernel, size_t bytes) {
 }
 
 using ScoreFn = void (*)(ScoreArgs);
+// waves8: four heads as 8 half-head wavefronts (two per SIMD) instead of 4 whole-head ones.
 template <typename T, bool I4, int NKS>
-ScoreFn score_fn_g(int lg) {
+ScoreFn score_fn_g(int lg, bool waves8) {
   if constexpr (NKS > 16) {
-    return score_kernel<T, NKS, 2, 1, I4>;
+    return score_kernel<T, NKS, 2, 1, 4, I4>;
   } else {
-    if constexpr (NKS <= 8) { if (lg == 2) return score_kernel<T, NKS, 4, 4, I4>; }
-    if (lg == 1) return score_kernel<T, NKS, 4, 2, I4>;
-    return score_kernel<T, NKS, 4, 1, I4>;
+    if (waves8) {
+      if constexpr (NKS <= 8) { if (lg == 2) return score_kernel<T, NKS, 2, 4, 8, I4>; }
+      if (lg == 1) return score_kernel<T, NKS, 2, 2, 8, I4>;
+      return score_kernel<T, NKS, 2, 1, 8, I4>;
+    }
+    if constexpr (NKS <= 8) { if (lg == 2) return score_kernel<T, NKS, 4, 4, 4, I4>; }
+    if (lg == 1) return score_kernel<T, NKS, 4, 2, 4, I4>;
+    return score_kernel<T, NKS, 4, 1, 4, I4>;
   }
 }
 template <typename T, bool I4>
-ScoreFn score_fn_t(int rc, int lg) {
+ScoreFn score_fn_t(int rc, int lg, bool w8) {
   switch (rc) {
-    case 0: return score_fn_g<T, I4, 2>(lg);
-    case 1: return score_fn_g<T, I4, 4>(lg);
-    case 2: return score_fn_g<T, I4, 6>(lg);
-    case 3: return score_fn_g<T, I4, 8>(lg);
-    case 4: return score_fn_g<T, I4, 10>(lg);
-    case 5: return score_fn_g<T, I4, 12>(lg);
-    case 6: return score_fn_g<T, I4, 14>(lg);
-    case 7: return score_fn_g<T, I4, 16>(lg);
-    case 8: return score_fn_g<T, I4, 18>(lg);
-    case 9: return score_fn_g<T, I4, 20>(lg);
-    case 10: return score_fn_g<T, I4, 22>(lg);
-    case 11: return score_fn_g<T, I4, 24>(lg);
-    case 12: return score_fn_g<T, I4, 26>(lg);
-    case 13: return score_fn_g<T, I4, 28>(lg);
-    case 14: return score_fn_g<T, I4, 30>(lg);
-    default: return score_fn_g<T, I4, 32>(lg);
+    case 0: return score_fn_g<T, I4, 2>(lg, w8);
+    case 1: return score_fn_g<T, I4, 4>(lg, w8);
+    case 2: return score_fn_g<T, I4, 6>(lg, w8);
+    case 3: return score_fn_g<T, I4, 8>(lg, w8);
+    case 4: return score_fn_g<T, I4, 10>(lg, w8);
+    case 5: return score_fn_g<T, I4, 12>(lg, w8);
+    case 6: return score_fn_g<T, I4, 14>(lg, w8);
+    case 7: return score_fn_g<T, I4, 16>(lg, w8);
+    case 8: return score_fn_g<T, I4, 18>(lg, w8);
+    case 9: return score_fn_g<T, I4, 20>(lg, w8);
+    case 10: return score_fn_g<T, I4, 22>(lg, w8);
+    case 11: return score_fn_g<T, I4, 24>(lg, w8);
+    case 12: return score_fn_g<T, I4, 26>(lg, w8);
+    case 13: return score_fn_g<T, I4, 28>(lg, w8);
+    case 14: return score_fn_g<T, I4, 30>(lg, w8);
+    default: return score_fn_g<T, I4, 32>(lg, w8);
   }
 }
-ScoreFn score_fn(int act, bool i4, int cls_id) {
+ScoreFn score_fn(int act, bool i4, int cls_id, bool w8) {
   const int rc = cls_id / 3, lg = cls_id % 3;
-  if (i4) return score_fn_t<F16, true>(rc, lg);
-  return act == PALU_F16 ? score_fn_t<F16, false>(rc, lg) : score_fn_t<BF16, false>(rc, lg);
+  if (i4) return score_fn_t<F16, true>(rc, lg, w8);
+  return act == PALU_F16 ? score_fn_t<F16, false>(rc, lg, w8) : score_fn_t<BF16, false>(rc, lg, w8);
 }
 
 using ValueFn = void (*)(ValueArgs);
@@ -304,6 +323,22 @@ const char* palu_status_string(int status) {
 }
 
 int palu_version(void) { return 100; }
+
+int palu_set_option(const char* name, int value) {
+  if (!name || value < 0) return PALU_ERR_INVALID_ARG;
+  if (!std::strcmp(name, "score_waves")) {
+    if (value != 0 && value != 4 && value != 8) return PALU_ERR_INVALID_ARG;
+    g_opt_score_waves = value;
+  } else if (!std::strcmp(name, "score_chunks")) {
+    g_opt_score_chunks = value;
+  } else if (!std::strcmp(name, "value_split_tokens")) {
+    if (value != 0 && (value % 32 != 0 || value > kSplitMax)) return PALU_ERR_INVALID_ARG;
+    g_opt_value_split = value;
+  } else {
+    return PALU_ERR_INVALID_ARG;
+  }
+  return PALU_OK;
+}
 
 int palu_rope_table_bytes(int32_t d_head, int32_t n_pos, size_t* out_bytes) {
   if (!out_bytes || n_pos <= 0 || d_head <= 0) return PALU_ERR_INVALID_ARG;
@@ -465,6 +500,10 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
   if ((st = plan_value(m, &vp)) != PALU_OK) return st;
   int split_tokens, n_split;
   split_geometry(vp.total_units, batch, seq_len, &split_tokens, &n_split);
+  if (g_opt_value_split > 0) {
+    split_tokens = g_opt_value_split;
+    n_split = ceil_div(seq_len, split_tokens);
+  }
   if (n_split > kMaxSplits) return PALU_ERR_UNSUPPORTED;
   const int n_split_cap = split_bound(vp.total_units, batch, max_seq);
   Workspace w;
@@ -475,6 +514,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   const int act = desc->act_dtype;
+  const bool waves8 = g_opt_score_waves != 4;
   auto mark = [&](int i) -> int {
     if (!stage_events) return PALU_OK;
     return hipEventRecord(static_cast<hipEvent_t>(stage_events[i]), s) == hipSuccess ? PALU_OK : PALU_ERR_HIP;
@@ -509,8 +549,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.hk_scale = static_cast<const uint16_t*>(hk_scale);
     a.hk_zero = static_cast<const uint16_t*>(hk_zero);
     a.mfold = reinterpret_cast<const uint16_t*>(ws + w.mfold);
-    a.rope = static_cast<const uint16_t*>(rope_table);
-    a.k_pos = k_pos;
+    a.rope_rows = static_cast<const uint16_t*>(rope_table);
     a.seq_lens = seq_lens;
     a.scores = reinterpret_cast<float*>(ws + w.scores);
     a.mfold_bstride = w.mfold_bstride;
@@ -519,26 +558,47 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.seq_len = seq_len;
     a.lpad = w.lpad;
     a.batch = batch;
-    a.rope_len = rope_table_len;
+    a.n_heads = m.n_heads;
     a.quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
     a.n_blocks_q = Rk / a.quant_block;
     a.scale = 1.4426950408889634f / std::sqrt((float)PALU_D_HEAD);
-    a.meta = m;
+    if ((st = mark(1)) != PALU_OK) return st;
+    if (k_pos) {
+      // cos/sin rows in cached-token order, so that the score kernel needs no position loads
+      RopeGatherArgs g;
+      g.table = static_cast<const uint16_t*>(rope_table);
+      g.k_pos = k_pos;
+      g.rows = reinterpret_cast<uint16_t*>(ws + w.rope_rows);
+      g.n = seq_len;
+      g.table_len = rope_table_len;
+      hipLaunchKernelGGL(rope_gather_kernel, dim3((unsigned)ceil_div(seq_len * 16, 256)), dim3(256), 0, s, g);
+      if ((st = launch_ok()) != PALU_OK) return st;
+      a.rope_rows = g.rows;
+    }
     const int tiles = ceil_div(seq_len, kTile);
     int n_chunks = std::max(1, std::min(tiles, (int)std::lround((double)device_cu_count() / (sp.total_units * batch))));
+    if (g_opt_score_chunks > 0) n_chunks = std::min(tiles, (int)g_opt_score_chunks);
+    // the kernel addresses a chunk of the cache with 32-bit byte offsets
+    const long long chunk_limit_tiles = std::max(1LL, (1LL << 31) / ((long long)Rk * 2 * kTile));
+    n_chunks = std::max(n_chunks, (int)ceil_div(tiles, (int)std::min<long long>(chunk_limit_tiles, tiles)));
     const int chunk_tiles = ceil_div(tiles, n_chunks);
     a.chunk_tokens = chunk_tiles * kTile;
     a.n_chunks = ceil_div(tiles, chunk_tiles);
-    if ((st = mark(1)) != PALU_OK) return st;
     for (int cls = 0; cls < sp.n_cls; ++cls) {
-      a.units = sp.units[cls];
-      const int width = 32 * (sp.cls_id[cls] / 3 + 1) << (sp.cls_id[cls] % 3);
+      const ScoreClass& c = sp.cls[cls];
+      const int rc = c.id / 3, lg = c.id % 3;
+      const int width = (32 * (rc + 1)) << lg;
       const size_t lds = (size_t)2 * kTile * (width * 2 + kRowPad + kRopeRowB);
-      ScoreFn fn = score_fn(act, k_i4, sp.cls_id[cls]);
+      ScoreFn fn = score_fn(act, k_i4, c.id, waves8);
       if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
-      const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
-      hipLaunchKernelGGL(fn, dim3(grid), dim3(256), lds, s, a);
-      if ((st = launch_ok()) != PALU_OK) return st;
+      const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
+      for (int u0 = 0; u0 < c.n_units; u0 += kMaxScoreUnits) {
+        a.units.n_units = std::min(kMaxScoreUnits, c.n_units - u0);
+        std::memcpy(a.units.u, c.u + u0, sizeof(ScoreUnit) * a.units.n_units);
+        const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
+        if ((st = launch_ok()) != PALU_OK) return st;
+      }
     }
   }
 
@@ -565,7 +625,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.n_blocks_q = Rv / a.quant_block;
     std::memset(a.parts_mask_lo, 0, sizeof(a.parts_mask_lo));
     for (int h = 0; h < m.n_heads; ++h)
-      if (sp.two_parts[h]) a.parts_mask_lo[h >> 5] |= 1u << (h & 31);
+      if (sp.two_parts[h] || waves8) a.parts_mask_lo[h >> 5] |= 1u << (h & 31);   // half-head wavefronts: two partial scores
     a.meta = m;
     if ((st = mark(2)) != PALU_OK) return st;
     for (int cls = 0; cls < kNumValCls; ++cls) {

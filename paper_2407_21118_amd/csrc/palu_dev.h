@@ -86,13 +86,28 @@ __host__ __device__ __forceinline__ int rope_slot(int cprime) {
   return hi * 64 + rt * 16 + i;
 }
 
+// A work unit of the score kernel: `nh` consecutive heads starting at h0, taken
+// from one group or from 2 / 4 adjacent groups of equal rank and `s` heads each.
+// Everything a wavefront needs about its head follows from these six numbers.
+struct ScoreUnit {
+  int h0, nh;
+  int s;                     // heads per group inside the unit
+  int head_off0;             // first head of the unit's first group
+  int k_off0;                // first latent column of the unit's first group
+  int bk_off0;               // element offset of that group's B_k (and folded weights)
+};
+constexpr int kMaxScoreUnits = 64;      // per launch
+struct ScoreUnits {
+  int n_units;
+  ScoreUnit u[kMaxScoreUnits];
+};
+
 struct ScoreArgs {
   const void* hk;            // latents or packed codes
   const uint16_t* hk_scale;  // fp16 bits (int4 only)
   const uint16_t* hk_zero;
   const uint16_t* mfold;     // folded query-weights, per batch stride mfold_bstride elements
-  const uint16_t* rope;      // table
-  const int32_t* k_pos;
+  const uint16_t* rope_rows; // cos/sin row of cached token t at rope_rows + t*128 (the table itself, or rows gathered by k_pos)
   const int32_t* seq_lens;
   float* scores;             // [parts][batch][n_heads][lpad]
   long long mfold_bstride;
@@ -103,12 +118,19 @@ struct ScoreArgs {
   int batch;
   int chunk_tokens;          // tokens per workgroup (multiple of kTile)
   int n_chunks;
-  int rope_len;
+  int n_heads;
   int n_blocks_q;            // R_k / quant_block (int4 only)
   int quant_block;
   float scale;               // log2(e) / sqrt(d_h)
-  Meta meta;
-  Units units;
+  ScoreUnits units;
+};
+
+struct RopeGatherArgs {
+  const uint16_t* table;
+  const int32_t* k_pos;
+  uint16_t* rows;            // [n] rows of 128 fp16
+  int n;
+  int table_len;
 };
 
 struct FoldArgs {

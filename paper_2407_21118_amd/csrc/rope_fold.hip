@@ -30,6 +30,17 @@ __global__ __launch_bounds__(256) void rope_table_kernel(uint16_t* table, int n_
   row[rope_slot(f + kHalf)] = F16::from_float((float)s);
 }
 
+// rows[t] = table[clamp(k_pos[t])]: lets the score kernel address cos/sin rows by
+// cached-token index without a dependent position load in its inner loop.
+// One thread per 16-byte piece of a row.
+__global__ __launch_bounds__(256) void rope_gather_kernel(RopeGatherArgs a) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int t = idx >> 4, c = idx & 15;
+  if (t >= a.n) return;
+  const int pos = max(0, min(a.k_pos[t], a.table_len - 1));
+  reinterpret_cast<uint4v*>(a.rows)[(size_t)t * 16 + c] = reinterpret_cast<const uint4v*>(a.table)[(size_t)pos * 16 + c];
+}
+
 constexpr int kFoldSlices = 8;   // workgroups per (head, sequence): slice z folds k-steps z, z+8, ...
 
 // grid (n_heads, batch, kFoldSlices), 256 threads.

@@ -6,23 +6,26 @@
 // only as MFMA accumulators.
 //
 // Design for gfx950 (not the paper's one-thread-block-per-tile Triton layout):
-//   * weight-stationary: each wavefront keeps its head's whole M_i (r x 128
-//     fp16, up to 256 registers) resident for the lifetime of the workgroup, so
-//     the only operand that moves per token tile is the latent tile;
-//   * a workgroup = 4 wavefronts = up to 4 heads that read the same (or
-//     adjacent) latent columns; it walks a chunk of the sequence in tiles of
-//     32 tokens; each tile (and its 32 cos/sin rows) is fetched once with
-//     coalesced 16-byte loads issued two tiles ahead, parked in registers, and
-//     published through a double-buffered LDS tile;
-//   * accumulators are computed transposed (features x tokens) so that the
-//     sum over the 128 features of a token is an in-lane sum plus one
-//     cross-half exchange.
+//   * weight-stationary: each wavefront keeps its slice of M_i (r x 128 fp16 per
+//     head) in registers for the lifetime of the workgroup, so the only operand
+//     that moves per token tile is the latent tile;
+//   * a workgroup covers up to 4 heads that read the same (or adjacent) latent
+//     columns and walks a chunk of the sequence in tiles of 32 tokens; each tile
+//     (and its 32 cos/sin rows) is fetched once with coalesced 16-byte loads
+//     issued two tiles ahead, parked in registers, and published through a
+//     double-buffered LDS tile;
+//   * accumulators are computed transposed (features x tokens) so that the sum
+//     over the features of a token is an in-lane sum plus one cross-half exchange;
+//   * with 8 wavefronts (two per SIMD) the two wavefronts of a SIMD run half a
+//     tile out of phase ("ping-pong"): while one issues its MFMAs the other does
+//     its RoPE epilogue, LDS stores and global loads, so the matrix pipe never
+//     waits for them.
 
 #include "palu_dev.h"
 
 namespace palu {
 
-constexpr int kRowPad = 16;                    // bytes of padding per LDS row: keeps 16-byte column reads conflict-free
+constexpr int kRowPad = 16;                      // bytes of padding per LDS row: keeps 16-byte column reads conflict-free
 constexpr int kRopeRowB = kDHead * 2 + kRowPad;  // LDS pitch of one cos/sin row
 
 // T:    storage type of unquantized latents.  The contraction itself always
@@ -33,112 +36,111 @@ constexpr int kRopeRowB = kDHead * 2 + kRowPad;  // LDS pitch of one cos/sin row
 //       than the whole error budget.
 // NKS:  k-steps of 16: the rank of every head in the workgroup is exactly 16*NKS
 // RT:   32-row feature tiles per wavefront: 4 = a whole head, 2 = half a head
-//       (two wavefronts per head, each writing its own partial score)
+//       (the two halves of a head write separate partial scores)
 // G:    groups spanned by the workgroup's heads (1, 2 or 4 adjacent groups of
 //       equal rank): the staged latent row is G*16*NKS columns wide
+// NW:   wavefronts per workgroup.  4: one per SIMD (RT = 4: four heads, RT = 2:
+//       two heads).  8: two per SIMD, RT = 2, four heads, ping-pong schedule:
+//       wavefronts 0-3 own the cos halves, 4-7 the sin halves.
 // I4:   latents are packed 4-bit codes with per-(token, block) scale and zero
-template <typename T, int NKS, int RT, int G, bool I4>
-__global__ __launch_bounds__(256, 1) void score_kernel(ScoreArgs a) {
+template <typename T, int NKS, int RT, int G, int NW, bool I4>
+__global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  static_assert(NW == 4 || (NW == 8 && RT == 2), "8 wavefronts only as half-head ping-pong");
   constexpr bool kIsBf16 = !__is_same(T, F16);
+  constexpr bool kPingPong = NW == 8;
   constexpr int kRank = NKS * 16;
   constexpr int kWidth = G * kRank;                             // staged columns per token
   static_assert(kWidth <= 512, "latent tile row too wide");
   constexpr int kCpr = kWidth / 8;                              // 16-byte chunks per tile row
   constexpr int kChunks = kTile * kCpr;                         // chunks per tile
-  constexpr int kPass = (kChunks + 255) / 256;                  // staging loads per thread and tile
+  constexpr int kThreads = NW * 64;
+  constexpr int kPass = (kChunks + kThreads - 1) / kThreads;    // staging loads per thread and tile
+  constexpr int kCsPass = (kTile * 16) / kThreads;              // cos/sin chunks per thread and tile (2 or 1)
   constexpr int kRowB = kWidth * 2 + kRowPad;                   // LDS row pitch in bytes
   constexpr int kTileB = kTile * kRowB;                         // latent tile bytes
   constexpr int kBufB = kTileB + kTile * kRopeRowB;             // + its cos/sin rows
 
   const int tid = threadIdx.x;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: everything derived from it is uniform
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // scalar: everything derived from it is uniform
   const int lane = tid & 63;
   const int lane_lo = lane & 31, lane_hi = lane >> 5;
-  const Meta& m = a.meta;
 
+  // chunk index fastest: neighbouring workgroups (spread over the XCDs) work on
+  // different sequence chunks of the same heads
   int wg = blockIdx.x;
-  const int unit = wg % a.units.n_units;
-  wg /= a.units.n_units;
   const int chunk = wg % a.n_chunks;
-  const int b = wg / a.n_chunks;
+  wg /= a.n_chunks;
+  const int unit = wg % a.units.n_units;
+  const int b = wg / a.units.n_units;
+  const ScoreUnit u = a.units.u[unit];
 
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
   const int t_begin = chunk * a.chunk_tokens;
-  if (t_begin >= L) return;                                   // uniform for the workgroup
+  if (t_begin >= L) return;                                     // uniform for the workgroup
   const int t_end = min(t_begin + a.chunk_tokens, L);
   const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
+  const int last_tile = n_tiles - 1;
+  const int rel_last = L - 1 - t_begin;                         // last attendable row, relative to the chunk
 
-  // ---- which head / feature rows this wavefront owns
-  const int h0 = a.units.h0[unit], nh = a.units.nh[unit];
-  int head, rt0;
-  if (RT == 4) { head = h0 + wave; rt0 = 0; }
-  else         { head = h0 + (wave >> 1); rt0 = (wave & 1) * 2; }
-  const bool active = head < h0 + nh;
-  const int hc = active ? head : h0;                           // idle wavefronts mirror head h0 but never store
-  const int j = m.group_of_head[hc];
-  // first column of the latent row staged by the workgroup (the groups of heads h0 .. h0+nh-1)
-  const int c_lo = m.k_off[m.group_of_head[h0]];
-  const int kbase_b = (m.k_off[j] - c_lo) * 2;                 // this head's first column inside the tile row
-
-  // ---- stationary operand: folded weights of (b, head), rows [32*rt0, 32*(rt0+RT))
-  half8 W[NKS][RT];
-  {
-    const uint16_t* mf = a.mfold + (size_t)b * a.mfold_bstride + m.bk_off[j] +
-                         (size_t)(hc - m.head_off[j]) * kRank * kDHead;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-        W[ks][rt] = *reinterpret_cast<const half8*>(mf + ((size_t)(ks * 4 + rt0 + rt) * 64 + lane) * 8);
-  }
-
-  // ---- staging geometry: chunk id = p*256 + tid -> (row, 16-byte column) of the tile
-  // cos/sin rows: 16 chunks of 16 bytes per token, 512 chunks per tile, two per thread
-  const int rope_row = tid >> 3, rope_col = (tid & 7) * 2;
+  // ---- staging geometry: chunk id = p*kThreads + tid -> (row, 16-byte column) of the tile.
+  // Global addresses are a uniform 64-bit base (first row of this workgroup's
+  // sequence chunk) plus a 32-bit per-thread byte offset (the host keeps a chunk
+  // of the cache below 2^31 bytes).
+  const int c_lo = u.k_off0;                                    // first latent column staged by the workgroup
   const size_t seq_base = (size_t)b * a.max_seq;
+  const unsigned row_bytes = I4 ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
+  const unsigned char* hk_base = (const unsigned char*)a.hk +
+                                 (I4 ? ((seq_base + t_begin) * a.row_elems + c_lo) / 2
+                                     : ((seq_base + t_begin) * a.row_elems + c_lo) * 2);
+  const unsigned char* rope_base = (const unsigned char*)(a.rope_rows + (size_t)t_begin * kDHead);
+  int st_row[kPass], st_col[kPass];
+#pragma unroll
+  for (int p = 0; p < kPass; ++p) {
+    const int id = min(p * kThreads + tid, kChunks - 1);        // surplus threads repeat the last chunk
+    st_row[p] = id / kCpr;
+    st_col[p] = id - st_row[p] * kCpr;
+  }
+  // cos/sin rows: 16 chunks of 16 bytes per token, 512 chunks per tile, kCsPass adjacent ones per thread
+  const int rope_row = (tid * kCsPass) >> 4, rope_col = (tid * kCsPass) & 15;
 
   struct Stage {
     uint4v h[kPass];
-    uint4v cs[2];
+    uint4v cs[kCsPass];
   };
   Stage st[2];
 
-  auto issue_loads = [&](Stage& s, int tile) {
-    const int t0 = t_begin + tile * kTile;
+  // Loads are issued unconditionally (tiles past the end of the chunk re-read its
+  // last tile) so that the number of loads in flight at every wait is a constant.
+  auto issue_loads = [&](Stage& s, int tile_unclamped) {
+    const int r0 = min(tile_unclamped, last_tile) * kTile;
     {
-      const int t = min(t0 + rope_row, L - 1);
-      int pos = a.k_pos ? a.k_pos[t] : t;
-      pos = max(0, min(pos, a.rope_len - 1));
-      const uint4v* rp = reinterpret_cast<const uint4v*>(a.rope + (size_t)pos * kDHead) + rope_col;
-      s.cs[0] = rp[0];
-      s.cs[1] = rp[1];
+      const unsigned rel = (unsigned)min(r0 + rope_row, rel_last);
+      const uint4v* rp = reinterpret_cast<const uint4v*>(rope_base + rel * (kDHead * 2u) + rope_col * 16u);
+#pragma unroll
+      for (int x = 0; x < kCsPass; ++x) s.cs[x] = rp[x];
     }
 #pragma unroll
     for (int p = 0; p < kPass; ++p) {
-      const int id = min(p * 256 + tid, kChunks - 1);          // surplus threads repeat the last chunk
-      const int rr = id / kCpr, col = id - rr * kCpr;
-      const int t = min(t0 + rr, L - 1);
+      const unsigned rel = (unsigned)min(r0 + st_row[p], rel_last);
       if (!I4) {
-        const uint16_t* src = (const uint16_t*)a.hk + (seq_base + t) * a.row_elems + c_lo + col * 8;
-        s.h[p] = *reinterpret_cast<const uint4v*>(src);
+        const unsigned off = __umul24(rel, row_bytes) + (unsigned)st_col[p] * 16u;
+        s.h[p] = *reinterpret_cast<const uint4v*>(hk_base + off);
       } else {
-        const int c = c_lo + col * 8;
-        const uint8_t* src = (const uint8_t*)a.hk + ((seq_base + t) * a.row_elems + c) / 2;
-        const size_t sb = (seq_base + t) * a.n_blocks_q + c / a.quant_block;
-        s.h[p].x = *reinterpret_cast<const uint32_t*>(src);
+        const unsigned off = __umul24(rel, row_bytes) + (unsigned)st_col[p] * 4u;
+        const size_t sb = (seq_base + t_begin + rel) * a.n_blocks_q + (c_lo + st_col[p] * 8) / a.quant_block;
+        s.h[p].x = *reinterpret_cast<const uint32_t*>(hk_base + off);
         s.h[p].y = (uint32_t)a.hk_scale[sb] | ((uint32_t)a.hk_zero[sb] << 16);
       }
     }
   };
   auto store_stage = [&](Stage& s, int buf) {
     unsigned char* base = lds + (size_t)buf * kBufB;
-    *reinterpret_cast<uint4v*>(base + kTileB + rope_row * kRopeRowB + rope_col * 16) = s.cs[0];
-    *reinterpret_cast<uint4v*>(base + kTileB + rope_row * kRopeRowB + rope_col * 16 + 16) = s.cs[1];
+#pragma unroll
+    for (int x = 0; x < kCsPass; ++x)
+      *reinterpret_cast<uint4v*>(base + kTileB + rope_row * kRopeRowB + (rope_col + x) * 16) = s.cs[x];
 #pragma unroll
     for (int p = 0; p < kPass; ++p) {
-      const int id = p * 256 + tid;
-      const int rr = id / kCpr, col = id - rr * kCpr;
       uint4v v = s.h[p];
       if (I4) {            // dequantize: (code - zero) * scale in float32, one rounding to fp16
         const uint32_t codes = v.x;
@@ -158,24 +160,63 @@ __global__ __launch_bounds__(256, 1) void score_kernel(ScoreArgs a) {
           v[e] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
         }
       }
-      if (id < kChunks) *reinterpret_cast<uint4v*>(base + rr * kRowB + col * 16) = v;
+      if (p * kThreads + tid < kChunks) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + st_col[p] * 16) = v;
     }
   };
 
-  float* out_row = a.scores + ((size_t)(RT == 2 ? (wave & 1) : 0) * a.batch + b) * m.n_heads * (size_t)a.lpad +
-                   (size_t)hc * a.lpad;
+  // ---- first latent tiles go out before the (larger) weight fetch so that their
+  // HBM latency overlaps it
+  issue_loads(st[0], 0);
 
-  auto compute_tile = [&](int tile) {
-    const int t0 = t_begin + tile * kTile;
+  // ---- which head / feature rows this wavefront owns
+  int wsel, rt0;
+  if (kPingPong)    { wsel = wave & 3; rt0 = (wave >> 2) * 2; }
+  else if (RT == 4) { wsel = wave; rt0 = 0; }
+  else              { wsel = wave >> 1; rt0 = (wave & 1) * 2; }
+  const bool active = wsel < u.nh;
+  const int hsel = active ? wsel : 0;                           // idle wavefronts mirror head h0: same values, same stores
+  const int hc = u.h0 + hsel;
+  // group of the head relative to the unit's first group (groups in a unit have equal rank and size)
+  const int g_rel = G == 1 ? 0 : (u.s == 1 ? (hc - u.head_off0) : ((hc - u.head_off0) >> 1));
+  const int u_in_g = hc - u.head_off0 - g_rel * u.s;
+  const int kbase_b = g_rel * kRank * 2;                        // this head's first column inside the tile row, bytes
+
+  // ---- stationary operand: folded weights of (b, head), rows [32*rt0, 32*(rt0+RT))
+  half8 W[NKS][RT];
+  {
+    const uint16_t* mf = a.mfold + (size_t)b * a.mfold_bstride + u.bk_off0 +
+                         ((size_t)g_rel * u.s + u_in_g) * kRank * kDHead;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+        W[ks][rt] = *reinterpret_cast<const half8*>(mf + ((size_t)(ks * 4 + rt0 + rt) * 64 + lane) * 8);
+  }
+
+  const int part_idx = RT == 2 ? (rt0 >> 1) : 0;
+  float* out_row = a.scores + ((size_t)part_idx * a.batch + b) * a.n_heads * (size_t)a.lpad + (size_t)hc * a.lpad;
+
+  // MFMA phase of one tile: accumulators (features x tokens) and the tile's cos/sin weights
+  struct TileAcc {
+    float16v acc[RT];
+    half8 cs[RT][2];
+  };
+  auto mfma_phase = [&](TileAcc& r, int tile) {
     const unsigned char* base = lds + (size_t)(tile & 1) * kBufB;
     const unsigned char* hrow = base + lane_lo * kRowB + kbase_b + lane_hi * 16;
+    // acc[rt][i] is feature 32*(rt0+rt) + mfma_row(i) of token lane_lo; its cos/sin
+    // weight sits at slot lane_hi*64 + (rt0+rt)*16 + i of the token's table row
     const unsigned char* crow = base + kTileB + lane_lo * kRopeRowB + (lane_hi * 64 + rt0 * 16) * 2;
     // B operand of k-step ks: 8 latent values of token lane_lo; fetched two steps ahead of its MFMAs
     constexpr int kAhead = 2;
     half8 hf[kAhead + 1];
 #pragma unroll
     for (int x = 0; x < kAhead && x < NKS; ++x) hf[x] = *reinterpret_cast<const half8*>(hrow + x * 32);
-    float16v acc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      r.cs[rt][0] = *reinterpret_cast<const half8*>(crow + rt * 32);
+      r.cs[rt][1] = *reinterpret_cast<const half8*>(crow + rt * 32 + 16);
+    }
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       if (ks + kAhead < NKS)
@@ -187,47 +228,99 @@ __global__ __launch_bounds__(256, 1) void score_kernel(ScoreArgs a) {
           float16v zero;
 #pragma unroll
           for (int i = 0; i < 16; ++i) zero[i] = 0.f;
-          acc[rt] = F16::mfma(W[ks][rt], hfrag, zero);
+          r.acc[rt] = F16::mfma(W[ks][rt], hfrag, zero);
         } else {
-          acc[rt] = F16::mfma(W[ks][rt], hfrag, acc[rt]);
+          r.acc[rt] = F16::mfma(W[ks][rt], hfrag, r.acc[rt]);
         }
       }
       __builtin_amdgcn_sched_barrier(0);        // keep the fetch-ahead order: nothing moves across a k-step
     }
-    // RoPE-weighted feature sum: acc[rt][i] is feature 32*(rt0+rt) + mfma_row(i) of token lane_lo;
-    // its cos/sin weight sits at slot lane_hi*64 + (rt0+rt)*16 + i of the token's table row.
-    float part = 0.f;
+  };
+  // RoPE-weighted feature sum of one tile and the score store
+  auto epilogue = [&](const TileAcc& r, int tile) {
+    const int t0 = t_begin + tile * kTile;
+    float part[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const half8 c0 = *reinterpret_cast<const half8*>(crow + rt * 32);
-      const half8 c1 = *reinterpret_cast<const half8*>(crow + rt * 32 + 16);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) part = fmaf(acc[rt][i], (float)c0[i], part);
+      for (int i = 0; i < 8; ++i) part[i & 3] = fmaf(r.acc[rt][i], (float)r.cs[rt][0][i], part[i & 3]);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) part = fmaf(acc[rt][8 + i], (float)c1[i], part);
+      for (int i = 0; i < 8; ++i) part[i & 3] = fmaf(r.acc[rt][8 + i], (float)r.cs[rt][1][i], part[i & 3]);
     }
-    part += __shfl_xor(part, 32, 64);
-    if (active && lane_hi == 0 && t0 + lane_lo < t_end) out_row[t0 + lane_lo] = part * a.scale;
+    float sum = (part[0] + part[1]) + (part[2] + part[3]);
+    sum += __shfl_xor(sum, 32, 64);
+    // Unconditional store (a constant number of memory operations in flight): both
+    // lane halves hold the same sum, idle wavefronts duplicate head h0's values,
+    // and rows past the end of the sequence fall into the padding of the score
+    // buffer (its pitch is a multiple of the tile), which nobody reads.
+    out_row[t0 + lane_lo] = sum * a.scale;
   };
 
-  // ---- pipeline: loads for tile i+2 are in flight while tile i is computed
-  issue_loads(st[0], 0);
-  if (n_tiles > 1) issue_loads(st[1], 1);
+  // ---- start-up: tile 0 into LDS, tiles 1 and 2 in flight.  The explicit wait
+  // (vmcnt = 0) lets the loop start from the same set of pending loads as every
+  // later iteration, which keeps the compiler's wait counts in the loop exact.
   store_stage(st[0], 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  issue_loads(st[1], 1);
+  issue_loads(st[0], 2);
   __syncthreads();
 
-  for (int tile = 0; tile < n_tiles; tile += 2) {
-    // even tile: stage set 0 is free (tile was stored), set 1 holds tile+1
-    if (tile + 2 < n_tiles) issue_loads(st[0], tile + 2);
-    compute_tile(tile);
-    if (tile + 1 < n_tiles) store_stage(st[1], 1);
-    __syncthreads();
-    if (tile + 1 >= n_tiles) break;
-    // odd tile
-    if (tile + 3 < n_tiles) issue_loads(st[1], tile + 3);
-    compute_tile(tile + 1);
-    if (tile + 2 < n_tiles) store_stage(st[0], 0);
-    __syncthreads();
+  if (!kPingPong) {
+    // one wavefront per SIMD: compute tile i, then publish tile i+1 (loaded two tiles ago)
+    TileAcc r;
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+      mfma_phase(r, tile);
+      epilogue(r, tile);
+      store_stage(st[1], 1);
+      issue_loads(st[1], tile + 3);
+      __syncthreads();
+      if (tile + 1 >= n_tiles) break;
+      mfma_phase(r, tile + 1);
+      epilogue(r, tile + 1);
+      store_stage(st[0], 0);
+      issue_loads(st[0], tile + 4);
+      __syncthreads();
+    }
+  } else {
+    // Ping-pong: phases alternate between barriers.  In even phases wavefronts
+    // 0-3 (group A) run the MFMAs of a tile while 4-7 (group B) do everything
+    // else (RoPE epilogue of their previous tile, LDS stores, global loads); in
+    // odd phases the roles swap.  Both groups execute the same loop - an aux
+    // step, a barrier, an MFMA step, a barrier - and group A simply enters it
+    // one MFMA step early, so group B computes tile k-1 where A computes tile k.
+    // At loop position k every thread publishes its share of tile k+1 (loaded
+    // two positions earlier) and queues tile k+3: a tile is complete one barrier
+    // before either group reads it, and a buffer is overwritten only after the
+    // barrier that follows its last read.
+    const int grp = wave >> 2;                       // uniform
+    const int n_iter = n_tiles + grp;
+    TileAcc r;
+    bool have = false;
+    int tile_done = 0;
+    if (grp == 0) {
+      mfma_phase(r, 0);
+      have = true;
+      __syncthreads();
+    }
+    auto position = [&](int k, Stage& s) {
+      if (have) epilogue(r, tile_done);
+      // past the last tile this publishes a duplicate of it into the buffer nobody reads any more
+      store_stage(s, (k + 1) & 1);
+      issue_loads(s, k + 3);
+      __syncthreads();
+      const int t = k + 1 - grp;
+      have = t < n_tiles;
+      if (have) {
+        mfma_phase(r, t);
+        tile_done = t;
+      }
+      if (grp == 0 || k + 1 < n_iter) __syncthreads();   // group B's last position has no partner phase
+    };
+    for (int k = 0; k < n_iter; k += 2) {
+      position(k, st[1]);
+      if (k + 1 >= n_iter) break;
+      position(k + 1, st[0]);
+    }
   }
 }
 
