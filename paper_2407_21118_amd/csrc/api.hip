@@ -588,7 +588,8 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
       const ScoreClass& c = sp.cls[cls];
       const int rc = c.id / 3, lg = c.id % 3;
       const int width = (32 * (rc + 1)) << lg;
-      const size_t lds = (size_t)2 * kTile * (width * 2 + kRowPad + kRopeRowB);
+      const bool dma = act == PALU_F16 && !k_i4;
+      const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width);
       ScoreFn fn = score_fn(act, k_i4, c.id, waves8);
       if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
       const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;

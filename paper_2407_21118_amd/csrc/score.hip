@@ -11,22 +11,44 @@
 //     that moves per token tile is the latent tile;
 //   * a workgroup covers up to 4 heads that read the same (or adjacent) latent
 //     columns and walks a chunk of the sequence in tiles of 32 tokens; each tile
-//     (and its 32 cos/sin rows) is fetched once with coalesced 16-byte loads
-//     issued two tiles ahead, parked in registers, and published through a
-//     double-buffered LDS tile;
+//     (and its 32 cos/sin rows) is fetched once, several tiles ahead of its use.
+//     fp16 latents go from global memory straight into LDS (LDS-direct loads,
+//     no staging registers, waits counted by hand); bf16 and int4 latents are
+//     parked in registers, converted, and stored to LDS;
 //   * accumulators are computed transposed (features x tokens) so that the sum
 //     over the features of a token is an in-lane sum plus one cross-half exchange;
 //   * with 8 wavefronts (two per SIMD) the two wavefronts of a SIMD run half a
 //     tile out of phase ("ping-pong"): while one issues its MFMAs the other does
-//     its RoPE epilogue, LDS stores and global loads, so the matrix pipe never
-//     waits for them.
+//     its RoPE epilogue and queues loads, so the matrix pipe never waits for them.
+
+#include <type_traits>
 
 #include "palu_dev.h"
 
 namespace palu {
 
-constexpr int kRowPad = 16;                      // bytes of padding per LDS row: keeps 16-byte column reads conflict-free
-constexpr int kRopeRowB = kDHead * 2 + kRowPad;  // LDS pitch of one cos/sin row
+// x[lane] + x[lane ^ 32] in every lane, on the VALU (no LDS crossbar round trip).
+__device__ __forceinline__ float sum_across_halves(float x) {
+  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+  // swaps lanes 32..63 of the first register with lanes 0..31 of the second:
+  // afterwards a holds the low half twice, b the high half twice
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+}
+
+// s_waitcnt immediate that waits only for the vector-memory counter (gfx9 layout:
+// vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+
+constexpr int kRowPad = 16;                      // bytes of padding per LDS latent row: 16-byte column reads hit distinct banks
+constexpr int kRopeTileB = kTile * kDHead * 2;   // cos/sin rows of one tile in LDS (unpadded, XOR-swizzled)
+constexpr int kLdsBudget = 160 * 1024 - 1024;    // LDS of one CU, less a little slack
+
+// LDS bytes per buffered tile and number of buffers, shared with the host for the launch
+constexpr int score_buf_bytes(int width) { return kTile * (width * 2 + kRowPad) + kRopeTileB; }
+constexpr int score_num_bufs(int width, bool dma) {
+  return !dma ? 2 : (4 * score_buf_bytes(width) <= kLdsBudget ? 4 : 3);
+}
 
 // T:    storage type of unquantized latents.  The contraction itself always
 //       runs in fp16 with float32 accumulation: bfloat16 latents are converted
@@ -48,6 +70,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   static_assert(NW == 4 || (NW == 8 && RT == 2), "8 wavefronts only as half-head ping-pong");
   constexpr bool kIsBf16 = !__is_same(T, F16);
+  constexpr bool kDma = !I4 && !kIsBf16;                        // fp16 latents: global -> LDS without registers
   constexpr bool kPingPong = NW == 8;
   constexpr int kRank = NKS * 16;
   constexpr int kWidth = G * kRank;                             // staged columns per token
@@ -55,11 +78,21 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   constexpr int kCpr = kWidth / 8;                              // 16-byte chunks per tile row
   constexpr int kChunks = kTile * kCpr;                         // chunks per tile
   constexpr int kThreads = NW * 64;
-  constexpr int kPass = (kChunks + kThreads - 1) / kThreads;    // staging loads per thread and tile
-  constexpr int kCsPass = (kTile * 16) / kThreads;              // cos/sin chunks per thread and tile (2 or 1)
+  constexpr int kPass = (kChunks + kThreads - 1) / kThreads;    // register staging: loads per thread and tile
+  constexpr int kCsPass = (kTile * 16) / kThreads;              // register staging: cos/sin chunks per thread and tile
   constexpr int kRowB = kWidth * 2 + kRowPad;                   // LDS row pitch in bytes
   constexpr int kTileB = kTile * kRowB;                         // latent tile bytes
-  constexpr int kBufB = kTileB + kTile * kRopeRowB;             // + its cos/sin rows
+  constexpr int kBufB = score_buf_bytes(kWidth);                // + its cos/sin rows
+  constexpr int kBufs = score_num_bufs(kWidth, kDma);           // tiles resident in LDS
+  // LDS-direct: loop position k requests tile k + kAhead into the buffer that tile k-1
+  // (whose last reader has passed a barrier) occupied; kBufs-2 requested tiles may
+  // still be in flight when tile k+1 is needed
+  constexpr int kAheadTiles = kBufs - 1;
+  constexpr int kInFlight = kBufs - 2;
+  // LDS-direct loads per wavefront and tile: one per latent row it owns, one per 4 cos/sin rows
+  constexpr int kRowsPerWave = kTile / NW;
+  constexpr int kCsPerWave = kTile / 4 / NW;
+  constexpr int kDmaOps = kRowsPerWave + kCsPerWave;
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // scalar: everything derived from it is uniform
@@ -83,10 +116,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   const int last_tile = n_tiles - 1;
   const int rel_last = L - 1 - t_begin;                         // last attendable row, relative to the chunk
 
-  // ---- staging geometry: chunk id = p*kThreads + tid -> (row, 16-byte column) of the tile.
-  // Global addresses are a uniform 64-bit base (first row of this workgroup's
-  // sequence chunk) plus a 32-bit per-thread byte offset (the host keeps a chunk
-  // of the cache below 2^31 bytes).
+  // ---- addressing: a uniform 64-bit base (first row of this workgroup's sequence
+  // chunk) plus 32-bit byte offsets (the host keeps a chunk of the cache below 2^31 bytes)
   const int c_lo = u.k_off0;                                    // first latent column staged by the workgroup
   const size_t seq_base = (size_t)b * a.max_seq;
   const unsigned row_bytes = I4 ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
@@ -94,6 +125,44 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
                                  (I4 ? ((seq_base + t_begin) * a.row_elems + c_lo) / 2
                                      : ((seq_base + t_begin) * a.row_elems + c_lo) * 2);
   const unsigned char* rope_base = (const unsigned char*)(a.rope_rows + (size_t)t_begin * kDHead);
+  const unsigned lds_base = (unsigned)(size_t)lds;
+
+  // =========================== staging, LDS-direct (fp16) ===========================
+  // Each load instruction moves 16 bytes per active lane to LDS address
+  // M0 + 16*lane.  A latent row (<= 1 KiB) is one instruction with kCpr active
+  // lanes; four cos/sin rows (4 x 256 B, stored without padding but with their
+  // 16-byte pieces XOR-swizzled by the row number) are one instruction.
+  // Loads are issued unconditionally (tiles past the end of the chunk re-read its
+  // last tile) so that the number of loads in flight at every wait is a constant.
+  auto dma_issue = [&](int tile_unclamped) {
+    const int r0 = min(tile_unclamped, last_tile) * kTile;
+    const unsigned buf_base = lds_base + (unsigned)((tile_unclamped % kBufs) * kBufB);
+#pragma unroll
+    for (int x = 0; x < kRowsPerWave; ++x) {
+      const int rr = wave * kRowsPerWave + x;                   // uniform
+      const unsigned rel = (unsigned)min(r0 + rr, rel_last);
+      const unsigned char* src = hk_base + (size_t)rel * row_bytes;          // scalar address
+      const unsigned m0v = buf_base + (unsigned)(rr * kRowB);
+      const unsigned voff = (unsigned)lane * 16u;
+      if (kCpr == 64 || lane < kCpr)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(src) : "memory");
+    }
+#pragma unroll
+    for (int x = 0; x < kCsPerWave; ++x) {
+      const int q = wave * kCsPerWave + x;                      // quad of rows 4q .. 4q+3, uniform
+      const int row = 4 * q + (lane >> 4);
+      const unsigned rel = (unsigned)min(r0 + row, rel_last);
+      const unsigned voff = rel * (kDHead * 2u) + (unsigned)(((lane & 15) ^ (row & 15)) * 16);
+      const unsigned m0v = buf_base + (unsigned)(kTileB + q * 4 * kDHead * 2);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(rope_base) : "memory");
+    }
+  };
+  // wait until at most `tiles_in_flight` tiles' worth of this wavefront's LDS-direct loads are outstanding
+  auto dma_wait = [&](auto tiles_in_flight) {
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(decltype(tiles_in_flight)::value * kDmaOps));
+  };
+
+  // =========================== staging through registers (bf16, int4) ===========================
   int st_row[kPass], st_col[kPass];
 #pragma unroll
   for (int p = 0; p < kPass; ++p) {
@@ -103,15 +172,11 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   }
   // cos/sin rows: 16 chunks of 16 bytes per token, 512 chunks per tile, kCsPass adjacent ones per thread
   const int rope_row = (tid * kCsPass) >> 4, rope_col = (tid * kCsPass) & 15;
-
   struct Stage {
     uint4v h[kPass];
     uint4v cs[kCsPass];
   };
   Stage st[2];
-
-  // Loads are issued unconditionally (tiles past the end of the chunk re-read its
-  // last tile) so that the number of loads in flight at every wait is a constant.
   auto issue_loads = [&](Stage& s, int tile_unclamped) {
     const int r0 = min(tile_unclamped, last_tile) * kTile;
     {
@@ -137,8 +202,10 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   auto store_stage = [&](Stage& s, int buf) {
     unsigned char* base = lds + (size_t)buf * kBufB;
 #pragma unroll
-    for (int x = 0; x < kCsPass; ++x)
-      *reinterpret_cast<uint4v*>(base + kTileB + rope_row * kRopeRowB + (rope_col + x) * 16) = s.cs[x];
+    for (int x = 0; x < kCsPass; ++x) {
+      const int c = rope_col + x;
+      *reinterpret_cast<uint4v*>(base + kTileB + rope_row * (kDHead * 2) + ((c ^ (rope_row & 15)) * 16)) = s.cs[x];
+    }
 #pragma unroll
     for (int p = 0; p < kPass; ++p) {
       uint4v v = s.h[p];
@@ -164,9 +231,14 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     }
   };
 
-  // ---- first latent tiles go out before the (larger) weight fetch so that their
-  // HBM latency overlaps it
-  issue_loads(st[0], 0);
+  // ---- the first latent tiles go out before the (larger) weight fetch so that
+  // their HBM latency overlaps it
+  if (kDma) {
+#pragma unroll
+    for (int x = 0; x < kAheadTiles; ++x) dma_issue(x);
+  } else {
+    issue_loads(st[0], 0);
+  }
 
   // ---- which head / feature rows this wavefront owns
   int wsel, rt0;
@@ -202,21 +274,24 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     half8 cs[RT][2];
   };
   auto mfma_phase = [&](TileAcc& r, int tile) {
-    const unsigned char* base = lds + (size_t)(tile & 1) * kBufB;
+    const unsigned char* base = lds + (size_t)(tile % kBufs) * kBufB;
     const unsigned char* hrow = base + lane_lo * kRowB + kbase_b + lane_hi * 16;
-    // acc[rt][i] is feature 32*(rt0+rt) + mfma_row(i) of token lane_lo; its cos/sin
-    // weight sits at slot lane_hi*64 + (rt0+rt)*16 + i of the token's table row
-    const unsigned char* crow = base + kTileB + lane_lo * kRopeRowB + (lane_hi * 64 + rt0 * 16) * 2;
+    // acc[rt][i] is feature 32*(rt0+rt) + mfma_row(i) of token lane_lo; its cos/sin weight is
+    // half (rt0+rt)*16 + i of the token's table row half lane_hi, i.e. 16-byte piece
+    // lane_hi*8 + (rt0+rt)*2 + i/8, stored at piece ^ (row & 15)
+    const unsigned char* crow = base + kTileB + lane_lo * (kDHead * 2);
     // B operand of k-step ks: 8 latent values of token lane_lo; fetched two steps ahead of its MFMAs
     constexpr int kAhead = 2;
     half8 hf[kAhead + 1];
 #pragma unroll
     for (int x = 0; x < kAhead && x < NKS; ++x) hf[x] = *reinterpret_cast<const half8*>(hrow + x * 32);
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      r.cs[rt][0] = *reinterpret_cast<const half8*>(crow + rt * 32);
-      r.cs[rt][1] = *reinterpret_cast<const half8*>(crow + rt * 32 + 16);
-    }
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int hx = 0; hx < 2; ++hx) {
+        const int piece = lane_hi * 8 + (rt0 + rt) * 2 + hx;
+        r.cs[rt][hx] = *reinterpret_cast<const half8*>(crow + ((piece ^ (lane_lo & 15)) * 16));
+      }
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       if (ks + kAhead < NKS)
@@ -247,8 +322,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) part[i & 3] = fmaf(r.acc[rt][8 + i], (float)r.cs[rt][1][i], part[i & 3]);
     }
-    float sum = (part[0] + part[1]) + (part[2] + part[3]);
-    sum += __shfl_xor(sum, 32, 64);
+    const float sum = sum_across_halves((part[0] + part[1]) + (part[2] + part[3]));
     // Unconditional store (a constant number of memory operations in flight): both
     // lane halves hold the same sum, idle wavefronts duplicate head h0's values,
     // and rows past the end of the sequence fall into the padding of the score
@@ -256,42 +330,47 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     out_row[t0 + lane_lo] = sum * a.scale;
   };
 
-  // ---- start-up: tile 0 into LDS, tiles 1 and 2 in flight.  The explicit wait
-  // (vmcnt = 0) lets the loop start from the same set of pending loads as every
-  // later iteration, which keeps the compiler's wait counts in the loop exact.
-  store_stage(st[0], 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);
-  issue_loads(st[1], 1);
-  issue_loads(st[0], 2);
+  // ---- start-up
+  if (kDma) {
+    // tiles 0 .. kAheadTiles-1 are in flight; tile 0 must have landed before the first MFMA phase
+    dma_wait(std::integral_constant<int, kInFlight>{});
+  } else {
+    // tile 0 into LDS, tiles 1 and 2 in flight.  The explicit wait (vmcnt = 0) lets
+    // the loop start from the same set of pending loads as every later iteration.
+    store_stage(st[0], 0);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    issue_loads(st[1], 1);
+    issue_loads(st[0], 2);
+  }
   __syncthreads();
 
   if (!kPingPong) {
-    // one wavefront per SIMD: compute tile i, then publish tile i+1 (loaded two tiles ago)
+    // one wavefront per SIMD: compute tile k, then publish tile k+1
     TileAcc r;
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-      mfma_phase(r, tile);
-      epilogue(r, tile);
-      store_stage(st[1], 1);
-      issue_loads(st[1], tile + 3);
+    for (int k = 0; k < n_tiles; k += 2) {
+      mfma_phase(r, k);
+      epilogue(r, k);
+      if (kDma) { dma_issue(k + kAheadTiles); dma_wait(std::integral_constant<int, kInFlight>{}); }
+      else      { store_stage(st[1], 1); issue_loads(st[1], k + 3); }
       __syncthreads();
-      if (tile + 1 >= n_tiles) break;
-      mfma_phase(r, tile + 1);
-      epilogue(r, tile + 1);
-      store_stage(st[0], 0);
-      issue_loads(st[0], tile + 4);
+      if (k + 1 >= n_tiles) break;
+      mfma_phase(r, k + 1);
+      epilogue(r, k + 1);
+      if (kDma) { dma_issue(k + 1 + kAheadTiles); dma_wait(std::integral_constant<int, kInFlight>{}); }
+      else      { store_stage(st[0], 0); issue_loads(st[0], k + 4); }
       __syncthreads();
     }
   } else {
     // Ping-pong: phases alternate between barriers.  In even phases wavefronts
     // 0-3 (group A) run the MFMAs of a tile while 4-7 (group B) do everything
-    // else (RoPE epilogue of their previous tile, LDS stores, global loads); in
-    // odd phases the roles swap.  Both groups execute the same loop - an aux
-    // step, a barrier, an MFMA step, a barrier - and group A simply enters it
-    // one MFMA step early, so group B computes tile k-1 where A computes tile k.
-    // At loop position k every thread publishes its share of tile k+1 (loaded
-    // two positions earlier) and queues tile k+3: a tile is complete one barrier
-    // before either group reads it, and a buffer is overwritten only after the
-    // barrier that follows its last read.
+    // else (RoPE epilogue of their previous tile, staging); in odd phases the
+    // roles swap.  Both groups execute the same loop - an aux step, a barrier,
+    // an MFMA step, a barrier - and group A simply enters it one MFMA step
+    // early, so group B computes tile k-1 where A computes tile k.  At loop
+    // position k every thread makes sure its share of tile k+1 is in LDS and
+    // requests a later tile into the buffer whose last reader (tile k-1) has
+    // passed a barrier: a tile is complete one barrier before either group
+    // reads it.
     const int grp = wave >> 2;                       // uniform
     const int n_iter = n_tiles + grp;
     TileAcc r;
@@ -303,10 +382,16 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
       __syncthreads();
     }
     auto position = [&](int k, Stage& s) {
-      if (have) epilogue(r, tile_done);
-      // past the last tile this publishes a duplicate of it into the buffer nobody reads any more
-      store_stage(s, (k + 1) & 1);
-      issue_loads(s, k + 3);
+      if (kDma) {
+        if (have) epilogue(r, tile_done);
+        dma_issue(k + kAheadTiles);                  // into the buffer tile k-1 occupied
+        dma_wait(std::integral_constant<int, kInFlight>{});   // everything up to tile k+1 has landed
+      } else {
+        // past the last tile this publishes a duplicate of it into the buffer nobody reads any more
+        store_stage(s, (k + 1) & 1);
+        if (have) epilogue(r, tile_done);
+        issue_loads(s, k + 3);
+      }
       __syncthreads();
       const int t = k + 1 - grp;
       have = t < n_tiles;
@@ -322,6 +407,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
       position(k + 1, st[0]);
     }
   }
+  if (kDma) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // no LDS-direct load may outlive the workgroup's LDS allocation
 }
 
 }  // namespace palu
