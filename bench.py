@@ -110,8 +110,7 @@ def main() -> int:
                        P.PALU_I4 if k_i4 else act, P.PALU_I4 if v_i4 else act, layer.quant_block, layer.rope_theta)
     table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, seq)
     ws = torch.empty(P.palu_attn_decode_workspace_bytes(desc, batch, seq), dtype=torch.uint8, device="cuda")
-    ws_ek = torch.empty(P.palu_encode_workspace_bytes(desc, 0, batch), dtype=torch.uint8, device="cuda")
-    ws_ev = torch.empty(P.palu_encode_workspace_bytes(desc, 1, batch), dtype=torch.uint8, device="cuda")
+    ws_e = torch.empty(P.palu_encode_workspace_bytes(desc, 2, batch), dtype=torch.uint8, device="cuda")
     out = torch.empty((batch, layer.n_heads, layer.d_head), dtype=torch.float32, device="cuda")
     dst_row = (torch.arange(batch, dtype=torch.int32, device="cuda") * seq + (seq - 1)).contiguous()
     nbk, nbv = layer.R_k // layer.quant_block, layer.R_v // layer.quant_block
@@ -135,22 +134,23 @@ def main() -> int:
 
     def step(i: int, events=None):
         s = i % n_sets
+        # down-project the new token into both caches (fp16 row first when the cache is int4)
+        k_dst, k_stride, k_rows = (new_k, layer.R_k, None) if k_i4 else (case.Hk[s], layer.R_k, dst_row)
+        v_dst, v_stride, v_rows = (new_v, layer.R_v, None) if v_i4 else (case.Hv[s], layer.R_v, dst_row)
+        if k_rows is v_rows:
+            P.palu_encode_kv(desc, case.x_new, case.Ak, case.Av, k_dst, k_stride, v_dst, v_stride, k_rows, ws_e)
+        else:
+            P.palu_encode(desc, 0, case.x_new, case.Ak, k_dst, k_stride, k_rows, ws_e)
+            P.palu_encode(desc, 1, case.x_new, case.Av, v_dst, v_stride, v_rows, ws_e)
+        hk, kq, hv, vq = case.Hk[s], {}, case.Hv[s], {}
         if k_i4:
-            P.palu_encode(desc, 0, case.x_new, case.Ak, new_k, layer.R_k, None, ws_ek)
             codes, sc, zp = qk[s]
             P.palu_quant_latent(desc, 0, new_k, layer.R_k, batch, codes, sc, zp, dst_row)
             hk, kq = codes, dict(hk_scale=sc, hk_zero=zp)
-        else:
-            P.palu_encode(desc, 0, case.x_new, case.Ak, case.Hk[s], layer.R_k, dst_row, ws_ek)
-            hk, kq = case.Hk[s], {}
         if v_i4:
-            P.palu_encode(desc, 1, case.x_new, case.Av, new_v, layer.R_v, None, ws_ev)
             codes, sc, zp = qv[s]
             P.palu_quant_latent(desc, 1, new_v, layer.R_v, batch, codes, sc, zp, dst_row)
             hv, vq = codes, dict(hv_scale=sc, hv_zero=zp)
-        else:
-            P.palu_encode(desc, 1, case.x_new, case.Av, case.Hv[s], layer.R_v, dst_row, ws_ev)
-            hv, vq = case.Hv[s], {}
         P.palu_attn_decode(desc, batch, seq, seq, case.q, case.q_pos, hk, hv, case.Bk, case.Bv, table, seq,
                            out=out, workspace=ws, stage_events=events, **kq, **vq)
 

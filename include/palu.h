@@ -112,7 +112,8 @@ int palu_rope_table_init(float rope_theta, int32_t d_head, int32_t n_pos, void* 
  * Down-projection h = x A of new tokens into the latent cache (Sec. 3.1,
  * first display; grouped A of Sec. 3.2.3: group j is columns rank_off[j].. of
  * A, so all groups are one product).
- *   which       0 = key side (k_rank_off), 1 = value side (v_rank_off)
+ *   which       0 = key side (k_rank_off), 1 = value side (v_rank_off); the workspace
+ *               query also accepts 2 = both sides, for palu_encode_kv
  *   x           DEVICE [n_tok, n_heads*d_head] act_dtype, row-major
  *   A           DEVICE [n_heads*d_head, R] act_dtype, row-major, R = rank_off[n_groups]
  *   latent      DEVICE base of the cache, act_dtype; token t is written to
@@ -126,6 +127,17 @@ int palu_encode_workspace_bytes(const palu_layer_desc* desc, int which, int32_t 
 int palu_encode(const palu_layer_desc* desc, int which, const void* x, int32_t n_tok, const void* A,
                 void* latent, int64_t row_stride_elems, const int32_t* dst_row,
                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Both down-projections of the same tokens in one pass (h_k = x A_k into the key
+ * cache, h_v = x A_v into the value cache; Sec. 3.1, Fig. 2): the same result as
+ * palu_encode(which = 0) followed by palu_encode(which = 1), with half the
+ * launches.  Arguments as for palu_encode; workspace of
+ * palu_encode_workspace_bytes(desc, 2, n_tok) bytes.
+ */
+int palu_encode_kv(const palu_layer_desc* desc, const void* x, int32_t n_tok, const void* Ak, const void* Av,
+                   void* hk, int64_t hk_row_stride_elems, void* hv, int64_t hv_row_stride_elems,
+                   const int32_t* dst_row, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Asymmetric uniform 4-bit quantization of latent rows (Appendix A with B = 4),

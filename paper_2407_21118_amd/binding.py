@@ -71,6 +71,8 @@ def load_library():
     lib.palu_rope_table_init.argtypes = [ctypes.c_float, i32, i32, vp, vp]
     lib.palu_encode_workspace_bytes.argtypes = [dp, ctypes.c_int, i32, szp]
     lib.palu_encode.argtypes = [dp, ctypes.c_int, vp, i32, vp, vp, i64, vp, vp, sz, vp]
+    lib.palu_encode_kv.argtypes = [dp, vp, i32, vp, vp, vp, i64, vp, i64, vp, vp, sz, vp]
+    lib.palu_encode_kv.restype = ctypes.c_int
     lib.palu_quant_latent.argtypes = [dp, ctypes.c_int, vp, i64, i32, vp, vp, vp, vp, vp]
     lib.palu_attn_decode_workspace_bytes.argtypes = [dp, i32, i32, szp]
     lib.palu_attn_decode.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -190,6 +192,20 @@ def palu_encode(desc: LayerDesc, which: int, x, A, latent, row_stride_elems: int
                                       int(row_stride_elems), _ptr(dst_row), _ptr(workspace),
                                       workspace.numel() * workspace.element_size(), _stream(stream)), "palu_encode")
     return latent
+
+
+def palu_encode_kv(desc: LayerDesc, x, Ak, Av, hk, hk_row_stride_elems: int, hv, hv_row_stride_elems: int,
+                   dst_row=None, workspace=None, stream=None):
+    import torch
+    n_tok = int(x.shape[0])
+    if workspace is None:
+        workspace = torch.empty(palu_encode_workspace_bytes(desc, 2, n_tok), dtype=torch.uint8, device=x.device)
+    _need_cuda(x, Ak, Av, hk, hv, dst_row, workspace)
+    _check(load_library().palu_encode_kv(desc.ref(), _ptr(x), n_tok, _ptr(Ak), _ptr(Av), _ptr(hk),
+                                         int(hk_row_stride_elems), _ptr(hv), int(hv_row_stride_elems),
+                                         _ptr(dst_row), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)),
+           "palu_encode_kv")
 
 
 def palu_quant_latent(desc: LayerDesc, which: int, latent, row_stride_elems: int, n_tok: int,

@@ -103,31 +103,69 @@ constexpr int kNumScoreCls = kNumRankCls * 3;     // (rank class, log2 of groups
 constexpr int kScoreMaxWidth = 512;               // latent columns one workgroup stages per token
 
 int rank_class(int r) { return (r >= 32 && r <= 512 && r % 32 == 0) ? r / 32 - 1 : -1; }
+constexpr int kSliceRank = 256;                   // ranks above 512 are contracted in slices of this many rows
 bool rank_class_half(int rc) { return rc >= 8; }
 
-struct ScoreClass {
-  int id;                              // rank class * 3 + log2(groups per workgroup)
-  int n_units;
-  ScoreUnit u[PALU_MAX_HEADS];         // split into launches of kMaxScoreUnits
-};
+constexpr int kMaxPlanUnits = 1024;
 struct ScorePlan {
-  int n_cls;                           // classes in use
-  ScoreClass cls[kNumScoreCls];
+  int n_cls;                           // kernel classes in use
+  int cls_id[kNumScoreCls];            // rank class * 3 + log2(groups per workgroup) of each class in use
   int total_units;
-  bool two_parts[PALU_MAX_HEADS];
+  ScoreUnit units[kMaxPlanUnits];      // all units; unit_cls[i] indexes cls_id
+  uint8_t unit_cls[kMaxPlanUnits];
+  int slices[PALU_MAX_HEADS];          // rank slices of each head (1 unless its rank exceeds 512)
+  bool half_heads[PALU_MAX_HEADS];     // head is always split over two wavefronts (rank 288..512)
+  int max_slices;
 };
 
 int plan_score(const Meta& m, ScorePlan* p) {
   p->n_cls = 0;
   p->total_units = 0;
-  std::memset(p->two_parts, 0, sizeof(p->two_parts));
+  p->max_slices = 1;
+  std::memset(p->half_heads, 0, sizeof(p->half_heads));
   int slot_of[kNumScoreCls];
   for (int& v : slot_of) v = -1;
+  auto add_unit = [&](int id, const ScoreUnit& u) -> int {
+    if (slot_of[id] < 0) {
+      slot_of[id] = p->n_cls;
+      p->cls_id[p->n_cls++] = id;
+    }
+    if (p->total_units >= kMaxPlanUnits) return PALU_ERR_UNSUPPORTED;
+    p->units[p->total_units] = u;
+    p->unit_cls[p->total_units] = (uint8_t)slot_of[id];
+    ++p->total_units;
+    return (int)PALU_OK;
+  };
   int h = 0;
   while (h < m.n_heads) {
     const int j0 = m.group_of_head[h];
     const int r = m.k_off[j0 + 1] - m.k_off[j0];
     const int s = m.head_off[j0 + 1] - m.head_off[j0];
+    ScoreUnit u;
+    u.h0 = h;
+    u.s = s;
+    u.head_off0 = m.head_off[j0];
+    u.head_stride = r * PALU_D_HEAD;
+    if (r > 512) {
+      // a rank too large for the register-resident weights: contract it in slices of
+      // 256 rows; every slice is a unit of its own and writes its own score planes
+      if (r % kSliceRank != 0) return PALU_ERR_UNSUPPORTED;
+      const int nh = std::min(4, m.head_off[j0 + 1] - h);
+      const int n_sl = r / kSliceRank;
+      for (int sl = 0; sl < n_sl; ++sl) {
+        u.nh = nh;
+        u.k_off0 = m.k_off[j0] + sl * kSliceRank;
+        u.bk_off0 = m.bk_off[j0] + (h - m.head_off[j0]) * u.head_stride + sl * kSliceRank * PALU_D_HEAD;
+        u.head_off0 = h;                 // heads of the unit are counted from h0 inside one group
+        u.part0 = 2 * sl;
+        const int st = add_unit(rank_class(kSliceRank) * 3, u);
+        if (st != PALU_OK) return st;
+      }
+      for (int x = 0; x < nh; ++x) p->slices[h + x] = n_sl;
+      p->max_slices = std::max(p->max_slices, n_sl);
+      h += nh;
+      continue;
+    }
     const int rc = rank_class(r);
     if (rc < 0) return PALU_ERR_UNSUPPORTED;
     int nh, lg = 0;
@@ -147,24 +185,16 @@ int plan_score(const Meta& m, ScorePlan* p) {
         }
       }
     }
-    const int id = rc * 3 + lg;
-    if (slot_of[id] < 0) {
-      slot_of[id] = p->n_cls;
-      p->cls[p->n_cls].id = id;
-      p->cls[p->n_cls].n_units = 0;
-      ++p->n_cls;
-    }
-    ScoreClass& c = p->cls[slot_of[id]];
-    ScoreUnit& u = c.u[c.n_units++];
-    u.h0 = h;
     u.nh = nh;
-    u.s = s;
-    u.head_off0 = m.head_off[j0];
     u.k_off0 = m.k_off[j0];
     u.bk_off0 = m.bk_off[j0];
-    ++p->total_units;
-    if (rank_class_half(rc))
-      for (int x = 0; x < nh; ++x) p->two_parts[h + x] = true;
+    u.part0 = 0;
+    const int st = add_unit(rc * 3 + lg, u);
+    if (st != PALU_OK) return st;
+    for (int x = 0; x < nh; ++x) {
+      p->slices[h + x] = 1;
+      p->half_heads[h + x] = rank_class_half(rc);
+    }
     h += nh;
   }
   return PALU_OK;
@@ -216,14 +246,14 @@ struct Workspace {
   long long mfold_bstride, part_stride;
 };
 
-int carve(const Meta& m, int batch, int max_seq, int n_split_cap, Workspace* w) {
+int carve(const Meta& m, int batch, int max_seq, int n_split_cap, int n_parts, Workspace* w) {
   w->lpad = ceil_div(max_seq, 32) * 32;
   w->mfold_bstride = m.bk_off[m.n_groups];
   w->o_stride = m.bv_off[m.n_groups] / PALU_D_HEAD;
   w->part_stride = (long long)batch * m.n_heads * w->lpad;
   size_t off = 0;
   w->mfold = off;   off = align_up(off + (size_t)batch * w->mfold_bstride * 2);
-  w->scores = off;  off = align_up(off + (size_t)2 * w->part_stride * 4);
+  w->scores = off;  off = align_up(off + (size_t)n_parts * w->part_stride * 4);
   w->o_part = off;  off = align_up(off + (size_t)batch * n_split_cap * w->o_stride * 4);
   w->ml_part = off; off = align_up(off + (size_t)batch * n_split_cap * m.n_heads * 2 * 4);
   w->rope_rows = off; off = align_up(off + (size_t)w->lpad * PALU_D_HEAD * 2);   // cos/sin rows gathered by k_pos
@@ -362,44 +392,58 @@ int palu_encode_workspace_bytes(const palu_layer_desc* desc, int which, int32_t 
   Meta m;
   const int st = check_desc(desc, &m);
   if (st != PALU_OK) return st;
-  if (!out_bytes || n_tok <= 0 || (which != 0 && which != 1)) return PALU_ERR_INVALID_ARG;
-  const int R = which ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
+  if (!out_bytes || n_tok <= 0 || which < 0 || which > 2) return PALU_ERR_INVALID_ARG;
   const int d = m.n_heads * PALU_D_HEAD;
-  *out_bytes = align_up((size_t)(d / kEncRows) * n_tok * R * 4);
+  size_t total = 0;
+  for (int side = 0; side < 2; ++side) {
+    if (which != 2 && which != side) continue;
+    const int R = side ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
+    total += align_up((size_t)(d / kEncRows) * n_tok * R * 4);
+  }
+  *out_bytes = total;
   return PALU_OK;
 }
 
-int palu_encode(const palu_layer_desc* desc, int which, const void* x, int32_t n_tok, const void* A,
-                void* latent, int64_t row_stride_elems, const int32_t* dst_row,
-                void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int encode_impl(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x, int32_t n_tok,
+                const void* Ak, const void* Av, void* hk, int64_t hk_stride, void* hv, int64_t hv_stride,
+                const int32_t* dst_row, void* workspace, size_t workspace_bytes, void* stream) {
   Meta m;
   const int st = check_desc(desc, &m);
   if (st != PALU_OK) return st;
-  if (!x || !A || !latent || !workspace || n_tok <= 0 || (which != 0 && which != 1)) return PALU_ERR_INVALID_ARG;
-  const int R = which ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
+  if (!x || !workspace || n_tok <= 0) return PALU_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 15)) return PALU_ERR_INVALID_ARG;
   const int d = m.n_heads * PALU_D_HEAD;
-  if (row_stride_elems < R || (row_stride_elems & 1)) return PALU_ERR_INVALID_ARG;
-  if ((reinterpret_cast<uintptr_t>(A) & 15) || (reinterpret_cast<uintptr_t>(latent) & 3) ||
-      (reinterpret_cast<uintptr_t>(workspace) & 15))
-    return PALU_ERR_INVALID_ARG;
-  size_t need = 0;
-  palu_encode_workspace_bytes(desc, which, n_tok, &need);
-  if (workspace_bytes < need) return PALU_ERR_WORKSPACE_TOO_SMALL;
-
   EncodeArgs a;
+  std::memset(&a, 0, sizeof(a));
   a.x = static_cast<const uint16_t*>(x);
-  a.A = static_cast<const uint16_t*>(A);
-  a.partial = static_cast<float*>(workspace);
-  a.latent = static_cast<uint16_t*>(latent);
   a.dst_row = dst_row;
-  a.row_stride = row_stride_elems;
   a.n_tok = n_tok;
   a.d = d;
-  a.R = R;
   a.k_splits = d / kEncRows;
+  size_t off = 0;
+  int n_sides = 0, max_R = 0;
+  for (int side = 0; side < 2; ++side) {
+    if (!(side ? do_v : do_k)) continue;
+    const void* A = side ? Av : Ak;
+    void* lat = side ? hv : hk;
+    const int64_t stride = side ? hv_stride : hk_stride;
+    const int R = side ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
+    if (!A || !lat || stride < R || (stride & 1)) return PALU_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(A) & 15) || (reinterpret_cast<uintptr_t>(lat) & 3)) return PALU_ERR_INVALID_ARG;
+    EncodeSide& sd = a.side[n_sides++];
+    sd.A = static_cast<const uint16_t*>(A);
+    sd.partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + off);
+    sd.latent = static_cast<uint16_t*>(lat);
+    sd.row_stride = stride;
+    sd.R = R;
+    off += align_up((size_t)a.k_splits * n_tok * R * 4);
+    max_R = std::max(max_R, R);
+  }
+  if (workspace_bytes < off) return PALU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const dim3 g1((unsigned)ceil_div(R, kEncCols), (unsigned)a.k_splits);
-  const dim3 g2((unsigned)ceil_div(R, 64), (unsigned)n_tok);
+  const dim3 g1((unsigned)ceil_div(max_R, kEncCols), (unsigned)a.k_splits, (unsigned)n_sides);
+  const dim3 g2((unsigned)ceil_div(max_R, 64), (unsigned)n_tok, (unsigned)n_sides);
   if (desc->act_dtype == PALU_F16) {
     hipLaunchKernelGGL(encode_partial_kernel<F16>, g1, dim3(256), 0, s, a);
     hipLaunchKernelGGL(encode_finish_kernel<F16>, g2, dim3(256), 0, s, a);
@@ -408,6 +452,22 @@ int palu_encode(const palu_layer_desc* desc, int which, const void* x, int32_t n
     hipLaunchKernelGGL(encode_finish_kernel<BF16>, g2, dim3(256), 0, s, a);
   }
   return launch_ok();
+}
+}  // namespace
+
+int palu_encode(const palu_layer_desc* desc, int which, const void* x, int32_t n_tok, const void* A,
+                void* latent, int64_t row_stride_elems, const int32_t* dst_row,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  if (which != 0 && which != 1) return PALU_ERR_INVALID_ARG;
+  return encode_impl(desc, which == 0, which == 1, x, n_tok, A, A, latent, row_stride_elems, latent,
+                     row_stride_elems, dst_row, workspace, workspace_bytes, stream);
+}
+
+int palu_encode_kv(const palu_layer_desc* desc, const void* x, int32_t n_tok, const void* Ak, const void* Av,
+                   void* hk, int64_t hk_row_stride_elems, void* hv, int64_t hv_row_stride_elems,
+                   const int32_t* dst_row, void* workspace, size_t workspace_bytes, void* stream) {
+  return encode_impl(desc, true, true, x, n_tok, Ak, Av, hk, hk_row_stride_elems, hv, hv_row_stride_elems,
+                     dst_row, workspace, workspace_bytes, stream);
 }
 
 // ------------------------------------------------------------------ quantize
@@ -453,7 +513,7 @@ int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch,
   if ((st = plan_score(m, &sp)) != PALU_OK) return st;
   if ((st = plan_value(m, &vp)) != PALU_OK) return st;
   Workspace w;
-  carve(m, batch, max_seq, split_bound(vp.total_units, batch, max_seq), &w);
+  carve(m, batch, max_seq, split_bound(vp.total_units, batch, max_seq), 2 * sp.max_slices, &w);
   *out_bytes = w.total;
   return PALU_OK;
 }
@@ -507,7 +567,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
   if (n_split > kMaxSplits) return PALU_ERR_UNSUPPORTED;
   const int n_split_cap = split_bound(vp.total_units, batch, max_seq);
   Workspace w;
-  carve(m, batch, max_seq, n_split_cap, &w);
+  carve(m, batch, max_seq, n_split_cap, 2 * sp.max_slices, &w);
   if (n_split > n_split_cap) return PALU_ERR_INVALID_ARG;
   if (workspace_bytes < w.total) return PALU_ERR_WORKSPACE_TOO_SMALL;
 
@@ -532,10 +592,16 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.mfold = reinterpret_cast<uint16_t*>(ws + w.mfold);
     a.mfold_bstride = w.mfold_bstride;
     a.theta = desc->rope_theta;
-    for (int f = 0; f < kHalf; ++f)
-      a.inv_freq[f] = desc->rope_theta > 0.f ? std::pow((double)desc->rope_theta, -2.0 * f / (double)PALU_D_HEAD) : 0.0;
+    for (int f = 0; f < kHalf; ++f) {
+      const double rev = desc->rope_theta > 0.f
+          ? std::pow((double)desc->rope_theta, -2.0 * f / (double)PALU_D_HEAD) / 6.283185307179586476925 : 0.0;
+      a.rev_hi[f] = (float)rev;
+      a.rev_lo[f] = (float)(rev - (double)a.rev_hi[f]);
+    }
     a.meta = m;
-    const dim3 g((unsigned)m.n_heads, (unsigned)batch, (unsigned)kFoldSlices);
+    int max_r = 0;
+    for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
+    const dim3 g((unsigned)(max_r / 16), (unsigned)m.n_heads, (unsigned)batch);
     if ((st = mark(0)) != PALU_OK) return st;
     if (act == PALU_F16) hipLaunchKernelGGL(fold_kernel<F16>, g, dim3(256), 0, s, a);
     else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
@@ -585,21 +651,28 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.chunk_tokens = chunk_tiles * kTile;
     a.n_chunks = ceil_div(tiles, chunk_tiles);
     for (int cls = 0; cls < sp.n_cls; ++cls) {
-      const ScoreClass& c = sp.cls[cls];
-      const int rc = c.id / 3, lg = c.id % 3;
+      const int id = sp.cls_id[cls];
+      const int rc = id / 3, lg = id % 3;
       const int width = (32 * (rc + 1)) << lg;
       const bool dma = act == PALU_F16 && !k_i4;
       const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width);
-      ScoreFn fn = score_fn(act, k_i4, c.id, waves8);
+      ScoreFn fn = score_fn(act, k_i4, id, waves8);
       if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
       const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
-      for (int u0 = 0; u0 < c.n_units; u0 += kMaxScoreUnits) {
-        a.units.n_units = std::min(kMaxScoreUnits, c.n_units - u0);
-        std::memcpy(a.units.u, c.u + u0, sizeof(ScoreUnit) * a.units.n_units);
+      auto flush = [&]() -> int {
+        if (a.units.n_units == 0) return PALU_OK;
         const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
         hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
-        if ((st = launch_ok()) != PALU_OK) return st;
+        a.units.n_units = 0;
+        return launch_ok();
+      };
+      a.units.n_units = 0;
+      for (int i = 0; i < sp.total_units; ++i) {
+        if (sp.unit_cls[i] != cls) continue;
+        a.units.u[a.units.n_units++] = sp.units[i];
+        if (a.units.n_units == kMaxScoreUnits && (st = flush()) != PALU_OK) return st;
       }
+      if ((st = flush()) != PALU_OK) return st;
     }
   }
 
@@ -624,9 +697,9 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.o_stride = w.o_stride;
     a.quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
     a.n_blocks_q = Rv / a.quant_block;
-    std::memset(a.parts_mask_lo, 0, sizeof(a.parts_mask_lo));
-    for (int h = 0; h < m.n_heads; ++h)
-      if (sp.two_parts[h] || waves8) a.parts_mask_lo[h >> 5] |= 1u << (h & 31);   // half-head wavefronts: two partial scores
+    std::memset(a.n_parts, 0, sizeof(a.n_parts));
+    for (int h = 0; h < m.n_heads; ++h)      // half-head wavefronts write two planes per rank slice
+      a.n_parts[h] = (uint8_t)((waves8 || sp.half_heads[h]) ? 2 * sp.slices[h] : sp.slices[h]);
     a.meta = m;
     if ((st = mark(2)) != PALU_OK) return st;
     for (int cls = 0; cls < kNumValCls; ++cls) {
@@ -651,7 +724,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.seq_len = seq_len;
     a.o_stride = w.o_stride;
     a.meta = m;
-    const dim3 g((unsigned)m.n_heads, (unsigned)batch);
+    const dim3 g((unsigned)m.n_heads * 4, (unsigned)batch);
     if ((st = mark(3)) != PALU_OK) return st;
     if (act == PALU_F16) hipLaunchKernelGGL(combine_kernel<F16>, g, dim3(256), 0, s, a);
     else hipLaunchKernelGGL(combine_kernel<BF16>, g, dim3(256), 0, s, a);

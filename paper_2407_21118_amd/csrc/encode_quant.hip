@@ -14,25 +14,40 @@ constexpr int kEncRows = 64;      // rows of A per workgroup (16 per wavefront)
 constexpr int kEncCols = 512;     // columns of A per workgroup (8 per lane)
 constexpr int kEncTok = 8;        // tokens accumulated per pass over the weights
 
-struct EncodeArgs {
-  const uint16_t* x;       // [n_tok, d]
+struct EncodeSide {
   const uint16_t* A;       // [d, R]
   float* partial;          // [k_splits][n_tok][R]
   uint16_t* latent;
-  const int32_t* dst_row;
   long long row_stride;
-  int n_tok, d, R, k_splits;
+  int R;
+};
+struct EncodeArgs {
+  const uint16_t* x;       // [n_tok, d]
+  const int32_t* dst_row;
+  EncodeSide side[2];      // key and value caches; blockIdx.z selects (one launch may cover both)
+  int n_tok, d, k_splits;
 };
 
-// grid (ceil(R / 512), d / 64), 256 threads.
+// grid (ceil(max R / 512), d / 64, sides), 256 threads.
 template <typename T>
 __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
   __shared__ float xs[kEncTok][kEncRows];
   __shared__ float red[3][kEncTok][kEncCols];     // wavefronts 1..3 hand their sums to wavefront 0
+  const EncodeSide sd = a.side[blockIdx.z];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c0 = blockIdx.x * kEncCols + lane * 8;
   const int k0 = blockIdx.y * kEncRows;
-  const bool col_ok = c0 < a.R;                   // R is a multiple of 32, so 8 columns are all in or all out
+  const bool col_ok = c0 < sd.R;                  // R is a multiple of 32, so 8 columns are all in or all out
+  if (blockIdx.x * kEncCols >= sd.R) return;      // uniform
+
+  // the weight rows go out first: they are the long-latency HBM stream and do
+  // not depend on the activations
+  uint4v wraw[16];
+#pragma unroll
+  for (int kk = 0; kk < 16; ++kk) {
+    const int k = wave * 16 + kk;
+    wraw[kk] = col_ok ? *reinterpret_cast<const uint4v*>(sd.A + (size_t)(k0 + k) * sd.R + c0) : uint4v{0, 0, 0, 0};
+  }
 
   for (int tb = 0; tb < a.n_tok; tb += kEncTok) {
     const int nt = min(kEncTok, a.n_tok - tb);
@@ -47,23 +62,20 @@ __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
     for (int t = 0; t < kEncTok; ++t)
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[t][e] = 0.f;
-    if (col_ok) {
 #pragma unroll
-      for (int kk = 0; kk < 16; ++kk) {
-        const int k = wave * 16 + kk;
-        const uint4v raw = *reinterpret_cast<const uint4v*>(a.A + (size_t)(k0 + k) * a.R + c0);
-        float wv[8];
+    for (int kk = 0; kk < 16; ++kk) {
+      const int k = wave * 16 + kk;
+      float wv[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          wv[2 * e] = T::to_float((uint16_t)(raw[e] & 0xffffu));
-          wv[2 * e + 1] = T::to_float((uint16_t)(raw[e] >> 16));
-        }
+      for (int e = 0; e < 4; ++e) {
+        wv[2 * e] = T::to_float((uint16_t)(wraw[kk][e] & 0xffffu));
+        wv[2 * e + 1] = T::to_float((uint16_t)(wraw[kk][e] >> 16));
+      }
 #pragma unroll
-        for (int t = 0; t < kEncTok; ++t) {
-          const float xv = xs[t][k];
+      for (int t = 0; t < kEncTok; ++t) {
+        const float xv = xs[t][k];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(xv, wv[e], acc[t][e]);
-        }
+        for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(xv, wv[e], acc[t][e]);
       }
     }
     if (wave > 0) {
@@ -77,7 +89,7 @@ __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
 #pragma unroll
       for (int t = 0; t < kEncTok; ++t) {
         if (t >= nt) break;
-        float* dst = a.partial + ((size_t)blockIdx.y * a.n_tok + tb + t) * a.R + c0;
+        float* dst = sd.partial + ((size_t)blockIdx.y * a.n_tok + tb + t) * sd.R + c0;
         float4v o0, o1;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -93,27 +105,29 @@ __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
 
 // Sums the split-K partials in a fixed order, rounds once, scatters the rows.
 // Workgroup = 64 columns of one token; thread = (quarter of the splits, column).
-// grid (R / 64, n_tok), 256 threads.
+// grid (ceil(max R / 64), n_tok, sides), 256 threads.
 template <typename T>
 __global__ __launch_bounds__(256) void encode_finish_kernel(EncodeArgs a) {
   __shared__ float part[4][64];
+  const EncodeSide sd = a.side[blockIdx.z];
+  if ((int)blockIdx.x * 64 >= sd.R) return;       // uniform
   const int tid = threadIdx.x;
   const int c = blockIdx.x * 64 + (tid & 63), t = blockIdx.y, sub = tid >> 6;
   const int per = (a.k_splits + 3) / 4;
   float s = 0.f;
-  if (c < a.R) {
-    const float* p = a.partial + (size_t)t * a.R + c;
+  if (c < sd.R) {
+    const float* p = sd.partial + (size_t)t * sd.R + c;
 #pragma unroll 8
-    for (int ks = sub * per; ks < min((sub + 1) * per, a.k_splits); ++ks) s += p[(size_t)ks * a.n_tok * a.R];
+    for (int ks = sub * per; ks < min((sub + 1) * per, a.k_splits); ++ks) s += p[(size_t)ks * a.n_tok * sd.R];
   }
   part[sub][tid & 63] = s;
   __syncthreads();
-  if (tid < 32 && blockIdx.x * 64 + tid * 2 < a.R) {
+  if (tid < 32 && (int)blockIdx.x * 64 + tid * 2 < sd.R) {
     const int cc = tid * 2;
     const float s0 = (part[0][cc] + part[1][cc]) + (part[2][cc] + part[3][cc]);
     const float s1 = (part[0][cc + 1] + part[1][cc + 1]) + (part[2][cc + 1] + part[3][cc + 1]);
     const long long row = a.dst_row ? a.dst_row[t] : t;
-    uint32_t* dst = reinterpret_cast<uint32_t*>(a.latent + row * a.row_stride + blockIdx.x * 64 + cc);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(sd.latent + row * sd.row_stride + blockIdx.x * 64 + cc);
     *dst = (uint32_t)T::from_float(s0) | ((uint32_t)T::from_float(s1) << 16);
   }
 }

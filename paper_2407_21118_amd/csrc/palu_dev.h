@@ -93,8 +93,10 @@ struct ScoreUnit {
   int h0, nh;
   int s;                     // heads per group inside the unit
   int head_off0;             // first head of the unit's first group
-  int k_off0;                // first latent column of the unit's first group
-  int bk_off0;               // element offset of that group's B_k (and folded weights)
+  int k_off0;                // first latent column the unit stages (group start + rank slice)
+  int bk_off0;               // element offset of the unit's first head's folded weights (+ rank slice)
+  int head_stride;           // elements between the folded weights of consecutive heads (rank * 128)
+  int part0;                 // first partial-score plane the unit writes (2 per rank slice)
 };
 constexpr int kMaxScoreUnits = 64;      // per launch
 struct ScoreUnits {
@@ -140,7 +142,8 @@ struct FoldArgs {
   uint16_t* mfold;
   long long mfold_bstride;
   float theta;
-  double inv_freq[kHalf];    // theta^(-2f/128), computed on the host in float64
+  float rev_hi[kHalf];       // theta^(-2f/128) / (2 pi) from the host's float64 value, as a float pair hi + lo
+  float rev_lo[kHalf];
   Meta meta;
 };
 
@@ -163,7 +166,7 @@ struct ValueArgs {
   int o_stride;              // sum_h r_v(group(h)): floats per (batch, split)
   int quant_block;
   int n_blocks_q;
-  unsigned parts_mask_lo[PALU_MAX_HEADS / 32];   // bit h set: head h has two score parts
+  uint8_t n_parts[PALU_MAX_HEADS];   // partial-score planes of head h (halves of a head x rank slices), summed here
   Meta meta;
   Units units;
 };

@@ -41,60 +41,72 @@ __global__ __launch_bounds__(256) void rope_gather_kernel(RopeGatherArgs a) {
   reinterpret_cast<uint4v*>(a.rows)[(size_t)t * 16 + c] = reinterpret_cast<const uint4v*>(a.table)[(size_t)pos * 16 + c];
 }
 
-constexpr int kFoldSlices = 8;   // workgroups per (head, sequence): slice z folds k-steps z, z+8, ...
-
-// grid (n_heads, batch, kFoldSlices), 256 threads.
+// grid (max k-steps of any head, n_heads, batch), 256 threads: one workgroup folds
+// one k-step (16 rows of B_k) of one head.  The 16 x 128 block of B_k is fetched
+// with coalesced 16-byte loads, transposed through LDS, and written as 256
+// 16-byte words in MFMA operand order.
 template <typename T>
 __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
   __shared__ float qr[kDHead];
-  const int h = blockIdx.x, b = blockIdx.y, slice = blockIdx.z;
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[16][kDHead + 8];
+  const int ks = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const Meta& m = a.meta;
   const int j = m.group_of_head[h];
   const int u = h - m.head_off[j];
   const int r = m.k_off[j + 1] - m.k_off[j];
-  const int nks = r >> 4;
-  if (slice >= nks) return;
+  if (ks >= (r >> 4)) return;
   const int width = (m.head_off[j + 1] - m.head_off[j]) * kDHead;
 
+  // rows 16*ks .. 16*ks+15 of this head's 128 columns: thread = (row, 8-column piece)
+  const uint16_t* B = a.Bk + m.bk_off[j] + u * kDHead;
+  const int lrow = tid >> 4, lcol = (tid & 15) * 8;
+  const uint4v raw = *reinterpret_cast<const uint4v*>(B + (size_t)(16 * ks + lrow) * width + lcol);
+
   if (tid < kHalf) {
+    // rotate the query: angle = pos * w_f with w_f / 2pi given as a float pair
+    // (hi, lo) from the host's float64 value, so that the angle in revolutions
+    // keeps ~1e-7 absolute accuracy for positions up to 2^24
     const uint16_t* qp = a.q + ((size_t)b * m.n_heads + h) * kDHead;
-    const double x0 = (double)T::to_float(qp[tid]);
-    const double x1 = (double)T::to_float(qp[tid + kHalf]);
-    double c = 1.0, s = 0.0;
-    if (a.theta > 0.f) sincos((double)a.q_pos[b] * a.inv_freq[tid], &s, &c);
-    qr[tid] = (float)(x0 * c - x1 * s);
-    qr[tid + kHalf] = (float)(x1 * c + x0 * s);
+    const float x0 = T::to_float(qp[tid]);
+    const float x1 = T::to_float(qp[tid + kHalf]);
+    float c = 1.f, s = 0.f;
+    if (a.theta > 0.f) {
+      const float pos = (float)a.q_pos[b];
+      const float p = pos * a.rev_hi[tid];
+      const float e = fmaf(pos, a.rev_hi[tid], -p);
+      const float rev = (p - floorf(p)) + (e + pos * a.rev_lo[tid]);
+      s = __builtin_amdgcn_sinf(rev);
+      c = __builtin_amdgcn_cosf(rev);
+    }
+    qr[tid] = x0 * c - x1 * s;
+    qr[tid + kHalf] = x1 * c + x0 * s;
   }
+  *reinterpret_cast<uint4v*>(&Bs[lrow][lcol]) = raw;
   __syncthreads();
 
-  const uint16_t* B = a.Bk + m.bk_off[j] + u * kDHead;                 // row k at B + k*width
-  uint16_t* out = a.mfold + (size_t)b * a.mfold_bstride + m.bk_off[j] + (size_t)u * r * kDHead;
-  // one item = (k-step, row tile, lane) = 8 consecutive k of one feature row, stored as one 16-byte word
-  const int lane = tid & 63;
-  const int rt = tid >> 6;
-  const int cp = 32 * rt + (lane & 31);         // feature c' of this A-operand row
+  // one item = (row tile rt, lane) = 8 consecutive k of feature row c' = 32*rt + lane%32
+  const int lane = tid & 63, rt = tid >> 6;
+  const int cp = 32 * rt + (lane & 31);
   const int f = cp & 63;
   const bool is_w = cp >= kHalf;
   const float qa = qr[f], qb = qr[f + kHalf];
-  for (int ks = slice; ks < nks; ks += kFoldSlices) {
-    const int k0 = 16 * ks + 8 * (lane >> 5);
-    uint16_t v[8];
+  const int k0 = 8 * (lane >> 5);
+  uint16_t v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint16_t* row = B + (size_t)(k0 + e) * width;
-      const float b1 = T::to_float(row[f]);
-      const float b2 = T::to_float(row[f + kHalf]);
-      const float val = is_w ? (qb * b1 - qa * b2) : (qa * b1 + qb * b2);
-      v[e] = F16::from_float(val);       // the score kernel always contracts in fp16
-    }
-    uint4v pk;
-    pk.x = v[0] | ((uint32_t)v[1] << 16);
-    pk.y = v[2] | ((uint32_t)v[3] << 16);
-    pk.z = v[4] | ((uint32_t)v[5] << 16);
-    pk.w = v[6] | ((uint32_t)v[7] << 16);
-    *reinterpret_cast<uint4v*>(out + ((size_t)ks * 256 + tid) * 8) = pk;
+  for (int e = 0; e < 8; ++e) {
+    const float b1 = T::to_float(Bs[k0 + e][f]);
+    const float b2 = T::to_float(Bs[k0 + e][f + kHalf]);
+    const float val = is_w ? (qb * b1 - qa * b2) : (qa * b1 + qb * b2);
+    v[e] = F16::from_float(val);       // the score kernel always contracts in fp16
   }
+  uint4v pk;
+  pk.x = v[0] | ((uint32_t)v[1] << 16);
+  pk.y = v[2] | ((uint32_t)v[3] << 16);
+  pk.z = v[4] | ((uint32_t)v[5] << 16);
+  pk.w = v[6] | ((uint32_t)v[7] << 16);
+  uint16_t* out = a.mfold + (size_t)b * a.mfold_bstride + m.bk_off[j] + (size_t)u * r * kDHead;
+  *reinterpret_cast<uint4v*>(out + ((size_t)ks * 256 + tid) * 8) = pk;
 }
 
 template __global__ void fold_kernel<F16>(FoldArgs);

@@ -257,7 +257,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   half8 W[NKS][RT];
   {
     const uint16_t* mf = a.mfold + (size_t)b * a.mfold_bstride + u.bk_off0 +
-                         ((size_t)g_rel * u.s + u_in_g) * kRank * kDHead;
+                         ((size_t)g_rel * u.s + u_in_g) * u.head_stride;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
         W[ks][rt] = *reinterpret_cast<const half8*>(mf + ((size_t)(ks * 4 + rt0 + rt) * 64 + lane) * 8);
   }
 
-  const int part_idx = RT == 2 ? (rt0 >> 1) : 0;
+  const int part_idx = u.part0 + (RT == 2 ? (rt0 >> 1) : 0);
   float* out_row = a.scores + ((size_t)part_idx * a.batch + b) * a.n_heads * (size_t)a.lpad + (size_t)hc * a.lpad;
 
   // MFMA phase of one tile: accumulators (features x tokens) and the tile's cos/sin weights

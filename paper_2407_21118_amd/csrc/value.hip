@@ -65,6 +65,39 @@ __global__ __launch_bounds__(256) void value_kernel(ValueArgs a) {
   const int v0 = m.v_off[j];
   const int rv = m.v_off[j + 1] - v0;
 
+  // ---- thread = (token in pass, 8-channel chunk) of the value-latent stream
+  const int lpt = rv >> 3;                       // 16-byte chunks per token row of this group
+  const int tpp = 256 / lpt;                     // tokens per pass
+  const int my_tok = tid / lpt, my_ch = tid - my_tok * lpt;
+  const bool worker = my_tok < tpp;
+  const size_t row0 = (size_t)b * a.max_seq + s0;
+  constexpr int U = 8;                           // loads in flight per thread
+  const unsigned row_bytes = I4 ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
+  const unsigned char* hv_base = (const unsigned char*)a.hv +
+                                 (I4 ? (row0 * a.row_elems + v0 + my_ch * 8) / 2 : (row0 * a.row_elems + v0 + my_ch * 8) * 2);
+  const size_t sb_base = row0 * a.n_blocks_q + (v0 + my_ch * 8) / a.quant_block;     // int4: scale / zero index of row 0
+
+  // raw latents (and int4 scale/zero) of U tokens: my_tok + tb, my_tok + tb + tpp, ...
+  struct Batch {
+    uint4v h[U];
+  };
+  auto load_batch = [&](Batch& bt, int tb) {
+#pragma unroll
+    for (int x = 0; x < U; ++x) {
+      const int tc = min(tb + x * tpp, ntok - 1);          // clamped: the weight of an out-of-range token is zero
+      if (!I4) {
+        bt.h[x] = *reinterpret_cast<const uint4v*>(hv_base + (size_t)tc * row_bytes);
+      } else {
+        bt.h[x].x = *reinterpret_cast<const uint32_t*>(hv_base + (size_t)tc * row_bytes);
+        const size_t sb = sb_base + (size_t)tc * a.n_blocks_q;
+        bt.h[x].y = (uint32_t)a.hv_scale[sb] | ((uint32_t)a.hv_zero[sb] << 16);
+      }
+    }
+  };
+  // the first batch goes out before the softmax prologue: HBM latency overlaps it
+  Batch cur;
+  if (worker) load_batch(cur, my_tok);
+
   // ---- scores of the split -> LDS, running max per head
   float mx[HB], sum[HB];
 #pragma unroll
@@ -74,10 +107,10 @@ __global__ __launch_bounds__(256) void value_kernel(ValueArgs a) {
     if (hh < nh) {
       const int h = h0 + hh;
       const float* s0p = a.scores + ((size_t)b * m.n_heads + h) * a.lpad + s0;
-      const bool two = (a.parts_mask_lo[h >> 5] >> (h & 31)) & 1u;
+      const int np = a.n_parts[h];
       for (int t = tid; t < ntok; t += 256) {
         float s = s0p[t];
-        if (two) s += s0p[a.part_stride + t];
+        for (int pl = 1; pl < np; ++pl) s += s0p[pl * a.part_stride + t];
         sh[t * HB + hh] = s;
         mx[hh] = fmaxf(mx[hh], s);
       }
@@ -94,56 +127,47 @@ __global__ __launch_bounds__(256) void value_kernel(ValueArgs a) {
   }
   block_reduce<HB>(sum, red, false);     // its barriers also publish the probabilities
 
-  // ---- stream the value latents: thread = (token in pass, 8-channel chunk)
-  const int lpt = rv >> 3;                       // 16-byte chunks per token row of this group
-  const int tpp = 256 / lpt;                     // tokens per pass
-  const int my_tok = tid / lpt, my_ch = tid - my_tok * lpt;
-  const bool worker = my_tok < tpp;
-
+  // ---- stream the value latents
   float acc[HB][8];
 #pragma unroll
   for (int hh = 0; hh < HB; ++hh)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
 
-  const size_t row0 = (size_t)b * a.max_seq + s0;
-  constexpr int U = 4;
   if (worker) {
     for (int tb = my_tok; tb < ntok; tb += tpp * U) {
-      float hv[U][8];
-      float pw[U][HB];
+      Batch nxt;
+      load_batch(nxt, tb + tpp * U);               // next batch in flight while this one is consumed
 #pragma unroll
       for (int x = 0; x < U; ++x) {
         const int t = tb + x * tpp;
         const bool ok = t < ntok;
         const int tc = ok ? t : ntok - 1;
-        const size_t e0 = (row0 + tc) * a.row_elems + v0 + my_ch * 8;
+        float hvf[8];
+        float pw[HB];
         if (!I4) {
-          const uint4v raw = *reinterpret_cast<const uint4v*>((const uint16_t*)a.hv + e0);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            hv[x][2 * e] = T::to_float((uint16_t)(raw[e] & 0xffffu));
-            hv[x][2 * e + 1] = T::to_float((uint16_t)(raw[e] >> 16));
+            hvf[2 * e] = T::to_float((uint16_t)(cur.h[x][e] & 0xffffu));
+            hvf[2 * e + 1] = T::to_float((uint16_t)(cur.h[x][e] >> 16));
           }
 #pragma unroll
-          for (int hh = 0; hh < HB; ++hh) pw[x][hh] = ok ? sh[tc * HB + hh] : 0.f;
+          for (int hh = 0; hh < HB; ++hh) pw[hh] = ok ? sh[tc * HB + hh] : 0.f;
         } else {
-          const uint32_t codes = *reinterpret_cast<const uint32_t*>((const uint8_t*)a.hv + e0 / 2);
-          const size_t sb = (row0 + tc) * a.n_blocks_q + (v0 + my_ch * 8) / a.quant_block;
-          const float s = F16::to_float(a.hv_scale[sb]);
-          const float z = F16::to_float(a.hv_zero[sb]);
+          const uint32_t codes = cur.h[x].x;
+          const float s = F16::to_float((uint16_t)(cur.h[x].y & 0xffffu));
+          const float z = F16::to_float((uint16_t)(cur.h[x].y >> 16));
 #pragma unroll
-          for (int e = 0; e < 8; ++e) hv[x][e] = (float)((codes >> (4 * e)) & 15u) - z;
+          for (int e = 0; e < 8; ++e) hvf[e] = (float)((codes >> (4 * e)) & 15u) - z;
 #pragma unroll
-          for (int hh = 0; hh < HB; ++hh) pw[x][hh] = ok ? sh[tc * HB + hh] * s : 0.f;
+          for (int hh = 0; hh < HB; ++hh) pw[hh] = ok ? sh[tc * HB + hh] * s : 0.f;
         }
-      }
-#pragma unroll
-      for (int x = 0; x < U; ++x)
 #pragma unroll
         for (int hh = 0; hh < HB; ++hh)
 #pragma unroll
-          for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pw[x][hh], hv[x][e], acc[hh][e]);
+          for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pw[hh], hvf[e], acc[hh][e]);
+      }
+      cur = nxt;
     }
   }
 
@@ -175,8 +199,11 @@ __global__ __launch_bounds__(256) void value_kernel(ValueArgs a) {
   }
 }
 
-// grid (n_heads, batch), 256 threads.  Small and latency-bound: every phase
-// spreads its loads over all 256 threads and keeps them independent.
+// grid (n_heads * 4, batch), 256 threads: a workgroup produces 32 of the 128
+// output columns of one head (the merge of the splits is repeated by the four
+// workgroups of a head; it is small and this keeps the kernel to one launch).
+// Small and latency-bound: every phase spreads its loads over all 256 threads
+// and keeps them independent.
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   __shared__ float w[kMaxSplits];
@@ -185,7 +212,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   __shared__ float red[4];
   const int tid = threadIdx.x;
   const Meta& m = a.meta;
-  const int h = blockIdx.x, b = blockIdx.y;
+  const int h = blockIdx.x >> 2, quarter = blockIdx.x & 3, b = blockIdx.y;
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
   const int nsp = (L + a.split_tokens - 1) / a.split_tokens;
   const int j = m.group_of_head[h];
@@ -238,12 +265,12 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
     __syncthreads();
   }
 
-  // ---- out = o_lat . B_v[:, head columns] / l: thread = (k part kp of 8, column quad cq of 32), 8-byte loads
-  const int kp = tid >> 5, cq = tid & 31;
-  const uint16_t* Bv = a.Bv + m.bv_off[j] + u * kDHead + cq * 4;
-  const int k_per = rv >> 3;                       // rank is a multiple of 32
+  // ---- out = o_lat . B_v[:, 32 of the head's columns] / l: thread = (k part kp of 32, column quad cq of 8), 8-byte loads
+  const int kp = tid >> 3, cq = tid & 7;
+  const uint16_t* Bv = a.Bv + m.bv_off[j] + u * kDHead + quarter * 32 + cq * 4;
+  const int k_per = rv >> 5;                       // rank is a multiple of 32
   float4v o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
+#pragma unroll 4
   for (int kk = 0; kk < k_per; ++kk) {
     const int k = kp * k_per + kk;
     const uint2v raw = *reinterpret_cast<const uint2v*>(Bv + (size_t)k * width);
@@ -253,14 +280,14 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
     o.z = fmaf(ol, T::to_float((uint16_t)(raw.y & 0xffffu)), o.z);
     o.w = fmaf(ol, T::to_float((uint16_t)(raw.y >> 16)), o.w);
   }
-  *reinterpret_cast<float4v*>(part + (kp * 32 + cq) * 4) = o;
+  *reinterpret_cast<float4v*>(part + (kp * 8 + cq) * 4) = o;
   __syncthreads();
-  if (tid < kDHead) {
+  if (tid < 32) {
     const int c4 = tid >> 2, e = tid & 3;
     float s = 0.f;
 #pragma unroll
-    for (int g = 0; g < 8; ++g) s += part[(g * 32 + c4) * 4 + e];
-    a.out[((size_t)b * m.n_heads + h) * kDHead + tid] = s / sum[0];
+    for (int g = 0; g < 32; ++g) s += part[(g * 8 + c4) * 4 + e];
+    a.out[((size_t)b * m.n_heads + h) * kDHead + quarter * 32 + tid] = s / sum[0];
   }
 }
 

@@ -116,3 +116,50 @@ def test_argument_errors_leave_output_untouched():
     assert e.value.status == -3
     torch.cuda.synchronize()
     assert (out == 3.0).all()
+
+
+def test_encode_kv_matches_oracle_and_single_side_calls():
+    say("[encode_kv]")
+    layer = synth.config_layer("3")
+    rng = np.random.default_rng(12)
+    d = layer.n_heads * layer.d_head
+    Ak = synth.round_to(rng.standard_normal((d, layer.R_k)) / 64.0, "f16")
+    Av = synth.round_to(rng.standard_normal((d, layer.R_v)) / 64.0, "f16")
+    x = synth.round_to(rng.standard_normal((4, d)), "f16")
+    desc = make_desc(layer, "f16")
+    hk = torch.zeros((9, layer.R_k), dtype=torch.float16, device="cuda")
+    hv = torch.zeros((9, layer.R_v), dtype=torch.float16, device="cuda")
+    dst = torch.tensor([8, 0, 3, 5], dtype=torch.int32, device="cuda")
+    P.palu_encode_kv(desc, to_dev(x, "f16"), to_dev(Ak, "f16"), to_dev(Av, "f16"), hk, layer.R_k, hv, layer.R_v, dst)
+    hk1 = torch.zeros_like(hk)
+    hv1 = torch.zeros_like(hv)
+    P.palu_encode(desc, 0, to_dev(x, "f16"), to_dev(Ak, "f16"), hk1, layer.R_k, dst)
+    P.palu_encode(desc, 1, to_dev(x, "f16"), to_dev(Av, "f16"), hv1, layer.R_v, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(hk, hk1) and torch.equal(hv, hv1)
+    for got, A in ((hk, Ak), (hv, Av)):
+        ref = O.encode(x, A)
+        g = got.float().cpu().numpy()
+        for t, r in enumerate([8, 0, 3, 5]):
+            assert np.abs(g[r] - ref[t]).max() <= 2.0 ** -11 * 1.01 * np.abs(ref[t]).max() + 1e-6
+
+
+def test_quantizer_scatter_rows():
+    layer = synth.config_layer("4")
+    rng = np.random.default_rng(13)
+    h = synth.round_to(rng.standard_normal((3, layer.R_v)) * 3.0, "f16")
+    desc = make_desc(layer, "f16")
+    rows = 7
+    codes = torch.zeros((rows, layer.R_v // 2), dtype=torch.uint8, device="cuda")
+    scale = torch.zeros((rows, layer.R_v // 128), dtype=torch.float16, device="cuda")
+    zero = torch.zeros_like(scale)
+    dst = torch.tensor([6, 2, 4], dtype=torch.int32, device="cuda")
+    P.palu_quant_latent(desc, 1, to_dev(h, "f16"), layer.R_v, 3, codes, scale, zero, dst)
+    torch.cuda.synchronize()
+    pk, s, z = O.quant_latent(h)
+    c = codes.cpu().numpy()
+    for t, r in enumerate([6, 2, 4]):
+        np.testing.assert_array_equal(c[r], pk[t])
+        np.testing.assert_array_equal(scale[r].cpu().view(torch.int16).numpy(), s[t].view(np.int16))
+        np.testing.assert_array_equal(zero[r].cpu().view(torch.int16).numpy(), z[t].view(np.int16))
+    assert not c[[0, 1, 3, 5]].any()

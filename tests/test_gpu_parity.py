@@ -101,3 +101,24 @@ def test_peaked_softmax_and_large_logits():
     case.q = synth.round_to(case.q * 12.0, "f16")
     case.name = "peaked"
     check(case, TOL_FP * 12.0)
+
+
+def test_config5b_joint_group_reduced_length():
+    """J-LRD: one group of all 32 heads, rank 2048 (contracted in rank slices)."""
+    layer = synth.config_layer("5b")
+    case = synth.make_case_svd(layer, 1, 200, seed=0, d_model=2048)
+    case.name = "cfg5b-reduced"
+    check(case, TOL_FP)
+
+
+def test_mixed_group_sizes_and_ranks():
+    """Groups of 1, 2, 3 and 6 heads with ranks 32 .. 512 in one layer."""
+    k_ranks = [32, 64, 128, 96, 128, 384, 512]          # each at most the group's width (heads * 128)
+    v_ranks = [64, 32, 128, 256, 96, 128, 512]
+    layer = synth.Layer(16, 128, [0, 1, 2, 4, 6, 7, 10, 16], [0] + list(np.cumsum(k_ranks)),
+                        [0] + list(np.cumsum(v_ranks)))
+    case = synth.make_case_orthonormal(layer, 2, 150, seed=8)
+    case.seq_lens = np.array([150, 33], np.int32)
+    case.q_pos = np.array([149, 32], np.int32)
+    case.name = "mixed"
+    check(case, TOL_FP)
