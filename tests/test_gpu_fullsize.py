@@ -1,0 +1,127 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+times: the HIP path runs the whole configuration on the GPU; the CPU oracle
+recomputes sampled (sequence, group, heads) slices of it from the same bits."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_21118_amd as P
+from oracle import palu_oracle as O
+from workloads import device as wd
+from workloads import synth
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import TOL_FP, TOL_I4, make_desc, rel_err, say  # noqa: E402
+
+
+def group_slice(layer, j, heads):
+    """Layer holding only `heads` (indices inside group j) of group j."""
+    rk = layer.k_rank_off[j + 1] - layer.k_rank_off[j]
+    rv = layer.v_rank_off[j + 1] - layer.v_rank_off[j]
+    return synth.Layer(len(heads), layer.d_head, [0, len(heads)], [0, rk], [0, rv], layer.rope_theta)
+
+
+def b_slice(flat, layer, which, j, heads):
+    """Columns of group j's reconstruction matrix that belong to `heads`."""
+    off = layer.k_rank_off if which == "k" else layer.v_rank_off
+    start = sum((off[i + 1] - off[i]) * layer.group_size(i) * layer.d_head for i in range(j))
+    r, w = off[j + 1] - off[j], layer.group_size(j) * layer.d_head
+    Bj = flat[start:start + r * w].reshape(r, w)
+    cols = np.concatenate([np.arange(u * layer.d_head, (u + 1) * layer.d_head) for u in heads])
+    return np.ascontiguousarray(Bj[:, cols]).reshape(-1)
+
+
+def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP):
+    case = wd.make_device_case(cfg, seed=0, n_sets=1)
+    layer, B, L = case.layer, case.batch, case.seq
+    say(f"[full] cfg {cfg} B={B} L={L} groups={layer.n_groups} R_k={layer.R_k} k_i4={k_i4} v_i4={v_i4}")
+    desc = make_desc(layer, "f16", k_i4, v_i4)
+    table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, L)
+    hk, hv, kw = case.Hk[0], case.Hv[0], {}
+    nbk, nbv = layer.R_k // 128, layer.R_v // 128
+    quant = {}
+    for side, flag, H, R, nb in (("k", k_i4, case.Hk[0], layer.R_k, nbk), ("v", v_i4, case.Hv[0], layer.R_v, nbv)):
+        if not flag:
+            continue
+        codes = torch.empty((B, L, R // 2), dtype=torch.uint8, device="cuda")
+        sc = torch.empty((B, L, nb), dtype=torch.float16, device="cuda")
+        zp = torch.empty_like(sc)
+        P.palu_quant_latent(desc, 0 if side == "k" else 1, H, R, B * L, codes, sc, zp)
+        quant[side] = (codes, sc, zp)
+        if side == "k":
+            hk, kw["hk_scale"], kw["hk_zero"] = codes, sc, zp
+        else:
+            hv, kw["hv_scale"], kw["hv_zero"] = codes, sc, zp
+    out = P.palu_attn_decode(desc, B, L, L, case.q, case.q_pos, hk, hv, case.Bk, case.Bv, table, L, **kw)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    Bk, Bv = case.Bk.float().cpu().numpy(), case.Bv.float().cpu().numpy()
+    worst = 0.0
+    for (b, j, heads) in samples:
+        sub = group_slice(layer, j, heads)
+        kc = slice(layer.k_rank_off[j], layer.k_rank_off[j + 1])
+        vc = slice(layer.v_rank_off[j], layer.v_rank_off[j + 1])
+        Hk = case.Hk[0][b, :, kc].float().cpu().numpy()[None]
+        Hv = case.Hv[0][b, :, vc].float().cpu().numpy()[None]
+        for side, H, cols in (("k", Hk, kc), ("v", Hv, vc)):
+            if side not in quant:
+                continue
+            # the oracle quantizes the same rows itself; the codes the GPU wrote must equal its codes
+            pk, s, z = O.quant_latent(H[0])
+            codes, sc, zp = quant[side]
+            np.testing.assert_array_equal(codes[b, :, cols.start // 2:cols.stop // 2].cpu().numpy(), pk)
+            np.testing.assert_array_equal(sc[b, :, cols.start // 128:cols.stop // 128].cpu().view(torch.int16).numpy(),
+                                          s.view(np.int16))
+            np.testing.assert_array_equal(zp[b, :, cols.start // 128:cols.stop // 128].cpu().view(torch.int16).numpy(),
+                                          z.view(np.int16))
+            deq = O.dequant_latent(pk, s, z)[None]
+            if side == "k":
+                Hk = deq
+            else:
+                Hv = deq
+        h_abs = [layer.group_head_off[j] + u for u in heads]
+        q = case.q[b, h_abs].float().cpu().numpy()[None]
+        ref = O.attn_decode(q, [int(case.q_pos[b])], Hk, Hv, b_slice(Bk, layer, "k", j, heads),
+                            b_slice(Bv, layer, "v", j, heads), sub.group_head_off, sub.k_rank_off, sub.v_rank_off,
+                            layer.d_head, layer.rope_theta)
+        whole, rows = rel_err(got[b, h_abs][None], ref)
+        say(f"       sample b={b} group={j} heads={heads}: rel err {whole:.3e} (rows {rows:.3e})")
+        worst = max(worst, whole, rows)
+    assert worst <= tol
+
+
+def test_full_config1():
+    run_full("1", [(0, 0, [0, 1, 2, 3]), (0, 1, [0, 1, 2, 3])])
+
+
+def test_full_config2_16k():
+    run_full("2", [(0, 0, [0, 1, 2, 3]), (0, 5, [1, 2]), (0, 7, [3])])
+
+
+def test_full_config2_64k():
+    run_full("2-64k", [(0, 3, [0, 2])])
+
+
+def test_full_config3_ragged():
+    layer = synth.config_layer("3")
+    ranks = np.diff(layer.k_rank_off)
+    run_full("3", [(0, int(np.argmax(ranks)), [0, 3]), (3, int(np.argmin(ranks)), [1]), (2, 4, [2])])
+
+
+def test_full_config4_int4_both():
+    run_full("4", [(0, 0, [0, 3]), (15, 6, [2])], k_i4=True, v_i4=True, tol=TOL_I4)
+
+
+def test_full_config4_int4_values_only():
+    run_full("4", [(7, 2, [1])], v_i4=True, tol=TOL_I4)
+
+
+def test_full_config5a_per_head():
+    run_full("5a", [(0, 0, [0]), (7, 31, [0]), (3, 17, [0])])
+
+
+def test_full_config5b_joint():
+    run_full("5b", [(0, 0, [0, 31]), (5, 0, [13])])
