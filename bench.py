@@ -251,7 +251,7 @@ def main() -> int:
                       f"(no encode); measured {cpu_s:.2f} s, scaled x{scale:g}",
             "affinity_cores": len(os.sched_getaffinity(0)),
         }
-    print(json.dumps(result), flush=True)
+    print(json.dumps(result, default=lambda o: o.item() if hasattr(o, "item") else str(o)), flush=True)
     return 0
 
 

@@ -5,6 +5,7 @@
 #include "rope_fold.hip"
 #include "score.hip"
 #include "value.hip"
+#include "pv.hip"
 
 #include <atomic>
 #include <cmath>
@@ -22,6 +23,7 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score workgroup (ranks <= 256)
 std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
 std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
+std::atomic<int> g_opt_value_kernel{0};       // 0: matrix-core kernel where it applies; 1: vector-ALU kernel always
 
 int device_cu_count() {
   static std::atomic<int> cached[64];
@@ -227,7 +229,69 @@ int plan_value(const Meta& m, ValuePlan* p) {
   return PALU_OK;
 }
 
+// Units of the matrix-core value kernel: at most 256 latent columns and 32 heads each.
+// Small adjacent groups are merged (up to 4 heads, 256 columns) so that a
+// wavefront's 64 lanes all stream; wide latents are cut into column slices.
+enum { kNumPvCls = 6 };
+struct PvPlan {
+  PvUnits units[kNumPvCls];      // class = 2 * (0: <=4 heads, 1: <=16, 2: <=32) + (columns > 128)
+  int total_units;
+  bool aligned128;               // every unit starts on a 128-column boundary
+};
+
+int plan_pv(const Meta& m, PvPlan* p) {
+  std::memset(p, 0, sizeof(*p));
+  p->aligned128 = true;
+  auto add = [&](int h0, int nh, int c0, int ncols, int write_ml) -> int {
+    const int hs = nh <= 4 ? 0 : (nh <= 16 ? 1 : 2);
+    PvUnits& u = p->units[2 * hs + (ncols > 128 ? 1 : 0)];
+    if (u.n_units >= kMaxPvUnits) return PALU_ERR_UNSUPPORTED;
+    PvUnit& x = u.u[u.n_units++];
+    x.h0 = (uint16_t)h0; x.c0 = c0; x.ncols = (uint16_t)ncols; x.nh = (uint8_t)nh; x.write_ml = (uint8_t)write_ml;
+    ++p->total_units;
+    if (c0 % 128) p->aligned128 = false;
+    return PALU_OK;
+  };
+  int st;
+  for (int j = 0; j < m.n_groups;) {
+    const int s = m.head_off[j + 1] - m.head_off[j];
+    const int rv = m.v_off[j + 1] - m.v_off[j];
+    if (s <= 4 && rv <= 256) {
+      int heads = s, cols = rv, j1 = j + 1;
+      while (j1 < m.n_groups && heads + (m.head_off[j1 + 1] - m.head_off[j1]) <= 4 &&
+             cols + (m.v_off[j1 + 1] - m.v_off[j1]) <= 256) {
+        heads += m.head_off[j1 + 1] - m.head_off[j1];
+        cols += m.v_off[j1 + 1] - m.v_off[j1];
+        ++j1;
+      }
+      if ((st = add(m.head_off[j], heads, m.v_off[j], cols, 1)) != PALU_OK) return st;
+      j = j1;
+      continue;
+    }
+    const int hb = s <= 4 ? 4 : (s <= 16 ? 16 : 32);
+    const int cw = hb == 32 ? 128 : 256;       // two 16-row tiles of accumulators leave room for one column block
+    for (int u0 = 0; u0 < s; u0 += hb)
+      for (int cs = 0; cs < rv; cs += cw)
+        if ((st = add(m.head_off[j] + u0, std::min(hb, s - u0), m.v_off[j] + cs, std::min(cw, rv - cs), cs == 0)) != PALU_OK)
+          return st;
+    ++j;
+  }
+  return PALU_OK;
+}
+
 // Tokens per value split and number of splits for a given attended length.
+// Matrix-core kernel: a split is one wavefront's share; aim at four wavefronts
+// per compute unit, splits of 64 to 512 tokens (more where the merge kernel's
+// split limit asks for it).
+constexpr int kPvSplitMin = 64, kPvSplitMax = 512;
+void pv_split_geometry(int total_units, int batch, int seq_len, int* split_tokens, int* n_split) {
+  const long long items = std::max(1, total_units * batch);
+  long long st = ceil_div((int)std::min<long long>(items * seq_len / (4LL * device_cu_count()) + 1, 1 << 30), 32) * 32LL;
+  st = std::min<long long>(std::max<long long>(st, kPvSplitMin), kPvSplitMax);
+  st = std::max<long long>(st, ceil_div(ceil_div(seq_len, kMaxSplits), 32) * 32LL);
+  *split_tokens = (int)st;
+  *n_split = ceil_div(seq_len, (int)st);
+}
 void split_geometry(int total_units, int batch, int seq_len, int* split_tokens, int* n_split) {
   const int target = std::max(1, ceil_div(4 * device_cu_count(), std::max(1, total_units * batch)));
   int st = ceil_div(ceil_div(seq_len, target), 32) * 32;
@@ -235,9 +299,13 @@ void split_geometry(int total_units, int batch, int seq_len, int* split_tokens, 
   *split_tokens = st;
   *n_split = ceil_div(seq_len, st);
 }
-int split_bound(int total_units, int batch, int max_seq) {
+// Upper bound of the number of splits of any attended length up to max_seq, for either kernel.
+int split_bound(int total_units, int pv_units, int batch, int max_seq) {
   const int target = std::max(1, ceil_div(4 * device_cu_count(), std::max(1, total_units * batch)));
-  return std::max(target, ceil_div(max_seq, kSplitMax)) + 1;
+  const int pv_target = ceil_div(4 * device_cu_count(), std::max(1, pv_units * batch));
+  int cap = std::max(std::max(target, ceil_div(max_seq, kSplitMax)), std::max(pv_target, ceil_div(max_seq, kPvSplitMax)));
+  if (g_opt_value_split > 0) cap = std::max(cap, ceil_div(max_seq, (int)g_opt_value_split));
+  return cap + 2;
 }
 
 struct Workspace {
@@ -335,6 +403,22 @@ ValueFn value_fn(int act, bool i4, int cls) {
   }
 }
 
+using PvFn = void (*)(PvArgs);
+template <typename T, bool I4>
+PvFn pv_fn_t(int cls) {
+  switch (cls) {
+    case 0: return pv_kernel<T, 2, 1, I4>;
+    case 1: return pv_kernel<T, 2, 2, I4>;
+    case 2: return pv_kernel<T, 8, 1, I4>;
+    case 3: return pv_kernel<T, 8, 2, I4>;
+    default: return pv_kernel<T, 16, 1, I4>;
+  }
+}
+PvFn pv_fn(int act, bool i4, int cls) {
+  if (i4) return pv_fn_t<F16, true>(cls);
+  return act == PALU_F16 ? pv_fn_t<F16, false>(cls) : pv_fn_t<BF16, false>(cls);
+}
+
 inline int launch_ok() { return hipGetLastError() == hipSuccess ? PALU_OK : PALU_ERR_HIP; }
 
 }  // namespace
@@ -364,6 +448,9 @@ int palu_set_option(const char* name, int value) {
   } else if (!std::strcmp(name, "value_split_tokens")) {
     if (value != 0 && (value % 32 != 0 || value > kSplitMax)) return PALU_ERR_INVALID_ARG;
     g_opt_value_split = value;
+  } else if (!std::strcmp(name, "value_kernel")) {
+    if (value > 1) return PALU_ERR_INVALID_ARG;
+    g_opt_value_kernel = value;
   } else {
     return PALU_ERR_INVALID_ARG;
   }
@@ -512,8 +599,10 @@ int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch,
   ValuePlan vp;
   if ((st = plan_score(m, &sp)) != PALU_OK) return st;
   if ((st = plan_value(m, &vp)) != PALU_OK) return st;
+  PvPlan pp;
+  if (plan_pv(m, &pp) != PALU_OK) pp.total_units = vp.total_units;
   Workspace w;
-  carve(m, batch, max_seq, split_bound(vp.total_units, batch, max_seq), 2 * sp.max_slices, &w);
+  carve(m, batch, max_seq, split_bound(vp.total_units, pp.total_units, batch, max_seq), 2 * sp.max_slices, &w);
   *out_bytes = w.total;
   return PALU_OK;
 }
@@ -558,14 +647,21 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
   ValuePlan vp;
   if ((st = plan_score(m, &sp)) != PALU_OK) return st;
   if ((st = plan_value(m, &vp)) != PALU_OK) return st;
+  PvPlan pp;
+  const bool pv_planned = plan_pv(m, &pp) == PALU_OK;     // too many units: the vector-ALU kernel takes the layer
+  if (!pv_planned) pp.total_units = vp.total_units;
+  const int quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
+  // the matrix-core value kernel folds int4 scales per 128-column block of a unit
+  const bool use_pv = pv_planned && g_opt_value_kernel != 1 && (!v_i4 || (quant_block == 128 && pp.aligned128));
   int split_tokens, n_split;
-  split_geometry(vp.total_units, batch, seq_len, &split_tokens, &n_split);
+  if (use_pv) pv_split_geometry(pp.total_units, batch, seq_len, &split_tokens, &n_split);
+  else split_geometry(vp.total_units, batch, seq_len, &split_tokens, &n_split);
   if (g_opt_value_split > 0) {
     split_tokens = g_opt_value_split;
     n_split = ceil_div(seq_len, split_tokens);
   }
   if (n_split > kMaxSplits) return PALU_ERR_UNSUPPORTED;
-  const int n_split_cap = split_bound(vp.total_units, batch, max_seq);
+  const int n_split_cap = split_bound(vp.total_units, pp.total_units, batch, max_seq);
   Workspace w;
   carve(m, batch, max_seq, n_split_cap, 2 * sp.max_slices, &w);
   if (n_split > n_split_cap) return PALU_ERR_INVALID_ARG;
@@ -677,7 +773,55 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
   }
 
   // 3. softmax partials and P.H_v per split
-  {
+  uint8_t n_parts[PALU_MAX_HEADS];
+  std::memset(n_parts, 0, sizeof(n_parts));
+  int max_parts = 0;
+  for (int h = 0; h < m.n_heads; ++h) {      // half-head wavefronts write two planes per rank slice
+    n_parts[h] = (uint8_t)((waves8 || sp.half_heads[h]) ? 2 * sp.slices[h] : sp.slices[h]);
+    max_parts = std::max(max_parts, (int)n_parts[h]);
+  }
+  if ((st = mark(2)) != PALU_OK) return st;
+  if (use_pv) {
+    if (max_parts > 2) {                     // ranks contracted in slices: fold those heads' planes into plane 0
+      PlaneSumArgs ps;
+      ps.scores = reinterpret_cast<float*>(ws + w.scores);
+      ps.part_stride = w.part_stride;
+      ps.lpad = w.lpad;
+      ps.seq_len = seq_len;
+      ps.n_heads = m.n_heads;
+      std::memcpy(ps.n_parts, n_parts, sizeof(n_parts));
+      hipLaunchKernelGGL(plane_sum_kernel, dim3((unsigned)ceil_div(seq_len, 256), (unsigned)m.n_heads, (unsigned)batch),
+                         dim3(256), 0, s, ps);
+      if ((st = launch_ok()) != PALU_OK) return st;
+    }
+    PvArgs a;
+    a.hv = hv;
+    a.hv_scale = static_cast<const uint16_t*>(hv_scale);
+    a.hv_zero = static_cast<const uint16_t*>(hv_zero);
+    a.scores = reinterpret_cast<const float*>(ws + w.scores);
+    a.seq_lens = seq_lens;
+    a.o_part = reinterpret_cast<float*>(ws + w.o_part);
+    a.ml_part = reinterpret_cast<float*>(ws + w.ml_part);
+    a.row_elems = Rv;
+    a.max_seq = max_seq;
+    a.part_stride = w.part_stride;
+    a.seq_len = seq_len;
+    a.lpad = w.lpad;
+    a.batch = batch;
+    a.split_tokens = split_tokens;
+    a.n_split = n_split;
+    a.o_stride = w.o_stride;
+    a.n_blocks_q = Rv / quant_block;
+    for (int h = 0; h < PALU_MAX_HEADS; ++h) a.n_parts[h] = (uint8_t)(n_parts[h] > 2 ? 1 : n_parts[h]);
+    a.meta = m;
+    for (int cls = 0; cls < kNumPvCls; ++cls) {
+      if (pp.units[cls].n_units == 0) continue;
+      a.units = pp.units[cls];
+      const unsigned grid = (unsigned)(a.units.n_units * ceil_div(n_split, 4) * batch);
+      hipLaunchKernelGGL(pv_fn(act, v_i4, cls), dim3(grid), dim3(256), 0, s, a);
+      if ((st = launch_ok()) != PALU_OK) return st;
+    }
+  } else {
     ValueArgs a;
     a.hv = hv;
     a.hv_scale = static_cast<const uint16_t*>(hv_scale);
@@ -695,13 +839,11 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.split_tokens = split_tokens;
     a.n_split = n_split;
     a.o_stride = w.o_stride;
-    a.quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
+    a.quant_block = quant_block;
     a.n_blocks_q = Rv / a.quant_block;
-    std::memset(a.n_parts, 0, sizeof(a.n_parts));
-    for (int h = 0; h < m.n_heads; ++h)      // half-head wavefronts write two planes per rank slice
-      a.n_parts[h] = (uint8_t)((waves8 || sp.half_heads[h]) ? 2 * sp.slices[h] : sp.slices[h]);
+    std::memcpy(a.n_parts, n_parts, sizeof(n_parts));
     a.meta = m;
-    if ((st = mark(2)) != PALU_OK) return st;
+    if (split_tokens > kSplitMax) return PALU_ERR_UNSUPPORTED;
     for (int cls = 0; cls < kNumValCls; ++cls) {
       if (vp.units[cls].n_units == 0) continue;
       a.units = vp.units[cls];

@@ -1,0 +1,420 @@
+// Softmax partials and the value contraction in latent space on the matrix cores
+// (Eq. 4: softmax(q K^T) (H_v B_v) evaluated as (p H_v) B_v; Sec. 3.1.1):
+//   per (sequence, split of the sequence, unit of heads x latent columns)
+//     p_t = exp2(score_t - m),  l = sum_t p_t,  o[c] = sum_t p_t H_v[t, c].
+//
+// One wavefront owns one split and shares nothing with the others: no workgroup
+// barrier anywhere.  It walks its tokens in sets of 32 with an online softmax
+// (running maximum m, accumulators rescaled when m grows) and contracts each
+// set with v_mfma_f32_16x16x32_f16: A = probabilities (rows = heads, k = tokens),
+// B = latents (k = tokens, columns = latent channels).  The cache is token-major,
+// so a 16-byte load brings 8 channels of one token, while the matrix cores want
+// 8 tokens of one channel per lane: each lane loads the same 8-channel chunk of
+// 8 consecutive tokens and transposes the 8x8 block in registers with byte
+// permutes (one per operand register); channel e of every chunk then forms the
+// B operand of the e-th of 8 accumulator sets.  The vector ALU only does the
+// softmax (a few operations per token and head) and the transposes, so the
+// kernel stays bound by the latent stream for every head-group size, including
+// one latent shared by all 32 heads.
+//
+// 4-bit latents: codes are expanded to exact fp16 integers while transposing;
+// the per-(token, 128-channel block) scale is folded into the probabilities
+// (one probability tile per block) and the zero-points into one scalar per
+// (head, block): sum_t p s (c - z) = sum_t (p s) c - sum_t (p s) z.
+
+#include "palu_dev.h"
+
+namespace palu {
+
+struct PvUnit {
+  int32_t c0;         // first column of the value-latent row
+  uint16_t h0;        // first head
+  uint16_t ncols;     // columns (multiple of 32, at most 128 * NG)
+  uint8_t nh;         // heads (at most 32); a head only keeps the columns of its own group
+  uint8_t write_ml;   // this unit stores the (max, sum) pair of its heads
+};
+constexpr int kMaxPvUnits = 128;
+struct PvUnits {
+  int n_units;
+  PvUnit u[kMaxPvUnits];
+};
+
+struct PvArgs {
+  const void* hv;
+  const uint16_t* hv_scale;
+  const uint16_t* hv_zero;
+  const float* scores;       // [parts][batch][n_heads][lpad]; planes 0 and 1 are read
+  const int32_t* seq_lens;
+  float* o_part;             // [batch][n_split][o_stride]
+  float* ml_part;            // [batch][n_split][n_heads][2]
+  long long row_elems;       // R_v
+  long long max_seq;
+  long long part_stride;
+  int seq_len;
+  int lpad;
+  int batch;
+  int split_tokens;          // tokens per wavefront (multiple of 32)
+  int n_split;
+  int o_stride;
+  int n_blocks_q;
+  uint8_t n_parts[PALU_MAX_HEADS];   // 1 or 2 score planes per head
+  Meta meta;
+  PvUnits units;
+};
+
+struct PlaneSumArgs {
+  float* scores;
+  long long part_stride;
+  int lpad;
+  int seq_len;
+  int n_heads;
+  uint8_t n_parts[PALU_MAX_HEADS];
+};
+
+// scores[0] += scores[1] + ... + scores[n_parts-1] for heads with more than two
+// partial planes (ranks contracted in slices); the value kernel then reads one.
+__global__ __launch_bounds__(256) void plane_sum_kernel(PlaneSumArgs a) {
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int np = a.n_parts[h];
+  if (np <= 2) return;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= a.seq_len) return;
+  float* p = a.scores + ((size_t)b * a.n_heads + h) * a.lpad + t;
+  float s = p[0];
+  for (int pl = 1; pl < np; ++pl) s += p[(size_t)pl * a.part_stride];
+  p[0] = s;
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+// lane ^ 16 inside each half of the wavefront
+__device__ __forceinline__ float swap16(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
+}
+// reductions over the 32 lanes of a wavefront half; the result is in all 32 lanes
+__device__ __forceinline__ float half_wave_max(float v) {
+  v = fmaxf(v, dpp_move<0xB1>(v));     // quad_perm [1,0,3,2]
+  v = fmaxf(v, dpp_move<0x4E>(v));     // quad_perm [2,3,0,1]
+  v = fmaxf(v, dpp_move<0x141>(v));    // row_half_mirror
+  v = fmaxf(v, dpp_move<0x140>(v));    // row_mirror
+  return fmaxf(v, swap16(v));
+}
+__device__ __forceinline__ float half_wave_sum(float v) {
+  v += dpp_move<0xB1>(v);
+  v += dpp_move<0x4E>(v);
+  v += dpp_move<0x141>(v);
+  v += dpp_move<0x140>(v);
+  return v + swap16(v);
+}
+
+// LDS written by some lanes of this wavefront is read by others: the hardware keeps
+// a wavefront's LDS operations in order, this keeps the compiler from moving them
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// T:  storage type of unquantized latents (bfloat16 is converted to fp16 in registers: exact in the fp16 range)
+// HS: score slots per lane: the unit has at most 2*HS heads (HS = 16: two 16-row tiles)
+// NG: 128-column blocks per unit (16 lanes x 8 channels each)
+// I4: latents are 4-bit codes; every 128-column block of the unit is one quantization block
+template <typename T, int HS, int NG, bool I4>
+__global__ __launch_bounds__(256) void pv_kernel(PvArgs a) {
+  constexpr bool kIsBf16 = !__is_same(T, F16);
+  constexpr int MT = HS > 8 ? 2 : 1;
+  constexpr int NA = I4 ? NG : 1;                  // probability tiles
+  constexpr int kPitch = 40;                       // halfs per head row: 80-byte pitch, 16-byte reads of 16 rows hit distinct banks
+  __shared__ __attribute__((aligned(16))) _Float16 p_lds[4][NA][MT * 16 * kPitch];
+  __shared__ __attribute__((aligned(16))) float x_lds[4][MT * 16 * NA];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 15, kq = lane >> 4;         // matrix-core roles: column (B, D) or head row (A); token quarter
+  const int tl = lane & 31, hp = lane >> 5;        // softmax roles: token of the set; head parity
+  const Meta& m = a.meta;
+
+  // unit fastest: neighbouring workgroups read neighbouring columns of the same rows
+  int wg = blockIdx.x;
+  const int unit = wg % a.units.n_units;
+  wg /= a.units.n_units;
+  const int n_sg = (a.n_split + 3) >> 2;
+  const int sg = wg % n_sg;
+  const int b = wg / n_sg;
+  const int split = sg * 4 + wave;
+  const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
+  const int s0 = split * a.split_tokens;
+  if (split >= a.n_split || s0 >= L) return;       // whole wavefront; nothing below synchronises wavefronts
+  const int ntok = min(a.split_tokens, L - s0);
+  const int n_sets = (ntok + 31) >> 5;
+  const int last = ntok - 1;
+
+  const PvUnit u = a.units.u[unit];
+  const int h0 = u.h0, nh = u.nh, c0 = u.c0;
+  const int lpt = u.ncols >> 3;                    // 8-channel chunks per row of the unit
+
+  const size_t row0 = (size_t)b * a.max_seq + s0;
+  const unsigned row_bytes = I4 ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
+  const unsigned char* base = (const unsigned char*)a.hv + row0 * row_bytes + (I4 ? c0 / 2 : c0 * 2);
+  unsigned coff[NG];
+#pragma unroll
+  for (int ng = 0; ng < NG; ++ng) coff[ng] = (unsigned)min(ng * 16 + n, lpt - 1) * (I4 ? 4u : 16u);
+
+  const float* sc_ptr[HS];
+  bool two[HS];
+#pragma unroll
+  for (int i = 0; i < HS; ++i) {
+    const int h = h0 + min(hp + 2 * i, nh - 1);
+    sc_ptr[i] = a.scores + ((size_t)b * m.n_heads + h) * a.lpad + s0;
+    two[i] = a.n_parts[h] > 1;
+  }
+  const size_t sz_idx0 = I4 ? row0 * a.n_blocks_q + (c0 >> 7) : 0;
+
+  struct Blk {
+    uint32_t h[8][I4 ? 1 : 4];                     // [token j of the lane's quarter][dword]
+  };
+  struct Set {
+    Blk blk[NG];
+    float sc[HS][2];
+    uint32_t sz[NA];                               // int4: scale | zero << 16 of the lane's softmax token
+  };
+
+  // every load is unconditional and in bounds (clamped to the last token / chunk / head);
+  // what a clamped load returns is given zero weight or never stored
+  auto issue = [&](Set& st, int k) {
+    const int tb = k * 32;
+#pragma unroll
+    for (int ng = 0; ng < NG; ++ng) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const unsigned t = (unsigned)min(tb + 8 * kq + j, last);
+        const unsigned char* p = base + (size_t)(t * row_bytes + coff[ng]);
+        if constexpr (I4) {
+          st.blk[ng].h[j][0] = *reinterpret_cast<const uint32_t*>(p);
+        } else {
+          const uint4v v = *reinterpret_cast<const uint4v*>(p);
+          st.blk[ng].h[j][0] = v.x; st.blk[ng].h[j][1] = v.y; st.blk[ng].h[j][2] = v.z; st.blk[ng].h[j][3] = v.w;
+        }
+      }
+    }
+    const int ts = min(tb + tl, last);
+#pragma unroll
+    for (int i = 0; i < HS; ++i) {
+      st.sc[i][0] = sc_ptr[i][ts];
+      st.sc[i][1] = sc_ptr[i][ts + a.part_stride];
+    }
+    if constexpr (I4) {
+#pragma unroll
+      for (int ng = 0; ng < NG; ++ng) {
+        const size_t idx = sz_idx0 + (size_t)ts * a.n_blocks_q + ng;
+        st.sz[ng] = (uint32_t)a.hv_scale[idx] | ((uint32_t)a.hv_zero[idx] << 16);
+      }
+    }
+  };
+
+  float mx[HS], lsum[HS], lz[HS][NA];
+#pragma unroll
+  for (int i = 0; i < HS; ++i) {
+    mx[i] = -INFINITY;
+    lsum[i] = 0.f;
+#pragma unroll
+    for (int g = 0; g < NA; ++g) lz[i][g] = 0.f;
+  }
+  float4v acc[MT][NG][8];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int ng = 0; ng < NG; ++ng)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[mt][ng][e] = float4v{0.f, 0.f, 0.f, 0.f};
+
+  _Float16* pw = &p_lds[wave][0][0];
+  float* xw = &x_lds[wave][0];
+
+  auto process = [&](Set& st, int k) {
+    const bool tok_ok = k * 32 + tl < ntok;
+    // ---- online softmax statistics of the 32 tokens
+    float s[HS], bm[HS];
+    bool grew = false;
+#pragma unroll
+    for (int i = 0; i < HS; ++i) {
+      const float v = st.sc[i][0] + (two[i] ? st.sc[i][1] : 0.f);
+      s[i] = (tok_ok && hp + 2 * i < nh) ? v : -INFINITY;
+      bm[i] = half_wave_max(s[i]);
+      grew |= bm[i] > mx[i];
+    }
+    if (__builtin_amdgcn_ballot_w64(grew) != 0) {             // uniform: some head's running maximum rises
+#pragma unroll
+      for (int i = 0; i < HS; ++i) {
+        const float mn = fmaxf(mx[i], bm[i]);
+        const float al = mx[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mx[i] - mn);
+        mx[i] = mn;
+        lsum[i] *= al;
+#pragma unroll
+        for (int g = 0; g < NA; ++g) lz[i][g] *= al;
+        if (tl == 0) xw[hp + 2 * i] = al;
+      }
+      wave_lds_fence();
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const float4v al = *reinterpret_cast<const float4v*>(xw + mt * 16 + 4 * kq);   // accumulator rows 4*kq + 0..3
+#pragma unroll
+        for (int ng = 0; ng < NG; ++ng)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[mt][ng][e] *= al;
+      }
+      wave_lds_fence();
+    }
+#pragma unroll
+    for (int i = 0; i < HS; ++i) {
+      const float p = s[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s[i] - mx[i]);
+      const int slot = (hp + 2 * i) * kPitch + tl;
+      if constexpr (!I4) {
+        const _Float16 ph = (_Float16)p;
+        lsum[i] += (float)ph;                                  // the weights that enter the contraction
+        pw[slot] = ph;
+      } else {
+        lsum[i] += p;
+#pragma unroll
+        for (int g = 0; g < NA; ++g) {
+          const float sc = F16::to_float((uint16_t)(st.sz[g] & 0xffffu));
+          const float zp = F16::to_float((uint16_t)(st.sz[g] >> 16));
+          const _Float16 ah = (_Float16)(p * sc);
+          lz[i][g] = fmaf((float)ah, zp, lz[i][g]);
+          pw[g * (MT * 16 * kPitch) + slot] = ah;
+        }
+      }
+    }
+    wave_lds_fence();
+    half8 pa[NA][MT];
+#pragma unroll
+    for (int g = 0; g < NA; ++g)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        pa[g][mt] = *reinterpret_cast<const half8*>(pw + g * (MT * 16 * kPitch) + (mt * 16 + n) * kPitch + 8 * kq);
+    wave_lds_fence();
+
+    // ---- transposed latents as B operands, 8 accumulator sets per 128-column block
+#pragma unroll
+    for (int ng = 0; ng < NG; ++ng) {
+      const Blk& bl = st.blk[ng];
+      uint32_t o[8][4];                                        // [channel e of the chunk][token pair]
+#pragma unroll
+      for (int jp = 0; jp < 4; ++jp) {
+        if constexpr (!I4) {
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            // perm(hi_src, lo_src, sel): selector bytes 0-3 pick from lo_src, 4-7 from hi_src
+            uint32_t lo = __builtin_amdgcn_perm(bl.h[2 * jp + 1][d], bl.h[2 * jp][d], 0x05040100u);
+            uint32_t hi = __builtin_amdgcn_perm(bl.h[2 * jp + 1][d], bl.h[2 * jp][d], 0x07060302u);
+            if constexpr (kIsBf16) {
+              lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__builtin_bit_cast(float, lo << 16),
+                                                                           __builtin_bit_cast(float, lo & 0xffff0000u)));
+              hi = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__builtin_bit_cast(float, hi << 16),
+                                                                           __builtin_bit_cast(float, hi & 0xffff0000u)));
+            }
+            o[2 * d][jp] = lo;
+            o[2 * d + 1][jp] = hi;
+          }
+        } else {
+#pragma unroll
+          for (int kb = 0; kb < 4; ++kb) {
+            // byte kb of both tokens' code words side by side: [0, tok b byte, 0, tok a byte]
+            const uint32_t w = __builtin_amdgcn_perm(bl.h[2 * jp + 1][0], bl.h[2 * jp][0], 0x0c040c00u + 0x00010001u * kb);
+            // 0x6400 | c is the fp16 number 1024 + c; 0x6400 | (c << 4) is 1024 + 16 c
+            const half2v ev = __builtin_bit_cast(half2v, (w & 0x000f000fu) | 0x64006400u) - half2v{(_Float16)1024.f, (_Float16)1024.f};
+            const half2v od = __builtin_bit_cast(half2v, (w & 0x00f000f0u) | 0x64006400u) * half2v{(_Float16)0.0625f, (_Float16)0.0625f} -
+                              half2v{(_Float16)64.f, (_Float16)64.f};
+            o[2 * kb][jp] = __builtin_bit_cast(uint32_t, ev);
+            o[2 * kb + 1][jp] = __builtin_bit_cast(uint32_t, od);
+          }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint4v bw = {o[e][0], o[e][1], o[e][2], o[e][3]};
+        const half8 bop = __builtin_bit_cast(half8, bw);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[mt][ng][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[I4 ? ng : 0][mt], bop, acc[mt][ng][e], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- two sets of registers in turn; the next set's loads are in flight while one is consumed
+  Set sa, sb;
+  issue(sa, 0);
+  int k = 0;
+  for (; k + 2 < n_sets; k += 2) {
+    issue(sb, k + 1);
+    process(sa, k);
+    issue(sa, k + 2);
+    process(sb, k + 1);
+  }
+  if (k + 1 < n_sets) {
+    issue(sb, k + 1);
+    process(sa, k);
+    process(sb, k + 1);
+  } else {
+    process(sa, k);
+  }
+
+  // ---- results of the split
+#pragma unroll
+  for (int i = 0; i < HS; ++i) {
+    const float ls = half_wave_sum(lsum[i]);
+    const int hh = hp + 2 * i;
+    if (tl == 0 && hh < nh && u.write_ml) {
+      float* ml = a.ml_part + (((size_t)b * a.n_split + split) * m.n_heads + h0 + hh) * 2;
+      ml[0] = mx[i];
+      ml[1] = ls;
+    }
+    if constexpr (I4) {
+#pragma unroll
+      for (int g = 0; g < NA; ++g) {
+        const float zs = half_wave_sum(lz[i][g]);
+        if (tl == 0) xw[hh * NA + g] = zs;
+      }
+    }
+  }
+  if constexpr (I4) wave_lds_fence();
+
+  float* op = a.o_part + ((size_t)b * a.n_split + split) * a.o_stride;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int hh = mt * 16 + 4 * kq + r;                    // accumulator row = head of the unit
+      if (hh >= nh) continue;
+      const int h = h0 + hh;
+      const int j = m.group_of_head[h];
+      const int lo = m.v_off[j], hi = m.v_off[j + 1];
+      float* oh = op + o_head_off(m, h) - lo;
+#pragma unroll
+      for (int ng = 0; ng < NG; ++ng) {
+        const int chunk = ng * 16 + n;
+        const int col = c0 + chunk * 8;
+        if (chunk >= lpt || col < lo || col >= hi) continue;   // a head keeps the columns of its own group
+        const float zt = I4 ? xw[hh * NA + ng] : 0.f;
+        float4v v0, v1;
+        v0.x = acc[mt][ng][0][r] - zt; v0.y = acc[mt][ng][1][r] - zt; v0.z = acc[mt][ng][2][r] - zt; v0.w = acc[mt][ng][3][r] - zt;
+        v1.x = acc[mt][ng][4][r] - zt; v1.y = acc[mt][ng][5][r] - zt; v1.z = acc[mt][ng][6][r] - zt; v1.w = acc[mt][ng][7][r] - zt;
+        *reinterpret_cast<float4v*>(oh + col) = v0;
+        *reinterpret_cast<float4v*>(oh + col + 4) = v1;
+      }
+    }
+  }
+}
+
+#define PALU_PV_INST(T, I4)                                        \
+  template __global__ void pv_kernel<T, 2, 1, I4>(PvArgs);         \
+  template __global__ void pv_kernel<T, 2, 2, I4>(PvArgs);         \
+  template __global__ void pv_kernel<T, 8, 1, I4>(PvArgs);         \
+  template __global__ void pv_kernel<T, 8, 2, I4>(PvArgs);         \
+  template __global__ void pv_kernel<T, 16, 1, I4>(PvArgs);
+PALU_PV_INST(F16, false)
+PALU_PV_INST(BF16, false)
+PALU_PV_INST(F16, true)
+
+}  // namespace palu
