@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ring-gib", type=float, default=1.0, help="distinct latent bytes to cycle through")
     ap.add_argument("--opt", action="append", default=[], help="tuning knob name=value (palu_set_option)")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="after the timed region also run a plain device copy of this size three times: "
+                         "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -224,6 +227,24 @@ def main() -> int:
         "step_GBps_algorithmic": total_gbs,
         "wall_ms_per_step": wall_ms / args.steps,
     }
+
+    if args.copy_probe > 0:
+        src = torch.empty(args.copy_probe * 2 ** 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"[bench] copy probe: 3 device copies of {args.copy_probe} MiB (reads and writes that many bytes each)")
+
+    # measured HBM traffic per launch of the dominant kernel, from counter runs kept under profiles/
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            tr = json.load(f).get(cfg)
+        if tr:
+            result["roofline"]["traffic"] = tr["score_kernel_bytes"]
+            result["roofline_value"]["traffic"] = tr["value_kernel_bytes"]
+    except OSError:
+        pass
 
     # ---- CPU baseline: the oracle as it stands, one decode step ------------------
     if not args.no_cpu_baseline:
