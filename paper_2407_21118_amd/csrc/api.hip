@@ -23,7 +23,6 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score workgroup (ranks <= 256)
 std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
 std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
-std::atomic<int> g_opt_value_kernel{0};       // 0: matrix-core kernel where it applies; 1: vector-ALU kernel always
 
 int device_cu_count() {
   static std::atomic<int> cached[64];
@@ -203,53 +202,24 @@ int plan_score(const Meta& m, ScorePlan* p) {
 }
 
 // ---- value-path work units -----------------------------------------------------
-enum { kVal1 = 0, kVal2, kVal4, kNumValCls };
-
-struct ValuePlan {
-  Units units[kNumValCls];
-  int total_units;
-};
-
-int plan_value(const Meta& m, ValuePlan* p) {
-  std::memset(p, 0, sizeof(*p));
-  for (int j = 0; j < m.n_groups; ++j) {
-    const int s = m.head_off[j + 1] - m.head_off[j];
-    if (m.v_off[j + 1] - m.v_off[j] > 2048) return PALU_ERR_UNSUPPORTED;
-    for (int u0 = 0; u0 < s; u0 += 4) {
-      const int nh = std::min(4, s - u0);
-      const int cls = s == 1 ? kVal1 : (s == 2 ? kVal2 : kVal4);
-      Units& u = p->units[cls];
-      if (u.n_units >= kMaxUnits) return PALU_ERR_UNSUPPORTED;
-      u.h0[u.n_units] = (uint16_t)(m.head_off[j] + u0);
-      u.nh[u.n_units] = (uint8_t)nh;
-      ++u.n_units;
-      ++p->total_units;
-    }
-  }
-  return PALU_OK;
-}
-
 // Units of the matrix-core value kernel: at most 256 latent columns and 32 heads each.
 // Small adjacent groups are merged (up to 4 heads, 256 columns) so that a
 // wavefront's 64 lanes all stream; wide latents are cut into column slices.
-enum { kNumPvCls = 6 };
+enum { kNumPvCls = 5 };            // class = 2 * (0: <=4 heads, 1: <=16, 2: <=32) + (columns > 128)
 struct PvPlan {
-  PvUnits units[kNumPvCls];      // class = 2 * (0: <=4 heads, 1: <=16, 2: <=32) + (columns > 128)
   int total_units;
-  bool aligned128;               // every unit starts on a 128-column boundary
+  PvUnit units[kMaxPlanUnits];
+  uint8_t unit_cls[kMaxPlanUnits];
 };
 
 int plan_pv(const Meta& m, PvPlan* p) {
-  std::memset(p, 0, sizeof(*p));
-  p->aligned128 = true;
+  p->total_units = 0;
   auto add = [&](int h0, int nh, int c0, int ncols, int write_ml) -> int {
+    if (p->total_units >= kMaxPlanUnits) return PALU_ERR_UNSUPPORTED;
     const int hs = nh <= 4 ? 0 : (nh <= 16 ? 1 : 2);
-    PvUnits& u = p->units[2 * hs + (ncols > 128 ? 1 : 0)];
-    if (u.n_units >= kMaxPvUnits) return PALU_ERR_UNSUPPORTED;
-    PvUnit& x = u.u[u.n_units++];
+    PvUnit& x = p->units[p->total_units];
     x.h0 = (uint16_t)h0; x.c0 = c0; x.ncols = (uint16_t)ncols; x.nh = (uint8_t)nh; x.write_ml = (uint8_t)write_ml;
-    ++p->total_units;
-    if (c0 % 128) p->aligned128 = false;
+    p->unit_cls[p->total_units++] = (uint8_t)(2 * hs + (ncols > 128 ? 1 : 0));
     return PALU_OK;
   };
   int st;
@@ -279,33 +249,24 @@ int plan_pv(const Meta& m, PvPlan* p) {
   return PALU_OK;
 }
 
-// Tokens per value split and number of splits for a given attended length.
-// Matrix-core kernel: a split is one wavefront's share; aim at four wavefronts
-// per compute unit, splits of 64 to 512 tokens (more where the merge kernel's
-// split limit asks for it).
+// Tokens per value split and number of splits for a given attended length: a
+// split is one wavefront's share; aim at four wavefronts per compute unit,
+// splits of 64 to 512 tokens (more where the merge kernel's split limit asks for it).
 constexpr int kPvSplitMin = 64, kPvSplitMax = 512;
-void pv_split_geometry(int total_units, int batch, int seq_len, int* split_tokens, int* n_split) {
+void split_geometry(int total_units, int batch, int seq_len, int* split_tokens, int* n_split) {
   const long long items = std::max(1, total_units * batch);
   long long st = ceil_div((int)std::min<long long>(items * seq_len / (4LL * device_cu_count()) + 1, 1 << 30), 32) * 32LL;
   st = std::min<long long>(std::max<long long>(st, kPvSplitMin), kPvSplitMax);
+  if (g_opt_value_split > 0) st = g_opt_value_split;
   st = std::max<long long>(st, ceil_div(ceil_div(seq_len, kMaxSplits), 32) * 32LL);
   *split_tokens = (int)st;
   *n_split = ceil_div(seq_len, (int)st);
 }
-void split_geometry(int total_units, int batch, int seq_len, int* split_tokens, int* n_split) {
-  const int target = std::max(1, ceil_div(4 * device_cu_count(), std::max(1, total_units * batch)));
-  int st = ceil_div(ceil_div(seq_len, target), 32) * 32;
-  st = std::min(std::max(st, 64), kSplitMax);
-  *split_tokens = st;
-  *n_split = ceil_div(seq_len, st);
-}
-// Upper bound of the number of splits of any attended length up to max_seq, for either kernel.
-int split_bound(int total_units, int pv_units, int batch, int max_seq) {
-  const int target = std::max(1, ceil_div(4 * device_cu_count(), std::max(1, total_units * batch)));
-  const int pv_target = ceil_div(4 * device_cu_count(), std::max(1, pv_units * batch));
-  int cap = std::max(std::max(target, ceil_div(max_seq, kSplitMax)), std::max(pv_target, ceil_div(max_seq, kPvSplitMax)));
+// Upper bound of the number of splits of any attended length up to max_seq.
+int split_bound(int total_units, int batch, int max_seq) {
+  int cap = std::max(ceil_div(4 * device_cu_count(), std::max(1, total_units * batch)), ceil_div(max_seq, kPvSplitMax));
   if (g_opt_value_split > 0) cap = std::max(cap, ceil_div(max_seq, (int)g_opt_value_split));
-  return cap + 2;
+  return std::min(cap, kMaxSplits) + 2;
 }
 
 struct Workspace {
@@ -380,29 +341,6 @@ ScoreFn score_fn(int act, bool i4, int cls_id, bool w8) {
   return act == PALU_F16 ? score_fn_t<F16, false>(rc, lg, w8) : score_fn_t<BF16, false>(rc, lg, w8);
 }
 
-using ValueFn = void (*)(ValueArgs);
-ValueFn value_fn(int act, bool i4, int cls) {
-  if (act == PALU_F16 && !i4) {
-    switch (cls) {
-      case kVal1: return value_kernel<F16, 1, false>;
-      case kVal2: return value_kernel<F16, 2, false>;
-      default: return value_kernel<F16, 4, false>;
-    }
-  }
-  if (act == PALU_F16 && i4) {
-    switch (cls) {
-      case kVal1: return value_kernel<F16, 1, true>;
-      case kVal2: return value_kernel<F16, 2, true>;
-      default: return value_kernel<F16, 4, true>;
-    }
-  }
-  switch (cls) {
-    case kVal1: return value_kernel<BF16, 1, false>;
-    case kVal2: return value_kernel<BF16, 2, false>;
-    default: return value_kernel<BF16, 4, false>;
-  }
-}
-
 using PvFn = void (*)(PvArgs);
 template <typename T, bool I4>
 PvFn pv_fn_t(int cls) {
@@ -446,11 +384,8 @@ int palu_set_option(const char* name, int value) {
   } else if (!std::strcmp(name, "score_chunks")) {
     g_opt_score_chunks = value;
   } else if (!std::strcmp(name, "value_split_tokens")) {
-    if (value != 0 && (value % 32 != 0 || value > kSplitMax)) return PALU_ERR_INVALID_ARG;
+    if (value != 0 && (value % 32 != 0 || value > 4096)) return PALU_ERR_INVALID_ARG;
     g_opt_value_split = value;
-  } else if (!std::strcmp(name, "value_kernel")) {
-    if (value > 1) return PALU_ERR_INVALID_ARG;
-    g_opt_value_kernel = value;
   } else {
     return PALU_ERR_INVALID_ARG;
   }
@@ -596,13 +531,11 @@ int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch,
   if (st != PALU_OK) return st;
   if (!out_bytes || batch <= 0 || max_seq <= 0) return PALU_ERR_INVALID_ARG;
   ScorePlan sp;
-  ValuePlan vp;
-  if ((st = plan_score(m, &sp)) != PALU_OK) return st;
-  if ((st = plan_value(m, &vp)) != PALU_OK) return st;
   PvPlan pp;
-  if (plan_pv(m, &pp) != PALU_OK) pp.total_units = vp.total_units;
+  if ((st = plan_score(m, &sp)) != PALU_OK) return st;
+  if ((st = plan_pv(m, &pp)) != PALU_OK) return st;
   Workspace w;
-  carve(m, batch, max_seq, split_bound(vp.total_units, pp.total_units, batch, max_seq), 2 * sp.max_slices, &w);
+  carve(m, batch, max_seq, split_bound(pp.total_units, batch, max_seq), 2 * sp.max_slices, &w);
   *out_bytes = w.total;
   return PALU_OK;
 }
@@ -644,24 +577,14 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
   if ((Rk % 8) || (Rv % 8)) return PALU_ERR_INVALID_ARG;
 
   ScorePlan sp;
-  ValuePlan vp;
-  if ((st = plan_score(m, &sp)) != PALU_OK) return st;
-  if ((st = plan_value(m, &vp)) != PALU_OK) return st;
   PvPlan pp;
-  const bool pv_planned = plan_pv(m, &pp) == PALU_OK;     // too many units: the vector-ALU kernel takes the layer
-  if (!pv_planned) pp.total_units = vp.total_units;
+  if ((st = plan_score(m, &sp)) != PALU_OK) return st;
+  if ((st = plan_pv(m, &pp)) != PALU_OK) return st;
   const int quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
-  // the matrix-core value kernel folds int4 scales per 128-column block of a unit
-  const bool use_pv = pv_planned && g_opt_value_kernel != 1 && (!v_i4 || (quant_block == 128 && pp.aligned128));
   int split_tokens, n_split;
-  if (use_pv) pv_split_geometry(pp.total_units, batch, seq_len, &split_tokens, &n_split);
-  else split_geometry(vp.total_units, batch, seq_len, &split_tokens, &n_split);
-  if (g_opt_value_split > 0) {
-    split_tokens = g_opt_value_split;
-    n_split = ceil_div(seq_len, split_tokens);
-  }
+  split_geometry(pp.total_units, batch, seq_len, &split_tokens, &n_split);
   if (n_split > kMaxSplits) return PALU_ERR_UNSUPPORTED;
-  const int n_split_cap = split_bound(vp.total_units, pp.total_units, batch, max_seq);
+  const int n_split_cap = split_bound(pp.total_units, batch, max_seq);
   Workspace w;
   carve(m, batch, max_seq, n_split_cap, 2 * sp.max_slices, &w);
   if (n_split > n_split_cap) return PALU_ERR_INVALID_ARG;
@@ -781,7 +704,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     max_parts = std::max(max_parts, (int)n_parts[h]);
   }
   if ((st = mark(2)) != PALU_OK) return st;
-  if (use_pv) {
+  {
     if (max_parts > 2) {                     // ranks contracted in slices: fold those heads' planes into plane 0
       PlaneSumArgs ps;
       ps.scores = reinterpret_cast<float*>(ws + w.scores);
@@ -815,41 +738,20 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     for (int h = 0; h < PALU_MAX_HEADS; ++h) a.n_parts[h] = (uint8_t)(n_parts[h] > 2 ? 1 : n_parts[h]);
     a.meta = m;
     for (int cls = 0; cls < kNumPvCls; ++cls) {
-      if (pp.units[cls].n_units == 0) continue;
-      a.units = pp.units[cls];
-      const unsigned grid = (unsigned)(a.units.n_units * ceil_div(n_split, 4) * batch);
-      hipLaunchKernelGGL(pv_fn(act, v_i4, cls), dim3(grid), dim3(256), 0, s, a);
-      if ((st = launch_ok()) != PALU_OK) return st;
-    }
-  } else {
-    ValueArgs a;
-    a.hv = hv;
-    a.hv_scale = static_cast<const uint16_t*>(hv_scale);
-    a.hv_zero = static_cast<const uint16_t*>(hv_zero);
-    a.scores = reinterpret_cast<const float*>(ws + w.scores);
-    a.seq_lens = seq_lens;
-    a.o_part = reinterpret_cast<float*>(ws + w.o_part);
-    a.ml_part = reinterpret_cast<float*>(ws + w.ml_part);
-    a.row_elems = Rv;
-    a.max_seq = max_seq;
-    a.part_stride = w.part_stride;
-    a.seq_len = seq_len;
-    a.lpad = w.lpad;
-    a.batch = batch;
-    a.split_tokens = split_tokens;
-    a.n_split = n_split;
-    a.o_stride = w.o_stride;
-    a.quant_block = quant_block;
-    a.n_blocks_q = Rv / a.quant_block;
-    std::memcpy(a.n_parts, n_parts, sizeof(n_parts));
-    a.meta = m;
-    if (split_tokens > kSplitMax) return PALU_ERR_UNSUPPORTED;
-    for (int cls = 0; cls < kNumValCls; ++cls) {
-      if (vp.units[cls].n_units == 0) continue;
-      a.units = vp.units[cls];
-      const unsigned grid = (unsigned)(a.units.n_units * n_split * batch);
-      hipLaunchKernelGGL(value_fn(act, v_i4, cls), dim3(grid), dim3(256), 0, s, a);
-      if ((st = launch_ok()) != PALU_OK) return st;
+      auto flush = [&]() -> int {
+        if (a.units.n_units == 0) return PALU_OK;
+        const unsigned grid = (unsigned)(a.units.n_units * ceil_div(n_split, 4) * batch);
+        hipLaunchKernelGGL(pv_fn(act, v_i4, cls), dim3(grid), dim3(256), 0, s, a);
+        a.units.n_units = 0;
+        return launch_ok();
+      };
+      a.units.n_units = 0;
+      for (int i = 0; i < pp.total_units; ++i) {
+        if (pp.unit_cls[i] != cls) continue;
+        a.units.u[a.units.n_units++] = pp.units[i];
+        if (a.units.n_units == kMaxPvUnits && (st = flush()) != PALU_OK) return st;
+      }
+      if ((st = flush()) != PALU_OK) return st;
     }
   }
 

@@ -20,7 +20,6 @@ typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 constexpr int kDHead = PALU_D_HEAD;        // 128
 constexpr int kHalf = kDHead / 2;          // 64 rotation pairs
 constexpr int kTile = 32;                  // tokens per MFMA tile (N of the 32x32x16 instruction)
-constexpr int kMaxUnits = 128;             // work units (head blocks) per launch
 
 // Layer metadata passed by value in the kernel arguments.
 struct Meta {
@@ -32,13 +31,6 @@ struct Meta {
   int bk_off[PALU_MAX_GROUPS + 1];   // element offset of group j inside the concatenated B_k
   int bv_off[PALU_MAX_GROUPS + 1];
   uint8_t group_of_head[PALU_MAX_HEADS];
-};
-
-// A work unit of the score or value kernel: `nh` consecutive heads starting at h0.
-struct Units {
-  int n_units;
-  uint16_t h0[kMaxUnits];
-  uint8_t nh[kMaxUnits];
 };
 
 // Storage type helpers: the activation dtype is either IEEE half or bfloat16,
@@ -145,30 +137,6 @@ struct FoldArgs {
   float rev_hi[kHalf];       // theta^(-2f/128) / (2 pi) from the host's float64 value, as a float pair hi + lo
   float rev_lo[kHalf];
   Meta meta;
-};
-
-struct ValueArgs {
-  const void* hv;
-  const uint16_t* hv_scale;
-  const uint16_t* hv_zero;
-  const float* scores;       // [parts][batch][n_heads][lpad]
-  const int32_t* seq_lens;
-  float* o_part;             // [batch][n_split][sum_h r_v(h)]
-  float* ml_part;            // [batch][n_split][n_heads][2]  (max, sum) in the log2 domain
-  long long row_elems;       // R_v
-  long long max_seq;
-  long long part_stride;     // floats between score parts
-  int seq_len;
-  int lpad;
-  int batch;
-  int split_tokens;
-  int n_split;
-  int o_stride;              // sum_h r_v(group(h)): floats per (batch, split)
-  int quant_block;
-  int n_blocks_q;
-  uint8_t n_parts[PALU_MAX_HEADS];   // partial-score planes of head h (halves of a head x rank slices), summed here
-  Meta meta;
-  Units units;
 };
 
 struct CombineArgs {

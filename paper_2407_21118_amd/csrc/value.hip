@@ -1,16 +1,12 @@
-// Softmax and the value side, contracted in latent space (Eq. 4: (p H_v) B_v):
-//   value_kernel   per (sequence, group, split of the sequence): p = exp2(score - max),
-//                  l = sum p, o = sum_t p_t H_v[t, group columns]   (split-K partials)
-//   combine_kernel merges the partials of a head, normalises, applies B_v.
-// The P.H_v contraction has only s (heads per group) FLOP per latent element,
-// so it is HBM-bound: plain float32 FMAs on coalesced 16-byte loads, no matrix
-// cores and no LDS staging of the latents.
+// Split merge, normalisation and the B_v up-projection (Eq. 4: (p H_v) B_v), after
+// the per-split softmax partials of pv.hip:
+//   combine_kernel merges the partials (m, l, o) of a head over the splits of its
+//   sequence, divides by l and multiplies by the head's block of B_v.
 
 #include "palu_dev.h"
 
 namespace palu {
 
-constexpr int kSplitMax = 1024;     // tokens per split kept as probabilities in LDS
 constexpr int kMaxSplits = 1024;    // splits per sequence the combine kernel accepts
 
 template <int HB>
@@ -37,165 +33,6 @@ __device__ __forceinline__ void block_reduce(float (&v)[HB], float* scratch, boo
 #pragma unroll
     for (int w = 1; w < 4; ++w) r = is_max ? fmaxf(r, scratch[w * HB + h]) : r + scratch[w * HB + h];
     v[h] = r;
-  }
-}
-
-// HB: heads of one group handled per workgroup (1, 2 or 4); all read the same latent columns.
-template <typename T, int HB, bool I4>
-__global__ __launch_bounds__(256) void value_kernel(ValueArgs a) {
-  __shared__ __attribute__((aligned(16))) float sh[256 * HB * 8];   // probabilities, then the reduction buffer
-  __shared__ float red[4 * HB];
-  static_assert(256 * HB * 8 >= kSplitMax * HB, "probability buffer too small");
-
-  const int tid = threadIdx.x;
-  const Meta& m = a.meta;
-  int wg = blockIdx.x;
-  const int unit = wg % a.units.n_units;
-  wg /= a.units.n_units;
-  const int split = wg % a.n_split;
-  const int b = wg / a.n_split;
-
-  const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
-  const int s0 = split * a.split_tokens;
-  if (s0 >= L) return;
-  const int ntok = min(a.split_tokens, L - s0);
-
-  const int h0 = a.units.h0[unit], nh = a.units.nh[unit];
-  const int j = m.group_of_head[h0];
-  const int v0 = m.v_off[j];
-  const int rv = m.v_off[j + 1] - v0;
-
-  // ---- thread = (token in pass, 8-channel chunk) of the value-latent stream
-  const int lpt = rv >> 3;                       // 16-byte chunks per token row of this group
-  const int tpp = 256 / lpt;                     // tokens per pass
-  const int my_tok = tid / lpt, my_ch = tid - my_tok * lpt;
-  const bool worker = my_tok < tpp;
-  const size_t row0 = (size_t)b * a.max_seq + s0;
-  constexpr int U = 8;                           // loads in flight per thread
-  const unsigned row_bytes = I4 ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
-  const unsigned char* hv_base = (const unsigned char*)a.hv +
-                                 (I4 ? (row0 * a.row_elems + v0 + my_ch * 8) / 2 : (row0 * a.row_elems + v0 + my_ch * 8) * 2);
-  const size_t sb_base = row0 * a.n_blocks_q + (v0 + my_ch * 8) / a.quant_block;     // int4: scale / zero index of row 0
-
-  // raw latents (and int4 scale/zero) of U tokens: my_tok + tb, my_tok + tb + tpp, ...
-  struct Batch {
-    uint4v h[U];
-  };
-  auto load_batch = [&](Batch& bt, int tb) {
-#pragma unroll
-    for (int x = 0; x < U; ++x) {
-      const int tc = min(tb + x * tpp, ntok - 1);          // clamped: the weight of an out-of-range token is zero
-      if (!I4) {
-        bt.h[x] = *reinterpret_cast<const uint4v*>(hv_base + (size_t)tc * row_bytes);
-      } else {
-        bt.h[x].x = *reinterpret_cast<const uint32_t*>(hv_base + (size_t)tc * row_bytes);
-        const size_t sb = sb_base + (size_t)tc * a.n_blocks_q;
-        bt.h[x].y = (uint32_t)a.hv_scale[sb] | ((uint32_t)a.hv_zero[sb] << 16);
-      }
-    }
-  };
-  // the first batch goes out before the softmax prologue: HBM latency overlaps it
-  Batch cur;
-  if (worker) load_batch(cur, my_tok);
-
-  // ---- scores of the split -> LDS, running max per head
-  float mx[HB], sum[HB];
-#pragma unroll
-  for (int hh = 0; hh < HB; ++hh) { mx[hh] = -INFINITY; sum[hh] = 0.f; }
-#pragma unroll
-  for (int hh = 0; hh < HB; ++hh) {
-    if (hh < nh) {
-      const int h = h0 + hh;
-      const float* s0p = a.scores + ((size_t)b * m.n_heads + h) * a.lpad + s0;
-      const int np = a.n_parts[h];
-      for (int t = tid; t < ntok; t += 256) {
-        float s = s0p[t];
-        for (int pl = 1; pl < np; ++pl) s += s0p[pl * a.part_stride + t];
-        sh[t * HB + hh] = s;
-        mx[hh] = fmaxf(mx[hh], s);
-      }
-    }
-  }
-  block_reduce<HB>(mx, red, true);
-#pragma unroll
-  for (int hh = 0; hh < HB; ++hh) {
-    for (int t = tid; t < ntok; t += 256) {
-      const float p = hh < nh ? exp2f(sh[t * HB + hh] - mx[hh]) : 0.f;
-      sh[t * HB + hh] = p;
-      sum[hh] += p;
-    }
-  }
-  block_reduce<HB>(sum, red, false);     // its barriers also publish the probabilities
-
-  // ---- stream the value latents
-  float acc[HB][8];
-#pragma unroll
-  for (int hh = 0; hh < HB; ++hh)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
-
-  if (worker) {
-    for (int tb = my_tok; tb < ntok; tb += tpp * U) {
-      Batch nxt;
-      load_batch(nxt, tb + tpp * U);               // next batch in flight while this one is consumed
-#pragma unroll
-      for (int x = 0; x < U; ++x) {
-        const int t = tb + x * tpp;
-        const bool ok = t < ntok;
-        const int tc = ok ? t : ntok - 1;
-        float hvf[8];
-        float pw[HB];
-        if (!I4) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            hvf[2 * e] = T::to_float((uint16_t)(cur.h[x][e] & 0xffffu));
-            hvf[2 * e + 1] = T::to_float((uint16_t)(cur.h[x][e] >> 16));
-          }
-#pragma unroll
-          for (int hh = 0; hh < HB; ++hh) pw[hh] = ok ? sh[tc * HB + hh] : 0.f;
-        } else {
-          const uint32_t codes = cur.h[x].x;
-          const float s = F16::to_float((uint16_t)(cur.h[x].y & 0xffffu));
-          const float z = F16::to_float((uint16_t)(cur.h[x].y >> 16));
-#pragma unroll
-          for (int e = 0; e < 8; ++e) hvf[e] = (float)((codes >> (4 * e)) & 15u) - z;
-#pragma unroll
-          for (int hh = 0; hh < HB; ++hh) pw[hh] = ok ? sh[tc * HB + hh] * s : 0.f;
-        }
-#pragma unroll
-        for (int hh = 0; hh < HB; ++hh)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pw[hh], hvf[e], acc[hh][e]);
-      }
-      cur = nxt;
-    }
-  }
-
-  // ---- reduce over the tokens-in-pass dimension and write the partial
-  __syncthreads();                               // everyone is done reading probabilities
-  if (worker) {
-#pragma unroll
-    for (int hh = 0; hh < HB; ++hh)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) sh[(hh * 8 + e) * 256 + tid] = acc[hh][e];
-  }
-  __syncthreads();
-  float* op = a.o_part + ((size_t)b * a.n_split + split) * a.o_stride;
-  for (int idx = tid; idx < nh * rv; idx += 256) {
-    const int hh = idx / rv, c = idx - hh * rv;
-    const int ch = c >> 3, e = c & 7;
-    float s = 0.f;
-    for (int tp = 0; tp < tpp; ++tp) s += sh[(hh * 8 + e) * 256 + tp * lpt + ch];
-    op[o_head_off(m, h0 + hh) + c] = s;
-  }
-  if (tid < nh) {
-    float* ml = a.ml_part + (((size_t)b * a.n_split + split) * m.n_heads + h0 + tid) * 2;
-    float mv = 0.f, sv = 0.f;
-#pragma unroll
-    for (int hh = 0; hh < HB; ++hh)
-      if (hh == tid) { mv = mx[hh]; sv = sum[hh]; }
-    ml[0] = mv;
-    ml[1] = sv;
   }
 }
 
@@ -291,16 +128,6 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   }
 }
 
-#define PALU_VALUE_INST(T, HB, I4) template __global__ void value_kernel<T, HB, I4>(ValueArgs);
-PALU_VALUE_INST(F16, 1, false)
-PALU_VALUE_INST(F16, 2, false)
-PALU_VALUE_INST(F16, 4, false)
-PALU_VALUE_INST(F16, 1, true)
-PALU_VALUE_INST(F16, 2, true)
-PALU_VALUE_INST(F16, 4, true)
-PALU_VALUE_INST(BF16, 1, false)
-PALU_VALUE_INST(BF16, 2, false)
-PALU_VALUE_INST(BF16, 4, false)
 template __global__ void combine_kernel<F16>(CombineArgs);
 template __global__ void combine_kernel<BF16>(CombineArgs);
 
