@@ -23,6 +23,8 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score workgroup (ranks <= 256)
 std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
 std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
+std::atomic<int> g_opt_score_order{0};        // 0: automatic; 1: sequence chunk fastest; 2: unit fastest
+std::atomic<int> g_opt_score_early{0};        // 1: first MFMA phase overlaps the tail of the weight fetch
 
 int device_cu_count() {
   static std::atomic<int> cached[64];
@@ -205,7 +207,7 @@ int plan_score(const Meta& m, ScorePlan* p) {
 // Units of the matrix-core value kernel: at most 256 latent columns and 32 heads each.
 // Small adjacent groups are merged (up to 4 heads, 256 columns) so that a
 // wavefront's 64 lanes all stream; wide latents are cut into column slices.
-enum { kNumPvCls = 5 };            // class = 2 * (0: <=4 heads, 1: <=16, 2: <=32) + (columns > 128)
+enum { kNumPvCls = 5 };            // class = 2 * (0: <=4 heads, 1: <=16, 2: <=32) + (units of up to 256 columns)
 struct PvPlan {
   int total_units;
   PvUnit units[kMaxPlanUnits];
@@ -245,6 +247,15 @@ int plan_pv(const Meta& m, PvPlan* p) {
         if ((st = add(m.head_off[j] + u0, std::min(hb, s - u0), m.v_off[j] + cs, std::min(cw, rv - cs), cs == 0)) != PALU_OK)
           return st;
     ++j;
+  }
+  // One launch per head-count class: if any of its units is wider than 128 columns, the
+  // narrower ones run in the two-block kernel as well (their second block idles).
+  for (int hs = 0; hs < 2; ++hs) {
+    bool wide = false;
+    for (int i = 0; i < p->total_units; ++i) wide |= p->unit_cls[i] == 2 * hs + 1;
+    if (wide)
+      for (int i = 0; i < p->total_units; ++i)
+        if (p->unit_cls[i] == 2 * hs) p->unit_cls[i] = (uint8_t)(2 * hs + 1);
   }
   return PALU_OK;
 }
@@ -383,6 +394,11 @@ int palu_set_option(const char* name, int value) {
     g_opt_score_waves = value;
   } else if (!std::strcmp(name, "score_chunks")) {
     g_opt_score_chunks = value;
+  } else if (!std::strcmp(name, "score_order")) {
+    if (value > 2) return PALU_ERR_INVALID_ARG;
+    g_opt_score_order = value;
+  } else if (!std::strcmp(name, "score_early_start")) {
+    g_opt_score_early = value != 0;
   } else if (!std::strcmp(name, "value_split_tokens")) {
     if (value != 0 && (value % 32 != 0 || value > 4096)) return PALU_ERR_INVALID_ARG;
     g_opt_value_split = value;
@@ -661,14 +677,18 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
       a.rope_rows = g.rows;
     }
     const int tiles = ceil_div(seq_len, kTile);
-    int n_chunks = std::max(1, std::min(tiles, (int)std::lround((double)device_cu_count() / (sp.total_units * batch))));
-    if (g_opt_score_chunks > 0) n_chunks = std::min(tiles, (int)g_opt_score_chunks);
-    // the kernel addresses a chunk of the cache with 32-bit byte offsets
-    const long long chunk_limit_tiles = std::max(1LL, (1LL << 31) / ((long long)Rk * 2 * kTile));
-    n_chunks = std::max(n_chunks, (int)ceil_div(tiles, (int)std::min<long long>(chunk_limit_tiles, tiles)));
-    const int chunk_tiles = ceil_div(tiles, n_chunks);
-    a.chunk_tokens = chunk_tiles * kTile;
-    a.n_chunks = ceil_div(tiles, chunk_tiles);
+    // Sequence chunks per (sequence, unit): every launch (one per rank class) should fill
+    // the chip by itself, since launches on one stream run one after the other.
+    auto set_chunks = [&](int launch_units) {
+      int n_chunks = std::max(1, std::min(tiles, (int)std::lround((double)device_cu_count() / (launch_units * batch))));
+      if (g_opt_score_chunks > 0) n_chunks = std::min(tiles, (int)g_opt_score_chunks);
+      // the kernel addresses a chunk of the cache with 32-bit byte offsets
+      const long long chunk_limit_tiles = std::max(1LL, (1LL << 31) / ((long long)Rk * 2 * kTile));
+      n_chunks = std::max(n_chunks, (int)ceil_div(tiles, (int)std::min<long long>(chunk_limit_tiles, tiles)));
+      const int chunk_tiles = ceil_div(tiles, n_chunks);
+      a.chunk_tokens = chunk_tiles * kTile;
+      a.n_chunks = ceil_div(tiles, chunk_tiles);
+    };
     for (int cls = 0; cls < sp.n_cls; ++cls) {
       const int id = sp.cls_id[cls];
       const int rc = id / 3, lg = id % 3;
@@ -680,7 +700,10 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
       const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
       auto flush = [&]() -> int {
         if (a.units.n_units == 0) return PALU_OK;
+        set_chunks(a.units.n_units);
         const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
+        a.unit_fastest = g_opt_score_order == 2;
+        a.early_start = g_opt_score_early;
         hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
         a.units.n_units = 0;
         return launch_ok();

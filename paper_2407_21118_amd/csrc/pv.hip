@@ -170,6 +170,7 @@ __global__ __launch_bounds__(256) void pv_kernel(PvArgs a) {
     two[i] = a.n_parts[h] > 1;
   }
   const size_t sz_idx0 = I4 ? row0 * a.n_blocks_q + (c0 >> 7) : 0;
+  const int n_blk = (u.ncols + 127) >> 7;          // 128-column blocks the unit really has
 
   struct Blk {
     uint32_t h[8][I4 ? 1 : 4];                     // [token j of the lane's quarter][dword]
@@ -207,7 +208,7 @@ __global__ __launch_bounds__(256) void pv_kernel(PvArgs a) {
     if constexpr (I4) {
 #pragma unroll
       for (int ng = 0; ng < NG; ++ng) {
-        const size_t idx = sz_idx0 + (size_t)ts * a.n_blocks_q + ng;
+        const size_t idx = sz_idx0 + (size_t)ts * a.n_blocks_q + min(ng, n_blk - 1);   // a narrow unit's idle block re-reads block 0
         st.sz[ng] = (uint32_t)a.hv_scale[idx] | ((uint32_t)a.hv_zero[idx] << 16);
       }
     }

@@ -36,6 +36,13 @@ __device__ __forceinline__ float sum_across_halves(float x) {
   return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
 }
 
+// A wavefront-uniform pointer, made scalar for the compiler too (operands of "s" asm constraints).
+__device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const unsigned char*)(((uint64_t)hi << 32) | lo);
+}
+
 // s_waitcnt immediate that waits only for the vector-memory counter (gfx9 layout:
 // vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
@@ -99,13 +106,23 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   const int lane = tid & 63;
   const int lane_lo = lane & 31, lane_hi = lane >> 5;
 
-  // chunk index fastest: neighbouring workgroups (spread over the XCDs) work on
-  // different sequence chunks of the same heads
+  // Workgroups are dealt to the 8 XCDs round-robin.  Unit fastest (with a multiple
+  // of 8 units): all sequence chunks of a unit run on one XCD, whose L2 then holds
+  // only that unit's folded weights.  Chunk fastest: an XCD sees every unit but
+  // only its share of the cos/sin rows.
   int wg = blockIdx.x;
-  const int chunk = wg % a.n_chunks;
-  wg /= a.n_chunks;
-  const int unit = wg % a.units.n_units;
-  const int b = wg / a.units.n_units;
+  int chunk, unit, b;
+  if (a.unit_fastest) {
+    unit = wg % a.units.n_units;
+    wg /= a.units.n_units;
+    chunk = wg % a.n_chunks;
+    b = wg / a.n_chunks;
+  } else {
+    chunk = wg % a.n_chunks;
+    wg /= a.n_chunks;
+    unit = wg % a.units.n_units;
+    b = wg / a.units.n_units;
+  }
   const ScoreUnit u = a.units.u[unit];
 
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
@@ -125,6 +142,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
                                  (I4 ? ((seq_base + t_begin) * a.row_elems + c_lo) / 2
                                      : ((seq_base + t_begin) * a.row_elems + c_lo) * 2);
   const unsigned char* rope_base = (const unsigned char*)(a.rope_rows + (size_t)t_begin * kDHead);
+  const unsigned char* rope_base_u = uniform_ptr(rope_base);
   const unsigned lds_base = (unsigned)(size_t)lds;
 
   // =========================== staging, LDS-direct (fp16) ===========================
@@ -134,28 +152,55 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   // 16-byte pieces XOR-swizzled by the row number) are one instruction.
   // Loads are issued unconditionally (tiles past the end of the chunk re-read its
   // last tile) so that the number of loads in flight at every wait is a constant.
-  auto dma_issue = [&](int tile_unclamped) {
-    const int r0 = min(tile_unclamped, last_tile) * kTile;
-    const unsigned buf_base = lds_base + (unsigned)((tile_unclamped % kBufs) * kBufB);
+  // Per-wavefront constants of its share of a tile, so that one request costs a
+  // handful of scalar instructions: byte offsets of its rows inside a tile and,
+  // per lane, of its pieces of the cos/sin rows.
+  unsigned dma_row_off[kRowsPerWave];
 #pragma unroll
-    for (int x = 0; x < kRowsPerWave; ++x) {
-      const int rr = wave * kRowsPerWave + x;                   // uniform
-      const unsigned rel = (unsigned)min(r0 + rr, rel_last);
-      const unsigned char* src = hk_base + (size_t)rel * row_bytes;          // scalar address
-      const unsigned m0v = buf_base + (unsigned)(rr * kRowB);
+  for (int x = 0; x < kRowsPerWave; ++x) dma_row_off[x] = (unsigned)(wave * kRowsPerWave + x) * row_bytes;
+  unsigned dma_cs_off[kCsPerWave], dma_cs_swz[kCsPerWave];
+#pragma unroll
+  for (int x = 0; x < kCsPerWave; ++x) {
+    const int row = 4 * (wave * kCsPerWave + x) + (lane >> 4);
+    dma_cs_off[x] = (unsigned)row * (kDHead * 2u);
+    dma_cs_swz[x] = (unsigned)(((lane & 15) ^ (row & 15)) * 16);
+  }
+  // what all requests of one tile share; rows past the last attendable one re-read it
+  struct DmaTile {
+    const unsigned char* src;    // first latent row of the tile
+    unsigned lim;                // byte offset of the last attendable row inside the tile
+    unsigned cs_base, cs_lim;    // the same for the cos/sin rows (32-bit offsets from rope_base)
+    unsigned m0;                 // LDS address of the tile's buffer
+  };
+  auto dma_tile = [&](int tile_unclamped) __attribute__((always_inline)) {
+    DmaTile d;
+    const int r0 = min(tile_unclamped, last_tile) * kTile;
+    d.src = uniform_ptr(hk_base + (size_t)((unsigned)r0 * row_bytes));
+    d.lim = (unsigned)(rel_last - r0) * row_bytes;
+    d.cs_base = (unsigned)r0 * (kDHead * 2u);
+    d.cs_lim = (unsigned)(rel_last - r0) * (kDHead * 2u);
+    d.m0 = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)((tile_unclamped % kBufs) * kBufB));
+    return d;
+  };
+  // op x of a tile: x < kRowsPerWave a latent row, else a quad of cos/sin rows
+  auto dma_issue_op = [&](const DmaTile& d, int x) __attribute__((always_inline)) {
+    if (x < kRowsPerWave) {
+      const unsigned char* src = d.src + min(dma_row_off[x], d.lim);        // scalar address
+      const unsigned m0v = d.m0 + (unsigned)((wave * kRowsPerWave + x) * kRowB);
       const unsigned voff = (unsigned)lane * 16u;
       if (kCpr == 64 || lane < kCpr)
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(src) : "memory");
+    } else {
+      const int y = x - kRowsPerWave;
+      const unsigned voff = d.cs_base + min(dma_cs_off[y], d.cs_lim) + dma_cs_swz[y];
+      const unsigned m0v = d.m0 + (unsigned)(kTileB + (wave * kCsPerWave + y) * 4 * kDHead * 2);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(rope_base_u) : "memory");
     }
+  };
+  auto dma_issue = [&](int tile_unclamped) __attribute__((always_inline)) {
+    const DmaTile d = dma_tile(tile_unclamped);
 #pragma unroll
-    for (int x = 0; x < kCsPerWave; ++x) {
-      const int q = wave * kCsPerWave + x;                      // quad of rows 4q .. 4q+3, uniform
-      const int row = 4 * q + (lane >> 4);
-      const unsigned rel = (unsigned)min(r0 + row, rel_last);
-      const unsigned voff = rel * (kDHead * 2u) + (unsigned)(((lane & 15) ^ (row & 15)) * 16);
-      const unsigned m0v = buf_base + (unsigned)(kTileB + q * 4 * kDHead * 2);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(rope_base) : "memory");
-    }
+    for (int x = 0; x < kDmaOps; ++x) dma_issue_op(d, x);
   };
   // wait until at most `tiles_in_flight` tiles' worth of this wavefront's LDS-direct loads are outstanding
   auto dma_wait = [&](auto tiles_in_flight) {
@@ -332,8 +377,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 
   // ---- start-up
   if (kDma) {
-    // tiles 0 .. kAheadTiles-1 are in flight; tile 0 must have landed before the first MFMA phase
-    dma_wait(std::integral_constant<int, kInFlight>{});
+    // tiles 0 .. kAheadTiles-1 are in flight; tile 0 must have landed before the first MFMA phase.
+    // The weight loads were issued after them: leaving those outstanding as well lets the first
+    // phase begin with the first k-steps' weights (the compiler waits per k-step from there on).
+    constexpr int kStartWait = kInFlight * kDmaOps + NKS * RT;
+    if (kStartWait <= 63 && a.early_start) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kStartWait <= 63 ? kStartWait : 0));
+    else dma_wait(std::integral_constant<int, kInFlight>{});
   } else {
     // tile 0 into LDS, tiles 1 and 2 in flight.  The explicit wait (vmcnt = 0) lets
     // the loop start from the same set of pending loads as every later iteration.
@@ -344,7 +393,117 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   }
   __syncthreads();
 
-  if (!kPingPong) {
+  if constexpr (!kPingPong && kDma && NKS >= 4) {
+    // One wavefront per SIMD, software-pipelined: while the matrix pipe works on
+    // tile k, the vector ALU does the cos/sin-weighted sums of tile k-1 (whose
+    // accumulators sit in a second register set) in the shadow of the MFMAs of
+    // the first half of the k-steps.  In the middle of the tile: make sure tile
+    // k+1 has landed, one barrier, request tile k+3 into the buffer of tile k-1
+    // (all its readers are past the barrier).  The last k-steps already fetch the
+    // first operands of tile k+1, so the pipe does not drain at the tile boundary.
+    constexpr int kHalfK = NKS / 2 > 0 ? NKS / 2 : 1;
+    constexpr int kGroups = 2 * RT;                      // epilogue groups of 8 accumulators
+    float16v acc[2][RT];
+    half8 hf[3], hn[2];                                  // B operands of this tile (ring) and the next tile's first two
+    auto hrow_of = [&](int tile) {
+      return lds + (size_t)(tile % kBufs) * kBufB + lane_lo * kRowB + kbase_b + lane_hi * 16;
+    };
+    auto cs_piece = [&](int tile, int g) {               // cos/sin halves of accumulators 8*(g&1) .. +7 of row tile g>>1
+      const unsigned char* crow = lds + (size_t)(tile % kBufs) * kBufB + kTileB + lane_lo * (kDHead * 2);
+      const int piece = lane_hi * 8 + (rt0 + (g >> 1)) * 2 + (g & 1);
+      return *reinterpret_cast<const half8*>(crow + ((piece ^ (lane_lo & 15)) * 16));
+    };
+    // `cur`: accumulator set of tile k; with_epi: tile k-1's sums are formed on the way.
+    // Every MFMA is followed by its share of the other work and a scheduling fence, so
+    // that the vector and memory instructions issue in the shadow of that MFMA.
+    constexpr int kEpiPer = (16 + kHalfK - 1) / kHalfK;  // previous tile's accumulators handled per MFMA of the first half
+    auto body = [&](auto cur_c, auto epi_c, int k) {
+      constexpr int cur = decltype(cur_c)::value;
+      constexpr bool with_epi = decltype(epi_c)::value;
+      const unsigned char* hrow = hrow_of(k);
+      const unsigned char* hnext = hrow_of(k + 1);
+      float part[4] = {0.f, 0.f, 0.f, 0.f};
+      half8 csr[2];
+      DmaTile nxt;
+      if (with_epi) csr[0] = cs_piece(k - 1, 0);
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        if (ks == kHalfK) {
+          if (with_epi) {
+            const float sum = sum_across_halves((part[0] + part[1]) + (part[2] + part[3]));
+            out_row[t_begin + (k - 1) * kTile + lane_lo] = sum * a.scale;
+          }
+          dma_wait(std::integral_constant<int, kAheadTiles - 2>{});   // tile k+1 has landed (this wavefront's share)
+          __syncthreads();
+          nxt = dma_tile(k + kAheadTiles);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // B operand two k-steps ahead; the last two steps fetch tile k+1's first operands
+        if (ks + 2 < NKS) hf[(ks + 2) % 3] = *reinterpret_cast<const half8*>(hrow + (ks + 2) * 32);
+        else hn[ks + 2 - NKS] = *reinterpret_cast<const half8*>(hnext + (ks + 2 - NKS) * 32);
+        const half8 hfrag = hf[ks % 3];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          if (ks == 0) {
+            float16v zero;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+            acc[cur][rt] = F16::mfma(W[ks][rt], hfrag, zero);
+          } else {
+            acc[cur][rt] = F16::mfma(W[ks][rt], hfrag, acc[cur][rt]);
+          }
+          if (ks < kHalfK) {
+            if (with_epi) {
+#pragma unroll
+              for (int j = 0; j < kEpiPer; ++j) {
+                const int e = (ks * RT + rt) * kEpiPer + j;      // accumulator e = 16 * row tile + i of tile k-1
+                if (e >= 16 * RT) continue;
+                const int g = e >> 3;
+                if ((e & 7) == 0 && g + 1 < kGroups) csr[(g + 1) & 1] = cs_piece(k - 1, g + 1);
+                part[e & 3] = fmaf(acc[cur ^ 1][e >> 4][e & 15], (float)csr[g & 1][e & 7], part[e & 3]);
+              }
+            }
+          } else {
+            const int x = (ks - kHalfK) * RT + rt;               // request tile k+3 into the buffer tile k-1 occupied
+            if (x < kDmaOps) dma_issue_op(nxt, x);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+#pragma unroll
+      for (int x = (NKS - kHalfK) * RT; x < kDmaOps; ++x) dma_issue_op(nxt, x);   // few k-steps: the rest of the requests
+      hf[0] = hn[0];
+      hf[1] = hn[1];
+    };
+    using C0 = std::integral_constant<int, 0>;
+    using C1 = std::integral_constant<int, 1>;
+    hf[0] = *reinterpret_cast<const half8*>(hrow_of(0));
+    hf[1] = *reinterpret_cast<const half8*>(hrow_of(0) + 32);
+    body(C0{}, std::false_type{}, 0);
+    int k = 1;
+    for (; k + 1 < n_tiles; k += 2) {
+      body(C1{}, std::true_type{}, k);
+      body(C0{}, std::true_type{}, k + 1);
+    }
+    // the last tile's sums (its accumulator set: parity of n_tiles - 1)
+    TileAcc r;
+    auto tail = [&](auto set_c, int tile) {
+      constexpr int set = decltype(set_c)::value;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        r.acc[rt] = acc[set][rt];
+        r.cs[rt][0] = cs_piece(tile, 2 * rt);
+        r.cs[rt][1] = cs_piece(tile, 2 * rt + 1);
+      }
+      epilogue(r, tile);
+    };
+    if (k < n_tiles) {
+      body(C1{}, std::true_type{}, k);
+      tail(C1{}, k);
+    } else {
+      tail(C0{}, k - 1);
+    }
+  } else if (!kPingPong) {
     // one wavefront per SIMD: compute tile k, then publish tile k+1
     TileAcc r;
     for (int k = 0; k < n_tiles; k += 2) {
