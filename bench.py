@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ring-gib", type=float, default=1.0, help="distinct latent bytes to cycle through")
     ap.add_argument("--opt", action="append", default=[], help="tuning knob name=value (palu_set_option)")
+    ap.add_argument("--no-rope", action="store_true",
+                    help="the paper's non-RoPE attention (rope_theta = 0): the query is folded into the latent "
+                         "space and the scores come straight from the key latents")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="after the timed region also run a plain device copy of this size three times: "
                          "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -99,12 +102,15 @@ def main() -> int:
     t0 = time.time()
     from workloads import synth
     layer = synth.config_layer(base_cfg.split("-")[0])
+    if args.no_rope:
+        import dataclasses
+        layer = dataclasses.replace(layer, rope_theta=0.0)
     batch, seq = synth.FULL_SIZES[base_cfg]
     work = algorithmic_work(layer, batch, seq, k_i4, v_i4)
     set_bytes = batch * seq * (layer.R_k + layer.R_v) * 2
     free_b = torch.cuda.mem_get_info()[0]
     n_sets = max(1, min(int(np.ceil(args.ring_gib * 2 ** 30 / set_bytes)) + 1, int(0.5 * free_b / set_bytes)))
-    case = wd.make_device_case(base_cfg, seed=0, dtype="f16", n_sets=n_sets)
+    case = wd.make_device_case(base_cfg, seed=0, dtype="f16", n_sets=n_sets, layer=layer)
     log(f"[bench] config {cfg}: batch {batch} seq {seq} groups {layer.n_groups} R_k {layer.R_k} R_v {layer.R_v}; "
         f"{n_sets} cache sets of {set_bytes / 2**20:.0f} MiB built in {time.time() - t0:.1f}s")
 
@@ -222,7 +228,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f16" if not (k_i4 or v_i4) else ("i4+f16" if k_i4 else "f16 keys, i4 values"),
         "data": "synthetic",
-        "config": {"workload": f"config {cfg}: Llama-2-7B-shaped layer decode, batch {batch}, seq {seq}, "
+        "config": {"workload": f"config {cfg}{' without RoPE' if args.no_rope else ''}: Llama-2-7B-shaped layer decode, batch {batch}, seq {seq}, "
                                f"{layer.n_groups} groups, R_k {layer.R_k}, R_v {layer.R_v}",
                    "batch": batch, "seq_len": seq, "n_heads": layer.n_heads, "group_size": layer.group_size(0),
                    "cache_sets": n_sets, "step": "encode K + encode V (+ quantize) + attn_decode"},
@@ -254,11 +260,18 @@ def main() -> int:
         torch.cuda.synchronize()
         log(f"[bench] copy probe: 3 device copies of {args.copy_probe} MiB (reads and writes that many bytes each)")
 
+    if args.no_rope:        # no reconstruction: the score kernel is a latent-streaming matrix-vector product
+        result["roofline"] = {
+            "kernel": "qk_kernel (folded query x key latents)", "bound": "hbm", "achieved": k_gbs, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": k_gbs / HBM_PEAK_GBS, "traffic": None, "launch_us": stage_us["score"],
+            "bytes_per_launch": work["k_latent_bytes"],
+        }
+
     # measured HBM traffic per launch of the dominant kernel, from counter runs kept under profiles/
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
             tr = json.load(f).get(cfg)
-        if tr:
+        if tr and not args.no_rope:
             result["roofline"]["traffic"] = tr["score_kernel_bytes"]
             result["roofline_value"]["traffic"] = tr["value_kernel_bytes"]
     except OSError:

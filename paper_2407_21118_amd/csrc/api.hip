@@ -6,6 +6,7 @@
 #include "score.hip"
 #include "value.hip"
 #include "pv.hip"
+#include "qk.hip"
 
 #include <atomic>
 #include <cmath>
@@ -260,13 +261,65 @@ int plan_pv(const Meta& m, PvPlan* p) {
   return PALU_OK;
 }
 
+// Units of the no-RoPE score kernel: the value kernel's merging rule for small
+// groups; a larger group is one unit with all its columns (32 heads at a time).
+struct QkPlan {
+  int total_units;
+  QkUnit units[kMaxPlanUnits];
+  long long qt_elems, qs_elems;    // per sequence
+  size_t max_lds[2];               // staged folded-query bytes of the largest unit, per head-tile class
+};
+
+int plan_qk(const Meta& m, QkPlan* p) {
+  p->total_units = 0;
+  p->qt_elems = p->qs_elems = 0;
+  p->max_lds[0] = p->max_lds[1] = 0;
+  auto add = [&](int h0, int nh, int c0, int ncols) -> int {
+    if (p->total_units >= kMaxPlanUnits) return PALU_ERR_UNSUPPORTED;
+    QkUnit& x = p->units[p->total_units++];
+    x.c0 = c0; x.h0 = (uint16_t)h0; x.ncols = (uint16_t)ncols; x.nh = (uint8_t)nh; x.pad = 0;
+    x.wpad = (uint16_t)(ceil_div(ncols, 256) * 256);
+    x.q_off = (int32_t)p->qt_elems;
+    x.qs_off = (int32_t)p->qs_elems;
+    p->qt_elems += (long long)nh * x.wpad;
+    p->qs_elems += (long long)nh * (x.wpad >> 7);
+    size_t& lds = p->max_lds[nh > 16 ? 1 : 0];
+    lds = std::max(lds, (size_t)nh * (x.wpad + 8) * 2);
+    return PALU_OK;
+  };
+  int st;
+  for (int j = 0; j < m.n_groups;) {
+    const int s = m.head_off[j + 1] - m.head_off[j];
+    const int r = m.k_off[j + 1] - m.k_off[j];
+    if (s <= 4 && r <= 256) {
+      int heads = s, cols = r, j1 = j + 1;
+      while (j1 < m.n_groups && heads + (m.head_off[j1 + 1] - m.head_off[j1]) <= 4 &&
+             cols + (m.k_off[j1 + 1] - m.k_off[j1]) <= 256) {
+        heads += m.head_off[j1 + 1] - m.head_off[j1];
+        cols += m.k_off[j1 + 1] - m.k_off[j1];
+        ++j1;
+      }
+      if ((st = add(m.head_off[j], heads, m.k_off[j], cols)) != PALU_OK) return st;
+      j = j1;
+      continue;
+    }
+    for (int u0 = 0; u0 < s; u0 += 32)
+      if ((st = add(m.head_off[j] + u0, std::min(32, s - u0), m.k_off[j], r)) != PALU_OK) return st;
+    ++j;
+  }
+  return PALU_OK;
+}
+
+// Wavefronts per compute unit the value kernel's splits aim at.
+inline int value_waves_per_cu(const palu_layer_desc*) { return 4; }
+
 // Tokens per value split and number of splits for a given attended length: a
 // split is one wavefront's share; aim at four wavefronts per compute unit,
 // splits of 64 to 512 tokens (more where the merge kernel's split limit asks for it).
 constexpr int kPvSplitMin = 64, kPvSplitMax = 512;
-void split_geometry(int total_units, int batch, int seq_len, int* split_tokens, int* n_split) {
+void split_geometry(int total_units, int batch, int seq_len, int waves_per_cu, int* split_tokens, int* n_split) {
   const long long items = std::max(1, total_units * batch);
-  long long st = ceil_div((int)std::min<long long>(items * seq_len / (4LL * device_cu_count()) + 1, 1 << 30), 32) * 32LL;
+  long long st = ceil_div((int)std::min<long long>(items * seq_len / ((long long)waves_per_cu * device_cu_count()) + 1, 1 << 30), 32) * 32LL;
   st = std::min<long long>(std::max<long long>(st, kPvSplitMin), kPvSplitMax);
   if (g_opt_value_split > 0) st = g_opt_value_split;
   st = std::max<long long>(st, ceil_div(ceil_div(seq_len, kMaxSplits), 32) * 32LL);
@@ -274,14 +327,14 @@ void split_geometry(int total_units, int batch, int seq_len, int* split_tokens, 
   *n_split = ceil_div(seq_len, (int)st);
 }
 // Upper bound of the number of splits of any attended length up to max_seq.
-int split_bound(int total_units, int batch, int max_seq) {
-  int cap = std::max(ceil_div(4 * device_cu_count(), std::max(1, total_units * batch)), ceil_div(max_seq, kPvSplitMax));
+int split_bound(int total_units, int batch, int max_seq, int waves_per_cu) {
+  int cap = std::max(ceil_div(waves_per_cu * device_cu_count(), std::max(1, total_units * batch)), ceil_div(max_seq, kPvSplitMax));
   if (g_opt_value_split > 0) cap = std::max(cap, ceil_div(max_seq, (int)g_opt_value_split));
   return std::min(cap, kMaxSplits) + 2;
 }
 
 struct Workspace {
-  size_t mfold, scores, o_part, ml_part, rope_rows, total;
+  size_t mfold, scores, o_part, ml_part, rope_rows, qsum, total;
   int lpad, o_stride;
   long long mfold_bstride, part_stride;
 };
@@ -297,6 +350,7 @@ int carve(const Meta& m, int batch, int max_seq, int n_split_cap, int n_parts, W
   w->o_part = off;  off = align_up(off + (size_t)batch * n_split_cap * w->o_stride * 4);
   w->ml_part = off; off = align_up(off + (size_t)batch * n_split_cap * m.n_heads * 2 * 4);
   w->rope_rows = off; off = align_up(off + (size_t)w->lpad * PALU_D_HEAD * 2);   // cos/sin rows gathered by k_pos
+  w->qsum = off; off = align_up(off + (size_t)batch * m.n_heads * (PALU_MAX_RANK / 128 + 2) * 4);   // int4 block sums of the folded queries (no-RoPE path)
   w->total = off;
   return PALU_OK;
 }
@@ -551,7 +605,7 @@ int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch,
   if ((st = plan_score(m, &sp)) != PALU_OK) return st;
   if ((st = plan_pv(m, &pp)) != PALU_OK) return st;
   Workspace w;
-  carve(m, batch, max_seq, split_bound(pp.total_units, batch, max_seq), 2 * sp.max_slices, &w);
+  carve(m, batch, max_seq, split_bound(pp.total_units, batch, max_seq, value_waves_per_cu(desc)), 2 * sp.max_slices, &w);
   *out_bytes = w.total;
   return PALU_OK;
 }
@@ -598,9 +652,9 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
   if ((st = plan_pv(m, &pp)) != PALU_OK) return st;
   const int quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
   int split_tokens, n_split;
-  split_geometry(pp.total_units, batch, seq_len, &split_tokens, &n_split);
+  split_geometry(pp.total_units, batch, seq_len, value_waves_per_cu(desc), &split_tokens, &n_split);
   if (n_split > kMaxSplits) return PALU_ERR_UNSUPPORTED;
-  const int n_split_cap = split_bound(pp.total_units, batch, max_seq);
+  const int n_split_cap = split_bound(pp.total_units, batch, max_seq, value_waves_per_cu(desc));
   Workspace w;
   carve(m, batch, max_seq, n_split_cap, 2 * sp.max_slices, &w);
   if (n_split > n_split_cap) return PALU_ERR_INVALID_ARG;
@@ -618,103 +672,189 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     for (int i = 0; i <= PALU_DECODE_STAGES; ++i)
       if (!stage_events[i]) return PALU_ERR_INVALID_ARG;
 
-  // 1. fold the rotated query into B_k
-  {
-    FoldArgs a;
-    a.q = static_cast<const uint16_t*>(q);
-    a.q_pos = q_pos;
-    a.Bk = static_cast<const uint16_t*>(Bk);
-    a.mfold = reinterpret_cast<uint16_t*>(ws + w.mfold);
-    a.mfold_bstride = w.mfold_bstride;
-    a.theta = desc->rope_theta;
-    for (int f = 0; f < kHalf; ++f) {
-      const double rev = desc->rope_theta > 0.f
-          ? std::pow((double)desc->rope_theta, -2.0 * f / (double)PALU_D_HEAD) / 6.283185307179586476925 : 0.0;
-      a.rev_hi[f] = (float)rev;
-      a.rev_lo[f] = (float)(rev - (double)a.rev_hi[f]);
-    }
-    a.meta = m;
-    int max_r = 0;
-    for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
-    const dim3 g((unsigned)(max_r / 16), (unsigned)m.n_heads, (unsigned)batch);
-    if ((st = mark(0)) != PALU_OK) return st;
-    if (act == PALU_F16) hipLaunchKernelGGL(fold_kernel<F16>, g, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
-    if ((st = launch_ok()) != PALU_OK) return st;
-  }
-
-  // 2. scores
-  {
-    ScoreArgs a;
+  const bool no_rope = !(desc->rope_theta > 0.f);
+  if (no_rope) {
+    // 1'. fold the query into the latent space (Eq. 5); 2'. scores straight from the latents
+    QkPlan qp;
+    if ((st = plan_qk(m, &qp)) != PALU_OK) return st;
+    if (qp.qt_elems > w.mfold_bstride) return PALU_ERR_UNSUPPORTED;     // the folded queries reuse the folded-weight region
+    QfoldArgs f;
+    f.q = static_cast<const uint16_t*>(q);
+    f.Bk = static_cast<const uint16_t*>(Bk);
+    f.qt = reinterpret_cast<uint16_t*>(ws + w.mfold);
+    f.qsum = reinterpret_cast<float*>(ws + w.qsum);
+    f.qt_bstride = w.mfold_bstride;
+    f.qs_bstride = (long long)m.n_heads * (PALU_MAX_RANK / 128 + 2);
+    if (qp.qs_elems > f.qs_bstride) return PALU_ERR_UNSUPPORTED;
+    f.meta = m;
+    QkArgs a;
     a.hk = hk;
     a.hk_scale = static_cast<const uint16_t*>(hk_scale);
     a.hk_zero = static_cast<const uint16_t*>(hk_zero);
-    a.mfold = reinterpret_cast<const uint16_t*>(ws + w.mfold);
-    a.rope_rows = static_cast<const uint16_t*>(rope_table);
+    a.qt = f.qt;
+    a.qsum = f.qsum;
     a.seq_lens = seq_lens;
     a.scores = reinterpret_cast<float*>(ws + w.scores);
-    a.mfold_bstride = w.mfold_bstride;
+    a.qt_bstride = f.qt_bstride;
+    a.qs_bstride = f.qs_bstride;
     a.row_elems = Rk;
     a.max_seq = max_seq;
     a.seq_len = seq_len;
     a.lpad = w.lpad;
     a.batch = batch;
     a.n_heads = m.n_heads;
-    a.quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
-    a.n_blocks_q = Rk / a.quant_block;
+    a.n_blocks_q = Rk / quant_block;
     a.scale = 1.4426950408889634f / std::sqrt((float)PALU_D_HEAD);
-    if ((st = mark(1)) != PALU_OK) return st;
-    if (k_pos) {
-      // cos/sin rows in cached-token order, so that the score kernel needs no position loads
-      RopeGatherArgs g;
-      g.table = static_cast<const uint16_t*>(rope_table);
-      g.k_pos = k_pos;
-      g.rows = reinterpret_cast<uint16_t*>(ws + w.rope_rows);
-      g.n = seq_len;
-      g.table_len = rope_table_len;
-      hipLaunchKernelGGL(rope_gather_kernel, dim3((unsigned)ceil_div(seq_len * 16, 256)), dim3(256), 0, s, g);
-      if ((st = launch_ok()) != PALU_OK) return st;
-      a.rope_rows = g.rows;
+    {   // tokens per wavefront: four wavefronts per compute unit, 64 to 512 tokens
+      const long long items = std::max(1, qp.total_units * batch);
+      const long long waves_per_cu = 4;
+      long long stq = ceil_div((int)std::min<long long>(items * seq_len / (waves_per_cu * device_cu_count()) + 1, 1 << 30), 32) * 32LL;
+      stq = std::min<long long>(std::max<long long>(stq, kPvSplitMin), kPvSplitMax);
+      a.split_tokens = (int)stq;
+      a.n_split = ceil_div(seq_len, (int)stq);
     }
-    const int tiles = ceil_div(seq_len, kTile);
-    // Sequence chunks per (sequence, unit): every launch (one per rank class) should fill
-    // the chip by itself, since launches on one stream run one after the other.
-    auto set_chunks = [&](int launch_units) {
-      int n_chunks = std::max(1, std::min(tiles, (int)std::lround((double)device_cu_count() / (launch_units * batch))));
-      if (g_opt_score_chunks > 0) n_chunks = std::min(tiles, (int)g_opt_score_chunks);
-      // the kernel addresses a chunk of the cache with 32-bit byte offsets
-      const long long chunk_limit_tiles = std::max(1LL, (1LL << 31) / ((long long)Rk * 2 * kTile));
-      n_chunks = std::max(n_chunks, (int)ceil_div(tiles, (int)std::min<long long>(chunk_limit_tiles, tiles)));
-      const int chunk_tiles = ceil_div(tiles, n_chunks);
-      a.chunk_tokens = chunk_tiles * kTile;
-      a.n_chunks = ceil_div(tiles, chunk_tiles);
-    };
-    for (int cls = 0; cls < sp.n_cls; ++cls) {
-      const int id = sp.cls_id[cls];
-      const int rc = id / 3, lg = id % 3;
-      const int width = (32 * (rc + 1)) << lg;
-      const bool dma = act == PALU_F16 && !k_i4;
-      const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width);
-      ScoreFn fn = score_fn(act, k_i4, id, waves8);
+    if ((st = mark(0)) != PALU_OK) return st;
+    f.batch = batch;
+    for (int i0 = 0; i0 < qp.total_units; i0 += kMaxQkUnits) {     // launches of up to 64 units; heads of other units idle
+      f.units.n_units = std::min(kMaxQkUnits, qp.total_units - i0);
+      int wmax = 0, h_lo = m.n_heads, h_hi = 0;
+      std::memset(f.unit_of_head, 0, sizeof(f.unit_of_head));
+      for (int i = 0; i < f.units.n_units; ++i) {
+        const QkUnit& x = f.units.u[i] = qp.units[i0 + i];
+        wmax = std::max(wmax, (int)x.wpad);
+        for (int h = x.h0; h < x.h0 + x.nh; ++h) f.unit_of_head[h] = (uint8_t)i;
+        h_lo = std::min(h_lo, (int)x.h0);
+        h_hi = std::max(h_hi, x.h0 + x.nh);
+      }
+      f.head0 = h_lo;
+      const dim3 g((unsigned)(wmax / 128), (unsigned)(h_hi - h_lo));
+      if (act == PALU_F16) hipLaunchKernelGGL(qfold_kernel<F16>, g, dim3(256), 0, s, f);
+      else hipLaunchKernelGGL(qfold_kernel<BF16>, g, dim3(256), 0, s, f);
+      if ((st = launch_ok()) != PALU_OK) return st;
+    }
+    if ((st = mark(1)) != PALU_OK) return st;
+    for (int cls = 0; cls < 2; ++cls) {              // 0: up to 16 heads per unit, 1: up to 32
+      using QkFn = void (*)(QkArgs);
+      QkFn fn = k_i4 ? (cls ? qk_kernel<F16, 2, true> : qk_kernel<F16, 1, true>)
+                     : act == PALU_F16 ? (cls ? qk_kernel<F16, 2, false> : qk_kernel<F16, 1, false>)
+                                       : (cls ? qk_kernel<BF16, 2, false> : qk_kernel<BF16, 1, false>);
+      const size_t lds = qp.max_lds[cls];
+      if (lds == 0) continue;
       if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
-      const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
       auto flush = [&]() -> int {
         if (a.units.n_units == 0) return PALU_OK;
-        set_chunks(a.units.n_units);
-        const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
-        a.unit_fastest = g_opt_score_order == 2;
-        a.early_start = g_opt_score_early;
-        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
+        const unsigned grid = (unsigned)(a.units.n_units * ceil_div(a.n_split, 4) * batch);
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(256), lds, s, a);
         a.units.n_units = 0;
         return launch_ok();
       };
       a.units.n_units = 0;
-      for (int i = 0; i < sp.total_units; ++i) {
-        if (sp.unit_cls[i] != cls) continue;
-        a.units.u[a.units.n_units++] = sp.units[i];
-        if (a.units.n_units == kMaxScoreUnits && (st = flush()) != PALU_OK) return st;
+      for (int i = 0; i < qp.total_units; ++i) {
+        if ((qp.units[i].nh > 16 ? 1 : 0) != cls) continue;
+        a.units.u[a.units.n_units++] = qp.units[i];
+        if (a.units.n_units == kMaxQkUnits && (st = flush()) != PALU_OK) return st;
       }
       if ((st = flush()) != PALU_OK) return st;
+    }
+  } else {
+    // 1. fold the rotated query into B_k
+    {
+      FoldArgs a;
+      a.q = static_cast<const uint16_t*>(q);
+      a.q_pos = q_pos;
+      a.Bk = static_cast<const uint16_t*>(Bk);
+      a.mfold = reinterpret_cast<uint16_t*>(ws + w.mfold);
+      a.mfold_bstride = w.mfold_bstride;
+      a.theta = desc->rope_theta;
+      for (int f = 0; f < kHalf; ++f) {
+        const double rev = desc->rope_theta > 0.f
+            ? std::pow((double)desc->rope_theta, -2.0 * f / (double)PALU_D_HEAD) / 6.283185307179586476925 : 0.0;
+        a.rev_hi[f] = (float)rev;
+        a.rev_lo[f] = (float)(rev - (double)a.rev_hi[f]);
+      }
+      a.meta = m;
+      int max_r = 0;
+      for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
+      const dim3 g((unsigned)(max_r / 16), (unsigned)m.n_heads, (unsigned)batch);
+      if ((st = mark(0)) != PALU_OK) return st;
+      if (act == PALU_F16) hipLaunchKernelGGL(fold_kernel<F16>, g, dim3(256), 0, s, a);
+      else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
+      if ((st = launch_ok()) != PALU_OK) return st;
+    }
+
+    // 2. scores
+    {
+      ScoreArgs a;
+      a.hk = hk;
+      a.hk_scale = static_cast<const uint16_t*>(hk_scale);
+      a.hk_zero = static_cast<const uint16_t*>(hk_zero);
+      a.mfold = reinterpret_cast<const uint16_t*>(ws + w.mfold);
+      a.rope_rows = static_cast<const uint16_t*>(rope_table);
+      a.seq_lens = seq_lens;
+      a.scores = reinterpret_cast<float*>(ws + w.scores);
+      a.mfold_bstride = w.mfold_bstride;
+      a.row_elems = Rk;
+      a.max_seq = max_seq;
+      a.seq_len = seq_len;
+      a.lpad = w.lpad;
+      a.batch = batch;
+      a.n_heads = m.n_heads;
+      a.quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
+      a.n_blocks_q = Rk / a.quant_block;
+      a.scale = 1.4426950408889634f / std::sqrt((float)PALU_D_HEAD);
+      if ((st = mark(1)) != PALU_OK) return st;
+      if (k_pos) {
+        // cos/sin rows in cached-token order, so that the score kernel needs no position loads
+        RopeGatherArgs g;
+        g.table = static_cast<const uint16_t*>(rope_table);
+        g.k_pos = k_pos;
+        g.rows = reinterpret_cast<uint16_t*>(ws + w.rope_rows);
+        g.n = seq_len;
+        g.table_len = rope_table_len;
+        hipLaunchKernelGGL(rope_gather_kernel, dim3((unsigned)ceil_div(seq_len * 16, 256)), dim3(256), 0, s, g);
+        if ((st = launch_ok()) != PALU_OK) return st;
+        a.rope_rows = g.rows;
+      }
+      const int tiles = ceil_div(seq_len, kTile);
+      // Sequence chunks per (sequence, unit): every launch (one per rank class) should fill
+      // the chip by itself, since launches on one stream run one after the other.
+      auto set_chunks = [&](int launch_units) {
+        int n_chunks = std::max(1, std::min(tiles, (int)std::lround((double)device_cu_count() / (launch_units * batch))));
+        if (g_opt_score_chunks > 0) n_chunks = std::min(tiles, (int)g_opt_score_chunks);
+        // the kernel addresses a chunk of the cache with 32-bit byte offsets
+        const long long chunk_limit_tiles = std::max(1LL, (1LL << 31) / ((long long)Rk * 2 * kTile));
+        n_chunks = std::max(n_chunks, (int)ceil_div(tiles, (int)std::min<long long>(chunk_limit_tiles, tiles)));
+        const int chunk_tiles = ceil_div(tiles, n_chunks);
+        a.chunk_tokens = chunk_tiles * kTile;
+        a.n_chunks = ceil_div(tiles, chunk_tiles);
+      };
+      for (int cls = 0; cls < sp.n_cls; ++cls) {
+        const int id = sp.cls_id[cls];
+        const int rc = id / 3, lg = id % 3;
+        const int width = (32 * (rc + 1)) << lg;
+        const bool dma = act == PALU_F16 && !k_i4;
+        const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width);
+        ScoreFn fn = score_fn(act, k_i4, id, waves8);
+        if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
+        const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
+        auto flush = [&]() -> int {
+          if (a.units.n_units == 0) return PALU_OK;
+          set_chunks(a.units.n_units);
+          const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
+          a.unit_fastest = g_opt_score_order == 2;
+          a.early_start = g_opt_score_early;
+          hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
+          a.units.n_units = 0;
+          return launch_ok();
+        };
+        a.units.n_units = 0;
+        for (int i = 0; i < sp.total_units; ++i) {
+          if (sp.unit_cls[i] != cls) continue;
+          a.units.u[a.units.n_units++] = sp.units[i];
+          if (a.units.n_units == kMaxScoreUnits && (st = flush()) != PALU_OK) return st;
+        }
+        if ((st = flush()) != PALU_OK) return st;
+      }
     }
   }
 
@@ -723,7 +863,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
   std::memset(n_parts, 0, sizeof(n_parts));
   int max_parts = 0;
   for (int h = 0; h < m.n_heads; ++h) {      // half-head wavefronts write two planes per rank slice
-    n_parts[h] = (uint8_t)((waves8 || sp.half_heads[h]) ? 2 * sp.slices[h] : sp.slices[h]);
+    n_parts[h] = no_rope ? (uint8_t)1 : (uint8_t)((waves8 || sp.half_heads[h]) ? 2 * sp.slices[h] : sp.slices[h]);
     max_parts = std::max(max_parts, (int)n_parts[h]);
   }
   if ((st = mark(2)) != PALU_OK) return st;

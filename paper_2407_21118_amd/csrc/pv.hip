@@ -343,22 +343,19 @@ __global__ __launch_bounds__(256) void pv_kernel(PvArgs a) {
     }
   };
 
-  // ---- two sets of registers in turn; the next set's loads are in flight while one is consumed
-  Set sa, sb;
-  issue(sa, 0);
-  int k = 0;
-  for (; k + 2 < n_sets; k += 2) {
-    issue(sb, k + 1);
-    process(sa, k);
-    issue(sa, k + 2);
-    process(sb, k + 1);
-  }
-  if (k + 1 < n_sets) {
-    issue(sb, k + 1);
-    process(sa, k);
-    process(sb, k + 1);
-  } else {
-    process(sa, k);
+  // ---- a ring of register sets: the loads of the next kDepth-1 sets are in flight while
+  // one is consumed.
+  // Requests past the last set re-read its rows and are never consumed.
+  constexpr int kDepth = 2;
+  Set ring[kDepth];
+#pragma unroll
+  for (int d = 0; d < kDepth - 1; ++d) issue(ring[d], d);
+  for (int k = 0; k < n_sets; k += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      issue(ring[(d + kDepth - 1) % kDepth], k + d + kDepth - 1);
+      if (k + d < n_sets) process(ring[d], k + d);
+    }
   }
 
   // ---- results of the split

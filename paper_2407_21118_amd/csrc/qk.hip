@@ -1,0 +1,333 @@
+// Scores without positional rotation (Sec. 3.1.2, Eq. 5): with no RoPE between
+// the reconstruction and the query product, B_k moves to the query side,
+//   q K^T = q (H_k B_k)^T = (q B_k^T) H_k^T,
+// so the keys are never rebuilt: one small kernel folds the query into the
+// latent space and the score is a matrix-vector product over the latents,
+// bound by the latent stream alone (2 FLOP per latent element and head).
+//
+//   qfold_kernel  qt[b, unit][head, column] = q[b, head] . B_k[column, head's 128 features]
+//                 for the columns of the head's own group, 0 elsewhere
+//   qk_kernel     scores[b, head, t] = H_k[b, t, unit columns] . qt[b, unit][head, :] * log2(e)/sqrt(d_h)
+//
+// qk_kernel: one wavefront owns a range of tokens of one (sequence, unit) and
+// shares nothing with the others after the folded query has been staged in
+// LDS.  v_mfma_f32_16x16x32_f16 with A = folded queries (rows = heads) and
+// B = latents (k = latent channels, columns = 16 tokens): the contraction runs
+// over the contiguous dimension of the cache, so a lane's 16-byte load is its
+// operand as it stands.  Units are the value kernel's: up to 256 latent columns
+// of up to 4 heads from adjacent small groups (the folded query is then block
+// diagonal), or one whole group of up to 32 heads, walked in chunks of 256 columns.
+//
+// 4-bit latents: a lane's 16-byte load holds the 32 codes of a quarter of a
+// quantization block; the codes enter the matrix cores as exact fp16 integers and
+// the scale and zero-point are applied to the block's sum per token:
+//   sum_k s (c_k - z) qt_k = s (sum_k c_k qt_k - z sum_k qt_k).
+
+#include "palu_dev.h"
+
+namespace palu {
+
+struct QkUnit {
+  int32_t c0;          // first latent column
+  int32_t q_off;       // element offset of the unit's [nh][wpad] folded-query matrix (per sequence)
+  int32_t qs_off;      // float offset of its [nh][wpad / 128] block sums (int4)
+  uint16_t h0;
+  uint16_t ncols;      // multiple of 32
+  uint16_t wpad;       // ncols rounded up to a multiple of 256: columns of the staged matrix
+  uint8_t nh;          // at most 32
+  uint8_t pad;
+};
+constexpr int kMaxQkUnits = 64;
+struct QkUnits {
+  int n_units;
+  QkUnit u[kMaxQkUnits];
+};
+
+struct QfoldArgs {
+  const uint16_t* q;         // [batch, n_heads, 128]
+  const uint16_t* Bk;
+  uint16_t* qt;              // fp16 folded queries, per sequence stride qt_bstride
+  float* qsum;               // per sequence stride qs_bstride
+  long long qt_bstride, qs_bstride;
+  int batch;
+  int head0;                              // first head of this launch (blockIdx.y = head - head0)
+  uint8_t unit_of_head[PALU_MAX_HEADS];   // index into units
+  Meta meta;
+  QkUnits units;
+};
+
+struct QkArgs {
+  const void* hk;
+  const uint16_t* hk_scale;
+  const uint16_t* hk_zero;
+  const uint16_t* qt;
+  const float* qsum;
+  const int32_t* seq_lens;
+  float* scores;             // plane 0: [batch][n_heads][lpad]
+  long long qt_bstride, qs_bstride;
+  long long row_elems;       // R_k
+  long long max_seq;
+  int seq_len;
+  int lpad;
+  int batch;
+  int n_heads;
+  int split_tokens;          // tokens per wavefront (multiple of 32)
+  int n_split;
+  int n_blocks_q;
+  float scale;               // log2(e) / sqrt(d_h)
+  QkUnits units;
+};
+
+// grid (wpad_max / 128, heads of the launch), 256 threads: a workgroup fills 128 columns of
+// one head's row for every sequence of the batch; thread = (column, half of the
+// features).  The B_k values are loaded once and reused for all sequences.
+template <typename T>
+__global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
+  __shared__ float blk[4];
+  const Meta& m = a.meta;
+  const int h = a.head0 + blockIdx.y;
+  const QkUnit u = a.units.u[a.unit_of_head[h]];
+  const int hh = h - u.h0;
+  const int col0 = blockIdx.x * 128;
+  if (col0 >= u.wpad) return;
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const int c = col0 + (tid >> 1);               // column inside the unit
+  const int fh = (tid & 1) * 64;                  // first of this thread's 64 features
+  const int cabs = u.c0 + c;                      // latent column
+  const int j = m.group_of_head[h];
+  const bool mine = c < u.ncols && cabs >= m.k_off[j] && cabs < m.k_off[j + 1];   // the same for both threads of a column
+  uint4v bw[8];
+#pragma unroll
+  for (int x = 0; x < 8; ++x) bw[x] = uint4v{0, 0, 0, 0};
+  if (mine) {
+    const int width = (m.head_off[j + 1] - m.head_off[j]) * kDHead;
+    const uint16_t* Brow = a.Bk + m.bk_off[j] + (size_t)(cabs - m.k_off[j]) * width + (h - m.head_off[j]) * kDHead + fh;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) bw[x] = *reinterpret_cast<const uint4v*>(Brow + 8 * x);
+  }
+  for (int b = 0; b < a.batch; ++b) {
+    const uint16_t* qp = a.q + ((size_t)b * m.n_heads + h) * kDHead + fh;
+    float s = 0.f;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const uint4v qw = *reinterpret_cast<const uint4v*>(qp + 8 * x);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s = fmaf(T::to_float((uint16_t)(qw[e] & 0xffffu)), T::to_float((uint16_t)(bw[x][e] & 0xffffu)), s);
+        s = fmaf(T::to_float((uint16_t)(qw[e] >> 16)), T::to_float((uint16_t)(bw[x][e] >> 16)), s);
+      }
+    }
+    s += __shfl_xor(s, 1, 64);
+    const uint16_t hv = F16::from_float(s);        // the contraction runs in fp16 whatever the storage type
+    if ((tid & 1) == 0) a.qt[(size_t)b * a.qt_bstride + u.q_off + (size_t)hh * u.wpad + c] = hv;
+    // sum of the rounded values over this 128-column block (int4 zero-point term)
+    float r = (tid & 1) == 0 ? F16::to_float(hv) : 0.f;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) r += __shfl_xor(r, off, 64);
+    __syncthreads();                               // the previous sequence's sum has been read
+    if ((tid & 63) == 0) blk[wave] = r;
+    __syncthreads();
+    if (tid == 0)
+      a.qsum[(size_t)b * a.qs_bstride + u.qs_off + (size_t)hh * (u.wpad >> 7) + blockIdx.x] = (blk[0] + blk[1]) + (blk[2] + blk[3]);
+  }
+}
+
+// T:  storage type of unquantized latents (bfloat16 converted to fp16 in registers)
+// MT: 16-row head tiles (1: up to 16 heads, 2: up to 32)
+// I4: latents are 4-bit codes
+template <typename T, int MT, bool I4>
+__global__ __launch_bounds__(256) void qk_kernel(QkArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char qk_lds[];
+  constexpr bool kIsBf16 = !__is_same(T, F16);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 15, kq = lane >> 4;       // token column (B, D) or head row (A); quarter of the 32 channels of a k-step
+
+  int wg = blockIdx.x;
+  const int unit = wg % a.units.n_units;
+  wg /= a.units.n_units;
+  const int n_sg = (a.n_split + 3) >> 2;
+  const int sg = wg % n_sg;
+  const int b = wg / n_sg;
+  const QkUnit u = a.units.u[unit];
+  const int nh = u.nh, wpad = u.wpad;
+  const int pitch = wpad + 8;                    // halfs per staged row: 16 bytes of padding keep the 16 head rows on distinct banks
+
+  // ---- folded queries of the unit -> LDS (rows of heads beyond nh are never read: their lanes re-read row nh-1)
+  {
+    const uint16_t* src = a.qt + (size_t)b * a.qt_bstride + u.q_off;
+    const int cpr = wpad >> 3;                   // 16-byte chunks per row
+    for (int i = tid; i < nh * cpr; i += 256) {
+      const int r = i / cpr, cc = i - r * cpr;
+      *reinterpret_cast<uint4v*>(qk_lds + ((size_t)r * pitch + cc * 8) * 2) = *reinterpret_cast<const uint4v*>(src + (size_t)r * wpad + cc * 8);
+    }
+  }
+  __syncthreads();
+
+  const int split = sg * 4 + wave;
+  const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
+  const int s0 = split * a.split_tokens;
+  if (split >= a.n_split || s0 >= L) return;     // whole wavefront; no barrier below
+  const int ntok = min(a.split_tokens, L - s0);
+  const int n_sets = (ntok + 31) >> 5;           // 32 tokens: two tiles of 16
+  const int last = ntok - 1;
+  const int n_chunks = wpad >> 8;                // chunks of 256 columns
+  const int ncols = u.ncols;
+
+  const size_t row0 = (size_t)b * a.max_seq + s0;
+  const unsigned row_bytes = I4 ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
+  const unsigned char* base = (const unsigned char*)a.hk + row0 * row_bytes + (I4 ? u.c0 / 2 : u.c0 * 2);
+  const size_t sz_idx0 = I4 ? row0 * a.n_blocks_q + (u.c0 >> 7) : 0;
+  const int n_blk = (ncols + 127) >> 7;
+
+  constexpr int NL = I4 ? 2 : 8;                 // 16-byte loads per tile and chunk: int4 one per 128-column block, else one per 32 columns
+  struct Step {
+    uint4v h[2][NL];
+    uint32_t sz[2][I4 ? 2 : 1];                  // int4: scale | zero << 16 of (tile token, block)
+  };
+  // loads of (set, chunk); clamped to the last token / last valid columns (whose folded query is zero-padded)
+  auto issue = [&](Step& st, int set, int chunk) {
+#pragma unroll
+    for (int tau = 0; tau < 2; ++tau) {
+      const unsigned t = (unsigned)min(set * 32 + tau * 16 + n, last);
+#pragma unroll
+      for (int x = 0; x < NL; ++x) {
+        unsigned off;
+        if (I4) {
+          const int blkc = min(chunk * 2 + x, n_blk - 1);
+          off = (unsigned)blkc * 64u + (unsigned)kq * 16u;
+          const size_t idx = sz_idx0 + (size_t)t * a.n_blocks_q + blkc;
+          st.sz[tau][x] = (uint32_t)a.hk_scale[idx] | ((uint32_t)a.hk_zero[idx] << 16);
+        } else {
+          const int col = min(chunk * 256 + x * 32 + kq * 8, ncols - 8);
+          off = (unsigned)col * 2u;
+        }
+        st.h[tau][x] = *reinterpret_cast<const uint4v*>(base + (size_t)(t * row_bytes + off));
+      }
+    }
+  };
+
+  float4v acc[MT][2];
+  int qrow[MT];                                  // byte offset of this lane's head row in the staged matrix
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) qrow[mt] = min(mt * 16 + n, nh - 1) * pitch * 2;
+  const float* qs_base = a.qsum + (size_t)b * a.qs_bstride + u.qs_off;
+
+  auto process = [&](Step& st, int set, int chunk) {
+    if (chunk == 0) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int tau = 0; tau < 2; ++tau) acc[mt][tau] = float4v{0.f, 0.f, 0.f, 0.f};
+    }
+    if constexpr (!I4) {
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        half8 af[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) af[mt] = *reinterpret_cast<const half8*>(qk_lds + qrow[mt] + (chunk * 256 + x * 32 + kq * 8) * 2);
+#pragma unroll
+        for (int tau = 0; tau < 2; ++tau) {
+          uint4v hw = st.h[tau][x];
+          if constexpr (kIsBf16) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              hw[e] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__builtin_bit_cast(float, hw[e] << 16),
+                                                                              __builtin_bit_cast(float, hw[e] & 0xffff0000u)));
+          }
+          const half8 bop = __builtin_bit_cast(half8, hw);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[mt], bop, acc[mt][tau], 0, 0, 0);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {                // quantization block chunk*2 + x
+        const int blkc = min(chunk * 2 + x, n_blk - 1);
+        half8 af[MT][4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj)            // lane's codes 8jj .. 8jj+7 are channels blk*128 + kq*32 + 8jj ..
+            af[mt][jj] = *reinterpret_cast<const half8*>(qk_lds + qrow[mt] + ((chunk * 2 + x) * 128 + kq * 32 + jj * 8) * 2);
+        float4v qs[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            qs[mt][r] = qs_base[(size_t)min(mt * 16 + 4 * kq + r, nh - 1) * (wpad >> 7) + blkc];
+#pragma unroll
+        for (int tau = 0; tau < 2; ++tau) {
+          float4v d[MT];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) d[mt] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const uint32_t w = st.h[tau][x][jj];
+            const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;     // even / odd channels, one per byte
+            uint4v bw;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              // (even code, odd code) of byte e as the fp16 pair (1024 + c_even, 1024 + c_odd), then minus 1024
+              const uint32_t pr = __builtin_amdgcn_perm(hi, lo, 0x0c040c00u + 0x00010001u * e) | 0x64006400u;
+              bw[e] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, pr) - half2v{(_Float16)1024.f, (_Float16)1024.f});
+            }
+            const half8 bop = __builtin_bit_cast(half8, bw);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) d[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[mt][jj], bop, d[mt], 0, 0, 0);
+          }
+          const float sc = chunk * 2 + x < n_blk ? F16::to_float((uint16_t)(st.sz[tau][x] & 0xffffu)) : 0.f;
+          const float zp = F16::to_float((uint16_t)(st.sz[tau][x] >> 16));
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[mt][tau][r] = fmaf(sc, fmaf(-zp, qs[mt][r], d[mt][r]), acc[mt][tau][r]);
+        }
+      }
+    }
+    if (chunk == n_chunks - 1) {
+      // accumulator row 4*kq + r (+16 per tile of heads) = head of the unit, column n = token of the tile
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int hh = mt * 16 + 4 * kq + r;
+          if (hh >= nh) continue;
+          float* row = a.scores + ((size_t)b * a.n_heads + u.h0 + hh) * a.lpad + s0 + set * 32 + n;
+          row[0] = acc[mt][0][r] * a.scale;         // tokens past the end fall into the padding of the score row
+          row[16] = acc[mt][1][r] * a.scale;
+        }
+    }
+  };
+
+  // steps (set, chunk) in order through a ring of register sets: the loads of the next
+  // kDepth-1 steps are in flight while one is consumed.
+  // Requests past the last step re-read its rows and are never consumed.
+  constexpr int kDepth = 2;
+  const int n_steps = n_sets * n_chunks;
+  auto next = [&](int& set, int& chunk) { if (++chunk == n_chunks) { chunk = 0; ++set; } };
+  Step ring[kDepth];
+  int is = 0, ic = 0, ps = 0, pc = 0;            // next step to request / to consume
+#pragma unroll
+  for (int d = 0; d < kDepth - 1; ++d) { issue(ring[d], is, ic); next(is, ic); }
+  for (int k = 0; k < n_steps; k += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      issue(ring[(d + kDepth - 1) % kDepth], is, ic);
+      next(is, ic);
+      if (k + d < n_steps) { process(ring[d], ps, pc); next(ps, pc); }
+    }
+  }
+}
+
+template __global__ void qfold_kernel<F16>(QfoldArgs);
+template __global__ void qfold_kernel<BF16>(QfoldArgs);
+#define PALU_QK_INST(T, I4)                                   \
+  template __global__ void qk_kernel<T, 1, I4>(QkArgs);       \
+  template __global__ void qk_kernel<T, 2, I4>(QkArgs);
+PALU_QK_INST(F16, false)
+PALU_QK_INST(BF16, false)
+PALU_QK_INST(F16, true)
+
+}  // namespace palu

@@ -97,9 +97,17 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   constexpr int kAheadTiles = kBufs - 1;
   constexpr int kInFlight = kBufs - 2;
   // LDS-direct loads per wavefront and tile: one per latent row it owns, one per 4 cos/sin rows
+  // A masked LDS-direct load (fewer than 64 active lanes) costs about 50 cycles of
+  // issue, a full one about 6.  Rows of 32 chunks (512 bytes) are therefore requested
+  // two per instruction: the pair lies contiguously in LDS (pitch 2*512+32 bytes) and
+  // the odd row is stored rotated by one chunk, which keeps the 16-byte column reads
+  // of 16 consecutive tokens on distinct banks.
+  constexpr bool kPair = kDma && kCpr == 32;
+  constexpr int kPairB = 2 * kWidth * 2 + 2 * kRowPad;           // = 2 * kRowB: same tile size as the padded layout
   constexpr int kRowsPerWave = kTile / NW;
+  constexpr int kRowOps = kPair ? kRowsPerWave / 2 : kRowsPerWave;
   constexpr int kCsPerWave = kTile / 4 / NW;
-  constexpr int kDmaOps = kRowsPerWave + kCsPerWave;
+  constexpr int kDmaOps = kRowOps + kCsPerWave;
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // scalar: everything derived from it is uniform
@@ -155,9 +163,14 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   // Per-wavefront constants of its share of a tile, so that one request costs a
   // handful of scalar instructions: byte offsets of its rows inside a tile and,
   // per lane, of its pieces of the cos/sin rows.
-  unsigned dma_row_off[kRowsPerWave];
+  unsigned dma_row_off[kRowOps];                                // scalar (one row per request) or per lane (pairs)
+  unsigned dma_pair_col = 0;
 #pragma unroll
-  for (int x = 0; x < kRowsPerWave; ++x) dma_row_off[x] = (unsigned)(wave * kRowsPerWave + x) * row_bytes;
+  for (int x = 0; x < kRowOps; ++x) {
+    if (kPair) dma_row_off[x] = (unsigned)(2 * (wave * kRowOps + x) + (lane >> 5)) * row_bytes;
+    else dma_row_off[x] = (unsigned)(wave * kRowsPerWave + x) * row_bytes;
+  }
+  if (kPair) dma_pair_col = (unsigned)((lane + (lane >> 5)) & 31) * 16u;     // odd row: LDS slot j holds chunk j+1
   unsigned dma_cs_off[kCsPerWave], dma_cs_swz[kCsPerWave];
 #pragma unroll
   for (int x = 0; x < kCsPerWave; ++x) {
@@ -182,16 +195,22 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     d.m0 = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)((tile_unclamped % kBufs) * kBufB));
     return d;
   };
-  // op x of a tile: x < kRowsPerWave a latent row, else a quad of cos/sin rows
+  // op x of a tile: x < kRowOps a latent row (or pair of rows), else a quad of cos/sin rows
   auto dma_issue_op = [&](const DmaTile& d, int x) __attribute__((always_inline)) {
-    if (x < kRowsPerWave) {
-      const unsigned char* src = d.src + min(dma_row_off[x], d.lim);        // scalar address
-      const unsigned m0v = d.m0 + (unsigned)((wave * kRowsPerWave + x) * kRowB);
-      const unsigned voff = (unsigned)lane * 16u;
-      if (kCpr == 64 || lane < kCpr)
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(src) : "memory");
+    if (x < kRowOps) {
+      if constexpr (kPair) {
+        const unsigned voff = min(dma_row_off[x], d.lim) + dma_pair_col;
+        const unsigned m0v = d.m0 + (unsigned)((wave * kRowOps + x) * kPairB);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(d.src) : "memory");
+      } else {
+        const unsigned char* src = d.src + min(dma_row_off[x], d.lim);        // scalar address
+        const unsigned m0v = d.m0 + (unsigned)((wave * kRowsPerWave + x) * kRowB);
+        const unsigned voff = (unsigned)lane * 16u;
+        if (kCpr == 64 || lane < kCpr)
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(src) : "memory");
+      }
     } else {
-      const int y = x - kRowsPerWave;
+      const int y = x - kRowOps;
       const unsigned voff = d.cs_base + min(dma_cs_off[y], d.cs_lim) + dma_cs_swz[y];
       const unsigned m0v = d.m0 + (unsigned)(kTileB + (wave * kCsPerWave + y) * 4 * kDHead * 2);
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(rope_base_u) : "memory");
@@ -297,6 +316,22 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   const int g_rel = G == 1 ? 0 : (u.s == 1 ? (hc - u.head_off0) : ((hc - u.head_off0) >> 1));
   const int u_in_g = hc - u.head_off0 - g_rel * u.s;
   const int kbase_b = g_rel * kRank * 2;                        // this head's first column inside the tile row, bytes
+  // B operand of k-step ks (8 latent values of token lane_lo, k-octet lane_hi) sits at
+  // tile + h_off + 32*ks; in the paired layout the odd rows are rotated by one chunk,
+  // which wraps for the very first chunk of the row only: k-step 0 has its own offset.
+  int h_off, h_off0;
+  if (kPair) {
+    const int odd = lane_lo & 1;
+    const int rowb = (lane_lo >> 1) * kPairB + odd * (kWidth * 2);
+    h_off = rowb + kbase_b + (lane_hi - odd) * 16;
+    h_off0 = rowb + (((kbase_b >> 4) + lane_hi - odd) & 31) * 16;
+  } else {
+    h_off = lane_lo * kRowB + kbase_b + lane_hi * 16;
+    h_off0 = h_off;
+  }
+  auto h_ptr = [&](const unsigned char* tile, int ks) __attribute__((always_inline)) {
+    return reinterpret_cast<const half8*>(tile + (ks == 0 ? h_off0 : h_off + ks * 32));
+  };
 
   // ---- stationary operand: folded weights of (b, head), rows [32*rt0, 32*(rt0+RT))
   half8 W[NKS][RT];
@@ -320,7 +355,6 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   };
   auto mfma_phase = [&](TileAcc& r, int tile) {
     const unsigned char* base = lds + (size_t)(tile % kBufs) * kBufB;
-    const unsigned char* hrow = base + lane_lo * kRowB + kbase_b + lane_hi * 16;
     // acc[rt][i] is feature 32*(rt0+rt) + mfma_row(i) of token lane_lo; its cos/sin weight is
     // half (rt0+rt)*16 + i of the token's table row half lane_hi, i.e. 16-byte piece
     // lane_hi*8 + (rt0+rt)*2 + i/8, stored at piece ^ (row & 15)
@@ -329,7 +363,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     constexpr int kAhead = 2;
     half8 hf[kAhead + 1];
 #pragma unroll
-    for (int x = 0; x < kAhead && x < NKS; ++x) hf[x] = *reinterpret_cast<const half8*>(hrow + x * 32);
+    for (int x = 0; x < kAhead && x < NKS; ++x) hf[x] = *h_ptr(base, x);
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -340,7 +374,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       if (ks + kAhead < NKS)
-        hf[(ks + kAhead) % (kAhead + 1)] = *reinterpret_cast<const half8*>(hrow + (ks + kAhead) * 32);
+        hf[(ks + kAhead) % (kAhead + 1)] = *h_ptr(base, ks + kAhead);
       const half8 hfrag = hf[ks % (kAhead + 1)];
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
@@ -405,9 +439,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     constexpr int kGroups = 2 * RT;                      // epilogue groups of 8 accumulators
     float16v acc[2][RT];
     half8 hf[3], hn[2];                                  // B operands of this tile (ring) and the next tile's first two
-    auto hrow_of = [&](int tile) {
-      return lds + (size_t)(tile % kBufs) * kBufB + lane_lo * kRowB + kbase_b + lane_hi * 16;
-    };
+    auto tile_of = [&](int tile) { return lds + (size_t)(tile % kBufs) * kBufB; };
     auto cs_piece = [&](int tile, int g) {               // cos/sin halves of accumulators 8*(g&1) .. +7 of row tile g>>1
       const unsigned char* crow = lds + (size_t)(tile % kBufs) * kBufB + kTileB + lane_lo * (kDHead * 2);
       const int piece = lane_hi * 8 + (rt0 + (g >> 1)) * 2 + (g & 1);
@@ -420,8 +452,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     auto body = [&](auto cur_c, auto epi_c, int k) {
       constexpr int cur = decltype(cur_c)::value;
       constexpr bool with_epi = decltype(epi_c)::value;
-      const unsigned char* hrow = hrow_of(k);
-      const unsigned char* hnext = hrow_of(k + 1);
+      const unsigned char* hrow = tile_of(k);
+      const unsigned char* hnext = tile_of(k + 1);
       float part[4] = {0.f, 0.f, 0.f, 0.f};
       half8 csr[2];
       DmaTile nxt;
@@ -439,8 +471,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
           __builtin_amdgcn_sched_barrier(0);
         }
         // B operand two k-steps ahead; the last two steps fetch tile k+1's first operands
-        if (ks + 2 < NKS) hf[(ks + 2) % 3] = *reinterpret_cast<const half8*>(hrow + (ks + 2) * 32);
-        else hn[ks + 2 - NKS] = *reinterpret_cast<const half8*>(hnext + (ks + 2 - NKS) * 32);
+        if (ks + 2 < NKS) hf[(ks + 2) % 3] = *h_ptr(hrow, ks + 2);
+        else hn[ks + 2 - NKS] = *h_ptr(hnext, ks + 2 - NKS);
         const half8 hfrag = hf[ks % 3];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
@@ -477,8 +509,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     };
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
-    hf[0] = *reinterpret_cast<const half8*>(hrow_of(0));
-    hf[1] = *reinterpret_cast<const half8*>(hrow_of(0) + 32);
+    hf[0] = *h_ptr(tile_of(0), 0);
+    hf[1] = *h_ptr(tile_of(0), 1);
     body(C0{}, std::false_type{}, 0);
     int k = 1;
     for (; k + 1 < n_tiles; k += 2) {

@@ -91,6 +91,34 @@ def test_no_rope():
     check(case, TOL_FP)
 
 
+@pytest.mark.parametrize("cfg,batch,seq,dtype", [("2", 2, 777, "f16"), ("2", 1, 300, "bf16"), ("3", 2, 500, "f16"),
+                                                 ("5a", 2, 333, "f16"), ("5b", 1, 200, "f16")])
+def test_no_rope_configs(cfg, batch, seq, dtype):
+    """The paper's non-RoPE attention (Eq. 5) on the shapes of the configurations: the
+    query is folded into the latent space and the keys are never rebuilt."""
+    import dataclasses
+    layer = dataclasses.replace(synth.config_layer(cfg), rope_theta=0.0)
+    kw = {"d_model": 2048} if cfg == "5b" else {}
+    case = synth.make_case_svd(layer, batch, seq, seed=2, dtype=dtype, **kw)
+    if batch > 1:
+        case.seq_lens = np.array([seq, max(1, seq // 3)], np.int32)
+        case.q_pos = case.seq_lens - 1
+    case.name = f"no-rope cfg{cfg}"
+    check(case, TOL_FP)
+
+
+@pytest.mark.parametrize("k_i4,v_i4", [(True, True), (True, False)])
+def test_no_rope_int4(k_i4, v_i4):
+    """Non-RoPE path on 4-bit key latents: codes go to the matrix cores as integers,
+    scale and zero-point are applied per (token, 128-channel block)."""
+    import dataclasses
+    layer = dataclasses.replace(synth.config_layer("4"), rope_theta=0.0)
+    case = synth.make_case_svd(layer, 2, 400, seed=3, rotate=True)
+    case.name = "no-rope int4"
+    quant = {"k": O.quant_latent(case.Hk), "v": O.quant_latent(case.Hv)}
+    check(case, TOL_I4, k_i4=k_i4, v_i4=v_i4, quant=quant)
+
+
 def test_peaked_softmax_and_large_logits():
     """Queries scaled by 12 give logits of order +-40: the max-subtracted softmax
     must not overflow.  The folded weights and the cos/sin table are fp16, so a
