@@ -311,7 +311,7 @@ int plan_qk(const Meta& m, QkPlan* p) {
 }
 
 // Wavefronts per compute unit the value kernel's splits aim at.
-inline int value_waves_per_cu(const palu_layer_desc*) { return 4; }
+inline int value_waves_per_cu(const palu_layer_desc* d) { return d->v_latent_dtype == PALU_I4 ? 8 : 4; }
 
 // Tokens per value split and number of splits for a given attended length: a
 // split is one wavefront's share; aim at four wavefronts per compute unit,
@@ -536,11 +536,17 @@ int encode_impl(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 g1((unsigned)ceil_div(max_R, kEncCols), (unsigned)a.k_splits, (unsigned)n_sides);
   const dim3 g2((unsigned)ceil_div(max_R, 64), (unsigned)n_tok, (unsigned)n_sides);
+  using EncFn = void (*)(EncodeArgs);
+  const int tok_cls = n_tok >= 5 ? 3 : (n_tok >= 3 ? 2 : (n_tok == 2 ? 1 : 0));     // 8, 4, 2 or 1 tokens per pass
+  static const EncFn partial_f16[4] = {encode_partial_kernel<F16, 1>, encode_partial_kernel<F16, 2>,
+                                       encode_partial_kernel<F16, 4>, encode_partial_kernel<F16, 8>};
+  static const EncFn partial_bf16[4] = {encode_partial_kernel<BF16, 1>, encode_partial_kernel<BF16, 2>,
+                                        encode_partial_kernel<BF16, 4>, encode_partial_kernel<BF16, 8>};
   if (desc->act_dtype == PALU_F16) {
-    hipLaunchKernelGGL(encode_partial_kernel<F16>, g1, dim3(256), 0, s, a);
+    hipLaunchKernelGGL(partial_f16[tok_cls], g1, dim3(256), 0, s, a);
     hipLaunchKernelGGL(encode_finish_kernel<F16>, g2, dim3(256), 0, s, a);
   } else {
-    hipLaunchKernelGGL(encode_partial_kernel<BF16>, g1, dim3(256), 0, s, a);
+    hipLaunchKernelGGL(partial_bf16[tok_cls], g1, dim3(256), 0, s, a);
     hipLaunchKernelGGL(encode_finish_kernel<BF16>, g2, dim3(256), 0, s, a);
   }
   return launch_ok();
@@ -707,7 +713,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.scale = 1.4426950408889634f / std::sqrt((float)PALU_D_HEAD);
     {   // tokens per wavefront: four wavefronts per compute unit, 64 to 512 tokens
       const long long items = std::max(1, qp.total_units * batch);
-      const long long waves_per_cu = 4;
+      const long long waves_per_cu = k_i4 ? 8 : 4;
       long long stq = ceil_div((int)std::min<long long>(items * seq_len / (waves_per_cu * device_cu_count()) + 1, 1 << 30), 32) * 32LL;
       stq = std::min<long long>(std::max<long long>(stq, kPvSplitMin), kPvSplitMax);
       a.split_tokens = (int)stq;
@@ -727,7 +733,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
         h_hi = std::max(h_hi, x.h0 + x.nh);
       }
       f.head0 = h_lo;
-      const dim3 g((unsigned)(wmax / 128), (unsigned)(h_hi - h_lo));
+      const dim3 g((unsigned)(wmax / 128), (unsigned)(h_hi - h_lo), (unsigned)ceil_div(batch, 4));
       if (act == PALU_F16) hipLaunchKernelGGL(qfold_kernel<F16>, g, dim3(256), 0, s, f);
       else hipLaunchKernelGGL(qfold_kernel<BF16>, g, dim3(256), 0, s, f);
       if ((st = launch_ok()) != PALU_OK) return st;

@@ -12,7 +12,7 @@ namespace palu {
 
 constexpr int kEncRows = 64;      // rows of A per workgroup (16 per wavefront)
 constexpr int kEncCols = 512;     // columns of A per workgroup (8 per lane)
-constexpr int kEncTok = 8;        // tokens accumulated per pass over the weights
+constexpr int kEncTokMax = 8;     // most tokens accumulated per pass over the weights
 
 struct EncodeSide {
   const uint16_t* A;       // [d, R]
@@ -29,7 +29,9 @@ struct EncodeArgs {
 };
 
 // grid (ceil(max R / 512), d / 64, sides), 256 threads.
-template <typename T>
+// kEncTok: tokens accumulated per pass over the weights (1, 2, 4 or 8: a decode
+// step of one sequence should not pay for eight).
+template <typename T, int kEncTok>
 __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
   __shared__ float xs[kEncTok][kEncRows];
   __shared__ float red[3][kEncTok][kEncCols];     // wavefronts 1..3 hand their sums to wavefront 0
@@ -179,8 +181,13 @@ __global__ __launch_bounds__(256) void quant_kernel(QuantArgs a) {
   }
 }
 
-template __global__ void encode_partial_kernel<F16>(EncodeArgs);
-template __global__ void encode_partial_kernel<BF16>(EncodeArgs);
+#define PALU_ENC_INST(T)                                              \
+  template __global__ void encode_partial_kernel<T, 1>(EncodeArgs);   \
+  template __global__ void encode_partial_kernel<T, 2>(EncodeArgs);   \
+  template __global__ void encode_partial_kernel<T, 4>(EncodeArgs);   \
+  template __global__ void encode_partial_kernel<T, 8>(EncodeArgs);
+PALU_ENC_INST(F16)
+PALU_ENC_INST(BF16)
 template __global__ void encode_finish_kernel<F16>(EncodeArgs);
 template __global__ void encode_finish_kernel<BF16>(EncodeArgs);
 template __global__ void quant_kernel<F16>(QuantArgs);

@@ -121,7 +121,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 // NG: 128-column blocks per unit (16 lanes x 8 channels each)
 // I4: latents are 4-bit codes; every 128-column block of the unit is one quantization block
 template <typename T, int HS, int NG, bool I4>
-__global__ __launch_bounds__(256) void pv_kernel(PvArgs a) {
+__global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs a) {
   constexpr bool kIsBf16 = !__is_same(T, F16);
   constexpr int MT = HS > 8 ? 2 : 1;
   constexpr int NA = I4 ? NG : 1;                  // probability tiles

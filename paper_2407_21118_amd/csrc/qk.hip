@@ -78,12 +78,12 @@ struct QkArgs {
   QkUnits units;
 };
 
-// grid (wpad_max / 128, heads of the launch), 256 threads: a workgroup fills 128 columns of
-// one head's row for every sequence of the batch; thread = (column, half of the
-// features).  The B_k values are loaded once and reused for all sequences.
+// grid (wpad_max / 128, heads of the launch, batch / 4), 256 threads: a workgroup fills
+// 128 columns of one head's row for four sequences; thread = (column, half of the
+// features).  The B_k values are loaded once and reused for the four.
 template <typename T>
 __global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
-  __shared__ float blk[4];
+  __shared__ float blk[4][4];
   const Meta& m = a.meta;
   const int h = a.head0 + blockIdx.y;
   const QkUnit u = a.units.u[a.unit_of_head[h]];
@@ -105,38 +105,47 @@ __global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
 #pragma unroll
     for (int x = 0; x < 8; ++x) bw[x] = *reinterpret_cast<const uint4v*>(Brow + 8 * x);
   }
-  for (int b = 0; b < a.batch; ++b) {
-    const uint16_t* qp = a.q + ((size_t)b * m.n_heads + h) * kDHead + fh;
+  // four sequences per workgroup, their query loads issued together
+  const int b0 = blockIdx.z * 4;
+  const int nb = min(4, a.batch - b0);
+  uint4v qw[4][8];
+#pragma unroll
+  for (int bb = 0; bb < 4; ++bb) {
+    const uint16_t* qp = a.q + ((size_t)min(b0 + bb, a.batch - 1) * m.n_heads + h) * kDHead + fh;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) qw[bb][x] = *reinterpret_cast<const uint4v*>(qp + 8 * x);
+  }
+#pragma unroll
+  for (int bb = 0; bb < 4; ++bb) {
     float s = 0.f;
 #pragma unroll
     for (int x = 0; x < 8; ++x) {
-      const uint4v qw = *reinterpret_cast<const uint4v*>(qp + 8 * x);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        s = fmaf(T::to_float((uint16_t)(qw[e] & 0xffffu)), T::to_float((uint16_t)(bw[x][e] & 0xffffu)), s);
-        s = fmaf(T::to_float((uint16_t)(qw[e] >> 16)), T::to_float((uint16_t)(bw[x][e] >> 16)), s);
+        s = fmaf(T::to_float((uint16_t)(qw[bb][x][e] & 0xffffu)), T::to_float((uint16_t)(bw[x][e] & 0xffffu)), s);
+        s = fmaf(T::to_float((uint16_t)(qw[bb][x][e] >> 16)), T::to_float((uint16_t)(bw[x][e] >> 16)), s);
       }
     }
     s += __shfl_xor(s, 1, 64);
     const uint16_t hv = F16::from_float(s);        // the contraction runs in fp16 whatever the storage type
-    if ((tid & 1) == 0) a.qt[(size_t)b * a.qt_bstride + u.q_off + (size_t)hh * u.wpad + c] = hv;
+    if ((tid & 1) == 0 && bb < nb) a.qt[(size_t)(b0 + bb) * a.qt_bstride + u.q_off + (size_t)hh * u.wpad + c] = hv;
     // sum of the rounded values over this 128-column block (int4 zero-point term)
     float r = (tid & 1) == 0 ? F16::to_float(hv) : 0.f;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) r += __shfl_xor(r, off, 64);
-    __syncthreads();                               // the previous sequence's sum has been read
-    if ((tid & 63) == 0) blk[wave] = r;
-    __syncthreads();
-    if (tid == 0)
-      a.qsum[(size_t)b * a.qs_bstride + u.qs_off + (size_t)hh * (u.wpad >> 7) + blockIdx.x] = (blk[0] + blk[1]) + (blk[2] + blk[3]);
+    if ((tid & 63) == 0) blk[bb][wave] = r;
   }
+  __syncthreads();
+  if (tid < nb)
+    a.qsum[(size_t)(b0 + tid) * a.qs_bstride + u.qs_off + (size_t)hh * (u.wpad >> 7) + blockIdx.x] =
+        (blk[tid][0] + blk[tid][1]) + (blk[tid][2] + blk[tid][3]);
 }
 
 // T:  storage type of unquantized latents (bfloat16 converted to fp16 in registers)
 // MT: 16-row head tiles (1: up to 16 heads, 2: up to 32)
 // I4: latents are 4-bit codes
 template <typename T, int MT, bool I4>
-__global__ __launch_bounds__(256) void qk_kernel(QkArgs a) {
+__global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char qk_lds[];
   constexpr bool kIsBf16 = !__is_same(T, F16);
   const int tid = threadIdx.x;
