@@ -150,3 +150,59 @@ def test_mixed_group_sizes_and_ranks():
     case.q_pos = np.array([149, 32], np.int32)
     case.name = "mixed"
     check(case, TOL_FP)
+
+
+def _random_layer(rng, theta):
+    """A random legal layer: groups of 1..8 heads, ranks in multiples of 32 up to
+    min(512, width of the group), different for keys and values."""
+    sizes = []
+    while sum(sizes) < 4 or (len(sizes) < 6 and rng.random() < 0.6):
+        sizes.append(int(rng.choice([1, 1, 2, 3, 4, 4, 8])))
+    head_off = [0] + list(np.cumsum(sizes))
+
+    def ranks():
+        return [int(rng.integers(1, min(512, s * 128) // 32 + 1)) * 32 for s in sizes]
+
+    return synth.Layer(int(head_off[-1]), 128, head_off, [0] + list(np.cumsum(ranks())), [0] + list(np.cumsum(ranks())),
+                       rope_theta=theta)
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_random_layers_and_lengths(seed):
+    """Seeded random layers (group sizes, ranks, with and without RoPE), batch sizes,
+    lengths and ragged sequence lengths: exercises the merging and slicing of work
+    units, partial tiles and sets, and sequences much shorter than the batch's longest."""
+    rng = np.random.default_rng([77, seed])
+    theta = 10000.0 if seed % 3 else 0.0
+    layer = _random_layer(rng, theta)
+    batch = int(rng.integers(1, 4))
+    seq = int(rng.choice([1, 2, 31, 32, 33, 65, 130, 257, 300]))
+    dtype = "bf16" if seed % 4 == 1 else "f16"
+    case = synth.make_case_orthonormal(layer, batch, seq, seed=100 + seed, dtype=dtype)
+    lens = np.array([seq] + [int(rng.integers(1, seq + 1)) for _ in range(batch - 1)], np.int32)
+    case.seq_lens = lens
+    case.q_pos = (lens - 1 + int(rng.integers(0, 5000))).astype(np.int32)
+    if seed % 2:
+        case.k_pos = np.sort(rng.choice(8192, size=seq, replace=False)).astype(np.int32)
+    case.name = f"random-{seed} heads={layer.n_heads} groups={layer.n_groups} theta={theta}"
+    check(case, TOL_FP)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_random_layers_int4(seed):
+    """Random layers whose ranks are multiples of the 128-channel quantization block,
+    key and / or value latents 4-bit, with and without RoPE."""
+    rng = np.random.default_rng([78, seed])
+    sizes = [int(rng.choice([1, 2, 4, 8])) for _ in range(int(rng.integers(2, 5)))]
+    head_off = [0] + list(np.cumsum(sizes))
+    kr = [int(rng.integers(1, min(512, s * 128) // 128 + 1)) * 128 for s in sizes]
+    vr = [int(rng.integers(1, min(512, s * 128) // 128 + 1)) * 128 for s in sizes]
+    layer = synth.Layer(int(head_off[-1]), 128, head_off, [0] + list(np.cumsum(kr)), [0] + list(np.cumsum(vr)),
+                        rope_theta=0.0 if seed % 2 else 10000.0)
+    batch, seq = 2, int(rng.choice([33, 100, 260]))
+    case = synth.make_case_orthonormal(layer, batch, seq, seed=200 + seed)
+    case.seq_lens = np.array([seq, int(rng.integers(1, seq + 1))], np.int32)
+    case.q_pos = (case.seq_lens - 1).astype(np.int32)
+    case.name = f"random-int4-{seed} groups={sizes} k_ranks={kr} v_ranks={vr}"
+    quant = {"k": O.quant_latent(case.Hk), "v": O.quant_latent(case.Hv)}
+    check(case, TOL_I4, k_i4=seed != 3, v_i4=seed != 2, quant=quant)
