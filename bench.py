@@ -10,7 +10,11 @@ P.H_v per split, merge + B_v).  Consecutive steps cycle through a ring of
 distinct latent caches larger than the 256 MB last-level cache so that every
 step streams its latents from HBM.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: the step time (metric/value/unit/ms_per_step), the
+workload (config), the roofline of the dominant kernel (roofline: algorithmic
+FLOPs or bytes per launch over its measured duration, against the MI355X peak),
+the same for the value kernel (roofline_value), per-stage times (stage_us) and
+the CPU oracle timed beside it (cpu_baseline).
 """
 
 from __future__ import annotations

@@ -86,10 +86,12 @@ int palu_version(void);
  * choose.  Not thread-safe against concurrent decode calls.
  *   "score_waves"         4 or 8 wavefronts per score workgroup for ranks <= 256
  *   "score_chunks"        sequence chunks per (sequence, head block) in the score kernel
- *   "value_split_tokens"  tokens per sequence split in the value kernel (multiple of 32, <= 1024)
- * Unknown names and out-of-range values return PALU_ERR_INVALID_ARG.  The workspace
- * size query assumes the defaults; a smaller value_split_tokens may need more
- * workspace, in which case palu_attn_decode reports the shortfall.
+ *   "score_order"         workgroup order of the score kernel: 1 = sequence chunk fastest, 2 = unit fastest
+ *   "score_early_start"   1 = the first MFMA phase overlaps the tail of the weight fetch
+ *   "value_split_tokens"  tokens per sequence split in the value kernel (multiple of 32, <= 4096)
+ * Unknown names and out-of-range values return PALU_ERR_INVALID_ARG.  Set
+ * value_split_tokens before querying the workspace size: a smaller split needs
+ * more workspace, and palu_attn_decode reports a shortfall.
  */
 int palu_set_option(const char* name, int value);
 
@@ -163,6 +165,10 @@ int palu_quant_latent(const palu_layer_desc* desc, int which, const void* latent
  * Appendix B; values contracted in latent space first, (p H_v) B_v, Eq. 4):
  *     out[b,i] = softmax_t( RoPE(q[b,i], q_pos[b]) . RoPE(H_k[b,t] B_k, k_pos[t])_i / sqrt(d_h) ) H_v[b] B_v |_i
  * over t in [0, seq_lens[b]).  No causal mask: every cached row is attended.
+ * With desc->rope_theta <= 0 there is no rotation and the non-RoPE form of
+ * Sec. 3.1.2 (Eq. 5) is used: the query is multiplied by B_k^T once and the
+ * scores are (q B_k^T) H_k^T, without rebuilding any key; q_pos, k_pos and the
+ * table are then not read (a valid table pointer is still required).
  *
  *   q          DEVICE [batch, n_heads, d_head] act_dtype, before RoPE (Sec. 4.5.2)
  *   q_pos      DEVICE int32 [batch] position of each query token
