@@ -66,7 +66,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="2", help="workload: 1, 2 (7B shape, seq 16K, headline), 2-4k, 2-64k, 3, 4, 4v, 5a, 5b")
+    ap.add_argument("--config", default="2", help="workload: 1, 2 (7B shape, seq 16K, headline), 2-4k, 2-64k, 3, 4, 4v, 5a, 5b, "
+                         "2p / 2p-64k (the paper's latency allocation: K rank 128, V rank 384 per group)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ring-gib", type=float, default=1.0, help="distinct latent bytes to cycle through")
     ap.add_argument("--opt", action="append", default=[], help="tuning knob name=value (palu_set_option)")

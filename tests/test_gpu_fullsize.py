@@ -33,8 +33,12 @@ def b_slice(flat, layer, which, j, heads):
     return np.ascontiguousarray(Bj[:, cols]).reshape(-1)
 
 
-def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP):
-    case = wd.make_device_case(cfg, seed=0, n_sets=1)
+def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP, no_rope=False):
+    layer = None
+    if no_rope:
+        import dataclasses
+        layer = dataclasses.replace(synth.config_layer(cfg.split("-")[0]), rope_theta=0.0)
+    case = wd.make_device_case(cfg, seed=0, n_sets=1, layer=layer)
     layer, B, L = case.layer, case.batch, case.seq
     say(f"[full] cfg {cfg} B={B} L={L} groups={layer.n_groups} R_k={layer.R_k} k_i4={k_i4} v_i4={v_i4}")
     desc = make_desc(layer, "f16", k_i4, v_i4)
@@ -125,3 +129,20 @@ def test_full_config5a_per_head():
 
 def test_full_config5b_joint():
     run_full("5b", [(0, 0, [0, 31]), (5, 0, [13])])
+
+
+def test_full_config2_paper_rank_allocation():
+    """Keys at rank 128, values at rank 384 per group (the paper's latency runs, Sec. 4.5)."""
+    run_full("2p", [(0, 0, [0, 1, 2, 3]), (0, 6, [2])])
+
+
+def test_full_config2_16k_no_rope():
+    run_full("2", [(0, 1, [0, 1, 2, 3]), (0, 4, [3])], no_rope=True)
+
+
+def test_full_config4_no_rope_int4():
+    run_full("4", [(0, 0, [0, 1]), (9, 5, [2])], k_i4=True, v_i4=True, tol=TOL_I4, no_rope=True)
+
+
+def test_full_config5b_no_rope():
+    run_full("5b", [(0, 0, [0, 13]), (6, 0, [31])], no_rope=True)

@@ -268,10 +268,15 @@ def config_layer(cfg: str, seed: int = 0) -> Layer:
         return uniform_layer(32, 1, 64)
     if cfg == "5b":
         return uniform_layer(32, 32, 2048)
+    if cfg == "2p":
+        # the allocation of the paper's latency experiments (Sec. 4.5): keys compressed by 75 %,
+        # values by 25 %, i.e. ranks 128 / 384 per group of 4 heads (50 % overall)
+        return ragged_layer(32, 4, [128] * 8, [384] * 8)
     raise ValueError(cfg)
 
 
 FULL_SIZES = {            # (batch, seq) at full size
     "1": (1, 1024), "2": (1, 16384), "2-4k": (1, 4096), "2-64k": (1, 65536),
     "3": (4, 16384), "4": (16, 8192), "5a": (8, 16384), "5b": (8, 16384),
+    "2p": (1, 16384), "2p-64k": (1, 65536),
 }
