@@ -240,6 +240,34 @@ def attn_decode(q, q_pos, Hk, Hv, Bk, Bv, group_head_off, k_rank_off, v_rank_off
     return out
 
 
+def attn_decode_latent(q, q_pos, Hk, Hv, Bk, group_head_off, k_rank_off, v_rank_off,
+                       d_head: int, rope_theta: float, k_pos=None, seq_lens=None) -> np.ndarray:
+    """Attention output left in the value latent space (Sec. 3.1.1, Eq. 4 before
+    the multiplication by B_v, which the paper absorbs into the output
+    projection W_o offline): for head i of group j, a^lat_i = p_i H_v[:, columns of j],
+    with p_i the same softmax as attn_decode.  Returns [B, sum_i r_v(group(i))]
+    float64, heads in order, head i occupying r_v(group(i)) entries."""
+    q = np.asarray(q, dtype=np.float64)
+    Bsz, n_heads, _ = q.shape
+    scores = attn_decode_scores(q, q_pos, Hk, Bk, group_head_off, k_rank_off, d_head,
+                                rope_theta, k_pos, seq_lens)
+    widths = []
+    for j in range(len(group_head_off) - 1):
+        widths += [v_rank_off[j + 1] - v_rank_off[j]] * (group_head_off[j + 1] - group_head_off[j])
+    out = np.empty((Bsz, int(sum(widths))), dtype=np.float64)
+    for b in range(Bsz):
+        L = scores[b].shape[1]
+        p = softmax_rows(scores[b])                       # [n, L]
+        H = np.asarray(Hv[b, :L], dtype=np.float64)
+        at = 0
+        for j in range(len(group_head_off) - 1):
+            Hj = H[:, v_rank_off[j]:v_rank_off[j + 1]]    # [L, r_j]
+            for i in range(group_head_off[j], group_head_off[j + 1]):
+                out[b, at:at + Hj.shape[1]] = p[i] @ Hj
+                at += Hj.shape[1]
+    return out
+
+
 # --------------------------------------------------------------------------
 # Closed forms the paper prints (used as pins and by the benchmark's counters)
 # --------------------------------------------------------------------------

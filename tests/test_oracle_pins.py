@@ -205,6 +205,33 @@ def test_fused_vo_identity():
             np.testing.assert_allclose(got[b, i], want, rtol=1e-10, atol=1e-12)
 
 
+def test_latent_output_times_b_v_is_the_attention_output():
+    """attn_decode_latent leaves the output in the value latent space (Sec. 3.1.1);
+    multiplying head i's slice by its block of B_v must give attn_decode's output,
+    and with L = 1 the latent output is the single value latent row itself."""
+    p = small_problem(seed=5)
+    full = run_oracle(p)
+    lat = O.attn_decode_latent(p["q"], p["q_pos"], p["Hk"], p["Hv"], p["Bk_flat"], p["gho"], p["kro"], p["vro"],
+                               p["d"], 10000.0, p["k_pos"])
+    at = 0
+    for i in range(p["n"]):
+        j, u = divmod(i, p["s"])
+        r = p["vro"][j + 1] - p["vro"][j]
+        for b in range(p["B"]):
+            np.testing.assert_allclose(lat[b, at:at + r] @ p["Bv"][j][:, u * p["d"]:(u + 1) * p["d"]], full[b, i],
+                                       rtol=1e-10, atol=1e-12)
+        at += r
+    assert at == lat.shape[1]
+    one = O.attn_decode_latent(p["q"], p["q_pos"], p["Hk"][:, :1], p["Hv"][:, :1], p["Bk_flat"], p["gho"], p["kro"],
+                               p["vro"], p["d"], 10000.0)
+    at = 0
+    for i in range(p["n"]):
+        j = i // p["s"]
+        r = p["vro"][j + 1] - p["vro"][j]
+        np.testing.assert_allclose(one[:, at:at + r], p["Hv"][:, 0, p["vro"][j]:p["vro"][j + 1]], rtol=1e-12)
+        at += r
+
+
 def test_zero_positions_equal_fused_qk_form():
     """With every position 0 RoPE is the identity and the score must equal
     (q B_k^T) H_k^T / sqrt(d_h) (Eq. 5)."""
