@@ -202,6 +202,25 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
                      float* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same decode step with the output left in the value latent space
+ * (Sec. 3.1.1: B_v is absorbed into the output projection W_o offline, so the
+ * attention module returns (p H_v) and never multiplies by B_v):
+ *     out_latent[b, off(i) .. off(i) + r_v(g(i))) = softmax_t(...) H_v[b][:, columns of group g(i)]
+ * with off(i) = sum over heads i' < i of r_v(g(i')).  Arguments as for
+ * palu_attn_decode, without Bv;
+ *   out_latent DEVICE float32 [batch, sum_i r_v(g(i))]
+ * Uses the same workspace size as palu_attn_decode.
+ */
+int palu_attn_decode_latent(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                            const void* q, const int32_t* q_pos,
+                            const void* hk, const void* hk_scale, const void* hk_zero,
+                            const void* hv, const void* hv_scale, const void* hv_zero,
+                            const int32_t* k_pos, const int32_t* seq_lens,
+                            const void* Bk,
+                            const void* rope_table, int32_t rope_table_len,
+                            float* out_latent, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Same call with per-stage timing hooks, for benchmarks that price each
  * stage against its own roofline.  The decode step runs as PALU_DECODE_STAGES
  * stages (0 fold the rotated query into B_k, 1 scores = reconstruction + RoPE +

@@ -79,6 +79,9 @@ def load_library():
                                      vp, i32, vp, vp, sz, vp]
     lib.palu_attn_decode_staged.argtypes = lib.palu_attn_decode.argtypes + [ctypes.POINTER(vp)]
     lib.palu_attn_decode_staged.restype = ctypes.c_int
+    lib.palu_attn_decode_latent.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                            vp, i32, vp, vp, sz, vp]
+    lib.palu_attn_decode_latent.restype = ctypes.c_int
     for name in ("palu_rope_table_bytes", "palu_rope_table_init", "palu_encode_workspace_bytes", "palu_encode",
                  "palu_quant_latent", "palu_attn_decode_workspace_bytes", "palu_attn_decode"):
         getattr(lib, name).restype = ctypes.c_int
@@ -249,3 +252,25 @@ def palu_attn_decode(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, q,
         arr = (ctypes.c_void_p * len(stage_events))(*[ctypes.c_void_p(e.cuda_event) for e in stage_events])
         _check(load_library().palu_attn_decode_staged(*args, arr), "palu_attn_decode_staged")
     return out
+
+
+def palu_attn_decode_latent(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, q, q_pos, hk, hv, Bk,
+                            rope_table, rope_table_len: int, out_latent=None, workspace=None, k_pos=None,
+                            seq_lens=None, hk_scale=None, hk_zero=None, hv_scale=None, hv_zero=None, stream=None):
+    """Decode step whose output stays in the value latent space: [batch, sum over heads of r_v(group)] float32."""
+    import torch
+    if out_latent is None:
+        width = sum((desc.v_rank_off[j + 1] - desc.v_rank_off[j]) * (desc.group_head_off[j + 1] - desc.group_head_off[j])
+                    for j in range(desc.n_groups))
+        out_latent = torch.empty((batch, width), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(palu_attn_decode_workspace_bytes(desc, batch, max_seq), dtype=torch.uint8,
+                                device=q.device)
+    _need_cuda(q, q_pos, hk, hv, Bk, rope_table, out_latent, workspace, k_pos, seq_lens, hk_scale, hk_zero,
+               hv_scale, hv_zero)
+    _check(load_library().palu_attn_decode_latent(
+        desc.ref(), batch, seq_len, max_seq, _ptr(q), _ptr(q_pos), _ptr(hk), _ptr(hk_scale), _ptr(hk_zero),
+        _ptr(hv), _ptr(hv_scale), _ptr(hv_zero), _ptr(k_pos), _ptr(seq_lens), _ptr(Bk),
+        _ptr(rope_table), int(rope_table_len), _ptr(out_latent), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)), "palu_attn_decode_latent")
+    return out_latent

@@ -616,38 +616,27 @@ int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch,
   return PALU_OK;
 }
 
-int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
-                     const void* q, const int32_t* q_pos,
-                     const void* hk, const void* hk_scale, const void* hk_zero,
-                     const void* hv, const void* hv_scale, const void* hv_zero,
-                     const int32_t* k_pos, const int32_t* seq_lens,
-                     const void* Bk, const void* Bv,
-                     const void* rope_table, int32_t rope_table_len,
-                     float* out, void* workspace, size_t workspace_bytes, void* stream) {
-  return palu_attn_decode_staged(desc, batch, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale,
-                                 hv_zero, k_pos, seq_lens, Bk, Bv, rope_table, rope_table_len, out, workspace,
-                                 workspace_bytes, stream, nullptr);
-}
-
-int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
-                            const void* q, const int32_t* q_pos,
-                            const void* hk, const void* hk_scale, const void* hk_zero,
-                            const void* hv, const void* hv_scale, const void* hv_zero,
-                            const int32_t* k_pos, const int32_t* seq_lens,
-                            const void* Bk, const void* Bv,
-                            const void* rope_table, int32_t rope_table_len,
-                            float* out, void* workspace, size_t workspace_bytes, void* stream,
-                            void* const* stage_events) {
+// out: attention output after B_v; out_latent: output left in the value latent space (then Bv is not read)
+static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                       const void* q, const int32_t* q_pos,
+                       const void* hk, const void* hk_scale, const void* hk_zero,
+                       const void* hv, const void* hv_scale, const void* hv_zero,
+                       const int32_t* k_pos, const int32_t* seq_lens,
+                       const void* Bk, const void* Bv,
+                       const void* rope_table, int32_t rope_table_len,
+                       float* out, float* out_latent, void* workspace, size_t workspace_bytes, void* stream,
+                       void* const* stage_events) {
   Meta m;
   int st = check_desc(desc, &m);
   if (st != PALU_OK) return st;
   if (batch <= 0 || seq_len <= 0 || max_seq < seq_len) return PALU_ERR_INVALID_ARG;
-  if (!q || !q_pos || !hk || !hv || !Bk || !Bv || !rope_table || !out || !workspace) return PALU_ERR_INVALID_ARG;
+  if (!q || !q_pos || !hk || !hv || !Bk || !rope_table || !workspace) return PALU_ERR_INVALID_ARG;
+  if (out_latent ? (out != nullptr) : (!out || !Bv)) return PALU_ERR_INVALID_ARG;
   const bool k_i4 = desc->k_latent_dtype == PALU_I4, v_i4 = desc->v_latent_dtype == PALU_I4;
   if (k_i4 && (!hk_scale || !hk_zero)) return PALU_ERR_INVALID_ARG;
   if (v_i4 && (!hv_scale || !hv_zero)) return PALU_ERR_INVALID_ARG;
   if (rope_table_len <= 0 || (!k_pos && rope_table_len < seq_len)) return PALU_ERR_INVALID_ARG;
-  for (const void* p : {hk, hv, Bk, Bv, rope_table, (const void*)workspace})
+  for (const void* p : {hk, hv, Bk, Bv, rope_table, (const void*)workspace, (const void*)out_latent})
     if (reinterpret_cast<uintptr_t>(p) & 15) return PALU_ERR_INVALID_ARG;
   const int Rk = m.k_off[m.n_groups], Rv = m.v_off[m.n_groups];
   if ((Rk % 8) || (Rv % 8)) return PALU_ERR_INVALID_ARG;
@@ -932,6 +921,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     a.Bv = static_cast<const uint16_t*>(Bv);
     a.seq_lens = seq_lens;
     a.out = out;
+    a.out_latent = out_latent;
     a.n_split = n_split;
     a.split_tokens = split_tokens;
     a.seq_len = seq_len;
@@ -945,6 +935,46 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
     if ((st = mark(4)) != PALU_OK) return st;
   }
   return PALU_OK;
+}
+
+int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                     const void* q, const int32_t* q_pos,
+                     const void* hk, const void* hk_scale, const void* hk_zero,
+                     const void* hv, const void* hv_scale, const void* hv_zero,
+                     const int32_t* k_pos, const int32_t* seq_lens,
+                     const void* Bk, const void* Bv,
+                     const void* rope_table, int32_t rope_table_len,
+                     float* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_impl(desc, batch, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
+                     seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream, nullptr);
+}
+
+int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                            const void* q, const int32_t* q_pos,
+                            const void* hk, const void* hk_scale, const void* hk_zero,
+                            const void* hv, const void* hv_scale, const void* hv_zero,
+                            const int32_t* k_pos, const int32_t* seq_lens,
+                            const void* Bk, const void* Bv,
+                            const void* rope_table, int32_t rope_table_len,
+                            float* out, void* workspace, size_t workspace_bytes, void* stream,
+                            void* const* stage_events) {
+  return decode_impl(desc, batch, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
+                     seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream,
+                     stage_events);
+}
+
+int palu_attn_decode_latent(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                            const void* q, const int32_t* q_pos,
+                            const void* hk, const void* hk_scale, const void* hk_zero,
+                            const void* hv, const void* hv_scale, const void* hv_zero,
+                            const int32_t* k_pos, const int32_t* seq_lens,
+                            const void* Bk,
+                            const void* rope_table, int32_t rope_table_len,
+                            float* out_latent, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!out_latent) return PALU_ERR_INVALID_ARG;
+  return decode_impl(desc, batch, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
+                     seq_lens, Bk, nullptr, rope_table, rope_table_len, nullptr, out_latent, workspace, workspace_bytes,
+                     stream, nullptr);
 }
 
 }  // extern "C"

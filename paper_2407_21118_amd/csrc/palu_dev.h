@@ -147,6 +147,7 @@ struct CombineArgs {
   const uint16_t* Bv;
   const int32_t* seq_lens;
   float* out;                // [batch, n_heads, 128]
+  float* out_latent;         // non-NULL: write the normalised latent output [batch, o_stride] instead and skip B_v
   int n_split;
   int split_tokens;
   int seq_len;

@@ -102,6 +102,13 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
     __syncthreads();
   }
 
+  if (a.out_latent) {          // output stays in the latent space: this workgroup writes its quarter of the head's r_v values
+    float* ol = a.out_latent + (size_t)b * a.o_stride + o_head_off(m, h);
+    const int per = ((rv >> 2) + 3) & ~3;
+    for (int k = quarter * per + tid; k < min(rv, (quarter + 1) * per); k += 256) ol[k] = olat[k] / sum[0];
+    return;
+  }
+
   // ---- out = o_lat . B_v[:, 32 of the head's columns] / l: thread = (k part kp of 32, column quad cq of 8), 8-byte loads
   const int kp = tid >> 3, cq = tid & 7;
   const uint16_t* Bv = a.Bv + m.bv_off[j] + u * kDHead + quarter * 32 + cq * 4;

@@ -163,3 +163,40 @@ def test_quantizer_scatter_rows():
         np.testing.assert_array_equal(scale[r].cpu().view(torch.int16).numpy(), s[t].view(np.int16))
         np.testing.assert_array_equal(zero[r].cpu().view(torch.int16).numpy(), z[t].view(np.int16))
     assert not c[[0, 1, 3, 5]].any()
+
+
+@pytest.mark.parametrize("theta,v_i4", [(10000.0, False), (0.0, False), (10000.0, True)])
+def test_latent_output_matches_oracle(theta, v_i4):
+    """palu_attn_decode_latent: the output stays in the value latent space (Sec. 3.1.1);
+    compared with the oracle's latent output, and times B_v with the full decode call."""
+    import dataclasses
+    from gpu_util import TOL_FP, TOL_I4, make_desc, to_dev
+    layer = dataclasses.replace(synth.config_layer("3" if not v_i4 else "4"), rope_theta=theta)
+    case = synth.make_case_svd(layer, 2, 300, seed=9, rotate=v_i4)
+    case.seq_lens = np.array([300, 77], np.int32)
+    case.q_pos = np.array([299, 76], np.int32)
+    desc = make_desc(layer, "f16", False, v_i4)
+    q, Bk = to_dev(case.q, "f16"), to_dev(case.Bk, "f16")
+    hk = to_dev(case.Hk, "f16")
+    kw = {}
+    Hv_ref = case.Hv
+    if v_i4:
+        pv, sv, zv = O.quant_latent(case.Hv)
+        hv = torch.from_numpy(pv).cuda()
+        kw["hv_scale"] = torch.from_numpy(sv.view(np.int16)).cuda().view(torch.float16)
+        kw["hv_zero"] = torch.from_numpy(zv.view(np.int16)).cuda().view(torch.float16)
+        Hv_ref = O.dequant_latent(pv, sv, zv)
+    else:
+        hv = to_dev(case.Hv, "f16")
+    table = P.palu_rope_table_init(theta, 128, 300)
+    q_pos = torch.from_numpy(case.q_pos).cuda()
+    lens = torch.from_numpy(case.seq_lens).cuda()
+    got = P.palu_attn_decode_latent(desc, 2, 300, 300, q, q_pos, hk, hv, Bk, table, 300, seq_lens=lens, **kw)
+    torch.cuda.synchronize()
+    ref = O.attn_decode_latent(case.q, case.q_pos, case.Hk, Hv_ref, case.Bk, layer.group_head_off, layer.k_rank_off,
+                               layer.v_rank_off, 128, theta, seq_lens=case.seq_lens)
+    got = got.cpu().numpy()
+    assert got.shape == ref.shape
+    err = np.abs(got - ref).max() / np.abs(ref).max()
+    say(f"[latent] theta={theta} v_i4={v_i4} width={ref.shape[1]} rel err {err:.3e}")
+    assert err <= (TOL_I4 if v_i4 else TOL_FP)
