@@ -25,7 +25,6 @@ std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score wor
 std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
 std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
 std::atomic<int> g_opt_score_order{0};        // 0: automatic; 1: sequence chunk fastest; 2: unit fastest
-std::atomic<int> g_opt_score_early{0};        // 1: first MFMA phase overlaps the tail of the weight fetch
 
 int device_cu_count() {
   static std::atomic<int> cached[64];
@@ -451,8 +450,6 @@ int palu_set_option(const char* name, int value) {
   } else if (!std::strcmp(name, "score_order")) {
     if (value > 2) return PALU_ERR_INVALID_ARG;
     g_opt_score_order = value;
-  } else if (!std::strcmp(name, "score_early_start")) {
-    g_opt_score_early = value != 0;
   } else if (!std::strcmp(name, "value_split_tokens")) {
     if (value != 0 && (value % 32 != 0 || value > 4096)) return PALU_ERR_INVALID_ARG;
     g_opt_value_split = value;
@@ -837,8 +834,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
           set_chunks(a.units.n_units);
           const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
           a.unit_fastest = g_opt_score_order == 2;
-          a.early_start = g_opt_score_early;
-          hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
+            hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
           a.units.n_units = 0;
           return launch_ok();
         };

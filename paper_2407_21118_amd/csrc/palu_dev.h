@@ -117,7 +117,6 @@ struct ScoreArgs {
   int quant_block;
   float scale;               // log2(e) / sqrt(d_h)
   int unit_fastest;          // workgroup index order: unit fastest (else sequence chunk fastest)
-  int early_start;           // first MFMA phase starts while the tail of the weight fetch is in flight
   ScoreUnits units;
 };
 

@@ -335,7 +335,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 
   // ---- stationary operand: folded weights of (b, head), rows [32*rt0, 32*(rt0+RT))
   half8 W[NKS][RT];
-  {
+  auto load_weights = [&]() __attribute__((always_inline)) {
     const uint16_t* mf = a.mfold + (size_t)b * a.mfold_bstride + u.bk_off0 +
                          ((size_t)g_rel * u.s + u_in_g) * u.head_stride;
 #pragma unroll
@@ -343,7 +343,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
         W[ks][rt] = *reinterpret_cast<const half8*>(mf + ((size_t)(ks * 4 + rt0 + rt) * 64 + lane) * 8);
-  }
+  };
+  // Ping-pong with LDS-direct loads: the wavefronts that run the first MFMA phase fetch their
+  // weights now; the others only after the first barrier, so that the barrier does not wait
+  // for the issue of their 32 KiB each and their fetch overlaps the first phase.
+  constexpr bool kSplitStart = kPingPong && kDma;
+  if (!kSplitStart || wave < 4) load_weights();
 
   const int part_idx = u.part0 + (RT == 2 ? (rt0 >> 1) : 0);
   float* out_row = a.scores + ((size_t)part_idx * a.batch + b) * a.n_heads * (size_t)a.lpad + (size_t)hc * a.lpad;
@@ -412,10 +417,11 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   // ---- start-up
   if (kDma) {
     // tiles 0 .. kAheadTiles-1 are in flight; tile 0 must have landed before the first MFMA phase.
-    // The weight loads were issued after them: leaving those outstanding as well lets the first
-    // phase begin with the first k-steps' weights (the compiler waits per k-step from there on).
+    // Where the weight loads were issued after them, those stay outstanding as well: the first
+    // phase begins with the first k-steps' weights (the compiler waits per k-step from there on).
     constexpr int kStartWait = kInFlight * kDmaOps + NKS * RT;
-    if (kStartWait <= 63 && a.early_start) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kStartWait <= 63 ? kStartWait : 0));
+    static_assert(!kSplitStart || kStartWait <= 63, "start-up wait exceeds the counter");
+    if (kSplitStart && wave < 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kStartWait <= 63 ? kStartWait : 0));
     else dma_wait(std::integral_constant<int, kInFlight>{});
   } else {
     // tile 0 into LDS, tiles 1 and 2 in flight.  The explicit wait (vmcnt = 0) lets
@@ -426,6 +432,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     issue_loads(st[0], 2);
   }
   __syncthreads();
+  if (kSplitStart && wave >= 4) load_weights();
 
   if constexpr (!kPingPong && kDma && NKS >= 4) {
     // One wavefront per SIMD, software-pipelined: while the matrix pipe works on

@@ -78,14 +78,23 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
     const int k = kb + kq * 4;
     float4v acc = {0.f, 0.f, 0.f, 0.f};
     if (k < rv) {
-#pragma unroll 4
-      for (int c = sg; c < nsp; c += 4) {
-        const float4v v = *reinterpret_cast<const float4v*>(op + (size_t)c * a.o_stride + k);
-        const float wc = w[c];
-        acc.x = fmaf(wc, v.x, acc.x);
-        acc.y = fmaf(wc, v.y, acc.y);
-        acc.z = fmaf(wc, v.z, acc.z);
-        acc.w = fmaf(wc, v.w, acc.w);
+      // 16 independent loads per batch: the merge is a chain of L2 latencies otherwise
+      for (int c0 = sg; c0 < nsp; c0 += 64) {
+        float4v v[16];
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          const int c = min(c0 + 4 * x, nsp - 1);
+          v[x] = *reinterpret_cast<const float4v*>(op + (size_t)c * a.o_stride + k);
+        }
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          const int c = c0 + 4 * x;
+          const float wc = c < nsp ? w[c] : 0.f;
+          acc.x = fmaf(wc, v[x].x, acc.x);
+          acc.y = fmaf(wc, v[x].y, acc.y);
+          acc.z = fmaf(wc, v[x].z, acc.z);
+          acc.w = fmaf(wc, v[x].w, acc.w);
+        }
       }
     }
     *reinterpret_cast<float4v*>(part + (sg * 64 + kq) * 4) = acc;
@@ -114,15 +123,18 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   const uint16_t* Bv = a.Bv + m.bv_off[j] + u * kDHead + quarter * 32 + cq * 4;
   const int k_per = rv >> 5;                       // rank is a multiple of 32
   float4v o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-  for (int kk = 0; kk < k_per; ++kk) {
-    const int k = kp * k_per + kk;
-    const uint2v raw = *reinterpret_cast<const uint2v*>(Bv + (size_t)k * width);
-    const float ol = olat[k];
-    o.x = fmaf(ol, T::to_float((uint16_t)(raw.x & 0xffffu)), o.x);
-    o.y = fmaf(ol, T::to_float((uint16_t)(raw.x >> 16)), o.y);
-    o.z = fmaf(ol, T::to_float((uint16_t)(raw.y & 0xffffu)), o.z);
-    o.w = fmaf(ol, T::to_float((uint16_t)(raw.y >> 16)), o.w);
+  for (int k0 = 0; k0 < k_per; k0 += 8) {          // 8 independent loads per batch
+    uint2v raw[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) raw[x] = *reinterpret_cast<const uint2v*>(Bv + (size_t)(kp * k_per + min(k0 + x, k_per - 1)) * width);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const float ol = k0 + x < k_per ? olat[kp * k_per + k0 + x] : 0.f;
+      o.x = fmaf(ol, T::to_float((uint16_t)(raw[x].x & 0xffffu)), o.x);
+      o.y = fmaf(ol, T::to_float((uint16_t)(raw[x].x >> 16)), o.y);
+      o.z = fmaf(ol, T::to_float((uint16_t)(raw[x].y & 0xffffu)), o.z);
+      o.w = fmaf(ol, T::to_float((uint16_t)(raw[x].y >> 16)), o.w);
+    }
   }
   *reinterpret_cast<float4v*>(part + (kp * 8 + cq) * 4) = o;
   __syncthreads();
