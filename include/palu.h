@@ -86,7 +86,6 @@ int palu_version(void);
  * choose.  Not thread-safe against concurrent decode calls.
  *   "score_waves"         4 or 8 wavefronts per score workgroup for ranks <= 256
  *   "score_chunks"        sequence chunks per (sequence, head block) in the score kernel
- *   "score_order"         workgroup order of the score kernel: 1 = sequence chunk fastest, 2 = unit fastest
  *   "value_split_tokens"  tokens per sequence split in the value kernel (multiple of 32, <= 4096)
  * Unknown names and out-of-range values return PALU_ERR_INVALID_ARG.  Set
  * value_split_tokens before querying the workspace size: a smaller split needs

@@ -24,7 +24,6 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score workgroup (ranks <= 256)
 std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
 std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
-std::atomic<int> g_opt_score_order{0};        // 0: automatic; 1: sequence chunk fastest; 2: unit fastest
 
 int device_cu_count() {
   static std::atomic<int> cached[64];
@@ -447,9 +446,6 @@ int palu_set_option(const char* name, int value) {
     g_opt_score_waves = value;
   } else if (!std::strcmp(name, "score_chunks")) {
     g_opt_score_chunks = value;
-  } else if (!std::strcmp(name, "score_order")) {
-    if (value > 2) return PALU_ERR_INVALID_ARG;
-    g_opt_score_order = value;
   } else if (!std::strcmp(name, "value_split_tokens")) {
     if (value != 0 && (value % 32 != 0 || value > 4096)) return PALU_ERR_INVALID_ARG;
     g_opt_value_split = value;
@@ -627,6 +623,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
   int st = check_desc(desc, &m);
   if (st != PALU_OK) return st;
   if (batch <= 0 || seq_len <= 0 || max_seq < seq_len) return PALU_ERR_INVALID_ARG;
+  if (batch > 65535) return PALU_ERR_UNSUPPORTED;      // the batch index is a grid dimension
   if (!q || !q_pos || !hk || !hv || !Bk || !rope_table || !workspace) return PALU_ERR_INVALID_ARG;
   if (out_latent ? (out != nullptr) : (!out || !Bv)) return PALU_ERR_INVALID_ARG;
   const bool k_i4 = desc->k_latent_dtype == PALU_I4, v_i4 = desc->v_latent_dtype == PALU_I4;
@@ -735,8 +732,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
       if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
       auto flush = [&]() -> int {
         if (a.units.n_units == 0) return PALU_OK;
-        const unsigned grid = (unsigned)(a.units.n_units * ceil_div(a.n_split, 4) * batch);
-        hipLaunchKernelGGL(fn, dim3(grid), dim3(256), lds, s, a);
+        const dim3 grid((unsigned)a.units.n_units, (unsigned)ceil_div(a.n_split, 4), (unsigned)batch);
+        hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, a);
         a.units.n_units = 0;
         return launch_ok();
       };
@@ -832,9 +829,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
         auto flush = [&]() -> int {
           if (a.units.n_units == 0) return PALU_OK;
           set_chunks(a.units.n_units);
-          const unsigned grid = (unsigned)(a.units.n_units * a.n_chunks * batch);
-          a.unit_fastest = g_opt_score_order == 2;
-            hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
+          const dim3 grid((unsigned)a.n_chunks, (unsigned)a.units.n_units, (unsigned)batch);
+          hipLaunchKernelGGL(fn, grid, dim3(threads), lds, s, a);
           a.units.n_units = 0;
           return launch_ok();
         };
@@ -894,8 +890,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
     for (int cls = 0; cls < kNumPvCls; ++cls) {
       auto flush = [&]() -> int {
         if (a.units.n_units == 0) return PALU_OK;
-        const unsigned grid = (unsigned)(a.units.n_units * ceil_div(n_split, 4) * batch);
-        hipLaunchKernelGGL(pv_fn(act, v_i4, cls), dim3(grid), dim3(256), 0, s, a);
+        const dim3 grid((unsigned)a.units.n_units, (unsigned)ceil_div(n_split, 4), (unsigned)batch);
+        hipLaunchKernelGGL(pv_fn(act, v_i4, cls), grid, dim3(256), 0, s, a);
         a.units.n_units = 0;
         return launch_ok();
       };

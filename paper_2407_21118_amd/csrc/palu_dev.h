@@ -116,7 +116,6 @@ struct ScoreArgs {
   int n_blocks_q;            // R_k / quant_block (int4 only)
   int quant_block;
   float scale;               // log2(e) / sqrt(d_h)
-  int unit_fastest;          // workgroup index order: unit fastest (else sequence chunk fastest)
   ScoreUnits units;
 };
 

@@ -135,13 +135,10 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
   const int tl = lane & 31, hp = lane >> 5;        // softmax roles: token of the set; head parity
   const Meta& m = a.meta;
 
-  // unit fastest: neighbouring workgroups read neighbouring columns of the same rows
-  int wg = blockIdx.x;
-  const int unit = wg % a.units.n_units;
-  wg /= a.units.n_units;
-  const int n_sg = (a.n_split + 3) >> 2;
-  const int sg = wg % n_sg;
-  const int b = wg / n_sg;
+  // grid (units, groups of 4 splits, batch); unit fastest: neighbouring workgroups read
+  // neighbouring columns of the same rows.  The indices come from the workgroup id
+  // registers, so the unit descriptor and the other arguments load independently.
+  const int unit = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
   const int split = sg * 4 + wave;
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
   const int s0 = split * a.split_tokens;
@@ -151,6 +148,9 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
   const int last = ntok - 1;
 
   const PvUnit u = a.units.u[unit];
+  asm volatile("" :: "s"(a.hv), "s"(a.scores), "s"(a.seq_lens), "s"(a.o_part), "s"(a.ml_part), "s"(a.row_elems), "s"(a.max_seq),
+               "s"(a.part_stride), "s"(a.seq_len), "s"(a.lpad), "s"(a.split_tokens), "s"(a.n_split), "s"(a.o_stride),
+               "s"(u.c0), "s"((int)u.h0), "s"((int)u.ncols), "s"((int)u.nh));      // all in registers here: one round trip
   const int h0 = u.h0, nh = u.nh, c0 = u.c0;
   const int lpt = u.ncols >> 3;                    // 8-channel chunks per row of the unit
 

@@ -153,13 +153,12 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, kq = lane >> 4;       // token column (B, D) or head row (A); quarter of the 32 channels of a k-step
 
-  int wg = blockIdx.x;
-  const int unit = wg % a.units.n_units;
-  wg /= a.units.n_units;
-  const int n_sg = (a.n_split + 3) >> 2;
-  const int sg = wg % n_sg;
-  const int b = wg / n_sg;
+  // grid (units, groups of 4 token ranges, batch)
+  const int unit = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
   const QkUnit u = a.units.u[unit];
+  asm volatile("" :: "s"(a.hk), "s"(a.qt), "s"(a.seq_lens), "s"(a.scores), "s"(a.qt_bstride), "s"(a.row_elems), "s"(a.max_seq),
+               "s"(a.seq_len), "s"(a.lpad), "s"(a.n_heads), "s"(a.split_tokens), "s"(a.n_split), "s"(u.c0), "s"(u.q_off),
+               "s"((int)u.h0), "s"((int)u.ncols), "s"((int)u.wpad), "s"((int)u.nh));   // all in registers here: one round trip
   const int nh = u.nh, wpad = u.wpad;
   const int pitch = wpad + 8;                    // halfs per staged row: 16 bytes of padding keep the 16 head rows on distinct banks
 

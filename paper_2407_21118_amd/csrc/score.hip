@@ -114,24 +114,18 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   const int lane = tid & 63;
   const int lane_lo = lane & 31, lane_hi = lane >> 5;
 
-  // Workgroups are dealt to the 8 XCDs round-robin.  Unit fastest (with a multiple
-  // of 8 units): all sequence chunks of a unit run on one XCD, whose L2 then holds
-  // only that unit's folded weights.  Chunk fastest: an XCD sees every unit but
-  // only its share of the cos/sin rows.
-  int wg = blockIdx.x;
-  int chunk, unit, b;
-  if (a.unit_fastest) {
-    unit = wg % a.units.n_units;
-    wg /= a.units.n_units;
-    chunk = wg % a.n_chunks;
-    b = wg / a.n_chunks;
-  } else {
-    chunk = wg % a.n_chunks;
-    wg /= a.n_chunks;
-    unit = wg % a.units.n_units;
-    b = wg / a.units.n_units;
-  }
+  // grid (sequence chunks, units, batch): the indices come straight from the workgroup
+  // id registers, so the unit descriptor and the other arguments are fetched by
+  // independent scalar loads (one round trip, not a chain through index arithmetic).
+  // Chunk fastest: neighbouring workgroups (dealt to the 8 XCDs round-robin) work on
+  // different sequence chunks of the same heads.
+  const int chunk = blockIdx.x, unit = blockIdx.y, b = blockIdx.z;
   const ScoreUnit u = a.units.u[unit];
+  // have them all in registers here: the loads are issued together and waited for once
+  asm volatile("" :: "s"(a.seq_lens), "s"(a.seq_len), "s"(a.chunk_tokens), "s"(a.hk), "s"(a.rope_rows), "s"(a.row_elems),
+               "s"(a.max_seq), "s"(a.mfold), "s"(a.mfold_bstride), "s"(a.scores), "s"(a.lpad), "s"(a.batch), "s"(a.n_heads));
+  asm volatile("" :: "s"(u.h0), "s"(u.nh), "s"(u.s), "s"(u.head_off0), "s"(u.k_off0), "s"(u.bk_off0), "s"(u.head_stride),
+               "s"(u.part0));
 
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
   const int t_begin = chunk * a.chunk_tokens;
