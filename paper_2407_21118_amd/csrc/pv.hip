@@ -343,19 +343,23 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
     }
   };
 
-  // ---- a ring of register sets: the loads of the next kDepth-1 sets are in flight while
-  // one is consumed.
-  // Requests past the last set re-read its rows and are never consumed.
-  constexpr int kDepth = 2;
-  Set ring[kDepth];
-#pragma unroll
-  for (int d = 0; d < kDepth - 1; ++d) issue(ring[d], d);
-  for (int k = 0; k < n_sets; k += kDepth) {
-#pragma unroll
-    for (int d = 0; d < kDepth; ++d) {
-      issue(ring[(d + kDepth - 1) % kDepth], k + d + kDepth - 1);
-      if (k + d < n_sets) process(ring[d], k + d);
-    }
+  // ---- two register sets in turn: the next set's loads are in flight while one is
+  // consumed; nothing is requested past the last set
+  Set ring[2];
+  issue(ring[0], 0);
+  int k = 0;
+  for (; k + 2 < n_sets; k += 2) {
+    issue(ring[1], k + 1);
+    process(ring[0], k);
+    issue(ring[0], k + 2);
+    process(ring[1], k + 1);
+  }
+  if (k + 1 < n_sets) {
+    issue(ring[1], k + 1);
+    process(ring[0], k);
+    process(ring[1], k + 1);
+  } else {
+    process(ring[0], k);
   }
 
   // ---- results of the split

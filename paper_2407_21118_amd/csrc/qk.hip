@@ -309,23 +309,26 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
     }
   };
 
-  // steps (set, chunk) in order through a ring of register sets: the loads of the next
-  // kDepth-1 steps are in flight while one is consumed.
-  // Requests past the last step re-read its rows and are never consumed.
-  constexpr int kDepth = 2;
+  // steps (set, chunk) in order, two register sets in turn: the next step's loads are in
+  // flight while one is consumed; nothing is requested past the last step
   const int n_steps = n_sets * n_chunks;
   auto next = [&](int& set, int& chunk) { if (++chunk == n_chunks) { chunk = 0; ++set; } };
-  Step ring[kDepth];
+  Step ring[2];
   int is = 0, ic = 0, ps = 0, pc = 0;            // next step to request / to consume
-#pragma unroll
-  for (int d = 0; d < kDepth - 1; ++d) { issue(ring[d], is, ic); next(is, ic); }
-  for (int k = 0; k < n_steps; k += kDepth) {
-#pragma unroll
-    for (int d = 0; d < kDepth; ++d) {
-      issue(ring[(d + kDepth - 1) % kDepth], is, ic);
-      next(is, ic);
-      if (k + d < n_steps) { process(ring[d], ps, pc); next(ps, pc); }
-    }
+  issue(ring[0], is, ic); next(is, ic);
+  int k = 0;
+  for (; k + 2 < n_steps; k += 2) {
+    issue(ring[1], is, ic); next(is, ic);
+    process(ring[0], ps, pc); next(ps, pc);
+    issue(ring[0], is, ic); next(is, ic);
+    process(ring[1], ps, pc); next(ps, pc);
+  }
+  if (k + 1 < n_steps) {
+    issue(ring[1], is, ic);
+    process(ring[0], ps, pc); next(ps, pc);
+    process(ring[1], ps, pc);
+  } else {
+    process(ring[0], ps, pc);
   }
 }
 
