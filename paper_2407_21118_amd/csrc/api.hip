@@ -473,6 +473,10 @@ int palu_rope_table_init(float rope_theta, int32_t d_head, int32_t n_pos, void* 
 }
 
 // ------------------------------------------------------------------ encode
+namespace {
+constexpr int kEncodeGemmTokens = 64;    // from this many tokens on the projection runs as a tiled GEMM (no workspace)
+}
+
 int palu_encode_workspace_bytes(const palu_layer_desc* desc, int which, int32_t n_tok, size_t* out_bytes) {
   Meta m;
   const int st = check_desc(desc, &m);
@@ -483,9 +487,9 @@ int palu_encode_workspace_bytes(const palu_layer_desc* desc, int which, int32_t 
   for (int side = 0; side < 2; ++side) {
     if (which != 2 && which != side) continue;
     const int R = side ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
-    total += align_up((size_t)(d / kEncRows) * n_tok * R * 4);
+    total += align_up((size_t)(d / kEncRows) * std::min(n_tok, kEncodeGemmTokens - 1) * R * 4);
   }
-  *out_bytes = total;
+  *out_bytes = std::max<size_t>(total, 256);
   return PALU_OK;
 }
 
@@ -496,16 +500,18 @@ int encode_impl(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x
   Meta m;
   const int st = check_desc(desc, &m);
   if (st != PALU_OK) return st;
-  if (!x || !workspace || n_tok <= 0) return PALU_ERR_INVALID_ARG;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 15)) return PALU_ERR_INVALID_ARG;
+  if (!x || n_tok <= 0) return PALU_ERR_INVALID_ARG;
+  if (n_tok < kEncodeGemmTokens && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15))) return PALU_ERR_INVALID_ARG;
   const int d = m.n_heads * PALU_D_HEAD;
+  const bool gemm = n_tok >= kEncodeGemmTokens;      // many tokens: tiled GEMM, no workspace
+  if (reinterpret_cast<uintptr_t>(x) & 15) return PALU_ERR_INVALID_ARG;
   EncodeArgs a;
   std::memset(&a, 0, sizeof(a));
   a.x = static_cast<const uint16_t*>(x);
   a.dst_row = dst_row;
   a.n_tok = n_tok;
   a.d = d;
-  a.k_splits = d / kEncRows;
+  a.k_splits = gemm ? 0 : d / kEncRows;
   size_t off = 0;
   int n_sides = 0, max_R = 0;
   for (int side = 0; side < 2; ++side) {
@@ -527,6 +533,18 @@ int encode_impl(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x
   }
   if (workspace_bytes < off) return PALU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (gemm) {
+    const size_t lds = (size_t)2 * kGemmTile * kGemmPitch * 2;
+    const dim3 g((unsigned)ceil_div(max_R, kGemmTile), (unsigned)ceil_div(n_tok, kGemmTile), (unsigned)n_sides);
+    if (desc->act_dtype == PALU_F16) {
+      if (allow_lds(encode_gemm_kernel<F16>, lds) != PALU_OK) return PALU_ERR_HIP;
+      hipLaunchKernelGGL(encode_gemm_kernel<F16>, g, dim3(256), lds, s, a);
+    } else {
+      if (allow_lds(encode_gemm_kernel<BF16>, lds) != PALU_OK) return PALU_ERR_HIP;
+      hipLaunchKernelGGL(encode_gemm_kernel<BF16>, g, dim3(256), lds, s, a);
+    }
+    return launch_ok();
+  }
   const dim3 g1((unsigned)ceil_div(max_R, kEncCols), (unsigned)a.k_splits, (unsigned)n_sides);
   const dim3 g2((unsigned)ceil_div(max_R, 64), (unsigned)n_tok, (unsigned)n_sides);
   using EncFn = void (*)(EncodeArgs);

@@ -134,6 +134,108 @@ __global__ __launch_bounds__(256) void encode_finish_kernel(EncodeArgs a) {
   }
 }
 
+// ---- many tokens at once (filling the cache from a prompt): a tiled GEMM on the matrix
+// cores, C[n_tok, R] = X[n_tok, d] A[d, R].  Workgroup = 128 x 128 outputs, four
+// wavefronts of 64 x 64 (2 x 2 tiles of v_mfma_f32_32x32x16), k in stages of 128
+// through LDS with the next stage prefetched into registers.  X is k-contiguous,
+// which is what an MFMA operand wants; A is column-contiguous, so each thread loads
+// one 8-column chunk of 8 consecutive k and transposes the 8 x 8 block in registers
+// (one byte permute per operand register) on its way to LDS.
+constexpr int kGemmTile = 128;    // outputs per workgroup in each dimension, and k per stage
+constexpr int kGemmPitch = kGemmTile + 8;    // halfs per LDS row: 16-byte reads of 16 consecutive rows hit distinct banks
+
+// grid (ceil(max R / 128), ceil(n_tok / 128), sides), 256 threads, 2 * 128 * kGemmPitch * 2 bytes of LDS.
+template <typename T>
+__global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char gemm_lds[];
+  uint16_t* Xs = reinterpret_cast<uint16_t*>(gemm_lds);                 // [128 tokens][kGemmPitch]
+  uint16_t* As = Xs + kGemmTile * kGemmPitch;                            // [128 columns][kGemmPitch]: transposed
+  const EncodeSide sd = a.side[blockIdx.z];
+  const int n0 = blockIdx.x * kGemmTile, m0 = blockIdx.y * kGemmTile;
+  if (n0 >= sd.R) return;                                                // uniform
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane_lo = lane & 31, lane_hi = lane >> 5;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;                 // this wavefront's 64 x 64 corner of the tile
+
+  // staging roles.  X: chunk id = tid + 256 i (i < 8): token row id / 16, 16-byte piece id % 16 of the stage's 128 k.
+  // A: one (k-octet oct, 8-column chunk cc) item per thread: rows k0 + 8 oct + j (j < 8), columns n0 + 8 cc ..
+  const int oct = tid >> 4, cc = tid & 15;
+  const int a_col = min(n0 + cc * 8, sd.R - 8);                          // R is a multiple of 32: clamped chunks are never stored
+  uint4v xr[8], ar[8];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int id = tid + 256 * i;
+      const int row = min(m0 + (id >> 4), a.n_tok - 1);
+      xr[i] = *reinterpret_cast<const uint4v*>(a.x + (size_t)row * a.d + k0 + (id & 15) * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ar[j] = *reinterpret_cast<const uint4v*>(sd.A + (size_t)(k0 + oct * 8 + j) * sd.R + a_col);
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int id = tid + 256 * i;
+      *reinterpret_cast<uint4v*>(Xs + (id >> 4) * kGemmPitch + (id & 15) * 8) = xr[i];
+    }
+    // 8 x 8 transpose: column e of the chunk over the 8 k rows, as four (k, k+1) pairs
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      uint4v t;
+#pragma unroll
+      for (int jp = 0; jp < 4; ++jp)
+        t[jp] = __builtin_amdgcn_perm(ar[2 * jp + 1][e >> 1], ar[2 * jp][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
+      *reinterpret_cast<uint4v*>(As + (cc * 8 + e) * kGemmPitch + oct * 8) = t;
+    }
+  };
+
+  float16v acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  fetch(0);
+  for (int k0 = 0; k0 < a.d; k0 += kGemmTile) {
+    __syncthreads();                        // the previous stage has been read
+    stash();
+    __syncthreads();
+    if (k0 + kGemmTile < a.d) fetch(k0 + kGemmTile);
+#pragma unroll
+    for (int ks = 0; ks < kGemmTile / 16; ++ks) {
+      typename T::vec8 xa[2], ab[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        xa[i] = *reinterpret_cast<const typename T::vec8*>(Xs + (wm + 32 * i + lane_lo) * kGemmPitch + ks * 16 + lane_hi * 8);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        ab[j] = *reinterpret_cast<const typename T::vec8*>(As + (wn + 32 * j + lane_lo) * kGemmPitch + ks * 16 + lane_hi * 8);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = T::mfma(xa[i], ab[j], acc[i][j]);
+    }
+  }
+
+  // accumulator element e of tile (i, j): token m0 + wm + 32 i + mfma_row(e), column n0 + wn + 32 j + lane_lo
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int t = m0 + wm + 32 * i + mfma_row(e, lane_hi);
+      if (t >= a.n_tok) continue;
+      const long long row = a.dst_row ? a.dst_row[t] : t;
+      uint16_t* dst = sd.latent + row * sd.row_stride;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int c = n0 + wn + 32 * j + lane_lo;
+        if (c < sd.R) dst[c] = T::from_float(acc[i][j][e]);
+      }
+    }
+}
+
 struct QuantArgs {
   const uint16_t* latent;
   uint8_t* codes;
@@ -188,6 +290,8 @@ __global__ __launch_bounds__(256) void quant_kernel(QuantArgs a) {
   template __global__ void encode_partial_kernel<T, 8>(EncodeArgs);
 PALU_ENC_INST(F16)
 PALU_ENC_INST(BF16)
+template __global__ void encode_gemm_kernel<F16>(EncodeArgs);
+template __global__ void encode_gemm_kernel<BF16>(EncodeArgs);
 template __global__ void encode_finish_kernel<F16>(EncodeArgs);
 template __global__ void encode_finish_kernel<BF16>(EncodeArgs);
 template __global__ void quant_kernel<F16>(QuantArgs);

@@ -200,3 +200,79 @@ def test_latent_output_matches_oracle(theta, v_i4):
     err = np.abs(got - ref).max() / np.abs(ref).max()
     say(f"[latent] theta={theta} v_i4={v_i4} width={ref.shape[1]} rel err {err:.3e}")
     assert err <= (TOL_I4 if v_i4 else TOL_FP)
+
+
+def test_decode_step_in_a_captured_graph():
+    """Append + decode captured into a HIP graph (the calls allocate nothing and never
+    synchronise): four replays with fresh inputs written into the captured buffers, each
+    compared bit for bit with the same step launched eagerly in between."""
+    from workloads import device as wd
+    layer = synth.config_layer("2")
+    batch, seq = 2, 1111
+    case = wd.make_device_case("2", seed=1, dtype="f16", n_sets=1, batch=batch, seq=seq)
+    desc = P.LayerDesc(layer.n_heads, layer.d_head, layer.group_head_off, layer.k_rank_off, layer.v_rank_off)
+    table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, seq)
+    ws = torch.empty(P.palu_attn_decode_workspace_bytes(desc, batch, seq), dtype=torch.uint8, device="cuda")
+    ws_e = torch.empty(P.palu_encode_workspace_bytes(desc, 2, batch), dtype=torch.uint8, device="cuda")
+    out = torch.empty((batch, layer.n_heads, layer.d_head), dtype=torch.float32, device="cuda")
+    dst_row = (torch.arange(batch, dtype=torch.int32, device="cuda") * seq + (seq - 1)).contiguous()
+    q_buf, x_buf = case.q.clone(), case.x_new.clone()
+    side = torch.cuda.Stream()
+
+    def step():
+        s = torch.cuda.current_stream()
+        P.palu_encode_kv(desc, x_buf, case.Ak, case.Av, case.Hk[0], layer.R_k, case.Hv[0], layer.R_v, dst_row, ws_e, stream=s)
+        P.palu_attn_decode(desc, batch, seq, seq, q_buf, case.q_pos, case.Hk[0], case.Hv[0], case.Bk, case.Bv, table,
+                           seq, out=out, workspace=ws, stream=s)
+
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    for it in range(4):
+        q_buf.copy_(torch.randn(q_buf.shape, generator=gen, device="cuda").half())
+        x_buf.copy_(torch.randn(x_buf.shape, generator=gen, device="cuda").half())
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.synchronize()
+        say(f"[graph] replay {it}: max abs diff to eager {float((got - out).abs().max()):.3e}")
+        assert torch.equal(got, out)
+
+
+@pytest.mark.parametrize("dtype,n_tok", [("f16", 64), ("f16", 300), ("bf16", 129)])
+def test_encode_many_tokens_gemm_path(dtype, n_tok):
+    """Prompt-sized append: from 64 tokens on palu_encode runs as a tiled GEMM on the matrix
+    cores.  A layer whose total rank (1344) is not a multiple of the 128-column tile, a
+    ragged token count, scattered destination rows; palu_encode_kv covers both sides."""
+    say(f"[encode-gemm] dtype={dtype} n_tok={n_tok}")
+    k_ranks = [32, 64, 128, 96, 128, 384, 512]
+    v_ranks = [64, 32, 128, 256, 96, 128, 512]
+    layer = synth.Layer(16, 128, [0, 1, 2, 4, 6, 7, 10, 16], [0] + list(np.cumsum(k_ranks)), [0] + list(np.cumsum(v_ranks)))
+    rng = np.random.default_rng(11)
+    d = layer.n_heads * layer.d_head
+    Ak = synth.round_to(rng.standard_normal((d, layer.R_k)) / 45.0, dtype)
+    Av = synth.round_to(rng.standard_normal((d, layer.R_v)) / 45.0, dtype)
+    x = synth.round_to(rng.standard_normal((n_tok, d)), dtype)
+    desc = make_desc(layer, dtype)
+    td = torch.float16 if dtype == "f16" else torch.bfloat16
+    rows = n_tok + 50
+    perm = rng.permutation(rows)[:n_tok].astype(np.int32)
+    hk = torch.full((rows, layer.R_k), 7.0, dtype=td, device="cuda")
+    hv = torch.full((rows, layer.R_v + 32), 7.0, dtype=td, device="cuda")
+    P.palu_encode_kv(desc, to_dev(x, dtype), to_dev(Ak, dtype), to_dev(Av, dtype), hk, layer.R_k, hv, layer.R_v + 32,
+                     torch.from_numpy(perm).cuda())
+    torch.cuda.synchronize()
+    eps = 2.0 ** -11 if dtype == "f16" else 2.0 ** -8
+    for got, ref, R in ((hk.float().cpu().numpy(), O.encode(x, Ak), layer.R_k), (hv.float().cpu().numpy(), O.encode(x, Av), layer.R_v)):
+        err = np.abs(got[perm, :R] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+        say(f"       worst row error {err.max():.3e} (bound {eps * 1.05:.3e})")
+        assert err.max() <= eps * 1.05 + 1e-6
+        untouched = np.setdiff1d(np.arange(rows), perm)
+        assert (got[untouched] == 7.0).all() and (got[:, R:] == 7.0).all()
