@@ -245,7 +245,7 @@ def main() -> int:
             "latent_read_GBps": k_gbs,
         },
         "roofline_value": {
-            "kernel": "value_kernel (softmax partials + P.H_v, split-K)",
+            "kernel": "pv_kernel (softmax partials + P.H_v on MFMA, one wavefront per sequence split)",
             "bound": "hbm", "achieved": v_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": v_gbs / HBM_PEAK_GBS,
             "traffic": None, "launch_us": stage_us["value"], "bytes_per_launch": work["v_latent_bytes"],
         },
