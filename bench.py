@@ -71,6 +71,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ring-gib", type=float, default=1.0, help="distinct latent bytes to cycle through")
     ap.add_argument("--opt", action="append", default=[], help="tuning knob name=value (palu_set_option)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the bare MFMA / read probes (measured_peaks)")
     ap.add_argument("--no-rope", action="store_true",
                     help="the paper's non-RoPE attention (rope_theta = 0): the query is folded into the latent "
                          "space and the scores come straight from the key latents")
@@ -256,6 +257,48 @@ def main() -> int:
         "step_GBps_algorithmic": total_gbs,
         "wall_ms_per_step": wall_ms / args.steps,
     }
+
+    # ---- what this GPU sustains on a bare matrix-core loop and a bare streaming read (device probes of the
+    # library): the rooflines above use the data-sheet peaks, these give the fractions of measured ceilings
+    if not args.no_probes:
+        props = torch.cuda.get_device_properties(0)
+        sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+        pe0, pe1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best_tf = 0.0
+        for _ in range(3):                                   # ~1.3 ms each
+            pe0.record()
+            fl = P.palu_probe_mfma(10000, sink)
+            pe1.record()
+            torch.cuda.synchronize()
+            best_tf = max(best_tf, fl / (pe0.elapsed_time(pe1) * 1e-3) / 1e12)
+        big = torch.empty(2 * 2 ** 30, dtype=torch.uint8, device="cuda").fill_(1)
+        best_big = best_small = 0.0
+        for _ in range(3):
+            pe0.record()
+            nb = P.palu_probe_read(big, sink)
+            pe1.record()
+            torch.cuda.synchronize()
+            best_big = max(best_big, nb / (pe0.elapsed_time(pe1) * 1e-3) / 1e9)
+        small_b = int(work["v_latent_bytes"])
+        for i in range(6):                                   # one launch of the value kernel's size, distinct memory each time
+            view = big[(i * small_b) % (big.numel() - small_b):][:small_b]
+            pe0.record()
+            nb = P.palu_probe_read(view, sink)
+            pe1.record()
+            torch.cuda.synchronize()
+            best_small = max(best_small, nb / (pe0.elapsed_time(pe1) * 1e-3) / 1e9)
+        del big
+        result["measured_peaks"] = {
+            "device": props.name, "compute_units": props.multi_processor_count,
+            "mfma_f16_TFLOPs": best_tf, "hbm_read_GBps_2GiB": best_big,
+            "hbm_read_GBps_one_launch_of_value_bytes": best_small,
+            "note": "best of 3 (6) launches of the library's probe kernels, timed with events on the launch stream",
+        }
+        result["roofline"]["frac_of_measured"] = (result["roofline"]["achieved"] /
+                                                  (best_tf if result["roofline"]["bound"] == "mfma" else best_big))
+        result["roofline_value"]["frac_of_measured"] = result["roofline_value"]["achieved"] / best_big
+        log(f"[bench] probes: MFMA fp16 {best_tf:.0f} TFLOP/s, read {best_big:.0f} GB/s (2 GiB), "
+            f"{best_small:.0f} GB/s (one {small_b / 2**20:.0f} MiB launch)")
 
     if args.copy_probe > 0:
         src = torch.empty(args.copy_probe * 2 ** 20, dtype=torch.uint8, device="cuda").fill_(1)

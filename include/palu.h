@@ -94,6 +94,19 @@ int palu_version(void);
 int palu_set_option(const char* name, int value);
 
 /*
+ * Device probes for benchmarking (not part of the method): what this GPU sustains
+ * on a bare matrix-core loop and on a bare streaming read, so that kernel rates can
+ * be quoted against measured ceilings as well as against the data-sheet peaks.
+ *   palu_probe_mfma  every SIMD issues iters*4*2 independent v_mfma_f32_32x32x16_f16;
+ *                    *out_flops (HOST, may be NULL) receives the FLOPs of the launch
+ *   palu_probe_read  reads `bytes` bytes (multiple of 16) at src (DEVICE, 16-byte aligned) once
+ *   sink             DEVICE float[1]; practically never written
+ * Time the launches with events on `stream`.
+ */
+int palu_probe_mfma(int32_t iters, float* sink, void* stream, double* out_flops);
+int palu_probe_read(const void* src, size_t bytes, float* sink, void* stream);
+
+/*
  * RoPE angle table (Sec. 3.1.2: RoPE acts on queries and keys before their
  * product).  For position p and pair f < d_h/2 the table stores, as float16,
  * cos(p w_f) and sin(p w_f) with w_f = theta^(-2f/d_h), computed in float64;

@@ -67,6 +67,10 @@ def load_library():
     lib.palu_version.argtypes = []
     lib.palu_set_option.restype = ctypes.c_int
     lib.palu_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
+    lib.palu_probe_mfma.argtypes = [i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.palu_probe_mfma.restype = ctypes.c_int
+    lib.palu_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.palu_probe_read.restype = ctypes.c_int
     lib.palu_rope_table_bytes.argtypes = [i32, i32, szp]
     lib.palu_rope_table_init.argtypes = [ctypes.c_float, i32, i32, vp, vp]
     lib.palu_encode_workspace_bytes.argtypes = [dp, ctypes.c_int, i32, szp]
@@ -274,3 +278,19 @@ def palu_attn_decode_latent(desc: LayerDesc, batch: int, seq_len: int, max_seq: 
         _ptr(rope_table), int(rope_table_len), _ptr(out_latent), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)), "palu_attn_decode_latent")
     return out_latent
+
+
+def palu_probe_mfma(iters: int, sink, stream=None) -> float:
+    """Launches the bare matrix-core loop; returns the FLOPs of the launch (time it with events)."""
+    _need_cuda(sink)
+    fl = ctypes.c_double(0.0)
+    _check(load_library().palu_probe_mfma(int(iters), _ptr(sink), _stream(stream), ctypes.byref(fl)), "palu_probe_mfma")
+    return float(fl.value)
+
+
+def palu_probe_read(src, sink, stream=None) -> int:
+    """Launches the bare streaming read over `src`; returns the bytes read."""
+    _need_cuda(src, sink)
+    nbytes = (src.numel() * src.element_size()) // 16 * 16
+    _check(load_library().palu_probe_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "palu_probe_read")
+    return nbytes

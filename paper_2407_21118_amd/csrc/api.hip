@@ -7,6 +7,7 @@
 #include "value.hip"
 #include "pv.hip"
 #include "qk.hip"
+#include "probe.hip"
 
 #include <atomic>
 #include <cmath>
@@ -438,6 +439,21 @@ const char* palu_status_string(int status) {
 }
 
 int palu_version(void) { return 100; }
+
+int palu_probe_mfma(int32_t iters, float* sink, void* stream, double* out_flops) {
+  if (iters <= 0 || !sink) return PALU_ERR_INVALID_ARG;
+  const int cus = device_cu_count();
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3((unsigned)(cus * 2)), dim3(256), 0, static_cast<hipStream_t>(stream), sink, iters);
+  if (out_flops) *out_flops = (double)cus * 2 * 4 /* wavefronts */ * iters * 4.0 * (2.0 * 32 * 32 * 16);
+  return launch_ok();
+}
+
+int palu_probe_read(const void* src, size_t bytes, float* sink, void* stream) {
+  if (!src || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15)) return PALU_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)(device_cu_count() * 8)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4v*>(src), bytes / 16, sink);
+  return launch_ok();
+}
 
 int palu_set_option(const char* name, int value) {
   if (!name || value < 0) return PALU_ERR_INVALID_ARG;
