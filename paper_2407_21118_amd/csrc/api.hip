@@ -4,7 +4,7 @@
 #include "encode_quant.hip"
 #include "rope_fold.hip"
 #include "score.hip"
-#include "value.hip"
+#include "combine.hip"
 #include "pv.hip"
 #include "qk.hip"
 #include "probe.hip"
