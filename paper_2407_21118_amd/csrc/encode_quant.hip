@@ -185,9 +185,17 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a) {
 #pragma unroll
       for (int jp = 0; jp < 4; ++jp)
         t[jp] = __builtin_amdgcn_perm(ar[2 * jp + 1][e >> 1], ar[2 * jp][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
-      *reinterpret_cast<uint4v*>(As + (cc * 8 + e) * kGemmPitch + oct * 8) = t;
+      // the 16-byte k-octets of a row are stored XOR-swizzled by the row's chunk number: the 16 lanes
+      // of a store pass (16 chunks, 8 rows apart) would otherwise share two bank groups
+      *reinterpret_cast<uint4v*>(As + (cc * 8 + e) * kGemmPitch + ((oct & 8) | ((oct ^ cc) & 7)) * 8) = t;
     }
   };
+  // read side of the swizzle: k-step ks reads octet 2 ks + lane_hi of row n, stored at octet ^ ((n >> 3) & 7)
+  int a_sw[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a_sw[j][q] = ((2 * q + lane_hi) ^ (((wn + 32 * j + lane_lo) >> 3) & 7)) * 8;
 
   float16v acc[2][2];
 #pragma unroll
@@ -211,7 +219,7 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a) {
         xa[i] = *reinterpret_cast<const typename T::vec8*>(Xs + (wm + 32 * i + lane_lo) * kGemmPitch + ks * 16 + lane_hi * 8);
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        ab[j] = *reinterpret_cast<const typename T::vec8*>(As + (wn + 32 * j + lane_lo) * kGemmPitch + ks * 16 + lane_hi * 8);
+        ab[j] = *reinterpret_cast<const typename T::vec8*>(As + (wn + 32 * j + lane_lo) * kGemmPitch + (ks >> 2) * 64 + a_sw[j][ks & 3]);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
