@@ -17,10 +17,11 @@
 // kernel stays bound by the latent stream for every head-group size, including
 // one latent shared by all 32 heads.
 //
-// 4-bit latents: codes are expanded to exact fp16 integers while transposing;
+// 4-bit latents: while transposing, a code c becomes the exact fp16 number 1 + c/16
+// (the nibble placed in the top mantissa bits, two operations per register);
 // the per-(token, 128-channel block) scale is folded into the probabilities
-// (one probability tile per block) and the zero-points into one scalar per
-// (head, block): sum_t p s (c - z) = sum_t (p s) c - sum_t (p s) z.
+// (one probability tile per block, a = p s) and the zero-points and the offset
+// into one scalar per (head, block): sum_t a (c - z) = 16 sum_t a (1 + c/16) - sum_t a (16 + z).
 
 #include "palu_dev.h"
 
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
           const float sc = F16::to_float((uint16_t)(st.sz[g] & 0xffffu));
           const float zp = F16::to_float((uint16_t)(st.sz[g] >> 16));
           const _Float16 ah = (_Float16)(p * sc);
-          lz[i][g] = fmaf((float)ah, zp, lz[i][g]);
+          lz[i][g] = fmaf((float)ah, zp + 16.f, lz[i][g]);      // codes enter the product as 1 + c/16, see below
           pw[g * (MT * 16 * kPitch) + slot] = ah;
         }
       }
@@ -323,12 +324,10 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
           for (int kb = 0; kb < 4; ++kb) {
             // byte kb of both tokens' code words side by side: [0, tok b byte, 0, tok a byte]
             const uint32_t w = __builtin_amdgcn_perm(bl.h[2 * jp + 1][0], bl.h[2 * jp][0], 0x0c040c00u + 0x00010001u * kb);
-            // 0x6400 | c is the fp16 number 1024 + c; 0x6400 | (c << 4) is 1024 + 16 c
-            const half2v ev = __builtin_bit_cast(half2v, (w & 0x000f000fu) | 0x64006400u) - half2v{(_Float16)1024.f, (_Float16)1024.f};
-            const half2v od = __builtin_bit_cast(half2v, (w & 0x00f000f0u) | 0x64006400u) * half2v{(_Float16)0.0625f, (_Float16)0.0625f} -
-                              half2v{(_Float16)64.f, (_Float16)64.f};
-            o[2 * kb][jp] = __builtin_bit_cast(uint32_t, ev);
-            o[2 * kb + 1][jp] = __builtin_bit_cast(uint32_t, od);
+            // a code c in the top four mantissa bits of 0x3c00 is the fp16 number 1 + c/16 (exact):
+            // sum_t a_t (1 + c_t/16) = sum a + (sum a c)/16, undone at the write-out together with the zero-points
+            o[2 * kb][jp] = ((w << 6) & 0x03c003c0u) | 0x3c003c00u;         // even channel: low nibbles
+            o[2 * kb + 1][jp] = ((w << 2) & 0x03c003c0u) | 0x3c003c00u;     // odd channel: high nibbles
           }
         }
       }
@@ -398,10 +397,14 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
         const int chunk = ng * 16 + n;
         const int col = c0 + chunk * 8;
         if (chunk >= lpt || col < lo || col >= hi) continue;   // a head keeps the columns of its own group
+        // int4: acc = sum a (1 + c/16) and zt = sum a (16 + z), so sum a (c - z) = 16 acc - zt
         const float zt = I4 ? xw[hh * NA + ng] : 0.f;
+        const float g = I4 ? 16.f : 1.f;
         float4v v0, v1;
-        v0.x = acc[mt][ng][0][r] - zt; v0.y = acc[mt][ng][1][r] - zt; v0.z = acc[mt][ng][2][r] - zt; v0.w = acc[mt][ng][3][r] - zt;
-        v1.x = acc[mt][ng][4][r] - zt; v1.y = acc[mt][ng][5][r] - zt; v1.z = acc[mt][ng][6][r] - zt; v1.w = acc[mt][ng][7][r] - zt;
+        v0.x = fmaf(g, acc[mt][ng][0][r], -zt); v0.y = fmaf(g, acc[mt][ng][1][r], -zt);
+        v0.z = fmaf(g, acc[mt][ng][2][r], -zt); v0.w = fmaf(g, acc[mt][ng][3][r], -zt);
+        v1.x = fmaf(g, acc[mt][ng][4][r], -zt); v1.y = fmaf(g, acc[mt][ng][5][r], -zt);
+        v1.z = fmaf(g, acc[mt][ng][6][r], -zt); v1.w = fmaf(g, acc[mt][ng][7][r], -zt);
         *reinterpret_cast<float4v*>(oh + col) = v0;
         *reinterpret_cast<float4v*>(oh + col + 4) = v1;
       }

@@ -19,9 +19,9 @@
 // diagonal), or one whole group of up to 32 heads, walked in chunks of 256 columns.
 //
 // 4-bit latents: a lane's 16-byte load holds the 32 codes of a quarter of a
-// quantization block; the codes enter the matrix cores as exact fp16 integers and
-// the scale and zero-point are applied to the block's sum per token:
-//   sum_k s (c_k - z) qt_k = s (sum_k c_k qt_k - z sum_k qt_k).
+// quantization block; a code c enters the matrix cores as the exact fp16 number
+// 1 + c/16 and the scale, zero-point and offset are applied to the block's sum per token:
+//   sum_k s (c_k - z) qt_k = s (16 sum_k (1 + c_k/16) qt_k - (16 + z) sum_k qt_k).
 
 #include "palu_dev.h"
 
@@ -277,9 +277,9 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
             uint4v bw;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              // (even code, odd code) of byte e as the fp16 pair (1024 + c_even, 1024 + c_odd), then minus 1024
-              const uint32_t pr = __builtin_amdgcn_perm(hi, lo, 0x0c040c00u + 0x00010001u * e) | 0x64006400u;
-              bw[e] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, pr) - half2v{(_Float16)1024.f, (_Float16)1024.f});
+              // (even code, odd code) of byte e as the fp16 pair (1 + c_even/16, 1 + c_odd/16): the nibble in the
+              // top mantissa bits of 0x3c00; the offset is undone on the block's sum below
+              bw[e] = (__builtin_amdgcn_perm(hi, lo, 0x0c040c00u + 0x00010001u * e) << 6) | 0x3c003c00u;
             }
             const half8 bop = __builtin_bit_cast(half8, bw);
 #pragma unroll
@@ -290,7 +290,8 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[mt][tau][r] = fmaf(sc, fmaf(-zp, qs[mt][r], d[mt][r]), acc[mt][tau][r]);
+            for (int r = 0; r < 4; ++r)      // d = sum qt (1 + c/16): sum qt (c - z) = 16 d - (16 + z) sum qt
+              acc[mt][tau][r] = fmaf(sc, fmaf(-(zp + 16.f), qs[mt][r], 16.f * d[mt][r]), acc[mt][tau][r]);
         }
       }
     }
