@@ -171,6 +171,25 @@ int palu_quant_latent(const palu_layer_desc* desc, int which, const void* latent
                       void* stream);
 
 /*
+ * Down-projection and 4-bit quantization of new tokens in one kernel, for filling
+ * a quantized cache from a prompt (Sec. 3.1 first display, then Appendix A with
+ * B = 4, Sec. 3.4): the unquantized latents never reach memory.  The bytes written
+ * are those of palu_encode (its many-token form, n_tok >= 64) followed by
+ * palu_quant_latent: the product is accumulated in float32, rounded once to
+ * act_dtype, and quantized from that rounded value.  Works for any n_tok >= 1 but
+ * computes in tiles of 128 tokens, so for a handful of tokens the two-call form
+ * is cheaper.
+ *   which       0 = key side, 1 = value side; R = rank_off[n_groups] must be a multiple of 128
+ *   x, A        as for palu_encode (16-byte aligned)
+ *   codes       DEVICE uint8 rows of R/2 bytes, 16-byte aligned, layout as palu_quant_latent
+ *   scale,zero  DEVICE float16 rows of R/128
+ *   dst_row     DEVICE int32 [n_tok] output row per token, or NULL for row t
+ * Needs no workspace.  Writes only the rows named.
+ */
+int palu_encode_quant(const palu_layer_desc* desc, int which, const void* x, int32_t n_tok, const void* A,
+                      uint8_t* codes, void* scale, void* zero, const int32_t* dst_row, void* stream);
+
+/*
  * One decode step of attention over the latent cache for `batch` sequences
  * (Sec. 2.1 Eq. 2 with K = RoPE(H_k B_k) rebuilt on the fly, Sec. 3.1.2 and
  * Appendix B; values contracted in latent space first, (p H_v) B_v, Eq. 4):

@@ -78,6 +78,8 @@ def load_library():
     lib.palu_encode_kv.argtypes = [dp, vp, i32, vp, vp, vp, i64, vp, i64, vp, vp, sz, vp]
     lib.palu_encode_kv.restype = ctypes.c_int
     lib.palu_quant_latent.argtypes = [dp, ctypes.c_int, vp, i64, i32, vp, vp, vp, vp, vp]
+    lib.palu_encode_quant.argtypes = [dp, ctypes.c_int, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.palu_encode_quant.restype = ctypes.c_int
     lib.palu_attn_decode_workspace_bytes.argtypes = [dp, i32, i32, szp]
     lib.palu_attn_decode.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                      vp, i32, vp, vp, sz, vp]
@@ -221,6 +223,14 @@ def palu_quant_latent(desc: LayerDesc, which: int, latent, row_stride_elems: int
     _check(load_library().palu_quant_latent(desc.ref(), which, _ptr(latent), int(row_stride_elems), int(n_tok),
                                             _ptr(codes), _ptr(scale), _ptr(zero), _ptr(dst_row), _stream(stream)),
            "palu_quant_latent")
+    return codes, scale, zero
+
+
+def palu_encode_quant(desc: LayerDesc, which: int, x, n_tok: int, A, codes, scale, zero, dst_row=None, stream=None):
+    _need_cuda(x, A, codes, scale, zero, dst_row)
+    _check(load_library().palu_encode_quant(desc.ref(), which, _ptr(x), int(n_tok), _ptr(A), _ptr(codes),
+                                            _ptr(scale), _ptr(zero), _ptr(dst_row), _stream(stream)),
+           "palu_encode_quant")
     return codes, scale, zero
 
 

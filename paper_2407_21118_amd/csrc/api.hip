@@ -553,11 +553,11 @@ int encode_impl(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x
     const size_t lds = (size_t)2 * kGemmTile * kGemmPitch * 2;
     const dim3 g((unsigned)ceil_div(max_R, kGemmTile), (unsigned)ceil_div(n_tok, kGemmTile), (unsigned)n_sides);
     if (desc->act_dtype == PALU_F16) {
-      if (allow_lds(encode_gemm_kernel<F16>, lds) != PALU_OK) return PALU_ERR_HIP;
-      hipLaunchKernelGGL(encode_gemm_kernel<F16>, g, dim3(256), lds, s, a);
+      if (allow_lds(encode_gemm_kernel<F16, false>, lds) != PALU_OK) return PALU_ERR_HIP;
+      hipLaunchKernelGGL((encode_gemm_kernel<F16, false>), g, dim3(256), lds, s, a);
     } else {
-      if (allow_lds(encode_gemm_kernel<BF16>, lds) != PALU_OK) return PALU_ERR_HIP;
-      hipLaunchKernelGGL(encode_gemm_kernel<BF16>, g, dim3(256), lds, s, a);
+      if (allow_lds(encode_gemm_kernel<BF16, false>, lds) != PALU_OK) return PALU_ERR_HIP;
+      hipLaunchKernelGGL((encode_gemm_kernel<BF16, false>), g, dim3(256), lds, s, a);
     }
     return launch_ok();
   }
@@ -593,6 +593,44 @@ int palu_encode_kv(const palu_layer_desc* desc, const void* x, int32_t n_tok, co
                    const int32_t* dst_row, void* workspace, size_t workspace_bytes, void* stream) {
   return encode_impl(desc, true, true, x, n_tok, Ak, Av, hk, hk_row_stride_elems, hv, hv_row_stride_elems,
                      dst_row, workspace, workspace_bytes, stream);
+}
+
+int palu_encode_quant(const palu_layer_desc* desc, int which, const void* x, int32_t n_tok, const void* A,
+                      uint8_t* codes, void* scale, void* zero, const int32_t* dst_row, void* stream) {
+  Meta m;
+  const int st = check_desc(desc, &m);
+  if (st != PALU_OK) return st;
+  if (!x || !A || !codes || !scale || !zero || n_tok <= 0 || (which != 0 && which != 1)) return PALU_ERR_INVALID_ARG;
+  if (desc->quant_block <= 0) return PALU_ERR_INVALID_ARG;
+  if (desc->quant_block != 128) return PALU_ERR_UNSUPPORTED;
+  const int R = which ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
+  if (R % 128 != 0) return PALU_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(A) & 15) ||
+      (reinterpret_cast<uintptr_t>(codes) & 15) || (reinterpret_cast<uintptr_t>(scale) & 1) ||
+      (reinterpret_cast<uintptr_t>(zero) & 1))
+    return PALU_ERR_INVALID_ARG;
+  EncodeArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.x = static_cast<const uint16_t*>(x);
+  a.dst_row = dst_row;
+  a.n_tok = n_tok;
+  a.d = m.n_heads * PALU_D_HEAD;
+  a.side[0].A = static_cast<const uint16_t*>(A);
+  a.side[0].R = R;
+  a.side[0].codes = codes;
+  a.side[0].scale = static_cast<uint16_t*>(scale);
+  a.side[0].zero = static_cast<uint16_t*>(zero);
+  const size_t lds = (size_t)2 * kGemmTile * kGemmPitch * 2;
+  const dim3 g((unsigned)(R / kGemmTile), (unsigned)ceil_div(n_tok, kGemmTile), 1u);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (desc->act_dtype == PALU_F16) {
+    if (allow_lds(encode_gemm_kernel<F16, true>, lds) != PALU_OK) return PALU_ERR_HIP;
+    hipLaunchKernelGGL((encode_gemm_kernel<F16, true>), g, dim3(256), lds, s, a);
+  } else {
+    if (allow_lds(encode_gemm_kernel<BF16, true>, lds) != PALU_OK) return PALU_ERR_HIP;
+    hipLaunchKernelGGL((encode_gemm_kernel<BF16, true>), g, dim3(256), lds, s, a);
+  }
+  return launch_ok();
 }
 
 // ------------------------------------------------------------------ quantize

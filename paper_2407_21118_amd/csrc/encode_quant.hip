@@ -20,6 +20,9 @@ struct EncodeSide {
   uint16_t* latent;
   long long row_stride;
   int R;
+  uint8_t* codes;          // fused quantization (GEMM path only): packed codes, rows of R/2 bytes ...
+  uint16_t* scale;         // ... and the fp16 (scale, zero) pairs, rows of R/128
+  uint16_t* zero;
 };
 struct EncodeArgs {
   const uint16_t* x;       // [n_tok, d]
@@ -134,6 +137,30 @@ __global__ __launch_bounds__(256) void encode_finish_kernel(EncodeArgs a) {
   }
 }
 
+// The quantizer of Appendix A with B = 4 (s = (max-min)/(2^B-1), z = round(-min/s),
+// code = clamp(round(x/s) + z, 0, 2^B-1)) for one (token, 128-channel block).
+// Every arithmetic step is a single IEEE float32 operation so the integer codes are
+// reproducible bit for bit; scale and zero are stored as fp16 and used as stored.
+struct QuantParams {
+  float sf, zf;
+  uint16_t s16, z16;
+};
+__device__ __forceinline__ QuantParams quant_params(float mn, float mx) {
+  QuantParams p;
+  const float s32 = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
+  p.s16 = F16::from_float(s32);
+  if ((p.s16 & 0x7fffu) == 0) p.s16 = 0x3c00u;                  // s == 0 -> 1
+  p.sf = F16::to_float(p.s16);
+  float z = rintf(__fdiv_rn(-mn, p.sf));
+  z = fminf(fmaxf(z, -65504.0f), 65504.0f);
+  p.z16 = F16::from_float(z);
+  p.zf = F16::to_float(p.z16);
+  return p;
+}
+__device__ __forceinline__ uint32_t quant_code(float x, const QuantParams& p) {
+  return (uint32_t)fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x, p.sf)), p.zf), 0.0f), 15.0f);
+}
+
 // ---- many tokens at once (filling the cache from a prompt): a tiled GEMM on the matrix
 // cores, C[n_tok, R] = X[n_tok, d] A[d, R].  Workgroup = 128 x 128 outputs, four
 // wavefronts of 64 x 64 (2 x 2 tiles of v_mfma_f32_32x32x16), k in stages of 128
@@ -144,8 +171,12 @@ __global__ __launch_bounds__(256) void encode_finish_kernel(EncodeArgs a) {
 constexpr int kGemmTile = 128;    // outputs per workgroup in each dimension, and k per stage
 constexpr int kGemmPitch = kGemmTile + 8;    // halfs per LDS row: 16-byte reads of 16 consecutive rows hit distinct banks
 
+// QUANT: the tile's 128 columns are exactly one quantization block per token, so the
+// workgroup quantizes its rounded outputs in place of storing them (Sec. 3.4 applied
+// while the cache is filled): codes, scales and zero-points are the ones quant_kernel
+// gives for the latents the plain kernel stores.
 // grid (ceil(max R / 128), ceil(n_tok / 128), sides), 256 threads, 2 * 128 * kGemmPitch * 2 bytes of LDS.
-template <typename T>
+template <typename T, bool QUANT>
 __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gemm_lds[];
   uint16_t* Xs = reinterpret_cast<uint16_t*>(gemm_lds);                 // [128 tokens][kGemmPitch]
@@ -228,6 +259,59 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a) {
   }
 
   // accumulator element e of tile (i, j): token m0 + wm + 32 i + mfma_row(e), column n0 + wn + 32 j + lane_lo
+  if constexpr (QUANT) {
+    __syncthreads();                          // the last stage has been read: Xs becomes the rounded output tile
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          Xs[(wm + 32 * i + mfma_row(e, lane_hi)) * kGemmPitch + wn + 32 * j + lane_lo] = T::from_float(acc[i][j][e]);
+    __syncthreads();
+    // two threads per token, 64 channels each
+    const int tr = tid >> 1, hf = tid & 1;
+    uint4v v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint4v*>(Xs + tr * kGemmPitch + hf * 64 + i * 8);
+    float mn = T::to_float((uint16_t)(v[0][0] & 0xffffu)), mx = mn;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float x0 = T::to_float((uint16_t)(v[i][w] & 0xffffu)), x1 = T::to_float((uint16_t)(v[i][w] >> 16));
+        mn = fminf(mn, fminf(x0, x1));
+        mx = fmaxf(mx, fmaxf(x0, x1));
+      }
+    mn = fminf(mn, __shfl_xor(mn, 1, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+    const int t = m0 + tr;
+    if (t >= a.n_tok) return;
+    const QuantParams qp = quant_params(mn, mx);
+    const size_t orow = a.dst_row ? (size_t)a.dst_row[t] : (size_t)t;
+    const int blk = blockIdx.x, n_blocks = sd.R / 128;
+    uint4v* dst = reinterpret_cast<uint4v*>(sd.codes + orow * (size_t)(sd.R / 2) + blk * 64 + hf * 32);
+#pragma unroll
+    for (int o = 0; o < 2; ++o) {
+      uint4v pk;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {           // output word w of this store: channels 8 (4 o + w) .. + 7 of the thread's 64
+        uint32_t word = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const uint32_t pr = v[4 * o + w][c];
+          word |= (quant_code(T::to_float((uint16_t)(pr & 0xffffu)), qp) | (quant_code(T::to_float((uint16_t)(pr >> 16)), qp) << 4)) << (8 * c);
+        }
+        pk[w] = word;
+      }
+      dst[o] = pk;
+    }
+    if (hf == 0) {
+      sd.scale[orow * n_blocks + blk] = qp.s16;
+      sd.zero[orow * n_blocks + blk] = qp.z16;
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -255,9 +339,6 @@ struct QuantArgs {
 };
 
 // One wavefront per (token, 128-channel block); lane l owns channels 2l, 2l+1.
-// Every arithmetic step is a single IEEE float32 operation so the integer
-// codes are reproducible bit for bit (Appendix A: s = (max-min)/(2^B-1),
-// z = round(-min/s), code = clamp(round(x/s) + z, 0, 2^B-1), B = 4).
 template <typename T>
 __global__ __launch_bounds__(256) void quant_kernel(QuantArgs a) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -273,21 +354,12 @@ __global__ __launch_bounds__(256) void quant_kernel(QuantArgs a) {
     mn = fminf(mn, __shfl_xor(mn, off, 64));
     mx = fmaxf(mx, __shfl_xor(mx, off, 64));
   }
-  const float s32 = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
-  uint16_t s16 = F16::from_float(s32);
-  if ((s16 & 0x7fffu) == 0) s16 = 0x3c00u;                    // s == 0 -> 1
-  const float sf = F16::to_float(s16);
-  float z = rintf(__fdiv_rn(-mn, sf));
-  z = fminf(fmaxf(z, -65504.0f), 65504.0f);
-  const uint16_t z16 = F16::from_float(z);
-  const float zf = F16::to_float(z16);
-  const float q0 = fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x0, sf)), zf), 0.0f), 15.0f);
-  const float q1 = fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x1, sf)), zf), 0.0f), 15.0f);
+  const QuantParams qp = quant_params(mn, mx);
   const size_t orow = a.dst_row ? (size_t)a.dst_row[t] : (size_t)t;
-  a.codes[orow * (a.R / 2) + blk * 64 + lane] = (uint8_t)((uint32_t)q0 | ((uint32_t)q1 << 4));
+  a.codes[orow * (a.R / 2) + blk * 64 + lane] = (uint8_t)(quant_code(x0, qp) | (quant_code(x1, qp) << 4));
   if (lane == 0) {
-    a.scale[orow * a.n_blocks + blk] = s16;
-    a.zero[orow * a.n_blocks + blk] = z16;
+    a.scale[orow * a.n_blocks + blk] = qp.s16;
+    a.zero[orow * a.n_blocks + blk] = qp.z16;
   }
 }
 
@@ -298,8 +370,10 @@ __global__ __launch_bounds__(256) void quant_kernel(QuantArgs a) {
   template __global__ void encode_partial_kernel<T, 8>(EncodeArgs);
 PALU_ENC_INST(F16)
 PALU_ENC_INST(BF16)
-template __global__ void encode_gemm_kernel<F16>(EncodeArgs);
-template __global__ void encode_gemm_kernel<BF16>(EncodeArgs);
+template __global__ void encode_gemm_kernel<F16, false>(EncodeArgs);
+template __global__ void encode_gemm_kernel<BF16, false>(EncodeArgs);
+template __global__ void encode_gemm_kernel<F16, true>(EncodeArgs);
+template __global__ void encode_gemm_kernel<BF16, true>(EncodeArgs);
 template __global__ void encode_finish_kernel<F16>(EncodeArgs);
 template __global__ void encode_finish_kernel<BF16>(EncodeArgs);
 template __global__ void quant_kernel<F16>(QuantArgs);

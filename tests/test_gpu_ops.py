@@ -276,3 +276,52 @@ def test_encode_many_tokens_gemm_path(dtype, n_tok):
         assert err.max() <= eps * 1.05 + 1e-6
         untouched = np.setdiff1d(np.arange(rows), perm)
         assert (got[untouched] == 7.0).all() and (got[:, R:] == 7.0).all()
+
+
+@pytest.mark.parametrize("dtype,n_tok", [("f16", 1), ("f16", 64), ("f16", 300), ("bf16", 129)])
+def test_encode_quant_fused(dtype, n_tok):
+    """Down-projection with the quantizer fused into the GEMM's write-out.  Two checks:
+    the dequantized cache is within half a quantization step (plus the rounding of the
+    latent) of the oracle's float64 product; and, where palu_encode runs the same GEMM
+    (n_tok >= 64), codes, scales and zero-points are bit for bit what the oracle's
+    quantizer gives for the latents that call stores."""
+    say(f"[encode-quant] dtype={dtype} n_tok={n_tok}")
+    layer = synth.config_layer("4")
+    rng = np.random.default_rng(12)
+    d = layer.n_heads * layer.d_head
+    R = layer.R_v
+    A = synth.round_to(rng.standard_normal((d, R)) / 45.0 * rng.uniform(0.05, 3.0, size=(1, R)), dtype)
+    x = synth.round_to(rng.standard_normal((n_tok, d)) * rng.uniform(0.1, 8.0, size=(n_tok, 1)), dtype)
+    desc = make_desc(layer, dtype)
+    td = torch.float16 if dtype == "f16" else torch.bfloat16
+    rows = n_tok + 9
+    perm = rng.permutation(rows)[:n_tok].astype(np.int32)
+    dst = torch.from_numpy(perm).cuda()
+    codes = torch.full((rows, R // 2), 0xA5, dtype=torch.uint8, device="cuda")
+    scale = torch.full((rows, R // 128), 3.0, dtype=torch.float16, device="cuda")
+    zero = torch.full((rows, R // 128), 3.0, dtype=torch.float16, device="cuda")
+    P.palu_encode_quant(desc, 1, to_dev(x, dtype), n_tok, to_dev(A, dtype), codes, scale, zero, dst)
+    torch.cuda.synchronize()
+    c = codes.cpu().numpy()
+    s = scale.float().cpu().numpy().astype(np.float64)
+    z = zero.float().cpu().numpy().astype(np.float64)
+    untouched = np.setdiff1d(np.arange(rows), perm)
+    assert (c[untouched] == 0xA5).all() and (s[untouched] == 3.0).all() and (z[untouched] == 3.0).all()
+    ref = O.encode(x, A)
+    unpacked = np.empty((rows, R), dtype=np.float64)
+    unpacked[:, 0::2] = c & 15
+    unpacked[:, 1::2] = c >> 4
+    deq = (unpacked.reshape(rows, R // 128, 128) - z[:, :, None]) * s[:, :, None]
+    err = np.abs(deq[perm] - ref.reshape(n_tok, R // 128, 128))
+    eps = 2.0 ** -11 if dtype == "f16" else 2.0 ** -8
+    bound = s[perm][:, :, None] * 0.51 + eps * 1.05 * np.abs(ref).max(axis=1)[:, None, None] + 1e-6
+    say(f"       worst error / bound {float((err / bound).max()):.3f}")
+    assert (err <= bound).all()
+    if n_tok >= 64:
+        lat = torch.zeros((rows, R), dtype=td, device="cuda")
+        P.palu_encode(desc, 1, to_dev(x, dtype), to_dev(A, dtype), lat, R, dst)
+        torch.cuda.synchronize()
+        pk, so, zo = O.quant_latent(lat.float().cpu().numpy()[perm])
+        np.testing.assert_array_equal(c[perm], pk)
+        np.testing.assert_array_equal(scale.cpu().view(torch.int16).numpy()[perm], so.view(np.int16))
+        np.testing.assert_array_equal(zero.cpu().view(torch.int16).numpy()[perm], zo.view(np.int16))
