@@ -191,25 +191,30 @@ def softmax_rows(s: np.ndarray) -> np.ndarray:
 
 
 def attn_decode_scores(q, q_pos, Hk, Bk, group_head_off, k_rank_off, d_head,
-                       rope_theta, k_pos=None, seq_lens=None):
+                       rope_theta, k_pos=None, seq_lens=None, q_per_kv: int = 1):
     """Pre-softmax scores q'_i . K'_{i,t} / sqrt(d_h) as a list over batch of
     [n_heads, L_b] float64 arrays (Eq. 2 numerator with RoPE on q and K,
-    Sec. 3.1.2)."""
+    Sec. 3.1.2).  With grouped-query attention (the Llama-3 / Mistral models of
+    Sec. 4.1) the decomposition covers the key/value heads only and query head
+    i reads key/value head i // q_per_kv: the rebuilt heads are repeated."""
     q = np.asarray(q, dtype=np.float64)
     Bsz, n_heads, _ = q.shape
+    n_kv = int(group_head_off[-1])
+    assert n_heads == n_kv * q_per_kv
     out = []
     for b in range(Bsz):
         L = int(seq_lens[b]) if seq_lens is not None else Hk.shape[1]
         pos = np.arange(L) if k_pos is None else np.asarray(k_pos)[:L]
         K = reconstruct(np.asarray(Hk[b, :L], dtype=np.float64), Bk, group_head_off, k_rank_off, d_head)
-        K = rope_rotate(K.reshape(L, n_heads, d_head), pos[:, None], rope_theta)      # [L, n, d_h]
+        K = np.repeat(K.reshape(L, n_kv, d_head), q_per_kv, axis=1)                   # [L, n, d_h]
+        K = rope_rotate(K, pos[:, None], rope_theta)
         qr = rope_rotate(q[b], np.full((n_heads,), int(np.asarray(q_pos)[b])), rope_theta)  # [n, d_h]
         out.append(np.einsum("lnd,nd->nl", K, qr) / np.sqrt(np.float64(d_head)))
     return out
 
 
 def attn_decode(q, q_pos, Hk, Hv, Bk, Bv, group_head_off, k_rank_off, v_rank_off,
-                d_head: int, rope_theta: float, k_pos=None, seq_lens=None) -> np.ndarray:
+                d_head: int, rope_theta: float, k_pos=None, seq_lens=None, q_per_kv: int = 1) -> np.ndarray:
     """One decode step of attention over the latent cache, by the definition.
 
     q   [B, n_heads, d_head]  pre-RoPE query (Sec. 4.5.2 times the kernel from
@@ -225,35 +230,39 @@ def attn_decode(q, q_pos, Hk, Hv, Bk, Bv, group_head_off, k_rank_off, v_rank_off
     (Sec. 3.2.3), RoPE on K rows and on q (Sec. 3.1.2), p = softmax(q K^T /
     sqrt(d_h)), a = p V (Eq. 2).  Returns [B, n_heads, d_head] float64.
     No causal mask: every cached row up to seq_lens[b] is attended.
+    q_per_kv > 1 is grouped-query attention: group_head_off counts key/value
+    heads, q has q_per_kv times as many, and query head i uses key/value head
+    i // q_per_kv.
     """
     q = np.asarray(q, dtype=np.float64)
     Bsz, n_heads, _ = q.shape
     scores = attn_decode_scores(q, q_pos, Hk, Bk, group_head_off, k_rank_off, d_head,
-                                rope_theta, k_pos, seq_lens)
+                                rope_theta, k_pos, seq_lens, q_per_kv)
     out = np.empty((Bsz, n_heads, d_head), dtype=np.float64)
     for b in range(Bsz):
         L = scores[b].shape[1]
         V = reconstruct(np.asarray(Hv[b, :L], dtype=np.float64), Bv, group_head_off, v_rank_off, d_head)
-        V = V.reshape(L, n_heads, d_head)
+        V = np.repeat(V.reshape(L, n_heads // q_per_kv, d_head), q_per_kv, axis=1)
         p = softmax_rows(scores[b])                       # [n, L]
         out[b] = np.einsum("nl,lnd->nd", p, V)
     return out
 
 
 def attn_decode_latent(q, q_pos, Hk, Hv, Bk, group_head_off, k_rank_off, v_rank_off,
-                       d_head: int, rope_theta: float, k_pos=None, seq_lens=None) -> np.ndarray:
+                       d_head: int, rope_theta: float, k_pos=None, seq_lens=None, q_per_kv: int = 1) -> np.ndarray:
     """Attention output left in the value latent space (Sec. 3.1.1, Eq. 4 before
     the multiplication by B_v, which the paper absorbs into the output
     projection W_o offline): for head i of group j, a^lat_i = p_i H_v[:, columns of j],
     with p_i the same softmax as attn_decode.  Returns [B, sum_i r_v(group(i))]
-    float64, heads in order, head i occupying r_v(group(i)) entries."""
+    float64, heads in order, head i occupying r_v(group(i)) entries.  With
+    q_per_kv > 1 the heads are the query heads, q_per_kv per key/value head."""
     q = np.asarray(q, dtype=np.float64)
     Bsz, n_heads, _ = q.shape
     scores = attn_decode_scores(q, q_pos, Hk, Bk, group_head_off, k_rank_off, d_head,
-                                rope_theta, k_pos, seq_lens)
+                                rope_theta, k_pos, seq_lens, q_per_kv)
     widths = []
     for j in range(len(group_head_off) - 1):
-        widths += [v_rank_off[j + 1] - v_rank_off[j]] * (group_head_off[j + 1] - group_head_off[j])
+        widths += [v_rank_off[j + 1] - v_rank_off[j]] * ((group_head_off[j + 1] - group_head_off[j]) * q_per_kv)
     out = np.empty((Bsz, int(sum(widths))), dtype=np.float64)
     for b in range(Bsz):
         L = scores[b].shape[1]
@@ -262,7 +271,7 @@ def attn_decode_latent(q, q_pos, Hk, Hv, Bk, group_head_off, k_rank_off, v_rank_
         at = 0
         for j in range(len(group_head_off) - 1):
             Hj = H[:, v_rank_off[j]:v_rank_off[j + 1]]    # [L, r_j]
-            for i in range(group_head_off[j], group_head_off[j + 1]):
+            for i in range(group_head_off[j] * q_per_kv, group_head_off[j + 1] * q_per_kv):
                 out[b, at:at + Hj.shape[1]] = p[i] @ Hj
                 at += Hj.shape[1]
     return out

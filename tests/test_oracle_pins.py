@@ -232,6 +232,33 @@ def test_latent_output_times_b_v_is_the_attention_output():
         at += r
 
 
+@pytest.mark.parametrize("qpk", [2, 4])
+def test_grouped_query_reduces_to_one_query_per_kv_head(qpk):
+    """Grouped-query attention (q_per_kv query heads share a key/value head): taking
+    every q_per_kv-th query head, starting at w, leaves one query per key/value head,
+    which is the multi-head case pinned above; heads i = kv * q_per_kv + w must agree.
+    A head map of i % n_kv instead of i // q_per_kv fails this."""
+    p = small_problem(seed=9)
+    rng = np.random.default_rng(90)
+    q = rng.standard_normal((p["B"], p["n"] * qpk, p["d"]))
+    got = O.attn_decode(q, p["q_pos"], p["Hk"], p["Hv"], p["Bk_flat"], p["Bv_flat"], p["gho"], p["kro"], p["vro"],
+                        p["d"], 10000.0, p["k_pos"], None, qpk)
+    lat = O.attn_decode_latent(q, p["q_pos"], p["Hk"], p["Hv"], p["Bk_flat"], p["gho"], p["kro"], p["vro"],
+                               p["d"], 10000.0, p["k_pos"], None, qpk)
+    assert got.shape == (p["B"], p["n"] * qpk, p["d"])
+    for w in range(qpk):
+        want = run_oracle(p, q=q[:, w::qpk])
+        np.testing.assert_allclose(got[:, w::qpk], want, rtol=1e-11, atol=1e-13)
+    at = 0
+    for i in range(p["n"] * qpk):
+        j, u = divmod(i // qpk, p["s"])
+        r = p["vro"][j + 1] - p["vro"][j]
+        np.testing.assert_allclose(lat[:, at:at + r] @ p["Bv"][j][:, u * p["d"]:(u + 1) * p["d"]], got[:, i],
+                                   rtol=1e-10, atol=1e-12)
+        at += r
+    assert at == lat.shape[1]
+
+
 def test_zero_positions_equal_fused_qk_form():
     """With every position 0 RoPE is the identity and the score must equal
     (q B_k^T) H_k^T / sqrt(d_h) (Eq. 5)."""
