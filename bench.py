@@ -46,7 +46,7 @@ def algorithmic_work(layer, batch, seq, k_i4, v_i4):
     for j in range(layer.n_groups):
         s = layer.group_size(j)
         recon += 2 * T * (layer.k_rank_off[j + 1] - layer.k_rank_off[j]) * s * d_h
-        pv += 2 * T * (layer.v_rank_off[j + 1] - layer.v_rank_off[j]) * s
+        pv += 2 * T * (layer.v_rank_off[j + 1] - layer.v_rank_off[j]) * s * layer.q_per_kv
 
     def side_bytes(R, i4):
         return T * (R // 2 + (R // layer.quant_block) * 4) if i4 else T * R * 2
@@ -57,7 +57,7 @@ def algorithmic_work(layer, batch, seq, k_i4, v_i4):
         "k_latent_bytes": side_bytes(layer.R_k, k_i4),
         "v_latent_bytes": side_bytes(layer.R_v, v_i4),
         "b_bytes": 2 * (layer.b_elems("k") + layer.b_elems("v")),
-        "a_bytes": 2 * layer.n_heads * d_h * (layer.R_k + layer.R_v),
+        "a_bytes": 2 * layer.n_q_heads * d_h * (layer.R_k + layer.R_v),
     }
 
 
@@ -67,7 +67,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="2", help="workload: 1, 2 (7B shape, seq 16K, headline), 2-4k, 2-64k, 3, 4, 4v, 5a, 5b, "
-                         "2p / 2p-64k (the paper's latency allocation: K rank 128, V rank 384 per group)")
+                         "2p / 2p-64k (the paper's latency allocation: K rank 128, V rank 384 per group), "
+                         "gqa / gqa-64k (32 query heads on 8 key/value heads, the Llama-3-8B / Mistral-7B shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ring-gib", type=float, default=1.0, help="distinct latent bytes to cycle through")
     ap.add_argument("--opt", action="append", default=[], help="tuning knob name=value (palu_set_option)")
@@ -122,11 +123,12 @@ def main() -> int:
 
     act = P.PALU_F16
     desc = P.LayerDesc(layer.n_heads, layer.d_head, layer.group_head_off, layer.k_rank_off, layer.v_rank_off, act,
-                       P.PALU_I4 if k_i4 else act, P.PALU_I4 if v_i4 else act, layer.quant_block, layer.rope_theta)
+                       P.PALU_I4 if k_i4 else act, P.PALU_I4 if v_i4 else act, layer.quant_block, layer.rope_theta,
+                       layer.q_per_kv)
     table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, seq)
     ws = torch.empty(P.palu_attn_decode_workspace_bytes(desc, batch, seq), dtype=torch.uint8, device="cuda")
     ws_e = torch.empty(P.palu_encode_workspace_bytes(desc, 2, batch), dtype=torch.uint8, device="cuda")
-    out = torch.empty((batch, layer.n_heads, layer.d_head), dtype=torch.float32, device="cuda")
+    out = torch.empty((batch, layer.n_q_heads, layer.d_head), dtype=torch.float32, device="cuda")
     dst_row = (torch.arange(batch, dtype=torch.int32, device="cuda") * seq + (seq - 1)).contiguous()
     nbk, nbv = layer.R_k // layer.quant_block, layer.R_v // layer.quant_block
 
@@ -236,7 +238,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"config {cfg}{' without RoPE' if args.no_rope else ''}: Llama-2-7B-shaped layer decode, batch {batch}, seq {seq}, "
                                f"{layer.n_groups} groups, R_k {layer.R_k}, R_v {layer.R_v}",
-                   "batch": batch, "seq_len": seq, "n_heads": layer.n_heads, "group_size": layer.group_size(0),
+                   "batch": batch, "seq_len": seq, "n_heads": layer.n_heads, "q_per_kv": layer.q_per_kv, "group_size": layer.group_size(0),
                    "cache_sets": n_sets, "step": "encode K + encode V (+ quantize) + attn_decode"},
         "roofline": {
             "kernel": "score_kernel (key reconstruction + RoPE + q.K on MFMA)",
@@ -343,7 +345,7 @@ def main() -> int:
         reps, t_c = 0, time.perf_counter()
         while reps < 20 and (reps == 0 or time.perf_counter() - t_c < 10.0):     # about 10 s of CPU work
             O.attn_decode(qn, np.full((nb,), lim - 1), Hk, Hv, Bk, Bv, layer.group_head_off, layer.k_rank_off,
-                          layer.v_rank_off, layer.d_head, layer.rope_theta)
+                          layer.v_rank_off, layer.d_head, layer.rope_theta, None, None, layer.q_per_kv)
             reps += 1
         cpu_s = (time.perf_counter() - t_c) / reps
         scale = (batch / nb) * (seq / lim)

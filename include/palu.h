@@ -60,6 +60,14 @@ enum {
  *   Head u of group j (u counted inside the group) owns columns
  *   [u d_h, (u+1) d_h) of B_gj.
  * The three offset arrays are HOST arrays of n_groups+1 int32, starting at 0.
+ *
+ * Grouped-query attention (the Llama-3 and Mistral models of Sec. 4.1): the
+ * decomposition covers the key and value projections, so n_heads,
+ * group_head_off and the B matrices count KEY/VALUE heads; there are
+ * n_heads*q_per_kv query heads, query head i attends key/value head
+ * i / q_per_kv, and wherever an argument below is shaped by heads (q, out, the
+ * latent output, the width n_heads*d_head of x) the heads are the query heads.
+ * n_heads*q_per_kv <= PALU_MAX_HEADS.
  */
 typedef struct palu_layer_desc {
   int32_t n_heads;
@@ -73,6 +81,7 @@ typedef struct palu_layer_desc {
   int32_t v_latent_dtype;          /* act_dtype or PALU_I4 */
   int32_t quant_block;             /* channels per (scale, zero) pair; 128 */
   float rope_theta;                /* RoPE base, e.g. 10000; <= 0: no rotation */
+  int32_t q_per_kv;                /* grouped-query attention: query heads per key/value head; 0 or 1 = multi-head */
 } palu_layer_desc;
 
 /* Human-readable text for a status code (static storage, never NULL). */

@@ -37,7 +37,7 @@ class _Desc(ctypes.Structure):
         ("k_rank_off", ctypes.POINTER(ctypes.c_int32)),
         ("v_rank_off", ctypes.POINTER(ctypes.c_int32)),
         ("act_dtype", ctypes.c_int32), ("k_latent_dtype", ctypes.c_int32), ("v_latent_dtype", ctypes.c_int32),
-        ("quant_block", ctypes.c_int32), ("rope_theta", ctypes.c_float),
+        ("quant_block", ctypes.c_int32), ("rope_theta", ctypes.c_float), ("q_per_kv", ctypes.c_int32),
     ]
 
 
@@ -100,7 +100,8 @@ class LayerDesc:
 
     def __init__(self, n_heads: int, d_head: int, group_head_off: Sequence[int], k_rank_off: Sequence[int],
                  v_rank_off: Sequence[int], act_dtype: int = PALU_F16, k_latent_dtype: Optional[int] = None,
-                 v_latent_dtype: Optional[int] = None, quant_block: int = 128, rope_theta: float = 10000.0):
+                 v_latent_dtype: Optional[int] = None, quant_block: int = 128, rope_theta: float = 10000.0,
+                 q_per_kv: int = 1):
         n_groups = len(group_head_off) - 1
         arr = ctypes.c_int32 * (n_groups + 1)
         self._gho = arr(*[int(v) for v in group_head_off])
@@ -115,8 +116,10 @@ class LayerDesc:
         self.v_latent_dtype = act_dtype if v_latent_dtype is None else v_latent_dtype
         self.quant_block = quant_block
         self.rope_theta = float(rope_theta)
+        self.q_per_kv = int(q_per_kv)
+        self.n_q_heads = self.n_heads * max(self.q_per_kv, 1)
         self.c = _Desc(self.n_heads, self.d_head, n_groups, self._gho, self._kro, self._vro, act_dtype,
-                       self.k_latent_dtype, self.v_latent_dtype, quant_block, self.rope_theta)
+                       self.k_latent_dtype, self.v_latent_dtype, quant_block, self.rope_theta, self.q_per_kv)
 
     @property
     def R_k(self) -> int:
@@ -248,7 +251,7 @@ def palu_attn_decode(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, q,
     already recorded once (so that their HIP handles exist); routes through palu_attn_decode_staged."""
     import torch
     if out is None:
-        out = torch.empty((batch, desc.n_heads, desc.d_head), dtype=torch.float32, device=q.device)
+        out = torch.empty((batch, desc.n_q_heads, desc.d_head), dtype=torch.float32, device=q.device)
     if workspace is None:
         workspace = torch.empty(palu_attn_decode_workspace_bytes(desc, batch, max_seq), dtype=torch.uint8,
                                 device=q.device)
@@ -275,7 +278,7 @@ def palu_attn_decode_latent(desc: LayerDesc, batch: int, seq_len: int, max_seq: 
     import torch
     if out_latent is None:
         width = sum((desc.v_rank_off[j + 1] - desc.v_rank_off[j]) * (desc.group_head_off[j + 1] - desc.group_head_off[j])
-                    for j in range(desc.n_groups))
+                    for j in range(desc.n_groups)) * max(desc.q_per_kv, 1)
         out_latent = torch.empty((batch, width), dtype=torch.float32, device=q.device)
     if workspace is None:
         workspace = torch.empty(palu_attn_decode_workspace_bytes(desc, batch, max_seq), dtype=torch.uint8,

@@ -55,6 +55,8 @@ int check_desc(const palu_layer_desc* d, Meta* m) {
     }
   }
   if (d->group_head_off[d->n_groups] != d->n_heads) return PALU_ERR_INVALID_ARG;
+  if (d->q_per_kv < 0) return PALU_ERR_INVALID_ARG;
+  const int qpk = d->q_per_kv > 0 ? d->q_per_kv : 1;
   const bool any_i4 = d->k_latent_dtype == PALU_I4 || d->v_latent_dtype == PALU_I4;
   if (any_i4) {
     if (d->quant_block <= 0) return PALU_ERR_INVALID_ARG;
@@ -67,7 +69,7 @@ int check_desc(const palu_layer_desc* d, Meta* m) {
   }
   // limits of this build
   if (d->d_head != PALU_D_HEAD) return PALU_ERR_UNSUPPORTED;
-  if (d->n_heads > PALU_MAX_HEADS || d->n_groups > PALU_MAX_GROUPS) return PALU_ERR_UNSUPPORTED;
+  if (d->n_heads > PALU_MAX_HEADS / qpk || d->n_groups > PALU_MAX_GROUPS) return PALU_ERR_UNSUPPORTED;
   if (any_i4 && (d->quant_block != 128 || d->act_dtype != PALU_F16)) return PALU_ERR_UNSUPPORTED;
   for (int j = 0; j < d->n_groups; ++j) {
     if (d->k_rank_off[j + 1] - d->k_rank_off[j] > PALU_MAX_RANK) return PALU_ERR_UNSUPPORTED;
@@ -75,20 +77,22 @@ int check_desc(const palu_layer_desc* d, Meta* m) {
   }
   if (m) {
     std::memset(m, 0, sizeof(*m));
-    m->n_heads = d->n_heads;
+    // from here on a head is a query head: qpk of them per key/value head of the descriptor
+    m->n_heads = d->n_heads * qpk;
     m->n_groups = d->n_groups;
+    m->qpk = qpk;
     int bk = 0, bv = 0;
     for (int j = 0; j <= d->n_groups; ++j) {
-      m->head_off[j] = d->group_head_off[j];
+      m->head_off[j] = d->group_head_off[j] * qpk;
       m->k_off[j] = d->k_rank_off[j];
       m->v_off[j] = d->v_rank_off[j];
       m->bk_off[j] = bk;
       m->bv_off[j] = bv;
       if (j < d->n_groups) {
-        const int s = d->group_head_off[j + 1] - d->group_head_off[j];
+        const int s = (d->group_head_off[j + 1] - d->group_head_off[j]) * qpk;
         bk += (d->k_rank_off[j + 1] - d->k_rank_off[j]) * s * PALU_D_HEAD;
         bv += (d->v_rank_off[j + 1] - d->v_rank_off[j]) * s * PALU_D_HEAD;
-        for (int h = d->group_head_off[j]; h < d->group_head_off[j + 1]; ++h) m->group_of_head[h] = (uint8_t)j;
+        for (int h = d->group_head_off[j] * qpk; h < d->group_head_off[j + 1] * qpk; ++h) m->group_of_head[h] = (uint8_t)j;
       }
     }
   }
@@ -121,7 +125,8 @@ struct ScorePlan {
   int max_slices;
 };
 
-int plan_score(const Meta& m, ScorePlan* p) {
+// widen: let a unit of small groups span 2 or 4 adjacent groups of equal rank and size
+int plan_score(const Meta& m, ScorePlan* p, bool widen = true) {
   p->n_cls = 0;
   p->total_units = 0;
   p->max_slices = 1;
@@ -176,7 +181,7 @@ int plan_score(const Meta& m, ScorePlan* p) {
       nh = std::min(2, m.head_off[j0 + 1] - h);
     } else {
       nh = std::min(4, m.head_off[j0 + 1] - h);
-      if (h == m.head_off[j0] && s <= 2) {
+      if (widen && h == m.head_off[j0] && s <= 2) {
         // a small group: widen the unit over 2 or 4 whole adjacent groups of the same rank and size
         for (int g : {4, 2}) {
           if (g * s > 4 || g * r > kScoreMaxWidth || j0 + g > m.n_groups) continue;
@@ -333,7 +338,7 @@ int split_bound(int total_units, int batch, int max_seq, int waves_per_cu) {
 }
 
 struct Workspace {
-  size_t mfold, scores, o_part, ml_part, rope_rows, qsum, total;
+  size_t mfold, scores, o_part, ml_part, rope_rows, qsum, qfrag, total;
   int lpad, o_stride;
   long long mfold_bstride, part_stride;
 };
@@ -350,6 +355,8 @@ int carve(const Meta& m, int batch, int max_seq, int n_split_cap, int n_parts, W
   w->ml_part = off; off = align_up(off + (size_t)batch * n_split_cap * m.n_heads * 2 * 4);
   w->rope_rows = off; off = align_up(off + (size_t)w->lpad * PALU_D_HEAD * 2);   // cos/sin rows gathered by k_pos
   w->qsum = off; off = align_up(off + (size_t)batch * m.n_heads * (PALU_MAX_RANK / 128 + 2) * 4);   // int4 block sums of the folded queries (no-RoPE path)
+  // grouped-query attention: rotated queries as contraction operands, 2 feature halves x 2 passes x 1 KiB per key/value head
+  w->qfrag = off; off = align_up(off + (m.qpk > 1 ? (size_t)batch * (m.n_heads / m.qpk) * 4 * 1024 : 0));
   w->total = off;
   return PALU_OK;
 }
@@ -403,6 +410,40 @@ ScoreFn score_fn(int act, bool i4, int cls_id, bool w8) {
   const int rc = cls_id / 3, lg = cls_id % 3;
   if (i4) return score_fn_t<F16, true>(rc, lg, w8);
   return act == PALU_F16 ? score_fn_t<F16, false>(rc, lg, w8) : score_fn_t<BF16, false>(rc, lg, w8);
+}
+
+// shared-key form (grouped-query attention): fp16 latents, ranks up to 256, 8 wavefronts, `passes` x 4 query heads
+template <int QP>
+ScoreFn score_fn_shared(int rc) {
+  switch (rc) {
+    case 0: return score_kernel<F16, 2, 2, 1, 8, false, QP>;
+    case 1: return score_kernel<F16, 4, 2, 1, 8, false, QP>;
+    case 2: return score_kernel<F16, 6, 2, 1, 8, false, QP>;
+    case 3: return score_kernel<F16, 8, 2, 1, 8, false, QP>;
+    case 4: return score_kernel<F16, 10, 2, 1, 8, false, QP>;
+    case 5: return score_kernel<F16, 12, 2, 1, 8, false, QP>;
+    case 6: return score_kernel<F16, 14, 2, 1, 8, false, QP>;
+    default: return score_kernel<F16, 16, 2, 1, 8, false, QP>;
+  }
+}
+
+// The same layer with one (virtual) query head per key/value head: the units of the shared-key score form.
+Meta kv_head_meta(const Meta& m) {
+  Meta k;
+  std::memset(&k, 0, sizeof(k));
+  k.n_heads = m.n_heads / m.qpk;
+  k.n_groups = m.n_groups;
+  k.qpk = 1;
+  for (int j = 0; j <= m.n_groups; ++j) {
+    k.head_off[j] = m.head_off[j] / m.qpk;
+    k.k_off[j] = m.k_off[j];
+    k.v_off[j] = m.v_off[j];
+    k.bk_off[j] = m.bk_off[j] / m.qpk;
+    k.bv_off[j] = m.bv_off[j] / m.qpk;
+    if (j < m.n_groups)
+      for (int h = k.head_off[j]; h < m.head_off[j + 1] / m.qpk; ++h) k.group_of_head[h] = (uint8_t)j;
+  }
+  return k;
 }
 
 using PvFn = void (*)(PvArgs);
@@ -818,7 +859,18 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
       if ((st = flush()) != PALU_OK) return st;
     }
   } else {
-    // 1. fold the rotated query into B_k
+    // Grouped-query attention with fp16 latents and ranks up to 256: the score kernel rebuilds each
+    // key once for the query heads that share it (shared-key form).  Other grouped-query layers
+    // run the folded form with one folded matrix per query head.
+    bool shared_key = m.qpk >= 2 && m.qpk <= 8 && act == PALU_F16 && !k_i4 && waves8;
+    for (int j = 0; j < m.n_groups && shared_key; ++j) shared_key = m.k_off[j + 1] - m.k_off[j] <= 256;
+    const Meta mk = shared_key ? kv_head_meta(m) : m;
+    static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)
+    if (shared_key && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
+    const ScorePlan& plan = shared_key ? spk : sp;
+    const int passes = ceil_div(m.qpk, 4);
+
+    // 1. fold the rotated query into B_k (shared-key form: B_k alone, and the rotated queries beside it)
     {
       FoldArgs a;
       a.q = static_cast<const uint16_t*>(q);
@@ -827,20 +879,35 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
       a.mfold = reinterpret_cast<uint16_t*>(ws + w.mfold);
       a.mfold_bstride = w.mfold_bstride;
       a.theta = desc->rope_theta;
+      a.plain = shared_key ? 1 : 0;
       for (int f = 0; f < kHalf; ++f) {
         const double rev = desc->rope_theta > 0.f
             ? std::pow((double)desc->rope_theta, -2.0 * f / (double)PALU_D_HEAD) / 6.283185307179586476925 : 0.0;
         a.rev_hi[f] = (float)rev;
         a.rev_lo[f] = (float)(rev - (double)a.rev_hi[f]);
       }
-      a.meta = m;
+      a.meta = mk;
       int max_r = 0;
       for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
-      const dim3 g((unsigned)(max_r / 16), (unsigned)m.n_heads, (unsigned)batch);
+      const dim3 g((unsigned)(max_r / 16), (unsigned)mk.n_heads, shared_key ? 1u : (unsigned)batch);
       if ((st = mark(0)) != PALU_OK) return st;
       if (act == PALU_F16) hipLaunchKernelGGL(fold_kernel<F16>, g, dim3(256), 0, s, a);
       else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
       if ((st = launch_ok()) != PALU_OK) return st;
+      if (shared_key) {
+        QfragArgs qa;
+        qa.q = a.q;
+        qa.q_pos = q_pos;
+        qa.qfrag = reinterpret_cast<uint16_t*>(ws + w.qfrag);
+        qa.theta = a.theta;
+        std::memcpy(qa.rev_hi, a.rev_hi, sizeof(qa.rev_hi));
+        std::memcpy(qa.rev_lo, a.rev_lo, sizeof(qa.rev_lo));
+        qa.n_kv = mk.n_heads;
+        qa.qpk = m.qpk;
+        qa.passes = passes;
+        hipLaunchKernelGGL(qfrag_kernel<F16>, dim3((unsigned)mk.n_heads, (unsigned)batch), dim3(256), 0, s, qa);
+        if ((st = launch_ok()) != PALU_OK) return st;
+      }
     }
 
     // 2. scores
@@ -853,7 +920,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
       a.rope_rows = static_cast<const uint16_t*>(rope_table);
       a.seq_lens = seq_lens;
       a.scores = reinterpret_cast<float*>(ws + w.scores);
-      a.mfold_bstride = w.mfold_bstride;
+      a.mfold_bstride = shared_key ? 0 : w.mfold_bstride;       // shared-key form: the weights do not depend on the sequence
       a.row_elems = Rk;
       a.max_seq = max_seq;
       a.seq_len = seq_len;
@@ -863,6 +930,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
       a.quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
       a.n_blocks_q = Rk / a.quant_block;
       a.scale = 1.4426950408889634f / std::sqrt((float)PALU_D_HEAD);
+      a.qfrag = reinterpret_cast<const uint16_t*>(ws + w.qfrag);
+      a.qpk = m.qpk;
+      a.n_kv = mk.n_heads;
       if ((st = mark(1)) != PALU_OK) return st;
       if (k_pos) {
         // cos/sin rows in cached-token order, so that the score kernel needs no position loads
@@ -889,13 +959,14 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
         a.chunk_tokens = chunk_tiles * kTile;
         a.n_chunks = ceil_div(tiles, chunk_tiles);
       };
-      for (int cls = 0; cls < sp.n_cls; ++cls) {
-        const int id = sp.cls_id[cls];
+      for (int cls = 0; cls < plan.n_cls; ++cls) {
+        const int id = plan.cls_id[cls];
         const int rc = id / 3, lg = id % 3;
         const int width = (32 * (rc + 1)) << lg;
         const bool dma = act == PALU_F16 && !k_i4;
-        const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width);
-        ScoreFn fn = score_fn(act, k_i4, id, waves8);
+        const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width) + (shared_key ? score_qf_bytes(passes) : 0);
+        ScoreFn fn = !shared_key ? score_fn(act, k_i4, id, waves8)
+                                 : (passes == 1 ? score_fn_shared<1>(rc) : score_fn_shared<2>(rc));
         if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
         const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
         auto flush = [&]() -> int {
@@ -907,9 +978,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
           return launch_ok();
         };
         a.units.n_units = 0;
-        for (int i = 0; i < sp.total_units; ++i) {
-          if (sp.unit_cls[i] != cls) continue;
-          a.units.u[a.units.n_units++] = sp.units[i];
+        for (int i = 0; i < plan.total_units; ++i) {
+          if (plan.unit_cls[i] != cls) continue;
+          a.units.u[a.units.n_units++] = plan.units[i];
           if (a.units.n_units == kMaxScoreUnits && (st = flush()) != PALU_OK) return st;
         }
         if ((st = flush()) != PALU_OK) return st;

@@ -53,9 +53,9 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
   const int nsp = (L + a.split_tokens - 1) / a.split_tokens;
   const int j = m.group_of_head[h];
-  const int u = h - m.head_off[j];
   const int rv = m.v_off[j + 1] - m.v_off[j];
-  const int width = (m.head_off[j + 1] - m.head_off[j]) * kDHead;
+  int width;
+  const int bv_blk = weight_block(m, j, h, m.bv_off[j], &width);
 
   // ---- softmax merge weights of the splits
   const float* ml = a.ml_part + ((size_t)b * a.n_split * m.n_heads + h) * 2;
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
 
   // ---- out = o_lat . B_v[:, 32 of the head's columns] / l: thread = (k part kp of 32, column quad cq of 8), 8-byte loads
   const int kp = tid >> 3, cq = tid & 7;
-  const uint16_t* Bv = a.Bv + m.bv_off[j] + u * kDHead + quarter * 32 + cq * 4;
+  const uint16_t* Bv = a.Bv + bv_blk + quarter * 32 + cq * 4;
   const int k_per = rv >> 5;                       // rank is a multiple of 32
   float4v o = {0.f, 0.f, 0.f, 0.f};
   for (int k0 = 0; k0 < k_per; k0 += 8) {          // 8 independent loads per batch

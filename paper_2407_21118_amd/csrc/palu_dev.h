@@ -21,10 +21,15 @@ constexpr int kDHead = PALU_D_HEAD;        // 128
 constexpr int kHalf = kDHead / 2;          // 64 rotation pairs
 constexpr int kTile = 32;                  // tokens per MFMA tile (N of the 32x32x16 instruction)
 
-// Layer metadata passed by value in the kernel arguments.
+// Layer metadata passed by value in the kernel arguments.  Heads are QUERY heads:
+// with grouped-query attention (qpk query heads per key/value head) head_off counts
+// qpk heads per key/value head of the descriptor, and bk_off / bv_off are the
+// offsets of per-query-head data laid out like the weights (the folded queries);
+// the weights themselves have one column block per key/value head, see weight_block.
 struct Meta {
   int n_heads;
   int n_groups;
+  int qpk;
   int head_off[PALU_MAX_GROUPS + 1];
   int k_off[PALU_MAX_GROUPS + 1];
   int v_off[PALU_MAX_GROUPS + 1];
@@ -116,6 +121,10 @@ struct ScoreArgs {
   int n_blocks_q;            // R_k / quant_block (int4 only)
   int quant_block;
   float scale;               // log2(e) / sqrt(d_h)
+  // shared-key form (grouped-query attention): units count key/value heads, n_heads the query heads
+  const uint16_t* qfrag;     // rotated queries as contraction operands, see qfrag_kernel
+  int qpk;                   // query heads per key/value head
+  int n_kv;                  // key/value heads
   ScoreUnits units;
 };
 
@@ -127,6 +136,17 @@ struct RopeGatherArgs {
   int table_len;
 };
 
+// Rotated queries of grouped-query attention as A operands of v_mfma_f32_4x4x4_16B_f16.
+struct QfragArgs {
+  const uint16_t* q;         // [batch, n_kv * qpk, 128]
+  const int32_t* q_pos;
+  uint16_t* qfrag;           // [batch][n_kv][2 feature halves][passes][16 steps][8 lane classes] 8-byte entries
+  float theta;
+  float rev_hi[kHalf];
+  float rev_lo[kHalf];
+  int n_kv, qpk, passes;
+};
+
 struct FoldArgs {
   const uint16_t* q;         // [batch, n_heads, 128]
   const int32_t* q_pos;
@@ -136,6 +156,7 @@ struct FoldArgs {
   float theta;
   float rev_hi[kHalf];       // theta^(-2f/128) / (2 pi) from the host's float64 value, as a float pair hi + lo
   float rev_lo[kHalf];
+  int plain;                 // 1: no query: M = B_k itself in operand order (the shared-key form of the score kernel)
   Meta meta;
 };
 
@@ -152,6 +173,19 @@ struct CombineArgs {
   int o_stride;
   Meta meta;
 };
+
+// Where query head h of group j finds its 128 columns inside the concatenated
+// reconstruction matrices: `off` is bk_off[j] or bv_off[j]; *width receives the
+// row pitch of the group's matrix (key/value heads of the group times 128).
+__device__ __forceinline__ int weight_block(const Meta& m, int j, int h, int off, int* width) {
+  const int s_q = m.head_off[j + 1] - m.head_off[j];
+  if (m.qpk == 1) {
+    *width = s_q * kDHead;
+    return off + (h - m.head_off[j]) * kDHead;
+  }
+  *width = s_q / m.qpk * kDHead;
+  return off / m.qpk + (h - m.head_off[j]) / m.qpk * kDHead;
+}
 
 // Per-head offset of its value-latent accumulator inside an o_part row:
 // heads are laid out in order, head h taking r_v(group(h)) floats.

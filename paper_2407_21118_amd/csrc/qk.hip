@@ -100,8 +100,9 @@ __global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
 #pragma unroll
   for (int x = 0; x < 8; ++x) bw[x] = uint4v{0, 0, 0, 0};
   if (mine) {
-    const int width = (m.head_off[j + 1] - m.head_off[j]) * kDHead;
-    const uint16_t* Brow = a.Bk + m.bk_off[j] + (size_t)(cabs - m.k_off[j]) * width + (h - m.head_off[j]) * kDHead + fh;
+    int width;
+    const int blk = weight_block(m, j, h, m.bk_off[j], &width);
+    const uint16_t* Brow = a.Bk + blk + (size_t)(cabs - m.k_off[j]) * width + fh;
 #pragma unroll
     for (int x = 0; x < 8; ++x) bw[x] = *reinterpret_cast<const uint4v*>(Brow + 8 * x);
   }

@@ -56,14 +56,14 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
   const int u = h - m.head_off[j];
   const int r = m.k_off[j + 1] - m.k_off[j];
   if (ks >= (r >> 4)) return;
-  const int width = (m.head_off[j + 1] - m.head_off[j]) * kDHead;
+  int width;
 
   // rows 16*ks .. 16*ks+15 of this head's 128 columns: thread = (row, 8-column piece)
-  const uint16_t* B = a.Bk + m.bk_off[j] + u * kDHead;
+  const uint16_t* B = a.Bk + weight_block(m, j, h, m.bk_off[j], &width);
   const int lrow = tid >> 4, lcol = (tid & 15) * 8;
   const uint4v raw = *reinterpret_cast<const uint4v*>(B + (size_t)(16 * ks + lrow) * width + lcol);
 
-  if (tid < kHalf) {
+  if (tid < kHalf && !a.plain) {
     // rotate the query: angle = pos * w_f with w_f / 2pi given as a float pair
     // (hi, lo) from the host's float64 value, so that the angle in revolutions
     // keeps ~1e-7 absolute accuracy for positions up to 2^24
@@ -90,14 +90,14 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
   const int cp = 32 * rt + (lane & 31);
   const int f = cp & 63;
   const bool is_w = cp >= kHalf;
-  const float qa = qr[f], qb = qr[f + kHalf];
+  const float qa = a.plain ? 0.f : qr[f], qb = a.plain ? 0.f : qr[f + kHalf];
   const int k0 = 8 * (lane >> 5);
   uint16_t v[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const float b1 = T::to_float(Bs[k0 + e][f]);
     const float b2 = T::to_float(Bs[k0 + e][f + kHalf]);
-    const float val = is_w ? (qb * b1 - qa * b2) : (qa * b1 + qb * b2);
+    const float val = a.plain ? (is_w ? b2 : b1) : (is_w ? (qb * b1 - qa * b2) : (qa * b1 + qb * b2));
     v[e] = F16::from_float(val);       // the score kernel always contracts in fp16
   }
   uint4v pk;
@@ -109,6 +109,61 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
   *reinterpret_cast<uint4v*>(out + ((size_t)ks * 256 + tid) * 8) = pk;
 }
 
+// Grouped-query attention, shared-key form of the score kernel: the rotated queries
+// q' = RoPE(q, q_pos) of the query heads of one key/value head, as A operands of the
+// 4x4x4 contractions, 8 bytes per (step, lane class = 4 (lane / 32) + lane % 4: lane half
+// and head).  Contraction step n of a lane half `hi` covers the accumulators
+// e = 2n, 2n+1 (e = 16 rt + i: rotation pair f = 32 rt + mfma_row(i, hi)) as the four
+// values K cos_f (both accumulators), then K sin_f (both); the matching query entries
+// are q'_f and q'_{f+64} for the wavefronts that hold K_f, and q'_{f+64} and -q'_f for
+// those that hold K_{f+64}.
+// grid (key/value heads, batch), 256 threads.
+template <typename T>
+__global__ __launch_bounds__(256) void qfrag_kernel(QfragArgs a) {
+  __shared__ float qr[8][kDHead];
+  const int kvh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  for (int h0 = 0; h0 < a.qpk; h0 += 4) {
+    const int hq = h0 + (tid >> 6), f = tid & 63;
+    if (hq >= a.qpk) continue;
+    const uint16_t* qp = a.q + (((size_t)b * a.n_kv + kvh) * a.qpk + hq) * kDHead;
+    const float x0 = T::to_float(qp[f]);
+    const float x1 = T::to_float(qp[f + kHalf]);
+    const float pos = (float)a.q_pos[b];
+    const float p = pos * a.rev_hi[f];
+    const float e = fmaf(pos, a.rev_hi[f], -p);
+    const float rev = (p - floorf(p)) + (e + pos * a.rev_lo[f]);      // angle in revolutions, as in fold_kernel
+    const float s = __builtin_amdgcn_sinf(rev), c = __builtin_amdgcn_cosf(rev);
+    qr[hq][f] = x0 * c - x1 * s;
+    qr[hq][f + kHalf] = x1 * c + x0 * s;
+  }
+  __syncthreads();
+  // one item = (feature half, pass, step n, lane class): 8 bytes
+  uint2v* out = reinterpret_cast<uint2v*>(a.qfrag) + ((size_t)b * a.n_kv + kvh) * 2 * a.passes * 128;
+  for (int item = tid; item < 2 * a.passes * 128; item += 256) {
+    const int cls = item & 7, n = (item >> 3) & 15;
+    const int p = (item >> 7) % a.passes, half = (item >> 7) / a.passes;
+    const int hq = 4 * p + (cls & 3), hi = cls >> 2;
+    uint16_t v[4];
+#pragma unroll
+    for (int y = 0; y < 2; ++y) {
+      const int e = 2 * n + y;
+      const int f = 32 * (e >> 4) + mfma_row(e & 15, hi);
+      float qc = 0.f, qs = 0.f;
+      if (hq < a.qpk) {
+        qc = half ? qr[hq][f + kHalf] : qr[hq][f];
+        qs = half ? -qr[hq][f] : qr[hq][f + kHalf];
+      }
+      v[y] = F16::from_float(qc);            // entry order of a step: cos parts of its two accumulators, then sin parts
+      v[2 + y] = F16::from_float(qs);
+    }
+    uint2v pk;
+    pk.x = v[0] | ((uint32_t)v[1] << 16);
+    pk.y = v[2] | ((uint32_t)v[3] << 16);
+    out[item] = pk;
+  }
+}
+
+template __global__ void qfrag_kernel<F16>(QfragArgs);
 template __global__ void fold_kernel<F16>(FoldArgs);
 template __global__ void fold_kernel<BF16>(FoldArgs);
 

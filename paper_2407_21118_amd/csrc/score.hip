@@ -53,6 +53,7 @@ constexpr int kLdsBudget = 160 * 1024 - 1024;    // LDS of one CU, less a little
 
 // LDS bytes per buffered tile and number of buffers, shared with the host for the launch
 constexpr int score_buf_bytes(int width) { return kTile * (width * 2 + kRowPad) + kRopeTileB; }
+constexpr int score_qf_bytes(int passes) { return 8 * passes * 1024; }      // shared-key form: query operands of 8 wavefronts
 constexpr int score_num_bufs(int width, bool dma) {
   return !dma ? 2 : (4 * score_buf_bytes(width) <= kLdsBudget ? 4 : 3);
 }
@@ -72,12 +73,24 @@ constexpr int score_num_bufs(int width, bool dma) {
 //       two heads).  8: two per SIMD, RT = 2, four heads, ping-pong schedule:
 //       wavefronts 0-3 own the cos halves, 4-7 the sin halves.
 // I4:   latents are packed 4-bit codes with per-(token, block) scale and zero
-template <typename T, int NKS, int RT, int G, int NW, bool I4>
+// QP:   0: one query per key/value head, folded into the weights as described above.
+//       1, 2: grouped-query attention with up to 4 QP query heads per key/value head.
+//       The stationary operand is B_k itself (transposed), so the accumulators are the
+//       key K[feature][token], rebuilt once for all query heads that share it.  With
+//       q' the rotated query, the score is the contraction over f < 64 of
+//         K_f (cos_f q'_f + sin_f q'_{f+64})  +  K_{f+64} (cos_f q'_{f+64} - sin_f q'_f):
+//       a wavefront owns one half of the features (K_f or K_{f+64}), scales its
+//       accumulators by the position's cos and sin, rounds the products to fp16 and
+//       contracts them with its query heads on v_mfma_f32_4x4x4_16B_f16 (16 blocks of
+//       4 heads x 4 tokens: a lane feeds its own token's values and collects that
+//       token's four scores; the two lane halves of a token are then added).
+template <typename T, int NKS, int RT, int G, int NW, bool I4, int QP = 0>
 __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   static_assert(NW == 4 || (NW == 8 && RT == 2), "8 wavefronts only as half-head ping-pong");
   constexpr bool kIsBf16 = !__is_same(T, F16);
   constexpr bool kDma = !I4 && !kIsBf16;                        // fp16 latents: global -> LDS without registers
+  static_assert(QP == 0 || (NW == 8 && G == 1 && kDma), "shared-key form: fp16 latents, ping-pong schedule, one group");
   constexpr bool kPingPong = NW == 8;
   constexpr int kRank = NKS * 16;
   constexpr int kWidth = G * kRank;                             // staged columns per token
@@ -329,6 +342,15 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 
   // ---- stationary operand: folded weights of (b, head), rows [32*rt0, 32*(rt0+RT))
   half8 W[NKS][RT];
+  // shared-key form: A operands of the 16 query contractions per pass, 8 bytes per (step, lane class):
+  // lanes with the same head (lane % 4) and lane half use the same entries (written by qfrag_kernel).
+  // 1 KiB per pass and wavefront; fetched with the weights and parked in LDS behind the tile buffers
+  // by the wavefront's first epilogue (by then the weight fetch it was queued behind has been consumed).
+  constexpr int kQfWords = QP > 0 ? QP : 1;
+  uint4v qf[kQfWords];
+  bool qf_pending = QP > 0;
+  unsigned char* qf_lds = lds + (size_t)kBufs * kBufB + (size_t)wave * (kQfWords * 1024);
+  const int qf_cls = ((lane >> 5) * 4 + (lane & 3)) * 8;
   auto load_weights = [&]() __attribute__((always_inline)) {
     const uint16_t* mf = a.mfold + (size_t)b * a.mfold_bstride + u.bk_off0 +
                          ((size_t)g_rel * u.s + u_in_g) * u.head_stride;
@@ -337,6 +359,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
         W[ks][rt] = *reinterpret_cast<const half8*>(mf + ((size_t)(ks * 4 + rt0 + rt) * 64 + lane) * 8);
+    if constexpr (QP > 0) {
+      const uint4v* src = reinterpret_cast<const uint4v*>(a.qfrag) +
+                          ((((size_t)b * a.n_kv + hc) * 2 + (rt0 >> 1)) * kQfWords) * 64 + lane;
+#pragma unroll
+      for (int x = 0; x < kQfWords; ++x) qf[x] = src[x * 64];
+    }
   };
   // Ping-pong with LDS-direct loads: the wavefronts that run the first MFMA phase fetch their
   // weights now; the others only after the first barrier, so that the barrier does not wait
@@ -345,12 +373,15 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   if (!kSplitStart || wave < 4) load_weights();
 
   const int part_idx = u.part0 + (RT == 2 ? (rt0 >> 1) : 0);
-  float* out_row = a.scores + ((size_t)part_idx * a.batch + b) * a.n_heads * (size_t)a.lpad + (size_t)hc * a.lpad;
+  // row of head hc; in the shared-key form hc is a key/value head and its query heads' rows follow each other
+  float* out_row = a.scores + ((size_t)part_idx * a.batch + b) * a.n_heads * (size_t)a.lpad +
+                   (size_t)hc * (QP > 0 ? a.qpk : 1) * a.lpad;
 
   // MFMA phase of one tile: accumulators (features x tokens) and the tile's cos/sin weights
   struct TileAcc {
     float16v acc[RT];
     half8 cs[RT][2];
+    half8 sn[QP > 0 ? RT : 1][2];    // shared-key form: cs = cos, sn = sin of the accumulators' rotation pairs
   };
   auto mfma_phase = [&](TileAcc& r, int tile) {
     const unsigned char* base = lds + (size_t)(tile % kBufs) * kBufB;
@@ -367,8 +398,16 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
       for (int hx = 0; hx < 2; ++hx) {
-        const int piece = lane_hi * 8 + (rt0 + rt) * 2 + hx;
-        r.cs[rt][hx] = *reinterpret_cast<const half8*>(crow + ((piece ^ (lane_lo & 15)) * 16));
+        if constexpr (QP > 0) {
+          // accumulator row 32 (rt0 + rt) + x is feature f or f + 64 of pair f = 32 rt + x: cos_f sits in
+          // the table row where the folded form keeps the weight of row f, sin_f where it keeps that of row f + 64
+          const int pc = lane_hi * 8 + rt * 2 + hx, ps = lane_hi * 8 + (rt + 2) * 2 + hx;
+          r.cs[rt][hx] = *reinterpret_cast<const half8*>(crow + ((pc ^ (lane_lo & 15)) * 16));
+          r.sn[rt][hx] = *reinterpret_cast<const half8*>(crow + ((ps ^ (lane_lo & 15)) * 16));
+        } else {
+          const int piece = lane_hi * 8 + (rt0 + rt) * 2 + hx;
+          r.cs[rt][hx] = *reinterpret_cast<const half8*>(crow + ((piece ^ (lane_lo & 15)) * 16));
+        }
       }
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
@@ -392,6 +431,51 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   // RoPE-weighted feature sum of one tile and the score store
   auto epilogue = [&](const TileAcc& r, int tile) {
     const int t0 = t_begin + tile * kTile;
+    if constexpr (QP > 0) {
+      typedef _Float16 half2f __attribute__((ext_vector_type(2)));
+      typedef float float2f __attribute__((ext_vector_type(2)));
+      // Step n = 8 rt + ip of the contraction takes (K cos)(2ip), (K cos)(2ip+1), (K sin)(2ip), (K sin)(2ip+1):
+      // the two accumulators rounded to fp16, then packed fp16 products with the position's cos and sin.
+      // Each step's products go straight into its 4x4x4 contractions (two independent chains per pass),
+      // so the vector work fills the waits for the matrix pipe, which the partner wavefront is using.
+      if (qf_pending) {
+#pragma unroll
+        for (int x = 0; x < kQfWords; ++x) *reinterpret_cast<uint4v*>(qf_lds + x * 1024 + lane * 16) = qf[x];
+        qf_pending = false;
+      }
+      float4v sc[QP][2];
+#pragma unroll
+      for (int p = 0; p < QP; ++p) sc[p][0] = sc[p][1] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int ip = 0; ip < 8; ++ip) {
+          const int n = 8 * rt + ip;
+          const float2f kf = {r.acc[rt][2 * ip], r.acc[rt][2 * ip + 1]};
+          const half2f kk = __builtin_convertvector(kf, half2f);
+          const uint4v cw = __builtin_bit_cast(uint4v, r.cs[rt][ip >> 2]), sw = __builtin_bit_cast(uint4v, r.sn[rt][ip >> 2]);
+          const uint32_t cb = cw[ip & 3], sb = sw[ip & 3];
+          const half2f pc = kk * __builtin_bit_cast(half2f, cb), ps = kk * __builtin_bit_cast(half2f, sb);
+          const uint2v bq = {__builtin_bit_cast(uint32_t, pc), __builtin_bit_cast(uint32_t, ps)};
+#pragma unroll
+          for (int p = 0; p < QP; ++p) {
+            const uint2v aq = *reinterpret_cast<const uint2v*>(qf_lds + (p * 16 + n) * 64 + qf_cls);
+            sc[p][n & 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4, aq), __builtin_bit_cast(half4, bq),
+                                                               sc[p][n & 1], 0, 0, 0);
+          }
+        }
+#pragma unroll
+      for (int p = 0; p < QP; ++p) {
+        // entry i: head 4p + i, this lane's token, this lane half's features.  Each lane half stores two of the heads.
+        const float s0 = sum_across_halves(sc[p][0][0] + sc[p][1][0]), s1 = sum_across_halves(sc[p][0][1] + sc[p][1][1]);
+        const float s2 = sum_across_halves(sc[p][0][2] + sc[p][1][2]), s3 = sum_across_halves(sc[p][0][3] + sc[p][1][3]);
+        const int hq = 4 * p + 2 * lane_hi;
+        float* row = out_row + (size_t)hq * a.lpad + t0 + lane_lo;
+        if (hq < a.qpk) row[0] = (lane_hi ? s2 : s0) * a.scale;
+        if (hq + 1 < a.qpk) row[a.lpad] = (lane_hi ? s3 : s1) * a.scale;
+      }
+      return;
+    }
     float part[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -413,7 +497,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     // tiles 0 .. kAheadTiles-1 are in flight; tile 0 must have landed before the first MFMA phase.
     // Where the weight loads were issued after them, those stay outstanding as well: the first
     // phase begins with the first k-steps' weights (the compiler waits per k-step from there on).
-    constexpr int kStartWait = kInFlight * kDmaOps + NKS * RT;
+    constexpr int kStartWait = kInFlight * kDmaOps + NKS * RT + QP;
     static_assert(!kSplitStart || kStartWait <= 63, "start-up wait exceeds the counter");
     if (kSplitStart && wave < 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kStartWait <= 63 ? kStartWait : 0));
     else dma_wait(std::integral_constant<int, kInFlight>{});

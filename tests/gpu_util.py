@@ -33,7 +33,7 @@ def make_desc(layer, dtype: str, k_i4: bool = False, v_i4: bool = False) -> "P.L
     act = P.PALU_F16 if dtype == "f16" else P.PALU_BF16
     return P.LayerDesc(layer.n_heads, layer.d_head, layer.group_head_off, layer.k_rank_off, layer.v_rank_off,
                        act, P.PALU_I4 if k_i4 else act, P.PALU_I4 if v_i4 else act, layer.quant_block,
-                       layer.rope_theta)
+                       layer.rope_theta, layer.q_per_kv)
 
 
 def rel_err(got: np.ndarray, ref: np.ndarray):
@@ -86,4 +86,4 @@ def run_oracle(case, quant=None, k_i4=False, v_i4=False):
     Hk = O.dequant_latent(*quant["k"]) if k_i4 else case.Hk
     Hv = O.dequant_latent(*quant["v"]) if v_i4 else case.Hv
     return O.attn_decode(case.q, case.q_pos, Hk, Hv, case.Bk, case.Bv, layer.group_head_off, layer.k_rank_off,
-                         layer.v_rank_off, layer.d_head, layer.rope_theta, case.k_pos, case.seq_lens)
+                         layer.v_rank_off, layer.d_head, layer.rope_theta, case.k_pos, case.seq_lens, layer.q_per_kv)

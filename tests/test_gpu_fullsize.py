@@ -20,7 +20,8 @@ def group_slice(layer, j, heads):
     """Layer holding only `heads` (indices inside group j) of group j."""
     rk = layer.k_rank_off[j + 1] - layer.k_rank_off[j]
     rv = layer.v_rank_off[j + 1] - layer.v_rank_off[j]
-    return synth.Layer(len(heads), layer.d_head, [0, len(heads)], [0, rk], [0, rv], layer.rope_theta)
+    return synth.Layer(len(heads), layer.d_head, [0, len(heads)], [0, rk], [0, rv], layer.rope_theta,
+                       q_per_kv=layer.q_per_kv)
 
 
 def b_slice(flat, layer, which, j, heads):
@@ -86,11 +87,12 @@ def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP, no_rope=False):
                 Hk = deq
             else:
                 Hv = deq
-        h_abs = [layer.group_head_off[j] + u for u in heads]
+        # query heads of the sampled key/value heads (one each unless the layer is grouped-query)
+        h_abs = [(layer.group_head_off[j] + u) * layer.q_per_kv + w for u in heads for w in range(layer.q_per_kv)]
         q = case.q[b, h_abs].float().cpu().numpy()[None]
         ref = O.attn_decode(q, [int(case.q_pos[b])], Hk, Hv, b_slice(Bk, layer, "k", j, heads),
                             b_slice(Bv, layer, "v", j, heads), sub.group_head_off, sub.k_rank_off, sub.v_rank_off,
-                            layer.d_head, layer.rope_theta)
+                            layer.d_head, layer.rope_theta, None, None, layer.q_per_kv)
         whole, rows = rel_err(got[b, h_abs][None], ref)
         say(f"       sample b={b} group={j} heads={heads}: rel err {whole:.3e} (rows {rows:.3e})")
         worst = max(worst, whole, rows)
@@ -146,3 +148,12 @@ def test_full_config4_no_rope_int4():
 
 def test_full_config5b_no_rope():
     run_full("5b", [(0, 0, [0, 13]), (6, 0, [31])], no_rope=True)
+
+
+def test_full_gqa_16k():
+    """32 query heads on 8 key/value heads (Llama-3-8B / Mistral-7B shape), batch 4 at 16K."""
+    run_full("gqa", [(0, 0, [0, 3]), (3, 1, [2])])
+
+
+def test_full_gqa_16k_no_rope():
+    run_full("gqa", [(1, 1, [1])], no_rope=True)

@@ -165,13 +165,14 @@ def test_quantizer_scatter_rows():
     assert not c[[0, 1, 3, 5]].any()
 
 
-@pytest.mark.parametrize("theta,v_i4", [(10000.0, False), (0.0, False), (10000.0, True)])
-def test_latent_output_matches_oracle(theta, v_i4):
+@pytest.mark.parametrize("theta,v_i4,cfg", [(10000.0, False, "3"), (0.0, False, "3"), (10000.0, True, "4"),
+                                            (500000.0, False, "gqa")])
+def test_latent_output_matches_oracle(theta, v_i4, cfg):
     """palu_attn_decode_latent: the output stays in the value latent space (Sec. 3.1.1);
     compared with the oracle's latent output, and times B_v with the full decode call."""
     import dataclasses
     from gpu_util import TOL_FP, TOL_I4, make_desc, to_dev
-    layer = dataclasses.replace(synth.config_layer("3" if not v_i4 else "4"), rope_theta=theta)
+    layer = dataclasses.replace(synth.config_layer(cfg), rope_theta=theta)
     case = synth.make_case_svd(layer, 2, 300, seed=9, rotate=v_i4)
     case.seq_lens = np.array([300, 77], np.int32)
     case.q_pos = np.array([299, 76], np.int32)
@@ -194,7 +195,7 @@ def test_latent_output_matches_oracle(theta, v_i4):
     got = P.palu_attn_decode_latent(desc, 2, 300, 300, q, q_pos, hk, hv, Bk, table, 300, seq_lens=lens, **kw)
     torch.cuda.synchronize()
     ref = O.attn_decode_latent(case.q, case.q_pos, case.Hk, Hv_ref, case.Bk, layer.group_head_off, layer.k_rank_off,
-                               layer.v_rank_off, 128, theta, seq_lens=case.seq_lens)
+                               layer.v_rank_off, 128, theta, seq_lens=case.seq_lens, q_per_kv=layer.q_per_kv)
     got = got.cpu().numpy()
     assert got.shape == ref.shape
     err = np.abs(got - ref).max() / np.abs(ref).max()

@@ -206,3 +206,41 @@ def test_random_layers_int4(seed):
     case.name = f"random-int4-{seed} groups={sizes} k_ranks={kr} v_ranks={vr}"
     quant = {"k": O.quant_latent(case.Hk), "v": O.quant_latent(case.Hv)}
     check(case, TOL_I4, k_i4=seed != 3, v_i4=seed != 2, quant=quant)
+
+
+@pytest.mark.parametrize("qpk,theta,dtype", [(4, 500000.0, "f16"), (4, 0.0, "f16"), (2, 10000.0, "bf16"), (8, 10000.0, "f16"),
+                                             (3, 10000.0, "f16"), (5, 500000.0, "f16"), (12, 10000.0, "f16")])
+def test_grouped_query_attention(qpk, theta, dtype):
+    """Grouped-query attention (the Llama-3 / Mistral models of Sec. 4.1): the latents and
+    B matrices cover the key/value heads, q_per_kv query heads share each of them.  Groups
+    of unequal size and rank, ragged lengths, with and without RoPE.  With fp16 latents,
+    RoPE and up to 8 query heads per key/value head the score kernel rebuilds each key once
+    for the heads that share it (one or two passes of four heads); the other cases (bf16,
+    12 heads) run one folded matrix per query head."""
+    n_kv = 8 if qpk <= 4 else 4
+    sizes = [4, 2, 1, 1] if n_kv == 8 else [2, 1, 1]
+    head_off = [0] + list(np.cumsum(sizes))
+    kr = [256, 96, 64, 128][:len(sizes)]
+    vr = [192, 128, 32, 96][:len(sizes)]
+    layer = synth.Layer(n_kv, 128, head_off, [0] + list(np.cumsum(kr)), [0] + list(np.cumsum(vr)), rope_theta=theta,
+                        q_per_kv=qpk)
+    case = synth.make_case_orthonormal(layer, 2, 300, seed=300 + qpk, dtype=dtype)
+    case.seq_lens = np.array([300, 131], np.int32)
+    case.q_pos = np.array([310, 130], np.int32)
+    if qpk in (3, 8):
+        case.k_pos = np.sort(np.random.default_rng(qpk).choice(4096, size=300, replace=False)).astype(np.int32)
+        case.q_pos = np.array([4100, 2000], np.int32)
+    case.name = f"gqa q_per_kv={qpk} kv_heads={n_kv} groups={sizes} theta={theta}"
+    check(case, TOL_FP)
+
+
+@pytest.mark.parametrize("k_i4,v_i4,theta", [(True, True, 500000.0), (True, True, 0.0)])
+def test_grouped_query_attention_int4(k_i4, v_i4, theta):
+    import dataclasses
+    layer = dataclasses.replace(synth.config_layer("gqa"), rope_theta=theta)
+    case = synth.make_case_svd(layer, 2, 260, seed=31, rotate=True)
+    case.seq_lens = np.array([260, 97], np.int32)
+    case.q_pos = (case.seq_lens - 1).astype(np.int32)
+    case.name = f"gqa-int4 theta={theta}"
+    quant = {"k": O.quant_latent(case.Hk), "v": O.quant_latent(case.Hv)}
+    check(case, TOL_I4, k_i4=k_i4, v_i4=v_i4, quant=quant)

@@ -74,7 +74,7 @@ def make_device_case(cfg: str, seed: int = 0, dtype: str = "f16", n_sets: int = 
     batch = fb if batch is None else batch
     seq = fs if seq is None else seq
     td = _tdtype(dtype)
-    d = layer.n_heads * layer.d_head
+    d = layer.n_q_heads * layer.d_head
     rotate = base == "4"
     dev = torch.device(device)
 
@@ -83,7 +83,7 @@ def make_device_case(cfg: str, seed: int = 0, dtype: str = "f16", n_sets: int = 
 
     g = torch.Generator(device=dev)
     g.manual_seed(seed * 7919 + 17)
-    q = torch.randn((batch, layer.n_heads, layer.d_head), generator=g, device=dev, dtype=torch.float32).to(td)
+    q = torch.randn((batch, layer.n_q_heads, layer.d_head), generator=g, device=dev, dtype=torch.float32).to(td)
     x_new = torch.randn((batch, d), generator=g, device=dev, dtype=torch.float32).to(td)
     q_pos = torch.full((batch,), seq - 1, dtype=torch.int32, device=dev)
     if base == "1":

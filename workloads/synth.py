@@ -32,6 +32,11 @@ class Layer:
     v_rank_off: List[int]
     rope_theta: float = 10000.0
     quant_block: int = 128
+    q_per_kv: int = 1                  # grouped-query attention: query heads per key/value head (n_heads counts the latter)
+
+    @property
+    def n_q_heads(self) -> int:
+        return self.n_heads * self.q_per_kv
 
     @property
     def n_groups(self) -> int:
@@ -54,24 +59,24 @@ class Layer:
 
 
 def uniform_layer(n_heads: int, group_size: int, rank_k: int, rank_v: Optional[int] = None,
-                  d_head: int = D_HEAD, rope_theta: float = 10000.0) -> Layer:
+                  d_head: int = D_HEAD, rope_theta: float = 10000.0, q_per_kv: int = 1) -> Layer:
     assert n_heads % group_size == 0
     ng = n_heads // group_size
     rank_v = rank_k if rank_v is None else rank_v
     return Layer(n_heads, d_head,
                  [j * group_size for j in range(ng + 1)],
                  [j * rank_k for j in range(ng + 1)],
-                 [j * rank_v for j in range(ng + 1)], rope_theta)
+                 [j * rank_v for j in range(ng + 1)], rope_theta, q_per_kv=q_per_kv)
 
 
 def ragged_layer(n_heads: int, group_size: int, k_ranks, v_ranks, d_head: int = D_HEAD,
-                 rope_theta: float = 10000.0) -> Layer:
+                 rope_theta: float = 10000.0, q_per_kv: int = 1) -> Layer:
     ng = n_heads // group_size
     assert len(k_ranks) == ng and len(v_ranks) == ng
     return Layer(n_heads, d_head,
                  [j * group_size for j in range(ng + 1)],
                  [0] + list(np.cumsum(k_ranks).astype(int)),
-                 [0] + list(np.cumsum(v_ranks).astype(int)), rope_theta)
+                 [0] + list(np.cumsum(v_ranks).astype(int)), rope_theta, q_per_kv=q_per_kv)
 
 
 # ------------------------------------------------------------------ ranks
@@ -147,7 +152,7 @@ def make_factors(layer: Layer, seed: int, which: str, d_model: Optional[int] = N
     [d_model, s*d_head]; rng = default_rng([seed, 10 + (which=='v'), j]) per
     group j, one standard_normal draw of W.  Returns A [d_model, R] float64 and
     the concatenated B buffer (flat float64, group j row-major [r_j, s_j*d_h])."""
-    d_model = layer.n_heads * layer.d_head if d_model is None else d_model
+    d_model = layer.n_q_heads * layer.d_head if d_model is None else d_model
     off = layer.k_rank_off if which == "k" else layer.v_rank_off
     A = np.empty((d_model, off[-1]), dtype=np.float64)
     Bs = []
@@ -226,7 +231,7 @@ def make_case_orthonormal(layer: Layer, batch: int, seq: int, seed: int = 0, dty
     rng = np.random.default_rng([seed, 1])
     Hk = round_to(rng.standard_normal((batch, seq, layer.R_k)), dtype)
     Hv = round_to(rng.standard_normal((batch, seq, layer.R_v)), dtype)
-    q = round_to(rng.standard_normal((batch, layer.n_heads, layer.d_head)), dtype)
+    q = round_to(rng.standard_normal((batch, layer.n_q_heads, layer.d_head)), dtype)
     Bk = round_to(make_orthonormal_B(layer, seed, "k"), dtype)
     Bv = round_to(make_orthonormal_B(layer, seed, "v"), dtype)
     q_pos = np.full((batch,), seq - 1, dtype=np.int32)
@@ -238,7 +243,7 @@ def make_case_svd(layer: Layer, batch: int, seq: int, seed: int = 0, dtype: str 
     """Configuration-2..5 recipe: (A, B) from truncated SVDs of random W,
     latents = x . A with x ~ N(0,1) [B, L, d_model] (default_rng([seed, 2, b])
     per batch element), q ~ N(0,1) from default_rng([seed, 3])."""
-    d_model = layer.n_heads * layer.d_head if d_model is None else d_model
+    d_model = layer.n_q_heads * layer.d_head if d_model is None else d_model
     Ak, Bk = make_factors(layer, seed, "k", d_model, rotate)
     Av, Bv = make_factors(layer, seed, "v", d_model, rotate)
     Ak16, Av16 = round_to(Ak, dtype), round_to(Av, dtype)
@@ -248,7 +253,7 @@ def make_case_svd(layer: Layer, batch: int, seq: int, seed: int = 0, dtype: str 
         x = round_to(np.random.default_rng([seed, 2, b]).standard_normal((seq, d_model)), dtype)
         Hk[b] = make_latents_cpu(x, Ak16, dtype)
         Hv[b] = make_latents_cpu(x, Av16, dtype)
-    q = round_to(np.random.default_rng([seed, 3]).standard_normal((batch, layer.n_heads, layer.d_head)), dtype)
+    q = round_to(np.random.default_rng([seed, 3]).standard_normal((batch, layer.n_q_heads, layer.d_head)), dtype)
     q_pos = np.full((batch,), seq - 1, dtype=np.int32)
     return Case("svd", layer, dtype, batch, seq, q, q_pos, Hk, Hv,
                 round_to(Bk, dtype), round_to(Bv, dtype), Ak16, Av16)
@@ -272,11 +277,15 @@ def config_layer(cfg: str, seed: int = 0) -> Layer:
         # the allocation of the paper's latency experiments (Sec. 4.5): keys compressed by 75 %,
         # values by 25 %, i.e. ranks 128 / 384 per group of 4 heads (50 % overall)
         return ragged_layer(32, 4, [128] * 8, [384] * 8)
+    if cfg == "gqa":
+        # the grouped-query models of Sec. 4.1 (Llama-3-8B, Mistral-7B): 32 query heads on 8 key/value
+        # heads, groups of 4 key/value heads at 50 % (rank 256 per side), Llama-3's RoPE base
+        return uniform_layer(8, 4, 256, rope_theta=500000.0, q_per_kv=4)
     raise ValueError(cfg)
 
 
 FULL_SIZES = {            # (batch, seq) at full size
     "1": (1, 1024), "2": (1, 16384), "2-4k": (1, 4096), "2-64k": (1, 65536),
     "3": (4, 16384), "4": (16, 8192), "5a": (8, 16384), "5b": (8, 16384),
-    "2p": (1, 16384), "2p-64k": (1, 65536),
+    "2p": (1, 16384), "2p-64k": (1, 65536), "gqa": (4, 16384), "gqa-64k": (1, 65536),
 }
