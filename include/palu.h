@@ -67,7 +67,10 @@ enum {
  * n_heads*q_per_kv query heads, query head i attends key/value head
  * i / q_per_kv, and wherever an argument below is shaped by heads (q, out, the
  * latent output, the width n_heads*d_head of x) the heads are the query heads.
- * n_heads*q_per_kv <= PALU_MAX_HEADS.
+ * n_heads*q_per_kv <= PALU_MAX_HEADS.  Several queries per sequence at one position
+ * (parallel samples over a shared prefix) are the same thing: multiply q_per_kv by
+ * the number of queries and lay q out as [batch, key/value head, query, head of the
+ * key/value head, d_head].
  */
 typedef struct palu_layer_desc {
   int32_t n_heads;

@@ -244,3 +244,26 @@ def test_grouped_query_attention_int4(k_i4, v_i4, theta):
     case.name = f"gqa-int4 theta={theta}"
     quant = {"k": O.quant_latent(case.Hk), "v": O.quant_latent(case.Hv)}
     check(case, TOL_I4, k_i4=k_i4, v_i4=v_i4, quant=quant)
+
+
+def test_parallel_queries_share_the_cache():
+    """Several queries per sequence at the same position (parallel samples or beams over a
+    shared prefix) are the grouped-query case with q_per_kv = number of queries: query j of
+    head i goes to row i * n_q + j.  One call must agree with the oracle and with n_q
+    single-query calls on the same cache."""
+    import dataclasses
+    n_q = 4
+    base = synth.uniform_layer(8, 4, 128, 96)
+    multi = dataclasses.replace(base, q_per_kv=n_q)
+    case = synth.make_case_orthonormal(multi, 2, 200, seed=41)
+    case.seq_lens = np.array([200, 61], np.int32)
+    case.q_pos = np.array([205, 60], np.int32)
+    case.name = f"parallel queries n_q={n_q}"
+    check(case, TOL_FP)
+    got = run_hip(case)
+    for j in range(n_q):
+        single = dataclasses.replace(case, layer=base, q=np.ascontiguousarray(case.q[:, j::n_q]))
+        one = run_hip(single)
+        whole, rows = rel_err(got[:, j::n_q], one.astype(np.float64))
+        say(f"         query {j}: against its own single-query call {whole:.3e}")
+        assert whole <= TOL_FP and rows <= TOL_FP
