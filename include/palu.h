@@ -263,6 +263,35 @@ int palu_attn_decode_latent(const palu_layer_desc* desc, int32_t batch, int32_t 
                             float* out_latent, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Several new query tokens per sequence in one call (a block of a chunked prompt,
+ * or a speculative-decoding check): each query is an ordinary decode step of Sec. 2.1
+ * Eq. 2 over the latent cache, with its own position and its own number of cached
+ * rows, so a causal block over rows that were appended first is
+ * q_len[b, j] = seq_lens[b] - n_q + j + 1.  Same result as n_q calls of
+ * palu_attn_decode with seq_lens = q_len[:, j]; the latents are read once and, for
+ * fp16 latents with RoPE and q_per_kv * n_q <= 16, each key is rebuilt once for all
+ * queries of its key/value head.
+ *   n_q        queries per sequence, n_heads * q_per_kv * n_q <= PALU_MAX_HEADS
+ *   q          DEVICE [batch, n_q, n_heads*q_per_kv, d_head] act_dtype, before RoPE
+ *   q_pos      DEVICE int32 [batch, n_q]
+ *   q_len      DEVICE int32 [batch, n_q] rows attended by each query, in [1, seq_lens[b]]
+ *              (seq_len where seq_lens is NULL), or NULL: every query attends all rows
+ *   out        DEVICE float32 [batch, n_q, n_heads*q_per_kv, d_head]
+ *   workspace  of palu_attn_decode_multi_workspace_bytes(desc, batch, n_q, max_seq) bytes
+ * Everything else as for palu_attn_decode.
+ */
+int palu_attn_decode_multi_workspace_bytes(const palu_layer_desc* desc, int32_t batch, int32_t n_q, int32_t max_seq,
+                                           size_t* out_bytes);
+int palu_attn_decode_multi(const palu_layer_desc* desc, int32_t batch, int32_t n_q, int32_t seq_len, int32_t max_seq,
+                           const void* q, const int32_t* q_pos, const int32_t* q_len,
+                           const void* hk, const void* hk_scale, const void* hk_zero,
+                           const void* hv, const void* hv_scale, const void* hv_zero,
+                           const int32_t* k_pos, const int32_t* seq_lens,
+                           const void* Bk, const void* Bv,
+                           const void* rope_table, int32_t rope_table_len,
+                           float* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Same call with per-stage timing hooks, for benchmarks that price each
  * stage against its own roofline.  The decode step runs as PALU_DECODE_STAGES
  * stages (0 fold the rotated query into B_k, 1 scores = reconstruction + RoPE +

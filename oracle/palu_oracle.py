@@ -277,6 +277,20 @@ def attn_decode_latent(q, q_pos, Hk, Hv, Bk, group_head_off, k_rank_off, v_rank_
     return out
 
 
+def attn_decode_multi(q, q_pos, q_len, Hk, Hv, Bk, Bv, group_head_off, k_rank_off, v_rank_off,
+                      d_head: int, rope_theta: float, k_pos=None, q_per_kv: int = 1) -> np.ndarray:
+    """Several new query tokens per sequence: query j of sequence b is its own
+    decode step (Sec. 2.1 Eq. 2 on the rebuilt keys and values) at position
+    q_pos[b, j] over the first q_len[b, j] cached rows.  q [B, n_q, n, d_head];
+    returns [B, n_q, n, d_head] float64."""
+    q = np.asarray(q, dtype=np.float64)
+    out = np.empty_like(q)
+    for j in range(q.shape[1]):
+        out[:, j] = attn_decode(q[:, j], np.asarray(q_pos)[:, j], Hk, Hv, Bk, Bv, group_head_off, k_rank_off,
+                                v_rank_off, d_head, rope_theta, k_pos, np.asarray(q_len)[:, j], q_per_kv)
+    return out
+
+
 # --------------------------------------------------------------------------
 # Closed forms the paper prints (used as pins and by the benchmark's counters)
 # --------------------------------------------------------------------------

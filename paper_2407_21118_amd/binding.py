@@ -88,6 +88,11 @@ def load_library():
     lib.palu_attn_decode_latent.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                             vp, i32, vp, vp, sz, vp]
     lib.palu_attn_decode_latent.restype = ctypes.c_int
+    lib.palu_attn_decode_multi_workspace_bytes.argtypes = [dp, i32, i32, i32, szp]
+    lib.palu_attn_decode_multi_workspace_bytes.restype = ctypes.c_int
+    lib.palu_attn_decode_multi.argtypes = [dp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                           vp, i32, vp, vp, sz, vp]
+    lib.palu_attn_decode_multi.restype = ctypes.c_int
     for name in ("palu_rope_table_bytes", "palu_rope_table_init", "palu_encode_workspace_bytes", "palu_encode",
                  "palu_quant_latent", "palu_attn_decode_workspace_bytes", "palu_attn_decode"):
         getattr(lib, name).restype = ctypes.c_int
@@ -307,3 +312,27 @@ def palu_probe_read(src, sink, stream=None) -> int:
     nbytes = (src.numel() * src.element_size()) // 16 * 16
     _check(load_library().palu_probe_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "palu_probe_read")
     return nbytes
+
+
+def palu_attn_decode_multi(desc: LayerDesc, batch: int, n_q: int, seq_len: int, max_seq: int, q, q_pos, hk, hv, Bk, Bv,
+                           rope_table, rope_table_len: int, q_len=None, out=None, workspace=None, k_pos=None,
+                           seq_lens=None, hk_scale=None, hk_zero=None, hv_scale=None, hv_zero=None, stream=None):
+    """n_q queries per sequence: q [batch, n_q, heads, d_head], q_pos and q_len [batch, n_q]."""
+    import torch
+    lib = load_library()
+    if out is None:
+        out = torch.empty((batch, n_q, desc.n_q_heads, desc.d_head), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        nbytes = ctypes.c_size_t(0)
+        _check(lib.palu_attn_decode_multi_workspace_bytes(desc.ref(), batch, n_q, max_seq, ctypes.byref(nbytes)),
+               "palu_attn_decode_multi_workspace_bytes")
+        workspace = torch.empty(int(nbytes.value), dtype=torch.uint8, device=q.device)
+    _need_cuda(q, q_pos, q_len, hk, hv, Bk, Bv, rope_table, out, workspace, k_pos, seq_lens, hk_scale, hk_zero,
+               hv_scale, hv_zero)
+    _check(lib.palu_attn_decode_multi(desc.ref(), batch, n_q, seq_len, max_seq, _ptr(q), _ptr(q_pos), _ptr(q_len),
+                                      _ptr(hk), _ptr(hk_scale), _ptr(hk_zero), _ptr(hv), _ptr(hv_scale), _ptr(hv_zero),
+                                      _ptr(k_pos), _ptr(seq_lens), _ptr(Bk), _ptr(Bv), _ptr(rope_table),
+                                      int(rope_table_len), _ptr(out), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream(stream)),
+           "palu_attn_decode_multi")
+    return out

@@ -38,7 +38,8 @@ int device_cu_count() {
 }
 
 // ---- descriptor validation -------------------------------------------------
-int check_desc(const palu_layer_desc* d, Meta* m) {
+// nq: queries per sequence of the call; the kernels then see q_per_kv * nq heads per key/value head
+int check_desc(const palu_layer_desc* d, Meta* m, int nq = 1) {
   if (!d || !d->group_head_off || !d->k_rank_off || !d->v_rank_off) return PALU_ERR_INVALID_ARG;
   if (d->n_heads <= 0 || d->n_groups <= 0 || d->d_head <= 0) return PALU_ERR_INVALID_ARG;
   if (d->act_dtype != PALU_F16 && d->act_dtype != PALU_BF16) return PALU_ERR_INVALID_ARG;
@@ -56,7 +57,8 @@ int check_desc(const palu_layer_desc* d, Meta* m) {
   }
   if (d->group_head_off[d->n_groups] != d->n_heads) return PALU_ERR_INVALID_ARG;
   if (d->q_per_kv < 0) return PALU_ERR_INVALID_ARG;
-  const int qpk = d->q_per_kv > 0 ? d->q_per_kv : 1;
+  if (nq < 1 || nq > PALU_MAX_HEADS) return PALU_ERR_INVALID_ARG;
+  const int qpk = (d->q_per_kv > 0 ? d->q_per_kv : 1) * nq;
   const bool any_i4 = d->k_latent_dtype == PALU_I4 || d->v_latent_dtype == PALU_I4;
   if (any_i4) {
     if (d->quant_block <= 0) return PALU_ERR_INVALID_ARG;
@@ -81,6 +83,7 @@ int check_desc(const palu_layer_desc* d, Meta* m) {
     m->n_heads = d->n_heads * qpk;
     m->n_groups = d->n_groups;
     m->qpk = qpk;
+    m->nq = nq;
     int bk = 0, bv = 0;
     for (int j = 0; j <= d->n_groups; ++j) {
       m->head_off[j] = d->group_head_off[j] * qpk;
@@ -355,8 +358,8 @@ int carve(const Meta& m, int batch, int max_seq, int n_split_cap, int n_parts, W
   w->ml_part = off; off = align_up(off + (size_t)batch * n_split_cap * m.n_heads * 2 * 4);
   w->rope_rows = off; off = align_up(off + (size_t)w->lpad * PALU_D_HEAD * 2);   // cos/sin rows gathered by k_pos
   w->qsum = off; off = align_up(off + (size_t)batch * m.n_heads * (PALU_MAX_RANK / 128 + 2) * 4);   // int4 block sums of the folded queries (no-RoPE path)
-  // grouped-query attention: rotated queries as contraction operands, 2 feature halves x 2 passes x 1 KiB per key/value head
-  w->qfrag = off; off = align_up(off + (m.qpk > 1 ? (size_t)batch * (m.n_heads / m.qpk) * 4 * 1024 : 0));
+  // several queries per key/value head: rotated queries as contraction operands, 2 feature halves x 4 KiB per key/value head
+  w->qfrag = off; off = align_up(off + (m.qpk > 1 ? (size_t)batch * (m.n_heads / m.qpk) * 2 * 4096 : 0));
   w->total = off;
   return PALU_OK;
 }
@@ -412,18 +415,17 @@ ScoreFn score_fn(int act, bool i4, int cls_id, bool w8) {
   return act == PALU_F16 ? score_fn_t<F16, false>(rc, lg, w8) : score_fn_t<BF16, false>(rc, lg, w8);
 }
 
-// shared-key form (grouped-query attention): fp16 latents, ranks up to 256, 8 wavefronts, `passes` x 4 query heads
-template <int QP>
+// shared-key form (several queries per key/value head): fp16 latents, ranks up to 256, 8 wavefronts, up to 16 queries
 ScoreFn score_fn_shared(int rc) {
   switch (rc) {
-    case 0: return score_kernel<F16, 2, 2, 1, 8, false, QP>;
-    case 1: return score_kernel<F16, 4, 2, 1, 8, false, QP>;
-    case 2: return score_kernel<F16, 6, 2, 1, 8, false, QP>;
-    case 3: return score_kernel<F16, 8, 2, 1, 8, false, QP>;
-    case 4: return score_kernel<F16, 10, 2, 1, 8, false, QP>;
-    case 5: return score_kernel<F16, 12, 2, 1, 8, false, QP>;
-    case 6: return score_kernel<F16, 14, 2, 1, 8, false, QP>;
-    default: return score_kernel<F16, 16, 2, 1, 8, false, QP>;
+    case 0: return score_kernel<F16, 2, 2, 1, 8, false, 1>;
+    case 1: return score_kernel<F16, 4, 2, 1, 8, false, 1>;
+    case 2: return score_kernel<F16, 6, 2, 1, 8, false, 1>;
+    case 3: return score_kernel<F16, 8, 2, 1, 8, false, 1>;
+    case 4: return score_kernel<F16, 10, 2, 1, 8, false, 1>;
+    case 5: return score_kernel<F16, 12, 2, 1, 8, false, 1>;
+    case 6: return score_kernel<F16, 14, 2, 1, 8, false, 1>;
+    default: return score_kernel<F16, 16, 2, 1, 8, false, 1>;
   }
 }
 
@@ -434,6 +436,7 @@ Meta kv_head_meta(const Meta& m) {
   k.n_heads = m.n_heads / m.qpk;
   k.n_groups = m.n_groups;
   k.qpk = 1;
+  k.nq = 1;
   for (int j = 0; j <= m.n_groups; ++j) {
     k.head_off[j] = m.head_off[j] / m.qpk;
     k.k_off[j] = m.k_off[j];
@@ -707,9 +710,9 @@ int palu_quant_latent(const palu_layer_desc* desc, int which, const void* latent
 }
 
 // ------------------------------------------------------------------ decode
-int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch, int32_t max_seq, size_t* out_bytes) {
+static int decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch, int32_t n_q, int32_t max_seq, size_t* out_bytes) {
   Meta m;
-  int st = check_desc(desc, &m);
+  int st = check_desc(desc, &m, n_q);
   if (st != PALU_OK) return st;
   if (!out_bytes || batch <= 0 || max_seq <= 0) return PALU_ERR_INVALID_ARG;
   ScorePlan sp;
@@ -722,8 +725,19 @@ int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch,
   return PALU_OK;
 }
 
-// out: attention output after B_v; out_latent: output left in the value latent space (then Bv is not read)
-static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch, int32_t max_seq, size_t* out_bytes) {
+  return decode_workspace_bytes(desc, batch, 1, max_seq, out_bytes);
+}
+
+int palu_attn_decode_multi_workspace_bytes(const palu_layer_desc* desc, int32_t batch, int32_t n_q, int32_t max_seq,
+                                           size_t* out_bytes) {
+  return decode_workspace_bytes(desc, batch, n_q, max_seq, out_bytes);
+}
+
+// out: attention output after B_v; out_latent: output left in the value latent space (then Bv is not read).
+// n_q queries per sequence (q_pos has batch * n_q entries); q_len: rows attended per query, or NULL (all of the sequence's).
+static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, const int32_t* q_len,
+                       int32_t seq_len, int32_t max_seq,
                        const void* q, const int32_t* q_pos,
                        const void* hk, const void* hk_scale, const void* hk_zero,
                        const void* hv, const void* hv_scale, const void* hv_zero,
@@ -733,8 +747,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
                        float* out, float* out_latent, void* workspace, size_t workspace_bytes, void* stream,
                        void* const* stage_events) {
   Meta m;
-  int st = check_desc(desc, &m);
+  int st = check_desc(desc, &m, n_q);
   if (st != PALU_OK) return st;
+  if (n_q > 1 && out_latent) return PALU_ERR_UNSUPPORTED;
   if (batch <= 0 || seq_len <= 0 || max_seq < seq_len) return PALU_ERR_INVALID_ARG;
   if (batch > 65535) return PALU_ERR_UNSUPPORTED;      // the batch index is a grid dimension
   if (!q || !q_pos || !hk || !hv || !Bk || !rope_table || !workspace) return PALU_ERR_INVALID_ARG;
@@ -859,16 +874,15 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
       if ((st = flush()) != PALU_OK) return st;
     }
   } else {
-    // Grouped-query attention with fp16 latents and ranks up to 256: the score kernel rebuilds each
-    // key once for the query heads that share it (shared-key form).  Other grouped-query layers
-    // run the folded form with one folded matrix per query head.
-    bool shared_key = m.qpk >= 2 && m.qpk <= 8 && act == PALU_F16 && !k_i4 && waves8;
+    // 2 .. 16 queries per key/value head (grouped-query heads times queries per sequence) with fp16
+    // latents and ranks up to 256: the score kernel rebuilds each key once for the queries that
+    // share it (shared-key form).  Otherwise the folded form runs with one folded matrix per query.
+    bool shared_key = m.qpk >= 2 && m.qpk <= 16 && act == PALU_F16 && !k_i4 && waves8;
     for (int j = 0; j < m.n_groups && shared_key; ++j) shared_key = m.k_off[j + 1] - m.k_off[j] <= 256;
     const Meta mk = shared_key ? kv_head_meta(m) : m;
     static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)
     if (shared_key && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
     const ScorePlan& plan = shared_key ? spk : sp;
-    const int passes = ceil_div(m.qpk, 4);
 
     // 1. fold the rotated query into B_k (shared-key form: B_k alone, and the rotated queries beside it)
     {
@@ -904,7 +918,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
         std::memcpy(qa.rev_lo, a.rev_lo, sizeof(qa.rev_lo));
         qa.n_kv = mk.n_heads;
         qa.qpk = m.qpk;
-        qa.passes = passes;
+        qa.nq = m.nq;
+        qa.n_heads = m.n_heads;
         hipLaunchKernelGGL(qfrag_kernel<F16>, dim3((unsigned)mk.n_heads, (unsigned)batch), dim3(256), 0, s, qa);
         if ((st = launch_ok()) != PALU_OK) return st;
       }
@@ -964,9 +979,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
         const int rc = id / 3, lg = id % 3;
         const int width = (32 * (rc + 1)) << lg;
         const bool dma = act == PALU_F16 && !k_i4;
-        const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width) + (shared_key ? score_qf_bytes(passes) : 0);
-        ScoreFn fn = !shared_key ? score_fn(act, k_i4, id, waves8)
-                                 : (passes == 1 ? score_fn_shared<1>(rc) : score_fn_shared<2>(rc));
+        const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width) + (shared_key ? score_qf_bytes() : 0);
+        ScoreFn fn = !shared_key ? score_fn(act, k_i4, id, waves8) : score_fn_shared(rc);
         if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
         const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
         auto flush = [&]() -> int {
@@ -1016,6 +1030,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t seq_l
     a.hv_zero = static_cast<const uint16_t*>(hv_zero);
     a.scores = reinterpret_cast<const float*>(ws + w.scores);
     a.seq_lens = seq_lens;
+    a.q_len = q_len;
     a.o_part = reinterpret_cast<float*>(ws + w.o_part);
     a.ml_part = reinterpret_cast<float*>(ws + w.ml_part);
     a.row_elems = Rv;
@@ -1080,7 +1095,7 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
                      const void* Bk, const void* Bv,
                      const void* rope_table, int32_t rope_table_len,
                      float* out, void* workspace, size_t workspace_bytes, void* stream) {
-  return decode_impl(desc, batch, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
+  return decode_impl(desc, batch, 1, nullptr, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
                      seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream, nullptr);
 }
 
@@ -1093,7 +1108,7 @@ int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t 
                             const void* rope_table, int32_t rope_table_len,
                             float* out, void* workspace, size_t workspace_bytes, void* stream,
                             void* const* stage_events) {
-  return decode_impl(desc, batch, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
+  return decode_impl(desc, batch, 1, nullptr, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
                      seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream,
                      stage_events);
 }
@@ -1107,9 +1122,22 @@ int palu_attn_decode_latent(const palu_layer_desc* desc, int32_t batch, int32_t 
                             const void* rope_table, int32_t rope_table_len,
                             float* out_latent, void* workspace, size_t workspace_bytes, void* stream) {
   if (!out_latent) return PALU_ERR_INVALID_ARG;
-  return decode_impl(desc, batch, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
+  return decode_impl(desc, batch, 1, nullptr, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
                      seq_lens, Bk, nullptr, rope_table, rope_table_len, nullptr, out_latent, workspace, workspace_bytes,
                      stream, nullptr);
+}
+
+int palu_attn_decode_multi(const palu_layer_desc* desc, int32_t batch, int32_t n_q, int32_t seq_len, int32_t max_seq,
+                           const void* q, const int32_t* q_pos, const int32_t* q_len,
+                           const void* hk, const void* hk_scale, const void* hk_zero,
+                           const void* hv, const void* hv_scale, const void* hv_zero,
+                           const int32_t* k_pos, const int32_t* seq_lens,
+                           const void* Bk, const void* Bv,
+                           const void* rope_table, int32_t rope_table_len,
+                           float* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_impl(desc, batch, n_q, q_len, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero,
+                     k_pos, seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream,
+                     nullptr);
 }
 
 }  // extern "C"

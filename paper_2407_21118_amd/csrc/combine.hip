@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
     float s = 0.f;
 #pragma unroll
     for (int g = 0; g < 32; ++g) s += part[(g * 8 + c4) * 4 + e];
-    a.out[((size_t)b * m.n_heads + h) * kDHead + quarter * 32 + tid] = s / sum[0];
+    a.out[q_row(m, b, h) * kDHead + quarter * 32 + tid] = s / sum[0];
   }
 }
 

@@ -29,7 +29,9 @@ constexpr int kTile = 32;                  // tokens per MFMA tile (N of the 32x
 struct Meta {
   int n_heads;
   int n_groups;
-  int qpk;
+  int qpk;                   // heads per key/value head: the model's query heads per key/value head times nq
+  int nq;                    // queries per sequence in this call (1 for plain decode); see q_row
+
   int head_off[PALU_MAX_GROUPS + 1];
   int k_off[PALU_MAX_GROUPS + 1];
   int v_off[PALU_MAX_GROUPS + 1];
@@ -136,15 +138,17 @@ struct RopeGatherArgs {
   int table_len;
 };
 
-// Rotated queries of grouped-query attention as A operands of v_mfma_f32_4x4x4_16B_f16.
+// Rotated queries of the shared-key score form as A operands of its query contractions.
 struct QfragArgs {
   const uint16_t* q;         // [batch, n_kv * qpk, 128]
   const int32_t* q_pos;
-  uint16_t* qfrag;           // [batch][n_kv][2 feature halves][passes][16 steps][8 lane classes] 8-byte entries
+  uint16_t* qfrag;           // [batch][n_kv][2 feature halves][8 steps][2 lane halves][16 queries] 16-byte entries
   float theta;
   float rev_hi[kHalf];
   float rev_lo[kHalf];
-  int n_kv, qpk, passes;
+  int n_kv, qpk;
+  int nq;                    // queries per sequence; q_pos has batch * nq entries
+  int n_heads;               // n_kv * qpk
 };
 
 struct FoldArgs {
@@ -185,6 +189,21 @@ __device__ __forceinline__ int weight_block(const Meta& m, int j, int h, int off
   }
   *width = s_q / m.qpk * kDHead;
   return off / m.qpk + (h - m.head_off[j]) / m.qpk * kDHead;
+}
+
+// With nq > 1 queries per sequence, head h of the kernels is (key/value head, query j, model
+// head of that key/value head): h = kv * qpk + j * (qpk / nq) + qh, so that all rows
+// that share a key/value head are adjacent.  The caller's q and out are laid out
+// [batch, nq, model query heads, 128]: q_row gives the row of head h there, q_token the query j.
+__device__ __forceinline__ int q_token(const Meta& m, int h) {
+  return m.nq == 1 ? 0 : (h % m.qpk) / (m.qpk / m.nq);
+}
+__device__ __forceinline__ size_t q_row(const Meta& m, int b, int h) {
+  if (m.nq == 1) return (size_t)b * m.n_heads + h;
+  const int per = m.qpk / m.nq;                     // model query heads per key/value head
+  const int kv = h / m.qpk, x = h - kv * m.qpk;
+  const int j = x / per, qh = x - j * per;
+  return ((size_t)b * m.nq + j) * (m.n_heads / m.nq) + kv * per + qh;
 }
 
 // Per-head offset of its value-latent accumulator inside an o_part row:

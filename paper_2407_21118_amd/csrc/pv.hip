@@ -46,6 +46,7 @@ struct PvArgs {
   const uint16_t* hv_zero;
   const float* scores;       // [parts][batch][n_heads][lpad]; planes 0 and 1 are read
   const int32_t* seq_lens;
+  const int32_t* q_len;      // several queries per sequence: rows attended by query j of sequence b at [b * nq + j]; or NULL
   float* o_part;             // [batch][n_split][o_stride]
   float* ml_part;            // [batch][n_split][n_heads][2]
   long long row_elems;       // R_v
@@ -164,11 +165,13 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
 
   const float* sc_ptr[HS];
   bool two[HS];
+  int lim[HS];                                     // tokens of this split the head's query attends (its own row limit)
 #pragma unroll
   for (int i = 0; i < HS; ++i) {
     const int h = h0 + min(hp + 2 * i, nh - 1);
     sc_ptr[i] = a.scores + ((size_t)b * m.n_heads + h) * a.lpad + s0;
     two[i] = a.n_parts[h] > 1;
+    lim[i] = a.q_len ? a.q_len[b * m.nq + q_token(m, h)] - s0 : 0x7fffffff;
   }
   const size_t sz_idx0 = I4 ? row0 * a.n_blocks_q + (c0 >> 7) : 0;
   const int n_blk = (u.ncols + 127) >> 7;          // 128-column blocks the unit really has
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
 #pragma unroll
     for (int i = 0; i < HS; ++i) {
       const float v = st.sc[i][0] + (two[i] ? st.sc[i][1] : 0.f);
-      s[i] = (tok_ok && hp + 2 * i < nh) ? v : -INFINITY;
+      s[i] = (tok_ok && hp + 2 * i < nh && k * 32 + tl < lim[i]) ? v : -INFINITY;
       bm[i] = half_wave_max(s[i]);
       grew |= bm[i] > mx[i];
     }

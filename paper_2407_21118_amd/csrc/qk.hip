@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
   uint4v qw[4][8];
 #pragma unroll
   for (int bb = 0; bb < 4; ++bb) {
-    const uint16_t* qp = a.q + ((size_t)min(b0 + bb, a.batch - 1) * m.n_heads + h) * kDHead + fh;
+    const uint16_t* qp = a.q + q_row(m, min(b0 + bb, a.batch - 1), h) * kDHead + fh;
 #pragma unroll
     for (int x = 0; x < 8; ++x) qw[bb][x] = *reinterpret_cast<const uint4v*>(qp + 8 * x);
   }

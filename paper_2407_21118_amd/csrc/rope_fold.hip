@@ -67,12 +67,12 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
     // rotate the query: angle = pos * w_f with w_f / 2pi given as a float pair
     // (hi, lo) from the host's float64 value, so that the angle in revolutions
     // keeps ~1e-7 absolute accuracy for positions up to 2^24
-    const uint16_t* qp = a.q + ((size_t)b * m.n_heads + h) * kDHead;
+    const uint16_t* qp = a.q + q_row(m, b, h) * kDHead;
     const float x0 = T::to_float(qp[tid]);
     const float x1 = T::to_float(qp[tid + kHalf]);
     float c = 1.f, s = 0.f;
     if (a.theta > 0.f) {
-      const float pos = (float)a.q_pos[b];
+      const float pos = (float)a.q_pos[b * m.nq + q_token(m, h)];
       const float p = pos * a.rev_hi[tid];
       const float e = fmaf(pos, a.rev_hi[tid], -p);
       const float rev = (p - floorf(p)) + (e + pos * a.rev_lo[tid]);
@@ -109,26 +109,30 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
   *reinterpret_cast<uint4v*>(out + ((size_t)ks * 256 + tid) * 8) = pk;
 }
 
-// Grouped-query attention, shared-key form of the score kernel: the rotated queries
-// q' = RoPE(q, q_pos) of the query heads of one key/value head, as A operands of the
-// 4x4x4 contractions, 8 bytes per (step, lane class = 4 (lane / 32) + lane % 4: lane half
-// and head).  Contraction step n of a lane half `hi` covers the accumulators
-// e = 2n, 2n+1 (e = 16 rt + i: rotation pair f = 32 rt + mfma_row(i, hi)) as the four
-// values K cos_f (both accumulators), then K sin_f (both); the matching query entries
-// are q'_f and q'_{f+64} for the wavefronts that hold K_f, and q'_{f+64} and -q'_f for
-// those that hold K_{f+64}.
+// Shared-key form of the score kernel: the rotated queries q' = RoPE(q, position of
+// the query) of the (up to 16) queries of one key/value head, as A operands of its 8
+// query contractions (v_mfma_f32_32x32x16: row = query, k-octet = lane half).  Step N
+// of lane half `hi` covers the accumulators e = 4N .. 4N+3 (e = 16 rt + i: rotation
+// pair f = 32 rt + mfma_row(i, hi)) as K cos_f and K sin_f in the order (cos e, cos
+// e+1, sin e, sin e+1, cos e+2, cos e+3, sin e+2, sin e+3); the matching query
+// entries are q'_f for cos and q'_{f+64} for sin where the wavefront holds K_f, and
+// q'_{f+64} and -q'_f where it holds K_{f+64}.  Rows of absent queries are zero.
+// Layout [batch][kv head][feature half][step 8][lane half 2][query 16] x 16 bytes.
 // grid (key/value heads, batch), 256 threads.
 template <typename T>
 __global__ __launch_bounds__(256) void qfrag_kernel(QfragArgs a) {
-  __shared__ float qr[8][kDHead];
+  __shared__ float qr[16][kDHead];
   const int kvh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  Meta m;                                             // only the fields q_row and q_token read
+  m.n_heads = a.n_heads; m.qpk = a.qpk; m.nq = a.nq;
   for (int h0 = 0; h0 < a.qpk; h0 += 4) {
     const int hq = h0 + (tid >> 6), f = tid & 63;
     if (hq >= a.qpk) continue;
-    const uint16_t* qp = a.q + (((size_t)b * a.n_kv + kvh) * a.qpk + hq) * kDHead;
+    const int h = kvh * a.qpk + hq;
+    const uint16_t* qp = a.q + q_row(m, b, h) * kDHead;
     const float x0 = T::to_float(qp[f]);
     const float x1 = T::to_float(qp[f + kHalf]);
-    const float pos = (float)a.q_pos[b];
+    const float pos = (float)a.q_pos[b * a.nq + q_token(m, h)];
     const float p = pos * a.rev_hi[f];
     const float e = fmaf(pos, a.rev_hi[f], -p);
     const float rev = (p - floorf(p)) + (e + pos * a.rev_lo[f]);      // angle in revolutions, as in fold_kernel
@@ -137,28 +141,28 @@ __global__ __launch_bounds__(256) void qfrag_kernel(QfragArgs a) {
     qr[hq][f + kHalf] = x1 * c + x0 * s;
   }
   __syncthreads();
-  // one item = (feature half, pass, step n, lane class): 8 bytes
-  uint2v* out = reinterpret_cast<uint2v*>(a.qfrag) + ((size_t)b * a.n_kv + kvh) * 2 * a.passes * 128;
-  for (int item = tid; item < 2 * a.passes * 128; item += 256) {
-    const int cls = item & 7, n = (item >> 3) & 15;
-    const int p = (item >> 7) % a.passes, half = (item >> 7) / a.passes;
-    const int hq = 4 * p + (cls & 3), hi = cls >> 2;
-    uint16_t v[4];
+  uint4v* out = reinterpret_cast<uint4v*>(a.qfrag) + ((size_t)b * a.n_kv + kvh) * 512;
+  for (int item = tid; item < 512; item += 256) {
+    const int row = item & 15, hi = (item >> 4) & 1, N = (item >> 5) & 7, half = item >> 8;
+    uint16_t v[8];
 #pragma unroll
-    for (int y = 0; y < 2; ++y) {
-      const int e = 2 * n + y;
+    for (int y = 0; y < 4; ++y) {
+      const int e = 4 * N + y;
       const int f = 32 * (e >> 4) + mfma_row(e & 15, hi);
       float qc = 0.f, qs = 0.f;
-      if (hq < a.qpk) {
-        qc = half ? qr[hq][f + kHalf] : qr[hq][f];
-        qs = half ? -qr[hq][f] : qr[hq][f + kHalf];
+      if (row < a.qpk) {
+        qc = half ? qr[row][f + kHalf] : qr[row][f];
+        qs = half ? -qr[row][f] : qr[row][f + kHalf];
       }
-      v[y] = F16::from_float(qc);            // entry order of a step: cos parts of its two accumulators, then sin parts
-      v[2 + y] = F16::from_float(qs);
+      // accumulators e = 4N + y: y = 0, 1 fill entries (0, 1) with cos parts and (2, 3) with sin parts; y = 2, 3 entries 4 .. 7
+      v[4 * (y >> 1) + (y & 1)] = F16::from_float(qc);
+      v[4 * (y >> 1) + 2 + (y & 1)] = F16::from_float(qs);
     }
-    uint2v pk;
+    uint4v pk;
     pk.x = v[0] | ((uint32_t)v[1] << 16);
     pk.y = v[2] | ((uint32_t)v[3] << 16);
+    pk.z = v[4] | ((uint32_t)v[5] << 16);
+    pk.w = v[6] | ((uint32_t)v[7] << 16);
     out[item] = pk;
   }
 }

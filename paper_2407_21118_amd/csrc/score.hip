@@ -53,7 +53,7 @@ constexpr int kLdsBudget = 160 * 1024 - 1024;    // LDS of one CU, less a little
 
 // LDS bytes per buffered tile and number of buffers, shared with the host for the launch
 constexpr int score_buf_bytes(int width) { return kTile * (width * 2 + kRowPad) + kRopeTileB; }
-constexpr int score_qf_bytes(int passes) { return 8 * passes * 1024; }      // shared-key form: query operands of 8 wavefronts
+constexpr int score_qf_bytes() { return 8 * 4096; }      // shared-key form: query operands of 8 wavefronts
 constexpr int score_num_bufs(int width, bool dma) {
   return !dma ? 2 : (4 * score_buf_bytes(width) <= kLdsBudget ? 4 : 3);
 }
@@ -74,16 +74,19 @@ constexpr int score_num_bufs(int width, bool dma) {
 //       wavefronts 0-3 own the cos halves, 4-7 the sin halves.
 // I4:   latents are packed 4-bit codes with per-(token, block) scale and zero
 // QP:   0: one query per key/value head, folded into the weights as described above.
-//       1, 2: grouped-query attention with up to 4 QP query heads per key/value head.
+//       1: shared-key form, for up to 16 queries per key/value head (the query heads
+//       of grouped-query attention, several query tokens per sequence, or both).
 //       The stationary operand is B_k itself (transposed), so the accumulators are the
-//       key K[feature][token], rebuilt once for all query heads that share it.  With
-//       q' the rotated query, the score is the contraction over f < 64 of
+//       key K[feature][token], rebuilt once for all queries that share it.  With q' a
+//       rotated query, its score is the contraction over f < 64 of
 //         K_f (cos_f q'_f + sin_f q'_{f+64})  +  K_{f+64} (cos_f q'_{f+64} - sin_f q'_f):
 //       a wavefront owns one half of the features (K_f or K_{f+64}), scales its
-//       accumulators by the position's cos and sin, rounds the products to fp16 and
-//       contracts them with its query heads on v_mfma_f32_4x4x4_16B_f16 (16 blocks of
-//       4 heads x 4 tokens: a lane feeds its own token's values and collects that
-//       token's four scores; the two lane halves of a token are then added).
+//       accumulators by the position's cos and sin (packed fp16), and contracts the
+//       128 products per token with the queries in 8 further 32x32x16 MFMAs whose B
+//       operand is what the lane already holds (its token, its 8 values per step) and
+//       whose A operand (queries x the same values' query entries, written by
+//       qfrag_kernel) sits in 4 KiB of LDS per wavefront.  Rows of the result are
+//       queries; the two lane halves' features are summed by the contraction itself.
 template <typename T, int NKS, int RT, int G, int NW, bool I4, int QP = 0>
 __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -304,6 +307,19 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 
   // ---- the first latent tiles go out before the (larger) weight fetch so that
   // their HBM latency overlaps it
+  if constexpr (QP > 0) {
+    // shared-key form: this wavefront's query operands (4 KiB) go first, straight into LDS.  Being the oldest
+    // requests of the wavefront they have landed whenever one of the counted waits below has been passed.
+    const int hq = u.h0 + ((wave & 3) < u.nh ? (wave & 3) : 0);
+    const unsigned char* src = uniform_ptr(reinterpret_cast<const unsigned char*>(a.qfrag) +
+                                           (((size_t)b * a.n_kv + hq) * 2 + (wave >> 2)) * 4096);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)(kBufs * kBufB) + (unsigned)(wave * 4096 + x * 1024));
+      const unsigned voff = (unsigned)lane * 16u + (unsigned)x * 1024u;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(src) : "memory");
+    }
+  }
   if (kDma) {
 #pragma unroll
     for (int x = 0; x < kAheadTiles; ++x) dma_issue(x);
@@ -342,15 +358,11 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 
   // ---- stationary operand: folded weights of (b, head), rows [32*rt0, 32*(rt0+RT))
   half8 W[NKS][RT];
-  // shared-key form: A operands of the 16 query contractions per pass, 8 bytes per (step, lane class):
-  // lanes with the same head (lane % 4) and lane half use the same entries (written by qfrag_kernel).
-  // 1 KiB per pass and wavefront; fetched with the weights and parked in LDS behind the tile buffers
-  // by the wavefront's first epilogue (by then the weight fetch it was queued behind has been consumed).
-  constexpr int kQfWords = QP > 0 ? QP : 1;
-  uint4v qf[kQfWords];
-  bool qf_pending = QP > 0;
-  unsigned char* qf_lds = lds + (size_t)kBufs * kBufB + (size_t)wave * (kQfWords * 1024);
-  const int qf_cls = ((lane >> 5) * 4 + (lane & 3)) * 8;
+  // shared-key form: the query operands of this wavefront's key/value head and feature half,
+  // [8 steps][2 lane halves][16 queries] x 16 bytes, behind the tile buffers
+  constexpr int kQfBytes = 4096;
+  const unsigned qf_off = (unsigned)(kBufs * kBufB) + (unsigned)wave * kQfBytes;
+  const unsigned char* qf_lds = lds + qf_off + (lane_hi * 16 + (lane_lo & 15)) * 16;      // + 512 per step
   auto load_weights = [&]() __attribute__((always_inline)) {
     const uint16_t* mf = a.mfold + (size_t)b * a.mfold_bstride + u.bk_off0 +
                          ((size_t)g_rel * u.s + u_in_g) * u.head_stride;
@@ -359,12 +371,6 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
         W[ks][rt] = *reinterpret_cast<const half8*>(mf + ((size_t)(ks * 4 + rt0 + rt) * 64 + lane) * 8);
-    if constexpr (QP > 0) {
-      const uint4v* src = reinterpret_cast<const uint4v*>(a.qfrag) +
-                          ((((size_t)b * a.n_kv + hc) * 2 + (rt0 >> 1)) * kQfWords) * 64 + lane;
-#pragma unroll
-      for (int x = 0; x < kQfWords; ++x) qf[x] = src[x * 64];
-    }
   };
   // Ping-pong with LDS-direct loads: the wavefronts that run the first MFMA phase fetch their
   // weights now; the others only after the first barrier, so that the barrier does not wait
@@ -434,45 +440,35 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     if constexpr (QP > 0) {
       typedef _Float16 half2f __attribute__((ext_vector_type(2)));
       typedef float float2f __attribute__((ext_vector_type(2)));
-      // Step n = 8 rt + ip of the contraction takes (K cos)(2ip), (K cos)(2ip+1), (K sin)(2ip), (K sin)(2ip+1):
-      // the two accumulators rounded to fp16, then packed fp16 products with the position's cos and sin.
-      // Each step's products go straight into its 4x4x4 contractions (two independent chains per pass),
-      // so the vector work fills the waits for the matrix pipe, which the partner wavefront is using.
-      if (qf_pending) {
+      // Step N of the contraction takes the accumulators e = 4N .. 4N+3 (e = 16 rt + i), rounded to fp16 and
+      // multiplied by the position's cos and sin as packed fp16, in the order
+      // (K cos)(e), (K cos)(e+1), (K sin)(e), (K sin)(e+1), then the same for e+2, e+3.
+      float16v sc;
 #pragma unroll
-        for (int x = 0; x < kQfWords; ++x) *reinterpret_cast<uint4v*>(qf_lds + x * 1024 + lane * 16) = qf[x];
-        qf_pending = false;
-      }
-      float4v sc[QP][2];
+      for (int i = 0; i < 16; ++i) sc[i] = 0.f;
 #pragma unroll
-      for (int p = 0; p < QP; ++p) sc[p][0] = sc[p][1] = float4v{0.f, 0.f, 0.f, 0.f};
+      for (int N = 0; N < 4 * RT; ++N) {
+        uint4v bw;
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int ip = 0; ip < 8; ++ip) {
-          const int n = 8 * rt + ip;
+        for (int y = 0; y < 2; ++y) {
+          const int e = 4 * N + 2 * y, rt = e >> 4, ip = (e & 15) >> 1;
           const float2f kf = {r.acc[rt][2 * ip], r.acc[rt][2 * ip + 1]};
           const half2f kk = __builtin_convertvector(kf, half2f);
           const uint4v cw = __builtin_bit_cast(uint4v, r.cs[rt][ip >> 2]), sw = __builtin_bit_cast(uint4v, r.sn[rt][ip >> 2]);
           const uint32_t cb = cw[ip & 3], sb = sw[ip & 3];
           const half2f pc = kk * __builtin_bit_cast(half2f, cb), ps = kk * __builtin_bit_cast(half2f, sb);
-          const uint2v bq = {__builtin_bit_cast(uint32_t, pc), __builtin_bit_cast(uint32_t, ps)};
-#pragma unroll
-          for (int p = 0; p < QP; ++p) {
-            const uint2v aq = *reinterpret_cast<const uint2v*>(qf_lds + (p * 16 + n) * 64 + qf_cls);
-            sc[p][n & 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4, aq), __builtin_bit_cast(half4, bq),
-                                                               sc[p][n & 1], 0, 0, 0);
-          }
+          bw[2 * y] = __builtin_bit_cast(uint32_t, pc);
+          bw[2 * y + 1] = __builtin_bit_cast(uint32_t, ps);
         }
+        const half8 aq = *reinterpret_cast<const half8*>(qf_lds + N * 512);
+        sc = F16::mfma(aq, __builtin_bit_cast(half8, bw), sc);
+      }
+      // sc[i]: query 8 (i / 4) + 4 lane_hi + i % 4 of this lane's token, i < 8 (queries 16.. are not kept)
+      float* row = out_row + t0 + lane_lo;
 #pragma unroll
-      for (int p = 0; p < QP; ++p) {
-        // entry i: head 4p + i, this lane's token, this lane half's features.  Each lane half stores two of the heads.
-        const float s0 = sum_across_halves(sc[p][0][0] + sc[p][1][0]), s1 = sum_across_halves(sc[p][0][1] + sc[p][1][1]);
-        const float s2 = sum_across_halves(sc[p][0][2] + sc[p][1][2]), s3 = sum_across_halves(sc[p][0][3] + sc[p][1][3]);
-        const int hq = 4 * p + 2 * lane_hi;
-        float* row = out_row + (size_t)hq * a.lpad + t0 + lane_lo;
-        if (hq < a.qpk) row[0] = (lane_hi ? s2 : s0) * a.scale;
-        if (hq + 1 < a.qpk) row[a.lpad] = (lane_hi ? s3 : s1) * a.scale;
+      for (int i = 0; i < 8; ++i) {
+        const int qi = 8 * (i >> 2) + 4 * lane_hi + (i & 3);
+        if (qi < a.qpk) row[(size_t)qi * a.lpad] = sc[i] * a.scale;
       }
       return;
     }
@@ -497,7 +493,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     // tiles 0 .. kAheadTiles-1 are in flight; tile 0 must have landed before the first MFMA phase.
     // Where the weight loads were issued after them, those stay outstanding as well: the first
     // phase begins with the first k-steps' weights (the compiler waits per k-step from there on).
-    constexpr int kStartWait = kInFlight * kDmaOps + NKS * RT + QP;
+    constexpr int kStartWait = kInFlight * kDmaOps + NKS * RT;
     static_assert(!kSplitStart || kStartWait <= 63, "start-up wait exceeds the counter");
     if (kSplitStart && wave < 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kStartWait <= 63 ? kStartWait : 0));
     else dma_wait(std::integral_constant<int, kInFlight>{});

@@ -214,9 +214,8 @@ def test_grouped_query_attention(qpk, theta, dtype):
     """Grouped-query attention (the Llama-3 / Mistral models of Sec. 4.1): the latents and
     B matrices cover the key/value heads, q_per_kv query heads share each of them.  Groups
     of unequal size and rank, ragged lengths, with and without RoPE.  With fp16 latents,
-    RoPE and up to 8 query heads per key/value head the score kernel rebuilds each key once
-    for the heads that share it (one or two passes of four heads); the other cases (bf16,
-    12 heads) run one folded matrix per query head."""
+    RoPE and up to 16 query heads per key/value head the score kernel rebuilds each key once
+    for the heads that share it; the other cases (bf16) run one folded matrix per query head."""
     n_kv = 8 if qpk <= 4 else 4
     sizes = [4, 2, 1, 1] if n_kv == 8 else [2, 1, 1]
     head_off = [0] + list(np.cumsum(sizes))
@@ -267,3 +266,52 @@ def test_parallel_queries_share_the_cache():
         whole, rows = rel_err(got[:, j::n_q], one.astype(np.float64))
         say(f"         query {j}: against its own single-query call {whole:.3e}")
         assert whole <= TOL_FP and rows <= TOL_FP
+
+
+@pytest.mark.parametrize("n_q,qpk,theta,i4", [(4, 1, 10000.0, False), (2, 4, 500000.0, False), (5, 2, 10000.0, False),
+                                              (3, 1, 0.0, False), (4, 1, 10000.0, True), (16, 1, 10000.0, False), (24, 1, 10000.0, False)])
+def test_several_queries_per_sequence(n_q, qpk, theta, i4):
+    """palu_attn_decode_multi: a causal block of n_q new tokens per sequence (rows appended
+    first; query j attends len - n_q + j + 1 rows at its own position), multi-head and
+    grouped-query layers, with and without RoPE, fp16 and 4-bit latents.  The oracle runs
+    every query as its own decode step."""
+    import paper_2407_21118_amd as P
+    from gpu_util import make_desc, to_dev
+    sizes = [4, 2, 2] if qpk == 1 else [2, 1, 1]
+    head_off = [0] + list(np.cumsum(sizes))
+    kr = [256, 128, 128]
+    vr = [128, 256, 128] if qpk == 1 else [128, 128, 128]      # a rank cannot exceed the group's width
+    layer = synth.Layer(int(head_off[-1]), 128, head_off, [0] + list(np.cumsum(kr)), [0] + list(np.cumsum(vr)),
+                        rope_theta=theta, q_per_kv=qpk)
+    B, L = 2, 300
+    case = synth.make_case_orthonormal(layer, B, L, seed=500 + n_q)
+    rng = np.random.default_rng([9, n_q, qpk])
+    q = synth.round_to(rng.standard_normal((B, n_q, layer.n_q_heads, 128)), "f16")
+    lens = np.array([L, 157], np.int32)
+    q_len = (lens[:, None] - n_q + np.arange(n_q)[None, :] + 1).astype(np.int32)
+    q_pos = (q_len - 1 + 7).astype(np.int32)
+    say(f"[multi] n_q={n_q} q_per_kv={qpk} theta={theta} int4={i4} groups={sizes}")
+    desc = make_desc(layer, "f16", i4, i4)
+    kw, Hk_ref, Hv_ref = {}, case.Hk, case.Hv
+    if i4:
+        (pk, sk, zk), (pv, sv, zv) = O.quant_latent(case.Hk), O.quant_latent(case.Hv)
+        hk, hv = torch.from_numpy(pk).cuda(), torch.from_numpy(pv).cuda()
+        for name, arr in (("hk_scale", sk), ("hk_zero", zk), ("hv_scale", sv), ("hv_zero", zv)):
+            kw[name] = torch.from_numpy(arr.view(np.int16)).cuda().view(torch.float16)
+        Hk_ref, Hv_ref = O.dequant_latent(pk, sk, zk), O.dequant_latent(pv, sv, zv)
+    else:
+        hk, hv = to_dev(case.Hk, "f16"), to_dev(case.Hv, "f16")
+    n_pos = int(q_pos.max()) + 1
+    table = P.palu_rope_table_init(theta, 128, max(n_pos, L))
+    out = P.palu_attn_decode_multi(desc, B, n_q, L, L, to_dev(q, "f16"), torch.from_numpy(q_pos).cuda(), hk, hv,
+                                   to_dev(case.Bk, "f16"), to_dev(case.Bv, "f16"), table, max(n_pos, L),
+                                   q_len=torch.from_numpy(q_len).cuda(), seq_lens=torch.from_numpy(lens).cuda(), **kw)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    ref = O.attn_decode_multi(q, q_pos, q_len, Hk_ref, Hv_ref, case.Bk, case.Bv, layer.group_head_off, layer.k_rank_off,
+                              layer.v_rank_off, 128, theta, None, qpk)
+    assert np.isfinite(got).all()
+    whole, rows = rel_err(got.reshape(B, -1, 128), ref.reshape(B, -1, 128))
+    say(f"        rel err whole={whole:.3e} worst row={rows:.3e}")
+    tol = TOL_I4 if i4 else TOL_FP
+    assert whole <= tol and rows <= tol

@@ -259,6 +259,32 @@ def test_grouped_query_reduces_to_one_query_per_kv_head(qpk):
     assert at == lat.shape[1]
 
 
+def test_several_queries_are_independent_decode_steps():
+    """attn_decode_multi against a hand-rolled causal block: with the new tokens' rows
+    appended, query j must equal textbook softmax attention over rows [0, L - n_q + j]
+    of the rebuilt K and V (a dropped '+ 1' in the row count or a shared position fails)."""
+    p = small_problem(seed=12, L=9)
+    n_q, L, d = 3, p["L"], p["d"]
+    rng = np.random.default_rng(120)
+    q = rng.standard_normal((p["B"], n_q, p["n"], d))
+    q_len = np.array([[L - n_q + j + 1 for j in range(n_q)]] * p["B"])
+    q_pos = q_len - 1
+    got = O.attn_decode_multi(q, q_pos, q_len, p["Hk"], p["Hv"], p["Bk_flat"], p["Bv_flat"], p["gho"], p["kro"],
+                              p["vro"], d, 10000.0)
+    for b in range(p["B"]):
+        K = O.reconstruct(p["Hk"][b], p["Bk_flat"], p["gho"], p["kro"], d).reshape(L, p["n"], d)
+        V = O.reconstruct(p["Hv"][b], p["Bv_flat"], p["gho"], p["vro"], d).reshape(L, p["n"], d)
+        Kr = O.rope_rotate(K, np.arange(L)[:, None], 10000.0)
+        for j in range(n_q):
+            n_rows = L - n_q + j + 1
+            for i in range(p["n"]):
+                qr = O.rope_rotate(q[b, j, i][None], np.array([n_rows - 1]), 10000.0)[0]
+                sc = Kr[:n_rows, i] @ qr / math.sqrt(d)
+                w = np.exp(sc - sc.max())
+                want = (w / w.sum()) @ V[:n_rows, i]
+                np.testing.assert_allclose(got[b, j, i], want, rtol=1e-10, atol=1e-12)
+
+
 def test_zero_positions_equal_fused_qk_form():
     """With every position 0 RoPE is the identity and the score must equal
     (q B_k^T) H_k^T / sqrt(d_h) (Eq. 5)."""
