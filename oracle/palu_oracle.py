@@ -85,23 +85,68 @@ def pack_int4(codes: np.ndarray) -> np.ndarray:
     return (codes[..., 0::2] | (codes[..., 1::2] << 4)).astype(np.uint8)
 
 
-def dequant_latent(packed, scale, zero, block: int = 128) -> np.ndarray:
-    """Dequantize packed int4 latents to float64.
+def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
+    """Storage format of B-bit codes (Sec. 4.4 quantizes the latents to 4, 3 and 2 bits;
+    the byte layouts are this build's):
+      4 bits: byte k holds channel 2k in its low nibble, channel 2k+1 in its high nibble;
+      2 bits: byte k holds channels 4k .. 4k+3, channel 4k+u in bits 2u, 2u+1;
+      3 bits: the low two bits of every code in the 2-bit layout (R/4 bytes), followed by
+              the third bits, byte k holding channels 8k .. 8k+7, channel 8k+u in bit u
+              (R/8 bytes): 3R/8 bytes per row."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    R = codes.shape[-1]
+    assert codes.max(initial=0) < (1 << bits)
+    if bits == 4:
+        return pack_int4(codes)
+    assert R % 8 == 0
+    lo = codes & 3
+    low_plane = (lo[..., 0::4] | (lo[..., 1::4] << 2) | (lo[..., 2::4] << 4) | (lo[..., 3::4] << 6)).astype(np.uint8)
+    if bits == 2:
+        return low_plane
+    assert bits == 3
+    hi = (codes >> 2) & 1
+    high_plane = np.zeros(codes.shape[:-1] + (R // 8,), dtype=np.uint8)
+    for u in range(8):
+        high_plane |= (hi[..., u::8] << u).astype(np.uint8)
+    return np.concatenate([low_plane, high_plane], axis=-1)
 
-    packed [..., R/2] uint8, scale/zero [..., R/block] (float16 values).
+
+def unpack_codes(packed: np.ndarray, bits: int) -> np.ndarray:
+    """Inverse of pack_codes: [..., R*bits/8] uint8 -> [..., R] uint8 codes."""
+    packed = np.asarray(packed, dtype=np.uint8)
+    if bits == 4:
+        return unpack_int4(packed)
+    nb = packed.shape[-1]
+    R = nb * 4 if bits == 2 else nb * 8 // 3
+    low = packed[..., :R // 4]
+    out = np.empty(packed.shape[:-1] + (R,), dtype=np.uint8)
+    for u in range(4):
+        out[..., u::4] = (low >> (2 * u)) & 3
+    if bits == 3:
+        high = packed[..., R // 4:]
+        for u in range(8):
+            out[..., u::8] |= (((high >> u) & 1) << 2).astype(np.uint8)
+    return out
+
+
+def dequant_latent(packed, scale, zero, block: int = 128, bits: int = 4) -> np.ndarray:
+    """Dequantize packed B-bit latents to float64.
+
+    packed [..., R*bits/8] uint8 (pack_codes), scale/zero [..., R/block] (float16 values).
     h[c] = (code[c] - zero[c // block]) * scale[c // block], evaluated in
     float64 from the stored float16 scale and zero-point (Appendix A read
     backwards; the benchmark configuration fixes one (scale, zero) per token
     per `block` channels).
     """
-    codes = unpack_int4(packed).astype(np.float64)
+    codes = unpack_codes(packed, bits).astype(np.float64)
     s = np.repeat(np.asarray(scale, dtype=np.float64), block, axis=-1)
     z = np.repeat(np.asarray(zero, dtype=np.float64), block, axis=-1)
     return (codes - z) * s
 
 
-def quant_latent(h: np.ndarray, block: int = 128):
-    """Asymmetric uniform 4-bit quantization of latents (Appendix A).
+def quant_latent(h: np.ndarray, block: int = 128, bits: int = 4):
+    """Asymmetric uniform B-bit quantization of latents (Appendix A; B = 4 below, and
+    the 3- and 2-bit settings of Sec. 4.4 with 15 replaced by 2^B - 1).
 
     h [..., R] with values exactly representable in float16/bfloat16 (they are
     converted to float32 exactly).  Per (row, block of `block` channels):
@@ -124,7 +169,8 @@ def quant_latent(h: np.ndarray, block: int = 128):
     hb = h32.reshape(h32.shape[:-1] + (R // block, block))
     mn = hb.min(axis=-1)
     mx = hb.max(axis=-1)
-    s32 = (mx - mn) / np.float32(15.0)
+    top = np.float32((1 << bits) - 1)
+    s32 = (mx - mn) / top
     s16 = s32.astype(np.float16)
     s16 = np.where(s16 == 0, np.float16(1.0), s16).astype(np.float16)
     sf = s16.astype(np.float32)
@@ -133,9 +179,9 @@ def quant_latent(h: np.ndarray, block: int = 128):
     z16 = z.astype(np.float16)
     zf = z16.astype(np.float32)
     q = np.rint(hb / sf[..., None]) + zf[..., None]
-    q = np.clip(q, np.float32(0.0), np.float32(15.0))
+    q = np.clip(q, np.float32(0.0), top)
     codes = q.astype(np.uint8).reshape(h32.shape)
-    return pack_int4(codes), s16, z16
+    return pack_codes(codes, bits), s16, z16
 
 
 # --------------------------------------------------------------------------

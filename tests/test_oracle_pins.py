@@ -452,6 +452,47 @@ def test_quantizer_hand_examples():
     np.testing.assert_array_equal(z6[0], [0.0, 4.0])
 
 
+@pytest.mark.parametrize("bits", [2, 3])
+def test_low_bit_formats_and_quantizer(bits):
+    """2- and 3-bit latents (Sec. 4.4): byte layouts spelled out by hand, round trip over random
+    codes, hand examples of Appendix A with 2^B - 1 levels, and the half-step error bound."""
+    top = (1 << bits) - 1
+    # layout, by hand: channels 0..7 = 1, 2, 3, 0, 3, 3, 0, 1 (2 bits) / 5, 2, 7, 0, 3, 6, 4, 1 (3 bits)
+    if bits == 2:
+        c = np.array([[1, 2, 3, 0, 3, 3, 0, 1]], np.uint8)
+        want = [1 | 2 << 2 | 3 << 4 | 0 << 6, 3 | 3 << 2 | 0 << 4 | 1 << 6]
+    else:
+        c = np.array([[5, 2, 7, 0, 3, 6, 4, 1]], np.uint8)
+        low = [1 | 2 << 2 | 3 << 4 | 0 << 6, 3 | 2 << 2 | 0 << 4 | 1 << 6]
+        high = [1 << 0 | 0 << 1 | 1 << 2 | 0 << 3 | 0 << 4 | 1 << 5 | 1 << 6 | 0 << 7]
+        want = low + high
+    np.testing.assert_array_equal(O.pack_codes(c, bits)[0], np.array(want, np.uint8))
+    rng = np.random.default_rng(bits)
+    codes = rng.integers(0, top + 1, size=(5, 256)).astype(np.uint8)
+    packed = O.pack_codes(codes, bits)
+    assert packed.shape == (5, 256 * bits // 8)
+    np.testing.assert_array_equal(O.unpack_codes(packed, bits), codes)
+    # values 0..top repeated: s = 1, z = 0, codes = values; shifted and scaled: same codes
+    x = np.tile(np.arange(top + 1, dtype=np.float32), 128 // (top + 1))[None, :]
+    pk, sc, zp = O.quant_latent(x, bits=bits)
+    assert float(sc[0, 0]) == 1.0 and float(zp[0, 0]) == 0.0
+    np.testing.assert_array_equal(O.unpack_codes(pk, bits)[0], x[0].astype(np.uint8))
+    x2 = (x - 1.0) * 0.25
+    pk2, sc2, zp2 = O.quant_latent(x2, bits=bits)
+    assert float(sc2[0, 0]) == 0.25 and float(zp2[0, 0]) == 1.0
+    np.testing.assert_array_equal(pk2, pk)
+    np.testing.assert_array_equal(O.dequant_latent(pk2, sc2, zp2, bits=bits), x2.astype(np.float64))
+    # random rows: every code within range, error at most half a step (plus the fp16 rounding of s and z)
+    h = (rng.standard_normal((20, 256)) * rng.uniform(0.1, 10, size=(20, 1))).astype(np.float16).astype(np.float32)
+    pk3, sc3, zp3 = O.quant_latent(h, bits=bits)
+    assert O.unpack_codes(pk3, bits).max() <= top
+    err = np.abs(O.dequant_latent(pk3, sc3, zp3, bits=bits) - h)
+    step = np.repeat(sc3.astype(np.float64), 128, axis=-1)
+    assert (err <= 0.51 * step + 1e-3 * np.abs(h).max()).all()
+    # 4 bits through the same entry points is the int4 format
+    np.testing.assert_array_equal(O.pack_codes(codes & 3, 4), O.pack_int4(codes & 3))
+
+
 def test_quantizer_properties_random():
     rng = np.random.default_rng(11)
     x = (rng.standard_normal((64, 512)) * rng.uniform(0.01, 30, size=(64, 1))).astype(np.float16).astype(np.float32)
