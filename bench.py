@@ -37,7 +37,7 @@ def log(msg: str) -> None:
     print(msg, file=sys.stderr, flush=True)
 
 
-def algorithmic_work(layer, batch, seq, k_i4, v_i4):
+def algorithmic_work(layer, batch, seq, k_i4, v_i4, bits=4):
     """FLOPs and HBM bytes the method itself needs per decode step."""
     T = batch * seq
     d_h = layer.d_head
@@ -49,7 +49,7 @@ def algorithmic_work(layer, batch, seq, k_i4, v_i4):
         pv += 2 * T * (layer.v_rank_off[j + 1] - layer.v_rank_off[j]) * s * layer.q_per_kv
 
     def side_bytes(R, i4):
-        return T * (R // 2 + (R // layer.quant_block) * 4) if i4 else T * R * 2
+        return T * (R * bits // 8 + (R // layer.quant_block) * 4) if i4 else T * R * 2
 
     return {
         "score_flops": recon,                               # H_k . B_k reconstruction (the q.K product adds < 1 %)
@@ -72,6 +72,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ring-gib", type=float, default=1.0, help="distinct latent bytes to cycle through")
     ap.add_argument("--opt", action="append", default=[], help="tuning knob name=value (palu_set_option)")
+    ap.add_argument("--latent-bits", type=int, default=4, choices=(4, 3, 2),
+                    help="config 4 / 4v: bits per quantized latent code (3 and 2: the low-bit settings of the paper's Sec. 4.4)")
     ap.add_argument("--no-probes", action="store_true", help="skip the bare MFMA / read probes (measured_peaks)")
     ap.add_argument("--no-rope", action="store_true",
                     help="the paper's non-RoPE attention (rope_theta = 0): the query is folded into the latent "
@@ -113,7 +115,8 @@ def main() -> int:
         import dataclasses
         layer = dataclasses.replace(layer, rope_theta=0.0)
     batch, seq = synth.FULL_SIZES[base_cfg]
-    work = algorithmic_work(layer, batch, seq, k_i4, v_i4)
+    bits = args.latent_bits
+    work = algorithmic_work(layer, batch, seq, k_i4, v_i4, bits)
     set_bytes = batch * seq * (layer.R_k + layer.R_v) * 2
     free_b = torch.cuda.mem_get_info()[0]
     n_sets = max(1, min(int(np.ceil(args.ring_gib * 2 ** 30 / set_bytes)) + 1, int(0.5 * free_b / set_bytes)))
@@ -122,8 +125,9 @@ def main() -> int:
         f"{n_sets} cache sets of {set_bytes / 2**20:.0f} MiB built in {time.time() - t0:.1f}s")
 
     act = P.PALU_F16
+    qdt = {4: P.PALU_I4, 3: P.PALU_I3, 2: P.PALU_I2}[bits]
     desc = P.LayerDesc(layer.n_heads, layer.d_head, layer.group_head_off, layer.k_rank_off, layer.v_rank_off, act,
-                       P.PALU_I4 if k_i4 else act, P.PALU_I4 if v_i4 else act, layer.quant_block, layer.rope_theta,
+                       qdt if k_i4 else act, qdt if v_i4 else act, layer.quant_block, layer.rope_theta,
                        layer.q_per_kv)
     table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, seq)
     ws = torch.empty(P.palu_attn_decode_workspace_bytes(desc, batch, seq), dtype=torch.uint8, device="cuda")
@@ -139,7 +143,7 @@ def main() -> int:
             for side, flag, H, R, nb, store in ((0, k_i4, case.Hk, layer.R_k, nbk, qk), (1, v_i4, case.Hv, layer.R_v, nbv, qv)):
                 if not flag:
                     continue
-                codes = torch.empty((batch, seq, R // 2), dtype=torch.uint8, device="cuda")
+                codes = torch.empty((batch, seq, R * bits // 8), dtype=torch.uint8, device="cuda")
                 sc = torch.empty((batch, seq, nb), dtype=torch.float16, device="cuda")
                 zp = torch.empty_like(sc)
                 P.palu_quant_latent(desc, side, H[s], R, batch * seq, codes, sc, zp)
@@ -234,7 +238,7 @@ def main() -> int:
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16" if not (k_i4 or v_i4) else ("i4+f16" if k_i4 else "f16 keys, i4 values"),
+        "dtype": "f16" if not (k_i4 or v_i4) else (f"i{bits}+f16" if k_i4 else f"f16 keys, i{bits} values"),
         "data": "synthetic",
         "config": {"workload": f"config {cfg}{' without RoPE' if args.no_rope else ''}: Llama-2-7B-shaped layer decode, batch {batch}, seq {seq}, "
                                f"{layer.n_groups} groups, R_k {layer.R_k}, R_v {layer.R_v}",

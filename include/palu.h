@@ -40,7 +40,8 @@ enum {
   PALU_ERR_HIP = -4                 /* a HIP runtime call failed (launch, attribute query) */
 };
 
-enum { PALU_F16 = 0, PALU_BF16 = 1, PALU_I4 = 2 };
+/* PALU_I4, PALU_I3, PALU_I2: latents quantized to 4, 3 or 2 bits (Appendix A; Sec. 4.4) */
+enum { PALU_F16 = 0, PALU_BF16 = 1, PALU_I4 = 2, PALU_I3 = 3, PALU_I2 = 4 };
 
 /* Limits of this build. */
 enum {
@@ -80,8 +81,8 @@ typedef struct palu_layer_desc {
   const int32_t* k_rank_off;       /* HOST [n_groups+1] */
   const int32_t* v_rank_off;       /* HOST [n_groups+1] */
   int32_t act_dtype;               /* PALU_F16 | PALU_BF16: q, x, A, B_k, B_v, unquantized latents */
-  int32_t k_latent_dtype;          /* act_dtype or PALU_I4 */
-  int32_t v_latent_dtype;          /* act_dtype or PALU_I4 */
+  int32_t k_latent_dtype;          /* act_dtype, PALU_I4, PALU_I3 or PALU_I2 */
+  int32_t v_latent_dtype;          /* act_dtype, PALU_I4, PALU_I3 or PALU_I2 */
   int32_t quant_block;             /* channels per (scale, zero) pair; 128 */
   float rope_theta;                /* RoPE base, e.g. 10000; <= 0: no rotation */
   int32_t q_per_kv;                /* grouped-query attention: query heads per key/value head; 0 or 1 = multi-head */
@@ -165,13 +166,18 @@ int palu_encode_kv(const palu_layer_desc* desc, const void* x, int32_t n_tok, co
                    const int32_t* dst_row, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Asymmetric uniform 4-bit quantization of latent rows (Appendix A with B = 4),
- * one (scale, zero) pair per token per quant_block channels:
- *     s = fp16((max - min) / 15), s == 0 -> 1;   z = fp16(clamp(rint(-min / s), +-65504));
- *     code = clamp(rint(x / s) + z, 0, 15)        (float32 arithmetic, ties to even)
+ * Asymmetric uniform B-bit quantization of latent rows (Appendix A), one (scale, zero)
+ * pair per token per quant_block channels; B = 4, 3 or 2 as the side's latent dtype
+ * says (PALU_I4 / PALU_I3 / PALU_I2; 4 where the side is not declared quantized):
+ *     s = fp16((max - min) / (2^B - 1)), s == 0 -> 1;   z = fp16(clamp(rint(-min / s), +-65504));
+ *     code = clamp(rint(x / s) + z, 0, 2^B - 1)         (float32 arithmetic, ties to even)
  *   latent      DEVICE act_dtype, token t at latent + t*row_stride_elems, R elements
- *   codes       DEVICE uint8 rows of R/2 bytes; byte c/2 holds channel c (c even) in its
- *               low nibble and channel c+1 in its high nibble
+ *   codes       DEVICE uint8 rows of R*B/8 bytes.  4 bits: byte c/2 holds channel c (c even)
+ *               in its low nibble and channel c+1 in its high nibble.  2 bits: byte k holds
+ *               channels 4k .. 4k+3, channel 4k+u in bits 2u, 2u+1.  3 bits: the low two bits
+ *               of every code in the 2-bit layout (R/4 bytes), then the third bits, byte k
+ *               holding channels 8k .. 8k+7, channel 8k+u in bit u (R/8 bytes).  The same
+ *               layouts are what palu_attn_decode reads.
  *   scale,zero  DEVICE float16 rows of R/quant_block
  *   dst_row     DEVICE int32 [n_tok]: token t is written to row dst_row[t] of codes,
  *               scale and zero (appending to several sequences of a cache at once),
@@ -215,9 +221,9 @@ int palu_encode_quant(const palu_layer_desc* desc, int which, const void* x, int
  *   q          DEVICE [batch, n_heads, d_head] act_dtype, before RoPE (Sec. 4.5.2)
  *   q_pos      DEVICE int32 [batch] position of each query token
  *   hk, hv     DEVICE latents [batch, max_seq, R] act_dtype, or packed codes
- *              [batch, max_seq, R/2] uint8 when the side is PALU_I4; sequence b
- *              starts at b*max_seq rows
- *   h*_scale, h*_zero   DEVICE float16 [batch, max_seq, R/quant_block] (PALU_I4 side), else NULL
+ *              [batch, max_seq, R*B/8] uint8 when the side is PALU_I4 / I3 / I2 (layouts
+ *              under palu_quant_latent); sequence b starts at b*max_seq rows
+ *   h*_scale, h*_zero   DEVICE float16 [batch, max_seq, R/quant_block] (quantized side), else NULL
  *   k_pos      DEVICE int32 [max_seq] position of cached row t, or NULL (row t is position t).
  *              Positions must lie in [0, rope_table_len); the kernels clamp to that
  *              range to stay in bounds, results for out-of-range positions are undefined

@@ -12,7 +12,7 @@ import ctypes
 import os
 from typing import Optional, Sequence
 
-PALU_F16, PALU_BF16, PALU_I4 = 0, 1, 2
+PALU_F16, PALU_BF16, PALU_I4, PALU_I3, PALU_I2 = 0, 1, 2, 3, 4
 PALU_DECODE_STAGES = 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -37,6 +37,9 @@ int device_cu_count() {
   return v;
 }
 
+// bits per code of a quantized latent dtype, 0 for fp16 / bf16 latents
+inline int latent_bits(int dtype) { return dtype == PALU_I4 ? 4 : (dtype == PALU_I3 ? 3 : (dtype == PALU_I2 ? 2 : 0)); }
+
 // ---- descriptor validation -------------------------------------------------
 // nq: queries per sequence of the call; the kernels then see q_per_kv * nq heads per key/value head
 int check_desc(const palu_layer_desc* d, Meta* m, int nq = 1) {
@@ -45,7 +48,7 @@ int check_desc(const palu_layer_desc* d, Meta* m, int nq = 1) {
   if (d->act_dtype != PALU_F16 && d->act_dtype != PALU_BF16) return PALU_ERR_INVALID_ARG;
   for (int side = 0; side < 2; ++side) {
     const int ld = side ? d->v_latent_dtype : d->k_latent_dtype;
-    if (ld != d->act_dtype && ld != PALU_I4) return PALU_ERR_INVALID_ARG;
+    if (ld != d->act_dtype && latent_bits(ld) == 0) return PALU_ERR_INVALID_ARG;
   }
   if (d->group_head_off[0] != 0 || d->k_rank_off[0] != 0 || d->v_rank_off[0] != 0) return PALU_ERR_INVALID_ARG;
   for (int j = 0; j < d->n_groups; ++j) {
@@ -59,11 +62,11 @@ int check_desc(const palu_layer_desc* d, Meta* m, int nq = 1) {
   if (d->q_per_kv < 0) return PALU_ERR_INVALID_ARG;
   if (nq < 1 || nq > PALU_MAX_HEADS) return PALU_ERR_INVALID_ARG;
   const int qpk = (d->q_per_kv > 0 ? d->q_per_kv : 1) * nq;
-  const bool any_i4 = d->k_latent_dtype == PALU_I4 || d->v_latent_dtype == PALU_I4;
+  const bool any_i4 = latent_bits(d->k_latent_dtype) != 0 || latent_bits(d->v_latent_dtype) != 0;
   if (any_i4) {
     if (d->quant_block <= 0) return PALU_ERR_INVALID_ARG;
     for (int side = 0; side < 2; ++side) {
-      if ((side ? d->v_latent_dtype : d->k_latent_dtype) != PALU_I4) continue;
+      if (latent_bits(side ? d->v_latent_dtype : d->k_latent_dtype) == 0) continue;
       const int32_t* off = side ? d->v_rank_off : d->k_rank_off;
       for (int j = 0; j <= d->n_groups; ++j)
         if (off[j] % d->quant_block != 0) return PALU_ERR_INVALID_ARG;
@@ -318,7 +321,7 @@ int plan_qk(const Meta& m, QkPlan* p) {
 }
 
 // Wavefronts per compute unit the value kernel's splits aim at.
-inline int value_waves_per_cu(const palu_layer_desc* d) { return d->v_latent_dtype == PALU_I4 ? 8 : 4; }
+inline int value_waves_per_cu(const palu_layer_desc* d) { return latent_bits(d->v_latent_dtype) ? 8 : 4; }
 
 // Tokens per value split and number of splits for a given attended length: a
 // split is one wavefront's share; aim at four wavefronts per compute unit,
@@ -415,6 +418,33 @@ ScoreFn score_fn(int act, bool i4, int cls_id, bool w8) {
   return act == PALU_F16 ? score_fn_t<F16, false>(rc, lg, w8) : score_fn_t<BF16, false>(rc, lg, w8);
 }
 
+// 3- and 2-bit key latents: one group per workgroup, 8 wavefronts up to rank 256, 4 half-head wavefronts above
+template <int NKS>
+ScoreFn score_fn_lowbit_n() {
+  if constexpr (NKS > 16) return score_kernel<F16, NKS, 2, 1, 4, true, 0, true>;
+  else return score_kernel<F16, NKS, 2, 1, 8, true, 0, true>;
+}
+ScoreFn score_fn_lowbit(int rc) {
+  switch (rc) {
+    case 0: return score_fn_lowbit_n<2>();
+    case 1: return score_fn_lowbit_n<4>();
+    case 2: return score_fn_lowbit_n<6>();
+    case 3: return score_fn_lowbit_n<8>();
+    case 4: return score_fn_lowbit_n<10>();
+    case 5: return score_fn_lowbit_n<12>();
+    case 6: return score_fn_lowbit_n<14>();
+    case 7: return score_fn_lowbit_n<16>();
+    case 8: return score_fn_lowbit_n<18>();
+    case 9: return score_fn_lowbit_n<20>();
+    case 10: return score_fn_lowbit_n<22>();
+    case 11: return score_fn_lowbit_n<24>();
+    case 12: return score_fn_lowbit_n<26>();
+    case 13: return score_fn_lowbit_n<28>();
+    case 14: return score_fn_lowbit_n<30>();
+    default: return score_fn_lowbit_n<32>();
+  }
+}
+
 // shared-key form (several queries per key/value head): fp16 latents, ranks up to 256, 8 wavefronts, up to 16 queries
 ScoreFn score_fn_shared(int rc) {
   switch (rc) {
@@ -450,19 +480,22 @@ Meta kv_head_meta(const Meta& m) {
 }
 
 using PvFn = void (*)(PvArgs);
-template <typename T, bool I4>
+template <typename T, int QB>
 PvFn pv_fn_t(int cls) {
   switch (cls) {
-    case 0: return pv_kernel<T, 2, 1, I4>;
-    case 1: return pv_kernel<T, 2, 2, I4>;
-    case 2: return pv_kernel<T, 8, 1, I4>;
-    case 3: return pv_kernel<T, 8, 2, I4>;
-    default: return pv_kernel<T, 16, 1, I4>;
+    case 0: return pv_kernel<T, 2, 1, QB>;
+    case 1: return pv_kernel<T, 2, 2, QB>;
+    case 2: return pv_kernel<T, 8, 1, QB>;
+    case 3: return pv_kernel<T, 8, 2, QB>;
+    default: return pv_kernel<T, 16, 1, QB>;
   }
 }
-PvFn pv_fn(int act, bool i4, int cls) {
-  if (i4) return pv_fn_t<F16, true>(cls);
-  return act == PALU_F16 ? pv_fn_t<F16, false>(cls) : pv_fn_t<BF16, false>(cls);
+// bits: 4, 3 or 2 for quantized value latents, else 0
+PvFn pv_fn(int act, int bits, int cls) {
+  if (bits == 4) return pv_fn_t<F16, 4>(cls);
+  if (bits == 3) return pv_fn_t<F16, 3>(cls);
+  if (bits == 2) return pv_fn_t<F16, 2>(cls);
+  return act == PALU_F16 ? pv_fn_t<F16, 0>(cls) : pv_fn_t<BF16, 0>(cls);
 }
 
 inline int launch_ok() { return hipGetLastError() == hipSuccess ? PALU_OK : PALU_ERR_HIP; }
@@ -649,6 +682,8 @@ int palu_encode_quant(const palu_layer_desc* desc, int which, const void* x, int
   if (desc->quant_block != 128) return PALU_ERR_UNSUPPORTED;
   const int R = which ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
   if (R % 128 != 0) return PALU_ERR_INVALID_ARG;
+  const int side_bits = latent_bits(which ? desc->v_latent_dtype : desc->k_latent_dtype);
+  if (side_bits != 0 && side_bits != 4) return PALU_ERR_UNSUPPORTED;      // the fused write-out packs 4-bit codes only
   if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(A) & 15) ||
       (reinterpret_cast<uintptr_t>(codes) & 15) || (reinterpret_cast<uintptr_t>(scale) & 1) ||
       (reinterpret_cast<uintptr_t>(zero) & 1))
@@ -701,6 +736,8 @@ int palu_quant_latent(const palu_layer_desc* desc, int which, const void* latent
   a.n_tok = n_tok;
   a.R = R;
   a.n_blocks = R / 128;
+  a.bits = latent_bits(which ? desc->v_latent_dtype : desc->k_latent_dtype);
+  if (a.bits == 0) a.bits = 4;
   const long long items = (long long)n_tok * a.n_blocks;
   const dim3 g((unsigned)((items + 3) / 4));
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -717,7 +754,8 @@ static int decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch, in
   if (!out_bytes || batch <= 0 || max_seq <= 0) return PALU_ERR_INVALID_ARG;
   ScorePlan sp;
   PvPlan pp;
-  if ((st = plan_score(m, &sp)) != PALU_OK) return st;
+  const int kb = latent_bits(desc->k_latent_dtype);
+  if ((st = plan_score(m, &sp, !(kb == 2 || kb == 3))) != PALU_OK) return st;
   if ((st = plan_pv(m, &pp)) != PALU_OK) return st;
   Workspace w;
   carve(m, batch, max_seq, split_bound(pp.total_units, batch, max_seq, value_waves_per_cu(desc)), 2 * sp.max_slices, &w);
@@ -754,7 +792,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   if (batch > 65535) return PALU_ERR_UNSUPPORTED;      // the batch index is a grid dimension
   if (!q || !q_pos || !hk || !hv || !Bk || !rope_table || !workspace) return PALU_ERR_INVALID_ARG;
   if (out_latent ? (out != nullptr) : (!out || !Bv)) return PALU_ERR_INVALID_ARG;
-  const bool k_i4 = desc->k_latent_dtype == PALU_I4, v_i4 = desc->v_latent_dtype == PALU_I4;
+  const int k_bits = latent_bits(desc->k_latent_dtype), v_bits = latent_bits(desc->v_latent_dtype);
+  const bool k_i4 = k_bits != 0, v_i4 = v_bits != 0;          // quantized sides (4, 3 or 2 bits)
   if (k_i4 && (!hk_scale || !hk_zero)) return PALU_ERR_INVALID_ARG;
   if (v_i4 && (!hv_scale || !hv_zero)) return PALU_ERR_INVALID_ARG;
   if (rope_table_len <= 0 || (!k_pos && rope_table_len < seq_len)) return PALU_ERR_INVALID_ARG;
@@ -765,7 +804,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
 
   ScorePlan sp;
   PvPlan pp;
-  if ((st = plan_score(m, &sp)) != PALU_OK) return st;
+  const bool k_lowbit = k_bits == 2 || k_bits == 3;        // their score kernels take one group per workgroup
+  if ((st = plan_score(m, &sp, !k_lowbit)) != PALU_OK) return st;
   if ((st = plan_pv(m, &pp)) != PALU_OK) return st;
   const int quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
   int split_tokens, n_split;
@@ -780,7 +820,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   const int act = desc->act_dtype;
-  const bool waves8 = g_opt_score_waves != 4;
+  const bool waves8 = g_opt_score_waves != 4 || k_lowbit;
   auto mark = [&](int i) -> int {
     if (!stage_events) return PALU_OK;
     return hipEventRecord(static_cast<hipEvent_t>(stage_events[i]), s) == hipSuccess ? PALU_OK : PALU_ERR_HIP;
@@ -852,9 +892,11 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     if ((st = mark(1)) != PALU_OK) return st;
     for (int cls = 0; cls < 2; ++cls) {              // 0: up to 16 heads per unit, 1: up to 32
       using QkFn = void (*)(QkArgs);
-      QkFn fn = k_i4 ? (cls ? qk_kernel<F16, 2, true> : qk_kernel<F16, 1, true>)
-                     : act == PALU_F16 ? (cls ? qk_kernel<F16, 2, false> : qk_kernel<F16, 1, false>)
-                                       : (cls ? qk_kernel<BF16, 2, false> : qk_kernel<BF16, 1, false>);
+      QkFn fn = k_bits == 4 ? (cls ? qk_kernel<F16, 2, 4> : qk_kernel<F16, 1, 4>)
+              : k_bits == 3 ? (cls ? qk_kernel<F16, 2, 3> : qk_kernel<F16, 1, 3>)
+              : k_bits == 2 ? (cls ? qk_kernel<F16, 2, 2> : qk_kernel<F16, 1, 2>)
+              : act == PALU_F16 ? (cls ? qk_kernel<F16, 2, 0> : qk_kernel<F16, 1, 0>)
+                                : (cls ? qk_kernel<BF16, 2, 0> : qk_kernel<BF16, 1, 0>);
       const size_t lds = qp.max_lds[cls];
       if (lds == 0) continue;
       if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
@@ -944,6 +986,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       a.n_heads = m.n_heads;
       a.quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
       a.n_blocks_q = Rk / a.quant_block;
+      a.bits = k_bits;
       a.scale = 1.4426950408889634f / std::sqrt((float)PALU_D_HEAD);
       a.qfrag = reinterpret_cast<const uint16_t*>(ws + w.qfrag);
       a.qpk = m.qpk;
@@ -980,7 +1023,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         const int width = (32 * (rc + 1)) << lg;
         const bool dma = act == PALU_F16 && !k_i4;
         const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width) + (shared_key ? score_qf_bytes() : 0);
-        ScoreFn fn = !shared_key ? score_fn(act, k_i4, id, waves8) : score_fn_shared(rc);
+        ScoreFn fn = shared_key ? score_fn_shared(rc) : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, id, waves8));
         if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
         const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
         auto flush = [&]() -> int {
@@ -1049,7 +1092,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       auto flush = [&]() -> int {
         if (a.units.n_units == 0) return PALU_OK;
         const dim3 grid((unsigned)a.units.n_units, (unsigned)ceil_div(n_split, 4), (unsigned)batch);
-        hipLaunchKernelGGL(pv_fn(act, v_i4, cls), grid, dim3(256), 0, s, a);
+        hipLaunchKernelGGL(pv_fn(act, v_bits, cls), grid, dim3(256), 0, s, a);
         a.units.n_units = 0;
         return launch_ok();
       };

@@ -142,12 +142,14 @@ __global__ __launch_bounds__(256) void encode_finish_kernel(EncodeArgs a) {
 // Every arithmetic step is a single IEEE float32 operation so the integer codes are
 // reproducible bit for bit; scale and zero are stored as fp16 and used as stored.
 struct QuantParams {
-  float sf, zf;
+  float sf, zf, top;
   uint16_t s16, z16;
 };
-__device__ __forceinline__ QuantParams quant_params(float mn, float mx) {
+// top = 2^B - 1: 15 for the 4-bit cache, 7 and 3 for the 3- and 2-bit settings of Sec. 4.4
+__device__ __forceinline__ QuantParams quant_params(float mn, float mx, float top = 15.0f) {
   QuantParams p;
-  const float s32 = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
+  p.top = top;
+  const float s32 = __fdiv_rn(__fsub_rn(mx, mn), top);
   p.s16 = F16::from_float(s32);
   if ((p.s16 & 0x7fffu) == 0) p.s16 = 0x3c00u;                  // s == 0 -> 1
   p.sf = F16::to_float(p.s16);
@@ -158,7 +160,7 @@ __device__ __forceinline__ QuantParams quant_params(float mn, float mx) {
   return p;
 }
 __device__ __forceinline__ uint32_t quant_code(float x, const QuantParams& p) {
-  return (uint32_t)fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x, p.sf)), p.zf), 0.0f), 15.0f);
+  return (uint32_t)fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x, p.sf)), p.zf), 0.0f), p.top);
 }
 
 // ---- many tokens at once (filling the cache from a prompt): a tiled GEMM on the matrix
@@ -336,6 +338,7 @@ struct QuantArgs {
   const int32_t* dst_row;     // output row of token t (NULL: t)
   long long row_stride;
   int n_tok, R, n_blocks;     // n_blocks = R / 128
+  int bits;                   // 4, 3 or 2
 };
 
 // One wavefront per (token, 128-channel block); lane l owns channels 2l, 2l+1.
@@ -354,9 +357,25 @@ __global__ __launch_bounds__(256) void quant_kernel(QuantArgs a) {
     mn = fminf(mn, __shfl_xor(mn, off, 64));
     mx = fmaxf(mx, __shfl_xor(mx, off, 64));
   }
-  const QuantParams qp = quant_params(mn, mx);
+  const QuantParams qp = quant_params(mn, mx, (float)((1 << a.bits) - 1));
   const size_t orow = a.dst_row ? (size_t)a.dst_row[t] : (size_t)t;
-  a.codes[orow * (a.R / 2) + blk * 64 + lane] = (uint8_t)(quant_code(x0, qp) | (quant_code(x1, qp) << 4));
+  const uint32_t c0 = quant_code(x0, qp), c1 = quant_code(x1, qp);
+  if (a.bits == 4) {
+    a.codes[orow * (a.R / 2) + blk * 64 + lane] = (uint8_t)(c0 | (c1 << 4));
+  } else {
+    // 2 bits: byte k of a row holds channels 4k .. 4k+3 (lanes 2k, 2k+1).  3 bits: the low two bits of every
+    // code in that layout, then the third bits, byte k holding channels 8k .. 8k+7 (lanes 4k .. 4k+3).
+    uint8_t* row = a.codes + orow * (size_t)(a.R * a.bits / 8);
+    const uint32_t lo = (c0 & 3u) | ((c1 & 3u) << 2);
+    const uint32_t lo_n = __shfl_xor(lo, 1, 64);
+    if ((lane & 1) == 0) row[blk * 32 + (lane >> 1)] = (uint8_t)(lo | (lo_n << 4));
+    if (a.bits == 3) {
+      uint32_t hi = (c0 >> 2) | ((c1 >> 2) << 1);                  // 2 bits: this lane's channels
+      hi |= __shfl_xor(hi, 1, 64) << 2;                            // even lanes: 4 bits
+      hi |= __shfl_xor(hi, 2, 64) << 4;                            // lanes 4k: 8 bits
+      if ((lane & 3) == 0) row[a.R / 4 + blk * 16 + (lane >> 2)] = (uint8_t)hi;
+    }
+  }
   if (lane == 0) {
     a.scale[orow * a.n_blocks + blk] = qp.s16;
     a.zero[orow * a.n_blocks + blk] = qp.z16;

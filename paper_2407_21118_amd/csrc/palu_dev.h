@@ -71,6 +71,24 @@ struct BF16 {
   }
 };
 
+// 2- and 3-bit latents (the low-bit settings of Sec. 4.4): eight channels' codes, stored as 16 bits of
+// two-bit fields (channel u in bits 2u, 2u+1) and, for 3 bits, 8 third bits (channel u in bit u), spread
+// into the 4-bit layout the kernels work on (channel u in bits 4u .. 4u+3).
+__device__ __forceinline__ uint32_t expand_low_bits(uint32_t lo16, uint32_t hi8, bool three) {
+  uint32_t x = lo16 & 0xffffu;
+  x = (x | (x << 8)) & 0x00ff00ffu;
+  x = (x | (x << 4)) & 0x0f0f0f0fu;
+  x = (x | (x << 2)) & 0x33333333u;
+  if (three) {
+    uint32_t y = hi8 & 0xffu;
+    y = (y | (y << 12)) & 0x000f000fu;
+    y = (y | (y << 6)) & 0x03030303u;
+    y = (y | (y << 3)) & 0x11111111u;
+    x |= y << 2;
+  }
+  return x;
+}
+
 // Position of accumulator element i of a 32x32 MFMA tile: the lane holds
 // column n = lane % 32 and rows 8*(i/4) + 4*(lane/32) + (i%4), i = 0..15.
 __device__ __forceinline__ int mfma_row(int i, int lane_hi) { return 8 * (i >> 2) + 4 * lane_hi + (i & 3); }
@@ -122,6 +140,7 @@ struct ScoreArgs {
   int n_heads;
   int n_blocks_q;            // R_k / quant_block (int4 only)
   int quant_block;
+  int bits;                  // quantized latents: 4, 3 or 2 bits per code
   float scale;               // log2(e) / sqrt(d_h)
   // shared-key form (grouped-query attention): units count key/value heads, n_heads the query heads
   const uint16_t* qfrag;     // rotated queries as contraction operands, see qfrag_kernel

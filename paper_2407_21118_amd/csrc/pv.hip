@@ -122,8 +122,10 @@ __device__ __forceinline__ void wave_lds_fence() {
 // HS: score slots per lane: the unit has at most 2*HS heads (HS = 16: two 16-row tiles)
 // NG: 128-column blocks per unit (16 lanes x 8 channels each)
 // I4: latents are 4-bit codes; every 128-column block of the unit is one quantization block
-template <typename T, int HS, int NG, bool I4>
-__global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs a) {
+// QB: bits per code of quantized latents (4, 3, 2), 0 for fp16 / bf16 latents
+template <typename T, int HS, int NG, int QB>
+__global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs a) {
+  constexpr bool I4 = QB != 0;
   constexpr bool kIsBf16 = !__is_same(T, F16);
   constexpr int MT = HS > 8 ? 2 : 1;
   constexpr int NA = I4 ? NG : 1;                  // probability tiles
@@ -157,11 +159,14 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
   const int lpt = u.ncols >> 3;                    // 8-channel chunks per row of the unit
 
   const size_t row0 = (size_t)b * a.max_seq + s0;
-  const unsigned row_bytes = I4 ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
-  const unsigned char* base = (const unsigned char*)a.hv + row0 * row_bytes + (I4 ? c0 / 2 : c0 * 2);
+  // quantized latents: 4-bit codes, or 2-bit fields followed (3 bits) by a plane of third bits at R/4 bytes
+  constexpr int bits = I4 ? QB : 16;
+  const unsigned row_bytes = (unsigned)a.row_elems * (unsigned)bits / 8u;
+  const unsigned char* base = (const unsigned char*)a.hv + row0 * row_bytes + (I4 ? (bits == 4 ? c0 / 2 : c0 / 4) : c0 * 2);
+  const unsigned hi_plane = (unsigned)a.row_elems / 4u + (unsigned)c0 / 8u - (unsigned)c0 / 4u;   // from `base` to the third bits
   unsigned coff[NG];
 #pragma unroll
-  for (int ng = 0; ng < NG; ++ng) coff[ng] = (unsigned)min(ng * 16 + n, lpt - 1) * (I4 ? 4u : 16u);
+  for (int ng = 0; ng < NG; ++ng) coff[ng] = (unsigned)min(ng * 16 + n, lpt - 1) * (I4 ? (bits == 4 ? 4u : 2u) : 16u);
 
   const float* sc_ptr[HS];
   bool two[HS];
@@ -177,7 +182,7 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
   const int n_blk = (u.ncols + 127) >> 7;          // 128-column blocks the unit really has
 
   struct Blk {
-    uint32_t h[8][I4 ? 1 : 4];                     // [token j of the lane's quarter][dword]
+    uint32_t h[8][I4 ? (QB == 3 ? 2 : 1) : 4];     // [token j of the lane's quarter][dword]; quantized: codes, third bits (3-bit only)
   };
   struct Set {
     Blk blk[NG];
@@ -196,7 +201,12 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
         const unsigned t = (unsigned)min(tb + 8 * kq + j, last);
         const unsigned char* p = base + (size_t)(t * row_bytes + coff[ng]);
         if constexpr (I4) {
-          st.blk[ng].h[j][0] = *reinterpret_cast<const uint32_t*>(p);
+          if constexpr (bits == 4) {
+            st.blk[ng].h[j][0] = *reinterpret_cast<const uint32_t*>(p);
+          } else {
+            st.blk[ng].h[j][0] = *reinterpret_cast<const uint16_t*>(p);
+            if constexpr (QB == 3) st.blk[ng].h[j][1] = p[hi_plane - (coff[ng] >> 1)];      // the chunk's byte of the third-bit plane
+          }
         } else {
           const uint4v v = *reinterpret_cast<const uint4v*>(p);
           st.blk[ng].h[j][0] = v.x; st.blk[ng].h[j][1] = v.y; st.blk[ng].h[j][2] = v.z; st.blk[ng].h[j][3] = v.w;
@@ -323,10 +333,15 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
             o[2 * d + 1][jp] = hi;
           }
         } else {
+          uint32_t ca = bl.h[2 * jp][0], cb = bl.h[2 * jp + 1][0];
+          if constexpr (bits != 4) {
+            ca = expand_low_bits(ca, bl.h[2 * jp][QB == 3 ? 1 : 0], QB == 3);
+            cb = expand_low_bits(cb, bl.h[2 * jp + 1][QB == 3 ? 1 : 0], QB == 3);
+          }
 #pragma unroll
           for (int kb = 0; kb < 4; ++kb) {
             // byte kb of both tokens' code words side by side: [0, tok b byte, 0, tok a byte]
-            const uint32_t w = __builtin_amdgcn_perm(bl.h[2 * jp + 1][0], bl.h[2 * jp][0], 0x0c040c00u + 0x00010001u * kb);
+            const uint32_t w = __builtin_amdgcn_perm(cb, ca, 0x0c040c00u + 0x00010001u * kb);
             // a code c in the top four mantissa bits of 0x3c00 is the fp16 number 1 + c/16 (exact):
             // sum_t a_t (1 + c_t/16) = sum a + (sum a c)/16, undone at the write-out together with the zero-points
             o[2 * kb][jp] = ((w << 6) & 0x03c003c0u) | 0x3c003c00u;         // even channel: low nibbles
@@ -421,8 +436,10 @@ __global__ __launch_bounds__(256, (I4 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs
   template __global__ void pv_kernel<T, 8, 1, I4>(PvArgs);         \
   template __global__ void pv_kernel<T, 8, 2, I4>(PvArgs);         \
   template __global__ void pv_kernel<T, 16, 1, I4>(PvArgs);
-PALU_PV_INST(F16, false)
-PALU_PV_INST(BF16, false)
-PALU_PV_INST(F16, true)
+PALU_PV_INST(F16, 0)
+PALU_PV_INST(BF16, 0)
+PALU_PV_INST(F16, 4)
+PALU_PV_INST(F16, 3)
+PALU_PV_INST(F16, 2)
 
 }  // namespace palu

@@ -145,8 +145,9 @@ __global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
 // T:  storage type of unquantized latents (bfloat16 converted to fp16 in registers)
 // MT: 16-row head tiles (1: up to 16 heads, 2: up to 32)
 // I4: latents are 4-bit codes
-template <typename T, int MT, bool I4>
+template <typename T, int MT, int QB>
 __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
+  constexpr bool I4 = QB != 0;                   // QB: bits per code of quantized latents (4, 3, 2), 0 for fp16 / bf16
   extern __shared__ __attribute__((aligned(16))) unsigned char qk_lds[];
   constexpr bool kIsBf16 = !__is_same(T, F16);
   const int tid = threadIdx.x;
@@ -185,8 +186,11 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   const int ncols = u.ncols;
 
   const size_t row0 = (size_t)b * a.max_seq + s0;
-  const unsigned row_bytes = I4 ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
-  const unsigned char* base = (const unsigned char*)a.hk + row0 * row_bytes + (I4 ? u.c0 / 2 : u.c0 * 2);
+  // quantized latents: 4-bit codes, or 2-bit fields followed (3 bits) by a plane of third bits at R/4 bytes
+  constexpr int bits = I4 ? QB : 16;
+  const unsigned row_bytes = (unsigned)a.row_elems * (unsigned)bits / 8u;
+  const unsigned char* base = (const unsigned char*)a.hk + row0 * row_bytes + (I4 ? (bits == 4 ? u.c0 / 2 : u.c0 / 4) : u.c0 * 2);
+  const unsigned hi_plane = (unsigned)a.row_elems / 4u + (unsigned)u.c0 / 8u - (unsigned)u.c0 / 4u;    // from `base` to the third bits
   const size_t sz_idx0 = I4 ? row0 * a.n_blocks_q + (u.c0 >> 7) : 0;
   const int n_blk = (ncols + 127) >> 7;
 
@@ -212,7 +216,16 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
           const int col = min(chunk * 256 + x * 32 + kq * 8, ncols - 8);
           off = (unsigned)col * 2u;
         }
-        st.h[tau][x] = *reinterpret_cast<const uint4v*>(base + (size_t)(t * row_bytes + off));
+        if constexpr (!I4 || bits == 4) {
+          st.h[tau][x] = *reinterpret_cast<const uint4v*>(base + (size_t)(t * row_bytes + off));
+        } else {
+          // the lane's 32 codes: 8 bytes of two-bit fields (half the 4-bit offset), 4 bytes of third bits (a quarter)
+          const unsigned char* p = base + (size_t)(t * row_bytes);
+          const uint2v lo = *reinterpret_cast<const uint2v*>(p + (off >> 1));
+          st.h[tau][x].x = lo.x;
+          st.h[tau][x].y = lo.y;
+          if constexpr (bits == 3) st.h[tau][x].z = *reinterpret_cast<const uint32_t*>(p + hi_plane + (off >> 2));
+        }
       }
     }
   };
@@ -273,7 +286,9 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
           for (int mt = 0; mt < MT; ++mt) d[mt] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) {
-            const uint32_t w = st.h[tau][x][jj];
+            uint32_t w = st.h[tau][x][jj];
+            if constexpr (bits != 4)
+              w = expand_low_bits(st.h[tau][x][jj >> 1] >> (16 * (jj & 1)), st.h[tau][x][2] >> (8 * jj), bits == 3);
             const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;     // even / odd channels, one per byte
             uint4v bw;
 #pragma unroll
@@ -339,8 +354,10 @@ template __global__ void qfold_kernel<BF16>(QfoldArgs);
 #define PALU_QK_INST(T, I4)                                   \
   template __global__ void qk_kernel<T, 1, I4>(QkArgs);       \
   template __global__ void qk_kernel<T, 2, I4>(QkArgs);
-PALU_QK_INST(F16, false)
-PALU_QK_INST(BF16, false)
-PALU_QK_INST(F16, true)
+PALU_QK_INST(F16, 0)
+PALU_QK_INST(BF16, 0)
+PALU_QK_INST(F16, 4)
+PALU_QK_INST(F16, 3)
+PALU_QK_INST(F16, 2)
 
 }  // namespace palu

@@ -87,8 +87,11 @@ constexpr int score_num_bufs(int width, bool dma) {
 //       whose A operand (queries x the same values' query entries, written by
 //       qfrag_kernel) sits in 4 KiB of LDS per wavefront.  Rows of the result are
 //       queries; the two lane halves' features are summed by the contraction itself.
-template <typename T, int NKS, int RT, int G, int NW, bool I4, int QP = 0>
+// LB:   quantized latents of 3 or 2 bits (a.bits) instead of 4: the codes are spread into the
+//       4-bit layout while they are staged
+template <typename T, int NKS, int RT, int G, int NW, bool I4, int QP = 0, bool LB = false>
 __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
+  static_assert(!LB || I4, "low-bit codes are quantized latents");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   static_assert(NW == 4 || (NW == 8 && RT == 2), "8 wavefronts only as half-head ping-pong");
   constexpr bool kIsBf16 = !__is_same(T, F16);
@@ -155,10 +158,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   // chunk) plus 32-bit byte offsets (the host keeps a chunk of the cache below 2^31 bytes)
   const int c_lo = u.k_off0;                                    // first latent column staged by the workgroup
   const size_t seq_base = (size_t)b * a.max_seq;
-  const unsigned row_bytes = I4 ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
-  const unsigned char* hk_base = (const unsigned char*)a.hk +
-                                 (I4 ? ((seq_base + t_begin) * a.row_elems + c_lo) / 2
-                                     : ((seq_base + t_begin) * a.row_elems + c_lo) * 2);
+  // quantized latents: 4-bit codes, or 2-bit fields followed (3 bits) by a plane of third bits at R/4 bytes
+  const int bits = I4 ? (LB ? a.bits : 4) : 16;
+  const unsigned row_bytes = (unsigned)a.row_elems * (unsigned)bits / 8u;
+  const unsigned char* hk_base = (const unsigned char*)a.hk + (seq_base + t_begin) * row_bytes +
+                                 (I4 ? (bits == 4 ? c_lo / 2 : c_lo / 4) : c_lo * 2);
+  const unsigned hi_plane = (unsigned)a.row_elems / 4u + (unsigned)c_lo / 8u - (unsigned)c_lo / 4u;   // from hk_base to the third bits
   const unsigned char* rope_base = (const unsigned char*)(a.rope_rows + (size_t)t_begin * kDHead);
   const unsigned char* rope_base_u = uniform_ptr(rope_base);
   const unsigned lds_base = (unsigned)(size_t)lds;
@@ -266,9 +271,15 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
         const unsigned off = __umul24(rel, row_bytes) + (unsigned)st_col[p] * 16u;
         s.h[p] = *reinterpret_cast<const uint4v*>(hk_base + off);
       } else {
-        const unsigned off = __umul24(rel, row_bytes) + (unsigned)st_col[p] * 4u;
         const size_t sb = (seq_base + t_begin + rel) * a.n_blocks_q + (c_lo + st_col[p] * 8) / a.quant_block;
-        s.h[p].x = *reinterpret_cast<const uint32_t*>(hk_base + off);
+        if constexpr (!LB) {
+          const unsigned off = __umul24(rel, row_bytes) + (unsigned)st_col[p] * 4u;
+          s.h[p].x = *reinterpret_cast<const uint32_t*>(hk_base + off);
+        } else {
+          const unsigned off = __umul24(rel, row_bytes) + (unsigned)st_col[p] * 2u;
+          s.h[p].x = *reinterpret_cast<const uint16_t*>(hk_base + off);
+          if (bits == 3) s.h[p].z = hk_base[off + hi_plane - (unsigned)st_col[p]];
+        }
         s.h[p].y = (uint32_t)a.hk_scale[sb] | ((uint32_t)a.hk_zero[sb] << 16);
       }
     }
@@ -284,7 +295,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     for (int p = 0; p < kPass; ++p) {
       uint4v v = s.h[p];
       if (I4) {            // dequantize: (code - zero) * scale in float32, one rounding to fp16
-        const uint32_t codes = v.x;
+        const uint32_t codes = !LB ? v.x : expand_low_bits(v.x, v.z, bits == 3);
         const float sc = F16::to_float((uint16_t)(v.y & 0xffffu));
         const float z = F16::to_float((uint16_t)(v.y >> 16));
 #pragma unroll

@@ -29,10 +29,12 @@ def to_dev(x: np.ndarray, dtype: str):
     return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch_dtype(dtype)).cuda()
 
 
-def make_desc(layer, dtype: str, k_i4: bool = False, v_i4: bool = False) -> "P.LayerDesc":
+def make_desc(layer, dtype: str, k_i4: bool = False, v_i4: bool = False, bits: int = 4) -> "P.LayerDesc":
+    """k_i4 / v_i4: the side's latents are quantized, to `bits` bits (4, 3 or 2)."""
     act = P.PALU_F16 if dtype == "f16" else P.PALU_BF16
+    qd = {4: P.PALU_I4, 3: P.PALU_I3, 2: P.PALU_I2}[bits]
     return P.LayerDesc(layer.n_heads, layer.d_head, layer.group_head_off, layer.k_rank_off, layer.v_rank_off,
-                       act, P.PALU_I4 if k_i4 else act, P.PALU_I4 if v_i4 else act, layer.quant_block,
+                       act, qd if k_i4 else act, qd if v_i4 else act, layer.quant_block,
                        layer.rope_theta, layer.q_per_kv)
 
 
@@ -44,10 +46,10 @@ def rel_err(got: np.ndarray, ref: np.ndarray):
     return float(whole), float(rows)
 
 
-def run_hip(case, k_i4=False, v_i4=False, quant=None, rope_len=None):
+def run_hip(case, k_i4=False, v_i4=False, quant=None, rope_len=None, bits=4):
     """HIP path on the case; `quant` = dict(k=(packed, scale, zero), v=(...)) of numpy arrays."""
     layer = case.layer
-    desc = make_desc(layer, case.dtype, k_i4, v_i4)
+    desc = make_desc(layer, case.dtype, k_i4, v_i4, bits)
     B, L = case.batch, case.seq
     q = to_dev(case.q, case.dtype)
     q_pos = torch.from_numpy(np.asarray(case.q_pos, np.int32)).cuda()
@@ -81,9 +83,9 @@ def run_hip(case, k_i4=False, v_i4=False, quant=None, rope_len=None):
     return out.cpu().numpy()
 
 
-def run_oracle(case, quant=None, k_i4=False, v_i4=False):
+def run_oracle(case, quant=None, k_i4=False, v_i4=False, bits=4):
     layer = case.layer
-    Hk = O.dequant_latent(*quant["k"]) if k_i4 else case.Hk
-    Hv = O.dequant_latent(*quant["v"]) if v_i4 else case.Hv
+    Hk = O.dequant_latent(*quant["k"], bits=bits) if k_i4 else case.Hk
+    Hv = O.dequant_latent(*quant["v"], bits=bits) if v_i4 else case.Hv
     return O.attn_decode(case.q, case.q_pos, Hk, Hv, case.Bk, case.Bv, layer.group_head_off, layer.k_rank_off,
                          layer.v_rank_off, layer.d_head, layer.rope_theta, case.k_pos, case.seq_lens, layer.q_per_kv)

@@ -326,3 +326,39 @@ def test_encode_quant_fused(dtype, n_tok):
         np.testing.assert_array_equal(c[perm], pk)
         np.testing.assert_array_equal(scale.cpu().view(torch.int16).numpy()[perm], so.view(np.int16))
         np.testing.assert_array_equal(zero.cpu().view(torch.int16).numpy()[perm], zo.view(np.int16))
+
+
+@pytest.mark.parametrize("bits,dtype", [(2, "f16"), (3, "f16")])
+def test_low_bit_quantizer_bit_exact(bits, dtype):
+    """palu_quant_latent on a side declared PALU_I3 / PALU_I2: codes in the 2- and 3-bit layouts,
+    scales and zero-points, bit for bit the oracle's; scattered destination rows."""
+    say(f"[quant] bits={bits} dtype={dtype}")
+    layer = synth.config_layer("4")
+    rng = np.random.default_rng(90 + bits)
+    n_tok = 200
+    h = rng.standard_normal((n_tok, layer.R_k)) * rng.uniform(0.01, 40.0, size=(n_tok, 1))
+    h[:10] += 9.0
+    h[10:12] = -1.5                                            # constant blocks
+    h[12, :128] = np.arange(128) % (1 << bits)                 # exact grid
+    h[13, :128] = (np.arange(128) % (1 << bits)) * 0.5 + 0.25  # ties
+    h = synth.round_to(h, dtype)
+    act = P.PALU_F16 if dtype == "f16" else P.PALU_BF16
+    qd = {3: P.PALU_I3, 2: P.PALU_I2}[bits]
+    # a quantized side needs an fp16 layer for decoding; the quantizer itself also takes bf16 inputs
+    desc = P.LayerDesc(layer.n_heads, layer.d_head, layer.group_head_off, layer.k_rank_off, layer.v_rank_off,
+                       P.PALU_F16, qd, qd) if dtype == "f16" else None
+    if desc is None:
+        pytest.skip("quantized sides are declared on fp16 layers")
+    rows = n_tok + 7
+    perm = rng.permutation(rows)[:n_tok].astype(np.int32)
+    codes = torch.full((rows, layer.R_k * bits // 8), 0x5A, dtype=torch.uint8, device="cuda")
+    scale = torch.zeros((rows, layer.R_k // 128), dtype=torch.float16, device="cuda")
+    zero = torch.zeros_like(scale)
+    P.palu_quant_latent(desc, 0, to_dev(h, dtype), layer.R_k, n_tok, codes, scale, zero, torch.from_numpy(perm).cuda())
+    torch.cuda.synchronize()
+    pk, s, z = O.quant_latent(h, bits=bits)
+    np.testing.assert_array_equal(codes.cpu().numpy()[perm], pk)
+    np.testing.assert_array_equal(scale.cpu().view(torch.int16).numpy()[perm], s.view(np.int16))
+    np.testing.assert_array_equal(zero.cpu().view(torch.int16).numpy()[perm], z.view(np.int16))
+    untouched = np.setdiff1d(np.arange(rows), perm)
+    assert (codes.cpu().numpy()[untouched] == 0x5A).all()

@@ -18,7 +18,7 @@ def check(case, tol, **kw):
     say(f"[parity] {case.name} dtype={case.dtype} B={case.batch} L={case.seq} "
         f"groups={case.layer.n_groups} Rk={case.layer.R_k} kw={ {k: v for k, v in kw.items() if k != 'quant'} }")
     got = run_hip(case, **kw)
-    ref = run_oracle(case, **{k: v for k, v in kw.items() if k in ("quant", "k_i4", "v_i4")})
+    ref = run_oracle(case, **{k: v for k, v in kw.items() if k in ("quant", "k_i4", "v_i4", "bits")})
     assert np.isfinite(got).all()
     whole, rows = rel_err(got, ref)
     say(f"         rel err whole={whole:.3e} worst row={rows:.3e} (tol {tol})")
@@ -315,3 +315,29 @@ def test_several_queries_per_sequence(n_q, qpk, theta, i4):
     say(f"        rel err whole={whole:.3e} worst row={rows:.3e}")
     tol = TOL_I4 if i4 else TOL_FP
     assert whole <= tol and rows <= tol
+
+
+@pytest.mark.parametrize("bits,theta,k_q,v_q", [(2, 10000.0, True, True), (3, 10000.0, True, True), (2, 0.0, True, True),
+                                                 (3, 0.0, True, True), (3, 10000.0, False, True), (2, 10000.0, True, False)])
+def test_low_bit_latents(bits, theta, k_q, v_q):
+    """2- and 3-bit latents (Sec. 4.4), Hadamard-rotated factors as in Sec. 3.4: key and / or value
+    side, with and without RoPE, a ragged layer (ranks 128 .. 384), ragged lengths.  The oracle is fed
+    the same dequantized values; what is measured is the kernels' arithmetic, as for 4 bits."""
+    import dataclasses
+    layer = synth.Layer(10, 128, [0, 4, 6, 7, 10], [0, 256, 384, 512, 896], [0, 384, 512, 640, 896], rope_theta=theta)
+    case = synth.make_case_svd(layer, 2, 270, seed=60 + bits, rotate=False)
+    case.seq_lens = np.array([270, 99], np.int32)
+    case.q_pos = (case.seq_lens - 1).astype(np.int32)
+    case.name = f"{bits}-bit latents theta={theta} K={k_q} V={v_q}"
+    quant = {"k": O.quant_latent(case.Hk, bits=bits), "v": O.quant_latent(case.Hv, bits=bits)}
+    check(case, TOL_I4, k_i4=k_q, v_i4=v_q, quant=quant, bits=bits)
+
+
+def test_low_bit_latents_grouped_query_and_config4_shape():
+    """3-bit keys and 2-bit-free mix on the 7B shape at reduced length and on a grouped-query layer."""
+    for cfg, bits in (("4", 3), ("gqa", 2)):
+        layer = synth.config_layer(cfg)
+        case = synth.make_case_svd(layer, 2, 200, seed=70 + bits, rotate=True)
+        case.name = f"config {cfg} with {bits}-bit latents"
+        quant = {"k": O.quant_latent(case.Hk, bits=bits), "v": O.quant_latent(case.Hv, bits=bits)}
+        check(case, TOL_I4, k_i4=True, v_i4=True, quant=quant, bits=bits)
