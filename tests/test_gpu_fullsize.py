@@ -34,7 +34,7 @@ def b_slice(flat, layer, which, j, heads):
     return np.ascontiguousarray(Bj[:, cols]).reshape(-1)
 
 
-def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP, no_rope=False):
+def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP, no_rope=False, bits=4):
     layer = None
     if no_rope:
         import dataclasses
@@ -42,7 +42,7 @@ def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP, no_rope=False):
     case = wd.make_device_case(cfg, seed=0, n_sets=1, layer=layer)
     layer, B, L = case.layer, case.batch, case.seq
     say(f"[full] cfg {cfg} B={B} L={L} groups={layer.n_groups} R_k={layer.R_k} k_i4={k_i4} v_i4={v_i4}")
-    desc = make_desc(layer, "f16", k_i4, v_i4)
+    desc = make_desc(layer, "f16", k_i4, v_i4, bits)
     table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, L)
     hk, hv, kw = case.Hk[0], case.Hv[0], {}
     nbk, nbv = layer.R_k // 128, layer.R_v // 128
@@ -50,7 +50,7 @@ def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP, no_rope=False):
     for side, flag, H, R, nb in (("k", k_i4, case.Hk[0], layer.R_k, nbk), ("v", v_i4, case.Hv[0], layer.R_v, nbv)):
         if not flag:
             continue
-        codes = torch.empty((B, L, R // 2), dtype=torch.uint8, device="cuda")
+        codes = torch.empty((B, L, R * bits // 8), dtype=torch.uint8, device="cuda")
         sc = torch.empty((B, L, nb), dtype=torch.float16, device="cuda")
         zp = torch.empty_like(sc)
         P.palu_quant_latent(desc, 0 if side == "k" else 1, H, R, B * L, codes, sc, zp)
@@ -75,14 +75,15 @@ def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP, no_rope=False):
             if side not in quant:
                 continue
             # the oracle quantizes the same rows itself; the codes the GPU wrote must equal its codes
-            pk, s, z = O.quant_latent(H[0])
+            pk, s, z = O.quant_latent(H[0], bits=bits)
             codes, sc, zp = quant[side]
-            np.testing.assert_array_equal(codes[b, :, cols.start // 2:cols.stop // 2].cpu().numpy(), pk)
+            got_codes = O.unpack_codes(codes[b].cpu().numpy(), bits)[:, cols]
+            np.testing.assert_array_equal(got_codes, O.unpack_codes(pk, bits))
             np.testing.assert_array_equal(sc[b, :, cols.start // 128:cols.stop // 128].cpu().view(torch.int16).numpy(),
                                           s.view(np.int16))
             np.testing.assert_array_equal(zp[b, :, cols.start // 128:cols.stop // 128].cpu().view(torch.int16).numpy(),
                                           z.view(np.int16))
-            deq = O.dequant_latent(pk, s, z)[None]
+            deq = O.dequant_latent(pk, s, z, bits=bits)[None]
             if side == "k":
                 Hk = deq
             else:
@@ -157,3 +158,55 @@ def test_full_gqa_16k():
 
 def test_full_gqa_16k_no_rope():
     run_full("gqa", [(1, 1, [1])], no_rope=True)
+
+
+def test_full_config4_three_bit_latents():
+    run_full("4", [(3, 1, [0, 2])], k_i4=True, v_i4=True, tol=TOL_I4, bits=3)
+
+
+def test_full_config4_two_bit_latents_no_rope():
+    run_full("4", [(9, 5, [1])], k_i4=True, v_i4=True, tol=TOL_I4, bits=2, no_rope=True)
+
+
+def test_full_config2_16k_four_query_tokens():
+    """A causal block of four new tokens per sequence at the 7B shape and 16K: every query against
+    its own single-query call of the library (itself checked against the oracle above), and one
+    sampled (query, group) against the oracle."""
+    case = wd.make_device_case("2", seed=0, n_sets=1)
+    layer, B, L, n_q = case.layer, case.batch, case.seq, 4
+    say(f"[full] cfg 2 with {n_q} query tokens per sequence, B={B} L={L}")
+    desc = make_desc(layer, "f16")
+    table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, L)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1234)
+    q = torch.randn((B, n_q, layer.n_heads, 128), generator=g, device="cuda", dtype=torch.float32).half()
+    q_len = (torch.full((B, 1), L, dtype=torch.int32, device="cuda") - n_q + 1 +
+             torch.arange(n_q, dtype=torch.int32, device="cuda")[None]).contiguous()
+    q_pos = (q_len - 1).contiguous()
+    out = P.palu_attn_decode_multi(desc, B, n_q, L, L, q, q_pos, case.Hk[0], case.Hv[0], case.Bk, case.Bv, table, L,
+                                   q_len=q_len)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    for j in range(n_q):
+        one = P.palu_attn_decode(desc, B, L, L, q[:, j].contiguous(), q_pos[:, j].contiguous(), case.Hk[0], case.Hv[0],
+                                 case.Bk, case.Bv, table, L, seq_lens=q_len[:, j].contiguous())
+        torch.cuda.synchronize()
+        whole, rows = rel_err(got[:, j], one.cpu().numpy().astype(np.float64))
+        say(f"       query {j}: against its single-query call {whole:.3e} (rows {rows:.3e})")
+        assert whole <= TOL_FP and rows <= TOL_FP
+    j, grp, heads = 2, 3, [1, 2]
+    sub = group_slice(layer, grp, heads)
+    kc = slice(layer.k_rank_off[grp], layer.k_rank_off[grp + 1])
+    vc = slice(layer.v_rank_off[grp], layer.v_rank_off[grp + 1])
+    n_rows = int(q_len[0, j])
+    Hk = case.Hk[0][0, :n_rows, kc].float().cpu().numpy()[None]
+    Hv = case.Hv[0][0, :n_rows, vc].float().cpu().numpy()[None]
+    h_abs = [layer.group_head_off[grp] + u for u in heads]
+    Bk, Bv = case.Bk.float().cpu().numpy(), case.Bv.float().cpu().numpy()
+    ref = O.attn_decode(q[0, j, h_abs].float().cpu().numpy()[None], [int(q_pos[0, j])], Hk, Hv,
+                        b_slice(Bk, layer, "k", grp, heads), b_slice(Bv, layer, "v", grp, heads),
+                        sub.group_head_off, sub.k_rank_off, sub.v_rank_off, 128, layer.rope_theta)
+    whole, rows = rel_err(got[0, j, h_abs][None], ref)
+    say(f"       oracle sample query {j} group {grp} heads {heads}: {whole:.3e}")
+    assert whole <= TOL_FP and rows <= TOL_FP
