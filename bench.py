@@ -324,8 +324,8 @@ def main() -> int:
     # measured HBM traffic per launch of the dominant kernel, from counter runs kept under profiles/
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
-            tr = json.load(f).get(cfg)
-        if tr and not args.no_rope:
+            tr = json.load(f).get(cfg + (":no-rope" if args.no_rope else ""))
+        if tr and args.latent_bits == 4:
             result["roofline"]["traffic"] = tr["score_kernel_bytes"]
             result["roofline_value"]["traffic"] = tr["value_kernel_bytes"]
     except OSError:
