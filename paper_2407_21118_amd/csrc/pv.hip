@@ -121,8 +121,9 @@ __device__ __forceinline__ void wave_lds_fence() {
 // T:  storage type of unquantized latents (bfloat16 is converted to fp16 in registers: exact in the fp16 range)
 // HS: score slots per lane: the unit has at most 2*HS heads (HS = 16: two 16-row tiles)
 // NG: 128-column blocks per unit (16 lanes x 8 channels each)
-// I4: latents are 4-bit codes; every 128-column block of the unit is one quantization block
-// QB: bits per code of quantized latents (4, 3, 2), 0 for fp16 / bf16 latents
+// QB: latents are QB-bit codes (4, 3 or 2; 0: unquantized); every 128-column block of the unit is one
+//     quantization block.  In the body I4 = "quantized": 3- and 2-bit codes are spread into the
+//     4-bit register layout when they are consumed and then follow the 4-bit arithmetic.
 template <typename T, int HS, int NG, int QB>
 __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs a) {
   constexpr bool I4 = QB != 0;

@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
 
 // T:  storage type of unquantized latents (bfloat16 converted to fp16 in registers)
 // MT: 16-row head tiles (1: up to 16 heads, 2: up to 32)
-// I4: latents are 4-bit codes
+// QB: latents are QB-bit codes (4, 3 or 2; 0: unquantized); I4 below means "quantized"
 template <typename T, int MT, int QB>
 __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   constexpr bool I4 = QB != 0;                   // QB: bits per code of quantized latents (4, 3, 2), 0 for fp16 / bf16

@@ -72,7 +72,7 @@ constexpr int score_num_bufs(int width, bool dma) {
 // NW:   wavefronts per workgroup.  4: one per SIMD (RT = 4: four heads, RT = 2:
 //       two heads).  8: two per SIMD, RT = 2, four heads, ping-pong schedule:
 //       wavefronts 0-3 own the cos halves, 4-7 the sin halves.
-// I4:   latents are packed 4-bit codes with per-(token, block) scale and zero
+// I4:   latents are packed codes (4 bits; 3 or 2 with LB) with per-(token, block) scale and zero
 // QP:   0: one query per key/value head, folded into the weights as described above.
 //       1: shared-key form, for up to 16 queries per key/value head (the query heads
 //       of grouped-query attention, several query tokens per sequence, or both).

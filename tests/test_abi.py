@@ -54,11 +54,32 @@ def test_workspace_queries_are_host_only():
     (dict(act_dtype=5), -1),
     (dict(k_latent_dtype=P.PALU_I4, k_rank_off=[0, 64, 128]), -1),   # int4 needs ranks in multiples of the block
     (dict(k_rank_off=[0, 4096, 8192]), -2),              # rank above the build limit
+    (dict(q_per_kv=-1), -1),                             # negative query-head count
+    (dict(q_per_kv=64), -2),                             # 8 * 64 query heads: above the build limit
+    (dict(v_latent_dtype=7), -1),                        # unknown latent dtype
+    (dict(v_latent_dtype=P.PALU_I2, v_rank_off=[0, 64, 128]), -1),   # 2-bit latents need ranks in multiples of the block
+    (dict(k_latent_dtype=P.PALU_I3, act_dtype=P.PALU_BF16, k_rank_off=[0, 128, 256]), -2),   # quantized sides: fp16 layers only
 ])
 def test_descriptor_validation(kw, status):
     with pytest.raises(P.PaluError) as e:
         P.palu_attn_decode_workspace_bytes(desc(**kw), 1, 128)
     assert e.value.status == status
+
+
+def test_grouped_query_and_multi_query_workspace_grow_with_the_queries():
+    lib = P.load_library()
+    base = P.palu_attn_decode_workspace_bytes(desc(), 2, 4096)
+    gqa = P.palu_attn_decode_workspace_bytes(desc(q_per_kv=4), 2, 4096)
+    assert gqa > base
+    out = ctypes.c_size_t(0)
+    assert lib.palu_attn_decode_multi_workspace_bytes(desc().ref(), 2, 4, 4096, ctypes.byref(out)) == 0
+    assert out.value == gqa                              # 4 queries per key/value head either way
+    assert lib.palu_attn_decode_multi_workspace_bytes(desc().ref(), 2, 0, 4096, ctypes.byref(out)) == -1
+    assert lib.palu_attn_decode_multi_workspace_bytes(desc().ref(), 2, 64, 4096, ctypes.byref(out)) == -2
+    # the fused projection + quantizer writes 4-bit codes only
+    d3 = desc(k_latent_dtype=P.PALU_I3, k_rank_off=[0, 128, 256])
+    one = ctypes.c_void_p(256)                           # non-NULL, aligned; never dereferenced: the call is refused first
+    assert lib.palu_encode_quant(d3.ref(), 0, one, 1, one, one, one, one, None, None) == -2
 
 
 def test_null_and_range_arguments():

@@ -341,3 +341,12 @@ def test_low_bit_latents_grouped_query_and_config4_shape():
         case.name = f"config {cfg} with {bits}-bit latents"
         quant = {"k": O.quant_latent(case.Hk, bits=bits), "v": O.quant_latent(case.Hv, bits=bits)}
         check(case, TOL_I4, k_i4=True, v_i4=True, quant=quant, bits=bits)
+
+
+@pytest.mark.parametrize("theta", [10000.0, 0.0])
+def test_build_limits_256_heads_64_groups(theta):
+    """The largest layer the build accepts: 256 heads in 64 groups (PALU_MAX_HEADS, PALU_MAX_GROUPS)."""
+    layer = synth.uniform_layer(256, 4, 64, 32, rope_theta=theta)
+    case = synth.make_case_orthonormal(layer, 1, 77, seed=88)
+    case.name = f"256 heads / 64 groups theta={theta}"
+    check(case, TOL_FP)
