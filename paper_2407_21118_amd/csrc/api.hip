@@ -446,16 +446,18 @@ ScoreFn score_fn_lowbit(int rc) {
 }
 
 // shared-key form (several queries per key/value head): fp16 latents, ranks up to 256, 8 wavefronts, up to 16 queries
+// QP = 1: at most 4 queries per key/value head, QP = 2: at most 16
+template <int QP>
 ScoreFn score_fn_shared(int rc) {
   switch (rc) {
-    case 0: return score_kernel<F16, 2, 2, 1, 8, false, 1>;
-    case 1: return score_kernel<F16, 4, 2, 1, 8, false, 1>;
-    case 2: return score_kernel<F16, 6, 2, 1, 8, false, 1>;
-    case 3: return score_kernel<F16, 8, 2, 1, 8, false, 1>;
-    case 4: return score_kernel<F16, 10, 2, 1, 8, false, 1>;
-    case 5: return score_kernel<F16, 12, 2, 1, 8, false, 1>;
-    case 6: return score_kernel<F16, 14, 2, 1, 8, false, 1>;
-    default: return score_kernel<F16, 16, 2, 1, 8, false, 1>;
+    case 0: return score_kernel<F16, 2, 2, 1, 8, false, QP>;
+    case 1: return score_kernel<F16, 4, 2, 1, 8, false, QP>;
+    case 2: return score_kernel<F16, 6, 2, 1, 8, false, QP>;
+    case 3: return score_kernel<F16, 8, 2, 1, 8, false, QP>;
+    case 4: return score_kernel<F16, 10, 2, 1, 8, false, QP>;
+    case 5: return score_kernel<F16, 12, 2, 1, 8, false, QP>;
+    case 6: return score_kernel<F16, 14, 2, 1, 8, false, QP>;
+    default: return score_kernel<F16, 16, 2, 1, 8, false, QP>;
   }
 }
 
@@ -962,6 +964,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         qa.qpk = m.qpk;
         qa.nq = m.nq;
         qa.n_heads = m.n_heads;
+        qa.small = m.qpk <= 4 ? 1 : 0;
         hipLaunchKernelGGL(qfrag_kernel<F16>, dim3((unsigned)mk.n_heads, (unsigned)batch), dim3(256), 0, s, qa);
         if ((st = launch_ok()) != PALU_OK) return st;
       }
@@ -1023,7 +1026,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         const int width = (32 * (rc + 1)) << lg;
         const bool dma = act == PALU_F16 && !k_i4;
         const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width) + (shared_key ? score_qf_bytes() : 0);
-        ScoreFn fn = shared_key ? score_fn_shared(rc) : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, id, waves8));
+        ScoreFn fn = shared_key ? (m.qpk <= 4 ? score_fn_shared<1>(rc) : score_fn_shared<2>(rc)) : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, id, waves8));
         if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
         const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
         auto flush = [&]() -> int {

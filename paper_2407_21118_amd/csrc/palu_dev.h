@@ -168,6 +168,7 @@ struct QfragArgs {
   int n_kv, qpk;
   int nq;                    // queries per sequence; q_pos has batch * nq entries
   int n_heads;               // n_kv * qpk
+  int small;                 // 1: qpk <= 4, operands of the 4x4x4 form
 };
 
 struct FoldArgs {

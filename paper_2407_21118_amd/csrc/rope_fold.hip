@@ -117,7 +117,8 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
 // e+1, sin e, sin e+1, cos e+2, cos e+3, sin e+2, sin e+3); the matching query
 // entries are q'_f for cos and q'_{f+64} for sin where the wavefront holds K_f, and
 // q'_{f+64} and -q'_f where it holds K_{f+64}.  Rows of absent queries are zero.
-// Layout [batch][kv head][feature half][step 8][lane half 2][query 16] x 16 bytes.
+// Layout [batch][kv head][feature half][step 8][lane half 2][query 16] x 16 bytes (4 KiB per feature half); with at
+// most 4 queries (`small`) the 4x4x4 form's operands instead, see below.
 // grid (key/value heads, batch), 256 threads.
 template <typename T>
 __global__ __launch_bounds__(256) void qfrag_kernel(QfragArgs a) {
@@ -141,6 +142,33 @@ __global__ __launch_bounds__(256) void qfrag_kernel(QfragArgs a) {
     qr[hq][f + kHalf] = x1 * c + x0 * s;
   }
   __syncthreads();
+  if (a.small) {
+    // at most 4 queries, contracted on 4x4x4 blocks: [feature half][step n 16][lane half 2][query 4] x 8 bytes, step n
+    // covering the accumulators e = 2n, 2n+1 in the order (cos e, cos e+1, sin e, sin e+1); 4 KiB apart per feature half
+    uint2v* out2 = reinterpret_cast<uint2v*>(a.qfrag) + ((size_t)b * a.n_kv + kvh) * 1024;
+    {
+      const int item = tid;                               // 2 x 16 x 2 x 4 = 256 entries
+      const int row = item & 3, hi = (item >> 2) & 1, n = (item >> 3) & 15, half = item >> 7;
+      uint16_t v[4];
+#pragma unroll
+      for (int y = 0; y < 2; ++y) {
+        const int e = 2 * n + y;
+        const int f = 32 * (e >> 4) + mfma_row(e & 15, hi);
+        float qc = 0.f, qs = 0.f;
+        if (row < a.qpk) {
+          qc = half ? qr[row][f + kHalf] : qr[row][f];
+          qs = half ? -qr[row][f] : qr[row][f + kHalf];
+        }
+        v[y] = F16::from_float(qc);
+        v[2 + y] = F16::from_float(qs);
+      }
+      uint2v pk;
+      pk.x = v[0] | ((uint32_t)v[1] << 16);
+      pk.y = v[2] | ((uint32_t)v[3] << 16);
+      out2[half * 512 + (item & 127)] = pk;
+    }
+    return;
+  }
   uint4v* out = reinterpret_cast<uint4v*>(a.qfrag) + ((size_t)b * a.n_kv + kvh) * 512;
   for (int item = tid; item < 512; item += 256) {
     const int row = item & 15, hi = (item >> 4) & 1, N = (item >> 5) & 7, half = item >> 8;

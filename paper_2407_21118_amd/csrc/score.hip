@@ -74,8 +74,9 @@ constexpr int score_num_bufs(int width, bool dma) {
 //       wavefronts 0-3 own the cos halves, 4-7 the sin halves.
 // I4:   latents are packed codes (4 bits; 3 or 2 with LB) with per-(token, block) scale and zero
 // QP:   0: one query per key/value head, folded into the weights as described above.
-//       1: shared-key form, for up to 16 queries per key/value head (the query heads
-//       of grouped-query attention, several query tokens per sequence, or both).
+//       1, 2: shared-key form, for up to 4 (QP = 1) or 16 (QP = 2) queries per key/value
+//       head (the query heads of grouped-query attention, several query tokens per
+//       sequence, or both).
 //       The stationary operand is B_k itself (transposed), so the accumulators are the
 //       key K[feature][token], rebuilt once for all queries that share it.  With q' a
 //       rotated query, its score is the contraction over f < 64 of
@@ -87,6 +88,11 @@ constexpr int score_num_bufs(int width, bool dma) {
 //       whose A operand (queries x the same values' query entries, written by
 //       qfrag_kernel) sits in 4 KiB of LDS per wavefront.  Rows of the result are
 //       queries; the two lane halves' features are summed by the contraction itself.
+//       With at most 4 queries (QP = 1) the query contraction runs on
+//       v_mfma_f32_4x4x4_16B_f16 instead (16 blocks of 4 queries x 4 tokens: a lane feeds
+//       its own token's 4 values per step and collects that token's four scores, the two
+//       lane halves are then added): 16 short instructions take less of the matrix pipe
+//       than 8 full-size ones with 28 of 32 rows empty.
 // LB:   quantized latents of 3 or 2 bits (a.bits) instead of 4: the codes are spread into the
 //       4-bit layout while they are staged
 template <typename T, int NKS, int RT, int G, int NW, bool I4, int QP = 0, bool LB = false>
@@ -325,7 +331,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     const unsigned char* src = uniform_ptr(reinterpret_cast<const unsigned char*>(a.qfrag) +
                                            (((size_t)b * a.n_kv + hq) * 2 + (wave >> 2)) * 4096);
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
+    for (int x = 0; x < (QP == 1 ? 1 : 4); ++x) {      // QP = 1: 1 KiB of operands
       const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)(kBufs * kBufB) + (unsigned)(wave * 4096 + x * 1024));
       const unsigned voff = (unsigned)lane * 16u + (unsigned)x * 1024u;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(src) : "memory");
@@ -373,7 +379,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   // [8 steps][2 lane halves][16 queries] x 16 bytes, behind the tile buffers
   constexpr int kQfBytes = 4096;
   const unsigned qf_off = (unsigned)(kBufs * kBufB) + (unsigned)wave * kQfBytes;
-  const unsigned char* qf_lds = lds + qf_off + (lane_hi * 16 + (lane_lo & 15)) * 16;      // + 512 per step
+  // QP = 2: [8 steps][2 lane halves][16 queries] x 16 bytes.  QP = 1: [16 steps][2 lane halves][4 queries] x 8 bytes.
+  const unsigned char* qf_lds = lds + qf_off + (QP == 1 ? (lane_hi * 4 + (lane & 3)) * 8 : (lane_hi * 16 + (lane_lo & 15)) * 16);
   auto load_weights = [&]() __attribute__((always_inline)) {
     const uint16_t* mf = a.mfold + (size_t)b * a.mfold_bstride + u.bk_off0 +
                          ((size_t)g_rel * u.s + u_in_g) * u.head_stride;
@@ -454,6 +461,33 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
       // Step N of the contraction takes the accumulators e = 4N .. 4N+3 (e = 16 rt + i), rounded to fp16 and
       // multiplied by the position's cos and sin as packed fp16, in the order
       // (K cos)(e), (K cos)(e+1), (K sin)(e), (K sin)(e+1), then the same for e+2, e+3.
+      if constexpr (QP == 1) {
+        // at most 4 queries: step n = 8 rt + ip takes accumulators 2ip, 2ip+1 as (cos, cos, sin, sin) products;
+        // two independent accumulation chains
+        float4v s4[2] = {float4v{0.f, 0.f, 0.f, 0.f}, float4v{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+          for (int ip = 0; ip < 8; ++ip) {
+            const int n = 8 * rt + ip;
+            const float2f kf = {r.acc[rt][2 * ip], r.acc[rt][2 * ip + 1]};
+            const half2f kk = __builtin_convertvector(kf, half2f);
+            const uint4v cw = __builtin_bit_cast(uint4v, r.cs[rt][ip >> 2]), sw = __builtin_bit_cast(uint4v, r.sn[rt][ip >> 2]);
+            const uint32_t cb = cw[ip & 3], sb = sw[ip & 3];
+            const half2f pc = kk * __builtin_bit_cast(half2f, cb), ps = kk * __builtin_bit_cast(half2f, sb);
+            const uint2v bq = {__builtin_bit_cast(uint32_t, pc), __builtin_bit_cast(uint32_t, ps)};
+            const uint2v aq = *reinterpret_cast<const uint2v*>(qf_lds + n * 64);
+            s4[n & 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4, aq), __builtin_bit_cast(half4, bq), s4[n & 1], 0, 0, 0);
+          }
+        // entry i: query i, this lane's token, this lane half's features.  Each lane half stores two of the queries.
+        const float s0 = sum_across_halves(s4[0][0] + s4[1][0]), s1 = sum_across_halves(s4[0][1] + s4[1][1]);
+        const float s2 = sum_across_halves(s4[0][2] + s4[1][2]), s3 = sum_across_halves(s4[0][3] + s4[1][3]);
+        const int hq = 2 * lane_hi;
+        float* row = out_row + (size_t)hq * a.lpad + t0 + lane_lo;
+        if (hq < a.qpk) row[0] = (lane_hi ? s2 : s0) * a.scale;
+        if (hq + 1 < a.qpk) row[a.lpad] = (lane_hi ? s3 : s1) * a.scale;
+        return;
+      }
       float16v sc;
 #pragma unroll
       for (int i = 0; i < 16; ++i) sc[i] = 0.f;
