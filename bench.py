@@ -153,8 +153,15 @@ def main() -> int:
     new_k = torch.empty((batch, layer.R_k), dtype=torch.float16, device="cuda")
     new_v = torch.empty((batch, layer.R_v), dtype=torch.float16, device="cuda")
 
+    fused = not (k_i4 or v_i4)          # one call per step (append + attend); quantized caches take the separate calls
+
     def step(i: int, events=None, decode_events=None):
         s = i % n_sets
+        if fused and events is None and decode_events is None:
+            P.palu_decode_step(desc, batch, seq, seq, case.x_new, case.Ak, case.Av, dst_row, case.q, case.q_pos,
+                               case.Hk[s], case.Hv[s], case.Bk, case.Bv, table, seq, out=out, workspace=ws,
+                               encode_workspace=ws_e)
+            return
         # down-project the new token into both caches (fp16 row first when the cache is int4)
         k_dst, k_stride, k_rows = (new_k, layer.R_k, None) if k_i4 else (case.Hk[s], layer.R_k, dst_row)
         v_dst, v_stride, v_rows = (new_v, layer.R_v, None) if v_i4 else (case.Hv[s], layer.R_v, dst_row)
@@ -243,7 +250,9 @@ def main() -> int:
         "config": {"workload": f"config {cfg}{' without RoPE' if args.no_rope else ''}: Llama-2-7B-shaped layer decode, batch {batch}, seq {seq}, "
                                f"{layer.n_groups} groups, R_k {layer.R_k}, R_v {layer.R_v}",
                    "batch": batch, "seq_len": seq, "n_heads": layer.n_heads, "q_per_kv": layer.q_per_kv, "group_size": layer.group_size(0),
-                   "cache_sets": n_sets, "step": "encode K + encode V (+ quantize) + attn_decode"},
+                   "cache_sets": n_sets,
+                   "step": ("palu_decode_step: encode K + encode V + attn_decode in one call" if fused
+                            else "encode K + encode V + quantize + attn_decode")},
         "roofline": {
             "kernel": "score_kernel (key reconstruction + RoPE + q.K on MFMA)",
             "bound": "mfma", "achieved": score_tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",

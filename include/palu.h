@@ -269,6 +269,31 @@ int palu_attn_decode_latent(const palu_layer_desc* desc, int32_t batch, int32_t 
                             float* out_latent, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * One whole decode step in one call: append the new token of every sequence to both
+ * caches (h = x A, Sec. 3.1) and attend (palu_attn_decode).  Same results, bit for
+ * bit, as palu_encode_kv followed by palu_attn_decode; where the step folds the
+ * query into B_k (RoPE, fp16 / bf16 latents, one query per key/value head, fewer
+ * than 64 sequences) the projection's first launch and the fold, which do not depend
+ * on each other, share one grid, so the step has one launch less.
+ *   x            DEVICE [batch, n_heads*q_per_kv*d_head] act_dtype: the new tokens' activations
+ *   Ak, Av       as for palu_encode_kv
+ *   dst_row      DEVICE int32 [batch]: row of hk / hv (counted over all batch*max_seq rows)
+ *                that receives sequence b's new latent; it must be one of the rows attended
+ *   encode_workspace  of palu_encode_workspace_bytes(desc, 2, batch) bytes
+ *   hk, hv       DEVICE caches [batch, max_seq, R] act_dtype (quantized caches: PALU_ERR_UNSUPPORTED,
+ *                use the separate calls with palu_quant_latent in between)
+ *   the rest     as for palu_attn_decode
+ */
+int palu_decode_step(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                     const void* x, const void* Ak, const void* Av, const int32_t* dst_row,
+                     void* encode_workspace, size_t encode_workspace_bytes,
+                     const void* q, const int32_t* q_pos, void* hk, void* hv,
+                     const int32_t* k_pos, const int32_t* seq_lens,
+                     const void* Bk, const void* Bv,
+                     const void* rope_table, int32_t rope_table_len,
+                     float* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Several new query tokens per sequence in one call (a block of a chunked prompt,
  * or a speculative-decoding check): each query is an ordinary decode step of Sec. 2.1
  * Eq. 2 over the latent cache, with its own position and its own number of cached

@@ -93,6 +93,9 @@ def load_library():
     lib.palu_attn_decode_multi.argtypes = [dp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                            vp, i32, vp, vp, sz, vp]
     lib.palu_attn_decode_multi.restype = ctypes.c_int
+    lib.palu_decode_step.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                     vp, vp, sz, vp]
+    lib.palu_decode_step.restype = ctypes.c_int
     for name in ("palu_rope_table_bytes", "palu_rope_table_init", "palu_encode_workspace_bytes", "palu_encode",
                  "palu_quant_latent", "palu_attn_decode_workspace_bytes", "palu_attn_decode"):
         getattr(lib, name).restype = ctypes.c_int
@@ -335,4 +338,25 @@ def palu_attn_decode_multi(desc: LayerDesc, batch: int, n_q: int, seq_len: int, 
                                       int(rope_table_len), _ptr(out), _ptr(workspace),
                                       workspace.numel() * workspace.element_size(), _stream(stream)),
            "palu_attn_decode_multi")
+    return out
+
+
+def palu_decode_step(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, x, Ak, Av, dst_row, q, q_pos, hk, hv,
+                     Bk, Bv, rope_table, rope_table_len: int, out=None, workspace=None, encode_workspace=None,
+                     k_pos=None, seq_lens=None, stream=None):
+    """Append the new tokens (x) to both caches and attend, in one call."""
+    import torch
+    if out is None:
+        out = torch.empty((batch, desc.n_q_heads, desc.d_head), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(palu_attn_decode_workspace_bytes(desc, batch, max_seq), dtype=torch.uint8,
+                                device=q.device)
+    if encode_workspace is None:
+        encode_workspace = torch.empty(palu_encode_workspace_bytes(desc, 2, batch), dtype=torch.uint8, device=q.device)
+    _need_cuda(x, Ak, Av, dst_row, q, q_pos, hk, hv, Bk, Bv, rope_table, out, workspace, encode_workspace, k_pos, seq_lens)
+    _check(load_library().palu_decode_step(
+        desc.ref(), batch, seq_len, max_seq, _ptr(x), _ptr(Ak), _ptr(Av), _ptr(dst_row), _ptr(encode_workspace),
+        encode_workspace.numel() * encode_workspace.element_size(), _ptr(q), _ptr(q_pos), _ptr(hk), _ptr(hv),
+        _ptr(k_pos), _ptr(seq_lens), _ptr(Bk), _ptr(Bv), _ptr(rope_table), int(rope_table_len), _ptr(out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "palu_decode_step")
     return out

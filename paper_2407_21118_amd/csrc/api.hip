@@ -500,6 +500,42 @@ PvFn pv_fn(int act, int bits, int cls) {
   return act == PALU_F16 ? pv_fn_t<F16, 0>(cls) : pv_fn_t<BF16, 0>(cls);
 }
 
+// First launch of a fused decode step: the split-K partial products of the new token's down-projection
+// (the long HBM stream) and the fold of the rotated query into B_k do not depend on each other.  The grid
+// is the projection's; its first fold_blocks workgroups also fold one (k-step, head, sequence) item each,
+// after their weight loads have gone out; items beyond the projection's grid get workgroups of their own.
+struct StepHeadArgs {
+  EncodeArgs enc;
+  FoldArgs fold;
+  int fold_blocks, fold_gx, fold_gy;     // fold grid (k-steps, heads, batch), linearised
+  int enc_blocks, enc_gx, enc_gy;        // projection grid (column blocks, k splits, sides), linearised
+};
+
+template <typename T, int kEncTok>
+__global__ __launch_bounds__(256) void step_head_kernel(StepHeadArgs a) {
+  const int id = blockIdx.x;
+  auto fold_item = [&]() __attribute__((always_inline)) {
+    if (id < a.fold_blocks) {
+      const int ks = id % a.fold_gx, rest = id / a.fold_gx;
+      fold_body<T>(a.fold, ks, rest % a.fold_gy, rest / a.fold_gy);
+    }
+  };
+  if (id < a.enc_blocks) {
+    const int bx = id % a.enc_gx, rest = id / a.enc_gx;
+    encode_partial_body<T, kEncTok>(a.enc, bx, rest % a.enc_gy, rest / a.enc_gy, fold_item);
+  } else {
+    fold_item();
+  }
+}
+
+using StepHeadFn = void (*)(StepHeadArgs);
+StepHeadFn step_head_fn(int act, int tok_cls) {
+  static const StepHeadFn f16[4] = {step_head_kernel<F16, 1>, step_head_kernel<F16, 2>, step_head_kernel<F16, 4>,
+                                    step_head_kernel<F16, 8>};
+  static const StepHeadFn bf16[4] = {step_head_kernel<BF16, 1>, step_head_kernel<BF16, 2>, step_head_kernel<BF16, 4>,
+                                     step_head_kernel<BF16, 8>};
+  return act == PALU_F16 ? f16[tok_cls] : bf16[tok_cls];
+}
 inline int launch_ok() { return hipGetLastError() == hipSuccess ? PALU_OK : PALU_ERR_HIP; }
 
 }  // namespace
@@ -589,26 +625,35 @@ int palu_encode_workspace_bytes(const palu_layer_desc* desc, int which, int32_t 
 }
 
 namespace {
-int encode_impl(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x, int32_t n_tok,
+// A validated down-projection call, ready to launch.
+struct EncodePlan {
+  EncodeArgs a;
+  bool gemm;              // many tokens: tiled GEMM, no workspace
+  int n_sides, max_R;
+  int tok_cls;            // split-K form: 8, 4, 2 or 1 tokens per pass (index 3 .. 0)
+};
+
+int plan_encode(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x, int32_t n_tok,
                 const void* Ak, const void* Av, void* hk, int64_t hk_stride, void* hv, int64_t hv_stride,
-                const int32_t* dst_row, void* workspace, size_t workspace_bytes, void* stream) {
+                const int32_t* dst_row, void* workspace, size_t workspace_bytes, EncodePlan* p) {
   Meta m;
   const int st = check_desc(desc, &m);
   if (st != PALU_OK) return st;
   if (!x || n_tok <= 0) return PALU_ERR_INVALID_ARG;
   if (n_tok < kEncodeGemmTokens && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15))) return PALU_ERR_INVALID_ARG;
   const int d = m.n_heads * PALU_D_HEAD;
-  const bool gemm = n_tok >= kEncodeGemmTokens;      // many tokens: tiled GEMM, no workspace
+  p->gemm = n_tok >= kEncodeGemmTokens;
   if (reinterpret_cast<uintptr_t>(x) & 15) return PALU_ERR_INVALID_ARG;
-  EncodeArgs a;
+  EncodeArgs& a = p->a;
   std::memset(&a, 0, sizeof(a));
   a.x = static_cast<const uint16_t*>(x);
   a.dst_row = dst_row;
   a.n_tok = n_tok;
   a.d = d;
-  a.k_splits = gemm ? 0 : d / kEncRows;
+  a.k_splits = p->gemm ? 0 : d / kEncRows;
   size_t off = 0;
-  int n_sides = 0, max_R = 0;
+  p->n_sides = 0;
+  p->max_R = 0;
   for (int side = 0; side < 2; ++side) {
     if (!(side ? do_v : do_k)) continue;
     const void* A = side ? Av : Ak;
@@ -617,21 +662,38 @@ int encode_impl(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x
     const int R = side ? m.v_off[m.n_groups] : m.k_off[m.n_groups];
     if (!A || !lat || stride < R || (stride & 1)) return PALU_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(A) & 15) || (reinterpret_cast<uintptr_t>(lat) & 3)) return PALU_ERR_INVALID_ARG;
-    EncodeSide& sd = a.side[n_sides++];
+    EncodeSide& sd = a.side[p->n_sides++];
     sd.A = static_cast<const uint16_t*>(A);
     sd.partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + off);
     sd.latent = static_cast<uint16_t*>(lat);
     sd.row_stride = stride;
     sd.R = R;
     off += align_up((size_t)a.k_splits * n_tok * R * 4);
-    max_R = std::max(max_R, R);
+    p->max_R = std::max(p->max_R, R);
   }
   if (workspace_bytes < off) return PALU_ERR_WORKSPACE_TOO_SMALL;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (gemm) {
+  p->tok_cls = n_tok >= 5 ? 3 : (n_tok >= 3 ? 2 : (n_tok == 2 ? 1 : 0));
+  return PALU_OK;
+}
+
+dim3 encode_partial_grid(const EncodePlan& p) {
+  return dim3((unsigned)ceil_div(p.max_R, kEncCols), (unsigned)p.a.k_splits, (unsigned)p.n_sides);
+}
+
+// second launch of the split-K form: sum the partials, round, scatter the rows
+int launch_encode_finish(int act, const EncodePlan& p, hipStream_t s) {
+  const dim3 g2((unsigned)ceil_div(p.max_R, 64), (unsigned)p.a.n_tok, (unsigned)p.n_sides);
+  if (act == PALU_F16) hipLaunchKernelGGL(encode_finish_kernel<F16>, g2, dim3(256), 0, s, p.a);
+  else hipLaunchKernelGGL(encode_finish_kernel<BF16>, g2, dim3(256), 0, s, p.a);
+  return launch_ok();
+}
+
+int launch_encode(int act, const EncodePlan& p, hipStream_t s) {
+  const EncodeArgs& a = p.a;
+  if (p.gemm) {
     const size_t lds = (size_t)2 * kGemmTile * kGemmPitch * 2;
-    const dim3 g((unsigned)ceil_div(max_R, kGemmTile), (unsigned)ceil_div(n_tok, kGemmTile), (unsigned)n_sides);
-    if (desc->act_dtype == PALU_F16) {
+    const dim3 g((unsigned)ceil_div(p.max_R, kGemmTile), (unsigned)ceil_div(a.n_tok, kGemmTile), (unsigned)p.n_sides);
+    if (act == PALU_F16) {
       if (allow_lds(encode_gemm_kernel<F16, false>, lds) != PALU_OK) return PALU_ERR_HIP;
       hipLaunchKernelGGL((encode_gemm_kernel<F16, false>), g, dim3(256), lds, s, a);
     } else {
@@ -640,23 +702,26 @@ int encode_impl(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x
     }
     return launch_ok();
   }
-  const dim3 g1((unsigned)ceil_div(max_R, kEncCols), (unsigned)a.k_splits, (unsigned)n_sides);
-  const dim3 g2((unsigned)ceil_div(max_R, 64), (unsigned)n_tok, (unsigned)n_sides);
   using EncFn = void (*)(EncodeArgs);
-  const int tok_cls = n_tok >= 5 ? 3 : (n_tok >= 3 ? 2 : (n_tok == 2 ? 1 : 0));     // 8, 4, 2 or 1 tokens per pass
   static const EncFn partial_f16[4] = {encode_partial_kernel<F16, 1>, encode_partial_kernel<F16, 2>,
                                        encode_partial_kernel<F16, 4>, encode_partial_kernel<F16, 8>};
   static const EncFn partial_bf16[4] = {encode_partial_kernel<BF16, 1>, encode_partial_kernel<BF16, 2>,
                                         encode_partial_kernel<BF16, 4>, encode_partial_kernel<BF16, 8>};
-  if (desc->act_dtype == PALU_F16) {
-    hipLaunchKernelGGL(partial_f16[tok_cls], g1, dim3(256), 0, s, a);
-    hipLaunchKernelGGL(encode_finish_kernel<F16>, g2, dim3(256), 0, s, a);
-  } else {
-    hipLaunchKernelGGL(partial_bf16[tok_cls], g1, dim3(256), 0, s, a);
-    hipLaunchKernelGGL(encode_finish_kernel<BF16>, g2, dim3(256), 0, s, a);
-  }
-  return launch_ok();
+  hipLaunchKernelGGL(act == PALU_F16 ? partial_f16[p.tok_cls] : partial_bf16[p.tok_cls], encode_partial_grid(p), dim3(256), 0, s, a);
+  if (launch_ok() != PALU_OK) return PALU_ERR_HIP;
+  return launch_encode_finish(act, p, s);
 }
+
+int encode_impl(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x, int32_t n_tok,
+                const void* Ak, const void* Av, void* hk, int64_t hk_stride, void* hv, int64_t hv_stride,
+                const int32_t* dst_row, void* workspace, size_t workspace_bytes, void* stream) {
+  EncodePlan p;
+  const int st = plan_encode(desc, do_k, do_v, x, n_tok, Ak, Av, hk, hk_stride, hv, hv_stride, dst_row, workspace,
+                             workspace_bytes, &p);
+  if (st != PALU_OK) return st;
+  return launch_encode(desc->act_dtype, p, static_cast<hipStream_t>(stream));
+}
+
 }  // namespace
 
 int palu_encode(const palu_layer_desc* desc, int which, const void* x, int32_t n_tok, const void* A,
@@ -785,7 +850,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
                        const void* Bk, const void* Bv,
                        const void* rope_table, int32_t rope_table_len,
                        float* out, float* out_latent, void* workspace, size_t workspace_bytes, void* stream,
-                       void* const* stage_events) {
+                       void* const* stage_events, const EncodePlan* enc = nullptr) {
+  // enc: the step's down-projection of the new token (validated by the caller), launched from here:
+  // ahead of everything else, or, where the step folds the query into B_k, in one grid with that fold
   Meta m;
   int st = check_desc(desc, &m, n_q);
   if (st != PALU_OK) return st;
@@ -832,6 +899,11 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       if (!stage_events[i]) return PALU_ERR_INVALID_ARG;
 
   const bool no_rope = !(desc->rope_theta > 0.f);
+  bool enc_pending = enc != nullptr;
+  if (enc_pending && (no_rope || enc->gemm)) {
+    if ((st = launch_encode(act, *enc, s)) != PALU_OK) return st;
+    enc_pending = false;
+  }
   if (no_rope) {
     // 1'. fold the query into the latent space (Eq. 5); 2'. scores straight from the latents
     QkPlan qp;
@@ -927,6 +999,10 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)
     if (shared_key && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
     const ScorePlan& plan = shared_key ? spk : sp;
+    if (enc_pending && shared_key) {
+      if ((st = launch_encode(act, *enc, s)) != PALU_OK) return st;
+      enc_pending = false;
+    }
 
     // 1. fold the rotated query into B_k (shared-key form: B_k alone, and the rotated queries beside it)
     {
@@ -949,9 +1025,27 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
       const dim3 g((unsigned)(max_r / 16), (unsigned)mk.n_heads, shared_key ? 1u : (unsigned)batch);
       if ((st = mark(0)) != PALU_OK) return st;
-      if (act == PALU_F16) hipLaunchKernelGGL(fold_kernel<F16>, g, dim3(256), 0, s, a);
-      else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
-      if ((st = launch_ok()) != PALU_OK) return st;
+      if (enc_pending) {
+        // the new token's partial products and the fold in one grid, then the projection's second launch
+        static thread_local StepHeadArgs h;
+        h.enc = enc->a;
+        h.fold = a;
+        h.fold_gx = (int)g.x;
+        h.fold_gy = (int)g.y;
+        h.fold_blocks = (int)(g.x * g.y * g.z);
+        const dim3 ge = encode_partial_grid(*enc);
+        h.enc_gx = (int)ge.x;
+        h.enc_gy = (int)ge.y;
+        h.enc_blocks = (int)(ge.x * ge.y * ge.z);
+        hipLaunchKernelGGL(step_head_fn(act, enc->tok_cls), dim3((unsigned)std::max(h.fold_blocks, h.enc_blocks)), dim3(256), 0, s, h);
+        if ((st = launch_ok()) != PALU_OK) return st;
+        if ((st = launch_encode_finish(act, *enc, s)) != PALU_OK) return st;
+        enc_pending = false;
+      } else {
+        if (act == PALU_F16) hipLaunchKernelGGL(fold_kernel<F16>, g, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
+        if ((st = launch_ok()) != PALU_OK) return st;
+      }
       if (shared_key) {
         QfragArgs qa;
         qa.q = a.q;
@@ -1184,6 +1278,30 @@ int palu_attn_decode_multi(const palu_layer_desc* desc, int32_t batch, int32_t n
   return decode_impl(desc, batch, n_q, q_len, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero,
                      k_pos, seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream,
                      nullptr);
+}
+
+int palu_decode_step(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                     const void* x, const void* Ak, const void* Av, const int32_t* dst_row,
+                     void* encode_workspace, size_t encode_workspace_bytes,
+                     const void* q, const int32_t* q_pos, void* hk, void* hv,
+                     const int32_t* k_pos, const int32_t* seq_lens,
+                     const void* Bk, const void* Bv,
+                     const void* rope_table, int32_t rope_table_len,
+                     float* out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!desc) return PALU_ERR_INVALID_ARG;
+  if (latent_bits(desc->k_latent_dtype) || latent_bits(desc->v_latent_dtype)) return PALU_ERR_UNSUPPORTED;
+  if (batch <= 0) return PALU_ERR_INVALID_ARG;
+  Meta m;
+  int st = check_desc(desc, &m);
+  if (st != PALU_OK) return st;
+  EncodePlan p;
+  const int Rk = m.k_off[m.n_groups], Rv = m.v_off[m.n_groups];
+  if ((st = plan_encode(desc, true, true, x, batch, Ak, Av, hk, Rk, hv, Rv, dst_row, encode_workspace,
+                        encode_workspace_bytes, &p)) != PALU_OK)
+    return st;
+  return decode_impl(desc, batch, 1, nullptr, seq_len, max_seq, q, q_pos, hk, nullptr, nullptr, hv, nullptr, nullptr, k_pos,
+                     seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream, nullptr,
+                     &p);
 }
 
 }  // extern "C"

@@ -34,16 +34,26 @@ struct EncodeArgs {
 // grid (ceil(max R / 512), d / 64, sides), 256 threads.
 // kEncTok: tokens accumulated per pass over the weights (1, 2, 4 or 8: a decode
 // step of one sequence should not pay for eight).
-template <typename T, int kEncTok>
-__global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
+// (bx, by, bz): the workgroup's position in that grid (the kernel below passes blockIdx; the fused
+// first launch of a decode step runs the same body next to the query fold)
+// while_loading(): work of the whole workgroup that is independent of the projection, run after the
+// weight loads have been issued, in the shadow of their latency (the fused decode step folds the query there)
+struct NoExtraWork {
+  __device__ __forceinline__ void operator()() const {}
+};
+template <typename T, int kEncTok, typename Extra = NoExtraWork>
+__device__ __forceinline__ void encode_partial_body(const EncodeArgs& a, int bx, int by, int bz, Extra while_loading = Extra{}) {
   __shared__ float xs[kEncTok][kEncRows];
   __shared__ float red[3][kEncTok][kEncCols];     // wavefronts 1..3 hand their sums to wavefront 0
-  const EncodeSide sd = a.side[blockIdx.z];
+  const EncodeSide sd = a.side[bz];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int c0 = blockIdx.x * kEncCols + lane * 8;
-  const int k0 = blockIdx.y * kEncRows;
+  const int c0 = bx * kEncCols + lane * 8;
+  const int k0 = by * kEncRows;
   const bool col_ok = c0 < sd.R;                  // R is a multiple of 32, so 8 columns are all in or all out
-  if (blockIdx.x * kEncCols >= sd.R) return;      // uniform
+  if (bx * kEncCols >= sd.R) {                    // uniform
+    while_loading();
+    return;
+  }
 
   // the weight rows go out first: they are the long-latency HBM stream and do
   // not depend on the activations
@@ -53,6 +63,7 @@ __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
     const int k = wave * 16 + kk;
     wraw[kk] = col_ok ? *reinterpret_cast<const uint4v*>(sd.A + (size_t)(k0 + k) * sd.R + c0) : uint4v{0, 0, 0, 0};
   }
+  while_loading();
 
   for (int tb = 0; tb < a.n_tok; tb += kEncTok) {
     const int nt = min(kEncTok, a.n_tok - tb);
@@ -94,7 +105,7 @@ __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
 #pragma unroll
       for (int t = 0; t < kEncTok; ++t) {
         if (t >= nt) break;
-        float* dst = sd.partial + ((size_t)blockIdx.y * a.n_tok + tb + t) * sd.R + c0;
+        float* dst = sd.partial + ((size_t)by * a.n_tok + tb + t) * sd.R + c0;
         float4v o0, o1;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -106,6 +117,11 @@ __global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
       }
     }
   }
+}
+
+template <typename T, int kEncTok>
+__global__ __launch_bounds__(256) void encode_partial_kernel(EncodeArgs a) {
+  encode_partial_body<T, kEncTok>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // Sums the split-K partials in a fixed order, rounds once, scatters the rows.

@@ -45,11 +45,11 @@ __global__ __launch_bounds__(256) void rope_gather_kernel(RopeGatherArgs a) {
 // one k-step (16 rows of B_k) of one head.  The 16 x 128 block of B_k is fetched
 // with coalesced 16-byte loads, transposed through LDS, and written as 256
 // 16-byte words in MFMA operand order.
+// (ks, h, b): the workgroup's position in that grid.
 template <typename T>
-__global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
+__device__ __forceinline__ void fold_body(const FoldArgs& a, int ks, int h, int b) {
   __shared__ float qr[kDHead];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[16][kDHead + 8];
-  const int ks = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const Meta& m = a.meta;
   const int j = m.group_of_head[h];
@@ -107,6 +107,11 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
   pk.w = v[6] | ((uint32_t)v[7] << 16);
   uint16_t* out = a.mfold + (size_t)b * a.mfold_bstride + m.bk_off[j] + (size_t)u * r * kDHead;
   *reinterpret_cast<uint4v*>(out + ((size_t)ks * 256 + tid) * 8) = pk;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
+  fold_body<T>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // Shared-key form of the score kernel: the rotated queries q' = RoPE(q, position of

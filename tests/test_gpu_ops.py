@@ -362,3 +362,43 @@ def test_low_bit_quantizer_bit_exact(bits, dtype):
     np.testing.assert_array_equal(zero.cpu().view(torch.int16).numpy()[perm], z.view(np.int16))
     untouched = np.setdiff1d(np.arange(rows), perm)
     assert (codes.cpu().numpy()[untouched] == 0x5A).all()
+
+
+@pytest.mark.parametrize("cfg,batch,theta,dtype", [("2", 1, 10000.0, "f16"), ("3", 3, 10000.0, "f16"), ("2", 8, 10000.0, "bf16"),
+                                                   ("2", 2, 0.0, "f16"), ("gqa", 2, 500000.0, "f16")])
+def test_decode_step_equals_encode_then_decode(cfg, batch, theta, dtype):
+    """palu_decode_step (append + attend in one call, the projection's first launch sharing a grid
+    with the query fold where the step has one) against palu_encode_kv followed by
+    palu_attn_decode: same caches and same output, bit for bit; and against the oracle."""
+    import dataclasses
+    from gpu_util import TOL_FP, make_desc, to_dev
+    layer = dataclasses.replace(synth.config_layer(cfg), rope_theta=theta)
+    L = 200
+    case = synth.make_case_svd(layer, batch, L, seed=17, dtype=dtype)
+    say(f"[step] cfg={cfg} batch={batch} theta={theta} dtype={dtype}")
+    desc = make_desc(layer, dtype)
+    td = torch.float16 if dtype == "f16" else torch.bfloat16
+    rng = np.random.default_rng(18)
+    d = layer.n_q_heads * 128
+    x = synth.round_to(rng.standard_normal((batch, d)), dtype)
+    dst = torch.arange(batch, dtype=torch.int32, device="cuda") * L + (L - 1)
+    args = dict(q=to_dev(case.q, dtype), q_pos=torch.from_numpy(case.q_pos).cuda(), Bk=to_dev(case.Bk, dtype),
+                Bv=to_dev(case.Bv, dtype))
+    Ak, Av, xd = to_dev(case.Ak, dtype), to_dev(case.Av, dtype), to_dev(x, dtype)
+    table = P.palu_rope_table_init(theta, 128, L)
+    hk1, hv1 = to_dev(case.Hk, dtype), to_dev(case.Hv, dtype)
+    hk2, hv2 = hk1.clone(), hv1.clone()
+    P.palu_encode_kv(desc, xd, Ak, Av, hk1, layer.R_k, hv1, layer.R_v, dst)
+    ref_out = P.palu_attn_decode(desc, batch, L, L, args["q"], args["q_pos"], hk1, hv1, args["Bk"], args["Bv"], table, L)
+    got = P.palu_decode_step(desc, batch, L, L, xd, Ak, Av, dst, args["q"], args["q_pos"], hk2, hv2, args["Bk"], args["Bv"],
+                             table, L)
+    torch.cuda.synchronize()
+    assert torch.equal(hk1, hk2) and torch.equal(hv1, hv2)
+    assert torch.equal(got, ref_out)
+    Hk = hk2.float().cpu().numpy().astype(np.float64)
+    Hv = hv2.float().cpu().numpy().astype(np.float64)
+    want = O.attn_decode(case.q, case.q_pos, Hk, Hv, case.Bk, case.Bv, layer.group_head_off, layer.k_rank_off,
+                         layer.v_rank_off, 128, theta, None, None, layer.q_per_kv)
+    err = np.abs(got.cpu().numpy() - want).max() / np.abs(want).max()
+    say(f"       rel err to the oracle on the appended cache {err:.3e}")
+    assert err <= TOL_FP
