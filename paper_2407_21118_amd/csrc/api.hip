@@ -509,6 +509,11 @@ struct StepHeadArgs {
   FoldArgs fold;
   int fold_blocks, fold_gx, fold_gy;     // fold grid (k-steps, heads, batch), linearised
   int enc_blocks, enc_gx, enc_gy;        // projection grid (column blocks, k splits, sides), linearised
+  // shared-key form of the score kernel: its rotated-query operands are further items, after the fold's
+  const uint16_t* sk_q;                  // the call's q, NULL when the step has no such items
+  const int32_t* sk_q_pos;
+  uint16_t* sk_qfrag;
+  int sk_blocks, sk_n_kv, sk_qpk, sk_nq, sk_n_heads, sk_small;
 };
 
 template <typename T, int kEncTok>
@@ -518,6 +523,21 @@ __global__ __launch_bounds__(256) void step_head_kernel(StepHeadArgs a) {
     if (id < a.fold_blocks) {
       const int ks = id % a.fold_gx, rest = id / a.fold_gx;
       fold_body<T>(a.fold, ks, rest % a.fold_gy, rest / a.fold_gy);
+    } else if (id < a.fold_blocks + a.sk_blocks) {
+      if constexpr (__is_same(T, F16)) {             // the shared-key form exists for fp16 latents only
+        struct View {                                // QfragArgs' members, read in place from this kernel's arguments
+          const uint16_t* q;
+          const int32_t* q_pos;
+          uint16_t* qfrag;
+          const float (&rev_hi)[kHalf];
+          const float (&rev_lo)[kHalf];
+          int n_kv, qpk, nq, n_heads, small;
+        };
+        const View qa{a.sk_q, a.sk_q_pos, a.sk_qfrag, a.fold.rev_hi, a.fold.rev_lo,
+                      a.sk_n_kv, a.sk_qpk, a.sk_nq, a.sk_n_heads, a.sk_small};
+        const int item = id - a.fold_blocks;
+        qfrag_body<T>(qa, item % a.sk_n_kv, item / a.sk_n_kv);
+      }
     }
   };
   if (id < a.enc_blocks) {
@@ -999,10 +1019,6 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)
     if (shared_key && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
     const ScorePlan& plan = shared_key ? spk : sp;
-    if (enc_pending && shared_key) {
-      if ((st = launch_encode(act, *enc, s)) != PALU_OK) return st;
-      enc_pending = false;
-    }
 
     // 1. fold the rotated query into B_k (shared-key form: B_k alone, and the rotated queries beside it)
     {
@@ -1025,6 +1041,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
       const dim3 g((unsigned)(max_r / 16), (unsigned)mk.n_heads, shared_key ? 1u : (unsigned)batch);
       if ((st = mark(0)) != PALU_OK) return st;
+      const bool fused_head = enc_pending;
       if (enc_pending) {
         // the new token's partial products and the fold in one grid, then the projection's second launch
         static thread_local StepHeadArgs h;
@@ -1037,7 +1054,21 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         h.enc_gx = (int)ge.x;
         h.enc_gy = (int)ge.y;
         h.enc_blocks = (int)(ge.x * ge.y * ge.z);
-        hipLaunchKernelGGL(step_head_fn(act, enc->tok_cls), dim3((unsigned)std::max(h.fold_blocks, h.enc_blocks)), dim3(256), 0, s, h);
+        h.sk_q = nullptr;
+        h.sk_blocks = 0;
+        if (shared_key) {                  // the rotated-query operands of the shared-key form ride along too
+          h.sk_q = a.q;
+          h.sk_q_pos = q_pos;
+          h.sk_qfrag = reinterpret_cast<uint16_t*>(ws + w.qfrag);
+          h.sk_n_kv = mk.n_heads;
+          h.sk_qpk = m.qpk;
+          h.sk_nq = m.nq;
+          h.sk_n_heads = m.n_heads;
+          h.sk_small = m.qpk <= 4 ? 1 : 0;
+          h.sk_blocks = mk.n_heads * batch;
+        }
+        hipLaunchKernelGGL(step_head_fn(act, enc->tok_cls), dim3((unsigned)std::max(h.fold_blocks + h.sk_blocks, h.enc_blocks)),
+                           dim3(256), 0, s, h);
         if ((st = launch_ok()) != PALU_OK) return st;
         if ((st = launch_encode_finish(act, *enc, s)) != PALU_OK) return st;
         enc_pending = false;
@@ -1046,7 +1077,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
         if ((st = launch_ok()) != PALU_OK) return st;
       }
-      if (shared_key) {
+      if (shared_key && !fused_head) {
         QfragArgs qa;
         qa.q = a.q;
         qa.q_pos = q_pos;

@@ -125,10 +125,12 @@ __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
 // Layout [batch][kv head][feature half][step 8][lane half 2][query 16] x 16 bytes (4 KiB per feature half); with at
 // most 4 queries (`small`) the 4x4x4 form's operands instead, see below.
 // grid (key/value heads, batch), 256 threads.
-template <typename T>
-__global__ __launch_bounds__(256) void qfrag_kernel(QfragArgs a) {
+// (kvh, b): the workgroup's position in that grid.
+// A: QfragArgs, or anything with the same members (the fused first launch of a decode step passes a view of its own arguments).
+template <typename T, typename A>
+__device__ __forceinline__ void qfrag_body(const A& a, int kvh, int b) {
   __shared__ float qr[16][kDHead];
-  const int kvh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   Meta m;                                             // only the fields q_row and q_token read
   m.n_heads = a.n_heads; m.qpk = a.qpk; m.nq = a.nq;
   for (int h0 = 0; h0 < a.qpk; h0 += 4) {
@@ -198,6 +200,11 @@ __global__ __launch_bounds__(256) void qfrag_kernel(QfragArgs a) {
     pk.w = v[6] | ((uint32_t)v[7] << 16);
     out[item] = pk;
   }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void qfrag_kernel(QfragArgs a) {
+  qfrag_body<T>(a, blockIdx.x, blockIdx.y);
 }
 
 template __global__ void qfrag_kernel<F16>(QfragArgs);
