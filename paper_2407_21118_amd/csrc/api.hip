@@ -548,6 +548,40 @@ __global__ __launch_bounds__(256) void step_head_kernel(StepHeadArgs a) {
   }
 }
 
+// The same for non-RoPE attention: the items are those of qfold_kernel (query folded into the latent space).
+struct StepHeadNoRopeArgs {
+  EncodeArgs enc;
+  QfoldArgs qfold;
+  int q_blocks, q_gx, q_gy;              // qfold grid (column blocks, heads, batch / 4), linearised
+  int enc_blocks, enc_gx, enc_gy;
+};
+
+template <typename T, int kEncTok>
+__global__ __launch_bounds__(256) void step_head_norope_kernel(StepHeadNoRopeArgs a) {
+  const int id = blockIdx.x;
+  auto item = [&]() __attribute__((always_inline)) {
+    if (id < a.q_blocks) {
+      const int bx = id % a.q_gx, rest = id / a.q_gx;
+      qfold_body<T>(a.qfold, bx, rest % a.q_gy, rest / a.q_gy);
+    }
+  };
+  if (id < a.enc_blocks) {
+    const int bx = id % a.enc_gx, rest = id / a.enc_gx;
+    encode_partial_body<T, kEncTok>(a.enc, bx, rest % a.enc_gy, rest / a.enc_gy, item);
+  } else {
+    item();
+  }
+}
+
+using StepHeadNoRopeFn = void (*)(StepHeadNoRopeArgs);
+StepHeadNoRopeFn step_head_norope_fn(int act, int tok_cls) {
+  static const StepHeadNoRopeFn f16[4] = {step_head_norope_kernel<F16, 1>, step_head_norope_kernel<F16, 2>,
+                                          step_head_norope_kernel<F16, 4>, step_head_norope_kernel<F16, 8>};
+  static const StepHeadNoRopeFn bf16[4] = {step_head_norope_kernel<BF16, 1>, step_head_norope_kernel<BF16, 2>,
+                                           step_head_norope_kernel<BF16, 4>, step_head_norope_kernel<BF16, 8>};
+  return act == PALU_F16 ? f16[tok_cls] : bf16[tok_cls];
+}
+
 using StepHeadFn = void (*)(StepHeadArgs);
 StepHeadFn step_head_fn(int act, int tok_cls) {
   static const StepHeadFn f16[4] = {step_head_kernel<F16, 1>, step_head_kernel<F16, 2>, step_head_kernel<F16, 4>,
@@ -696,8 +730,11 @@ int plan_encode(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x
   return PALU_OK;
 }
 
-dim3 encode_partial_grid(const EncodePlan& p) {
-  return dim3((unsigned)ceil_div(p.max_R, kEncCols), (unsigned)p.a.k_splits, (unsigned)p.n_sides);
+// grid of the split-K form's first launch: (column blocks, k splits, sides)
+void encode_partial_grid(const EncodePlan& p, unsigned g[3]) {
+  g[0] = (unsigned)ceil_div(p.max_R, kEncCols);
+  g[1] = (unsigned)p.a.k_splits;
+  g[2] = (unsigned)p.n_sides;
 }
 
 // second launch of the split-K form: sum the partials, round, scatter the rows
@@ -727,7 +764,9 @@ int launch_encode(int act, const EncodePlan& p, hipStream_t s) {
                                        encode_partial_kernel<F16, 4>, encode_partial_kernel<F16, 8>};
   static const EncFn partial_bf16[4] = {encode_partial_kernel<BF16, 1>, encode_partial_kernel<BF16, 2>,
                                         encode_partial_kernel<BF16, 4>, encode_partial_kernel<BF16, 8>};
-  hipLaunchKernelGGL(act == PALU_F16 ? partial_f16[p.tok_cls] : partial_bf16[p.tok_cls], encode_partial_grid(p), dim3(256), 0, s, a);
+  unsigned g1[3];
+  encode_partial_grid(p, g1);
+  hipLaunchKernelGGL(act == PALU_F16 ? partial_f16[p.tok_cls] : partial_bf16[p.tok_cls], dim3(g1[0], g1[1], g1[2]), dim3(256), 0, s, a);
   if (launch_ok() != PALU_OK) return PALU_ERR_HIP;
   return launch_encode_finish(act, p, s);
 }
@@ -920,7 +959,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
 
   const bool no_rope = !(desc->rope_theta > 0.f);
   bool enc_pending = enc != nullptr;
-  if (enc_pending && (no_rope || enc->gemm)) {
+  if (enc_pending && enc->gemm) {
     if ((st = launch_encode(act, *enc, s)) != PALU_OK) return st;
     enc_pending = false;
   }
@@ -979,9 +1018,29 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       }
       f.head0 = h_lo;
       const dim3 g((unsigned)(wmax / 128), (unsigned)(h_hi - h_lo), (unsigned)ceil_div(batch, 4));
-      if (act == PALU_F16) hipLaunchKernelGGL(qfold_kernel<F16>, g, dim3(256), 0, s, f);
-      else hipLaunchKernelGGL(qfold_kernel<BF16>, g, dim3(256), 0, s, f);
-      if ((st = launch_ok()) != PALU_OK) return st;
+      if (enc_pending) {
+        // the new token's partial products with the query fold in their shadow, then the projection's second launch
+        static thread_local StepHeadNoRopeArgs hn;
+        hn.enc = enc->a;
+        hn.qfold = f;
+        hn.q_gx = (int)g.x;
+        hn.q_gy = (int)g.y;
+        hn.q_blocks = (int)(g.x * g.y * g.z);
+        unsigned ge[3];
+        encode_partial_grid(*enc, ge);
+        hn.enc_gx = (int)ge[0];
+        hn.enc_gy = (int)ge[1];
+        hn.enc_blocks = (int)(ge[0] * ge[1] * ge[2]);
+        hipLaunchKernelGGL(step_head_norope_fn(act, enc->tok_cls), dim3((unsigned)std::max(hn.q_blocks, hn.enc_blocks)),
+                           dim3(256), 0, s, hn);
+        if ((st = launch_ok()) != PALU_OK) return st;
+        if ((st = launch_encode_finish(act, *enc, s)) != PALU_OK) return st;
+        enc_pending = false;
+      } else {
+        if (act == PALU_F16) hipLaunchKernelGGL(qfold_kernel<F16>, g, dim3(256), 0, s, f);
+        else hipLaunchKernelGGL(qfold_kernel<BF16>, g, dim3(256), 0, s, f);
+        if ((st = launch_ok()) != PALU_OK) return st;
+      }
     }
     if ((st = mark(1)) != PALU_OK) return st;
     for (int cls = 0; cls < 2; ++cls) {              // 0: up to 16 heads per unit, 1: up to 32
@@ -1050,10 +1109,11 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         h.fold_gx = (int)g.x;
         h.fold_gy = (int)g.y;
         h.fold_blocks = (int)(g.x * g.y * g.z);
-        const dim3 ge = encode_partial_grid(*enc);
-        h.enc_gx = (int)ge.x;
-        h.enc_gy = (int)ge.y;
-        h.enc_blocks = (int)(ge.x * ge.y * ge.z);
+        unsigned ge[3];
+        encode_partial_grid(*enc, ge);
+        h.enc_gx = (int)ge[0];
+        h.enc_gy = (int)ge[1];
+        h.enc_blocks = (int)(ge[0] * ge[1] * ge[2]);
         h.sk_q = nullptr;
         h.sk_blocks = 0;
         if (shared_key) {                  // the rotated-query operands of the shared-key form ride along too

@@ -81,14 +81,15 @@ struct QkArgs {
 // grid (wpad_max / 128, heads of the launch, batch / 4), 256 threads: a workgroup fills
 // 128 columns of one head's row for four sequences; thread = (column, half of the
 // features).  The B_k values are loaded once and reused for the four.
+// (bx, by, bz): the workgroup's position in that grid.
 template <typename T>
-__global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
+__device__ __forceinline__ void qfold_body(const QfoldArgs& a, int bx, int by, int bz) {
   __shared__ float blk[4][4];
   const Meta& m = a.meta;
-  const int h = a.head0 + blockIdx.y;
+  const int h = a.head0 + by;
   const QkUnit u = a.units.u[a.unit_of_head[h]];
   const int hh = h - u.h0;
-  const int col0 = blockIdx.x * 128;
+  const int col0 = bx * 128;
   if (col0 >= u.wpad) return;
   const int tid = threadIdx.x, wave = tid >> 6;
   const int c = col0 + (tid >> 1);               // column inside the unit
@@ -107,17 +108,19 @@ __global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
     for (int x = 0; x < 8; ++x) bw[x] = *reinterpret_cast<const uint4v*>(Brow + 8 * x);
   }
   // four sequences per workgroup, their query loads issued together
-  const int b0 = blockIdx.z * 4;
+  const int b0 = bz * 4;
   const int nb = min(4, a.batch - b0);
   uint4v qw[4][8];
 #pragma unroll
   for (int bb = 0; bb < 4; ++bb) {
-    const uint16_t* qp = a.q + q_row(m, min(b0 + bb, a.batch - 1), h) * kDHead + fh;
+    if (bb >= nb) break;                             // uniform
+    const uint16_t* qp = a.q + q_row(m, b0 + bb, h) * kDHead + fh;
 #pragma unroll
     for (int x = 0; x < 8; ++x) qw[bb][x] = *reinterpret_cast<const uint4v*>(qp + 8 * x);
   }
 #pragma unroll
   for (int bb = 0; bb < 4; ++bb) {
+    if (bb >= nb) break;                             // uniform: fewer than four sequences left
     float s = 0.f;
 #pragma unroll
     for (int x = 0; x < 8; ++x) {
@@ -138,8 +141,13 @@ __global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
   }
   __syncthreads();
   if (tid < nb)
-    a.qsum[(size_t)(b0 + tid) * a.qs_bstride + u.qs_off + (size_t)hh * (u.wpad >> 7) + blockIdx.x] =
+    a.qsum[(size_t)(b0 + tid) * a.qs_bstride + u.qs_off + (size_t)hh * (u.wpad >> 7) + bx] =
         (blk[tid][0] + blk[tid][1]) + (blk[tid][2] + blk[tid][3]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
+  qfold_body<T>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // T:  storage type of unquantized latents (bfloat16 converted to fp16 in registers)
