@@ -74,6 +74,8 @@ def main() -> int:
     ap.add_argument("--opt", action="append", default=[], help="tuning knob name=value (palu_set_option)")
     ap.add_argument("--latent-bits", type=int, default=4, choices=(4, 3, 2),
                     help="config 4 / 4v: bits per quantized latent code (3 and 2: the low-bit settings of the paper's Sec. 4.4)")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="time palu_encode_kv + palu_attn_decode instead of the one-call palu_decode_step")
     ap.add_argument("--no-probes", action="store_true", help="skip the bare MFMA / read probes (measured_peaks)")
     ap.add_argument("--no-rope", action="store_true",
                     help="the paper's non-RoPE attention (rope_theta = 0): the query is folded into the latent "
@@ -153,7 +155,7 @@ def main() -> int:
     new_k = torch.empty((batch, layer.R_k), dtype=torch.float16, device="cuda")
     new_v = torch.empty((batch, layer.R_v), dtype=torch.float16, device="cuda")
 
-    fused = not (k_i4 or v_i4)          # one call per step (append + attend); quantized caches take the separate calls
+    fused = not (k_i4 or v_i4 or args.separate_calls)          # one call per step (append + attend); quantized caches take the separate calls
 
     def step(i: int, events=None, decode_events=None):
         s = i % n_sets

@@ -1018,6 +1018,12 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       }
       f.head0 = h_lo;
       const dim3 g((unsigned)(wmax / 128), (unsigned)(h_hi - h_lo), (unsigned)ceil_div(batch, 4));
+      unsigned gq[3] = {0, 0, 0};
+      if (enc_pending) encode_partial_grid(*enc, gq);
+      if (enc_pending && (long long)g.x * g.y * g.z > (long long)gq[0] * gq[1] * gq[2]) {     // more items than workgroups to ride in
+        if ((st = launch_encode(act, *enc, s)) != PALU_OK) return st;
+        enc_pending = false;
+      }
       if (enc_pending) {
         // the new token's partial products with the query fold in their shadow, then the projection's second launch
         static thread_local StepHeadNoRopeArgs hn;
@@ -1100,8 +1106,17 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
       const dim3 g((unsigned)(max_r / 16), (unsigned)mk.n_heads, shared_key ? 1u : (unsigned)batch);
       if ((st = mark(0)) != PALU_OK) return st;
-      const bool fused_head = enc_pending;
-      if (enc_pending) {
+      // Fused only while every fold item finds a projection workgroup to ride in (one sequence of the 7B
+      // shape: 512 items, 512 workgroups); with more items than that the fold would dominate the launch.
+      unsigned ge0[3] = {0, 0, 0};
+      if (enc_pending) encode_partial_grid(*enc, ge0);
+      const long long fold_items = (long long)g.x * g.y * g.z + (shared_key ? (long long)mk.n_heads * batch : 0);
+      const bool fused_head = enc_pending && fold_items <= (long long)ge0[0] * ge0[1] * ge0[2];
+      if (enc_pending && !fused_head) {
+        if ((st = launch_encode(act, *enc, s)) != PALU_OK) return st;
+        enc_pending = false;
+      }
+      if (fused_head) {
         // the new token's partial products and the fold in one grid, then the projection's second launch
         static thread_local StepHeadArgs h;
         h.enc = enc->a;
