@@ -203,7 +203,8 @@ def test_latent_output_matches_oracle(theta, v_i4, cfg):
     assert err <= (TOL_I4 if v_i4 else TOL_FP)
 
 
-def test_decode_step_in_a_captured_graph():
+@pytest.mark.parametrize("one_call", [False, True])
+def test_decode_step_in_a_captured_graph(one_call):
     """Append + decode captured into a HIP graph (the calls allocate nothing and never
     synchronise): four replays with fresh inputs written into the captured buffers, each
     compared bit for bit with the same step launched eagerly in between."""
@@ -222,6 +223,10 @@ def test_decode_step_in_a_captured_graph():
 
     def step():
         s = torch.cuda.current_stream()
+        if one_call:          # palu_decode_step: the projection's first launch carries the query fold
+            P.palu_decode_step(desc, batch, seq, seq, x_buf, case.Ak, case.Av, dst_row, q_buf, case.q_pos, case.Hk[0],
+                               case.Hv[0], case.Bk, case.Bv, table, seq, out=out, workspace=ws, encode_workspace=ws_e, stream=s)
+            return
         P.palu_encode_kv(desc, x_buf, case.Ak, case.Av, case.Hk[0], layer.R_k, case.Hv[0], layer.R_v, dst_row, ws_e, stream=s)
         P.palu_attn_decode(desc, batch, seq, seq, q_buf, case.q_pos, case.Hk[0], case.Hv[0], case.Bk, case.Bv, table,
                            seq, out=out, workspace=ws, stream=s)
