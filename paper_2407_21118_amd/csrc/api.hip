@@ -939,6 +939,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   int split_tokens, n_split;
   split_geometry(pp.total_units, batch, seq_len, value_waves_per_cu(desc), &split_tokens, &n_split);
   if (n_split > kMaxSplits) return PALU_ERR_UNSUPPORTED;
+  // the value and no-RoPE kernels address a split of the cache with 32-bit byte offsets
+  if ((long long)split_tokens * std::max(Rk, Rv) * 2 >= (1LL << 32)) return PALU_ERR_UNSUPPORTED;
   const int n_split_cap = split_bound(pp.total_units, batch, max_seq, value_waves_per_cu(desc));
   Workspace w;
   carve(m, batch, max_seq, n_split_cap, 2 * sp.max_slices, &w);
@@ -1213,8 +1215,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       auto set_chunks = [&](int launch_units) {
         int n_chunks = std::max(1, std::min(tiles, (int)std::lround((double)device_cu_count() / (launch_units * batch))));
         if (g_opt_score_chunks > 0) n_chunks = std::min(tiles, (int)g_opt_score_chunks);
-        // the kernel addresses a chunk of the cache with 32-bit byte offsets
-        const long long chunk_limit_tiles = std::max(1LL, (1LL << 31) / ((long long)Rk * 2 * kTile));
+        // the kernel addresses a chunk of the cache with 32-bit byte offsets, and rows of it with 24-bit numbers
+        const long long chunk_limit_tiles = std::max(1LL, std::min<long long>((1LL << 31) / ((long long)Rk * 2 * kTile), (1LL << 24) / kTile));
         n_chunks = std::max(n_chunks, (int)ceil_div(tiles, (int)std::min<long long>(chunk_limit_tiles, tiles)));
         const int chunk_tiles = ceil_div(tiles, n_chunks);
         a.chunk_tokens = chunk_tiles * kTile;

@@ -34,12 +34,12 @@ def b_slice(flat, layer, which, j, heads):
     return np.ascontiguousarray(Bj[:, cols]).reshape(-1)
 
 
-def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP, no_rope=False, bits=4):
+def run_full(cfg, samples, k_i4=False, v_i4=False, tol=TOL_FP, no_rope=False, bits=4, seq=None):
     layer = None
     if no_rope:
         import dataclasses
         layer = dataclasses.replace(synth.config_layer(cfg.split("-")[0]), rope_theta=0.0)
-    case = wd.make_device_case(cfg, seed=0, n_sets=1, layer=layer)
+    case = wd.make_device_case(cfg, seed=0, n_sets=1, layer=layer, seq=seq)
     layer, B, L = case.layer, case.batch, case.seq
     say(f"[full] cfg {cfg} B={B} L={L} groups={layer.n_groups} R_k={layer.R_k} k_i4={k_i4} v_i4={v_i4}")
     desc = make_desc(layer, "f16", k_i4, v_i4, bits)
@@ -210,3 +210,63 @@ def test_full_config2_16k_four_query_tokens():
     whole, rows = rel_err(got[0, j, h_abs][None], ref)
     say(f"       oracle sample query {j} group {grp} heads {heads}: {whole:.3e}")
     assert whole <= TOL_FP and rows <= TOL_FP
+
+
+@pytest.mark.parametrize("quantized", [False, True])
+def test_cache_rows_beyond_4gib(quantized):
+    """Caches whose rows lie more than 4 GiB from the base pointer: few attended tokens per
+    sequence, but a row pitch (max_seq) that puts the later sequences beyond 32-bit byte
+    offsets.  Rows past a sequence's length hold NaN bit patterns: they must not reach
+    the result.  The oracle sees only the attended rows."""
+    layer = synth.uniform_layer(8, 4, 256)
+    B, L = (4, 1500) if quantized else (3, 2500)
+    max_seq = (6 << 20) if quantized else (3 << 20)
+    case = synth.make_case_svd(layer, B, L, seed=11, dtype="f16")
+    case.seq_lens = np.array([L, L - 723, L - 400, L - 1][:B], np.int32)
+    case.q_pos = (case.seq_lens - 1).astype(np.int32)
+    desc = make_desc(layer, "f16", quantized, quantized)
+    row_bytes = layer.R_k // 2 if quantized else layer.R_k * 2
+    assert (B - 1) * max_seq * row_bytes > (1 << 32)
+    say(f"[4gib] B={B} L={L} max_seq={max_seq} quantized={quantized}: {B * max_seq * row_bytes / 2**30:.1f} GiB per cache")
+    kw, quant = {}, {}
+    if quantized:
+        caches = []
+        for side, H in (("k", case.Hk), ("v", case.Hv)):
+            pk, s, z = O.quant_latent(H.reshape(B * L, -1))
+            quant[side] = (pk.reshape(B, L, -1), s.reshape(B, L, -1), z.reshape(B, L, -1))
+            codes = torch.full((B, max_seq, pk.shape[-1]), 0xFF, dtype=torch.uint8, device="cuda")
+            sc = torch.full((B, max_seq, s.shape[-1]), float("nan"), dtype=torch.float16, device="cuda")
+            zp = torch.full((B, max_seq, s.shape[-1]), float("nan"), dtype=torch.float16, device="cuda")
+            for b in range(B):
+                n = int(case.seq_lens[b])
+                codes[b, :n] = torch.from_numpy(quant[side][0][b, :n]).cuda()
+                sc[b, :n] = torch.from_numpy(quant[side][1][b, :n].view(np.int16)).cuda().view(torch.float16)
+                zp[b, :n] = torch.from_numpy(quant[side][2][b, :n].view(np.int16)).cuda().view(torch.float16)
+            caches.append(codes)
+            kw[f"h{side}_scale"], kw[f"h{side}_zero"] = sc, zp
+        hk, hv = caches
+    else:
+        hk = torch.full((B, max_seq, layer.R_k), float("nan"), dtype=torch.float16, device="cuda")
+        hv = torch.full((B, max_seq, layer.R_v), float("nan"), dtype=torch.float16, device="cuda")
+        for b in range(B):
+            n = int(case.seq_lens[b])
+            hk[b, :n] = torch.from_numpy(case.Hk[b, :n]).to(torch.float16).cuda()
+            hv[b, :n] = torch.from_numpy(case.Hv[b, :n]).to(torch.float16).cuda()
+    from gpu_util import run_oracle, to_dev
+    table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, L)
+    out = P.palu_attn_decode(desc, B, L, max_seq, to_dev(case.q, "f16"), torch.from_numpy(case.q_pos).cuda(), hk, hv,
+                             to_dev(case.Bk, "f16"), to_dev(case.Bv, "f16"), table, L,
+                             seq_lens=torch.from_numpy(case.seq_lens).cuda(), **kw)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    ref = run_oracle(case, quant if quantized else None, quantized, quantized)
+    whole, rows = rel_err(got, ref)
+    say(f"       rel err {whole:.3e} (rows {rows:.3e})")
+    assert max(whole, rows) <= (TOL_I4 if quantized else TOL_FP)
+
+
+def test_one_sequence_longer_than_4gib():
+    """One sequence of 1.2 M tokens in the 7B shape: 4.6 GiB of key latents attended in one
+    call, more splits than compute units, the value kernel's split count at its limit."""
+    run_full("2", [(0, 3, [2])], seq=1_200_007)
