@@ -61,6 +61,47 @@ def algorithmic_work(layer, batch, seq, k_i4, v_i4, bits=4):
     }
 
 
+def prompt_encode(args, P, torch) -> int:
+    """Cache fill from a prompt: x [N, d] . (A_k | A_v) -> latents, timed with events around `steps` calls."""
+    from workloads import synth
+    layer = synth.config_layer(args.config.split("-")[0])
+    desc = P.LayerDesc(layer.n_heads, layer.d_head, layer.group_head_off, layer.k_rank_off, layer.v_rank_off,
+                       P.PALU_F16, P.PALU_F16, P.PALU_F16, layer.quant_block, layer.rope_theta, layer.q_per_kv)
+    n, d = args.prompt_tokens, layer.n_q_heads * layer.d_head
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    x = torch.randn((n, d), generator=g, device="cuda").half()
+    Ak = (torch.randn((d, layer.R_k), generator=g, device="cuda") / d ** 0.5).half()
+    Av = (torch.randn((d, layer.R_v), generator=g, device="cuda") / d ** 0.5).half()
+    hk = torch.empty((n, layer.R_k), dtype=torch.float16, device="cuda")
+    hv = torch.empty((n, layer.R_v), dtype=torch.float16, device="cuda")
+    ws = torch.empty(max(16, P.palu_encode_workspace_bytes(desc, 2, n)), dtype=torch.uint8, device="cuda")
+
+    def call():
+        P.palu_encode_kv(desc, x, Ak, Av, hk, layer.R_k, hv, layer.R_v, None, ws)
+    for _ in range(args.warmup):
+        call()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    flops = 2.0 * n * d * (layer.R_k + layer.R_v)
+    ref = x[:64].float() @ Ak.float()
+    err = float((hk[:64].float() - ref).abs().max() / ref.abs().max())
+    print(json.dumps({"metric": "prompt_encode_tokens_per_s", "value": n / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+                      "dtype": "f16", "data": "synthetic",
+                      "config": {"workload": f"config {args.config} layer, {n}-token prompt, K and V projections"},
+                      "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": 2500.0,
+                                   "unit": "TFLOP/s", "frac": flops / (ms * 1e-3) / 2.5e15, "traffic": None},
+                      "max_rel_err_vs_fp32_matmul": err}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +124,9 @@ def main() -> int:
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="after the timed region also run a plain device copy of this size three times: "
                          "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--prompt-tokens", type=int, default=0, metavar="N",
+                    help="instead of the decode step, time the projection of an N-token prompt into both latent "
+                         "caches (palu_encode_kv on its tiled-GEMM path) and print its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -102,6 +146,9 @@ def main() -> int:
     for kv in args.opt:
         k, v = kv.split("=")
         P.palu_set_option(k, int(v))
+
+    if args.prompt_tokens > 0:
+        return prompt_encode(args, P, torch)
 
     cfg = args.config
     v_only = cfg == "4v"

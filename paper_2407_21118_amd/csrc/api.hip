@@ -594,6 +594,23 @@ inline int launch_ok() { return hipGetLastError() == hipSuccess ? PALU_OK : PALU
 
 }  // namespace
 
+// The prompt-sized projection: tile height by the number of tokens, tiles dealt to the XCDs in contiguous ranges.
+template <typename T, bool Q>
+int launch_encode_gemm_t(const EncodeArgs& a, int max_R, int n_sides, hipStream_t s) {
+  GemmGrid gg;
+  gg.n_col_tiles = ceil_div(max_R, kGemmCols);
+  int tm = 256;                    // the tallest tile that still gives every compute unit a workgroup
+  while (tm > 64 && gg.n_col_tiles * ceil_div(a.n_tok, tm) * n_sides < device_cu_count()) tm >>= 1;
+  gg.n_row_tiles = ceil_div(a.n_tok, tm);
+  gg.n_tiles = gg.n_col_tiles * gg.n_row_tiles * n_sides;
+  gg.per_xcd = ceil_div(gg.n_tiles, 8);
+  const size_t lds = gemm_lds_bytes(tm);
+  auto fn = tm == 256 ? encode_gemm_kernel<T, Q, 256> : tm == 128 ? encode_gemm_kernel<T, Q, 128> : encode_gemm_kernel<T, Q, 64>;
+  if (allow_lds(fn, lds) != PALU_OK) return PALU_ERR_HIP;
+  hipLaunchKernelGGL(fn, dim3((unsigned)(8 * gg.per_xcd)), dim3(256), lds, s, a, gg);
+  return launch_ok();
+}
+
 extern "C" {
 
 const char* palu_status_string(int status) {
@@ -745,20 +762,14 @@ int launch_encode_finish(int act, const EncodePlan& p, hipStream_t s) {
   return launch_ok();
 }
 
+int launch_encode_gemm(int act, const EncodeArgs& a, int max_R, int n_sides, bool quant, hipStream_t s) {
+  if (act == PALU_F16) return quant ? launch_encode_gemm_t<F16, true>(a, max_R, n_sides, s) : launch_encode_gemm_t<F16, false>(a, max_R, n_sides, s);
+  return quant ? launch_encode_gemm_t<BF16, true>(a, max_R, n_sides, s) : launch_encode_gemm_t<BF16, false>(a, max_R, n_sides, s);
+}
+
 int launch_encode(int act, const EncodePlan& p, hipStream_t s) {
   const EncodeArgs& a = p.a;
-  if (p.gemm) {
-    const size_t lds = (size_t)2 * kGemmTile * kGemmPitch * 2;
-    const dim3 g((unsigned)ceil_div(p.max_R, kGemmTile), (unsigned)ceil_div(a.n_tok, kGemmTile), (unsigned)p.n_sides);
-    if (act == PALU_F16) {
-      if (allow_lds(encode_gemm_kernel<F16, false>, lds) != PALU_OK) return PALU_ERR_HIP;
-      hipLaunchKernelGGL((encode_gemm_kernel<F16, false>), g, dim3(256), lds, s, a);
-    } else {
-      if (allow_lds(encode_gemm_kernel<BF16, false>, lds) != PALU_OK) return PALU_ERR_HIP;
-      hipLaunchKernelGGL((encode_gemm_kernel<BF16, false>), g, dim3(256), lds, s, a);
-    }
-    return launch_ok();
-  }
+  if (p.gemm) return launch_encode_gemm(act, a, p.max_R, p.n_sides, false, s);
   using EncFn = void (*)(EncodeArgs);
   static const EncFn partial_f16[4] = {encode_partial_kernel<F16, 1>, encode_partial_kernel<F16, 2>,
                                        encode_partial_kernel<F16, 4>, encode_partial_kernel<F16, 8>};
@@ -825,17 +836,7 @@ int palu_encode_quant(const palu_layer_desc* desc, int which, const void* x, int
   a.side[0].codes = codes;
   a.side[0].scale = static_cast<uint16_t*>(scale);
   a.side[0].zero = static_cast<uint16_t*>(zero);
-  const size_t lds = (size_t)2 * kGemmTile * kGemmPitch * 2;
-  const dim3 g((unsigned)(R / kGemmTile), (unsigned)ceil_div(n_tok, kGemmTile), 1u);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (desc->act_dtype == PALU_F16) {
-    if (allow_lds(encode_gemm_kernel<F16, true>, lds) != PALU_OK) return PALU_ERR_HIP;
-    hipLaunchKernelGGL((encode_gemm_kernel<F16, true>), g, dim3(256), lds, s, a);
-  } else {
-    if (allow_lds(encode_gemm_kernel<BF16, true>, lds) != PALU_OK) return PALU_ERR_HIP;
-    hipLaunchKernelGGL((encode_gemm_kernel<BF16, true>), g, dim3(256), lds, s, a);
-  }
-  return launch_ok();
+  return launch_encode_gemm(desc->act_dtype, a, R, 1, true, static_cast<hipStream_t>(stream));
 }
 
 // ------------------------------------------------------------------ quantize
