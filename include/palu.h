@@ -227,8 +227,9 @@ int palu_encode_quant(const palu_layer_desc* desc, int which, const void* x, int
  *   k_pos      DEVICE int32 [max_seq] position of cached row t, or NULL (row t is position t).
  *              Positions must lie in [0, rope_table_len); the kernels clamp to that
  *              range to stay in bounds, results for out-of-range positions are undefined
- *   seq_lens   DEVICE int32 [batch] rows to attend per sequence, each in [1, seq_len],
- *              or NULL (all seq_len rows)
+ *   seq_lens   DEVICE int32 [batch] rows to attend per sequence, each in [0, seq_len],
+ *              or NULL (all seq_len rows).  A sequence with 0 rows (an idle slot of the
+ *              batch) reads nothing from the caches and gets an output row of zeros
  *   seq_len    upper bound of rows attended (1 <= seq_len <= max_seq)
  *   Bk, Bv     DEVICE act_dtype; group j at element offset sum_{i<j} r_i s_i d_h,
  *              row-major [r_j, s_j d_h]
@@ -305,8 +306,9 @@ int palu_decode_step(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
  *   n_q        queries per sequence, n_heads * q_per_kv * n_q <= PALU_MAX_HEADS
  *   q          DEVICE [batch, n_q, n_heads*q_per_kv, d_head] act_dtype, before RoPE
  *   q_pos      DEVICE int32 [batch, n_q]
- *   q_len      DEVICE int32 [batch, n_q] rows attended by each query, in [1, seq_lens[b]]
- *              (seq_len where seq_lens is NULL), or NULL: every query attends all rows
+ *   q_len      DEVICE int32 [batch, n_q] rows attended by each query, in [0, seq_lens[b]]
+ *              (seq_len where seq_lens is NULL), or NULL: every query attends all rows.
+ *              A query with 0 rows gets zeros
  *   out        DEVICE float32 [batch, n_q, n_heads*q_per_kv, d_head]
  *   workspace  of palu_attn_decode_multi_workspace_bytes(desc, batch, n_q, max_seq) bytes
  * Everything else as for palu_attn_decode.

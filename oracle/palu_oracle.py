@@ -230,8 +230,12 @@ def reconstruct(H: np.ndarray, B_flat, group_head_off, rank_off, d_head: int) ->
 
 
 def softmax_rows(s: np.ndarray) -> np.ndarray:
-    """Softmax over the last axis, max-subtracted, float64."""
+    """Softmax over the last axis, max-subtracted, float64.  Over an empty axis
+    (a sequence with no cached row: the sums of Eq. 2 are empty) the result is
+    empty and every product with it is the empty sum, zero."""
     s = np.asarray(s, dtype=np.float64)
+    if s.shape[-1] == 0:
+        return np.zeros_like(s)
     e = np.exp(s - s.max(axis=-1, keepdims=True))
     return e / e.sum(axis=-1, keepdims=True)
 

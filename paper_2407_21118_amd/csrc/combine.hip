@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   const Meta& m = a.meta;
   const int h = blockIdx.x >> 2, quarter = blockIdx.x & 3, b = blockIdx.y;
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
-  const int nsp = (L + a.split_tokens - 1) / a.split_tokens;
+  const int nsp = L > 0 ? (L + a.split_tokens - 1) / a.split_tokens : 0;
   const int j = m.group_of_head[h];
   const int rv = m.v_off[j + 1] - m.v_off[j];
   int width;
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   block_reduce<1>(mx, red, true);
   float sum[1] = {0.f};
   for (int c = tid; c < nsp; c += 256) {
-    const float wc = exp2f(ml[c * ml_stride] - mx[0]);
+    const float wc = mx[0] == -INFINITY ? 0.f : exp2f(ml[c * ml_stride] - mx[0]);     // no split saw an attended row: all weights 0
     w[c] = wc;
     sum[0] += wc * ml[c * ml_stride + 1];
   }
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   if (a.out_latent) {          // output stays in the latent space: this workgroup writes its quarter of the head's r_v values
     float* ol = a.out_latent + (size_t)b * a.o_stride + o_head_off(m, h);
     const int per = ((rv >> 2) + 3) & ~3;
-    for (int k = quarter * per + tid; k < min(rv, (quarter + 1) * per); k += 256) ol[k] = olat[k] / sum[0];
+    for (int k = quarter * per + tid; k < min(rv, (quarter + 1) * per); k += 256) ol[k] = sum[0] > 0.f ? olat[k] / sum[0] : 0.f;
     return;
   }
 
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
     float s = 0.f;
 #pragma unroll
     for (int g = 0; g < 32; ++g) s += part[(g * 8 + c4) * 4 + e];
-    a.out[q_row(m, b, h) * kDHead + quarter * 32 + tid] = s / sum[0];
+    a.out[q_row(m, b, h) * kDHead + quarter * 32 + tid] = sum[0] > 0.f ? s / sum[0] : 0.f;   // no row attended: zeros
   }
 }
 

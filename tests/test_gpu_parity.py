@@ -350,3 +350,71 @@ def test_build_limits_256_heads_64_groups(theta):
     case = synth.make_case_orthonormal(layer, 1, 77, seed=88)
     case.name = f"256 heads / 64 groups theta={theta}"
     check(case, TOL_FP)
+
+
+@pytest.mark.parametrize("theta,i4", [(10000.0, False), (0.0, False), (10000.0, True), (0.0, True)])
+def test_idle_sequences_and_queries_give_zeros(theta, i4):
+    """A sequence with no cached row (an idle slot of the batch) and a query that attends no row get
+    output rows of zeros, exactly; their neighbours in the batch are unaffected.  Single-query call,
+    latent output and the several-queries call, with and without RoPE, fp16 and 4-bit latents."""
+    import paper_2407_21118_amd as P
+    from gpu_util import make_desc, to_dev
+    layer = synth.Layer(8, 128, [0, 4, 8], [0, 256, 384], [0, 128, 384], rope_theta=theta)
+    B, L, n_q = 3, 200, 3
+    case = synth.make_case_orthonormal(layer, B, L, seed=77)
+    lens = np.array([L, 0, 57], np.int32)
+    case.seq_lens, case.q_pos = lens, np.maximum(lens - 1, 0).astype(np.int32)
+    say(f"[idle] theta={theta} int4={i4} lens={lens.tolist()}")
+    quant = {"k": O.quant_latent(case.Hk), "v": O.quant_latent(case.Hv)} if i4 else None
+    tol = TOL_I4 if i4 else TOL_FP
+    got = run_hip(case, k_i4=i4, v_i4=i4, quant=quant)
+    ref = run_oracle(case, quant, i4, i4)
+    assert np.isfinite(got).all() and not got[1].any() and not ref[1].any()
+    live = [0, 2]
+    whole, rows = rel_err(got[live], ref[live])
+    say(f"       single query: rel err {whole:.3e}")
+    assert max(whole, rows) <= tol
+
+    desc = make_desc(layer, "f16", i4, i4)
+    kw, Hk_ref, Hv_ref = {}, case.Hk, case.Hv
+    if i4:
+        (pk, sk, zk), (pv, sv, zv) = quant["k"], quant["v"]
+        hk, hv = torch.from_numpy(pk).cuda(), torch.from_numpy(pv).cuda()
+        for name, arr in (("hk_scale", sk), ("hk_zero", zk), ("hv_scale", sv), ("hv_zero", zv)):
+            kw[name] = torch.from_numpy(arr.view(np.int16)).cuda().view(torch.float16)
+        Hk_ref, Hv_ref = O.dequant_latent(pk, sk, zk), O.dequant_latent(pv, sv, zv)
+    else:
+        hk, hv = to_dev(case.Hk, "f16"), to_dev(case.Hv, "f16")
+    table = P.palu_rope_table_init(theta, 128, L + 8)
+    d_lens, Bk, Bv = torch.from_numpy(lens).cuda(), to_dev(case.Bk, "f16"), to_dev(case.Bv, "f16")
+
+    lat = P.palu_attn_decode_latent(desc, B, L, L, to_dev(case.q, "f16"), torch.from_numpy(case.q_pos).cuda(), hk, hv, Bk,
+                                    table, L + 8, seq_lens=d_lens, **kw)
+    torch.cuda.synchronize()
+    lat = lat.cpu().numpy()
+    lat_ref = O.attn_decode_latent(case.q, case.q_pos, Hk_ref, Hv_ref, case.Bk, layer.group_head_off, layer.k_rank_off,
+                                   layer.v_rank_off, 128, theta, None, lens)
+    assert np.isfinite(lat).all() and not lat[1].any()
+    whole = np.abs(lat[live] - lat_ref[live]).max() / np.abs(lat_ref[live]).max()
+    say(f"       latent output: rel err {whole:.3e}")
+    assert whole <= tol
+
+    rng = np.random.default_rng([78, int(theta), int(i4)])
+    q = synth.round_to(rng.standard_normal((B, n_q, layer.n_q_heads, 128)), "f16")
+    q_len = np.array([[L, 0, 150], [0, 0, 0], [57, 20, 0]], np.int32)
+    q_pos = (np.maximum(q_len - 1, 0) + 3).astype(np.int32)
+    out = P.palu_attn_decode_multi(desc, B, n_q, L, L, to_dev(q, "f16"), torch.from_numpy(q_pos).cuda(), hk, hv, Bk, Bv,
+                                   table, L + 8, q_len=torch.from_numpy(q_len).cuda(), seq_lens=d_lens, **kw)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    mref = O.attn_decode_multi(q, q_pos, q_len, Hk_ref, Hv_ref, case.Bk, case.Bv, layer.group_head_off, layer.k_rank_off,
+                               layer.v_rank_off, 128, theta, None, 1)
+    assert np.isfinite(out).all()
+    for b in range(B):
+        for j in range(n_q):
+            if q_len[b, j] == 0:
+                assert not out[b, j].any() and not mref[b, j].any()
+            else:
+                whole, rows = rel_err(out[b, j][None], mref[b, j][None])
+                assert max(whole, rows) <= tol, (b, j, whole, rows)
+    say("       several queries: idle rows zero, the rest within tolerance")

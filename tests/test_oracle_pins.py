@@ -595,3 +595,16 @@ def test_planted_mistake_is_caught(monkeypatch, mutation):
         monkeypatch.setattr(O, "rope_rotate", inter)
     with pytest.raises(AssertionError):
         test_full_rank_orthogonal_equals_textbook_mha(2, 4)
+
+
+def test_empty_sequence_is_the_empty_sum():
+    """A sequence with no cached row: every sum of Eq. 2 is empty, the output is zero, and the
+    other sequences of the batch are what they are alone."""
+    layer = synth.Layer(4, 128, [0, 2, 4], [0, 128, 256], [0, 128, 192])
+    case = synth.make_case_orthonormal(layer, 2, 40, seed=3)
+    args = (layer.group_head_off, layer.k_rank_off, layer.v_rank_off, 128, 10000.0)
+    both = O.attn_decode(case.q, [0, 39], case.Hk, case.Hv, case.Bk, case.Bv, *args, None, np.array([0, 40]))
+    alone = O.attn_decode(case.q[1:], [39], case.Hk[1:], case.Hv[1:], case.Bk, case.Bv, *args, None, None)
+    assert not both[0].any()
+    np.testing.assert_array_equal(both[1], alone[0])
+    assert O.softmax_rows(np.zeros((3, 0))).shape == (3, 0)
