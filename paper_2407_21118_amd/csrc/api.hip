@@ -25,6 +25,7 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score workgroup (ranks <= 256)
 std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
 std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
+std::atomic<int> g_opt_encode_tile{0};        // token rows per workgroup of the prompt-sized projection
 
 int device_cu_count() {
   static std::atomic<int> cached[64];
@@ -601,6 +602,7 @@ int launch_encode_gemm_t(const EncodeArgs& a, int max_R, int n_sides, hipStream_
   gg.n_col_tiles = ceil_div(max_R, kGemmCols);
   int tm = 256;                    // the tallest tile that still gives every compute unit a workgroup
   while (tm > 64 && gg.n_col_tiles * ceil_div(a.n_tok, tm) * n_sides < device_cu_count()) tm >>= 1;
+  if (g_opt_encode_tile > 0) tm = g_opt_encode_tile;
   gg.n_row_tiles = ceil_div(a.n_tok, tm);
   gg.n_tiles = gg.n_col_tiles * gg.n_row_tiles * n_sides;
   gg.per_xcd = ceil_div(gg.n_tiles, 8);
@@ -651,6 +653,9 @@ int palu_set_option(const char* name, int value) {
   } else if (!std::strcmp(name, "value_split_tokens")) {
     if (value != 0 && (value % 32 != 0 || value > 4096)) return PALU_ERR_INVALID_ARG;
     g_opt_value_split = value;
+  } else if (!std::strcmp(name, "encode_tile_rows")) {
+    if (value != 0 && value != 64 && value != 128 && value != 256) return PALU_ERR_INVALID_ARG;
+    g_opt_encode_tile = value;
   } else {
     return PALU_ERR_INVALID_ARG;
   }

@@ -252,12 +252,24 @@ def test_decode_step_in_a_captured_graph(one_call):
         assert torch.equal(got, out)
 
 
-@pytest.mark.parametrize("dtype,n_tok", [("f16", 64), ("f16", 300), ("bf16", 129)])
-def test_encode_many_tokens_gemm_path(dtype, n_tok):
+@pytest.fixture
+def encode_tile(request):
+    """Forces the projection's tile height (the library picks it from the token count: the tall
+    tiles are otherwise reached only by prompts of thousands of tokens)."""
+    P.palu_set_option("encode_tile_rows", request.param)
+    yield request.param
+    P.palu_set_option("encode_tile_rows", 0)
+
+
+@pytest.mark.parametrize("dtype,n_tok,encode_tile", [("f16", 64, 0), ("f16", 300, 0), ("bf16", 129, 0), ("f16", 300, 128),
+                                                     ("f16", 300, 256), ("bf16", 700, 256), ("bf16", 129, 128)],
+                         indirect=["encode_tile"])
+def test_encode_many_tokens_gemm_path(dtype, n_tok, encode_tile):
     """Prompt-sized append: from 64 tokens on palu_encode runs as a tiled GEMM on the matrix
-    cores.  A layer whose total rank (1344) is not a multiple of the 128-column tile, a
-    ragged token count, scattered destination rows; palu_encode_kv covers both sides."""
-    say(f"[encode-gemm] dtype={dtype} n_tok={n_tok}")
+    cores.  A layer whose total rank (1344) is not a multiple of the 256-column tile, a
+    ragged token count, scattered destination rows, every tile height; palu_encode_kv covers
+    both sides."""
+    say(f"[encode-gemm] dtype={dtype} n_tok={n_tok} tile rows={encode_tile or 'auto'}")
     k_ranks = [32, 64, 128, 96, 128, 384, 512]
     v_ranks = [64, 32, 128, 256, 96, 128, 512]
     layer = synth.Layer(16, 128, [0, 1, 2, 4, 6, 7, 10, 16], [0] + list(np.cumsum(k_ranks)), [0] + list(np.cumsum(v_ranks)))
@@ -284,14 +296,16 @@ def test_encode_many_tokens_gemm_path(dtype, n_tok):
         assert (got[untouched] == 7.0).all() and (got[:, R:] == 7.0).all()
 
 
-@pytest.mark.parametrize("dtype,n_tok", [("f16", 1), ("f16", 64), ("f16", 300), ("bf16", 129)])
-def test_encode_quant_fused(dtype, n_tok):
+@pytest.mark.parametrize("dtype,n_tok,encode_tile", [("f16", 1, 0), ("f16", 64, 0), ("f16", 300, 0), ("bf16", 129, 0),
+                                                     ("f16", 300, 128), ("f16", 600, 256), ("bf16", 300, 256)],
+                         indirect=["encode_tile"])
+def test_encode_quant_fused(dtype, n_tok, encode_tile):
     """Down-projection with the quantizer fused into the GEMM's write-out.  Two checks:
     the dequantized cache is within half a quantization step (plus the rounding of the
     latent) of the oracle's float64 product; and, where palu_encode runs the same GEMM
     (n_tok >= 64), codes, scales and zero-points are bit for bit what the oracle's
     quantizer gives for the latents that call stores."""
-    say(f"[encode-quant] dtype={dtype} n_tok={n_tok}")
+    say(f"[encode-quant] dtype={dtype} n_tok={n_tok} tile rows={encode_tile or 'auto'}")
     layer = synth.config_layer("4")
     rng = np.random.default_rng(12)
     d = layer.n_heads * layer.d_head
