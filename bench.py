@@ -115,6 +115,8 @@ def main() -> int:
     ap.add_argument("--opt", action="append", default=[], help="tuning knob name=value (palu_set_option)")
     ap.add_argument("--latent-bits", type=int, default=4, choices=(4, 3, 2),
                     help="config 4 / 4v: bits per quantized latent code (3 and 2: the low-bit settings of the paper's Sec. 4.4)")
+    ap.add_argument("--row-major-weights", action="store_true",
+                    help="give the step A_k, A_v as [d, R] (palu_decode_step) instead of transposed, [R, d] (palu_decode_step_t)")
     ap.add_argument("--separate-calls", action="store_true",
                     help="time palu_encode_kv + palu_attn_decode instead of the one-call palu_decode_step")
     ap.add_argument("--no-probes", action="store_true", help="skip the bare MFMA / read probes (measured_peaks)")
@@ -203,9 +205,16 @@ def main() -> int:
     new_v = torch.empty((batch, layer.R_v), dtype=torch.float16, device="cuda")
 
     fused = not (k_i4 or v_i4 or args.separate_calls)          # one call per step (append + attend); quantized caches take the separate calls
+    transposed = fused and not args.row_major_weights and batch < 64
+    if transposed:                                             # the projection weights column by column: made once, like the decomposition
+        Akt, Avt = case.Ak.t().contiguous(), case.Av.t().contiguous()
 
     def step(i: int, events=None, decode_events=None):
         s = i % n_sets
+        if transposed and events is None and decode_events is None:
+            P.palu_decode_step_t(desc, batch, seq, seq, case.x_new, Akt, Avt, dst_row, case.q, case.q_pos,
+                                 case.Hk[s], case.Hv[s], case.Bk, case.Bv, table, seq, out=out, workspace=ws)
+            return
         if fused and events is None and decode_events is None:
             P.palu_decode_step(desc, batch, seq, seq, case.x_new, case.Ak, case.Av, dst_row, case.q, case.q_pos,
                                case.Hk[s], case.Hv[s], case.Bk, case.Bv, table, seq, out=out, workspace=ws,
@@ -300,7 +309,8 @@ def main() -> int:
                                f"{layer.n_groups} groups, R_k {layer.R_k}, R_v {layer.R_v}",
                    "batch": batch, "seq_len": seq, "n_heads": layer.n_heads, "q_per_kv": layer.q_per_kv, "group_size": layer.group_size(0),
                    "cache_sets": n_sets,
-                   "step": ("palu_decode_step: encode K + encode V + attn_decode in one call" if fused
+                   "step": ("palu_decode_step_t: encode K + encode V (transposed weights) + attn_decode in one call" if transposed
+                            else "palu_decode_step: encode K + encode V + attn_decode in one call" if fused
                             else "encode K + encode V + quantize + attn_decode")},
         "roofline": {
             "kernel": "score_kernel (key reconstruction + RoPE + q.K on MFMA)",

@@ -167,6 +167,26 @@ int palu_encode_kv(const palu_layer_desc* desc, const void* x, int32_t n_tok, co
                    const int32_t* dst_row, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * palu_encode_kv from transposed weights: Akt = A_k^T [R_k, n_heads*d_head] and
+ * Avt = A_v^T [R_v, n_heads*d_head], row-major, so that the weights of one latent
+ * channel are contiguous (h = x A of Sec. 3.1 with A stored column by column; the
+ * projection matrices are fixed after the decomposition, so this layout is made once,
+ * offline).  A wavefront then owns whole columns and finishes their sums by itself:
+ * one launch, no workspace, no partial sums in memory - for the few tokens of a decode
+ * step this is about twice as fast as the row-major form (it pays up to about 8
+ * tokens; beyond that the row-major form is the faster one).
+ *   n_tok       1 <= n_tok < 64 (a prompt goes through palu_encode / palu_encode_kv)
+ *   hk, hv      DEVICE caches, act_dtype; 2-byte aligned, any row stride >= R
+ * Everything else as for palu_encode_kv.  Accumulates in float32, rounds once to
+ * act_dtype; the order of the sum differs from palu_encode_kv, so the two can differ
+ * in the last bit of a latent.  PALU_ERR_UNSUPPORTED for quantized caches, for
+ * n_tok >= 64 and for models wider than 32768 (n_heads*d_head).
+ */
+int palu_encode_kv_t(const palu_layer_desc* desc, const void* x, int32_t n_tok, const void* Akt, const void* Avt,
+                     void* hk, int64_t hk_row_stride_elems, void* hv, int64_t hv_row_stride_elems,
+                     const int32_t* dst_row, void* stream);
+
+/*
  * Asymmetric uniform B-bit quantization of latent rows (Appendix A), one (scale, zero)
  * pair per token per quant_block channels; B = 4, 3 or 2 as the side's latent dtype
  * says (PALU_I4 / PALU_I3 / PALU_I2; 4 where the side is not declared quantized):
@@ -294,6 +314,21 @@ int palu_decode_step(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
                      const void* Bk, const void* Bv,
                      const void* rope_table, int32_t rope_table_len,
                      float* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * palu_decode_step from transposed weights (palu_encode_kv_t followed by
+ * palu_attn_decode, in one call): the projection is one launch, and where the step
+ * folds the query into B_k that fold rides in the projection's workgroups, so the
+ * whole append costs one launch.  No encode workspace.  Arguments as for
+ * palu_decode_step with Akt, Avt as for palu_encode_kv_t; batch < 64.
+ */
+int palu_decode_step_t(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                       const void* x, const void* Akt, const void* Avt, const int32_t* dst_row,
+                       const void* q, const int32_t* q_pos, void* hk, void* hv,
+                       const int32_t* k_pos, const int32_t* seq_lens,
+                       const void* Bk, const void* Bv,
+                       const void* rope_table, int32_t rope_table_len,
+                       float* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Several new query tokens per sequence in one call (a block of a chunked prompt,

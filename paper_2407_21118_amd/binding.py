@@ -96,6 +96,11 @@ def load_library():
     lib.palu_decode_step.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                      vp, vp, sz, vp]
     lib.palu_decode_step.restype = ctypes.c_int
+    lib.palu_encode_kv_t.argtypes = [dp, vp, i32, vp, vp, vp, i64, vp, i64, vp, vp]
+    lib.palu_encode_kv_t.restype = ctypes.c_int
+    lib.palu_decode_step_t.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                       vp, vp, sz, vp]
+    lib.palu_decode_step_t.restype = ctypes.c_int
     for name in ("palu_rope_table_bytes", "palu_rope_table_init", "palu_encode_workspace_bytes", "palu_encode",
                  "palu_quant_latent", "palu_attn_decode_workspace_bytes", "palu_attn_decode"):
         getattr(lib, name).restype = ctypes.c_int
@@ -338,6 +343,35 @@ def palu_attn_decode_multi(desc: LayerDesc, batch: int, n_q: int, seq_len: int, 
                                       int(rope_table_len), _ptr(out), _ptr(workspace),
                                       workspace.numel() * workspace.element_size(), _stream(stream)),
            "palu_attn_decode_multi")
+    return out
+
+
+def palu_encode_kv_t(desc: LayerDesc, x, Akt, Avt, hk, hk_row_stride_elems: int, hv, hv_row_stride_elems: int,
+                     dst_row=None, stream=None):
+    """palu_encode_kv from transposed weights Akt [R_k, d], Avt [R_v, d]; fewer than 64 tokens, no workspace."""
+    n_tok = int(x.shape[0])
+    _need_cuda(x, Akt, Avt, hk, hv, dst_row)
+    _check(load_library().palu_encode_kv_t(desc.ref(), _ptr(x), n_tok, _ptr(Akt), _ptr(Avt), _ptr(hk),
+                                           int(hk_row_stride_elems), _ptr(hv),
+                                           int(hv_row_stride_elems), _ptr(dst_row), _stream(stream)),
+           "palu_encode_kv_t")
+
+
+def palu_decode_step_t(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, x, Akt, Avt, dst_row, q, q_pos, hk, hv,
+                       Bk, Bv, rope_table, rope_table_len: int, out=None, workspace=None, k_pos=None, seq_lens=None,
+                       stream=None):
+    """palu_decode_step from transposed weights (Akt [R_k, d], Avt [R_v, d])."""
+    import torch
+    if out is None:
+        out = torch.empty((batch, desc.n_q_heads, desc.d_head), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(palu_attn_decode_workspace_bytes(desc, batch, max_seq), dtype=torch.uint8,
+                                device=q.device)
+    _need_cuda(x, Akt, Avt, dst_row, q, q_pos, hk, hv, Bk, Bv, rope_table, out, workspace, k_pos, seq_lens)
+    _check(load_library().palu_decode_step_t(
+        desc.ref(), batch, seq_len, max_seq, _ptr(x), _ptr(Akt), _ptr(Avt), _ptr(dst_row), _ptr(q), _ptr(q_pos),
+        _ptr(hk), _ptr(hv), _ptr(k_pos), _ptr(seq_lens), _ptr(Bk), _ptr(Bv), _ptr(rope_table), int(rope_table_len),
+        _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "palu_decode_step_t")
     return out
 
 

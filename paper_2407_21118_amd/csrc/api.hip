@@ -368,6 +368,16 @@ int carve(const Meta& m, int batch, int max_seq, int n_split_cap, int n_parts, W
   return PALU_OK;
 }
 
+// Dynamic LDS next to a kernel's static arrays (at most kStaticLdsMax bytes of them): past 64 KiB in total the
+// kernel's limit has to be raised.
+constexpr size_t kStaticLdsMax = 16 * 1024;
+template <typename K>
+int allow_dynamic_lds(K kernel, size_t dynamic_bytes) {
+  if (dynamic_bytes + kStaticLdsMax <= 64 * 1024) return PALU_OK;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)dynamic_bytes) == hipSuccess ? PALU_OK : PALU_ERR_HIP;
+}
+
 template <typename K>
 int allow_lds(K kernel, size_t bytes) {
   if (bytes <= 64 * 1024) return PALU_OK;
@@ -507,6 +517,7 @@ PvFn pv_fn(int act, int bits, int cls) {
 // after their weight loads have gone out; items beyond the projection's grid get workgroups of their own.
 struct StepHeadArgs {
   EncodeArgs enc;
+  EncodeTArgs enc_t;                     // TR instantiations: the projection from transposed weights, grid (enc_blocks)
   FoldArgs fold;
   int fold_blocks, fold_gx, fold_gy;     // fold grid (k-steps, heads, batch), linearised
   int enc_blocks, enc_gx, enc_gy;        // projection grid (column blocks, k splits, sides), linearised
@@ -517,7 +528,7 @@ struct StepHeadArgs {
   int sk_blocks, sk_n_kv, sk_qpk, sk_nq, sk_n_heads, sk_small;
 };
 
-template <typename T, int kEncTok>
+template <typename T, int kEncTok, bool TR>
 __global__ __launch_bounds__(256) void step_head_kernel(StepHeadArgs a) {
   const int id = blockIdx.x;
   auto fold_item = [&]() __attribute__((always_inline)) {
@@ -542,8 +553,12 @@ __global__ __launch_bounds__(256) void step_head_kernel(StepHeadArgs a) {
     }
   };
   if (id < a.enc_blocks) {
-    const int bx = id % a.enc_gx, rest = id / a.enc_gx;
-    encode_partial_body<T, kEncTok>(a.enc, bx, rest % a.enc_gy, rest / a.enc_gy, fold_item);
+    if constexpr (TR) {
+      encode_t_body<T, kEncTok>(a.enc_t, id, fold_item);
+    } else {
+      const int bx = id % a.enc_gx, rest = id / a.enc_gx;
+      encode_partial_body<T, kEncTok>(a.enc, bx, rest % a.enc_gy, rest / a.enc_gy, fold_item);
+    }
   } else {
     fold_item();
   }
@@ -552,12 +567,13 @@ __global__ __launch_bounds__(256) void step_head_kernel(StepHeadArgs a) {
 // The same for non-RoPE attention: the items are those of qfold_kernel (query folded into the latent space).
 struct StepHeadNoRopeArgs {
   EncodeArgs enc;
+  EncodeTArgs enc_t;
   QfoldArgs qfold;
   int q_blocks, q_gx, q_gy;              // qfold grid (column blocks, heads, batch / 4), linearised
   int enc_blocks, enc_gx, enc_gy;
 };
 
-template <typename T, int kEncTok>
+template <typename T, int kEncTok, bool TR>
 __global__ __launch_bounds__(256) void step_head_norope_kernel(StepHeadNoRopeArgs a) {
   const int id = blockIdx.x;
   auto item = [&]() __attribute__((always_inline)) {
@@ -567,29 +583,31 @@ __global__ __launch_bounds__(256) void step_head_norope_kernel(StepHeadNoRopeArg
     }
   };
   if (id < a.enc_blocks) {
-    const int bx = id % a.enc_gx, rest = id / a.enc_gx;
-    encode_partial_body<T, kEncTok>(a.enc, bx, rest % a.enc_gy, rest / a.enc_gy, item);
+    if constexpr (TR) {
+      encode_t_body<T, kEncTok>(a.enc_t, id, item);
+    } else {
+      const int bx = id % a.enc_gx, rest = id / a.enc_gx;
+      encode_partial_body<T, kEncTok>(a.enc, bx, rest % a.enc_gy, rest / a.enc_gy, item);
+    }
   } else {
     item();
   }
 }
 
 using StepHeadNoRopeFn = void (*)(StepHeadNoRopeArgs);
-StepHeadNoRopeFn step_head_norope_fn(int act, int tok_cls) {
-  static const StepHeadNoRopeFn f16[4] = {step_head_norope_kernel<F16, 1>, step_head_norope_kernel<F16, 2>,
-                                          step_head_norope_kernel<F16, 4>, step_head_norope_kernel<F16, 8>};
-  static const StepHeadNoRopeFn bf16[4] = {step_head_norope_kernel<BF16, 1>, step_head_norope_kernel<BF16, 2>,
-                                           step_head_norope_kernel<BF16, 4>, step_head_norope_kernel<BF16, 8>};
-  return act == PALU_F16 ? f16[tok_cls] : bf16[tok_cls];
+StepHeadNoRopeFn step_head_norope_fn(int act, int tok_cls, bool tr) {
+#define PALU_SH(K, T, TR) {K<T, 1, TR>, K<T, 2, TR>, K<T, 4, TR>, K<T, 8, TR>}
+  static const StepHeadNoRopeFn f16[2][4] = {PALU_SH(step_head_norope_kernel, F16, false), PALU_SH(step_head_norope_kernel, F16, true)};
+  static const StepHeadNoRopeFn bf16[2][4] = {PALU_SH(step_head_norope_kernel, BF16, false), PALU_SH(step_head_norope_kernel, BF16, true)};
+  return act == PALU_F16 ? f16[tr][tok_cls] : bf16[tr][tok_cls];
 }
 
 using StepHeadFn = void (*)(StepHeadArgs);
-StepHeadFn step_head_fn(int act, int tok_cls) {
-  static const StepHeadFn f16[4] = {step_head_kernel<F16, 1>, step_head_kernel<F16, 2>, step_head_kernel<F16, 4>,
-                                    step_head_kernel<F16, 8>};
-  static const StepHeadFn bf16[4] = {step_head_kernel<BF16, 1>, step_head_kernel<BF16, 2>, step_head_kernel<BF16, 4>,
-                                     step_head_kernel<BF16, 8>};
-  return act == PALU_F16 ? f16[tok_cls] : bf16[tok_cls];
+StepHeadFn step_head_fn(int act, int tok_cls, bool tr) {
+  static const StepHeadFn f16[2][4] = {PALU_SH(step_head_kernel, F16, false), PALU_SH(step_head_kernel, F16, true)};
+  static const StepHeadFn bf16[2][4] = {PALU_SH(step_head_kernel, BF16, false), PALU_SH(step_head_kernel, BF16, true)};
+#undef PALU_SH
+  return act == PALU_F16 ? f16[tr][tok_cls] : bf16[tr][tok_cls];
 }
 inline int launch_ok() { return hipGetLastError() == hipSuccess ? PALU_OK : PALU_ERR_HIP; }
 
@@ -706,7 +724,11 @@ struct EncodePlan {
   EncodeArgs a;
   bool gemm;              // many tokens: tiled GEMM, no workspace
   int n_sides, max_R;
-  int tok_cls;            // split-K form: 8, 4, 2 or 1 tokens per pass (index 3 .. 0)
+  int tok_cls;            // split-K and transposed forms: 8, 4, 2 or 1 tokens per pass (index 3 .. 0)
+  bool transposed;        // weights given as At [R, d]: one launch, no partial sums (t, t_lds, t_blocks)
+  EncodeTArgs t;
+  size_t t_lds;
+  unsigned t_blocks;
 };
 
 int plan_encode(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x, int32_t n_tok,
@@ -720,6 +742,7 @@ int plan_encode(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x
   const int d = m.n_heads * PALU_D_HEAD;
   p->gemm = n_tok >= kEncodeGemmTokens;
   if (reinterpret_cast<uintptr_t>(x) & 15) return PALU_ERR_INVALID_ARG;
+  p->transposed = false;
   EncodeArgs& a = p->a;
   std::memset(&a, 0, sizeof(a));
   a.x = static_cast<const uint16_t*>(x);
@@ -752,8 +775,56 @@ int plan_encode(const palu_layer_desc* desc, bool do_k, bool do_v, const void* x
   return PALU_OK;
 }
 
-// grid of the split-K form's first launch: (column blocks, k splits, sides)
+// The same for transposed weights (Akt [R_k, d], Avt [R_v, d]), both sides, fewer than kEncodeGemmTokens tokens.
+int plan_encode_t(const palu_layer_desc* desc, const void* x, int32_t n_tok, const void* Akt, const void* Avt,
+                  void* hk, int64_t hk_stride, void* hv, int64_t hv_stride, const int32_t* dst_row, EncodePlan* p) {
+  Meta m;
+  const int st = check_desc(desc, &m);
+  if (st != PALU_OK) return st;
+  if (!x || !Akt || !Avt || !hk || !hv || n_tok <= 0) return PALU_ERR_INVALID_ARG;
+  if (n_tok >= kEncodeGemmTokens) return PALU_ERR_UNSUPPORTED;
+  if (latent_bits(desc->k_latent_dtype) || latent_bits(desc->v_latent_dtype)) return PALU_ERR_UNSUPPORTED;
+  const int d = m.n_heads * PALU_D_HEAD;
+  const int Rk = m.k_off[m.n_groups], Rv = m.v_off[m.n_groups];
+  if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(Akt) & 15) || (reinterpret_cast<uintptr_t>(Avt) & 15) ||
+      (reinterpret_cast<uintptr_t>(hk) & 1) || (reinterpret_cast<uintptr_t>(hv) & 1) || hk_stride < Rk || hv_stride < Rv)
+    return PALU_ERR_INVALID_ARG;
+  std::memset(&p->a, 0, sizeof(p->a));
+  p->gemm = false;
+  p->transposed = true;
+  p->n_sides = 2;
+  p->max_R = std::max(Rk, Rv);
+  EncodeTArgs& a = p->t;
+  a.x = static_cast<const uint16_t*>(x);
+  a.dst_row = dst_row;
+  a.At[0] = static_cast<const uint16_t*>(Akt);
+  a.At[1] = static_cast<const uint16_t*>(Avt);
+  a.latent[0] = static_cast<uint16_t*>(hk);
+  a.latent[1] = static_cast<uint16_t*>(hv);
+  a.row_stride[0] = hk_stride;
+  a.row_stride[1] = hv_stride;
+  a.R[0] = Rk;
+  a.R[1] = Rv;
+  a.n_tok = n_tok;
+  a.d = d;
+  // tokens per pass over the weights: as many as n_tok asks for, up to 8, while their activations fit 64 KiB of LDS
+  int tok = 1, cls = 0;
+  while (tok < 8 && tok < n_tok && (size_t)(2 * tok) * d * 2 <= 64 * 1024) tok <<= 1, ++cls;
+  if ((size_t)tok * d * 2 > 64 * 1024) return PALU_ERR_UNSUPPORTED;
+  p->tok_cls = cls;
+  p->t_lds = tok <= 2 ? 0 : (size_t)tok * d * 2;      // one or two tokens per pass stay in registers
+  a.wg_side1 = ceil_div(Rk, 4 * kTCols);
+  p->t_blocks = (unsigned)(a.wg_side1 + ceil_div(Rv, 4 * kTCols));
+  return PALU_OK;
+}
+
+// grid of the projection's first (transposed weights: only) launch: (column blocks, k splits, sides)
 void encode_partial_grid(const EncodePlan& p, unsigned g[3]) {
+  if (p.transposed) {
+    g[0] = p.t_blocks;
+    g[1] = g[2] = 1;
+    return;
+  }
   g[0] = (unsigned)ceil_div(p.max_R, kEncCols);
   g[1] = (unsigned)p.a.k_splits;
   g[2] = (unsigned)p.n_sides;
@@ -761,6 +832,7 @@ void encode_partial_grid(const EncodePlan& p, unsigned g[3]) {
 
 // second launch of the split-K form: sum the partials, round, scatter the rows
 int launch_encode_finish(int act, const EncodePlan& p, hipStream_t s) {
+  if (p.transposed) return PALU_OK;         // nothing left to sum
   const dim3 g2((unsigned)ceil_div(p.max_R, 64), (unsigned)p.a.n_tok, (unsigned)p.n_sides);
   if (act == PALU_F16) hipLaunchKernelGGL(encode_finish_kernel<F16>, g2, dim3(256), 0, s, p.a);
   else hipLaunchKernelGGL(encode_finish_kernel<BF16>, g2, dim3(256), 0, s, p.a);
@@ -775,6 +847,13 @@ int launch_encode_gemm(int act, const EncodeArgs& a, int max_R, int n_sides, boo
 int launch_encode(int act, const EncodePlan& p, hipStream_t s) {
   const EncodeArgs& a = p.a;
   if (p.gemm) return launch_encode_gemm(act, a, p.max_R, p.n_sides, false, s);
+  if (p.transposed) {
+    using EncTFn = void (*)(EncodeTArgs);
+    static const EncTFn t_f16[4] = {encode_t_kernel<F16, 1>, encode_t_kernel<F16, 2>, encode_t_kernel<F16, 4>, encode_t_kernel<F16, 8>};
+    static const EncTFn t_bf16[4] = {encode_t_kernel<BF16, 1>, encode_t_kernel<BF16, 2>, encode_t_kernel<BF16, 4>, encode_t_kernel<BF16, 8>};
+    hipLaunchKernelGGL(act == PALU_F16 ? t_f16[p.tok_cls] : t_bf16[p.tok_cls], dim3(p.t_blocks), dim3(256), p.t_lds, s, p.t);
+    return launch_ok();
+  }
   using EncFn = void (*)(EncodeArgs);
   static const EncFn partial_f16[4] = {encode_partial_kernel<F16, 1>, encode_partial_kernel<F16, 2>,
                                        encode_partial_kernel<F16, 4>, encode_partial_kernel<F16, 8>};
@@ -812,6 +891,16 @@ int palu_encode_kv(const palu_layer_desc* desc, const void* x, int32_t n_tok, co
                    const int32_t* dst_row, void* workspace, size_t workspace_bytes, void* stream) {
   return encode_impl(desc, true, true, x, n_tok, Ak, Av, hk, hk_row_stride_elems, hv, hv_row_stride_elems,
                      dst_row, workspace, workspace_bytes, stream);
+}
+
+int palu_encode_kv_t(const palu_layer_desc* desc, const void* x, int32_t n_tok, const void* Akt, const void* Avt,
+                     void* hk, int64_t hk_row_stride_elems, void* hv, int64_t hv_row_stride_elems,
+                     const int32_t* dst_row, void* stream) {
+  if (!desc) return PALU_ERR_INVALID_ARG;
+  static thread_local EncodePlan p;
+  const int st = plan_encode_t(desc, x, n_tok, Akt, Avt, hk, hk_row_stride_elems, hv, hv_row_stride_elems, dst_row, &p);
+  if (st != PALU_OK) return st;
+  return launch_encode(desc->act_dtype, p, static_cast<hipStream_t>(stream));
 }
 
 int palu_encode_quant(const palu_layer_desc* desc, int which, const void* x, int32_t n_tok, const void* A,
@@ -1036,6 +1125,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         // the new token's partial products with the query fold in their shadow, then the projection's second launch
         static thread_local StepHeadNoRopeArgs hn;
         hn.enc = enc->a;
+        hn.enc_t = enc->t;
         hn.qfold = f;
         hn.q_gx = (int)g.x;
         hn.q_gy = (int)g.y;
@@ -1045,8 +1135,10 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         hn.enc_gx = (int)ge[0];
         hn.enc_gy = (int)ge[1];
         hn.enc_blocks = (int)(ge[0] * ge[1] * ge[2]);
-        hipLaunchKernelGGL(step_head_norope_fn(act, enc->tok_cls), dim3((unsigned)std::max(hn.q_blocks, hn.enc_blocks)),
-                           dim3(256), 0, s, hn);
+        const StepHeadNoRopeFn hfn = step_head_norope_fn(act, enc->tok_cls, enc->transposed);
+        const size_t hlds = enc->transposed ? enc->t_lds : 0;
+        if ((st = allow_dynamic_lds(hfn, hlds)) != PALU_OK) return st;
+        hipLaunchKernelGGL(hfn, dim3((unsigned)std::max(hn.q_blocks, hn.enc_blocks)), dim3(256), hlds, s, hn);
         if ((st = launch_ok()) != PALU_OK) return st;
         if ((st = launch_encode_finish(act, *enc, s)) != PALU_OK) return st;
         enc_pending = false;
@@ -1128,6 +1220,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         // the new token's partial products and the fold in one grid, then the projection's second launch
         static thread_local StepHeadArgs h;
         h.enc = enc->a;
+        h.enc_t = enc->t;
         h.fold = a;
         h.fold_gx = (int)g.x;
         h.fold_gy = (int)g.y;
@@ -1150,8 +1243,10 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
           h.sk_small = m.qpk <= 4 ? 1 : 0;
           h.sk_blocks = mk.n_heads * batch;
         }
-        hipLaunchKernelGGL(step_head_fn(act, enc->tok_cls), dim3((unsigned)std::max(h.fold_blocks + h.sk_blocks, h.enc_blocks)),
-                           dim3(256), 0, s, h);
+        const StepHeadFn hfn = step_head_fn(act, enc->tok_cls, enc->transposed);
+        const size_t hlds = enc->transposed ? enc->t_lds : 0;
+        if ((st = allow_dynamic_lds(hfn, hlds)) != PALU_OK) return st;
+        hipLaunchKernelGGL(hfn, dim3((unsigned)std::max(h.fold_blocks + h.sk_blocks, h.enc_blocks)), dim3(256), hlds, s, h);
         if ((st = launch_ok()) != PALU_OK) return st;
         if ((st = launch_encode_finish(act, *enc, s)) != PALU_OK) return st;
         enc_pending = false;
@@ -1413,6 +1508,26 @@ int palu_decode_step(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
   if ((st = plan_encode(desc, true, true, x, batch, Ak, Av, hk, Rk, hv, Rv, dst_row, encode_workspace,
                         encode_workspace_bytes, &p)) != PALU_OK)
     return st;
+  return decode_impl(desc, batch, 1, nullptr, seq_len, max_seq, q, q_pos, hk, nullptr, nullptr, hv, nullptr, nullptr, k_pos,
+                     seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream, nullptr,
+                     &p);
+}
+
+int palu_decode_step_t(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                       const void* x, const void* Akt, const void* Avt, const int32_t* dst_row,
+                       const void* q, const int32_t* q_pos, void* hk, void* hv,
+                       const int32_t* k_pos, const int32_t* seq_lens,
+                       const void* Bk, const void* Bv,
+                       const void* rope_table, int32_t rope_table_len,
+                       float* out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!desc) return PALU_ERR_INVALID_ARG;
+  if (batch <= 0) return PALU_ERR_INVALID_ARG;
+  Meta m;
+  int st = check_desc(desc, &m);
+  if (st != PALU_OK) return st;
+  static thread_local EncodePlan p;
+  const int Rk = m.k_off[m.n_groups], Rv = m.v_off[m.n_groups];
+  if ((st = plan_encode_t(desc, x, batch, Akt, Avt, hk, Rk, hv, Rv, dst_row, &p)) != PALU_OK) return st;
   return decode_impl(desc, batch, 1, nullptr, seq_len, max_seq, q, q_pos, hk, nullptr, nullptr, hv, nullptr, nullptr, k_pos,
                      seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream, nullptr,
                      &p);

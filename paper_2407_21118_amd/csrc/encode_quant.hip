@@ -153,6 +153,129 @@ __global__ __launch_bounds__(256) void encode_finish_kernel(EncodeArgs a) {
   }
 }
 
+// ---- the same projection from transposed weights At [R, d] (column c of A contiguous): a wavefront owns
+// kTCols columns and all of k, so a column's sum is finished inside the wavefront, in one launch, with no
+// partial sums in memory.  Workgroup = 4 wavefronts = 4 kTCols columns of one side; every weight load of
+// the wavefront (kTCols x 8 chunks of 1 KiB) goes out before anything else.
+constexpr int kTCols = 2;          // columns per wavefront (4 for passes of 4 or 8 tokens was slower: half the workgroups)
+constexpr int kTBlock = 4096;      // k per batch of loads: 8 chunks of 64 lanes x 8
+struct EncodeTArgs {
+  const uint16_t* x;               // [n_tok, d]
+  const int32_t* dst_row;
+  const uint16_t* At[2];           // [R, d]
+  uint16_t* latent[2];
+  long long row_stride[2];
+  int R[2];
+  int n_tok, d, wg_side1;          // workgroups below wg_side1 work on side 0
+};
+// acc + sum of the 8 products of two packed 16-byte operands
+template <typename T>
+__device__ __forceinline__ float dot8(const uint4v& w, const uint4v& x, float acc) {
+  if constexpr (__is_same(T, F16)) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t we = w[e], xe = x[e];                       // named copies: a bit cast applied to a vector element reads element 0
+      acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, we), __builtin_bit_cast(h2, xe), acc, false);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc = fmaf(T::to_float((uint16_t)(x[e] & 0xffffu)), T::to_float((uint16_t)(w[e] & 0xffffu)), acc);
+      acc = fmaf(T::to_float((uint16_t)(x[e] >> 16)), T::to_float((uint16_t)(w[e] >> 16)), acc);
+    }
+  }
+  return acc;
+}
+
+// wg_id: the workgroup's index in the projection's grid of wg_side1 + ceil(R_v / (4 kTCols)) workgroups
+// while_loading(): as for encode_partial_body
+template <typename T, int TOK, typename Extra = NoExtraWork>
+__device__ __forceinline__ void encode_t_body(const EncodeTArgs& a, int wg_id, Extra while_loading = Extra{}) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char enct_lds[];
+  uint16_t* xs = reinterpret_cast<uint16_t*>(enct_lds);          // [TOK][d]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int side = wg_id >= a.wg_side1 ? 1 : 0;
+  const int wg = wg_id - (side ? a.wg_side1 : 0);
+  const int R = a.R[side];
+  const int c0 = (wg * 4 + wave) * kTCols;                       // R is a multiple of 32: a wavefront's columns are all in or all out
+  const bool cols_ok = c0 < R;
+  const uint16_t* At = a.At[side] + (size_t)min(c0, R - kTCols) * a.d;
+  for (int tb = 0; tb < a.n_tok; tb += TOK) {
+    float acc[kTCols][TOK];
+#pragma unroll
+    for (int c = 0; c < kTCols; ++c)
+#pragma unroll
+      for (int t = 0; t < TOK; ++t) acc[c][t] = 0.f;
+    for (int kb = 0; kb < a.d; kb += kTBlock) {
+      // One or two tokens: a lane needs only its own k of x, the same for every column, and takes them straight
+      // from memory ahead of the weights (loads return in order: behind the weights they would cost a second
+      // round trip).  More tokens would not fit the registers and go through LDS.
+      constexpr bool kDirect = TOK <= 2;
+      uint4v xd[kDirect ? TOK : 1][8];
+      if constexpr (kDirect) {
+#pragma unroll
+        for (int t = 0; t < TOK; ++t)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int k = kb + (i * 64 + lane) * 8;
+            xd[t][i] = (k < a.d && tb + t < a.n_tok) ? *reinterpret_cast<const uint4v*>(a.x + (size_t)(tb + t) * a.d + k) : uint4v{0, 0, 0, 0};
+          }
+      }
+      uint4v w[kTCols][8];
+#pragma unroll
+      for (int c = 0; c < kTCols; ++c)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int k = kb + (i * 64 + lane) * 8;
+          w[c][i] = k < a.d ? *reinterpret_cast<const uint4v*>(At + (size_t)c * a.d + k) : uint4v{0, 0, 0, 0};
+        }
+      if (kb == 0) {
+        if (tb == 0) while_loading();
+        if constexpr (!kDirect) {
+          __syncthreads();                                       // the previous pass has read xs
+          const int nt = min(TOK, a.n_tok - tb);
+          for (int i = tid; i < TOK * (a.d >> 3); i += 256) {
+            const int t = i / (a.d >> 3), k8 = i - t * (a.d >> 3);
+            reinterpret_cast<uint4v*>(xs)[i] = t < nt ? reinterpret_cast<const uint4v*>(a.x + (size_t)(tb + t) * a.d)[k8] : uint4v{0, 0, 0, 0};
+          }
+          __syncthreads();
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int k = kb + (i * 64 + lane) * 8;
+        if (k >= a.d) continue;
+#pragma unroll
+        for (int t = 0; t < TOK; ++t) {
+          uint4v xv;
+          if constexpr (kDirect) xv = xd[t][i];
+          else xv = *reinterpret_cast<const uint4v*>(xs + (size_t)t * a.d + k);
+#pragma unroll
+          for (int c = 0; c < kTCols; ++c) acc[c][t] = dot8<T>(w[c][i], xv, acc[c][t]);
+        }
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < kTCols; ++c)
+#pragma unroll
+      for (int t = 0; t < TOK; ++t) {
+        float v = acc[c][t];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+        if (lane == 0 && cols_ok && tb + t < a.n_tok) {
+          const long long row = a.dst_row ? a.dst_row[tb + t] : tb + t;
+          a.latent[side][row * a.row_stride[side] + c0 + c] = T::from_float(v);
+        }
+      }
+  }
+}
+
+template <typename T, int TOK>
+__global__ __launch_bounds__(256) void encode_t_kernel(EncodeTArgs a) {
+  encode_t_body<T, TOK>(a, blockIdx.x);
+}
+
 // The quantizer of Appendix A with B = 4 (s = (max-min)/(2^B-1), z = round(-min/s),
 // code = clamp(round(x/s) + z, 0, 2^B-1)) for one (token, 128-channel block).
 // Every arithmetic step is a single IEEE float32 operation so the integer codes are
@@ -523,6 +646,13 @@ PALU_GEMM_INST(F16, false)
 PALU_GEMM_INST(BF16, false)
 PALU_GEMM_INST(F16, true)
 PALU_GEMM_INST(BF16, true)
+#define PALU_ENCT_INST(T) \
+  template __global__ void encode_t_kernel<T, 1>(EncodeTArgs); \
+  template __global__ void encode_t_kernel<T, 2>(EncodeTArgs); \
+  template __global__ void encode_t_kernel<T, 4>(EncodeTArgs); \
+  template __global__ void encode_t_kernel<T, 8>(EncodeTArgs);
+PALU_ENCT_INST(F16)
+PALU_ENCT_INST(BF16)
 template __global__ void encode_finish_kernel<F16>(EncodeArgs);
 template __global__ void encode_finish_kernel<BF16>(EncodeArgs);
 template __global__ void quant_kernel<F16>(QuantArgs);

@@ -421,3 +421,75 @@ def test_decode_step_equals_encode_then_decode(cfg, batch, theta, dtype):
     err = np.abs(got.cpu().numpy() - want).max() / np.abs(want).max()
     say(f"       rel err to the oracle on the appended cache {err:.3e}")
     assert err <= TOL_FP
+
+
+@pytest.mark.parametrize("dtype,n_tok", [("f16", 1), ("f16", 2), ("bf16", 5), ("f16", 8), ("f16", 19), ("bf16", 63)])
+def test_encode_from_transposed_weights(dtype, n_tok):
+    """palu_encode_kv_t: the down-projection from A^T (one launch, a wavefront per pair of columns)
+    against the oracle's float64 product, on a ragged layer (total ranks 1344 and 1216), with
+    scattered destination rows and padded cache rows; untouched memory stays untouched."""
+    say(f"[encode-t] dtype={dtype} n_tok={n_tok}")
+    k_ranks = [32, 64, 128, 96, 128, 384, 512]
+    v_ranks = [64, 32, 128, 256, 96, 128, 512]
+    layer = synth.Layer(16, 128, [0, 1, 2, 4, 6, 7, 10, 16], [0] + list(np.cumsum(k_ranks)), [0] + list(np.cumsum(v_ranks)))
+    rng = np.random.default_rng(21)
+    d = layer.n_heads * layer.d_head
+    Ak = synth.round_to(rng.standard_normal((d, layer.R_k)) / 45.0, dtype)
+    Av = synth.round_to(rng.standard_normal((d, layer.R_v)) / 45.0, dtype)
+    x = synth.round_to(rng.standard_normal((n_tok, d)), dtype)
+    desc = make_desc(layer, dtype)
+    td = torch.float16 if dtype == "f16" else torch.bfloat16
+    rows = n_tok + 11
+    perm = rng.permutation(rows)[:n_tok].astype(np.int32)
+    hk = torch.full((rows, layer.R_k + 2), 7.0, dtype=td, device="cuda")
+    hv = torch.full((rows, layer.R_v + 32), 7.0, dtype=td, device="cuda")
+    P.palu_encode_kv_t(desc, to_dev(x, dtype), to_dev(np.ascontiguousarray(Ak.T), dtype), to_dev(np.ascontiguousarray(Av.T), dtype),
+                       hk, layer.R_k + 2, hv, layer.R_v + 32, torch.from_numpy(perm).cuda())
+    torch.cuda.synchronize()
+    eps = 2.0 ** -11 if dtype == "f16" else 2.0 ** -8
+    for got, ref, R in ((hk.float().cpu().numpy(), O.encode(x, Ak), layer.R_k), (hv.float().cpu().numpy(), O.encode(x, Av), layer.R_v)):
+        err = np.abs(got[perm, :R] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+        say(f"       worst row error {err.max():.3e} (bound {eps * 1.05:.3e})")
+        assert err.max() <= eps * 1.05 + 1e-6
+        untouched = np.setdiff1d(np.arange(rows), perm)
+        assert (got[untouched] == 7.0).all() and (got[:, R:] == 7.0).all()
+
+
+@pytest.mark.parametrize("cfg,batch,theta,dtype", [("2", 1, 10000.0, "f16"), ("3", 3, 10000.0, "f16"), ("2", 8, 10000.0, "bf16"),
+                                                   ("2", 2, 0.0, "f16"), ("gqa", 2, 500000.0, "f16"), ("5a", 11, 10000.0, "f16")])
+def test_decode_step_from_transposed_weights(cfg, batch, theta, dtype):
+    """palu_decode_step_t (the projection from A^T, the query fold riding in its workgroups where the
+    step has one): the appended rows against the oracle's projection, the rest of the caches
+    untouched, and the output against the oracle's attention over the cache as it then stands."""
+    import dataclasses
+    from gpu_util import TOL_FP, make_desc, to_dev
+    layer = dataclasses.replace(synth.config_layer(cfg), rope_theta=theta)
+    L = 200
+    case = synth.make_case_svd(layer, batch, L, seed=19, dtype=dtype)
+    say(f"[step-t] cfg={cfg} batch={batch} theta={theta} dtype={dtype}")
+    desc = make_desc(layer, dtype)
+    rng = np.random.default_rng(20)
+    d = layer.n_q_heads * 128
+    x = synth.round_to(rng.standard_normal((batch, d)), dtype)
+    rows = (np.arange(batch) * L + (L - 1)).astype(np.int32)
+    table = P.palu_rope_table_init(theta, 128, L)
+    hk, hv = to_dev(case.Hk, dtype), to_dev(case.Hv, dtype)
+    got = P.palu_decode_step_t(desc, batch, L, L, to_dev(x, dtype), to_dev(np.ascontiguousarray(case.Ak.T), dtype),
+                               to_dev(np.ascontiguousarray(case.Av.T), dtype), torch.from_numpy(rows).cuda(),
+                               to_dev(case.q, dtype), torch.from_numpy(case.q_pos).cuda(), hk, hv, to_dev(case.Bk, dtype),
+                               to_dev(case.Bv, dtype), table, L)
+    torch.cuda.synchronize()
+    Hk = hk.float().cpu().numpy().astype(np.float64).reshape(batch * L, -1)
+    Hv = hv.float().cpu().numpy().astype(np.float64).reshape(batch * L, -1)
+    eps = 2.0 ** -11 if dtype == "f16" else 2.0 ** -8
+    keep = np.setdiff1d(np.arange(batch * L), rows)
+    for H, H0, A in ((Hk, case.Hk, case.Ak), (Hv, case.Hv, case.Av)):
+        ref = O.encode(x, A)
+        err = np.abs(H[rows] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+        assert err.max() <= eps * 1.05 + 1e-6
+        np.testing.assert_array_equal(H[keep], H0.reshape(batch * L, -1)[keep])
+    want = O.attn_decode(case.q, case.q_pos, Hk.reshape(batch, L, -1), Hv.reshape(batch, L, -1), case.Bk, case.Bv,
+                         layer.group_head_off, layer.k_rank_off, layer.v_rank_off, 128, theta, None, None, layer.q_per_kv)
+    err = np.abs(got.cpu().numpy() - want).max() / np.abs(want).max()
+    say(f"       rel err to the oracle on the appended cache {err:.3e}")
+    assert err <= TOL_FP
