@@ -205,7 +205,7 @@ def main() -> int:
     new_v = torch.empty((batch, layer.R_v), dtype=torch.float16, device="cuda")
 
     fused = not (k_i4 or v_i4 or args.separate_calls)          # one call per step (append + attend); quantized caches take the separate calls
-    transposed = fused and not args.row_major_weights and batch < 64
+    transposed = fused and not args.row_major_weights and batch <= 2    # with more tokens per step the row-major split-K form is the faster one
     if transposed:                                             # the projection weights column by column: made once, like the decomposition
         Akt, Avt = case.Ak.t().contiguous(), case.Av.t().contiguous()
 

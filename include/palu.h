@@ -172,9 +172,10 @@ int palu_encode_kv(const palu_layer_desc* desc, const void* x, int32_t n_tok, co
  * channel are contiguous (h = x A of Sec. 3.1 with A stored column by column; the
  * projection matrices are fixed after the decomposition, so this layout is made once,
  * offline).  A wavefront then owns whole columns and finishes their sums by itself:
- * one launch, no workspace, no partial sums in memory - for the few tokens of a decode
- * step this is about twice as fast as the row-major form (it pays up to about 8
- * tokens; beyond that the row-major form is the faster one).
+ * one launch, no workspace, no partial sums in memory.  It pays for one or two tokens
+ * per call (a decode step of one or two sequences: one launch instead of two, about
+ * 3 us less on a 7B-shaped layer); from about four tokens on the row-major form is
+ * the faster one.
  *   n_tok       1 <= n_tok < 64 (a prompt goes through palu_encode / palu_encode_kv)
  *   hk, hv      DEVICE caches, act_dtype; 2-byte aligned, any row stride >= R
  * Everything else as for palu_encode_kv.  Accumulates in float32, rounds once to

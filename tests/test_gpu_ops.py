@@ -203,7 +203,7 @@ def test_latent_output_matches_oracle(theta, v_i4, cfg):
     assert err <= (TOL_I4 if v_i4 else TOL_FP)
 
 
-@pytest.mark.parametrize("one_call", [False, True])
+@pytest.mark.parametrize("one_call", [False, True, "transposed"])
 def test_decode_step_in_a_captured_graph(one_call):
     """Append + decode captured into a HIP graph (the calls allocate nothing and never
     synchronise): four replays with fresh inputs written into the captured buffers, each
@@ -221,8 +221,14 @@ def test_decode_step_in_a_captured_graph(one_call):
     q_buf, x_buf = case.q.clone(), case.x_new.clone()
     side = torch.cuda.Stream()
 
+    Akt, Avt = case.Ak.t().contiguous(), case.Av.t().contiguous()
+
     def step():
         s = torch.cuda.current_stream()
+        if one_call == "transposed":      # palu_decode_step_t: the whole append is one launch
+            P.palu_decode_step_t(desc, batch, seq, seq, x_buf, Akt, Avt, dst_row, q_buf, case.q_pos, case.Hk[0],
+                                 case.Hv[0], case.Bk, case.Bv, table, seq, out=out, workspace=ws, stream=s)
+            return
         if one_call:          # palu_decode_step: the projection's first launch carries the query fold
             P.palu_decode_step(desc, batch, seq, seq, x_buf, case.Ak, case.Av, dst_row, q_buf, case.q_pos, case.Hk[0],
                                case.Hv[0], case.Bk, case.Bv, table, seq, out=out, workspace=ws, encode_workspace=ws_e, stream=s)
