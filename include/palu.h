@@ -180,8 +180,8 @@ int palu_encode_kv(const palu_layer_desc* desc, const void* x, int32_t n_tok, co
  *   hk, hv      DEVICE caches, act_dtype; 2-byte aligned, any row stride >= R
  * Everything else as for palu_encode_kv.  Accumulates in float32, rounds once to
  * act_dtype; the order of the sum differs from palu_encode_kv, so the two can differ
- * in the last bit of a latent.  PALU_ERR_UNSUPPORTED for quantized caches, for
- * n_tok >= 64 and for models wider than 32768 (n_heads*d_head).
+ * in the last bit of a latent.  PALU_ERR_UNSUPPORTED for quantized caches and for
+ * n_tok >= 64.
  */
 int palu_encode_kv_t(const palu_layer_desc* desc, const void* x, int32_t n_tok, const void* Akt, const void* Avt,
                      void* hk, int64_t hk_row_stride_elems, void* hv, int64_t hv_row_stride_elems,
