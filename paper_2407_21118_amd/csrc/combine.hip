@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   const int h = blockIdx.x >> 2, quarter = blockIdx.x & 3, b = blockIdx.y;
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
   const int nsp = L > 0 ? (L + a.split_tokens - 1) / a.split_tokens : 0;
-  const int j = m.group_of_head[h];
+  const int j = group_of(m, h);
   const int rv = m.v_off[j + 1] - m.v_off[j];
   int width;
   const int bv_blk = weight_block(m, j, h, m.bv_off[j], &width);

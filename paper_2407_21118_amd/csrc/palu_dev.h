@@ -226,10 +226,17 @@ __device__ __forceinline__ size_t q_row(const Meta& m, int b, int h) {
   return ((size_t)b * m.nq + j) * (m.n_heads / m.nq) + kv * per + qh;
 }
 
+// Group of head h, read as the word that holds its byte: for a workgroup-uniform h that is a scalar load
+// from the kernel arguments, where indexing the byte array is always a vector load (a memory round trip
+// ahead of whatever needs the group).
+__device__ __forceinline__ int group_of(const Meta& m, int h) {
+  return (int)((reinterpret_cast<const uint32_t*>(m.group_of_head)[h >> 2] >> (8 * (h & 3))) & 0xffu);
+}
+
 // Per-head offset of its value-latent accumulator inside an o_part row:
 // heads are laid out in order, head h taking r_v(group(h)) floats.
 __device__ __forceinline__ int o_head_off(const Meta& m, int h) {
-  const int j = m.group_of_head[h];
+  const int j = group_of(m, h);
   // heads before group j take sum_{i<j} s_i r_i floats = bv_off[j] / 128
   return m.bv_off[j] / kDHead + (h - m.head_off[j]) * (m.v_off[j + 1] - m.v_off[j]);
 }

@@ -408,7 +408,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
       const int hh = mt * 16 + 4 * kq + r;                    // accumulator row = head of the unit
       if (hh >= nh) continue;
       const int h = h0 + hh;
-      const int j = m.group_of_head[h];
+      const int j = group_of(m, h);
       const int lo = m.v_off[j], hi = m.v_off[j + 1];
       float* oh = op + o_head_off(m, h) - lo;
 #pragma unroll

@@ -95,7 +95,7 @@ __device__ __forceinline__ void qfold_body(const QfoldArgs& a, int bx, int by, i
   const int c = col0 + (tid >> 1);               // column inside the unit
   const int fh = (tid & 1) * 64;                  // first of this thread's 64 features
   const int cabs = u.c0 + c;                      // latent column
-  const int j = m.group_of_head[h];
+  const int j = group_of(m, h);
   const bool mine = c < u.ncols && cabs >= m.k_off[j] && cabs < m.k_off[j + 1];   // the same for both threads of a column
   uint4v bw[8];
 #pragma unroll

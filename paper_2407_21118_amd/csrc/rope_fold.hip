@@ -52,7 +52,7 @@ __device__ __forceinline__ void fold_body(const FoldArgs& a, int ks, int h, int 
   __shared__ __attribute__((aligned(16))) uint16_t Bs[16][kDHead + 8];
   const int tid = threadIdx.x;
   const Meta& m = a.meta;
-  const int j = m.group_of_head[h];
+  const int j = group_of(m, h);
   const int u = h - m.head_off[j];
   const int r = m.k_off[j + 1] - m.k_off[j];
   if (ks >= (r >> 4)) return;
