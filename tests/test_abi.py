@@ -94,3 +94,24 @@ def test_null_and_range_arguments():
     assert lib.palu_encode(d.ref(), 2, None, 1, None, None, 128, None, None, 0, None) == -1
     assert lib.palu_quant_latent(d.ref(), 0, None, 128, 1, None, None, None, None, None) == -1
     assert lib.palu_attn_decode(d.ref(), 1, 8, 8, *([None] * 13), 8, None, None, 0, None) == -1
+
+
+def test_transposed_weight_entry_points_refuse_what_they_do_not_do():
+    """palu_encode_kv_t / palu_decode_step_t: NULL and misaligned pointers, prompt-sized token counts and
+    quantized caches are refused on the host, before anything is launched."""
+    lib = P.load_library()
+    d = desc()
+    one, odd = ctypes.c_void_p(256), ctypes.c_void_p(264)    # non-NULL; never dereferenced: the calls are refused first
+    R = 128                                                  # desc(): two groups of rank 64
+    assert lib.palu_encode_kv_t(None, one, 1, one, one, one, R, one, R, None, None) == -1
+    assert lib.palu_encode_kv_t(d.ref(), None, 1, one, one, one, R, one, R, None, None) == -1
+    assert lib.palu_encode_kv_t(d.ref(), one, 0, one, one, one, R, one, R, None, None) == -1
+    assert lib.palu_encode_kv_t(d.ref(), one, 1, odd, one, one, R, one, R, None, None) == -1      # weights: 16-byte aligned
+    assert lib.palu_encode_kv_t(d.ref(), one, 1, one, one, one, R - 2, one, R, None, None) == -1  # row stride below the rank
+    assert lib.palu_encode_kv_t(d.ref(), one, 64, one, one, one, R, one, R, None, None) == -2     # a prompt: the GEMM form
+    dq = desc(v_latent_dtype=P.PALU_I4, v_rank_off=[0, 128, 256])
+    assert lib.palu_encode_kv_t(dq.ref(), one, 1, one, one, one, R, one, R, None, None) == -2
+    args = [one, one, one, one, one, one, one, one, None, None, one, one, one, 8, one, one, 1 << 20, None]
+    assert lib.palu_decode_step_t(d.ref(), 64, 8, 8, *args) == -2
+    assert lib.palu_decode_step_t(d.ref(), 0, 8, 8, *args) == -1
+    assert lib.palu_decode_step_t(dq.ref(), 1, 8, 8, *args) == -2
