@@ -117,6 +117,8 @@ def main() -> int:
                     help="config 4 / 4v: bits per quantized latent code (3 and 2: the low-bit settings of the paper's Sec. 4.4)")
     ap.add_argument("--row-major-weights", action="store_true",
                     help="give the step A_k, A_v as [d, R] (palu_decode_step) instead of transposed, [R, d] (palu_decode_step_t)")
+    ap.add_argument("--transposed-weights", action="store_true",
+                    help="use palu_decode_step_t for any batch below 64 (by default only for batches of one and two)")
     ap.add_argument("--separate-calls", action="store_true",
                     help="time palu_encode_kv + palu_attn_decode instead of the one-call palu_decode_step")
     ap.add_argument("--no-probes", action="store_true", help="skip the bare MFMA / read probes (measured_peaks)")
@@ -205,7 +207,8 @@ def main() -> int:
     new_v = torch.empty((batch, layer.R_v), dtype=torch.float16, device="cuda")
 
     fused = not (k_i4 or v_i4 or args.separate_calls)          # one call per step (append + attend); quantized caches take the separate calls
-    transposed = fused and not args.row_major_weights and batch <= 2    # with more tokens per step the row-major split-K form is the faster one
+    # with more than two tokens per step the row-major split-K form is the faster one
+    transposed = fused and not args.row_major_weights and (batch <= 2 or (args.transposed_weights and batch < 64))
     if transposed:                                             # the projection weights column by column: made once, like the decomposition
         Akt, Avt = case.Ak.t().contiguous(), case.Av.t().contiguous()
 
