@@ -1,7 +1,8 @@
 """Seeded random sweep over everything palu_attn_decode_multi takes at once: group sizes and
 ranks, query heads per key/value head, query tokens per sequence, RoPE base (or none), key and
 value latents in fp16 / bf16 / 4 / 3 / 2 bits independently, batch, ragged lengths, explicit
-cache positions.  Each case is compared with the oracle (fed the same dequantized latents)."""
+cache positions.  Each case is compared with the oracle (fed the same dequantized latents).
+A second sweep runs whole decode steps (append + attend) through both weight layouts."""
 
 import numpy as np
 import pytest
@@ -89,3 +90,70 @@ def test_random_sweep(first):
         worst = max(worst, err / tol)
         assert finite and err <= tol, f"{what}: error {err:.3e} above {tol}"
     say(f"[sweep] seeds {first}..{first + 39}: worst error / tolerance {worst:.2f}")
+
+
+def step_case(seed):
+    """One random decode step (append, then attend) through both weight layouts: palu_decode_step with
+    A [d, R] and palu_decode_step_t with A^T [R, d]; the appended rows against the oracle's projection,
+    the outputs against the oracle's attention over each call's own cache."""
+    rng = np.random.default_rng([777, seed])
+    qpk = int(rng.choice([1, 1, 2, 4]))
+    theta = float(rng.choice([0.0, 10000.0, 10000.0, 500000.0]))
+    dtype = "bf16" if rng.random() < 0.3 else "f16"
+    sizes = [int(rng.choice([1, 2, 4, 8])) for _ in range(int(rng.integers(1, 5)))]
+    kr = [int(rng.integers(1, min(512, s * 128) // 32 + 1)) * 32 for s in sizes]
+    vr = [int(rng.integers(1, min(512, s * 128) // 32 + 1)) * 32 for s in sizes]
+    head_off = [0] + list(np.cumsum(sizes))
+    layer = synth.Layer(int(head_off[-1]), 128, head_off, [0] + list(np.cumsum(kr)), [0] + list(np.cumsum(vr)),
+                        rope_theta=theta, q_per_kv=qpk)
+    B = int(rng.choice([1, 1, 2, 3, 5, 8, 9]))
+    L = int(rng.choice([1, 7, 33, 100, 257]))
+    case = synth.make_case_orthonormal(layer, B, L, seed=2000 + seed, dtype=dtype)
+    d = layer.n_q_heads * 128
+    A = {side: synth.round_to(rng.standard_normal((d, R)) / np.sqrt(d), dtype) for side, R in (("k", layer.R_k), ("v", layer.R_v))}
+    x = synth.round_to(rng.standard_normal((B, d)), dtype)
+    lens = np.array([L] + [int(rng.integers(1, L + 1)) for _ in range(B - 1)], np.int32)
+    rows = (np.arange(B) * L + lens - 1).astype(np.int32)          # the new token is each sequence's last attended row
+    q_pos = (lens - 1 + int(rng.integers(0, 3000))).astype(np.int32)
+    act = P.PALU_F16 if dtype == "f16" else P.PALU_BF16
+    desc = P.LayerDesc(layer.n_heads, 128, layer.group_head_off, layer.k_rank_off, layer.v_rank_off, act, act, act, 128, theta, qpk)
+    n_pos = int(q_pos.max()) + 1 + L
+    table = P.palu_rope_table_init(theta, 128, n_pos)
+    common = dict(q=to_dev(case.q, dtype), q_pos=torch.from_numpy(q_pos).cuda(), Bk=to_dev(case.Bk, dtype), Bv=to_dev(case.Bv, dtype))
+    d_rows, d_lens, xd = torch.from_numpy(rows).cuda(), torch.from_numpy(lens).cuda(), to_dev(x, dtype)
+    eps = 2.0 ** -11 if dtype == "f16" else 2.0 ** -8
+    worst = 0.0
+    for transposed in (False, True):
+        hk, hv = to_dev(case.Hk, dtype), to_dev(case.Hv, dtype)
+        if transposed:
+            got = P.palu_decode_step_t(desc, B, L, L, xd, to_dev(np.ascontiguousarray(A["k"].T), dtype),
+                                       to_dev(np.ascontiguousarray(A["v"].T), dtype), d_rows, common["q"], common["q_pos"], hk, hv,
+                                       common["Bk"], common["Bv"], table, n_pos, seq_lens=d_lens)
+        else:
+            got = P.palu_decode_step(desc, B, L, L, xd, to_dev(A["k"], dtype), to_dev(A["v"], dtype), d_rows, common["q"],
+                                     common["q_pos"], hk, hv, common["Bk"], common["Bv"], table, n_pos, seq_lens=d_lens)
+        torch.cuda.synchronize()
+        Hk = hk.float().cpu().numpy().astype(np.float64)
+        Hv = hv.float().cpu().numpy().astype(np.float64)
+        keep = np.setdiff1d(np.arange(B * L), rows)
+        for H, H0, side in ((Hk, case.Hk, "k"), (Hv, case.Hv, "v")):
+            ref = O.encode(x, A[side])
+            flat = H.reshape(B * L, -1)
+            err = np.abs(flat[rows] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+            assert err.max() <= eps * 1.05 + 1e-6, (seed, transposed, side, err.max())
+            np.testing.assert_array_equal(flat[keep], H0.reshape(B * L, -1)[keep])
+        want = O.attn_decode(case.q, q_pos, Hk, Hv, case.Bk, case.Bv, layer.group_head_off, layer.k_rank_off,
+                             layer.v_rank_off, 128, theta, None, lens, qpk)
+        out = got.cpu().numpy()
+        assert np.isfinite(out).all()
+        whole, per_row = rel_err(out, want)
+        worst = max(worst, whole, per_row)
+        assert max(whole, per_row) <= TOL_FP, (seed, transposed, sizes, kr, vr, qpk, theta, dtype, B, L, whole, per_row)
+    return worst
+
+
+def test_sweep_decode_step_both_weight_layouts():
+    worst = 0.0
+    for seed in range(30):
+        worst = max(worst, step_case(seed))
+    say(f"[sweep-step] 30 cases x 2 weight layouts, worst rel err {worst:.3e}")
