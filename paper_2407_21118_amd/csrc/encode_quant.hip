@@ -395,12 +395,12 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
 #pragma unroll
       for (int jp = 0; jp < 4; ++jp)
         t[jp] = __builtin_amdgcn_perm(ar[2 * jp + 1][e >> 1], ar[2 * jp][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
-      // the 16-byte k-octets of a row are stored XOR-swizzled by bits 4..6 of the row number: the 16 lanes
-      // of a store pass (16 chunks, rows 8 apart) then cover all banks instead of two bank groups
+      // the 16-byte k-octets of a row are stored XOR-swizzled by bits 3..5 of the row number (its chunk
+      // number): the lanes of a store pass (chunks, rows 8 apart) would otherwise share two bank groups
       *reinterpret_cast<uint4v*>(As + (cc * 8 + e) * kGemmPitch + ((oct ^ cc) & 7) * 8) = t;
     }
   };
-  // read side of the swizzle: k-step ks reads octet 2 ks + lane_hi of row n, stored at octet ^ ((n >> 4) & 7)
+  // read side of the swizzle: k-step ks reads octet 2 ks + lane_hi of row n, stored at octet ^ ((n >> 3) & 7)
   int a_row[4], a_swz[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
