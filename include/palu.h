@@ -100,7 +100,8 @@ int palu_version(void);
  *   "score_waves"         4 or 8 wavefronts per score workgroup for ranks <= 256
  *   "score_chunks"        sequence chunks per (sequence, head block) in the score kernel
  *   "value_split_tokens"  tokens per sequence split in the value kernel (multiple of 32, <= 4096)
- *   "encode_tile_rows"    token rows per workgroup of the prompt-sized projection (64, 128 or 256)
+ *   "encode_tile_rows"    token rows per workgroup of the prompt-sized projection (64, 128 or 256, each
+ *                         with 256 columns; 32 selects the narrow tile of 64 rows x 128 columns)
  * Unknown names and out-of-range values return PALU_ERR_INVALID_ARG.  Set
  * value_split_tokens before querying the workspace size: a smaller split needs
  * more workspace, and palu_attn_decode reports a shortfall.

@@ -318,14 +318,13 @@ __device__ __forceinline__ uint32_t quant_code(float x, const QuantParams& p) {
 // Workgroups are numbered so that each of the 8 XCDs (workgroup id mod 8) owns a
 // contiguous range of the tiles, columns fastest: the column tiles of a token row share
 // their X rows through that XCD's L2.
-constexpr int kGemmCols = 256;                 // output columns per workgroup
+// output columns per workgroup: 256, or 128 with the 64-row tile where even that leaves compute units idle
 constexpr int kGemmK = 64;                     // k per stage
 constexpr int kGemmPitch = kGemmK + 8;         // halfs per LDS row: 16-byte reads of 16 consecutive rows hit distinct banks
-constexpr int kGemmOutPitch = kGemmCols + 8;   // halfs per row of the output tile
 // token rows per workgroup: 256, or 128 / 64 while the taller tile would leave compute units without a workgroup
 
-constexpr size_t gemm_lds_bytes(int tm) {
-  const size_t stages = (size_t)2 * (tm + kGemmCols) * kGemmPitch * 2, out = (size_t)tm * kGemmOutPitch * 2;
+constexpr size_t gemm_lds_bytes(int tm, int tn) {
+  const size_t stages = (size_t)2 * (tm + tn) * kGemmPitch * 2, out = (size_t)tm * (tn + 8) * 2;
   return stages > out ? stages : out;
 }
 
@@ -337,13 +336,16 @@ struct GemmGrid {
 // workgroup quantizes its rounded outputs in place of storing them (Sec. 3.4 applied
 // while the cache is filled): codes, scales and zero-points are the ones quant_kernel
 // gives for the latents the plain kernel stores.
-// grid (8 * per_xcd), 256 threads, gemm_lds_bytes(TM) of LDS.
-template <typename T, bool QUANT, int TM>
+// grid (8 * per_xcd), 256 threads, gemm_lds_bytes(TM, TN) of LDS.
+template <typename T, bool QUANT, int TM, int TN>
 __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid gg) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gemm_lds[];
   constexpr int MI = TM / 64;                                            // 32-row tiles of a wavefront
   constexpr int XC = TM / 32;                                            // 16-byte X chunks per thread and stage
-  constexpr int kBufHalfs = (TM + kGemmCols) * kGemmPitch;
+  constexpr int NJ = TN / 64;                                            // 32-column tiles of a wavefront
+  constexpr int kOutPitch = TN + 8;                                      // halfs per row of the output tile
+  constexpr int kAL = TN == 256 ? 8 : 4;                                 // 16-byte A loads per thread and stage
+  constexpr int kBufHalfs = (TM + TN) * kGemmPitch;
   uint16_t* lds16 = reinterpret_cast<uint16_t*>(gemm_lds);
 
   const int tile = (blockIdx.x & 7) * gg.per_xcd + (blockIdx.x >> 3);
@@ -352,16 +354,18 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
   const int side = tile / per_side, in_side = tile - side * per_side;
   const int row_tile = in_side / gg.n_col_tiles, col_tile = in_side - row_tile * gg.n_col_tiles;
   const EncodeSide sd = a.side[side];
-  const int n0 = col_tile * kGemmCols, m0 = row_tile * TM;
+  const int n0 = col_tile * TN, m0 = row_tile * TM;
   if (n0 >= sd.R) return;                                                // uniform
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lane_lo = lane & 31, lane_hi = lane >> 5;
-  const int wm = (wave >> 1) * (TM / 2), wn = (wave & 1) * 128;          // this wavefront's corner of the tile
+  const int wm = (wave >> 1) * (TM / 2), wn = (wave & 1) * (TN / 2);     // this wavefront's corner of the tile
 
   // staging roles.  X: 16-byte piece lane % 8 of the stage's 64 k of row x_row(i) (i < XC): the 16 lanes of a store
   // pass hold rows r and r + 8, whose pieces lie 32 banks apart with this pitch (neighbouring rows overlap by 4 banks).
-  // A: one (k-octet oct, 8-column chunk cc) item per thread: rows k0 + 8 oct + j (j < 8), columns n0 + 8 cc ..
-  const int oct = tid >> 5, cc = tid & 31;
+  // A, 256 columns: one (k-octet oct, 8-column chunk cc) item per thread: rows k0 + 8 oct + j (j < 8), columns
+  // n0 + 8 cc ..; 128 columns: half an octet per thread (quad = tid / 16: rows k0 + 4 quad + j, j < 4).
+  const int quad = tid >> 4;
+  const int oct = TN == 256 ? tid >> 5 : quad >> 1, cc = TN == 256 ? tid & 31 : tid & 15;
   const int a_col = min(n0 + cc * 8, sd.R - 8);                          // R is a multiple of 32: clamped chunks are never stored
   const uint16_t* x_base = a.x + (size_t)m0 * a.d;
   unsigned x_off[XC];                                                    // rows past the last token re-read it; they are never stored
@@ -369,17 +373,17 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
 #pragma unroll
   for (int i = 0; i < XC; ++i)
     x_off[i] = (unsigned)min(x_row(i), a.n_tok - 1 - m0) * (unsigned)a.d + (unsigned)(lane & 7) * 8u;
-  const uint16_t* a_src = sd.A + (size_t)(oct * 8) * sd.R + a_col;
+  const uint16_t* a_src = sd.A + (size_t)(TN == 256 ? oct * 8 : quad * 4) * sd.R + a_col;
   // the stage after the one being multiplied waits in these registers; the one after that is requested as
   // soon as they have been written to LDS
-  uint4v xr[XC], ar[8];
+  uint4v xr[XC], ar[kAL];
   auto fetch_x = [&](int stage) {
 #pragma unroll
     for (int i = 0; i < XC; ++i) xr[i] = *reinterpret_cast<const uint4v*>(x_base + x_off[i] + stage * kGemmK);
   };
   auto fetch_a = [&](int stage) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) ar[j] = *reinterpret_cast<const uint4v*>(a_src + (size_t)(stage * kGemmK + j) * sd.R);
+    for (int j = 0; j < kAL; ++j) ar[j] = *reinterpret_cast<const uint4v*>(a_src + (size_t)(stage * kGemmK + j) * sd.R);
   };
   auto stash_x = [&](int buf) {
     uint16_t* Xs = lds16 + buf * kBufHalfs;
@@ -393,33 +397,35 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
     for (int e = 0; e < 8; ++e) {
       uint4v t;
 #pragma unroll
-      for (int jp = 0; jp < 4; ++jp)
+      for (int jp = 0; jp < kAL / 2; ++jp)
         t[jp] = __builtin_amdgcn_perm(ar[2 * jp + 1][e >> 1], ar[2 * jp][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
       // the 16-byte k-octets of a row are stored XOR-swizzled by bits 3..5 of the row number (its chunk
       // number): the lanes of a store pass (chunks, rows 8 apart) would otherwise share two bank groups
-      *reinterpret_cast<uint4v*>(As + (cc * 8 + e) * kGemmPitch + ((oct ^ cc) & 7) * 8) = t;
+      uint16_t* dst = As + (cc * 8 + e) * kGemmPitch + ((oct ^ cc) & 7) * 8;
+      if constexpr (TN == 256) *reinterpret_cast<uint4v*>(dst) = t;
+      else *reinterpret_cast<uint2v*>(dst + (quad & 1) * 4) = uint2v{t[0], t[1]};
     }
   };
   // read side of the swizzle: k-step ks reads octet 2 ks + lane_hi of row n, stored at octet ^ ((n >> 3) & 7)
-  int a_row[4], a_swz[4];
+  int a_row[NJ], a_swz[NJ];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NJ; ++j) {
     const int n = wn + 32 * j + lane_lo;
     a_row[j] = n * kGemmPitch;
     a_swz[j] = (n >> 3) & 7;
   }
 
-  float16v acc[MI][4];
+  float16v acc[MI][NJ];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   // operand registers of one k-step (16 k); two sets, so that a k-step's reads are in flight
   // while the previous one is multiplied (one wavefront per SIMD: nobody else hides them)
-  typename T::vec8 xa[2][MI], ab[2][4];
+  typename T::vec8 xa[2][MI], ab[2][NJ];
   auto read_step = [&](int set, int buf, int ks) {
     const uint16_t* Xs = lds16 + buf * kBufHalfs;
     const uint16_t* As = Xs + TM * kGemmPitch;
@@ -427,7 +433,7 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
     for (int i = 0; i < MI; ++i)
       xa[set][i] = *reinterpret_cast<const typename T::vec8*>(Xs + (wm + 32 * i + lane_lo) * kGemmPitch + ks * 16 + lane_hi * 8);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NJ; ++j)
       ab[set][j] = *reinterpret_cast<const typename T::vec8*>(As + a_row[j] + (((2 * ks + lane_hi) ^ a_swz[j]) * 8));
   };
 
@@ -435,7 +441,7 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = T::mfma(xa[set][i], ab[set][j], acc[i][j]);
+      for (int j = 0; j < NJ; ++j) acc[i][j] = T::mfma(xa[set][i], ab[set][j], acc[i][j]);
   };
   // One stage: four k-steps, each with the next step's operand reads in flight.  The first writes the X rows of
   // stage s + 1 from their registers to the other LDS buffer (last read before the previous barrier), the second
@@ -446,9 +452,9 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
   // the matrix pipe idle.  Past the end of k the last stage is fetched and stored again, into the buffer nobody
   // reads any more.
   const int n_stages = a.d / kGemmK;
-  constexpr int kMma = MI * 4, kRd = MI + 4;     // matrix instructions and operand reads of a k-step
+  constexpr int kMma = MI * NJ, kRd = MI + NJ;   // matrix instructions and operand reads of a k-step
   constexpr int kHalf = kMma / 2, kRdPer = (kRd + kHalf - 1) / kHalf;
-  constexpr int kXwPer = (XC + kHalf - 1) / kHalf, kAwPer = (8 + kHalf - 1) / kHalf, kLdPerMma = (8 + kMma - 1) / kMma;
+  constexpr int kXwPer = (XC + kHalf - 1) / kHalf, kAwPer = (8 + kHalf - 1) / kHalf, kLdPerMma = (kAL + kMma - 1) / kMma;
   fetch_x(0);
   fetch_a(0);
   stash_x(0);
@@ -494,7 +500,7 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
 #pragma unroll
     for (int i = 0; i < kMma; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i * kLdPerMma < 8) __builtin_amdgcn_sched_group_barrier(0x020, kLdPerMma, 0);
+      if (i * kLdPerMma < kAL) __builtin_amdgcn_sched_group_barrier(0x020, kLdPerMma, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();                             // the next stage is in LDS; this one has been read
@@ -503,25 +509,26 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
   }
 
   // accumulator element e of tile (i, j): token m0 + wm + 32 i + mfma_row(e), column n0 + wn + 32 j + lane_lo.
-  // Every stage has been read (barrier above): LDS becomes the rounded output tile [TM][kGemmOutPitch].
+  // Every stage has been read (barrier above): LDS becomes the rounded output tile [TM][kOutPitch].
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        lds16[(wm + 32 * i + mfma_row(e, lane_hi)) * kGemmOutPitch + wn + 32 * j + lane_lo] = T::from_float(acc[i][j][e]);
+      for (int j = 0; j < NJ; ++j)
+        lds16[(wm + 32 * i + mfma_row(e, lane_hi)) * kOutPitch + wn + 32 * j + lane_lo] = T::from_float(acc[i][j][e]);
   __syncthreads();
 
   if constexpr (QUANT) {
     // two threads per (token, 128-column block), 64 channels each
     const int n_blocks = sd.R / 128;
+    constexpr int NB = TN / 128;                     // quantization blocks per token in the tile
 #pragma unroll 1
-    for (int item = tid; item < TM * 4; item += 256) {
-      const int tr = item >> 2, bl = (item >> 1) & 1, hf = item & 1;
+    for (int item = tid; item < TM * NB * 2; item += 256) {
+      const int tr = item / (NB * 2), bl = (item >> 1) % NB, hf = item & 1;
       uint4v v[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint4v*>(lds16 + tr * kGemmOutPitch + bl * 128 + hf * 64 + i * 8);
+      for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint4v*>(lds16 + tr * kOutPitch + bl * 128 + hf * 64 + i * 8);
       float mn = T::to_float((uint16_t)(v[0][0] & 0xffffu)), mx = mn;
 #pragma unroll
       for (int i = 0; i < 8; ++i)
@@ -533,7 +540,7 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
         }
       mn = fminf(mn, __shfl_xor(mn, 1, 64));
       mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
-      const int t = m0 + tr, blk = col_tile * 2 + bl;
+      const int t = m0 + tr, blk = col_tile * NB + bl;
       if (t >= a.n_tok || blk >= n_blocks) continue;
       const QuantParams qp = quant_params(mn, mx);
       const size_t orow = a.dst_row ? (size_t)a.dst_row[t] : (size_t)t;
@@ -563,11 +570,11 @@ __global__ __launch_bounds__(256) void encode_gemm_kernel(EncodeArgs a, GemmGrid
   // rows leave in 16-byte pieces where the destination allows it (4-byte alignment is all the interface asks for)
   const bool wide = ((reinterpret_cast<uintptr_t>(sd.latent) & 15) == 0) && ((sd.row_stride & 7) == 0);
 #pragma unroll 4
-  for (int id = tid; id < TM * 32; id += 256) {
-    const int tr = id >> 5, c8 = (id & 31) * 8;
+  for (int id = tid; id < TM * (TN / 8); id += 256) {
+    const int tr = id / (TN / 8), c8 = (id % (TN / 8)) * 8;
     const int t = m0 + tr;
     if (t >= a.n_tok || n0 + c8 >= sd.R) continue;
-    const uint4v v = *reinterpret_cast<const uint4v*>(lds16 + tr * kGemmOutPitch + c8);
+    const uint4v v = *reinterpret_cast<const uint4v*>(lds16 + tr * kOutPitch + c8);
     const long long row = a.dst_row ? a.dst_row[t] : t;
     uint16_t* dst = sd.latent + row * sd.row_stride + n0 + c8;
     if (wide) {
@@ -639,9 +646,10 @@ __global__ __launch_bounds__(256) void quant_kernel(QuantArgs a) {
 PALU_ENC_INST(F16)
 PALU_ENC_INST(BF16)
 #define PALU_GEMM_INST(T, Q) \
-  template __global__ void encode_gemm_kernel<T, Q, 64>(EncodeArgs, GemmGrid); \
-  template __global__ void encode_gemm_kernel<T, Q, 128>(EncodeArgs, GemmGrid); \
-  template __global__ void encode_gemm_kernel<T, Q, 256>(EncodeArgs, GemmGrid);
+  template __global__ void encode_gemm_kernel<T, Q, 64, 128>(EncodeArgs, GemmGrid); \
+  template __global__ void encode_gemm_kernel<T, Q, 64, 256>(EncodeArgs, GemmGrid); \
+  template __global__ void encode_gemm_kernel<T, Q, 128, 256>(EncodeArgs, GemmGrid); \
+  template __global__ void encode_gemm_kernel<T, Q, 256, 256>(EncodeArgs, GemmGrid);
 PALU_GEMM_INST(F16, false)
 PALU_GEMM_INST(BF16, false)
 PALU_GEMM_INST(F16, true)

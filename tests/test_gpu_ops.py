@@ -260,15 +260,17 @@ def test_decode_step_in_a_captured_graph(one_call):
 
 @pytest.fixture
 def encode_tile(request):
-    """Forces the projection's tile height (the library picks it from the token count: the tall
-    tiles are otherwise reached only by prompts of thousands of tokens)."""
+    """Forces the projection's tile (the library picks it from the token count: short prompts get
+    64 x 128, the tall tiles are otherwise reached only by prompts of thousands of tokens; 32 names
+    the 64 x 128 tile)."""
     P.palu_set_option("encode_tile_rows", request.param)
     yield request.param
     P.palu_set_option("encode_tile_rows", 0)
 
 
 @pytest.mark.parametrize("dtype,n_tok,encode_tile", [("f16", 64, 0), ("f16", 300, 0), ("bf16", 129, 0), ("f16", 300, 128),
-                                                     ("f16", 300, 256), ("bf16", 700, 256), ("bf16", 129, 128)],
+                                                     ("f16", 300, 256), ("bf16", 700, 256), ("bf16", 129, 128), ("f16", 300, 64), ("bf16", 129, 64),
+                                                     ("f16", 700, 32)],
                          indirect=["encode_tile"])
 def test_encode_many_tokens_gemm_path(dtype, n_tok, encode_tile):
     """Prompt-sized append: from 64 tokens on palu_encode runs as a tiled GEMM on the matrix
@@ -303,7 +305,7 @@ def test_encode_many_tokens_gemm_path(dtype, n_tok, encode_tile):
 
 
 @pytest.mark.parametrize("dtype,n_tok,encode_tile", [("f16", 1, 0), ("f16", 64, 0), ("f16", 300, 0), ("bf16", 129, 0),
-                                                     ("f16", 300, 128), ("f16", 600, 256), ("bf16", 300, 256)],
+                                                     ("f16", 300, 128), ("f16", 600, 256), ("bf16", 300, 256), ("f16", 300, 64), ("bf16", 200, 32)],
                          indirect=["encode_tile"])
 def test_encode_quant_fused(dtype, n_tok, encode_tile):
     """Down-projection with the quantizer fused into the GEMM's write-out.  Two checks:
