@@ -274,6 +274,29 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
                      float* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * palu_attn_decode for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and same results as palu_attn_decode, without
+ * the workspace: the scratch is a static device array of PALU_NOALLOC_SCRATCH_BYTES inside
+ * the library (each GPU the library is used on holds that much until the process ends).
+ * The call allocates nothing; the first call on a device looks up the array's address
+ * there.  PALU_ERR_WORKSPACE_TOO_SMALL when palu_attn_decode_workspace_bytes(desc, batch,
+ * max_seq) exceeds PALU_NOALLOC_SCRATCH_BYTES (nothing is enqueued).  All calls on one GPU
+ * share the array, which keeps the previous call's contents (no call relies on them):
+ * calls that overlap on one GPU, on different streams or from different threads, race;
+ * order them on one stream.
+ */
+enum { PALU_NOALLOC_SCRATCH_BYTES = 32 * 1024 * 1024 };
+int palu_attn_decode_noalloc(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                             const void* q, const int32_t* q_pos,
+                             const void* hk, const void* hk_scale, const void* hk_zero,
+                             const void* hv, const void* hv_scale, const void* hv_zero,
+                             const int32_t* k_pos, const int32_t* seq_lens,
+                             const void* Bk, const void* Bv,
+                             const void* rope_table, int32_t rope_table_len,
+                             float* out, void* stream);
+
+/*
  * The same decode step with the output left in the value latent space
  * (Sec. 3.1.1: B_v is absorbed into the output projection W_o offline, so the
  * attention module returns (p H_v) and never multiplies by B_v):

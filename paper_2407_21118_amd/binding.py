@@ -83,6 +83,8 @@ def load_library():
     lib.palu_attn_decode_workspace_bytes.argtypes = [dp, i32, i32, szp]
     lib.palu_attn_decode.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                      vp, i32, vp, vp, sz, vp]
+    lib.palu_attn_decode_noalloc.argtypes = lib.palu_attn_decode.argtypes[:-3] + [vp]
+    lib.palu_attn_decode_noalloc.restype = ctypes.c_int
     lib.palu_attn_decode_staged.argtypes = lib.palu_attn_decode.argtypes + [ctypes.POINTER(vp)]
     lib.palu_attn_decode_staged.restype = ctypes.c_int
     lib.palu_attn_decode_latent.argtypes = [dp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -281,6 +283,18 @@ def palu_attn_decode(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, q,
             raise ValueError("stage_events needs PALU_DECODE_STAGES + 1 events")
         arr = (ctypes.c_void_p * len(stage_events))(*[ctypes.c_void_p(e.cuda_event) for e in stage_events])
         _check(load_library().palu_attn_decode_staged(*args, arr), "palu_attn_decode_staged")
+    return out
+
+
+def palu_attn_decode_noalloc(desc: LayerDesc, batch: int, seq_len: int, max_seq: int, q, q_pos, hk, hv, Bk, Bv,
+                             rope_table, rope_table_len: int, out, k_pos=None, seq_lens=None,
+                             hk_scale=None, hk_zero=None, hv_scale=None, hv_zero=None, stream=None):
+    """palu_attn_decode on the library's static scratch; `out` is the caller's (nothing is allocated here)."""
+    _need_cuda(q, q_pos, hk, hv, Bk, Bv, rope_table, out, k_pos, seq_lens, hk_scale, hk_zero, hv_scale, hv_zero)
+    _check(load_library().palu_attn_decode_noalloc(
+        desc.ref(), batch, seq_len, max_seq, _ptr(q), _ptr(q_pos), _ptr(hk), _ptr(hk_scale), _ptr(hk_zero),
+        _ptr(hv), _ptr(hv_scale), _ptr(hv_zero), _ptr(k_pos), _ptr(seq_lens), _ptr(Bk), _ptr(Bv),
+        _ptr(rope_table), int(rope_table_len), _ptr(out), _stream(stream)), "palu_attn_decode_noalloc")
     return out
 
 

@@ -1456,6 +1456,50 @@ int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len
                      seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, workspace, workspace_bytes, stream, nullptr);
 }
 
+// ---- the decode step for callers that cannot allocate ---------------------------
+// Its scratch is a file-scope device array: every GPU the library runs on holds its own
+// copy at its own address, looked up once per device; host code only ever uses that
+// address, never the array's name.
+namespace {
+static __device__ __align__(256) unsigned char scratch[PALU_NOALLOC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// address of `scratch` on the current device, or NULL
+void* scratch_of_current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  g_scratch_ptr[dev].store(p, std::memory_order_release);     // racing first calls look up the same address
+  return p;
+}
+}  // namespace
+
+int palu_attn_decode_noalloc(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
+                             const void* q, const int32_t* q_pos,
+                             const void* hk, const void* hk_scale, const void* hk_zero,
+                             const void* hv, const void* hv_scale, const void* hv_zero,
+                             const int32_t* k_pos, const int32_t* seq_lens,
+                             const void* Bk, const void* Bv,
+                             const void* rope_table, int32_t rope_table_len,
+                             float* out, void* stream) {
+  size_t need = 0;
+  const int st = decode_workspace_bytes(desc, batch, 1, max_seq, &need);
+  if (st != PALU_OK) return st;
+  if (need > (size_t)PALU_NOALLOC_SCRATCH_BYTES) return PALU_ERR_WORKSPACE_TOO_SMALL;
+  void* ws = scratch_of_current_device();
+  if (!ws) return PALU_ERR_HIP;
+  // every region of the scratch is written by the step before it is read: nothing has to start at zero
+  return decode_impl(desc, batch, 1, nullptr, seq_len, max_seq, q, q_pos, hk, hk_scale, hk_zero, hv, hv_scale, hv_zero, k_pos,
+                     seq_lens, Bk, Bv, rope_table, rope_table_len, out, nullptr, ws, PALU_NOALLOC_SCRATCH_BYTES, stream,
+                     nullptr);
+}
+
 int palu_attn_decode_staged(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,
                             const void* q, const int32_t* q_pos,
                             const void* hk, const void* hk_scale, const void* hk_zero,
