@@ -350,17 +350,19 @@ struct Workspace {
   long long mfold_bstride, part_stride;
 };
 
-int carve(const Meta& m, int batch, int max_seq, int n_split_cap, int n_parts, Workspace* w) {
+// per_sequence_fold: the region behind `mfold` holds something per sequence (the folded queries of the non-RoPE
+// form); with RoPE it holds B_k in operand order, once.
+int carve(const Meta& m, int batch, int max_seq, int n_split_cap, int n_parts, bool per_sequence_fold, Workspace* w) {
   w->lpad = ceil_div(max_seq, 32) * 32;
   w->mfold_bstride = m.bk_off[m.n_groups];
   w->o_stride = m.bv_off[m.n_groups] / PALU_D_HEAD;
   w->part_stride = (long long)batch * m.n_heads * w->lpad;
   size_t off = 0;
-  w->mfold = off;   off = align_up(off + (size_t)batch * w->mfold_bstride * 2);
+  w->mfold = off;   off = align_up(off + (size_t)(per_sequence_fold ? batch : 1) * w->mfold_bstride * 2);
   w->scores = off;  off = align_up(off + (size_t)n_parts * w->part_stride * 4);
   w->o_part = off;  off = align_up(off + (size_t)batch * n_split_cap * w->o_stride * 4);
   w->ml_part = off; off = align_up(off + (size_t)batch * n_split_cap * m.n_heads * 2 * 4);
-  w->rope_rows = off; off = align_up(off + (size_t)w->lpad * PALU_D_HEAD * 2);   // cos/sin rows gathered by k_pos
+  w->rope_rows = off; off = align_up(off + (size_t)(w->lpad / 32) * kRopeTileBytes);   // angle tiles gathered by k_pos
   w->qsum = off; off = align_up(off + (size_t)batch * m.n_heads * (PALU_MAX_RANK / 128 + 2) * 4);   // int4 block sums of the folded queries (no-RoPE path)
   // several queries per key/value head: rotated queries as contraction operands, 2 feature halves x 4 KiB per key/value head
   w->qfrag = off; off = align_up(off + (m.qpk > 1 ? (size_t)batch * (m.n_heads / m.qpk) * 2 * 4096 : 0));
@@ -519,7 +521,7 @@ struct StepHeadArgs {
   EncodeArgs enc;
   EncodeTArgs enc_t;                     // TR instantiations: the projection from transposed weights, grid (enc_blocks)
   FoldArgs fold;
-  int fold_blocks, fold_gx, fold_gy;     // fold grid (k-steps, heads, batch), linearised
+  int fold_blocks, fold_gx;              // weight layout grid (k-steps, heads), linearised
   int enc_blocks, enc_gx, enc_gy;        // projection grid (column blocks, k splits, sides), linearised
   // shared-key form of the score kernel: its rotated-query operands are further items, after the fold's
   const uint16_t* sk_q;                  // the call's q, NULL when the step has no such items
@@ -533,8 +535,7 @@ __global__ __launch_bounds__(256) void step_head_kernel(StepHeadArgs a) {
   const int id = blockIdx.x;
   auto fold_item = [&]() __attribute__((always_inline)) {
     if (id < a.fold_blocks) {
-      const int ks = id % a.fold_gx, rest = id / a.fold_gx;
-      fold_body<T>(a.fold, ks, rest % a.fold_gy, rest / a.fold_gy);
+      fold_body(a.fold, id % a.fold_gx, id / a.fold_gx);
     } else if (id < a.fold_blocks + a.sk_blocks) {
       if constexpr (__is_same(T, F16)) {             // the shared-key form exists for fp16 latents only
         struct View {                                // QfragArgs' members, read in place from this kernel's arguments
@@ -691,7 +692,7 @@ int palu_set_option(const char* name, int value) {
 int palu_rope_table_bytes(int32_t d_head, int32_t n_pos, size_t* out_bytes) {
   if (!out_bytes || n_pos <= 0 || d_head <= 0) return PALU_ERR_INVALID_ARG;
   if (d_head != PALU_D_HEAD) return PALU_ERR_UNSUPPORTED;
-  *out_bytes = (size_t)n_pos * PALU_D_HEAD * 2;
+  *out_bytes = rope_tiles(n_pos) * kRopeTableStride;
   return PALU_OK;
 }
 
@@ -699,9 +700,11 @@ int palu_rope_table_init(float rope_theta, int32_t d_head, int32_t n_pos, void* 
   if (!table || n_pos <= 0 || d_head <= 0) return PALU_ERR_INVALID_ARG;
   if (d_head != PALU_D_HEAD) return PALU_ERR_UNSUPPORTED;
   if ((reinterpret_cast<uintptr_t>(table) & 15) != 0) return PALU_ERR_INVALID_ARG;
-  const long long items = (long long)n_pos * kHalf;
+  const long long n_pad = (long long)rope_tiles(n_pos) * kRopeTilePos;
+  if (n_pad > (1LL << 30)) return PALU_ERR_UNSUPPORTED;
+  const long long items = n_pad * kHalf;
   hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), static_cast<uint16_t*>(table), n_pos, rope_theta);
+                     static_cast<hipStream_t>(stream), static_cast<unsigned char*>(table), (int)n_pad, rope_theta);
   return launch_ok();
 }
 
@@ -987,7 +990,8 @@ static int decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch, in
   if ((st = plan_score(m, &sp, !(kb == 2 || kb == 3))) != PALU_OK) return st;
   if ((st = plan_pv(m, &pp)) != PALU_OK) return st;
   Workspace w;
-  carve(m, batch, max_seq, split_bound(pp.total_units, batch, max_seq, value_waves_per_cu(desc)), 2 * sp.max_slices, &w);
+  carve(m, batch, max_seq, split_bound(pp.total_units, batch, max_seq, value_waves_per_cu(desc)), 2 * sp.max_slices,
+        !(desc->rope_theta > 0.f), &w);
   *out_bytes = w.total;
   return PALU_OK;
 }
@@ -1046,7 +1050,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   if ((long long)split_tokens * std::max(Rk, Rv) * 2 >= (1LL << 32)) return PALU_ERR_UNSUPPORTED;
   const int n_split_cap = split_bound(pp.total_units, batch, max_seq, value_waves_per_cu(desc));
   Workspace w;
-  carve(m, batch, max_seq, n_split_cap, 2 * sp.max_slices, &w);
+  const bool no_rope = !(desc->rope_theta > 0.f);
+  carve(m, batch, max_seq, n_split_cap, 2 * sp.max_slices, no_rope, &w);
   if (n_split > n_split_cap) return PALU_ERR_INVALID_ARG;
   if (workspace_bytes < w.total) return PALU_ERR_WORKSPACE_TOO_SMALL;
 
@@ -1062,7 +1067,6 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     for (int i = 0; i <= PALU_DECODE_STAGES; ++i)
       if (!stage_events[i]) return PALU_ERR_INVALID_ARG;
 
-  const bool no_rope = !(desc->rope_theta > 0.f);
   bool enc_pending = enc != nullptr;
   if (enc_pending && enc->gemm) {
     if ((st = launch_encode(act, *enc, s)) != PALU_OK) return st;
@@ -1185,7 +1189,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   } else {
     // 2 .. 16 queries per key/value head (grouped-query heads times queries per sequence) with fp16
     // latents and ranks up to 256: the score kernel rebuilds each key once for the queries that
-    // share it (shared-key form).  Otherwise the folded form runs with one folded matrix per query.
+    // share it (shared-key form).  Otherwise every query head rebuilds its key/value head's keys (one-query form).
     bool shared_key = m.qpk >= 2 && m.qpk <= 16 && act == PALU_F16 && !k_i4 && waves8;
     for (int j = 0; j < m.n_groups && shared_key; ++j) shared_key = m.k_off[j + 1] - m.k_off[j] <= 256;
     const Meta mk = shared_key ? kv_head_meta(m) : m;
@@ -1193,29 +1197,24 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     if (shared_key && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
     const ScorePlan& plan = shared_key ? spk : sp;
 
-    // 1. fold the rotated query into B_k (shared-key form: B_k alone, and the rotated queries beside it)
+    // 1. B_k in the score kernel's operand order (shared-key form: and the rotated queries beside it)
+    static thread_local FoldArgs fa;
     {
-      FoldArgs a;
-      a.q = static_cast<const uint16_t*>(q);
-      a.q_pos = q_pos;
-      a.Bk = static_cast<const uint16_t*>(Bk);
-      a.mfold = reinterpret_cast<uint16_t*>(ws + w.mfold);
-      a.mfold_bstride = w.mfold_bstride;
-      a.theta = desc->rope_theta;
-      a.plain = shared_key ? 1 : 0;
+      fa.Bk = static_cast<const uint16_t*>(Bk);
+      fa.mfold = reinterpret_cast<uint16_t*>(ws + w.mfold);
       for (int f = 0; f < kHalf; ++f) {
         const double rev = desc->rope_theta > 0.f
             ? std::pow((double)desc->rope_theta, -2.0 * f / (double)PALU_D_HEAD) / 6.283185307179586476925 : 0.0;
-        a.rev_hi[f] = (float)rev;
-        a.rev_lo[f] = (float)(rev - (double)a.rev_hi[f]);
+        fa.rev_hi[f] = (float)rev;
+        fa.rev_lo[f] = (float)(rev - (double)fa.rev_hi[f]);
       }
-      a.meta = mk;
+      fa.meta = mk;
       int max_r = 0;
       for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
-      const dim3 g((unsigned)(max_r / 16), (unsigned)mk.n_heads, shared_key ? 1u : (unsigned)batch);
+      const dim3 g((unsigned)(max_r / 16), (unsigned)mk.n_heads, 1u);
       if ((st = mark(0)) != PALU_OK) return st;
-      // Fused only while every fold item finds a projection workgroup to ride in (one sequence of the 7B
-      // shape: 512 items, 512 workgroups); with more items than that the fold would dominate the launch.
+      // Fused only while every item finds a projection workgroup to ride in (the 7B shape: 512 items,
+      // 512 workgroups); with more items than that they would dominate the launch.
       unsigned ge0[3] = {0, 0, 0};
       if (enc_pending) encode_partial_grid(*enc, ge0);
       const long long fold_items = (long long)g.x * g.y * g.z + (shared_key ? (long long)mk.n_heads * batch : 0);
@@ -1229,10 +1228,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         static thread_local StepHeadArgs h;
         h.enc = enc->a;
         h.enc_t = enc->t;
-        h.fold = a;
+        h.fold = fa;
         h.fold_gx = (int)g.x;
-        h.fold_gy = (int)g.y;
-        h.fold_blocks = (int)(g.x * g.y * g.z);
+        h.fold_blocks = (int)(g.x * g.y);
         unsigned ge[3];
         encode_partial_grid(*enc, ge);
         h.enc_gx = (int)ge[0];
@@ -1241,7 +1239,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         h.sk_q = nullptr;
         h.sk_blocks = 0;
         if (shared_key) {                  // the rotated-query operands of the shared-key form ride along too
-          h.sk_q = a.q;
+          h.sk_q = static_cast<const uint16_t*>(q);
           h.sk_q_pos = q_pos;
           h.sk_qfrag = reinterpret_cast<uint16_t*>(ws + w.qfrag);
           h.sk_n_kv = mk.n_heads;
@@ -1259,18 +1257,17 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         if ((st = launch_encode_finish(act, *enc, s)) != PALU_OK) return st;
         enc_pending = false;
       } else {
-        if (act == PALU_F16) hipLaunchKernelGGL(fold_kernel<F16>, g, dim3(256), 0, s, a);
-        else hipLaunchKernelGGL(fold_kernel<BF16>, g, dim3(256), 0, s, a);
+        hipLaunchKernelGGL(fold_kernel, g, dim3(256), 0, s, fa);
         if ((st = launch_ok()) != PALU_OK) return st;
       }
       if (shared_key && !fused_head) {
         QfragArgs qa;
-        qa.q = a.q;
+        qa.q = static_cast<const uint16_t*>(q);
         qa.q_pos = q_pos;
         qa.qfrag = reinterpret_cast<uint16_t*>(ws + w.qfrag);
-        qa.theta = a.theta;
-        std::memcpy(qa.rev_hi, a.rev_hi, sizeof(qa.rev_hi));
-        std::memcpy(qa.rev_lo, a.rev_lo, sizeof(qa.rev_lo));
+        qa.theta = desc->rope_theta;
+        std::memcpy(qa.rev_hi, fa.rev_hi, sizeof(qa.rev_hi));
+        std::memcpy(qa.rev_lo, fa.rev_lo, sizeof(qa.rev_lo));
         qa.n_kv = mk.n_heads;
         qa.qpk = m.qpk;
         qa.nq = m.nq;
@@ -1283,15 +1280,23 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
 
     // 2. scores
     {
-      ScoreArgs a;
+      static thread_local ScoreArgs a;
       a.hk = hk;
       a.hk_scale = static_cast<const uint16_t*>(hk_scale);
       a.hk_zero = static_cast<const uint16_t*>(hk_zero);
       a.mfold = reinterpret_cast<const uint16_t*>(ws + w.mfold);
-      a.rope_rows = static_cast<const uint16_t*>(rope_table);
+      // the table's tiles: float32 part first, the shared-key form's float16 rows behind it
+      a.rope_rows = static_cast<const unsigned char*>(rope_table) + (shared_key ? kRopeTileBytes : 0);
+      a.rope_tile_stride = kRopeTableStride;
+      a.q = static_cast<const uint16_t*>(q);
+      a.q_pos = q_pos;
+      a.m_qpk = m.qpk;
+      a.m_nq = m.nq;
+      std::memcpy(a.rev_hi, fa.rev_hi, sizeof(a.rev_hi));
+      std::memcpy(a.rev_lo, fa.rev_lo, sizeof(a.rev_lo));
       a.seq_lens = seq_lens;
       a.scores = reinterpret_cast<float*>(ws + w.scores);
-      a.mfold_bstride = shared_key ? 0 : w.mfold_bstride;       // shared-key form: the weights do not depend on the sequence
+      a.mfold_bstride = 0;                                       // the weights do not depend on the sequence
       a.row_elems = Rk;
       a.max_seq = max_seq;
       a.seq_len = seq_len;
@@ -1307,16 +1312,19 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       a.n_kv = mk.n_heads;
       if ((st = mark(1)) != PALU_OK) return st;
       if (k_pos) {
-        // cos/sin rows in cached-token order, so that the score kernel needs no position loads
+        // angles in cached-token order, so that the score kernel needs no position loads
         RopeGatherArgs g;
-        g.table = static_cast<const uint16_t*>(rope_table);
+        g.table = rope_table;
         g.k_pos = k_pos;
-        g.rows = reinterpret_cast<uint16_t*>(ws + w.rope_rows);
-        g.n = seq_len;
+        g.rows = ws + w.rope_rows;
+        g.n = ceil_div(seq_len, 32) * 32;
+        g.k_pos_len = max_seq;
         g.table_len = rope_table_len;
-        hipLaunchKernelGGL(rope_gather_kernel, dim3((unsigned)ceil_div(seq_len * 16, 256)), dim3(256), 0, s, g);
+        if (shared_key) hipLaunchKernelGGL(rope_gather_kernel, dim3((unsigned)ceil_div(g.n * 16, 256)), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL(rope_gather_tiles_kernel, dim3((unsigned)ceil_div(g.n * 64, 256)), dim3(256), 0, s, g);
         if ((st = launch_ok()) != PALU_OK) return st;
         a.rope_rows = g.rows;
+        a.rope_tile_stride = shared_key ? kRopeRowsBytes : kRopeTileBytes;
       }
       const int tiles = ceil_div(seq_len, kTile);
       // Sequence chunks per (sequence, unit): every launch (one per rank class) should fill
@@ -1325,7 +1333,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         int n_chunks = std::max(1, std::min(tiles, (int)std::lround((double)device_cu_count() / (launch_units * batch))));
         if (g_opt_score_chunks > 0) n_chunks = std::min(tiles, (int)g_opt_score_chunks);
         // the kernel addresses a chunk of the cache with 32-bit byte offsets, and rows of it with 24-bit numbers
-        const long long chunk_limit_tiles = std::max(1LL, std::min<long long>((1LL << 31) / ((long long)Rk * 2 * kTile), (1LL << 24) / kTile));
+        // (and its angle tiles with 32-bit byte offsets)
+        const long long chunk_limit_tiles = std::max(1LL, std::min<long long>({(1LL << 31) / ((long long)Rk * 2 * kTile), (1LL << 24) / kTile,
+                                                                                 (1LL << 31) / kRopeTableStride}));
         n_chunks = std::max(n_chunks, (int)ceil_div(tiles, (int)std::min<long long>(chunk_limit_tiles, tiles)));
         const int chunk_tiles = ceil_div(tiles, n_chunks);
         a.chunk_tokens = chunk_tiles * kTile;
@@ -1335,8 +1345,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         const int id = plan.cls_id[cls];
         const int rc = id / 3, lg = id % 3;
         const int width = (32 * (rc + 1)) << lg;
-        const bool dma = act == PALU_F16 && !k_i4;
-        const size_t lds = (size_t)score_num_bufs(width, dma) * score_buf_bytes(width) + (shared_key ? score_qf_bytes() : 0);
+        const bool dma = !k_i4;
+        const bool pingpong = (waves8 && !rank_class_half(rc)) || shared_key;
+        const size_t lds = (size_t)score_lds_bytes(width, dma, !shared_key, pingpong);
         ScoreFn fn = shared_key ? (m.qpk <= 4 ? score_fn_shared<1>(rc) : score_fn_shared<2>(rc)) : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, id, waves8));
         if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
         const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;

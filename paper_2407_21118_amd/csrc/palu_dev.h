@@ -93,8 +93,23 @@ __device__ __forceinline__ uint32_t expand_low_bits(uint32_t lo16, uint32_t hi8,
 // column n = lane % 32 and rows 8*(i/4) + 4*(lane/32) + (i%4), i = 0..15.
 __device__ __forceinline__ int mfma_row(int i, int lane_hi) { return 8 * (i >> 2) + 4 * lane_hi + (i & 3); }
 
+// RoPE angle table, in tiles of 32 positions (tile T = positions 32T .. 32T+31), each tile two parts:
+//  (1) float32 [pair f 0..63][cos | sin][position j 0..31], 16 KiB, so that a lane that owns
+//      one rotation pair finds the angles of consecutive positions contiguously;
+//  (2) float16 rows [position j][128] in rope_slot order, 8 KiB, read by the shared-key score form.
+// Positions are rounded up to whole tiles.
+constexpr int kRopeTilePos = 32;
+constexpr int kRopeTileBytes = kHalf * 2 * kRopeTilePos * 4;      // 16384: part (1) of a tile
+constexpr int kRopeRowsBytes = kRopeTilePos * kDHead * 2;         //  8192: part (2) of a tile
+constexpr int kRopeTableStride = kRopeTileBytes + kRopeRowsBytes; // the table keeps both parts of a tile together
+__host__ __device__ __forceinline__ size_t rope_tiles(long long n_pos) { return (size_t)((n_pos + kRopeTilePos - 1) / kRopeTilePos); }
+// float index of (position p, pair f, cs = 0 cos / 1 sin) in tiles `stride` bytes apart
+__host__ __device__ __forceinline__ size_t rope_f32_index(long long p, int f, int cs, int stride) {
+  return (size_t)(p >> 5) * (stride / 4) + (size_t)((f * 2 + cs) * kRopeTilePos) + (size_t)(p & 31);
+}
+
 // Index of feature c' (0..127: 0..63 pair with cos, 64..127 with sin) inside a
-// rope-table row, arranged so that lane-half `hi` of a wave finds the 64
+// row of part (2), arranged so that lane-half `hi` of a wave finds the 64
 // values its accumulators need contiguously: [hi][row tile][i].
 __host__ __device__ __forceinline__ int rope_slot(int cprime) {
   const int rt = cprime >> 5, rr = cprime & 31;
@@ -125,8 +140,12 @@ struct ScoreArgs {
   const void* hk;            // latents or packed codes
   const uint16_t* hk_scale;  // fp16 bits (int4 only)
   const uint16_t* hk_zero;
-  const uint16_t* mfold;     // folded query-weights, per batch stride mfold_bstride elements
-  const uint16_t* rope_rows; // cos/sin row of cached token t at rope_rows + t*128 (the table itself, or rows gathered by k_pos)
+  const uint16_t* mfold;     // B_k transposed, in matrix-core operand order (fold_kernel); per batch stride mfold_bstride elements
+  const void* rope_rows;     // angles of the cached tokens in tiles of 32 tokens, rope_tile_stride bytes apart (the table
+                             // itself, or tiles gathered by k_pos): float32 parts (1) for the one-query form, float16 rows (2)
+                             // for the shared-key form
+  const uint16_t* q;         // one-query form: the queries before RoPE [batch, heads, 128] (see q_row) ...
+  const int32_t* q_pos;      // ... and their positions [batch * nq]
   const int32_t* seq_lens;
   float* scores;             // [parts][batch][n_heads][lpad]
   long long mfold_bstride;
@@ -146,14 +165,19 @@ struct ScoreArgs {
   const uint16_t* qfrag;     // rotated queries as contraction operands, see qfrag_kernel
   int qpk;                   // query heads per key/value head
   int n_kv;                  // key/value heads
+  int m_qpk, m_nq;           // one-query form: Meta::qpk and Meta::nq of the call (layout of q, see q_row)
+  int rope_tile_stride;
+  float rev_hi[kHalf];       // theta^(-2f/128) / (2 pi) from the host's float64 value, as a float pair hi + lo
+  float rev_lo[kHalf];
   ScoreUnits units;
 };
 
 struct RopeGatherArgs {
-  const uint16_t* table;
-  const int32_t* k_pos;
-  uint16_t* rows;            // [n] rows of 128 fp16
+  const void* table;         // the part of the table that is gathered
+  const int32_t* k_pos;      // [k_pos_len]
+  void* rows;                // tiles over token indices 0 .. n-1 (n a multiple of 32): float16 rows (8 KiB per tile) or float32 parts (16 KiB)
   int n;
+  int k_pos_len;
   int table_len;
 };
 
@@ -172,15 +196,10 @@ struct QfragArgs {
 };
 
 struct FoldArgs {
-  const uint16_t* q;         // [batch, n_heads, 128]
-  const int32_t* q_pos;
   const uint16_t* Bk;
-  uint16_t* mfold;
-  long long mfold_bstride;
-  float theta;
+  uint16_t* mfold;           // B_k transposed per head, in matrix-core operand order
   float rev_hi[kHalf];       // theta^(-2f/128) / (2 pi) from the host's float64 value, as a float pair hi + lo
-  float rev_lo[kHalf];
-  int plain;                 // 1: no query: M = B_k itself in operand order (the shared-key form of the score kernel)
+  float rev_lo[kHalf];       // (read by the query items that ride in the same launch, see qfrag_body)
   Meta meta;
 };
 

@@ -1,54 +1,69 @@
-// RoPE angle table and the per-step fold of the rotated query into B_k.
+// RoPE angle table, and B_k laid out as the stationary operand of the score kernel.
 //
-// Score identity used by the whole score path (RoPE pairs feature f with
-// f + 64, angle phi_f(t) = pos_t * theta^(-2f/128); Sec. 3.1.2):
-//   q' . RoPE(k, t) = sum_f cos(phi_f(t)) (q'_f k_f + q'_{f+64} k_{f+64})
-//                         + sin(phi_f(t)) (q'_{f+64} k_f - q'_f k_{f+64})
-// and with k = h B (Sec. 3.2.3) every bracket is h . (a column built from q' and B):
-//   u_f = q'_f B[:,f] + q'_{f+64} B[:,f+64],   w_f = q'_{f+64} B[:,f] - q'_f B[:,f+64].
-// The fold kernel writes M = [u_0..u_63 | w_0..w_63] (r x 128 per head, fp16) in the
-// register layout of the MFMA A operand, so that the score kernel's contraction
-// H_k . M is the reconstruction GEMM itself (same r x 128 MACs per token and
-// head) and RoPE reduces to one cos/sin-weighted sum per accumulator.
+// The score path rebuilds the key of every cached position, K[t] = H_k[t] B_k
+// (Sec. 3.2.3), on the matrix cores from the exact 16-bit inputs with float32
+// accumulation, rotates it (RoPE pairs feature f with f + 64, angle
+// phi_f(t) = pos_t * theta^(-2f/128); Sec. 3.1.2) and multiplies by the rotated query
+// q' in float32 (Sec. 2.1 Eq. 2).  With k = K[t], c = cos phi_f(t), s = sin phi_f(t):
+//   q' . RoPE(k, t) = sum_f  k_f (c q'_f + s q'_{f+64})  +  k_{f+64} (c q'_{f+64} - s q'_f).
+// fold_kernel writes B_k^T per head (128 x r) in the register layout of the matrix
+// instruction's operand; that layout does not depend on the query or the sequence.
 
 #include "palu_dev.h"
 
 namespace palu {
 
-// table[p][slot(c')] = fp16(cos(p w_c')) for c' < 64, fp16(sin(p w_{c'-64})) otherwise.
-__global__ __launch_bounds__(256) void rope_table_kernel(uint16_t* table, int n_pos, float theta) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;      // one (position, pair) per thread
+// One (position, pair) per thread; positions 0 .. 32 * ceil(n_pos / 32) - 1 (whole tiles); layout in palu_dev.h.
+__global__ __launch_bounds__(256) void rope_table_kernel(unsigned char* table, int n_pos_padded, float theta) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
   const int p = idx >> 6, f = idx & 63;
-  if (p >= n_pos) return;
+  if (p >= n_pos_padded) return;
   double c = 1.0, s = 0.0;
   if (theta > 0.f) {
     const double w = pow((double)theta, -2.0 * (double)f / (double)kDHead);
     sincos((double)p * w, &s, &c);
   }
-  uint16_t* row = table + (size_t)p * kDHead;
+  float* f32 = reinterpret_cast<float*>(table);
+  f32[rope_f32_index(p, f, 0, kRopeTableStride)] = (float)c;
+  f32[rope_f32_index(p, f, 1, kRopeTableStride)] = (float)s;
+  uint16_t* row = reinterpret_cast<uint16_t*>(table + (size_t)(p >> 5) * kRopeTableStride + kRopeTileBytes) + (size_t)(p & 31) * kDHead;
   row[rope_slot(f)] = F16::from_float((float)c);
   row[rope_slot(f + kHalf)] = F16::from_float((float)s);
 }
 
-// rows[t] = table[clamp(k_pos[t])]: lets the score kernel address cos/sin rows by
-// cached-token index without a dependent position load in its inner loop.
-// One thread per 16-byte piece of a row.
+// rows[t] = table[clamp(k_pos[t])] for the float16 rows: lets the shared-key score form address
+// cos/sin rows by cached-token index.  One thread per 16-byte piece of a row.
 __global__ __launch_bounds__(256) void rope_gather_kernel(RopeGatherArgs a) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
   const int t = idx >> 4, c = idx & 15;
   if (t >= a.n) return;
-  const int pos = max(0, min(a.k_pos[t], a.table_len - 1));
-  reinterpret_cast<uint4v*>(a.rows)[(size_t)t * 16 + c] = reinterpret_cast<const uint4v*>(a.table)[(size_t)pos * 16 + c];
+  const int pos = max(0, min(a.k_pos[min(t, a.k_pos_len - 1)], a.table_len - 1));
+  const unsigned char* src = static_cast<const unsigned char*>(a.table) + (size_t)(pos >> 5) * kRopeTableStride + kRopeTileBytes;
+  reinterpret_cast<uint4v*>(a.rows)[(size_t)t * 16 + c] = reinterpret_cast<const uint4v*>(src)[(size_t)(pos & 31) * 16 + c];
 }
 
-// grid (max k-steps of any head, n_heads, batch), 256 threads: one workgroup folds
-// one k-step (16 rows of B_k) of one head.  The 16 x 128 block of B_k is fetched
+// The same for the float32 tiles: the angles of cached token t (position k_pos[t]) at token
+// index t of the output tiles.  One thread per (token, pair); a.n is a multiple of 32 and
+// token indices past the end of k_pos repeat its last entry (they are never attended).
+__global__ __launch_bounds__(256) void rope_gather_tiles_kernel(RopeGatherArgs a) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int t = idx & 31, f = (idx >> 5) & 63, tile = idx >> 11;     // token fastest: coalesced stores
+  const int tok = tile * 32 + t;
+  if (tok >= a.n) return;
+  const int pos = max(0, min(a.k_pos[min(tok, a.k_pos_len - 1)], a.table_len - 1));
+  const float* src = static_cast<const float*>(a.table);
+  float* dst = static_cast<float*>(a.rows);
+  dst[rope_f32_index(tok, f, 0, kRopeTileBytes)] = src[rope_f32_index(pos, f, 0, kRopeTableStride)];
+  dst[rope_f32_index(tok, f, 1, kRopeTileBytes)] = src[rope_f32_index(pos, f, 1, kRopeTableStride)];
+}
+
+// grid (max k-steps of any head, n_heads), 256 threads: one workgroup lays out one
+// k-step (16 rows of B_k) of one head.  The 16 x 128 block of B_k is fetched
 // with coalesced 16-byte loads, transposed through LDS, and written as 256
-// 16-byte words in MFMA operand order.
-// (ks, h, b): the workgroup's position in that grid.
-template <typename T>
-__device__ __forceinline__ void fold_body(const FoldArgs& a, int ks, int h, int b) {
-  __shared__ float qr[kDHead];
+// 16-byte words in operand order: word (row tile rt, lane) = 8 consecutive k of
+// feature 32 rt + lane % 32, k-octet lane / 32.  The 16-bit values are copied as they are.
+// (ks, h): the workgroup's position in that grid.
+__device__ __forceinline__ void fold_body(const FoldArgs& a, int ks, int h) {
   __shared__ __attribute__((aligned(16))) uint16_t Bs[16][kDHead + 8];
   const int tid = threadIdx.x;
   const Meta& m = a.meta;
@@ -61,57 +76,26 @@ __device__ __forceinline__ void fold_body(const FoldArgs& a, int ks, int h, int 
   // rows 16*ks .. 16*ks+15 of this head's 128 columns: thread = (row, 8-column piece)
   const uint16_t* B = a.Bk + weight_block(m, j, h, m.bk_off[j], &width);
   const int lrow = tid >> 4, lcol = (tid & 15) * 8;
-  const uint4v raw = *reinterpret_cast<const uint4v*>(B + (size_t)(16 * ks + lrow) * width + lcol);
-
-  if (tid < kHalf && !a.plain) {
-    // rotate the query: angle = pos * w_f with w_f / 2pi given as a float pair
-    // (hi, lo) from the host's float64 value, so that the angle in revolutions
-    // keeps ~1e-7 absolute accuracy for positions up to 2^24
-    const uint16_t* qp = a.q + q_row(m, b, h) * kDHead;
-    const float x0 = T::to_float(qp[tid]);
-    const float x1 = T::to_float(qp[tid + kHalf]);
-    float c = 1.f, s = 0.f;
-    if (a.theta > 0.f) {
-      const float pos = (float)a.q_pos[b * m.nq + q_token(m, h)];
-      const float p = pos * a.rev_hi[tid];
-      const float e = fmaf(pos, a.rev_hi[tid], -p);
-      const float rev = (p - floorf(p)) + (e + pos * a.rev_lo[tid]);
-      s = __builtin_amdgcn_sinf(rev);
-      c = __builtin_amdgcn_cosf(rev);
-    }
-    qr[tid] = x0 * c - x1 * s;
-    qr[tid + kHalf] = x1 * c + x0 * s;
-  }
-  *reinterpret_cast<uint4v*>(&Bs[lrow][lcol]) = raw;
+  *reinterpret_cast<uint4v*>(&Bs[lrow][lcol]) = *reinterpret_cast<const uint4v*>(B + (size_t)(16 * ks + lrow) * width + lcol);
   __syncthreads();
 
-  // one item = (row tile rt, lane) = 8 consecutive k of feature row c' = 32*rt + lane%32
   const int lane = tid & 63, rt = tid >> 6;
   const int cp = 32 * rt + (lane & 31);
-  const int f = cp & 63;
-  const bool is_w = cp >= kHalf;
-  const float qa = a.plain ? 0.f : qr[f], qb = a.plain ? 0.f : qr[f + kHalf];
   const int k0 = 8 * (lane >> 5);
   uint16_t v[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float b1 = T::to_float(Bs[k0 + e][f]);
-    const float b2 = T::to_float(Bs[k0 + e][f + kHalf]);
-    const float val = a.plain ? (is_w ? b2 : b1) : (is_w ? (qb * b1 - qa * b2) : (qa * b1 + qb * b2));
-    v[e] = F16::from_float(val);       // the score kernel always contracts in fp16
-  }
+  for (int e = 0; e < 8; ++e) v[e] = Bs[k0 + e][cp];
   uint4v pk;
   pk.x = v[0] | ((uint32_t)v[1] << 16);
   pk.y = v[2] | ((uint32_t)v[3] << 16);
   pk.z = v[4] | ((uint32_t)v[5] << 16);
   pk.w = v[6] | ((uint32_t)v[7] << 16);
-  uint16_t* out = a.mfold + (size_t)b * a.mfold_bstride + m.bk_off[j] + (size_t)u * r * kDHead;
+  uint16_t* out = a.mfold + m.bk_off[j] + (size_t)u * r * kDHead;
   *reinterpret_cast<uint4v*>(out + ((size_t)ks * 256 + tid) * 8) = pk;
 }
 
-template <typename T>
 __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a) {
-  fold_body<T>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+  fold_body(a, blockIdx.x, blockIdx.y);
 }
 
 // Shared-key form of the score kernel: the rotated queries q' = RoPE(q, position of
@@ -143,7 +127,7 @@ __device__ __forceinline__ void qfrag_body(const A& a, int kvh, int b) {
     const float pos = (float)a.q_pos[b * a.nq + q_token(m, h)];
     const float p = pos * a.rev_hi[f];
     const float e = fmaf(pos, a.rev_hi[f], -p);
-    const float rev = (p - floorf(p)) + (e + pos * a.rev_lo[f]);      // angle in revolutions, as in fold_kernel
+    const float rev = (p - floorf(p)) + (e + pos * a.rev_lo[f]);      // angle in revolutions: ~1e-7 absolute accuracy for positions up to 2^24
     const float s = __builtin_amdgcn_sinf(rev), c = __builtin_amdgcn_cosf(rev);
     qr[hq][f] = x0 * c - x1 * s;
     qr[hq][f + kHalf] = x1 * c + x0 * s;
@@ -208,7 +192,5 @@ __global__ __launch_bounds__(256) void qfrag_kernel(QfragArgs a) {
 }
 
 template __global__ void qfrag_kernel<F16>(QfragArgs);
-template __global__ void fold_kernel<F16>(FoldArgs);
-template __global__ void fold_kernel<BF16>(FoldArgs);
 
 }  // namespace palu

@@ -1,22 +1,27 @@
 // Fused key reconstruction + RoPE + query product (Sec. 3.1.2, Appendix B):
 //   score[b,i,t] = RoPE(q_i) . RoPE(H_k[b,t] B_k)_i * log2(e)/sqrt(d_h)
-// computed as the contraction H_k . M_i on the matrix cores, where M_i is the
-// query-folded reconstruction matrix (see rope_fold.hip), followed by one
-// cos/sin-weighted sum per position in registers.  Reconstructed keys exist
-// only as MFMA accumulators.
+// The keys K = H_k B_k are rebuilt on the matrix cores from the 16-bit latents and
+// weights as they are (float32 accumulation), exist only as MFMA accumulators, and
+// are rotated and multiplied by the rotated query in float32 on the vector ALU:
+//   q' . RoPE(k, t) = sum_f k_f (c_f q'_f + s_f q'_{f+64}) + k_{f+64} (c_f q'_{f+64} - s_f q'_f)
+// with c_f, s_f the float32 cos / sin of the position's angle, read from the table.
+// Nothing on the way is rounded to 16 bits, so the logit error does not grow with the logit.
 //
 // Design for gfx950 (not the paper's one-thread-block-per-tile Triton layout):
-//   * weight-stationary: each wavefront keeps its slice of M_i (r x 128 fp16 per
-//     head) in registers for the lifetime of the workgroup, so the only operand
-//     that moves per token tile is the latent tile;
+//   * weight-stationary: each wavefront keeps its slice of B_k^T (128 x r per head,
+//     laid out by fold_kernel) in registers for the lifetime of the workgroup, so the
+//     only operand that moves per token tile is the latent tile;
 //   * a workgroup covers up to 4 heads that read the same (or adjacent) latent
 //     columns and walks a chunk of the sequence in tiles of 32 tokens; each tile
 //     (and its 32 cos/sin rows) is fetched once, several tiles ahead of its use.
 //     fp16 latents go from global memory straight into LDS (LDS-direct loads,
 //     no staging registers, waits counted by hand); bf16 and int4 latents are
 //     parked in registers, converted, and stored to LDS;
-//   * accumulators are computed transposed (features x tokens) so that the sum
-//     over the features of a token is an in-lane sum plus one cross-half exchange;
+//   * accumulators are tokens x features: a lane owns one feature (one rotation pair's
+//     half) of 16 tokens, so the rotated query enters as two registers per 32 features
+//     and the angles of consecutive tokens are one 16-byte LDS read; the sum over
+//     the features of a token is a halving exchange between lanes (DPP), 15 adds for
+//     16 tokens.  (The shared-key form below keeps the transposed layout, features x tokens.);
 //   * with 8 wavefronts (two per SIMD) the two wavefronts of a SIMD run half a
 //     tile out of phase ("ping-pong"): while one issues its MFMAs the other does
 //     its RoPE epilogue and queues loads, so the matrix pipe never waits for them.
@@ -48,37 +53,82 @@ __device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char*
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 constexpr int kRowPad = 16;                      // bytes of padding per LDS latent row: 16-byte column reads hit distinct banks
-constexpr int kRopeTileB = kTile * kDHead * 2;   // cos/sin rows of one tile in LDS (unpadded, XOR-swizzled)
+constexpr int kRopeTileB = kTile * kDHead * 2;   // shared-key form: float16 cos/sin rows of one tile in LDS (unpadded, XOR-swizzled)
 constexpr int kLdsBudget = 160 * 1024 - 1024;    // LDS of one CU, less a little slack
 
-// LDS bytes per buffered tile and number of buffers, shared with the host for the launch
-constexpr int score_buf_bytes(int width) { return kTile * (width * 2 + kRowPad) + kRopeTileB; }
+// LDS layout, shared with the host for the launch.
+// One-query form (`exact`): a ring of latent tiles, then a ring of float32 angle tiles (kRopeTileBytes each).
+// With the ping-pong schedule a wavefront reads a tile's angles one barrier phase after the tile's
+// latents were last read, so that ring is one tile longer than the latent ring.
+// Shared-key form: one ring of (latent tile + float16 angle rows), then the query operands.
+constexpr int score_tile_bytes(int width) { return kTile * (width * 2 + kRowPad); }
 constexpr int score_qf_bytes() { return 8 * 4096; }      // shared-key form: query operands of 8 wavefronts
-constexpr int score_num_bufs(int width, bool dma) {
-  return !dma ? 2 : (4 * score_buf_bytes(width) <= kLdsBudget ? 4 : 3);
+constexpr int score_num_bufs(int width, bool dma, bool exact, bool pingpong) {
+  if (!dma) return 2;
+  if (!exact) return 4 * (score_tile_bytes(width) + kRopeTileB) <= kLdsBudget ? 4 : 3;
+  for (int n = 4; n > 2; --n)
+    if (n * score_tile_bytes(width) + (n + (pingpong ? 1 : 0)) * kRopeTileBytes <= kLdsBudget) return n;
+  return 2;
+}
+constexpr int score_angle_bufs(int width, bool dma, bool exact, bool pingpong) {
+  if (!exact) return 0;
+  if (!dma) return pingpong ? 3 : 2;
+  return score_num_bufs(width, dma, exact, pingpong) + (pingpong ? 1 : 0);
+}
+constexpr int score_lds_bytes(int width, bool dma, bool exact, bool pingpong) {
+  return exact ? score_num_bufs(width, dma, true, pingpong) * score_tile_bytes(width) +
+                     score_angle_bufs(width, dma, true, pingpong) * kRopeTileBytes
+               : score_num_bufs(width, dma, false, pingpong) * (score_tile_bytes(width) + kRopeTileB) + score_qf_bytes();
 }
 
-// T:    storage type of unquantized latents.  The contraction itself always
-//       runs in fp16 with float32 accumulation: bfloat16 latents are converted
-//       while they are staged (exact for magnitudes in [2^-14, 65504],
-//       saturating above, truncating below), because a bfloat16 copy of the
-//       folded weights alone would cost 2^-9 relative error per element, more
-//       than the whole error budget.
+template <int CTRL>
+__device__ __forceinline__ float dpp_lane_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+
+// p[i], i = 4a + b, belongs to token 8a + 4 (lane / 32) + b of a 32-token tile and to the feature this lane
+// owns.  Returns the sum over the 32 lanes of the wavefront half of ONE of the lane's 16 tokens:
+//   token 16 L2 + 8 L0 + 4 (lane / 32) + 2 L1 + L3     (Lk = bit k of the lane number)
+// Four halving exchanges (a lane keeps the half of its values that its partner sends it the other half
+// of): 8 + 4 + 2 + 1 adds instead of 16 x 5.  Partners: 7 - l inside 8 lanes (any pairing serves while all
+// lanes hold all tokens), then lane ^ 1, lane ^ 2 and lane ^ 8, each agreeing on the bits that chose earlier
+// halves; the last step adds lane ^ 16.
+__device__ __forceinline__ float sum_tokens_over_features(const float (&p)[16], int lane) {
+  const bool l0 = lane & 1, l1 = lane & 2, l2 = lane & 4, l3 = lane & 8;
+  float v8[8], v4[4], v2[2];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v8[j] = (l2 ? p[8 + j] : p[j]) + dpp_lane_move<0x141>(l2 ? p[j] : p[8 + j]);       // row_half_mirror
+#pragma unroll
+  for (int j = 0; j < 4; ++j) v4[j] = (l0 ? v8[4 + j] : v8[j]) + dpp_lane_move<0xB1>(l0 ? v8[j] : v8[4 + j]);   // quad_perm [1,0,3,2]
+#pragma unroll
+  for (int j = 0; j < 2; ++j) v2[j] = (l1 ? v4[2 + j] : v4[j]) + dpp_lane_move<0x4E>(l1 ? v4[j] : v4[2 + j]);   // quad_perm [2,3,0,1]
+  const float v1 = (l3 ? v2[1] : v2[0]) + dpp_lane_move<0x128>(l3 ? v2[0] : v2[1]);                              // row_ror 8
+  return v1 + __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v1), 0x401F));       // lane ^ 16
+}
+__device__ __forceinline__ int summed_token_of_lane(int lane) {
+  return 16 * ((lane >> 2) & 1) + 8 * (lane & 1) + 4 * (lane >> 5) + 2 * ((lane >> 1) & 1) + ((lane >> 3) & 1);
+}
+
+// T:    storage type of the weights and of unquantized latents; the matrix instruction is
+//       the one of that type (fp16 or bf16 inputs as they are, float32 accumulation).
 // NKS:  k-steps of 16: the rank of every head in the workgroup is exactly 16*NKS
-// RT:   32-row feature tiles per wavefront: 4 = a whole head, 2 = half a head
-//       (the two halves of a head write separate partial scores)
+// RT:   32-feature tiles per wavefront: 4 = a whole head, 2 = half a head: features
+//       0..63 (the k_f of the identity above) or 64..127 (the k_{f+64}); the two halves
+//       of a head write separate partial scores
 // G:    groups spanned by the workgroup's heads (1, 2 or 4 adjacent groups of
 //       equal rank): the staged latent row is G*16*NKS columns wide
 // NW:   wavefronts per workgroup.  4: one per SIMD (RT = 4: four heads, RT = 2:
 //       two heads).  8: two per SIMD, RT = 2, four heads, ping-pong schedule:
-//       wavefronts 0-3 own the cos halves, 4-7 the sin halves.
+//       wavefronts 0-3 own features 0..63, 4-7 features 64..127.
 // I4:   latents are packed codes (4 bits; 3 or 2 with LB) with per-(token, block) scale and zero
-// QP:   0: one query per key/value head, folded into the weights as described above.
+// QP:   0: one query per head, float32 rotation and query product as described above.
 //       1, 2: shared-key form, for up to 4 (QP = 1) or 16 (QP = 2) queries per key/value
 //       head (the query heads of grouped-query attention, several query tokens per
-//       sequence, or both).
-//       The stationary operand is B_k itself (transposed), so the accumulators are the
-//       key K[feature][token], rebuilt once for all queries that share it.  With q' a
+//       sequence, or both).  Faster per query, but the rebuilt key, the angles and their
+//       products are rounded to fp16 on the way into the query contraction: its logit
+//       error grows with the logit (about 4e-4 of it).
+//       The accumulators are the key K[feature][token], rebuilt once for all queries
+//       that share it.  With q' a
 //       rotated query, its score is the contraction over f < 64 of
 //         K_f (cos_f q'_f + sin_f q'_{f+64})  +  K_{f+64} (cos_f q'_{f+64} - sin_f q'_f):
 //       a wavefront owns one half of the features (K_f or K_{f+64}), scales its
@@ -101,9 +151,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   static_assert(NW == 4 || (NW == 8 && RT == 2), "8 wavefronts only as half-head ping-pong");
   constexpr bool kIsBf16 = !__is_same(T, F16);
-  constexpr bool kDma = !I4 && !kIsBf16;                        // fp16 latents: global -> LDS without registers
-  static_assert(QP == 0 || (NW == 8 && G == 1 && kDma), "shared-key form: fp16 latents, ping-pong schedule, one group");
+  constexpr bool kExact = QP == 0;                              // one-query form
+  constexpr bool kDma = !I4;                                    // unquantized latents: global -> LDS without registers
+  static_assert(QP == 0 || (NW == 8 && G == 1 && kDma && !kIsBf16), "shared-key form: fp16 latents, ping-pong schedule, one group");
+  static_assert(!I4 || !kIsBf16, "quantized latents are dequantized to fp16");
   constexpr bool kPingPong = NW == 8;
+  using Vec = typename T::vec8;
   constexpr int kRank = NKS * 16;
   constexpr int kWidth = G * kRank;                             // staged columns per token
   static_assert(kWidth <= 512, "latent tile row too wide");
@@ -111,11 +164,13 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   constexpr int kChunks = kTile * kCpr;                         // chunks per tile
   constexpr int kThreads = NW * 64;
   constexpr int kPass = (kChunks + kThreads - 1) / kThreads;    // register staging: loads per thread and tile
-  constexpr int kCsPass = (kTile * 16) / kThreads;              // register staging: cos/sin chunks per thread and tile
+  constexpr int kCsPass = (kExact ? kRopeTileBytes / 16 : kTile * 16) / kThreads;   // register staging: angle chunks per thread and tile
   constexpr int kRowB = kWidth * 2 + kRowPad;                   // LDS row pitch in bytes
   constexpr int kTileB = kTile * kRowB;                         // latent tile bytes
-  constexpr int kBufB = score_buf_bytes(kWidth);                // + its cos/sin rows
-  constexpr int kBufs = score_num_bufs(kWidth, kDma);           // tiles resident in LDS
+  constexpr int kBufB = kExact ? kTileB : kTileB + kRopeTileB;  // pitch of the latent ring (shared-key form: + the tile's cos/sin rows)
+  constexpr int kBufs = score_num_bufs(kWidth, kDma, kExact, kPingPong);      // latent tiles resident in LDS
+  constexpr int kCsBufs = kExact ? score_angle_bufs(kWidth, kDma, true, kPingPong) : 1;   // one-query form: angle tiles resident in LDS ...
+  constexpr int kCsRing = kBufs * kBufB;                        // ... in a ring of their own behind the latent ring
   // LDS-direct: loop position k requests tile k + kAhead into the buffer that tile k-1
   // (whose last reader has passed a barrier) occupied; kBufs-2 requested tiles may
   // still be in flight when tile k+1 is needed
@@ -131,7 +186,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   constexpr int kPairB = 2 * kWidth * 2 + 2 * kRowPad;           // = 2 * kRowB: same tile size as the padded layout
   constexpr int kRowsPerWave = kTile / NW;
   constexpr int kRowOps = kPair ? kRowsPerWave / 2 : kRowsPerWave;
-  constexpr int kCsPerWave = kTile / 4 / NW;
+  constexpr int kCsPerWave = kExact ? kRopeTileBytes / 1024 / NW : kTile / 4 / NW;
   constexpr int kDmaOps = kRowOps + kCsPerWave;
 
   const int tid = threadIdx.x;
@@ -170,7 +225,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   const unsigned char* hk_base = (const unsigned char*)a.hk + (seq_base + t_begin) * row_bytes +
                                  (I4 ? (bits == 4 ? c_lo / 2 : c_lo / 4) : c_lo * 2);
   const unsigned hi_plane = (unsigned)a.row_elems / 4u + (unsigned)c_lo / 8u - (unsigned)c_lo / 4u;   // from hk_base to the third bits
-  const unsigned char* rope_base = (const unsigned char*)(a.rope_rows + (size_t)t_begin * kDHead);
+  // angles of the chunk's first token: float32 tiles of 32 tokens (t_begin is a multiple of 32), or float16 rows
+  const unsigned char* rope_base = (const unsigned char*)a.rope_rows + (size_t)(t_begin >> 5) * a.rope_tile_stride;
   const unsigned char* rope_base_u = uniform_ptr(rope_base);
   const unsigned lds_base = (unsigned)(size_t)lds;
 
@@ -192,6 +248,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     else dma_row_off[x] = (unsigned)(wave * kRowsPerWave + x) * row_bytes;
   }
   if (kPair) dma_pair_col = (unsigned)((lane + (lane >> 5)) & 31) * 16u;     // odd row: LDS slot j holds chunk j+1
+  // One-query form: an angle tile is 64 rows (rotation pairs) of 256 bytes: 8 pieces of cos, 8 of sin, 4 tokens
+  // each; in LDS piece P of row f sits at slot P ^ (f & 15), so that the 16-byte reads of 16 lanes that own
+  // consecutive pairs fall on distinct banks.  One request moves 4 rows: lane = (row, slot).
   unsigned dma_cs_off[kCsPerWave], dma_cs_swz[kCsPerWave];
 #pragma unroll
   for (int x = 0; x < kCsPerWave; ++x) {
@@ -203,17 +262,19 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   struct DmaTile {
     const unsigned char* src;    // first latent row of the tile
     unsigned lim;                // byte offset of the last attendable row inside the tile
-    unsigned cs_base, cs_lim;    // the same for the cos/sin rows (32-bit offsets from rope_base)
+    unsigned cs_base, cs_lim;    // the same for the cos/sin rows (32-bit offsets from rope_base); one-query form: the angle tile
     unsigned m0;                 // LDS address of the tile's buffer
+    unsigned m0cs;               // one-query form: LDS address of the tile's angle buffer
   };
   auto dma_tile = [&](int tile_unclamped) __attribute__((always_inline)) {
     DmaTile d;
     const int r0 = min(tile_unclamped, last_tile) * kTile;
     d.src = uniform_ptr(hk_base + (size_t)((unsigned)r0 * row_bytes));
     d.lim = (unsigned)(rel_last - r0) * row_bytes;
-    d.cs_base = (unsigned)r0 * (kDHead * 2u);
+    d.cs_base = (unsigned)(r0 >> 5) * (unsigned)a.rope_tile_stride;      // the tile's angles (float32 tile, or 32 float16 rows)
     d.cs_lim = (unsigned)(rel_last - r0) * (kDHead * 2u);
     d.m0 = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)((tile_unclamped % kBufs) * kBufB));
+    d.m0cs = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)(kCsRing + (tile_unclamped % kCsBufs) * kRopeTileBytes));
     return d;
   };
   // op x of a tile: x < kRowOps a latent row (or pair of rows), else a quad of cos/sin rows
@@ -230,6 +291,11 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
         if (kCpr == 64 || lane < kCpr)
           asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(src) : "memory");
       }
+    } else if constexpr (kExact) {
+      const int y = x - kRowOps;
+      const unsigned voff = d.cs_base + dma_cs_off[y] + dma_cs_swz[y];      // whole tiles exist in the table: no clamping
+      const unsigned m0v = d.m0cs + (unsigned)((wave * kCsPerWave + y) * 1024);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(m0v), "v"(voff), "s"(rope_base_u) : "memory");
     } else {
       const int y = x - kRowOps;
       const unsigned voff = d.cs_base + min(dma_cs_off[y], d.cs_lim) + dma_cs_swz[y];
@@ -255,8 +321,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     st_row[p] = id / kCpr;
     st_col[p] = id - st_row[p] * kCpr;
   }
-  // cos/sin rows: 16 chunks of 16 bytes per token, 512 chunks per tile, kCsPass adjacent ones per thread
-  const int rope_row = (tid * kCsPass) >> 4, rope_col = (tid * kCsPass) & 15;
+  // the angle tile's 1024 chunks, chunk x * kThreads + tid per pass (row = chunk / 16, piece = chunk % 16)
   struct Stage {
     uint4v h[kPass];
     uint4v cs[kCsPass];
@@ -264,11 +329,10 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   Stage st[2];
   auto issue_loads = [&](Stage& s, int tile_unclamped) {
     const int r0 = min(tile_unclamped, last_tile) * kTile;
-    {
-      const unsigned rel = (unsigned)min(r0 + rope_row, rel_last);
-      const uint4v* rp = reinterpret_cast<const uint4v*>(rope_base + rel * (kDHead * 2u) + rope_col * 16u);
+    if constexpr (kExact) {                              // (the shared-key form never stages through registers)
+      const uint4v* rp = reinterpret_cast<const uint4v*>(rope_base + (size_t)(r0 >> 5) * a.rope_tile_stride) + tid;
 #pragma unroll
-      for (int x = 0; x < kCsPass; ++x) s.cs[x] = rp[x];
+      for (int x = 0; x < kCsPass; ++x) s.cs[x] = rp[x * kThreads];
     }
 #pragma unroll
     for (int p = 0; p < kPass; ++p) {
@@ -290,12 +354,16 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
       }
     }
   };
-  auto store_stage = [&](Stage& s, int buf) {
+  // tile: the tile the stage holds (its angles go to buffer tile % kCsBufs of their own ring)
+  auto store_stage = [&](Stage& s, int buf, int tile) {
     unsigned char* base = lds + (size_t)buf * kBufB;
+    if constexpr (kExact) {
+      unsigned char* cb = lds + kCsRing + (size_t)(tile % kCsBufs) * kRopeTileBytes;
 #pragma unroll
-    for (int x = 0; x < kCsPass; ++x) {
-      const int c = rope_col + x;
-      *reinterpret_cast<uint4v*>(base + kTileB + rope_row * (kDHead * 2) + ((c ^ (rope_row & 15)) * 16)) = s.cs[x];
+      for (int x = 0; x < kCsPass; ++x) {
+        const int id = x * kThreads + tid, f = id >> 4, piece = id & 15;
+        *reinterpret_cast<uint4v*>(cb + f * 256 + ((piece ^ (f & 15)) * 16)) = s.cs[x];
+      }
     }
 #pragma unroll
     for (int p = 0; p < kPass; ++p) {
@@ -309,13 +377,6 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
           const float lo = ((float)((codes >> (8 * e)) & 15u) - z) * sc;
           const float hi = ((float)((codes >> (8 * e + 4)) & 15u) - z) * sc;
           v[e] = (uint32_t)F16::from_float(lo) | ((uint32_t)F16::from_float(hi) << 16);
-        }
-      } else if (kIsBf16) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float lo = __builtin_bit_cast(float, v[e] << 16);
-          const float hi = __builtin_bit_cast(float, v[e] & 0xffff0000u);
-          v[e] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
         }
       }
       if (p * kThreads + tid < kChunks) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + st_col[p] * 16) = v;
@@ -370,11 +431,11 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     h_off0 = h_off;
   }
   auto h_ptr = [&](const unsigned char* tile, int ks) __attribute__((always_inline)) {
-    return reinterpret_cast<const half8*>(tile + (ks == 0 ? h_off0 : h_off + ks * 32));
+    return reinterpret_cast<const Vec*>(tile + (ks == 0 ? h_off0 : h_off + ks * 32));
   };
 
-  // ---- stationary operand: folded weights of (b, head), rows [32*rt0, 32*(rt0+RT))
-  half8 W[NKS][RT];
+  // ---- stationary operand: B_k^T of the head, features [32*rt0, 32*(rt0+RT))
+  Vec W[NKS][RT];
   // shared-key form: the query operands of this wavefront's key/value head and feature half,
   // [8 steps][2 lane halves][16 queries] x 16 bytes, behind the tile buffers
   constexpr int kQfBytes = 4096;
@@ -388,7 +449,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
-        W[ks][rt] = *reinterpret_cast<const half8*>(mf + ((size_t)(ks * 4 + rt0 + rt) * 64 + lane) * 8);
+        W[ks][rt] = *reinterpret_cast<const Vec*>(mf + ((size_t)(ks * 4 + rt0 + rt) * 64 + lane) * 8);
   };
   // Ping-pong with LDS-direct loads: the wavefronts that run the first MFMA phase fetch their
   // weights now; the others only after the first barrier, so that the barrier does not wait
@@ -403,9 +464,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
 
   // MFMA phase of one tile: accumulators (features x tokens) and the tile's cos/sin weights
   struct TileAcc {
-    float16v acc[RT];
-    half8 cs[RT][2];
-    half8 sn[QP > 0 ? RT : 1][2];    // shared-key form: cs = cos, sn = sin of the accumulators' rotation pairs
+    float16v acc[RT];                // one-query form: K[token][feature]; shared-key form: K[feature][token]
+    half8 cs[QP > 0 ? RT : 1][2];    // shared-key form: cs = cos, sn = sin of the accumulators' rotation pairs
+    half8 sn[QP > 0 ? RT : 1][2];
   };
   auto mfma_phase = [&](TileAcc& r, int tile) {
     const unsigned char* base = lds + (size_t)(tile % kBufs) * kBufB;
@@ -415,42 +476,123 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     const unsigned char* crow = base + kTileB + lane_lo * (kDHead * 2);
     // B operand of k-step ks: 8 latent values of token lane_lo; fetched two steps ahead of its MFMAs
     constexpr int kAhead = 2;
-    half8 hf[kAhead + 1];
+    Vec hf[kAhead + 1];
 #pragma unroll
     for (int x = 0; x < kAhead && x < NKS; ++x) hf[x] = *h_ptr(base, x);
+    if constexpr (QP > 0) {
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
+      for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-      for (int hx = 0; hx < 2; ++hx) {
-        if constexpr (QP > 0) {
-          // accumulator row 32 (rt0 + rt) + x is feature f or f + 64 of pair f = 32 rt + x: cos_f sits in
-          // the table row where the folded form keeps the weight of row f, sin_f where it keeps that of row f + 64
+        for (int hx = 0; hx < 2; ++hx) {
+          // accumulator row 32 (rt0 + rt) + x is feature f or f + 64 of pair f = 32 rt + x: the table row
+          // keeps cos_f at slot(f) and sin_f at slot(f + 64)
           const int pc = lane_hi * 8 + rt * 2 + hx, ps = lane_hi * 8 + (rt + 2) * 2 + hx;
           r.cs[rt][hx] = *reinterpret_cast<const half8*>(crow + ((pc ^ (lane_lo & 15)) * 16));
           r.sn[rt][hx] = *reinterpret_cast<const half8*>(crow + ((ps ^ (lane_lo & 15)) * 16));
-        } else {
-          const int piece = lane_hi * 8 + (rt0 + rt) * 2 + hx;
-          r.cs[rt][hx] = *reinterpret_cast<const half8*>(crow + ((piece ^ (lane_lo & 15)) * 16));
         }
-      }
+    }
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       if (ks + kAhead < NKS)
         hf[(ks + kAhead) % (kAhead + 1)] = *h_ptr(base, ks + kAhead);
-      const half8 hfrag = hf[ks % (kAhead + 1)];
+      const Vec hfrag = hf[ks % (kAhead + 1)];
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
+        float16v prev;
         if (ks == 0) {
-          float16v zero;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) zero[i] = 0.f;
-          r.acc[rt] = F16::mfma(W[ks][rt], hfrag, zero);
+          for (int i = 0; i < 16; ++i) prev[i] = 0.f;
         } else {
-          r.acc[rt] = F16::mfma(W[ks][rt], hfrag, r.acc[rt]);
+          prev = r.acc[rt];
         }
+        // one-query form: rows = the tile's tokens (latents), columns = features (weights); shared-key form: transposed
+        r.acc[rt] = kExact ? T::mfma(hfrag, W[ks][rt], prev) : T::mfma(W[ks][rt], hfrag, prev);
       }
       __builtin_amdgcn_sched_barrier(0);        // keep the fetch-ahead order: nothing moves across a k-step
     }
+  };
+
+  // ---- one-query form: the rotated query of this wavefront's head, as the two factors of
+  // the identity at the top of the file for each of the lane's RT features, scaled by
+  // log2(e) / sqrt(d_h): score += K[t][feature] * (cos * qa + sin * qb).
+  // Feature 32 (rt0 + rt) + lane_lo is k_f (rows 0..63: qa = q'_f, qb = q'_{f+64}) or
+  // k_{f+64} (rows 64..127: qa = q'_{f+64}, qb = -q'_f) of pair f = 32 ((rt0 + rt) & 1) + lane_lo.
+  float qa[RT], qb[RT];
+  // (requested here, next to the weights; rotated after the start-up barrier, when they have long arrived)
+  uint16_t q_raw[RT][2];
+  float q_rev[RT][2];
+  int q_position = 0;
+  if constexpr (kExact) {
+    Meta mq;                                            // only the fields q_row and q_token read
+    mq.n_heads = a.n_heads; mq.qpk = a.m_qpk; mq.nq = a.m_nq;
+    const uint16_t* qp = a.q + q_row(mq, b, hc) * kDHead;
+    q_position = a.q_pos[b * a.m_nq + q_token(mq, hc)];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int f = 32 * ((rt0 + rt) & 1) + lane_lo;
+      q_raw[rt][0] = qp[f];
+      q_raw[rt][1] = qp[f + kHalf];
+      q_rev[rt][0] = a.rev_hi[f];
+      q_rev[rt][1] = a.rev_lo[f];
+    }
+  }
+  auto rotate_query = [&]() __attribute__((always_inline)) {
+    const float pos = (float)q_position;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int R = rt0 + rt;
+      const float x0 = T::to_float(q_raw[rt][0]), x1 = T::to_float(q_raw[rt][1]);
+      // angle = pos * w_f in revolutions, w_f / 2 pi given as a float pair (hi, lo) from the host's
+      // float64 value: ~1e-7 absolute accuracy for positions up to 2^24
+      const float ph = pos * q_rev[rt][0];
+      const float pe = fmaf(pos, q_rev[rt][0], -ph);
+      const float rev = (ph - floorf(ph)) + (pe + pos * q_rev[rt][1]);
+      const float sn = __builtin_amdgcn_sinf(rev), cn = __builtin_amdgcn_cosf(rev);
+      const float q0 = x0 * cn - x1 * sn, q1 = x1 * cn + x0 * sn;       // q'_f, q'_{f+64}
+      qa[rt] = (R < 2 ? q0 : q1) * a.scale;
+      qb[rt] = (R < 2 ? q1 : -q0) * a.scale;
+    }
+  };
+  // angle tile in LDS: pair f at row f (256 bytes), piece P (cos: 2a + lane_hi, sin: 8 + 2a + lane_hi, each the
+  // four tokens 8a + 4 lane_hi + 0..3) at slot P ^ (f & 15)
+  const unsigned cs_lane_off = (unsigned)lane_lo * 256u;
+  const unsigned cs_fx = (unsigned)(lane_lo & 15);
+  auto angle_piece = [&](const unsigned char* cst, int rp, int piece) __attribute__((always_inline)) {
+    return *reinterpret_cast<const float4v*>(cst + cs_lane_off + rp * (32 * 256) + (((unsigned)(piece + lane_hi) ^ cs_fx) * 16u));
+  };
+  auto angle_tile = [&](int tile) __attribute__((always_inline)) {
+    return lds + kCsRing + (size_t)(tile % kCsBufs) * kRopeTileBytes;
+  };
+  // part[4a + b] += contributions of the accumulators of angle rows rp (both of a pair's features when RT = 4)
+  auto rotate_dot_piece = [&](const float16v (&acc)[RT], float (&part)[16], int rp, int a4, const float4v& c, const float4v& s)
+      __attribute__((always_inline)) {
+#pragma unroll
+    for (int bb = 0; bb < 4; ++bb) {
+      const int i = 4 * a4 + bb;
+#pragma unroll
+      for (int rt = rp; rt < RT; rt += 2) {
+        const float coef = fmaf(s[bb], qb[rt], c[bb] * qa[rt]);
+        part[i] = fmaf(acc[rt][i], coef, part[i]);
+      }
+    }
+  };
+  auto exact_epilogue = [&](const float16v (&acc)[RT], int tile) __attribute__((always_inline)) {
+    const unsigned char* cst = angle_tile(tile);
+    float part[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) part[i] = 0.f;
+#pragma unroll
+    for (int rp = 0; rp < 2; ++rp)
+#pragma unroll
+      for (int a4 = 0; a4 < 4; ++a4) {
+        const float4v c = angle_piece(cst, rp, 2 * a4), s = angle_piece(cst, rp, 8 + 2 * a4);
+        rotate_dot_piece(acc, part, rp, a4, c, s);
+      }
+    const float sum = sum_tokens_over_features(part, lane);
+    // Unconditional store (a constant number of memory operations in flight): lanes l and l ^ 16 hold the
+    // same sum, idle wavefronts duplicate head h0's values, and rows past the end of the sequence fall into
+    // the padding of the score buffer (its pitch is a multiple of the tile), which nobody reads.
+    out_row[t_begin + tile * kTile + summed_token_of_lane(lane)] = sum;
   };
   // RoPE-weighted feature sum of one tile and the score store
   auto epilogue = [&](const TileAcc& r, int tile) {
@@ -517,20 +659,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
       }
       return;
     }
-    float part[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) part[i & 3] = fmaf(r.acc[rt][i], (float)r.cs[rt][0][i], part[i & 3]);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) part[i & 3] = fmaf(r.acc[rt][8 + i], (float)r.cs[rt][1][i], part[i & 3]);
-    }
-    const float sum = sum_across_halves((part[0] + part[1]) + (part[2] + part[3]));
-    // Unconditional store (a constant number of memory operations in flight): both
-    // lane halves hold the same sum, idle wavefronts duplicate head h0's values,
-    // and rows past the end of the sequence fall into the padding of the score
-    // buffer (its pitch is a multiple of the tile), which nobody reads.
-    out_row[t0 + lane_lo] = sum * a.scale;
+    exact_epilogue(r.acc, tile);
   };
 
   // ---- start-up
@@ -545,13 +674,14 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   } else {
     // tile 0 into LDS, tiles 1 and 2 in flight.  The explicit wait (vmcnt = 0) lets
     // the loop start from the same set of pending loads as every later iteration.
-    store_stage(st[0], 0);
+    store_stage(st[0], 0, 0);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     issue_loads(st[1], 1);
     issue_loads(st[0], 2);
   }
   __syncthreads();
   if (kSplitStart && wave >= 4) load_weights();
+  if constexpr (kExact) rotate_query();
 
   if constexpr (!kPingPong && kDma && NKS >= 4) {
     // One wavefront per SIMD, software-pipelined: while the matrix pipe works on
@@ -562,34 +692,37 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     // (all its readers are past the barrier).  The last k-steps already fetch the
     // first operands of tile k+1, so the pipe does not drain at the tile boundary.
     constexpr int kHalfK = NKS / 2 > 0 ? NKS / 2 : 1;
-    constexpr int kGroups = 2 * RT;                      // epilogue groups of 8 accumulators
+    // the previous tile's rotation and query product, in 32 items: item e = (angle row block rp, token quad a4, token bb)
+    // handles accumulator 4 a4 + bb of the feature tiles that read angle rows rp (one, or two when RT = 4)
+    constexpr int kItems = 32;
     float16v acc[2][RT];
-    half8 hf[3], hn[2];                                  // B operands of this tile (ring) and the next tile's first two
+    Vec hf[3], hn[2];                                    // latent operands of this tile (ring) and the next tile's first two
     auto tile_of = [&](int tile) { return lds + (size_t)(tile % kBufs) * kBufB; };
-    auto cs_piece = [&](int tile, int g) {               // cos/sin halves of accumulators 8*(g&1) .. +7 of row tile g>>1
-      const unsigned char* crow = lds + (size_t)(tile % kBufs) * kBufB + kTileB + lane_lo * (kDHead * 2);
-      const int piece = lane_hi * 8 + (rt0 + (g >> 1)) * 2 + (g & 1);
-      return *reinterpret_cast<const half8*>(crow + ((piece ^ (lane_lo & 15)) * 16));
-    };
     // `cur`: accumulator set of tile k; with_epi: tile k-1's sums are formed on the way.
     // Every MFMA is followed by its share of the other work and a scheduling fence, so
     // that the vector and memory instructions issue in the shadow of that MFMA.
-    constexpr int kEpiPer = (16 + kHalfK - 1) / kHalfK;  // previous tile's accumulators handled per MFMA of the first half
+    constexpr int kEpiPer = (kItems + kHalfK * RT - 1) / (kHalfK * RT);   // items per MFMA of the first half
     auto body = [&](auto cur_c, auto epi_c, int k) {
       constexpr int cur = decltype(cur_c)::value;
       constexpr bool with_epi = decltype(epi_c)::value;
       const unsigned char* hrow = tile_of(k);
       const unsigned char* hnext = tile_of(k + 1);
-      float part[4] = {0.f, 0.f, 0.f, 0.f};
-      half8 csr[2];
+      const unsigned char* cst = angle_tile(k - 1);
+      float part[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) part[i] = 0.f;
+      float4v csr[2][2];                                 // [ring][cos | sin] of the token quad being worked on and the next
       DmaTile nxt;
-      if (with_epi) csr[0] = cs_piece(k - 1, 0);
+      if (with_epi) {
+        csr[0][0] = angle_piece(cst, 0, 0);
+        csr[0][1] = angle_piece(cst, 0, 8);
+      }
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
         if (ks == kHalfK) {
           if (with_epi) {
-            const float sum = sum_across_halves((part[0] + part[1]) + (part[2] + part[3]));
-            out_row[t_begin + (k - 1) * kTile + lane_lo] = sum * a.scale;
+            const float sum = sum_tokens_over_features(part, lane);
+            out_row[t_begin + (k - 1) * kTile + summed_token_of_lane(lane)] = sum;
           }
           dma_wait(std::integral_constant<int, kAheadTiles - 2>{});   // tile k+1 has landed (this wavefront's share)
           __syncthreads();
@@ -599,26 +732,34 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
         // B operand two k-steps ahead; the last two steps fetch tile k+1's first operands
         if (ks + 2 < NKS) hf[(ks + 2) % 3] = *h_ptr(hrow, ks + 2);
         else hn[ks + 2 - NKS] = *h_ptr(hnext, ks + 2 - NKS);
-        const half8 hfrag = hf[ks % 3];
+        const Vec hfrag = hf[ks % 3];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
           if (ks == 0) {
             float16v zero;
 #pragma unroll
             for (int i = 0; i < 16; ++i) zero[i] = 0.f;
-            acc[cur][rt] = F16::mfma(W[ks][rt], hfrag, zero);
+            acc[cur][rt] = T::mfma(hfrag, W[ks][rt], zero);
           } else {
-            acc[cur][rt] = F16::mfma(W[ks][rt], hfrag, acc[cur][rt]);
+            acc[cur][rt] = T::mfma(hfrag, W[ks][rt], acc[cur][rt]);
           }
           if (ks < kHalfK) {
             if (with_epi) {
 #pragma unroll
               for (int j = 0; j < kEpiPer; ++j) {
-                const int e = (ks * RT + rt) * kEpiPer + j;      // accumulator e = 16 * row tile + i of tile k-1
-                if (e >= 16 * RT) continue;
-                const int g = e >> 3;
-                if ((e & 7) == 0 && g + 1 < kGroups) csr[(g + 1) & 1] = cs_piece(k - 1, g + 1);
-                part[e & 3] = fmaf(acc[cur ^ 1][e >> 4][e & 15], (float)csr[g & 1][e & 7], part[e & 3]);
+                const int e = (ks * RT + rt) * kEpiPer + j;      // item of tile k-1
+                if (e >= kItems) continue;
+                const int g = e >> 2, bb = e & 3, rp = g >> 2, a4 = g & 3;
+                if (bb == 0 && g + 1 < 8) {                      // the next token quad's angles
+                  csr[(g + 1) & 1][0] = angle_piece(cst, (g + 1) >> 2, 2 * ((g + 1) & 3));
+                  csr[(g + 1) & 1][1] = angle_piece(cst, (g + 1) >> 2, 8 + 2 * ((g + 1) & 3));
+                }
+                const int i = 4 * a4 + bb;
+#pragma unroll
+                for (int rr = rp; rr < RT; rr += 2) {
+                  const float coef = fmaf(csr[g & 1][1][bb], qb[rr], csr[g & 1][0][bb] * qa[rr]);
+                  part[i] = fmaf(acc[cur ^ 1][rr][i], coef, part[i]);
+                }
               }
             }
           } else {
@@ -644,16 +785,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
       body(C0{}, std::true_type{}, k + 1);
     }
     // the last tile's sums (its accumulator set: parity of n_tiles - 1)
-    TileAcc r;
     auto tail = [&](auto set_c, int tile) {
       constexpr int set = decltype(set_c)::value;
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        r.acc[rt] = acc[set][rt];
-        r.cs[rt][0] = cs_piece(tile, 2 * rt);
-        r.cs[rt][1] = cs_piece(tile, 2 * rt + 1);
-      }
-      epilogue(r, tile);
+      exact_epilogue(acc[set], tile);
     };
     if (k < n_tiles) {
       body(C1{}, std::true_type{}, k);
@@ -668,13 +802,13 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
       mfma_phase(r, k);
       epilogue(r, k);
       if (kDma) { dma_issue(k + kAheadTiles); dma_wait(std::integral_constant<int, kInFlight>{}); }
-      else      { store_stage(st[1], 1); issue_loads(st[1], k + 3); }
+      else      { store_stage(st[1], 1, k + 1); issue_loads(st[1], k + 3); }
       __syncthreads();
       if (k + 1 >= n_tiles) break;
       mfma_phase(r, k + 1);
       epilogue(r, k + 1);
       if (kDma) { dma_issue(k + 1 + kAheadTiles); dma_wait(std::integral_constant<int, kInFlight>{}); }
-      else      { store_stage(st[0], 0); issue_loads(st[0], k + 4); }
+      else      { store_stage(st[0], 0, k + 2); issue_loads(st[0], k + 4); }
       __syncthreads();
     }
   } else {
@@ -705,7 +839,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
         dma_wait(std::integral_constant<int, kInFlight>{});   // everything up to tile k+1 has landed
       } else {
         // past the last tile this publishes a duplicate of it into the buffer nobody reads any more
-        store_stage(s, (k + 1) & 1);
+        store_stage(s, (k + 1) & 1, k + 1);
         if (have) epilogue(r, tile_done);
         issue_loads(s, k + 3);
       }

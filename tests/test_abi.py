@@ -43,7 +43,7 @@ def test_workspace_queries_are_host_only():
     d = desc()
     assert P.palu_attn_decode_workspace_bytes(d, 2, 1000) > 0
     assert P.palu_encode_workspace_bytes(d, 0, 3) > 0
-    assert P.palu_rope_table_bytes(128, 1000) == 1000 * 128 * 2
+    assert P.palu_rope_table_bytes(128, 1000) == 32 * (16384 + 8192)      # whole tiles of 32 positions: float32 angles + float16 rows
 
 
 @pytest.mark.parametrize("kw,status", [

@@ -119,16 +119,16 @@ def test_no_rope_int4(k_i4, v_i4):
     check(case, TOL_I4, k_i4=k_i4, v_i4=v_i4, quant=quant)
 
 
-def test_peaked_softmax_and_large_logits():
-    """Queries scaled by 12 give logits of order +-40: the max-subtracted softmax
-    must not overflow.  The folded weights and the cos/sin table are fp16, so a
-    logit carries an absolute error proportional to its own scale (about 3e-4
-    of the logit spread); the output tolerance is scaled by the same factor."""
+@pytest.mark.parametrize("scale", [4.0, 8.0, 12.0])
+def test_peaked_softmax_and_large_logits(scale):
+    """Queries scaled by 4, 8 and 12 give logits of order +-13, +-27, +-40, the sizes trained models
+    produce: the max-subtracted softmax must not overflow, and the logit error must not grow with the
+    logit (keys are rebuilt and rotated in float32 from the exact 16-bit inputs): same tolerance."""
     layer = synth.uniform_layer(8, 4, 128)
     case = synth.make_case_orthonormal(layer, 1, 600, seed=6)
-    case.q = synth.round_to(case.q * 12.0, "f16")
-    case.name = "peaked"
-    check(case, TOL_FP * 12.0)
+    case.q = synth.round_to(case.q * scale, "f16")
+    case.name = f"peaked x{scale:g}"
+    check(case, TOL_FP)
 
 
 def test_config5b_joint_group_reduced_length():
