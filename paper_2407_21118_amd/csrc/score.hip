@@ -30,6 +30,10 @@
 
 #include "palu_dev.h"
 
+#ifndef PALU_PROBE
+#define PALU_PROBE 0
+#endif
+
 namespace palu {
 
 // x[lane] + x[lane ^ 32] in every lane, on the VALU (no LDS crossbar round trip).
@@ -406,10 +410,16 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   }
 
   // ---- which head / feature rows this wavefront owns
-  int wsel, rt0;
-  if (kPingPong)    { wsel = wave & 3; rt0 = (wave >> 2) * 2; }
-  else if (RT == 4) { wsel = wave; rt0 = 0; }
-  else              { wsel = wave >> 1; rt0 = (wave & 1) * 2; }
+  // wsel: head of the unit; hh: which half of it (RT = 2).  Shared-key form: the half is features 0..63 or
+  // 64..127 (feature tiles 2 hh, 2 hh + 1).  One-query form: the half is rotation pairs 0..31 or 32..63 with
+  // both of their features, k_f and k_{f+64} (feature tiles hh and hh + 2), so that a wavefront reads the
+  // angles of its pairs once for both.
+  int wsel, hh;
+  if (kPingPong)    { wsel = wave & 3; hh = wave >> 2; }
+  else if (RT == 4) { wsel = wave; hh = 0; }
+  else              { wsel = wave >> 1; hh = wave & 1; }
+  const int rt0 = 2 * hh;                                       // shared-key form: first feature tile
+  auto feature_tile = [&](int rt) __attribute__((always_inline)) { return (kExact && RT == 2) ? hh + 2 * rt : rt0 + rt; };
   const bool active = wsel < u.nh;
   const int hsel = active ? wsel : 0;                           // idle wavefronts mirror head h0: same values, same stores
   const int hc = u.h0 + hsel;
@@ -434,7 +444,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     return reinterpret_cast<const Vec*>(tile + (ks == 0 ? h_off0 : h_off + ks * 32));
   };
 
-  // ---- stationary operand: B_k^T of the head, features [32*rt0, 32*(rt0+RT))
+  // ---- stationary operand: B_k^T of the head, feature tiles feature_tile(0 .. RT-1)
   Vec W[NKS][RT];
   // shared-key form: the query operands of this wavefront's key/value head and feature half,
   // [8 steps][2 lane halves][16 queries] x 16 bytes, behind the tile buffers
@@ -449,7 +459,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
-        W[ks][rt] = *reinterpret_cast<const Vec*>(mf + ((size_t)(ks * 4 + rt0 + rt) * 64 + lane) * 8);
+        W[ks][rt] = *reinterpret_cast<const Vec*>(mf + ((size_t)(ks * 4 + feature_tile(rt)) * 64 + lane) * 8);
   };
   // Ping-pong with LDS-direct loads: the wavefronts that run the first MFMA phase fetch their
   // weights now; the others only after the first barrier, so that the barrier does not wait
@@ -457,7 +467,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   constexpr bool kSplitStart = kPingPong && kDma;
   if (!kSplitStart || wave < 4) load_weights();
 
-  const int part_idx = u.part0 + (RT == 2 ? (rt0 >> 1) : 0);
+  const int part_idx = u.part0 + (RT == 2 ? hh : 0);
   // row of head hc; in the shared-key form hc is a key/value head and its query heads' rows follow each other
   float* out_row = a.scores + ((size_t)part_idx * a.batch + b) * a.n_heads * (size_t)a.lpad +
                    (size_t)hc * (QP > 0 ? a.qpk : 1) * a.lpad;
@@ -470,9 +480,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   };
   auto mfma_phase = [&](TileAcc& r, int tile) {
     const unsigned char* base = lds + (size_t)(tile % kBufs) * kBufB;
-    // acc[rt][i] is feature 32*(rt0+rt) + mfma_row(i) of token lane_lo; its cos/sin weight is
-    // half (rt0+rt)*16 + i of the token's table row half lane_hi, i.e. 16-byte piece
-    // lane_hi*8 + (rt0+rt)*2 + i/8, stored at piece ^ (row & 15)
+    // shared-key form: acc[rt][i] is feature 32*(rt0+rt) + mfma_row(i) of token lane_lo; the cos/sin of its pair are
+    // halves of the token's table row, in 16-byte pieces stored at piece ^ (row & 15)
     const unsigned char* crow = base + kTileB + lane_lo * (kDHead * 2);
     // B operand of k-step ks: 8 latent values of token lane_lo; fetched two steps ahead of its MFMAs
     constexpr int kAhead = 2;
@@ -515,8 +524,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   // ---- one-query form: the rotated query of this wavefront's head, as the two factors of
   // the identity at the top of the file for each of the lane's RT features, scaled by
   // log2(e) / sqrt(d_h): score += K[t][feature] * (cos * qa + sin * qb).
-  // Feature 32 (rt0 + rt) + lane_lo is k_f (rows 0..63: qa = q'_f, qb = q'_{f+64}) or
-  // k_{f+64} (rows 64..127: qa = q'_{f+64}, qb = -q'_f) of pair f = 32 ((rt0 + rt) & 1) + lane_lo.
+  // Feature 32 R + lane_lo, R = feature_tile(rt), is k_f (R < 2: qa = q'_f, qb = q'_{f+64}) or
+  // k_{f+64} (R >= 2: qa = q'_{f+64}, qb = -q'_f) of pair f = 32 (R & 1) + lane_lo.
   float qa[RT], qb[RT];
   // (requested here, next to the weights; rotated after the start-up barrier, when they have long arrived)
   uint16_t q_raw[RT][2];
@@ -529,7 +538,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     q_position = a.q_pos[b * a.m_nq + q_token(mq, hc)];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const int f = 32 * ((rt0 + rt) & 1) + lane_lo;
+      const int f = 32 * (feature_tile(rt) & 1) + lane_lo;
       q_raw[rt][0] = qp[f];
       q_raw[rt][1] = qp[f + kHalf];
       q_rev[rt][0] = a.rev_hi[f];
@@ -540,7 +549,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     const float pos = (float)q_position;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const int R = rt0 + rt;
+      const int R = feature_tile(rt);
       const float x0 = T::to_float(q_raw[rt][0]), x1 = T::to_float(q_raw[rt][1]);
       // angle = pos * w_f in revolutions, w_f / 2 pi given as a float pair (hi, lo) from the host's
       // float64 value: ~1e-7 absolute accuracy for positions up to 2^24
@@ -555,25 +564,27 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   };
   // angle tile in LDS: pair f at row f (256 bytes), piece P (cos: 2a + lane_hi, sin: 8 + 2a + lane_hi, each the
   // four tokens 8a + 4 lane_hi + 0..3) at slot P ^ (f & 15)
-  const unsigned cs_lane_off = (unsigned)lane_lo * 256u;
+  // A wavefront works on kPairBlocks blocks of 32 pairs: block pb holds pairs 32 rp + lane_lo, rp = hh (RT = 2) or pb
+  // (RT = 4), and the accumulators of their two features: acc[pair_acc(pb, 0)] = k_f, acc[pair_acc(pb, 1)] = k_{f+64}.
+  constexpr int kPairBlocks = RT / 2;
+  auto pair_acc = [&](int pb, int h2) __attribute__((always_inline)) { return RT == 2 ? h2 : pb + 2 * h2; };
+  const unsigned cs_lane_off = (unsigned)((RT == 2 ? 32 * hh : 0) + lane_lo) * 256u;
   const unsigned cs_fx = (unsigned)(lane_lo & 15);
-  auto angle_piece = [&](const unsigned char* cst, int rp, int piece) __attribute__((always_inline)) {
-    return *reinterpret_cast<const float4v*>(cst + cs_lane_off + rp * (32 * 256) + (((unsigned)(piece + lane_hi) ^ cs_fx) * 16u));
+  auto angle_piece = [&](const unsigned char* cst, int pb, int piece) __attribute__((always_inline)) {
+    return *reinterpret_cast<const float4v*>(cst + cs_lane_off + (RT == 2 ? 0 : pb) * (32 * 256) + (((unsigned)(piece + lane_hi) ^ cs_fx) * 16u));
   };
   auto angle_tile = [&](int tile) __attribute__((always_inline)) {
     return lds + kCsRing + (size_t)(tile % kCsBufs) * kRopeTileBytes;
   };
-  // part[4a + b] += contributions of the accumulators of angle rows rp (both of a pair's features when RT = 4)
-  auto rotate_dot_piece = [&](const float16v (&acc)[RT], float (&part)[16], int rp, int a4, const float4v& c, const float4v& s)
+  // part[4 a4 + bb] += contribution of both features of pair block pb, token bb of token quad a4
+  auto rotate_dot = [&](const float16v (&acc)[RT], float (&part)[16], int pb, int a4, int bb, const float4v& c, const float4v& s)
       __attribute__((always_inline)) {
+    const int i = 4 * a4 + bb;
 #pragma unroll
-    for (int bb = 0; bb < 4; ++bb) {
-      const int i = 4 * a4 + bb;
-#pragma unroll
-      for (int rt = rp; rt < RT; rt += 2) {
-        const float coef = fmaf(s[bb], qb[rt], c[bb] * qa[rt]);
-        part[i] = fmaf(acc[rt][i], coef, part[i]);
-      }
+    for (int h2 = 0; h2 < 2; ++h2) {
+      const int rt = pair_acc(pb, h2);
+      const float coef = fmaf(s[bb], qb[rt], c[bb] * qa[rt]);
+      part[i] = fmaf(acc[rt][i], coef, part[i]);
     }
   };
   auto exact_epilogue = [&](const float16v (&acc)[RT], int tile) __attribute__((always_inline)) {
@@ -581,14 +592,30 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     float part[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) part[i] = 0.f;
+#if PALU_PROBE == 3
+    part[0] = acc[0][0] + acc[RT - 1][15];
+#else
 #pragma unroll
-    for (int rp = 0; rp < 2; ++rp)
+    for (int pb = 0; pb < kPairBlocks; ++pb)
 #pragma unroll
       for (int a4 = 0; a4 < 4; ++a4) {
-        const float4v c = angle_piece(cst, rp, 2 * a4), s = angle_piece(cst, rp, 8 + 2 * a4);
-        rotate_dot_piece(acc, part, rp, a4, c, s);
+#if PALU_PROBE == 1
+        const float4v c = {1.f, 0.5f, 0.25f, 2.f}, s = {1.f, 0.5f, 0.25f, 2.f};
+        (void)cst;
+#else
+        const float4v c = angle_piece(cst, pb, 2 * a4), s = angle_piece(cst, pb, 8 + 2 * a4);
+#endif
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb) rotate_dot(acc, part, pb, a4, bb, c, s);
       }
+#endif
+#if PALU_PROBE == 2 || PALU_PROBE == 3
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum += part[i];
+#else
     const float sum = sum_tokens_over_features(part, lane);
+#endif
     // Unconditional store (a constant number of memory operations in flight): lanes l and l ^ 16 hold the
     // same sum, idle wavefronts duplicate head h0's values, and rows past the end of the sequence fall into
     // the padding of the score buffer (its pitch is a multiple of the tile), which nobody reads.
@@ -692,9 +719,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     // (all its readers are past the barrier).  The last k-steps already fetch the
     // first operands of tile k+1, so the pipe does not drain at the tile boundary.
     constexpr int kHalfK = NKS / 2 > 0 ? NKS / 2 : 1;
-    // the previous tile's rotation and query product, in 32 items: item e = (angle row block rp, token quad a4, token bb)
-    // handles accumulator 4 a4 + bb of the feature tiles that read angle rows rp (one, or two when RT = 4)
-    constexpr int kItems = 32;
+    // the previous tile's rotation and query product, in items: item e = (pair block pb, token quad a4, token bb)
+    // handles accumulator 4 a4 + bb of both features of the block's pairs
+    constexpr int kItems = 16 * kPairBlocks;
     float16v acc[2][RT];
     Vec hf[3], hn[2];                                    // latent operands of this tile (ring) and the next tile's first two
     auto tile_of = [&](int tile) { return lds + (size_t)(tile % kBufs) * kBufB; };
@@ -749,17 +776,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
               for (int j = 0; j < kEpiPer; ++j) {
                 const int e = (ks * RT + rt) * kEpiPer + j;      // item of tile k-1
                 if (e >= kItems) continue;
-                const int g = e >> 2, bb = e & 3, rp = g >> 2, a4 = g & 3;
-                if (bb == 0 && g + 1 < 8) {                      // the next token quad's angles
+                const int g = e >> 2, bb = e & 3, pb = g >> 2, a4 = g & 3;
+                if (bb == 0 && g + 1 < 4 * kPairBlocks) {        // the next token quad's angles
                   csr[(g + 1) & 1][0] = angle_piece(cst, (g + 1) >> 2, 2 * ((g + 1) & 3));
                   csr[(g + 1) & 1][1] = angle_piece(cst, (g + 1) >> 2, 8 + 2 * ((g + 1) & 3));
                 }
-                const int i = 4 * a4 + bb;
-#pragma unroll
-                for (int rr = rp; rr < RT; rr += 2) {
-                  const float coef = fmaf(csr[g & 1][1][bb], qb[rr], csr[g & 1][0][bb] * qa[rr]);
-                  part[i] = fmaf(acc[cur ^ 1][rr][i], coef, part[i]);
-                }
+                rotate_dot(acc[cur ^ 1], part, pb, a4, bb, csr[g & 1][0], csr[g & 1][1]);
               }
             }
           } else {
