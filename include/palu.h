@@ -100,6 +100,12 @@ int palu_version(void);
  *   "score_waves"         4 or 8 wavefronts per score workgroup for ranks <= 256
  *   "score_chunks"        sequence chunks per (sequence, head block) in the score kernel
  *   "value_split_tokens"  tokens per sequence split in the value kernel (multiple of 32, <= 4096)
+ *   "shared_key_fp16"     1: with 2 .. 16 queries per key/value head (grouped-query heads, several queries per
+ *                         sequence), fp16 latents and ranks <= 256, rebuild each key once for the queries that
+ *                         share it and contract it with them on the matrix cores after rounding the key and
+ *                         its cos / sin products to fp16.  About 3x faster on a 4:1 grouped-query layer, but
+ *                         the logit error is about 4e-4 of the logit (output error 2e-3 reached at logits of
+ *                         about +-25).  Default 0: every query head rebuilds its keys in float32.
  *   "encode_tile_rows"    token rows per workgroup of the prompt-sized projection (64, 128 or 256, each
  *                         with 256 columns; 32 selects the narrow tile of 64 rows x 128 columns)
  * Unknown names and out-of-range values return PALU_ERR_INVALID_ARG.  Set

@@ -25,6 +25,7 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score workgroup (ranks <= 256)
 std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
 std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
+std::atomic<int> g_opt_shared_key_fp16{0};    // 1: the faster, fp16-rounded shared-key score form for 2 .. 16 queries per key/value head
 std::atomic<int> g_opt_encode_tile{0};        // token rows per workgroup of the prompt-sized projection
 
 int device_cu_count() {
@@ -281,21 +282,24 @@ struct QkPlan {
   size_t max_lds[2];               // staged folded-query bytes of the largest unit, per head-tile class
 };
 
-int plan_qk(const Meta& m, QkPlan* p) {
+// quantized: the key latents are codes (their kernels contract the hi part of the folded query only)
+int plan_qk(const Meta& m, bool quantized, QkPlan* p) {
   p->total_units = 0;
   p->qt_elems = p->qs_elems = 0;
   p->max_lds[0] = p->max_lds[1] = 0;
   auto add = [&](int h0, int nh, int c0, int ncols) -> int {
     if (p->total_units >= kMaxPlanUnits) return PALU_ERR_UNSUPPORTED;
     QkUnit& x = p->units[p->total_units++];
-    x.c0 = c0; x.h0 = (uint16_t)h0; x.ncols = (uint16_t)ncols; x.nh = (uint8_t)nh; x.pad = 0;
+    x.c0 = c0; x.h0 = (uint16_t)h0; x.ncols = (uint16_t)ncols; x.nh = (uint8_t)nh;
     x.wpad = (uint16_t)(ceil_div(ncols, 256) * 256);
     x.q_off = (int32_t)p->qt_elems;
     x.qs_off = (int32_t)p->qs_elems;
-    p->qt_elems += (long long)nh * x.wpad;
+    p->qt_elems += 2LL * nh * x.wpad;                  // hi and lo parts
     p->qs_elems += (long long)nh * (x.wpad >> 7);
+    const size_t staged = (size_t)nh * (x.wpad + 8) * 2;
+    x.use_lo = (uint8_t)((!quantized && 2 * staged <= 159 * 1024) ? 1 : 0);   // both parts staged in LDS while they fit
     size_t& lds = p->max_lds[nh > 16 ? 1 : 0];
-    lds = std::max(lds, (size_t)nh * (x.wpad + 8) * 2);
+    lds = std::max(lds, staged * (x.use_lo ? 2 : 1));
     return PALU_OK;
   };
   int st;
@@ -680,6 +684,9 @@ int palu_set_option(const char* name, int value) {
   } else if (!std::strcmp(name, "value_split_tokens")) {
     if (value != 0 && (value % 32 != 0 || value > 4096)) return PALU_ERR_INVALID_ARG;
     g_opt_value_split = value;
+  } else if (!std::strcmp(name, "shared_key_fp16")) {
+    if (value > 1) return PALU_ERR_INVALID_ARG;
+    g_opt_shared_key_fp16 = value;
   } else if (!std::strcmp(name, "encode_tile_rows")) {
     if (value != 0 && value != 32 && value != 64 && value != 128 && value != 256) return PALU_ERR_INVALID_ARG;
     g_opt_encode_tile = value;
@@ -1075,7 +1082,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   if (no_rope) {
     // 1'. fold the query into the latent space (Eq. 5); 2'. scores straight from the latents
     QkPlan qp;
-    if ((st = plan_qk(m, &qp)) != PALU_OK) return st;
+    if ((st = plan_qk(m, k_i4, &qp)) != PALU_OK) return st;
     if (qp.qt_elems > w.mfold_bstride) return PALU_ERR_UNSUPPORTED;     // the folded queries reuse the folded-weight region
     QfoldArgs f;
     f.q = static_cast<const uint16_t*>(q);
@@ -1190,7 +1197,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     // 2 .. 16 queries per key/value head (grouped-query heads times queries per sequence) with fp16
     // latents and ranks up to 256: the score kernel rebuilds each key once for the queries that
     // share it (shared-key form).  Otherwise every query head rebuilds its key/value head's keys (one-query form).
-    bool shared_key = m.qpk >= 2 && m.qpk <= 16 && act == PALU_F16 && !k_i4 && waves8;
+    bool shared_key = g_opt_shared_key_fp16 != 0 && m.qpk >= 2 && m.qpk <= 16 && act == PALU_F16 && !k_i4 && waves8;
     for (int j = 0; j < m.n_groups && shared_key; ++j) shared_key = m.k_off[j + 1] - m.k_off[j] <= 256;
     const Meta mk = shared_key ? kv_head_meta(m) : m;
     static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)

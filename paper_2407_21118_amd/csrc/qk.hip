@@ -6,7 +6,10 @@
 // bound by the latent stream alone (2 FLOP per latent element and head).
 //
 //   qfold_kernel  qt[b, unit][head, column] = q[b, head] . B_k[column, head's 128 features]
-//                 for the columns of the head's own group, 0 elsewhere
+//                 for the columns of the head's own group, 0 elsewhere; kept as a pair of fp16
+//                 numbers hi + lo (lo = the rounding error of hi), so that the folded query
+//                 carries ~22 bits into the matrix cores and the logit error stays far below
+//                 the tolerance for logits of any size (one fp16 number alone: ~3e-4 of the logit)
 //   qk_kernel     scores[b, head, t] = H_k[b, t, unit columns] . qt[b, unit][head, :] * log2(e)/sqrt(d_h)
 //
 // qk_kernel: one wavefront owns a range of tokens of one (sequence, unit) and
@@ -29,13 +32,13 @@ namespace palu {
 
 struct QkUnit {
   int32_t c0;          // first latent column
-  int32_t q_off;       // element offset of the unit's [nh][wpad] folded-query matrix (per sequence)
+  int32_t q_off;       // element offset of the unit's [2][nh][wpad] folded-query matrices, hi then lo (per sequence)
   int32_t qs_off;      // float offset of its [nh][wpad / 128] block sums (int4)
   uint16_t h0;
   uint16_t ncols;      // multiple of 32
   uint16_t wpad;       // ncols rounded up to a multiple of 256: columns of the staged matrix
   uint8_t nh;          // at most 32
-  uint8_t pad;
+  uint8_t use_lo;      // unquantized latents: the score kernel also contracts the lo part (its staging fits the LDS)
 };
 constexpr int kMaxQkUnits = 64;
 struct QkUnits {
@@ -132,7 +135,11 @@ __device__ __forceinline__ void qfold_body(const QfoldArgs& a, int bx, int by, i
     }
     s += __shfl_xor(s, 1, 64);
     const uint16_t hv = F16::from_float(s);        // the contraction runs in fp16 whatever the storage type
-    if ((tid & 1) == 0 && bb < nb) a.qt[(size_t)(b0 + bb) * a.qt_bstride + u.q_off + (size_t)hh * u.wpad + c] = hv;
+    if ((tid & 1) == 0 && bb < nb) {
+      uint16_t* dst = a.qt + (size_t)(b0 + bb) * a.qt_bstride + u.q_off + (size_t)hh * u.wpad + c;
+      dst[0] = hv;
+      dst[(size_t)u.nh * u.wpad] = F16::from_float(s - F16::to_float(hv));
+    }
     // sum of the rounded values over this 128-column block (int4 zero-point term)
     float r = (tid & 1) == 0 ? F16::to_float(hv) : 0.f;
 #pragma unroll
@@ -171,12 +178,14 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
                "s"((int)u.h0), "s"((int)u.ncols), "s"((int)u.wpad), "s"((int)u.nh));   // all in registers here: one round trip
   const int nh = u.nh, wpad = u.wpad;
   const int pitch = wpad + 8;                    // halfs per staged row: 16 bytes of padding keep the 16 head rows on distinct banks
+  const bool use_lo = !I4 && u.use_lo;           // uniform
+  const int lo_rows = nh * pitch * 2;            // byte offset of the lo rows behind the hi rows
 
   // ---- folded queries of the unit -> LDS (rows of heads beyond nh are never read: their lanes re-read row nh-1)
   {
     const uint16_t* src = a.qt + (size_t)b * a.qt_bstride + u.q_off;
     const int cpr = wpad >> 3;                   // 16-byte chunks per row
-    for (int i = tid; i < nh * cpr; i += 256) {
+    for (int i = tid; i < (use_lo ? 2 : 1) * nh * cpr; i += 256) {
       const int r = i / cpr, cc = i - r * cpr;
       *reinterpret_cast<uint4v*>(qk_lds + ((size_t)r * pitch + cc * 8) * 2) = *reinterpret_cast<const uint4v*>(src + (size_t)r * wpad + cc * 8);
     }
@@ -254,9 +263,12 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
     if constexpr (!I4) {
 #pragma unroll
       for (int x = 0; x < 8; ++x) {
-        half8 af[MT];
+        half8 af[MT], al[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) af[mt] = *reinterpret_cast<const half8*>(qk_lds + qrow[mt] + (chunk * 256 + x * 32 + kq * 8) * 2);
+        for (int mt = 0; mt < MT; ++mt) {
+          af[mt] = *reinterpret_cast<const half8*>(qk_lds + qrow[mt] + (chunk * 256 + x * 32 + kq * 8) * 2);
+          if (use_lo) al[mt] = *reinterpret_cast<const half8*>(qk_lds + lo_rows + qrow[mt] + (chunk * 256 + x * 32 + kq * 8) * 2);
+        }
 #pragma unroll
         for (int tau = 0; tau < 2; ++tau) {
           uint4v hw = st.h[tau][x];
@@ -268,7 +280,10 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
           }
           const half8 bop = __builtin_bit_cast(half8, hw);
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[mt], bop, acc[mt][tau], 0, 0, 0);
+          for (int mt = 0; mt < MT; ++mt) {
+            acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[mt], bop, acc[mt][tau], 0, 0, 0);
+            if (use_lo) acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al[mt], bop, acc[mt][tau], 0, 0, 0);
+          }
         }
       }
     } else {

@@ -80,19 +80,28 @@ def test_quantizer_bit_exact(dtype):
 
 
 def test_rope_table_values():
-    """Every (position, pair) of the table against float64 cos/sin, through the
-    private slot order probed with the library's own fold (indirectly covered by
-    parity) and directly here via sorted multisets per position."""
+    """Every tested (position, pair) of the table against float64 cos/sin.  The table is tiles of 32
+    positions, each a float32 part [pair][cos | sin][position in tile] (read by the score kernel; checked
+    entry by entry to float32 rounding) and float16 rows [position][128] in a private slot order (the
+    opt-in shared-key form; checked as sorted multisets per position)."""
     n_pos = 70000
+    tiles = (n_pos + 31) // 32
     table = P.palu_rope_table_init(10000.0, 128, n_pos)
     torch.cuda.synchronize()
-    t = table.view(torch.float16).view(n_pos, 128).float().cpu().numpy().astype(np.float64)
-    for p in (0, 1, 4095, 65535, 69999):
-        ang = p * O.rope_inv_freq(128, 10000.0)
+    assert table.numel() == tiles * (16384 + 8192) == P.palu_rope_table_bytes(128, n_pos)
+    raw = table.cpu().numpy().reshape(tiles, 16384 + 8192)
+    f32 = raw[:, :16384].copy().view(np.float32).reshape(tiles, 64, 2, 32).astype(np.float64)
+    f16 = raw[:, 16384:].copy().view(np.float16).reshape(tiles * 32, 128).astype(np.float64)
+    inv = O.rope_inv_freq(128, 10000.0)
+    for p in (0, 1, 31, 32, 4095, 65535, 69999, tiles * 32 - 1):       # the last tile is filled to its end
+        ang = p * inv
+        assert np.abs(f32[p // 32, :, 0, p % 32] - np.cos(ang)).max() <= 2.0 ** -24
+        assert np.abs(f32[p // 32, :, 1, p % 32] - np.sin(ang)).max() <= 2.0 ** -24
         want = np.sort(np.concatenate([np.cos(ang), np.sin(ang)]))
-        assert np.abs(np.sort(t[p]) - want).max() <= 2.0 ** -11
-    none = P.palu_rope_table_init(0.0, 128, 4).view(torch.float16).view(4, 128).float().cpu().numpy()
-    assert sorted(none[3].tolist()) == [0.0] * 64 + [1.0] * 64
+        assert np.abs(np.sort(f16[p]) - want).max() <= 2.0 ** -11
+    none = P.palu_rope_table_init(0.0, 128, 4).cpu().numpy().reshape(1, 16384 + 8192)
+    flat = none[:, :16384].copy().view(np.float32).reshape(64, 2, 32)
+    assert (flat[:, 0, :] == 1.0).all() and (flat[:, 1, :] == 0.0).all()
 
 
 def test_argument_errors_leave_output_untouched():

@@ -131,6 +131,35 @@ def test_peaked_softmax_and_large_logits(scale):
     check(case, TOL_FP)
 
 
+@pytest.mark.parametrize("theta,dtype,scale", [(0.0, "f16", 12.0), (0.0, "bf16", 12.0), (0.0, "f16", 4.0),
+                                               (10000.0, "bf16", 12.0), (500000.0, "f16", 8.0)])
+def test_large_logits_other_paths(theta, dtype, scale):
+    """The same for the non-RoPE form (folded query kept as an fp16 pair hi + lo), bf16 layers and
+    grouped-query heads (each query head rebuilds its keys in float32 by default)."""
+    import dataclasses
+    layer = dataclasses.replace(synth.uniform_layer(8, 4, 128), rope_theta=theta, q_per_kv=2 if theta > 10000.0 else 1)
+    case = synth.make_case_orthonormal(layer, 2, 500, seed=16, dtype=dtype)
+    case.q = synth.round_to(case.q * scale, dtype)
+    case.name = f"large logits theta={theta:g} x{scale:g}"
+    check(case, TOL_FP)
+
+
+def test_shared_key_fp16_option():
+    """The opt-in shared-key score form (fp16-rounded keys and angles in the query contraction, each key rebuilt
+    once for the queries that share it): within the tolerance at logits of order +-3; its error grows with the
+    logit, which is why it is not the default."""
+    import dataclasses
+    import paper_2407_21118_amd as P
+    layer = dataclasses.replace(synth.uniform_layer(8, 4, 128), q_per_kv=4)
+    case = synth.make_case_orthonormal(layer, 2, 300, seed=21)
+    case.name = "shared-key fp16"
+    P.palu_set_option("shared_key_fp16", 1)
+    try:
+        check(case, TOL_FP)
+    finally:
+        P.palu_set_option("shared_key_fp16", 0)
+
+
 def test_config5b_joint_group_reduced_length():
     """J-LRD: one group of all 32 heads, rank 2048 (contracted in rank slices)."""
     layer = synth.config_layer("5b")

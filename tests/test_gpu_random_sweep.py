@@ -1,7 +1,7 @@
 """Seeded random sweep over everything palu_attn_decode_multi takes at once: group sizes and
 ranks, query heads per key/value head, query tokens per sequence, RoPE base (or none), key and
 value latents in fp16 / bf16 / 4 / 3 / 2 bits independently, batch, ragged lengths, explicit
-cache positions.  Each case is compared with the oracle (fed the same dequantized latents).
+cache positions, and queries scaled by 1, 4, 8 or 12 (logits up to about +-40).  Each case is compared with the oracle (fed the same dequantized latents).
 A second sweep runs whole decode steps (append + attend) through both weight layouts."""
 
 import numpy as np
@@ -42,7 +42,9 @@ def one_case(seed):
     L = int(rng.choice([1, 7, 32, 33, 64, 100, 257, 300]))
     case = synth.make_case_orthonormal(layer, B, L, seed=1000 + seed, dtype=dtype)
     lens = np.array([L] + [int(rng.integers(1, L + 1)) for _ in range(B - 1)], np.int32)
-    q = synth.round_to(rng.standard_normal((B, n_q, layer.n_q_heads, 128)), dtype)
+    # logits of order +-3 (unit queries) up to +-40, the sizes trained models produce: the tolerance does not change
+    q_scale = float(np.random.default_rng([4243, seed]).choice([1.0, 1.0, 4.0, 8.0, 12.0]))
+    q = synth.round_to(rng.standard_normal((B, n_q, layer.n_q_heads, 128)) * q_scale, dtype)
     q_len = np.maximum(1, lens[:, None] - n_q + np.arange(n_q)[None, :] + 1).astype(np.int32)
     q_pos = (q_len - 1 + int(rng.integers(0, 3000))).astype(np.int32)
     k_pos = np.sort(rng.choice(8192, size=L, replace=False)).astype(np.int32) if rng.random() < 0.4 else None
@@ -77,7 +79,7 @@ def one_case(seed):
                               layer.v_rank_off, 128, theta, k_pos, qpk)
     whole, rows = rel_err(got.reshape(B, -1, 128), ref.reshape(B, -1, 128))
     tol = TOL_I4 if quant else TOL_FP
-    what = (f"seed {seed}: q_per_kv={qpk} n_q={n_q} theta={theta:g} k_bits={kb} v_bits={vb} {dtype} groups={sizes} "
+    what = (f"seed {seed}: q_per_kv={qpk} n_q={n_q} q_scale={q_scale:g} theta={theta:g} k_bits={kb} v_bits={vb} {dtype} groups={sizes} "
             f"k_ranks={kr} v_ranks={vr} B={B} L={L} k_pos={k_pos is not None}")
     return what, bool(np.isfinite(got).all()), max(whole, rows), tol
 
