@@ -4,6 +4,7 @@
 #include "encode_quant.hip"
 #include "rope_fold.hip"
 #include "score.hip"
+#include "score16.hip"
 #include "combine.hip"
 #include "pv.hip"
 #include "qk.hip"
@@ -114,7 +115,8 @@ int check_desc(const palu_layer_desc* d, Meta* m, int nq = 1) {
 // of equal rank as long as the staged row stays within 512 columns.  Above rank
 // 256 a wavefront owns half a head and a workgroup takes 2 heads of one group.
 constexpr int kNumRankCls = 16;
-constexpr int kNumScoreCls = kNumRankCls * 3;     // (rank class, log2 of groups per workgroup)
+constexpr int kSlicedCls = kNumRankCls * 3;       // class of the 256-row slices of ranks above 512
+constexpr int kNumScoreCls = kNumRankCls * 3 + 1; // (rank class, log2 of groups per workgroup), and the slices
 constexpr int kScoreMaxWidth = 512;               // latent columns one workgroup stages per token
 
 int rank_class(int r) { return (r >= 32 && r <= 512 && r % 32 == 0) ? r / 32 - 1 : -1; }
@@ -174,7 +176,7 @@ int plan_score(const Meta& m, ScorePlan* p, bool widen = true) {
         u.bk_off0 = m.bk_off[j0] + (h - m.head_off[j0]) * u.head_stride + sl * kSliceRank * PALU_D_HEAD;
         u.head_off0 = h;                 // heads of the unit are counted from h0 inside one group
         u.part0 = 2 * sl;
-        const int st = add_unit(rank_class(kSliceRank) * 3, u);
+        const int st = add_unit(kSlicedCls, u);
         if (st != PALU_OK) return st;
       }
       for (int x = 0; x < nh; ++x) p->slices[h + x] = n_sl;
@@ -434,6 +436,27 @@ ScoreFn score_fn(int act, bool i4, int cls_id, bool w8) {
   if (i4) return score_fn_t<F16, true>(rc, lg, w8);
   return act == PALU_F16 ? score_fn_t<F16, false>(rc, lg, w8) : score_fn_t<BF16, false>(rc, lg, w8);
 }
+
+// unquantized latents, ranks 64 .. 256, one query per head: one whole head per wavefront (score16.hip)
+template <typename T, int NK>
+ScoreFn score16_fn_g(int lg) {
+  if constexpr (NK <= 2) { if (lg == 2) return score16_kernel<T, NK, 4>; }
+  if constexpr (NK <= 4) { if (lg >= 1) return score16_kernel<T, NK, 2>; }
+  return score16_kernel<T, NK, 1>;
+}
+template <typename T>
+ScoreFn score16_fn_t(int rc, int lg) {
+  switch (rc) {
+    case 1: return score16_fn_g<T, 2>(lg);
+    case 2: return score16_fn_g<T, 3>(lg);
+    case 3: return score16_fn_g<T, 4>(lg);
+    case 4: return score16_fn_g<T, 5>(lg);
+    case 5: return score16_fn_g<T, 6>(lg);
+    case 6: return score16_fn_g<T, 7>(lg);
+    default: return score16_fn_g<T, 8>(lg);
+  }
+}
+inline bool rank_class_16(int rc) { return rc >= 1 && rc <= 7; }
 
 // 3- and 2-bit key latents: one group per workgroup, 8 wavefronts up to rank 256, 4 half-head wavefronts above
 template <int NKS>
@@ -1075,6 +1098,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       if (!stage_events[i]) return PALU_ERR_INVALID_ARG;
 
   bool enc_pending = enc != nullptr;
+  bool used16 = false;
   if (enc_pending && enc->gemm) {
     if ((st = launch_encode(act, *enc, s)) != PALU_OK) return st;
     enc_pending = false;
@@ -1200,6 +1224,10 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     bool shared_key = g_opt_shared_key_fp16 != 0 && m.qpk >= 2 && m.qpk <= 16 && act == PALU_F16 && !k_i4 && waves8;
     for (int j = 0; j < m.n_groups && shared_key; ++j) shared_key = m.k_off[j + 1] - m.k_off[j] <= 256;
     const Meta mk = shared_key ? kv_head_meta(m) : m;
+    // unquantized latents, one query per head: heads of rank 64 .. 256 run one whole head per wavefront
+    // (option score_waves = 4 or 8 forces the half-head / ping-pong schedules of score_kernel)
+    const bool use16 = !shared_key && !k_i4 && g_opt_score_waves == 0;
+    used16 = use16;
     static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)
     if (shared_key && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
     const ScorePlan& plan = shared_key ? spk : sp;
@@ -1216,6 +1244,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         fa.rev_lo[f] = (float)(rev - (double)fa.rev_hi[f]);
       }
       fa.meta = mk;
+      fa.layout16 = use16 ? 1 : 0;
       int max_r = 0;
       for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
       const dim3 g((unsigned)(max_r / 16), (unsigned)mk.n_heads, 1u);
@@ -1350,14 +1379,19 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       };
       for (int cls = 0; cls < plan.n_cls; ++cls) {
         const int id = plan.cls_id[cls];
-        const int rc = id / 3, lg = id % 3;
+        const bool sliced = id == kSlicedCls;
+        const int rc = sliced ? rank_class(kSliceRank) : id / 3, lg = sliced ? 0 : id % 3;
         const int width = (32 * (rc + 1)) << lg;
         const bool dma = !k_i4;
         const bool pingpong = (waves8 && !rank_class_half(rc)) || shared_key;
-        const size_t lds = (size_t)score_lds_bytes(width, dma, !shared_key, pingpong);
-        ScoreFn fn = shared_key ? (m.qpk <= 4 ? score_fn_shared<1>(rc) : score_fn_shared<2>(rc)) : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, id, waves8));
+        size_t lds = (size_t)score_lds_bytes(width, dma, !shared_key, pingpong);
+        const bool k16 = use16 && rank_class_16(rc) && !sliced;
+        ScoreFn fn = shared_key ? (m.qpk <= 4 ? score_fn_shared<1>(rc) : score_fn_shared<2>(rc))
+                   : k16 ? (act == PALU_F16 ? score16_fn_t<F16>(rc, lg) : score16_fn_t<BF16>(rc, lg))
+                   : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, rc * 3 + lg, waves8));
+        if (k16) lds = (size_t)score16_lds_bytes(width);
         if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
-        const unsigned threads = (waves8 && !rank_class_half(rc)) ? 512 : 256;
+        const unsigned threads = (waves8 && !rank_class_half(rc) && !k16) ? 512 : 256;
         auto flush = [&]() -> int {
           if (a.units.n_units == 0) return PALU_OK;
           set_chunks(a.units.n_units);
@@ -1382,7 +1416,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   std::memset(n_parts, 0, sizeof(n_parts));
   int max_parts = 0;
   for (int h = 0; h < m.n_heads; ++h) {      // half-head wavefronts write two planes per rank slice
-    n_parts[h] = no_rope ? (uint8_t)1 : (uint8_t)((waves8 || sp.half_heads[h]) ? 2 * sp.slices[h] : sp.slices[h]);
+    const int rk = m.k_off[m.group_of_head[h] + 1] - m.k_off[m.group_of_head[h]];
+    const bool whole = used16 && rank_class_16(rank_class(rk));       // one wavefront per head: one plane
+    n_parts[h] = no_rope ? (uint8_t)1 : (uint8_t)(((waves8 || sp.half_heads[h]) && !whole) ? 2 * sp.slices[h] : sp.slices[h]);
     max_parts = std::max(max_parts, (int)n_parts[h]);
   }
   if ((st = mark(2)) != PALU_OK) return st;

@@ -62,9 +62,13 @@ __global__ __launch_bounds__(256) void rope_gather_tiles_kernel(RopeGatherArgs a
 // with coalesced 16-byte loads, transposed through LDS, and written as 256
 // 16-byte words in operand order: word (row tile rt, lane) = 8 consecutive k of
 // feature 32 rt + lane % 32, k-octet lane / 32.  The 16-bit values are copied as they are.
+// Heads of rank 64 .. 256 are laid out for score16_kernel instead when a.layout16 is set (16-feature
+// operands of v_mfma_f32_16x16x32): per k-step of 32 rows, 512 words: word (feature tile ct, lane) =
+// 8 consecutive k (k-octet lane / 16 of the 32) of feature 16 ct + lane % 16; the workgroups of even ks
+// do two 16-row steps each.
 // (ks, h): the workgroup's position in that grid.
 __device__ __forceinline__ void fold_body(const FoldArgs& a, int ks, int h) {
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[16][kDHead + 8];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[32][kDHead + 8];
   const int tid = threadIdx.x;
   const Meta& m = a.meta;
   const int j = group_of(m, h);
@@ -72,6 +76,31 @@ __device__ __forceinline__ void fold_body(const FoldArgs& a, int ks, int h) {
   const int r = m.k_off[j + 1] - m.k_off[j];
   if (ks >= (r >> 4)) return;
   int width;
+  if (a.layout16 && r >= 64 && r <= 256) {
+    if (ks & 1) return;
+    const uint16_t* B = a.Bk + weight_block(m, j, h, m.bk_off[j], &width);
+    const int lrow = tid >> 3, lcol = (tid & 7) * 16;             // thread = (row of 32, 16-column piece)
+    const uint16_t* src = B + (size_t)(16 * ks + lrow) * width + lcol;
+    *reinterpret_cast<uint4v*>(&Bs[lrow][lcol]) = *reinterpret_cast<const uint4v*>(src);
+    *reinterpret_cast<uint4v*>(&Bs[lrow][lcol + 8]) = *reinterpret_cast<const uint4v*>(src + 8);
+    __syncthreads();
+    uint16_t* out = a.mfold + m.bk_off[j] + (size_t)u * r * kDHead + (size_t)(ks >> 1) * 512 * 8;
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const int w = tid + 256 * x, ct = w >> 6, lane = w & 63;
+      const int col = 16 * ct + (lane & 15), k0 = 8 * (lane >> 4);
+      uint16_t v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = Bs[k0 + e][col];
+      uint4v pk;
+      pk.x = v[0] | ((uint32_t)v[1] << 16);
+      pk.y = v[2] | ((uint32_t)v[3] << 16);
+      pk.z = v[4] | ((uint32_t)v[5] << 16);
+      pk.w = v[6] | ((uint32_t)v[7] << 16);
+      *reinterpret_cast<uint4v*>(out + (size_t)w * 8) = pk;
+    }
+    return;
+  }
 
   // rows 16*ks .. 16*ks+15 of this head's 128 columns: thread = (row, 8-column piece)
   const uint16_t* B = a.Bk + weight_block(m, j, h, m.bk_off[j], &width);

@@ -28,11 +28,8 @@
 
 #include <type_traits>
 
+#pragma once
 #include "palu_dev.h"
-
-#ifndef PALU_PROBE
-#define PALU_PROBE 0
-#endif
 
 namespace palu {
 
@@ -464,7 +461,11 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   // Ping-pong with LDS-direct loads: the wavefronts that run the first MFMA phase fetch their
   // weights now; the others only after the first barrier, so that the barrier does not wait
   // for the issue of their 32 KiB each and their fetch overlaps the first phase.
-  constexpr bool kSplitStart = kPingPong && kDma;
+  // one-query form with LDS-direct staging: every wavefront runs the software-pipelined loop below by itself (two to a
+  // SIMD with 8 wavefronts: the matrix instructions of the two interleave, which hides the issue gap between
+  // back-to-back matrix instructions of one wavefront); the phase-alternating ping-pong remains for the other forms
+  constexpr bool kPipelined = kExact && kDma && NKS >= 4 && kBufs >= 3;
+  constexpr bool kSplitStart = kPingPong && kDma && !kPipelined;
   if (!kSplitStart || wave < 4) load_weights();
 
   const int part_idx = u.part0 + (RT == 2 ? hh : 0);
@@ -592,30 +593,15 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     float part[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) part[i] = 0.f;
-#if PALU_PROBE == 3
-    part[0] = acc[0][0] + acc[RT - 1][15];
-#else
 #pragma unroll
     for (int pb = 0; pb < kPairBlocks; ++pb)
 #pragma unroll
       for (int a4 = 0; a4 < 4; ++a4) {
-#if PALU_PROBE == 1
-        const float4v c = {1.f, 0.5f, 0.25f, 2.f}, s = {1.f, 0.5f, 0.25f, 2.f};
-        (void)cst;
-#else
         const float4v c = angle_piece(cst, pb, 2 * a4), s = angle_piece(cst, pb, 8 + 2 * a4);
-#endif
 #pragma unroll
         for (int bb = 0; bb < 4; ++bb) rotate_dot(acc, part, pb, a4, bb, c, s);
       }
-#endif
-#if PALU_PROBE == 2 || PALU_PROBE == 3
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) sum += part[i];
-#else
     const float sum = sum_tokens_over_features(part, lane);
-#endif
     // Unconditional store (a constant number of memory operations in flight): lanes l and l ^ 16 hold the
     // same sum, idle wavefronts duplicate head h0's values, and rows past the end of the sequence fall into
     // the padding of the score buffer (its pitch is a multiple of the tile), which nobody reads.
@@ -710,7 +696,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   if (kSplitStart && wave >= 4) load_weights();
   if constexpr (kExact) rotate_query();
 
-  if constexpr (!kPingPong && kDma && NKS >= 4) {
+  if constexpr (kPipelined) {
     // One wavefront per SIMD, software-pipelined: while the matrix pipe works on
     // tile k, the vector ALU does the cos/sin-weighted sums of tile k-1 (whose
     // accumulators sit in a second register set) in the shadow of the MFMAs of
@@ -723,7 +709,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     // handles accumulator 4 a4 + bb of both features of the block's pairs
     constexpr int kItems = 16 * kPairBlocks;
     float16v acc[2][RT];
-    Vec hf[3], hn[2];                                    // latent operands of this tile (ring) and the next tile's first two
+    // latent operands are fetched kOpAhead k-steps ahead (two wavefronts to a SIMD: one is enough and saves registers)
+    constexpr int kOpAhead = NW == 8 ? 1 : 2;
+    Vec hf[kOpAhead + 1], hn[kOpAhead];                  // latent operands of this tile (ring) and the next tile's first ones
     auto tile_of = [&](int tile) { return lds + (size_t)(tile % kBufs) * kBufB; };
     // `cur`: accumulator set of tile k; with_epi: tile k-1's sums are formed on the way.
     // Every MFMA is followed by its share of the other work and a scheduling fence, so
@@ -756,10 +744,10 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
           nxt = dma_tile(k + kAheadTiles);
           __builtin_amdgcn_sched_barrier(0);
         }
-        // B operand two k-steps ahead; the last two steps fetch tile k+1's first operands
-        if (ks + 2 < NKS) hf[(ks + 2) % 3] = *h_ptr(hrow, ks + 2);
-        else hn[ks + 2 - NKS] = *h_ptr(hnext, ks + 2 - NKS);
-        const Vec hfrag = hf[ks % 3];
+        // latent operand kOpAhead k-steps ahead; the last steps fetch tile k+1's first operands
+        if (ks + kOpAhead < NKS) hf[(ks + kOpAhead) % (kOpAhead + 1)] = *h_ptr(hrow, ks + kOpAhead);
+        else hn[ks + kOpAhead - NKS] = *h_ptr(hnext, ks + kOpAhead - NKS);
+        const Vec hfrag = hf[ks % (kOpAhead + 1)];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
           if (ks == 0) {
@@ -793,13 +781,13 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
       }
 #pragma unroll
       for (int x = (NKS - kHalfK) * RT; x < kDmaOps; ++x) dma_issue_op(nxt, x);   // few k-steps: the rest of the requests
-      hf[0] = hn[0];
-      hf[1] = hn[1];
+#pragma unroll
+      for (int x = 0; x < kOpAhead; ++x) hf[x] = hn[x];
     };
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
-    hf[0] = *h_ptr(tile_of(0), 0);
-    hf[1] = *h_ptr(tile_of(0), 1);
+#pragma unroll
+    for (int x = 0; x < kOpAhead; ++x) hf[x] = *h_ptr(tile_of(0), x);
     body(C0{}, std::false_type{}, 0);
     int k = 1;
     for (; k + 1 < n_tiles; k += 2) {

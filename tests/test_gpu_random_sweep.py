@@ -70,17 +70,23 @@ def one_case(seed):
     table = P.palu_rope_table_init(theta, 128, n_pos)
     if k_pos is not None:
         kw["k_pos"] = torch.from_numpy(k_pos).cuda()
-    out = P.palu_attn_decode_multi(desc, B, n_q, L, L, to_dev(q, dtype), torch.from_numpy(q_pos).cuda(), hk, hv,
-                                   to_dev(case.Bk, dtype), to_dev(case.Bv, dtype), table, n_pos,
-                                   q_len=torch.from_numpy(q_len).cuda(), seq_lens=torch.from_numpy(lens).cuda(), **kw)
-    torch.cuda.synchronize()
+    # the score kernel's schedules: 0 = the library's choice, 8 / 4 = wavefronts per workgroup of the general kernel
+    waves = int(np.random.default_rng([4244, seed]).choice([0, 0, 8, 4]))
+    P.palu_set_option("score_waves", waves)
+    try:
+        out = P.palu_attn_decode_multi(desc, B, n_q, L, L, to_dev(q, dtype), torch.from_numpy(q_pos).cuda(), hk, hv,
+                                       to_dev(case.Bk, dtype), to_dev(case.Bv, dtype), table, n_pos,
+                                       q_len=torch.from_numpy(q_len).cuda(), seq_lens=torch.from_numpy(lens).cuda(), **kw)
+        torch.cuda.synchronize()
+    finally:
+        P.palu_set_option("score_waves", 0)
     got = out.cpu().numpy()
     ref = O.attn_decode_multi(q, q_pos, q_len, Hk_ref, Hv_ref, case.Bk, case.Bv, layer.group_head_off, layer.k_rank_off,
                               layer.v_rank_off, 128, theta, k_pos, qpk)
     whole, rows = rel_err(got.reshape(B, -1, 128), ref.reshape(B, -1, 128))
     tol = TOL_I4 if quant else TOL_FP
     what = (f"seed {seed}: q_per_kv={qpk} n_q={n_q} q_scale={q_scale:g} theta={theta:g} k_bits={kb} v_bits={vb} {dtype} groups={sizes} "
-            f"k_ranks={kr} v_ranks={vr} B={B} L={L} k_pos={k_pos is not None}")
+            f"k_ranks={kr} v_ranks={vr} B={B} L={L} k_pos={k_pos is not None} score_waves={waves}")
     return what, bool(np.isfinite(got).all()), max(whole, rows), tol
 
 
