@@ -263,6 +263,25 @@ def main() -> int:
     ms_per_step = max(gpu_ms, 0.0) / args.steps
     log(f"[bench] {args.steps} steps: {gpu_ms:.3f} ms on the stream, {wall_ms:.3f} ms wall")
 
+    # ---- distribution of the step time: the same steps again, bracketed in groups of kGroup (an event between
+    # two steps costs marker time the steps do not have back to back; a group spreads it over kGroup steps);
+    # median and minimum over at least 100 steps
+    kGroup = 5
+    n_groups = max(20, -(-args.steps // kGroup))
+    gev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_groups)]
+    it = args.warmup + args.steps
+    for a, b in gev:
+        a.record()
+        for _ in range(kGroup):
+            step(it)
+            it += 1
+        b.record()
+    torch.cuda.synchronize()
+    group_us = np.array([a.elapsed_time(b) for a, b in gev]) * 1e3 / kGroup
+    step_us_median, step_us_min = float(np.median(group_us)), float(np.min(group_us))
+    log(f"[bench] per step over {n_groups} groups of {kGroup}: median {step_us_median:.2f} us, min {step_us_min:.2f} us, "
+        f"mean of the {args.steps} bracketed steps {ms_per_step * 1e3:.2f} us")
+
     # ---- per-stage durations: same steps again with event hooks between the stages
     n_prof = min(args.steps, 100)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(P.PALU_DECODE_STAGES + 1)] for _ in range(n_prof)]
@@ -297,7 +316,12 @@ def main() -> int:
 
     result = {
         "metric": "decode_attn_us_per_step",
-        "value": ms_per_step * 1e3,
+        "value": step_us_median,
+        "value_is": f"median over {n_groups} groups of {kGroup} consecutive steps, each group between two events on the launch stream "
+                    f"(ms_per_step: mean over the {args.steps} steps of the bracketed region)",
+        "step_us_median": step_us_median,
+        "step_us_min": step_us_min,
+        "step_us_mean": ms_per_step * 1e3,
         "unit": "us/step",
         "n_gpus": 1,
         "steps": args.steps,
@@ -316,7 +340,7 @@ def main() -> int:
                             else "palu_decode_step: encode K + encode V + attn_decode in one call" if fused
                             else "encode K + encode V + quantize + attn_decode")},
         "roofline": {
-            "kernel": "score_kernel (key reconstruction + RoPE + q.K on MFMA)",
+            "kernel": "score16_kernel / score_kernel (key reconstruction on MFMA + RoPE + q.K in float32)",
             "bound": "mfma", "achieved": score_tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": score_tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
             "launch_us": stage_us["score"], "flops_per_launch": work["score_flops"],
@@ -396,9 +420,12 @@ def main() -> int:
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
             tr = json.load(f).get(cfg + (":no-rope" if args.no_rope else ""))
-        if tr and args.latent_bits == 4:
+        if tr and args.latent_bits == 4 and not args.opt:
             result["roofline"]["traffic"] = tr["score_kernel_bytes"]
             result["roofline_value"]["traffic"] = tr["value_kernel_bytes"]
+            # not measured in this run: rocprofv3 counter runs of this same command, kept under profiles/
+            result["roofline"]["traffic_source"] = result["roofline_value"]["traffic_source"] = tr.get(
+                "source", "profiles/hbm_traffic.json")
     except OSError:
         pass
 
