@@ -268,6 +268,20 @@ int palu_encode_quant(const palu_layer_desc* desc, int which, const void* x, int
  *   workspace  DEVICE scratch, at least palu_attn_decode_workspace_bytes(desc, batch, max_seq)
  *              bytes, 256-byte aligned; contents need not be preserved between calls.
  *              Calls sharing a workspace must be ordered on one stream.
+ *
+ * Arithmetic.  Keys are rebuilt on the matrix cores from the 16-bit latents and B_k as they are (fp16 or
+ * bf16 instruction of act_dtype, float32 accumulation), rotated and multiplied by the rotated query in
+ * float32 with float32 cos / sin: the logit error does not grow with the logit.  The value side contracts
+ * fp16 numbers: probabilities exp(score - running max) rounded to fp16 (float32 row sums of the rounded
+ * values), latents in fp16.  The non-RoPE form contracts the key latents in fp16 with q B_k^T kept as an
+ * fp16 pair hi + lo.  Quantized latents are dequantized to fp16 ((code - zero) * scale, one rounding).
+ *
+ * bfloat16 layers: on the RoPE score path bf16 key latents and B_k enter the bf16 matrix instruction
+ * unchanged.  bf16 VALUE latents, and bf16 KEY latents of the non-RoPE form, are converted to fp16 before
+ * their contraction: exact for 2^-17 <= |h| <= 65504 (every bf16 number in that range is an fp16 number);
+ * larger magnitudes are clamped to +-65504 (infinities stay infinite), smaller ones are truncated toward
+ * zero to the fp16 subnormal grid (multiples of 2^-24; below 2^-24: zero).  No error is reported for
+ * latents outside that range; a cache that holds such values should be stored as fp16 with its own scaling.
  */
 int palu_attn_decode_workspace_bytes(const palu_layer_desc* desc, int32_t batch, int32_t max_seq, size_t* out_bytes);
 int palu_attn_decode(const palu_layer_desc* desc, int32_t batch, int32_t seq_len, int32_t max_seq,

@@ -144,6 +144,52 @@ def test_large_logits_other_paths(theta, dtype, scale):
     check(case, TOL_FP)
 
 
+def _bf16_to_fp16_as_documented(h):
+    """include/palu.h: clamp to +-65504, else truncate toward zero onto the fp16 grid (exact from 2^-17 up)."""
+    h = np.clip(np.asarray(h, np.float64), -65504.0, 65504.0)
+    r = h.astype(np.float16)                                    # nearest; step back toward zero where it rounded away
+    away = np.abs(r.astype(np.float64)) > np.abs(h)
+    r[away] = np.nextafter(r[away], np.float16(0.0))
+    return r.astype(np.float64)
+
+
+@pytest.mark.parametrize("theta", [10000.0, 0.0])
+def test_bf16_latents_outside_the_fp16_range(theta):
+    """bf16 latents beyond +-65504 and below 2^-17.  RoPE keys: no narrowing (bf16 matrix instruction): all key
+    latents times 2^17 with B_k times 2^-17 (both exact in bf16) must give the result of the unscaled layer.
+    Values, and keys of the non-RoPE form: the documented conversion to fp16 (clamp, truncate toward zero),
+    which the oracle is fed."""
+    import dataclasses
+    layer = dataclasses.replace(synth.uniform_layer(8, 4, 128), rope_theta=theta)
+    case = synth.make_case_orthonormal(layer, 2, 300, seed=23, dtype="bf16")
+    rng = np.random.default_rng(5)
+
+    def sprinkle(H):
+        tiny = rng.random(H.shape) < 0.2
+        huge = rng.random(H.shape) < 0.01
+        return synth.round_to(np.where(huge, H * 9.0e4, np.where(tiny, H * 3.0e-6, H)), "bf16")
+
+    case.Hv = sprinkle(case.Hv)
+    assert (np.abs(case.Hv) > 65504).any() and ((np.abs(case.Hv) < 2.0 ** -17) & (case.Hv != 0)).any()
+    case.name = f"bf16 range theta={theta:g}"
+    ref_case = dataclasses.replace(case, Hv=_bf16_to_fp16_as_documented(case.Hv))
+    if theta > 0:
+        case.Hk = synth.round_to(case.Hk * 2.0 ** 17, "bf16")
+        case.Bk = synth.round_to(case.Bk * 2.0 ** -17, "bf16")
+        assert (np.abs(case.Hk) > 65504).mean() > 0.5
+        ref_case.Hk, ref_case.Bk = case.Hk, case.Bk              # the oracle sees the same scaled pair: same keys
+    else:
+        case.q = synth.round_to(case.q * 1.0e-4, "bf16")         # keeps the logits of the clamped entries moderate
+        case.Hk = sprinkle(case.Hk)
+        assert (np.abs(case.Hk) > 65504).any()
+        ref_case.q, ref_case.Hk = case.q, _bf16_to_fp16_as_documented(case.Hk)
+    got = run_hip(case)
+    assert np.isfinite(got).all()
+    whole, rows = rel_err(got, run_oracle(ref_case))
+    say(f"         {case.name}: rel err {whole:.3e} rows {rows:.3e}")
+    assert max(whole, rows) <= TOL_FP
+
+
 def test_shared_key_fp16_option():
     """The opt-in shared-key score form (fp16-rounded keys and angles in the query contraction, each key rebuilt
     once for the queries that share it): within the tolerance at logits of order +-3; its error grows with the
