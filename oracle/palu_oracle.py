@@ -29,6 +29,7 @@ __all__ = [
     "dequant_latent", "quant_latent", "encode", "reconstruct",
     "attn_decode", "attn_decode_scores", "softmax_rows",
     "storage_ratio", "kv_cache_bytes", "reconstruction_macs_per_token",
+    "fp8_e4m3_value", "fp8_e4m3_round", "fp8_weight_scales", "fp8_keys", "attn_decode_fp8_keys",
 ]
 
 
@@ -363,3 +364,80 @@ def reconstruction_macs_per_token(group_head_off, rank_off, d_head: int) -> int:
     for j in range(len(group_head_off) - 1):
         total += (rank_off[j + 1] - rank_off[j]) * (group_head_off[j + 1] - group_head_off[j]) * d_head
     return int(total)
+
+
+# --------------------------------------------------------------------------
+# Low-precision key reconstruction (Sec. 4.5.2, last paragraph: the decomposed
+# weight matrices quantized further so that low-precision matrix hardware does
+# the online reconstruction).  The paper names the idea and fixes no format;
+# this build's reading, which the kernels follow and this section defines:
+#   * format: 8-bit float E4M3 of the OCP 8-bit floating point specification
+#     (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities;
+#     exponent 15 with mantissa 7 is NaN; largest finite 448; subnormals are
+#     multiples of 2^-9), round to nearest even, magnitudes above 448 saturate;
+#   * B_k: every column (one feature of one head) has a power-of-two scale e,
+#     the smallest with max |B[:, f]| / e <= 448 (e = 1 for a zero column), and
+#     is stored as round(B[:, f] / e): the division is exact;
+#   * key latents: round(h), no scale;
+#   * the key is K[t, f] = e_f sum_k round(h[t, k]) round(B[k, f] / e_f), and
+#     everything after it (RoPE, scores, softmax, values) is unchanged.
+# Parity status: fp8_e4m3_value / fp8_e4m3_round are pinned by the format's
+# definition (all 256 codes, ties, saturation, subnormals) in
+# tests/test_oracle_pins.py; attn_decode_fp8_keys is attn_decode on the rounded
+# operands and is pinned through it.  What the rounding does to model accuracy
+# is the paper's open question, not measured here.
+# --------------------------------------------------------------------------
+
+def fp8_e4m3_value(code) -> np.ndarray:
+    """Value of an E4M3 byte (float64; NaN for 0x7f / 0xff)."""
+    code = np.asarray(code, dtype=np.int64)
+    sign = np.where(code & 0x80, -1.0, 1.0)
+    e = (code >> 3) & 0xF
+    m = (code & 7).astype(np.float64)
+    val = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7.0))
+    return np.where((e == 15) & ((code & 7) == 7), np.nan, sign * val)
+
+
+def fp8_e4m3_round(x) -> np.ndarray:
+    """Nearest E4M3 value (ties to the even mantissa), as float64; magnitudes
+    above 448 (and infinities) give +-448."""
+    x = np.asarray(x, dtype=np.float64)
+    a = np.minimum(np.abs(x), 448.0)
+    # spacing of the grid at a: 2^(floor(log2 a) - 3) in the normal range, 2^-9 below 2^-6
+    with np.errstate(divide="ignore"):
+        ex = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    step = 2.0 ** (np.maximum(ex, -6.0) - 3.0)
+    q = np.rint(a / step) * step                 # a / step is exact (power of two); rint rounds half to even
+    return np.copysign(np.minimum(q, 448.0), x)
+
+
+def fp8_weight_scales(Bj: np.ndarray) -> np.ndarray:
+    """Power-of-two scale of every column of one group's reconstruction matrix [r, s*d_head]."""
+    m = np.abs(np.asarray(Bj, dtype=np.float64)).max(axis=0)
+    with np.errstate(divide="ignore"):
+        e = 2.0 ** np.ceil(np.log2(np.where(m > 0, m, 448.0) / 448.0))
+    return e
+
+
+def fp8_keys(Hk, Bk, group_head_off, k_rank_off, d_head):
+    """The operands of the low-precision reconstruction as float64 arrays: rounded latents, and
+    the concatenated B_k with every column replaced by e_f * round(B[:, f] / e_f)."""
+    H8 = fp8_e4m3_round(Hk)
+    B8 = np.array(np.asarray(Bk, dtype=np.float64).reshape(-1), copy=True)
+    off = 0
+    for j in range(len(group_head_off) - 1):
+        r = k_rank_off[j + 1] - k_rank_off[j]
+        w = (group_head_off[j + 1] - group_head_off[j]) * d_head
+        Bj = B8[off:off + r * w].reshape(r, w)
+        e = fp8_weight_scales(Bj)
+        Bj[:] = fp8_e4m3_round(Bj / e) * e
+        off += r * w
+    return H8, B8
+
+
+def attn_decode_fp8_keys(q, q_pos, Hk, Hv, Bk, Bv, group_head_off, k_rank_off, v_rank_off,
+                         d_head: int, rope_theta: float, k_pos=None, seq_lens=None, q_per_kv: int = 1) -> np.ndarray:
+    """attn_decode with the keys rebuilt from E4M3-rounded latents and weights (see above)."""
+    H8, B8 = fp8_keys(Hk, Bk, group_head_off, k_rank_off, d_head)
+    return attn_decode(q, q_pos, H8, Hv, B8, Bv, group_head_off, k_rank_off, v_rank_off, d_head, rope_theta,
+                       k_pos, seq_lens, q_per_kv)

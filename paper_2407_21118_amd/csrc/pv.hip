@@ -361,23 +361,22 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
     }
   };
 
-  // ---- two register sets in turn: the next set's loads are in flight while one is
-  // consumed; nothing is requested past the last set
-  Set ring[2];
-  issue(ring[0], 0);
-  int k = 0;
-  for (; k + 2 < n_sets; k += 2) {
-    issue(ring[1], k + 1);
-    process(ring[0], k);
-    issue(ring[0], k + 2);
-    process(ring[1], k + 1);
-  }
-  if (k + 1 < n_sets) {
-    issue(ring[1], k + 1);
-    process(ring[0], k);
-    process(ring[1], k + 1);
-  } else {
-    process(ring[0], k);
+  // ---- kDepth register sets in turn: the loads of the next kDepth - 1 sets are in flight while one is
+  // consumed; nothing is requested past the last set.  A set of quantized latents is a quarter (or less) of
+  // the bytes of an unquantized one, so twice as many are kept in flight: what bounds this kernel is the
+  // bytes a compute unit has outstanding against the memory latency.
+  constexpr int kDepth = I4 ? 4 : 2;
+  Set ring[kDepth];
+#pragma unroll
+  for (int d = 0; d < kDepth - 1; ++d)
+    if (d < n_sets) issue(ring[d], d);
+  for (int k = 0; k < n_sets; k += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      if (k + d >= n_sets) break;                                // uniform
+      if (k + d + kDepth - 1 < n_sets) issue(ring[(d + kDepth - 1) % kDepth], k + d + kDepth - 1);
+      process(ring[d], k + d);
+    }
   }
 
   // ---- results of the split

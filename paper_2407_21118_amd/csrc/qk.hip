@@ -349,26 +349,24 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
     }
   };
 
-  // steps (set, chunk) in order, two register sets in turn: the next step's loads are in
-  // flight while one is consumed; nothing is requested past the last step
+  // steps (set, chunk) in order, kDepth register sets in turn: the loads of the next kDepth - 1 steps are in
+  // flight while one is consumed; nothing is requested past the last step.  Quantized steps are a quarter of
+  // the bytes, so twice as many are kept in flight (the kernel is bound by the bytes outstanding per compute unit).
   const int n_steps = n_sets * n_chunks;
   auto next = [&](int& set, int& chunk) { if (++chunk == n_chunks) { chunk = 0; ++set; } };
-  Step ring[2];
+  constexpr int kDepth = I4 ? 4 : 2;
+  Step ring[kDepth];
   int is = 0, ic = 0, ps = 0, pc = 0;            // next step to request / to consume
-  issue(ring[0], is, ic); next(is, ic);
-  int k = 0;
-  for (; k + 2 < n_steps; k += 2) {
-    issue(ring[1], is, ic); next(is, ic);
-    process(ring[0], ps, pc); next(ps, pc);
-    issue(ring[0], is, ic); next(is, ic);
-    process(ring[1], ps, pc); next(ps, pc);
-  }
-  if (k + 1 < n_steps) {
-    issue(ring[1], is, ic);
-    process(ring[0], ps, pc); next(ps, pc);
-    process(ring[1], ps, pc);
-  } else {
-    process(ring[0], ps, pc);
+#pragma unroll
+  for (int d = 0; d < kDepth - 1; ++d)
+    if (d < n_steps) { issue(ring[d], is, ic); next(is, ic); }
+  for (int k = 0; k < n_steps; k += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      if (k + d >= n_steps) break;               // uniform
+      if (k + d + kDepth - 1 < n_steps) { issue(ring[(d + kDepth - 1) % kDepth], is, ic); next(is, ic); }
+      process(ring[d], ps, pc); next(ps, pc);
+    }
   }
 }
 

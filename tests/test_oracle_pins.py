@@ -608,3 +608,86 @@ def test_empty_sequence_is_the_empty_sum():
     assert not both[0].any()
     np.testing.assert_array_equal(both[1], alone[0])
     assert O.softmax_rows(np.zeros((3, 0))).shape == (3, 0)
+
+
+# --------------------------------------------------------------------------
+# 8-bit float operands of the low-precision key reconstruction (Sec. 4.5.2, last paragraph)
+# --------------------------------------------------------------------------
+
+def _e4m3_table():
+    """All finite E4M3 values written out from the format's definition, independently of the oracle."""
+    vals = []
+    for code in range(256):
+        s, e, m = code >> 7, (code >> 3) & 15, code & 7
+        if e == 15 and m == 7:
+            continue
+        v = (m / 8) * 2.0 ** -6 if e == 0 else (1 + m / 8) * 2.0 ** (e - 7)
+        vals.append(-v if s else v)
+    return np.array(sorted(set(vals)))
+
+
+def test_fp8_e4m3_codes_and_rounding():
+    tab = _e4m3_table()
+    assert tab.max() == 448.0 and tab.min() == -448.0 and len(tab) == 253        # 254 finite codes, +0 and -0 coincide
+    assert np.abs(tab[tab != 0]).min() == 2.0 ** -9
+    # every code decodes to its table value; every table value rounds to itself
+    dec = O.fp8_e4m3_value(np.arange(256))
+    assert np.isnan(dec[0x7f]) and np.isnan(dec[0xff]) and np.isnan(dec).sum() == 2
+    assert set(dec[~np.isnan(dec)].tolist()) == set(tab.tolist())
+    np.testing.assert_array_equal(O.fp8_e4m3_round(tab), tab)
+    # hand examples: 1.0625 is halfway between 1.0 (mantissa 0, even) and 1.125 (mantissa 1): down; 1.1875 between
+    # 1.125 (odd) and 1.25 (even): up; 17 -> 16 (tie, even), 19 -> 20 (tie: 18 has mantissa 1, 20 mantissa 2)
+    np.testing.assert_array_equal(O.fp8_e4m3_round([1.0625, 1.1875, 17.0, 19.0, 0.3, -5.3, 1e9, -np.inf, 460.0, 2.0 ** -10, 3 * 2.0 ** -10]),
+                                  [1.0, 1.25, 16.0, 20.0, 0.3125, -5.5, 448.0, -448.0, 448.0, 0.0, 2.0 ** -8])
+    # brute force: nearest table value for random inputs, ties excluded
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(4000) * 3, rng.standard_normal(2000) * 200, rng.standard_normal(2000) * 0.01])
+    d = np.abs(x[:, None] - tab[None, :])
+    near = tab[np.argmin(d, axis=1)]
+    srt = np.sort(d, axis=1)
+    clear = srt[:, 1] - srt[:, 0] > 1e-12
+    np.testing.assert_array_equal(O.fp8_e4m3_round(x)[clear], np.clip(near, -448, 448)[clear])
+    # half-ulp bound in the normal range: relative error at most 2^-4
+    xn = x[(np.abs(x) >= 2.0 ** -6) & (np.abs(x) <= 448)]
+    assert (np.abs(O.fp8_e4m3_round(xn) - xn) <= np.abs(xn) * 2.0 ** -4).all()
+
+
+def test_fp8_weight_scales_and_key_operands():
+    rng = np.random.default_rng(1)
+    B = rng.standard_normal((64, 256)) * rng.uniform(1e-3, 50.0, size=(1, 256))
+    B[:, 5] = 0.0
+    e = O.fp8_weight_scales(B)
+    assert e[5] == 1.0
+    assert (np.log2(e) == np.round(np.log2(e))).all()                       # powers of two
+    m = np.abs(B).max(axis=0)
+    nz = m > 0
+    assert ((m[nz] / e[nz] <= 448) & (m[nz] / e[nz] > 224)).all()           # the smallest such power of two
+    # multiplying a column by a power of two changes its scale, not its codes: the operands scale exactly
+    layer = ([0, 2], [0, 64], 128)
+    H = rng.standard_normal((1, 9, 64))
+    H8, B8 = O.fp8_keys(H, B.reshape(-1), layer[0], layer[1], layer[2])
+    B2 = B.copy()
+    B2[:, 7] *= 2.0 ** 5
+    _, B8b = O.fp8_keys(H, B2.reshape(-1), layer[0], layer[1], layer[2])
+    np.testing.assert_array_equal(B8b.reshape(64, 256)[:, 7], B8.reshape(64, 256)[:, 7] * 2.0 ** 5)
+    # operands are on the grid: latents as they are, weights after division by their scale
+    np.testing.assert_array_equal(O.fp8_e4m3_round(H8), H8)
+    np.testing.assert_array_equal(O.fp8_e4m3_round(B8.reshape(64, 256) / e), B8.reshape(64, 256) / e)
+    assert np.abs(B8.reshape(64, 256) - B).max() <= (np.abs(B) * 2.0 ** -4 + e * 2.0 ** -10).max()
+
+
+def test_attn_decode_fp8_keys_is_attention_on_the_rounded_operands():
+    rng = np.random.default_rng(2)
+    gho, kro, vro, d = [0, 2], [0, 32], [0, 32], 8
+    q = rng.standard_normal((2, 2, d))
+    Hk, Hv = rng.standard_normal((2, 11, 32)) * 2, rng.standard_normal((2, 11, 32))
+    Bk, Bv = rng.standard_normal(32 * 2 * d), rng.standard_normal(32 * 2 * d)
+    got = O.attn_decode_fp8_keys(q, [10, 4], Hk, Hv, Bk, Bv, gho, kro, vro, d, 10000.0)
+    H8, B8 = O.fp8_keys(Hk, Bk, gho, kro, d)
+    np.testing.assert_array_equal(got, O.attn_decode(q, [10, 4], H8, Hv, B8, Bv, gho, kro, vro, d, 10000.0))
+    # operands already on the grid (small integers, columns whose largest entry is a power of two <= 448): nothing changes
+    Hi = rng.integers(-8, 9, size=(2, 11, 32)).astype(np.float64)
+    Bi = rng.integers(-4, 5, size=(32, 2 * d)).astype(np.float64)
+    Bi[0, :] = 4.0
+    np.testing.assert_allclose(O.attn_decode_fp8_keys(q, [10, 4], Hi, Hv, Bi.reshape(-1), Bv, gho, kro, vro, d, 10000.0),
+                               O.attn_decode(q, [10, 4], Hi, Hv, Bi.reshape(-1), Bv, gho, kro, vro, d, 10000.0), rtol=0, atol=1e-13)
