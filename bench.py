@@ -30,6 +30,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_F16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 matrix peak
+MFMA_F8_PEAK_TFLOPS = 5000.0       # MI355X dense fp8 matrix peak
 HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak
 
 
@@ -409,6 +410,12 @@ def main() -> int:
         torch.cuda.synchronize()
         log(f"[bench] copy probe: 3 device copies of {args.copy_probe} MiB (reads and writes that many bytes each)")
 
+    if "score_fp8=1" in args.opt and not (k_i4 or args.no_rope):
+        # opt-in: keys rebuilt from E4M3-rounded latents and weights on the 8-bit matrix instructions
+        result["dtype"] = "e4m3 keys (option score_fp8), f16 values"
+        result["roofline"].update(kernel="score8_kernel (8-bit key reconstruction on MFMA + RoPE + q.K in float32)",
+                                  peak=MFMA_F8_PEAK_TFLOPS, frac=score_tflops / MFMA_F8_PEAK_TFLOPS)
+        result["roofline"].pop("frac_of_measured", None)
     if args.no_rope:        # no reconstruction: the score kernel is a latent-streaming matrix-vector product
         result["roofline"] = {
             "kernel": "qk_kernel (folded query x key latents)", "bound": "hbm", "achieved": k_gbs, "peak": HBM_PEAK_GBS,

@@ -5,6 +5,7 @@
 #include "rope_fold.hip"
 #include "score.hip"
 #include "score16.hip"
+#include "score8.hip"
 #include "combine.hip"
 #include "pv.hip"
 #include "qk.hip"
@@ -26,6 +27,7 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score workgroup (ranks <= 256)
 std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
 std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
+std::atomic<int> g_opt_score_fp8{0};          // 1: keys rebuilt from E4M3-rounded latents and weights (score8_kernel)
 std::atomic<int> g_opt_shared_key_fp16{0};    // 1: the faster, fp16-rounded shared-key score form for 2 .. 16 queries per key/value head
 std::atomic<int> g_opt_encode_tile{0};        // token rows per workgroup of the prompt-sized projection
 
@@ -351,7 +353,7 @@ int split_bound(int total_units, int batch, int max_seq, int waves_per_cu) {
 }
 
 struct Workspace {
-  size_t mfold, scores, o_part, ml_part, rope_rows, qsum, qfrag, total;
+  size_t mfold, scores, o_part, ml_part, rope_rows, qsum, qfrag, w8, w_scale, total;
   int lpad, o_stride;
   long long mfold_bstride, part_stride;
 };
@@ -372,6 +374,9 @@ int carve(const Meta& m, int batch, int max_seq, int n_split_cap, int n_parts, b
   w->qsum = off; off = align_up(off + (size_t)batch * m.n_heads * (PALU_MAX_RANK / 128 + 2) * 4);   // int4 block sums of the folded queries (no-RoPE path)
   // several queries per key/value head: rotated queries as contraction operands, 2 feature halves x 4 KiB per key/value head
   w->qfrag = off; off = align_up(off + (m.qpk > 1 ? (size_t)batch * (m.n_heads / m.qpk) * 2 * 4096 : 0));
+  // 8-bit key reconstruction (option score_fp8): B_k as E4M3 bytes in operand order, and its column scales
+  w->w8 = off; off = align_up(off + (g_opt_score_fp8 ? (size_t)w->mfold_bstride : 0));
+  w->w_scale = off; off = align_up(off + (g_opt_score_fp8 ? (size_t)m.n_heads * PALU_D_HEAD * 4 : 0));
   w->total = off;
   return PALU_OK;
 }
@@ -443,6 +448,23 @@ ScoreFn score16_fn_g(int lg) {
   if constexpr (NK <= 2) { if (lg == 2) return score16_kernel<T, NK, 4>; }
   if constexpr (NK <= 4) { if (lg >= 1) return score16_kernel<T, NK, 2>; }
   return score16_kernel<T, NK, 1>;
+}
+template <int NK>
+ScoreFn score8_fn_g(int lg) {
+  if constexpr (NK <= 2) { if (lg == 2) return score8_kernel<NK, 4>; }
+  if constexpr (NK <= 4) { if (lg >= 1) return score8_kernel<NK, 2>; }
+  return score8_kernel<NK, 1>;
+}
+ScoreFn score8_fn(int rc, int lg) {
+  switch (rc) {
+    case 1: return score8_fn_g<2>(lg);
+    case 2: return score8_fn_g<3>(lg);
+    case 3: return score8_fn_g<4>(lg);
+    case 4: return score8_fn_g<5>(lg);
+    case 5: return score8_fn_g<6>(lg);
+    case 6: return score8_fn_g<7>(lg);
+    default: return score8_fn_g<8>(lg);
+  }
 }
 template <typename T>
 ScoreFn score16_fn_t(int rc, int lg) {
@@ -707,6 +729,9 @@ int palu_set_option(const char* name, int value) {
   } else if (!std::strcmp(name, "value_split_tokens")) {
     if (value != 0 && (value % 32 != 0 || value > 4096)) return PALU_ERR_INVALID_ARG;
     g_opt_value_split = value;
+  } else if (!std::strcmp(name, "score_fp8")) {
+    if (value > 1) return PALU_ERR_INVALID_ARG;
+    g_opt_score_fp8 = value;
   } else if (!std::strcmp(name, "shared_key_fp16")) {
     if (value > 1) return PALU_ERR_INVALID_ARG;
     g_opt_shared_key_fp16 = value;
@@ -1228,6 +1253,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     // (option score_waves = 4 or 8 forces the half-head / ping-pong schedules of score_kernel)
     const bool use16 = !shared_key && !k_i4 && g_opt_score_waves == 0;
     used16 = use16;
+    // option score_fp8: those heads rebuild their keys from E4M3-rounded latents and weights (fp16 layers)
+    const bool use8 = use16 && g_opt_score_fp8 != 0 && act == PALU_F16;
     static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)
     if (shared_key && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
     const ScorePlan& plan = shared_key ? spk : sp;
@@ -1314,6 +1341,16 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       }
     }
 
+    if (use8) {
+      Fold8Args f8;
+      f8.Bk = static_cast<const uint16_t*>(Bk);
+      f8.w8 = ws + w.w8;
+      f8.scale = reinterpret_cast<float*>(ws + w.w_scale);
+      f8.meta = m;
+      hipLaunchKernelGGL(fold8_kernel<F16>, dim3((unsigned)m.n_heads, 4u), dim3(256), 0, s, f8);
+      if ((st = launch_ok()) != PALU_OK) return st;
+    }
+
     // 2. scores
     {
       static thread_local ScoreArgs a;
@@ -1321,6 +1358,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       a.hk_scale = static_cast<const uint16_t*>(hk_scale);
       a.hk_zero = static_cast<const uint16_t*>(hk_zero);
       a.mfold = reinterpret_cast<const uint16_t*>(ws + w.mfold);
+      a.w_scale = reinterpret_cast<const float*>(ws + w.w_scale);
       // the table's tiles: float32 part first, the shared-key form's float16 rows behind it
       a.rope_rows = static_cast<const unsigned char*>(rope_table) + (shared_key ? kRopeTileBytes : 0);
       a.rope_tile_stride = kRopeTableStride;
@@ -1390,6 +1428,14 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
                    : k16 ? (act == PALU_F16 ? score16_fn_t<F16>(rc, lg) : score16_fn_t<BF16>(rc, lg))
                    : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, rc * 3 + lg, waves8));
         if (k16) lds = (size_t)score16_lds_bytes(width);
+        const bool k8 = k16 && use8;
+        if (k8) {
+          fn = score8_fn(rc, lg);
+          lds = (size_t)score8_lds_bytes(width);
+          a.mfold = reinterpret_cast<const uint16_t*>(ws + w.w8);
+        } else {
+          a.mfold = reinterpret_cast<const uint16_t*>(ws + w.mfold);
+        }
         if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
         const unsigned threads = (waves8 && !rank_class_half(rc) && !k16) ? 512 : 256;
         auto flush = [&]() -> int {

@@ -165,6 +165,7 @@ struct ScoreArgs {
   const uint16_t* qfrag;     // rotated queries as contraction operands, see qfrag_kernel
   int qpk;                   // query heads per key/value head
   int n_kv;                  // key/value heads
+  const float* w_scale;      // 8-bit weights (score8_kernel): the power-of-two scale of every feature column [heads][128]
   int m_qpk, m_nq;           // one-query form: Meta::qpk and Meta::nq of the call (layout of q, see q_row)
   int rope_tile_stride;
   float rev_hi[kHalf];       // theta^(-2f/128) / (2 pi) from the host's float64 value, as a float pair hi + lo

@@ -362,10 +362,9 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   };
 
   // ---- kDepth register sets in turn: the loads of the next kDepth - 1 sets are in flight while one is
-  // consumed; nothing is requested past the last set.  A set of quantized latents is a quarter (or less) of
-  // the bytes of an unquantized one, so twice as many are kept in flight: what bounds this kernel is the
-  // bytes a compute unit has outstanding against the memory latency.
-  constexpr int kDepth = I4 ? 4 : 2;
+  // consumed; nothing is requested past the last set.  (Four sets for quantized latents, whose sets are a quarter
+  // of the bytes, measured no faster: the 4-bit kernel waits on its own dependent chain, not on bytes in flight.)
+  constexpr int kDepth = 2;
   Set ring[kDepth];
 #pragma unroll
   for (int d = 0; d < kDepth - 1; ++d)

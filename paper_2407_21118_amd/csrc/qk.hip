@@ -350,11 +350,10 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   };
 
   // steps (set, chunk) in order, kDepth register sets in turn: the loads of the next kDepth - 1 steps are in
-  // flight while one is consumed; nothing is requested past the last step.  Quantized steps are a quarter of
-  // the bytes, so twice as many are kept in flight (the kernel is bound by the bytes outstanding per compute unit).
+  // flight while one is consumed; nothing is requested past the last step.
   const int n_steps = n_sets * n_chunks;
   auto next = [&](int& set, int& chunk) { if (++chunk == n_chunks) { chunk = 0; ++set; } };
-  constexpr int kDepth = I4 ? 4 : 2;
+  constexpr int kDepth = 2;
   Step ring[kDepth];
   int is = 0, ic = 0, ps = 0, pc = 0;            // next step to request / to consume
 #pragma unroll

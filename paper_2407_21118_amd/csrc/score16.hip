@@ -16,6 +16,7 @@
 // Per 32-token tile and CU this moves 160 KiB through the LDS where the ping-pong schedule moves 225,
 // and issues 0.75 as many vector instructions.
 
+#pragma once
 #include <type_traits>
 
 #include "score.hip"

@@ -190,6 +190,34 @@ def test_bf16_latents_outside_the_fp16_range(theta):
     assert max(whole, rows) <= TOL_FP
 
 
+@pytest.mark.parametrize("cfg,L,scale", [("1", 300, 1.0), ("2", 500, 1.0), ("2", 333, 8.0), ("5a", 200, 1.0)])
+def test_score_fp8_option(cfg, L, scale):
+    """Opt-in low-precision key reconstruction (Sec. 4.5.2, last paragraph): keys rebuilt from E4M3-rounded latents
+    and column-scaled E4M3 weights on the 8-bit matrix instruction.  The oracle rounds the same operands the same
+    way (O.attn_decode_fp8_keys); what remains is float32 accumulation, so the plain tolerance applies.  The
+    distance to the unrounded attention is printed: it is the price of the format, not an error of the kernel."""
+    import paper_2407_21118_amd as P
+    layer = synth.config_layer(cfg)
+    case = synth.make_case_svd(layer, 2, L, seed=31) if cfg != "1" else synth.make_case_orthonormal(layer, 2, L, seed=31)
+    case.q = synth.round_to(case.q * scale, "f16")
+    case.seq_lens = np.array([L, L - 37], np.int32)
+    case.q_pos = (case.seq_lens - 1).astype(np.int32)
+    case.name = f"fp8 keys cfg {cfg} x{scale:g}"
+    P.palu_set_option("score_fp8", 1)
+    try:
+        got = run_hip(case)
+    finally:
+        P.palu_set_option("score_fp8", 0)
+    assert np.isfinite(got).all()
+    ref8 = O.attn_decode_fp8_keys(case.q, case.q_pos, case.Hk, case.Hv, case.Bk, case.Bv, layer.group_head_off, layer.k_rank_off,
+                                  layer.v_rank_off, layer.d_head, layer.rope_theta, case.k_pos, case.seq_lens, layer.q_per_kv)
+    whole, rows = rel_err(got, ref8)
+    w2, r2 = rel_err(got, run_oracle(case))
+    say(f"[parity] {case.name}: against the oracle on the same rounded operands {whole:.3e} (rows {rows:.3e}); "
+        f"against unrounded attention {w2:.3e} (rows {r2:.3e})")
+    assert whole <= TOL_FP and rows <= TOL_FP
+
+
 def test_shared_key_fp16_option():
     """The opt-in shared-key score form (fp16-rounded keys and angles in the query contraction, each key rebuilt
     once for the queries that share it): within the tolerance at logits of order +-3; its error grows with the
