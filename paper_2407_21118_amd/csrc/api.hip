@@ -1255,6 +1255,12 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     used16 = use16;
     // option score_fp8: those heads rebuild their keys from E4M3-rounded latents and weights (fp16 layers)
     const bool use8 = use16 && g_opt_score_fp8 != 0 && act == PALU_F16;
+    if (use16) {
+      // the 256-row slices of ranks above 512 run there too and write one score plane each (the planned two are
+      // those of the half-head wavefronts)
+      for (int i = 0; i < sp.total_units; ++i)
+        if (sp.cls_id[sp.unit_cls[i]] == kSlicedCls) sp.units[i].part0 /= 2;
+    }
     static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)
     if (shared_key && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
     const ScorePlan& plan = shared_key ? spk : sp;
@@ -1423,12 +1429,12 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         const bool dma = !k_i4;
         const bool pingpong = (waves8 && !rank_class_half(rc)) || shared_key;
         size_t lds = (size_t)score_lds_bytes(width, dma, !shared_key, pingpong);
-        const bool k16 = use16 && rank_class_16(rc) && !sliced;
+        const bool k16 = use16 && rank_class_16(rc);
         ScoreFn fn = shared_key ? (m.qpk <= 4 ? score_fn_shared<1>(rc) : score_fn_shared<2>(rc))
                    : k16 ? (act == PALU_F16 ? score16_fn_t<F16>(rc, lg) : score16_fn_t<BF16>(rc, lg))
                    : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, rc * 3 + lg, waves8));
         if (k16) lds = (size_t)score16_lds_bytes(width);
-        const bool k8 = k16 && use8;
+        const bool k8 = k16 && use8 && !sliced;
         if (k8) {
           fn = score8_fn(rc, lg);
           lds = (size_t)score8_lds_bytes(width);
@@ -1463,7 +1469,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   int max_parts = 0;
   for (int h = 0; h < m.n_heads; ++h) {      // half-head wavefronts write two planes per rank slice
     const int rk = m.k_off[m.group_of_head[h] + 1] - m.k_off[m.group_of_head[h]];
-    const bool whole = used16 && rank_class_16(rank_class(rk));       // one wavefront per head: one plane
+    const bool whole = used16 && (rank_class_16(rank_class(rk)) || rk > 512);      // one wavefront per head: one plane (per rank slice)
     n_parts[h] = no_rope ? (uint8_t)1 : (uint8_t)(((waves8 || sp.half_heads[h]) && !whole) ? 2 * sp.slices[h] : sp.slices[h]);
     max_parts = std::max(max_parts, (int)n_parts[h]);
   }
