@@ -663,32 +663,6 @@ inline int launch_ok() { return hipGetLastError() == hipSuccess ? PALU_OK : PALU
 
 }  // namespace
 
-// The prompt-sized projection: tile height by the number of tokens, tiles dealt to the XCDs in contiguous ranges.
-template <typename T, bool Q>
-int launch_encode_gemm_t(const EncodeArgs& a, int max_R, int n_sides, hipStream_t s) {
-  // the largest tile that still gives most compute units (7 of 10: measured at 512 .. 4096 tokens) a workgroup:
-  // 256 or 128 token rows of 256 columns; below that 64 rows of 128 columns, two workgroups to a compute unit
-  int tm = 256, tn = 256;
-  auto tiles = [&]() { return ceil_div(max_R, tn) * ceil_div(a.n_tok, tm) * n_sides; };
-  while (tm > 64 && tiles() * 10 < device_cu_count() * 7) tm >>= 1;
-  if (tm == 64) tn = 128;
-  if (g_opt_encode_tile > 0) {
-    tm = g_opt_encode_tile == 32 ? 64 : (int)g_opt_encode_tile;     // 32: the narrow tile
-    tn = g_opt_encode_tile == 32 ? 128 : 256;
-  }
-  GemmGrid gg;
-  gg.n_col_tiles = ceil_div(max_R, tn);
-  gg.n_row_tiles = ceil_div(a.n_tok, tm);
-  gg.n_tiles = gg.n_col_tiles * gg.n_row_tiles * n_sides;
-  gg.per_xcd = ceil_div(gg.n_tiles, 8);
-  const size_t lds = gemm_lds_bytes(tm, tn);
-  auto fn = tn == 128 ? encode_gemm_kernel<T, Q, 64, 128>
-                      : tm == 256 ? encode_gemm_kernel<T, Q, 256, 256> : tm == 128 ? encode_gemm_kernel<T, Q, 128, 256> : encode_gemm_kernel<T, Q, 64, 256>;
-  if (allow_lds(fn, lds) != PALU_OK) return PALU_ERR_HIP;
-  hipLaunchKernelGGL(fn, dim3((unsigned)(8 * gg.per_xcd)), dim3(256), lds, s, a, gg);
-  return launch_ok();
-}
-
 extern "C" {
 
 const char* palu_status_string(int status) {
@@ -906,8 +880,7 @@ int launch_encode_finish(int act, const EncodePlan& p, hipStream_t s) {
 }
 
 int launch_encode_gemm(int act, const EncodeArgs& a, int max_R, int n_sides, bool quant, hipStream_t s) {
-  if (act == PALU_F16) return quant ? launch_encode_gemm_t<F16, true>(a, max_R, n_sides, s) : launch_encode_gemm_t<F16, false>(a, max_R, n_sides, s);
-  return quant ? launch_encode_gemm_t<BF16, true>(a, max_R, n_sides, s) : launch_encode_gemm_t<BF16, false>(a, max_R, n_sides, s);
+  return launch_encode_gemm_tiles(act, a, max_R, n_sides, quant, (int)g_opt_encode_tile, device_cu_count(), s);
 }
 
 int launch_encode(int act, const EncodePlan& p, hipStream_t s) {
