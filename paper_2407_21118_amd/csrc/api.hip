@@ -303,7 +303,8 @@ int plan_qk(const Meta& m, bool quantized, QkPlan* p) {
     const size_t staged = (size_t)nh * (x.wpad + 8) * 2;
     x.use_lo = (uint8_t)((!quantized && 2 * staged <= 159 * 1024) ? 1 : 0);   // both parts staged in LDS while they fit
     size_t& lds = p->max_lds[nh > 16 ? 1 : 0];
-    lds = std::max(lds, staged * (x.use_lo ? 2 : 1));
+    // quantized: the block sums of the folded query are staged behind its rows
+    lds = std::max(lds, staged * (x.use_lo ? 2 : 1) + (quantized ? (size_t)nh * (x.wpad >> 7) * 4 : 0));
     return PALU_OK;
   };
   int st;
@@ -1197,12 +1198,21 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
               : k_bits == 2 ? (cls ? qk_kernel<F16, 2, 2> : qk_kernel<F16, 1, 2>)
               : act == PALU_F16 ? (cls ? qk_kernel<F16, 2, 0> : qk_kernel<F16, 1, 0>)
                                 : (cls ? qk_kernel<BF16, 2, 0> : qk_kernel<BF16, 1, 0>);
-      const size_t lds = qp.max_lds[cls];
-      if (lds == 0) continue;
-      if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
+      const size_t lds1 = align_up(qp.max_lds[cls], 16);     // one unit's staged folded queries
+      if (lds1 == 0) continue;
       auto flush = [&]() -> int {
         if (a.units.n_units == 0) return PALU_OK;
-        const dim3 grid((unsigned)a.units.n_units, (unsigned)ceil_div(a.n_split, 4), (unsigned)batch);
+        // quantized latents: as many units per workgroup (4, 2 or 1) as the launch has and as fit 64 KiB of LDS, two
+        // workgroups to a compute unit (the units then share the cache lines of their tokens' scales and zero-points;
+        // unquantized latents have nothing to share and measured faster with one unit's staging per workgroup)
+        int upw = k_bits == 0 ? 1 : (a.units.n_units >= 4 ? 4 : (a.units.n_units >= 2 ? 2 : 1));
+        while (upw > 1 && lds1 * upw > 64 * 1024) upw >>= 1;
+        a.units_per_wg = upw;
+        a.lds_unit_stride = (int)lds1;
+        const size_t lds = lds1 * upw;
+        int rc = allow_lds(fn, lds);
+        if (rc != PALU_OK) return rc;
+        const dim3 grid((unsigned)ceil_div(a.units.n_units, upw), (unsigned)ceil_div(a.n_split, 4 / upw), (unsigned)batch);
         hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, a);
         a.units.n_units = 0;
         return launch_ok();
@@ -1484,7 +1494,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     for (int cls = 0; cls < kNumPvCls; ++cls) {
       auto flush = [&]() -> int {
         if (a.units.n_units == 0) return PALU_OK;
-        const dim3 grid((unsigned)a.units.n_units, (unsigned)ceil_div(n_split, 4), (unsigned)batch);
+        a.units_per_wg = a.units.n_units >= 4 ? 4 : (a.units.n_units >= 2 ? 2 : 1);
+        const dim3 grid((unsigned)ceil_div(a.units.n_units, a.units_per_wg), (unsigned)ceil_div(n_split, 4 / a.units_per_wg),
+                        (unsigned)batch);
         hipLaunchKernelGGL(pv_fn(act, v_bits, cls), grid, dim3(256), 0, s, a);
         a.units.n_units = 0;
         return launch_ok();

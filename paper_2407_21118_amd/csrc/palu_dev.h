@@ -71,6 +71,29 @@ struct BF16 {
   }
 };
 
+// A constant in a vector register that the compiler takes for a per-lane value.  (x & mask) | c becomes one
+// v_and_or_b32 only if at most one of its operands is uniform: with two constants the compiler emits v_and + v_or.
+// The statement emits no instruction, so the compiler still sees, and spaces, everything around the matrix instructions.
+__device__ __forceinline__ uint32_t per_lane_constant(uint32_t c) {
+  asm volatile("" : "+v"(c));
+  return c;
+}
+// Four 4-bit codes of each of two 16-bit halves of w (code u of a half in its bits 4u .. 4u+3) as four fp16
+// pairs: pair u holds code u of the low half and code u of the high half, each in mantissa bits 4 .. 7 of
+// 0x3c00, i.e. the exact fp16 numbers 1 + c/64.  one = per_lane_constant(0x3c003c00), made once by the caller.
+struct NibblePairs {
+  uint32_t p[4];
+};
+__device__ __forceinline__ NibblePairs nibbles_to_fp16_pairs(uint32_t w, uint32_t one) {
+  constexpr uint32_t kNib = 0x00f000f0u;
+  NibblePairs r;
+  r.p[0] = ((w << 4) & kNib) | one;
+  r.p[1] = (w & kNib) | one;
+  r.p[2] = ((w >> 4) & kNib) | one;
+  r.p[3] = ((w >> 8) & kNib) | one;
+  return r;
+}
+
 // 2- and 3-bit latents (the low-bit settings of Sec. 4.4): eight channels' codes, stored as 16 bits of
 // two-bit fields (channel u in bits 2u, 2u+1) and, for 3 bits, 8 third bits (channel u in bit u), spread
 // into the 4-bit layout the kernels work on (channel u in bits 4u .. 4u+3).

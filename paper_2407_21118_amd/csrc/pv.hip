@@ -17,11 +17,11 @@
 // kernel stays bound by the latent stream for every head-group size, including
 // one latent shared by all 32 heads.
 //
-// 4-bit latents: while transposing, a code c becomes the exact fp16 number 1 + c/16
-// (the nibble placed in the top mantissa bits, two operations per register);
+// 4-bit latents: while transposing, a code c becomes the exact fp16 number 1 + c/64
+// (the nibble placed in mantissa bits 4 .. 7, at most two operations per register);
 // the per-(token, 128-channel block) scale is folded into the probabilities
 // (one probability tile per block, a = p s) and the zero-points and the offset
-// into one scalar per (head, block): sum_t a (c - z) = 16 sum_t a (1 + c/16) - sum_t a (16 + z).
+// into one scalar per (head, block): sum_t a (c - z) = 64 sum_t a (1 + c/64) - sum_t a (64 + z).
 
 #include "palu_dev.h"
 
@@ -59,6 +59,7 @@ struct PvArgs {
   int n_split;
   int o_stride;
   int n_blocks_q;
+  int units_per_wg;          // 1, 2 or 4: the wavefronts of a workgroup take this many units of the same splits
   uint8_t n_parts[PALU_MAX_HEADS];   // 1 or 2 score planes per head
   Meta meta;
   PvUnits units;
@@ -95,13 +96,23 @@ __device__ __forceinline__ float dpp_move(float v) {
 __device__ __forceinline__ float swap16(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
 }
-// reductions over the 32 lanes of a wavefront half; the result is in all 32 lanes
-__device__ __forceinline__ float half_wave_max(float v) {
-  v = fmaxf(v, dpp_move<0xB1>(v));     // quad_perm [1,0,3,2]
-  v = fmaxf(v, dpp_move<0x4E>(v));     // quad_perm [2,3,0,1]
-  v = fmaxf(v, dpp_move<0x141>(v));    // row_half_mirror
-  v = fmaxf(v, dpp_move<0x140>(v));    // row_mirror
-  return fmaxf(v, swap16(v));
+// Maximum over the 32 lanes of a wavefront half; the result is in all 32 lanes.  The numbers (no NaN among
+// them) are compared as integers of the same order (negative floats have their low 31 bits inverted): an
+// integer maximum with its lane move is one instruction, where fmaxf() of a moved float takes four (the move
+// and its initial value, and one per operand to quiet signalling NaNs).
+__device__ __forceinline__ int float_order(int b) { return b ^ ((b >> 31) & 0x7fffffff); }     // its own inverse
+template <int CTRL>
+__device__ __forceinline__ int dpp_peek(int v) {          // every lane has a source lane under these controls: no old value to keep
+  return __builtin_amdgcn_update_dpp((int)0x80000000, v, CTRL, 0xf, 0xf, false);
+}
+__device__ __forceinline__ float half_wave_max(float f) {
+  int v = float_order(__builtin_bit_cast(int, f));
+  v = max(v, dpp_peek<0xB1>(v));      // quad_perm [1,0,3,2]
+  v = max(v, dpp_peek<0x4E>(v));      // quad_perm [2,3,0,1]
+  v = max(v, dpp_peek<0x141>(v));     // row_half_mirror
+  v = max(v, dpp_peek<0x140>(v));     // row_mirror
+  v = max(v, __builtin_amdgcn_ds_swizzle(v, 0x401F));
+  return __builtin_bit_cast(float, float_order(v));
 }
 __device__ __forceinline__ float half_wave_sum(float v) {
   v += dpp_move<0xB1>(v);
@@ -140,11 +151,14 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   const int tl = lane & 31, hp = lane >> 5;        // softmax roles: token of the set; head parity
   const Meta& m = a.meta;
 
-  // grid (units, groups of 4 splits, batch); unit fastest: neighbouring workgroups read
-  // neighbouring columns of the same rows.  The indices come from the workgroup id
-  // registers, so the unit descriptor and the other arguments load independently.
-  const int unit = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
-  const int split = sg * 4 + wave;
+  // grid (groups of units_per_wg units, groups of 4 / units_per_wg splits, batch); the wavefronts of a
+  // workgroup take neighbouring units of the same split first: they read neighbouring columns of the same
+  // rows, and the scales and zero-points of a token's blocks, which lie side by side, come into this
+  // compute unit's cache once instead of once per unit.
+  const int upw = a.units_per_wg;
+  const int unit = blockIdx.x * upw + (wave & (upw - 1)), b = blockIdx.z;
+  const int split = blockIdx.y * (4 / upw) + wave / upw;
+  if (unit >= a.units.n_units) return;             // whole wavefront; nothing below synchronises wavefronts
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
   const int s0 = split * a.split_tokens;
   if (split >= a.n_split || s0 >= L) return;       // whole wavefront; nothing below synchronises wavefronts
@@ -168,6 +182,11 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   unsigned coff[NG];
 #pragma unroll
   for (int ng = 0; ng < NG; ++ng) coff[ng] = (unsigned)min(ng * 16 + n, lpt - 1) * (I4 ? (bits == 4 ? 4u : 2u) : 16u);
+  // byte offset of the row of the lane's token j in set 0; a set further on is 32 rows further, clamped to the last row
+  unsigned roff[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) roff[j] = (unsigned)(8 * kq + j) * row_bytes;
+  const unsigned last_off = (unsigned)last * row_bytes, set_bytes = 32u * row_bytes;
 
   const float* sc_ptr[HS];
   bool two[HS];
@@ -188,7 +207,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   struct Set {
     Blk blk[NG];
     float sc[HS][2];
-    uint32_t sz[NA];                               // int4: scale | zero << 16 of the lane's softmax token
+    uint16_t qs[NA], qz[NA];                       // quantized: scale and zero-point of the lane's softmax token (as loaded: nothing waits on them at the request)
   };
 
   // every load is unconditional and in bounds (clamped to the last token / chunk / head);
@@ -199,8 +218,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
     for (int ng = 0; ng < NG; ++ng) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const unsigned t = (unsigned)min(tb + 8 * kq + j, last);
-        const unsigned char* p = base + (size_t)(t * row_bytes + coff[ng]);
+        const unsigned char* p = base + (size_t)(min(roff[j] + (unsigned)k * set_bytes, last_off) + coff[ng]);
         if constexpr (I4) {
           if constexpr (bits == 4) {
             st.blk[ng].h[j][0] = *reinterpret_cast<const uint32_t*>(p);
@@ -224,11 +242,13 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
 #pragma unroll
       for (int ng = 0; ng < NG; ++ng) {
         const size_t idx = sz_idx0 + (size_t)ts * a.n_blocks_q + min(ng, n_blk - 1);   // a narrow unit's idle block re-reads block 0
-        st.sz[ng] = (uint32_t)a.hv_scale[idx] | ((uint32_t)a.hv_zero[idx] << 16);
+        st.qs[ng] = a.hv_scale[idx];
+        st.qz[ng] = a.hv_zero[idx];
       }
     }
   };
 
+  const uint32_t fp16_ones = per_lane_constant(0x3c003c00u);
   float mx[HS], lsum[HS], lz[HS][NA];
 #pragma unroll
   for (int i = 0; i < HS; ++i) {
@@ -294,10 +314,10 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
         lsum[i] += p;
 #pragma unroll
         for (int g = 0; g < NA; ++g) {
-          const float sc = F16::to_float((uint16_t)(st.sz[g] & 0xffffu));
-          const float zp = F16::to_float((uint16_t)(st.sz[g] >> 16));
+          const float sc = F16::to_float(st.qs[g]);
+          const float zp = F16::to_float(st.qz[g]);
           const _Float16 ah = (_Float16)(p * sc);
-          lz[i][g] = fmaf((float)ah, zp + 16.f, lz[i][g]);      // codes enter the product as 1 + c/16, see below
+          lz[i][g] = fmaf((float)ah, zp + 64.f, lz[i][g]);      // codes enter the product as 1 + c/64, see below
           pw[g * (MT * 16 * kPitch) + slot] = ah;
         }
       }
@@ -339,14 +359,16 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
             ca = expand_low_bits(ca, bl.h[2 * jp][QB == 3 ? 1 : 0], QB == 3);
             cb = expand_low_bits(cb, bl.h[2 * jp + 1][QB == 3 ? 1 : 0], QB == 3);
           }
+          // a code c in mantissa bits 4 .. 7 of 0x3c00 is the fp16 number 1 + c/64 (exact):
+          // sum_t a_t (1 + c_t/64) = sum a + (sum a c)/64, undone at the write-out together with the zero-points.
+          // Four channels of both tokens side by side (token a's 16 bits of codes below token b's): the codes of
+          // channel u of the two tokens are then 16 bits apart, i.e. in the two halves of one operand register
+          // after one shift and one masked merge.
 #pragma unroll
-          for (int kb = 0; kb < 4; ++kb) {
-            // byte kb of both tokens' code words side by side: [0, tok b byte, 0, tok a byte]
-            const uint32_t w = __builtin_amdgcn_perm(cb, ca, 0x0c040c00u + 0x00010001u * kb);
-            // a code c in the top four mantissa bits of 0x3c00 is the fp16 number 1 + c/16 (exact):
-            // sum_t a_t (1 + c_t/16) = sum a + (sum a c)/16, undone at the write-out together with the zero-points
-            o[2 * kb][jp] = ((w << 6) & 0x03c003c0u) | 0x3c003c00u;         // even channel: low nibbles
-            o[2 * kb + 1][jp] = ((w << 2) & 0x03c003c0u) | 0x3c003c00u;     // odd channel: high nibbles
+          for (int half = 0; half < 2; ++half) {
+            const NibblePairs np = nibbles_to_fp16_pairs(__builtin_amdgcn_perm(cb, ca, half ? 0x07060302u : 0x05040100u), fp16_ones);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) o[4 * half + u][jp] = np.p[u];                             // channel 4 half + u
           }
         }
       }
@@ -362,19 +384,20 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   };
 
   // ---- kDepth register sets in turn: the loads of the next kDepth - 1 sets are in flight while one is
-  // consumed; nothing is requested past the last set.  (Four sets for quantized latents, whose sets are a quarter
-  // of the bytes, measured no faster: the 4-bit kernel waits on its own dependent chain, not on bytes in flight.)
+  // consumed.  Every request is unconditional (past the last set the clamped addresses re-read the last
+  // token, and nothing consumes them): with a request under a branch the wait in front of process() would
+  // have to cover both ways of reaching it, i.e. every load in flight, and nothing would be prefetched.
+  // (Three and four sets for quantized latents, whose sets are a quarter of the bytes, measured 5 - 10 % slower,
+  // and 2-bit codes take as long as 4-bit ones: that kernel is bound by its instruction stream, not by bytes in flight.)
   constexpr int kDepth = 2;
   Set ring[kDepth];
 #pragma unroll
-  for (int d = 0; d < kDepth - 1; ++d)
-    if (d < n_sets) issue(ring[d], d);
+  for (int d = 0; d < kDepth - 1; ++d) issue(ring[d], d);
   for (int k = 0; k < n_sets; k += kDepth) {
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) {
-      if (k + d >= n_sets) break;                                // uniform
-      if (k + d + kDepth - 1 < n_sets) issue(ring[(d + kDepth - 1) % kDepth], k + d + kDepth - 1);
-      process(ring[d], k + d);
+      issue(ring[(d + kDepth - 1) % kDepth], k + d + kDepth - 1);
+      if (d == 0 || k + d < n_sets) process(ring[d], k + d);      // uniform
     }
   }
 
@@ -414,9 +437,9 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
         const int chunk = ng * 16 + n;
         const int col = c0 + chunk * 8;
         if (chunk >= lpt || col < lo || col >= hi) continue;   // a head keeps the columns of its own group
-        // int4: acc = sum a (1 + c/16) and zt = sum a (16 + z), so sum a (c - z) = 16 acc - zt
+        // int4: acc = sum a (1 + c/64) and zt = sum a (64 + z), so sum a (c - z) = 64 acc - zt
         const float zt = I4 ? xw[hh * NA + ng] : 0.f;
-        const float g = I4 ? 16.f : 1.f;
+        const float g = I4 ? 64.f : 1.f;
         float4v v0, v1;
         v0.x = fmaf(g, acc[mt][ng][0][r], -zt); v0.y = fmaf(g, acc[mt][ng][1][r], -zt);
         v0.z = fmaf(g, acc[mt][ng][2][r], -zt); v0.w = fmaf(g, acc[mt][ng][3][r], -zt);

@@ -23,8 +23,8 @@
 //
 // 4-bit latents: a lane's 16-byte load holds the 32 codes of a quarter of a
 // quantization block; a code c enters the matrix cores as the exact fp16 number
-// 1 + c/16 and the scale, zero-point and offset are applied to the block's sum per token:
-//   sum_k s (c_k - z) qt_k = s (16 sum_k (1 + c_k/16) qt_k - (16 + z) sum_k qt_k).
+// 1 + c/64 and the scale, zero-point and offset are applied to the block's sum per token:
+//   sum_k s (c_k - z) qt_k = s (64 sum_k (1 + c_k/64) qt_k - (64 + z) sum_k qt_k).
 
 #include "palu_dev.h"
 
@@ -77,6 +77,8 @@ struct QkArgs {
   int split_tokens;          // tokens per wavefront (multiple of 32)
   int n_split;
   int n_blocks_q;
+  int units_per_wg;          // 1, 2 or 4: the wavefronts of a workgroup take this many units of the same token ranges
+  int lds_unit_stride;       // bytes of LDS per staged unit
   float scale;               // log2(e) / sqrt(d_h)
   QkUnits units;
 };
@@ -163,16 +165,21 @@ __global__ __launch_bounds__(256) void qfold_kernel(QfoldArgs a) {
 template <typename T, int MT, int QB>
 __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   constexpr bool I4 = QB != 0;                   // QB: bits per code of quantized latents (4, 3, 2), 0 for fp16 / bf16
-  extern __shared__ __attribute__((aligned(16))) unsigned char qk_lds[];
+  extern __shared__ __attribute__((aligned(16))) unsigned char qk_lds_all[];
   constexpr bool kIsBf16 = !__is_same(T, F16);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, kq = lane >> 4;       // token column (B, D) or head row (A); quarter of the 32 channels of a k-step
 
-  // grid (units, groups of 4 token ranges, batch)
-  const int unit = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
-  const QkUnit u = a.units.u[unit];
+  // grid (groups of units_per_wg units, groups of 4 / units_per_wg token ranges, batch); the wavefronts of a
+  // workgroup take neighbouring units of the same token range first: they read neighbouring columns of the
+  // same rows, and the scales and zero-points of a token's blocks, which lie side by side, come into this
+  // compute unit's cache once instead of once per unit.
+  const int upw = a.units_per_wg, b = blockIdx.z;
+  const int unit = blockIdx.x * upw + (wave & (upw - 1));
+  const bool has_unit = unit < a.units.n_units;                       // wavefront-uniform
+  const QkUnit u = a.units.u[min(unit, a.units.n_units - 1)];
   asm volatile("" :: "s"(a.hk), "s"(a.qt), "s"(a.seq_lens), "s"(a.scores), "s"(a.qt_bstride), "s"(a.row_elems), "s"(a.max_seq),
                "s"(a.seq_len), "s"(a.lpad), "s"(a.n_heads), "s"(a.split_tokens), "s"(a.n_split), "s"(u.c0), "s"(u.q_off),
                "s"((int)u.h0), "s"((int)u.ncols), "s"((int)u.wpad), "s"((int)u.nh));   // all in registers here: one round trip
@@ -180,19 +187,42 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   const int pitch = wpad + 8;                    // halfs per staged row: 16 bytes of padding keep the 16 head rows on distinct banks
   const bool use_lo = !I4 && u.use_lo;           // uniform
   const int lo_rows = nh * pitch * 2;            // byte offset of the lo rows behind the hi rows
+  unsigned char* const qk_lds = qk_lds_all + (wave & (upw - 1)) * a.lds_unit_stride;   // this wavefront's unit
 
-  // ---- folded queries of the unit -> LDS (rows of heads beyond nh are never read: their lanes re-read row nh-1)
-  {
-    const uint16_t* src = a.qt + (size_t)b * a.qt_bstride + u.q_off;
-    const int cpr = wpad >> 3;                   // 16-byte chunks per row
-    for (int i = tid; i < (use_lo ? 2 : 1) * nh * cpr; i += 256) {
+  // ---- folded queries of the workgroup's units -> LDS (rows of heads beyond nh are never read: their lanes re-read row nh-1)
+  for (int j = 0; j < upw; ++j) {
+    const int uj = blockIdx.x * upw + j;
+    if (uj >= a.units.n_units) break;              // uniform
+    const QkUnit& v_u = a.units.u[uj];
+    const int j_wpad = v_u.wpad, j_nh = v_u.nh, j_pitch = j_wpad + 8;
+    const int j_rows = ((!I4 && v_u.use_lo) ? 2 : 1) * j_nh;
+    const uint16_t* src = a.qt + (size_t)b * a.qt_bstride + v_u.q_off;
+    unsigned char* dst = qk_lds_all + j * a.lds_unit_stride;
+    const int cpr = j_wpad >> 3;                   // 16-byte chunks per row
+    for (int i = tid; i < j_rows * cpr; i += 256) {
       const int r = i / cpr, cc = i - r * cpr;
-      *reinterpret_cast<uint4v*>(qk_lds + ((size_t)r * pitch + cc * 8) * 2) = *reinterpret_cast<const uint4v*>(src + (size_t)r * wpad + cc * 8);
+      uint4v v = *reinterpret_cast<const uint4v*>(src + (size_t)r * j_wpad + cc * 8);
+      if constexpr (I4) {
+        // channels (0 .. 7) of a chunk in the order 0 4 1 5 2 6 3 7: the order in which the codes of one
+        // 32-bit word leave the dequantizer below (perm: selector bytes 0-3 pick from the second operand)
+        v = uint4v{__builtin_amdgcn_perm(v.z, v.x, 0x05040100u), __builtin_amdgcn_perm(v.z, v.x, 0x07060302u),
+                   __builtin_amdgcn_perm(v.w, v.y, 0x05040100u), __builtin_amdgcn_perm(v.w, v.y, 0x07060302u)};
+      }
+      *reinterpret_cast<uint4v*>(dst + ((size_t)r * j_pitch + cc * 8) * 2) = v;
+    }
+    if constexpr (I4) {
+      // the block sums [nh][wpad / 128] of the folded query behind its rows: read from LDS in the loop, they are
+      // not in the queue of the memory loads (which return in order, so a wait for a value requested after
+      // the next step's latents would wait for those latents too)
+      const float* qs_src = a.qsum + (size_t)b * a.qs_bstride + v_u.qs_off;
+      float* qs_dst = reinterpret_cast<float*>(dst + (size_t)j_nh * j_pitch * 2);
+      for (int i = tid; i < j_nh * (j_wpad >> 7); i += 256) qs_dst[i] = qs_src[i];
     }
   }
   __syncthreads();
+  if (!has_unit) return;                         // whole wavefront; no barrier below
 
-  const int split = sg * 4 + wave;
+  const int split = blockIdx.y * (4 / upw) + wave / upw;
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
   const int s0 = split * a.split_tokens;
   if (split >= a.n_split || s0 >= L) return;     // whole wavefront; no barrier below
@@ -214,7 +244,7 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   constexpr int NL = I4 ? 2 : 8;                 // 16-byte loads per tile and chunk: int4 one per 128-column block, else one per 32 columns
   struct Step {
     uint4v h[2][NL];
-    uint32_t sz[2][I4 ? 2 : 1];                  // int4: scale | zero << 16 of (tile token, block)
+    uint16_t qs[2][I4 ? 2 : 1], qz[2][I4 ? 2 : 1];   // quantized: scale and zero-point of (tile token, block), as loaded
   };
   // loads of (set, chunk); clamped to the last token / last valid columns (whose folded query is zero-padded)
   auto issue = [&](Step& st, int set, int chunk) {
@@ -228,7 +258,8 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
           const int blkc = min(chunk * 2 + x, n_blk - 1);
           off = (unsigned)blkc * 64u + (unsigned)kq * 16u;
           const size_t idx = sz_idx0 + (size_t)t * a.n_blocks_q + blkc;
-          st.sz[tau][x] = (uint32_t)a.hk_scale[idx] | ((uint32_t)a.hk_zero[idx] << 16);
+          st.qs[tau][x] = a.hk_scale[idx];
+          st.qz[tau][x] = a.hk_zero[idx];
         } else {
           const int col = min(chunk * 256 + x * 32 + kq * 8, ncols - 8);
           off = (unsigned)col * 2u;
@@ -247,11 +278,12 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
     }
   };
 
+  const uint32_t fp16_ones = per_lane_constant(0x3c003c00u);
   float4v acc[MT][2];
   int qrow[MT];                                  // byte offset of this lane's head row in the staged matrix
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) qrow[mt] = min(mt * 16 + n, nh - 1) * pitch * 2;
-  const float* qs_base = a.qsum + (size_t)b * a.qs_bstride + u.qs_off;
+  const float* qs_base = reinterpret_cast<const float*>(qk_lds + (size_t)nh * pitch * 2);     // staged block sums (quantized latents)
 
   auto process = [&](Step& st, int set, int chunk) {
     if (chunk == 0) {
@@ -312,25 +344,23 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
             uint32_t w = st.h[tau][x][jj];
             if constexpr (bits != 4)
               w = expand_low_bits(st.h[tau][x][jj >> 1] >> (16 * (jj & 1)), st.h[tau][x][2] >> (8 * jj), bits == 3);
-            const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;     // even / odd channels, one per byte
-            uint4v bw;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              // (even code, odd code) of byte e as the fp16 pair (1 + c_even/16, 1 + c_odd/16): the nibble in the
-              // top mantissa bits of 0x3c00; the offset is undone on the block's sum below
-              bw[e] = (__builtin_amdgcn_perm(hi, lo, 0x0c040c00u + 0x00010001u * e) << 6) | 0x3c003c00u;
-            }
+            // code c of channel u sits in bits 4u .. 4u+3; moved to mantissa bits 4 .. 7 of 0x3c00 it is the fp16
+            // number 1 + c/64 (exact).  Channels u and u + 4 are 16 bits apart, i.e. already in the two halves of
+            // one operand register: one shift and one masked merge per register, and the k order 0 4 1 5 2 6 3 7,
+            // which is the order the folded query was staged in.  The offset is undone on the block's sum below.
+            const NibblePairs np = nibbles_to_fp16_pairs(w, fp16_ones);
+            const uint4v bw = {np.p[0], np.p[1], np.p[2], np.p[3]};
             const half8 bop = __builtin_bit_cast(half8, bw);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) d[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[mt][jj], bop, d[mt], 0, 0, 0);
           }
-          const float sc = chunk * 2 + x < n_blk ? F16::to_float((uint16_t)(st.sz[tau][x] & 0xffffu)) : 0.f;
-          const float zp = F16::to_float((uint16_t)(st.sz[tau][x] >> 16));
+          const float sc = chunk * 2 + x < n_blk ? F16::to_float(st.qs[tau][x]) : 0.f;
+          const float zp = F16::to_float(st.qz[tau][x]);
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)      // d = sum qt (1 + c/16): sum qt (c - z) = 16 d - (16 + z) sum qt
-              acc[mt][tau][r] = fmaf(sc, fmaf(-(zp + 16.f), qs[mt][r], 16.f * d[mt][r]), acc[mt][tau][r]);
+            for (int r = 0; r < 4; ++r)      // d = sum qt (1 + c/64): sum qt (c - z) = 64 d - (64 + z) sum qt
+              acc[mt][tau][r] = fmaf(sc, fmaf(-(zp + 64.f), qs[mt][r], 64.f * d[mt][r]), acc[mt][tau][r]);
         }
       }
     }
@@ -350,21 +380,23 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   };
 
   // steps (set, chunk) in order, kDepth register sets in turn: the loads of the next kDepth - 1 steps are in
-  // flight while one is consumed; nothing is requested past the last step.
+  // flight while one is consumed (four steps deep measured slower for quantized latents).  Every request is
+  // unconditional (past the last step the clamped addresses re-read the last token, and nothing consumes
+  // them): with a request under a branch the wait in front of process() would have to cover both ways of
+  // reaching it, i.e. every load in flight, and nothing would be prefetched.
   const int n_steps = n_sets * n_chunks;
   auto next = [&](int& set, int& chunk) { if (++chunk == n_chunks) { chunk = 0; ++set; } };
   constexpr int kDepth = 2;
   Step ring[kDepth];
   int is = 0, ic = 0, ps = 0, pc = 0;            // next step to request / to consume
 #pragma unroll
-  for (int d = 0; d < kDepth - 1; ++d)
-    if (d < n_steps) { issue(ring[d], is, ic); next(is, ic); }
+  for (int d = 0; d < kDepth - 1; ++d) { issue(ring[d], is, ic); next(is, ic); }
   for (int k = 0; k < n_steps; k += kDepth) {
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) {
-      if (k + d >= n_steps) break;               // uniform
-      if (k + d + kDepth - 1 < n_steps) { issue(ring[(d + kDepth - 1) % kDepth], is, ic); next(is, ic); }
-      process(ring[d], ps, pc); next(ps, pc);
+      issue(ring[(d + kDepth - 1) % kDepth], is, ic); next(is, ic);
+      __builtin_amdgcn_sched_barrier(0);           // the requests stay in front of the work that hides them
+      if (d == 0 || k + d < n_steps) { process(ring[d], ps, pc); next(ps, pc); }     // uniform
     }
   }
 }
