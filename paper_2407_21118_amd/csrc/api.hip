@@ -138,7 +138,7 @@ struct ScorePlan {
 };
 
 // widen: let a unit of small groups span 2 or 4 adjacent groups of equal rank and size
-int plan_score(const Meta& m, ScorePlan* p, bool widen = true) {
+int plan_score(const Meta& m, ScorePlan* p, bool widen = true, bool split16 = false) {
   p->n_cls = 0;
   p->total_units = 0;
   p->max_slices = 1;
@@ -188,6 +188,28 @@ int plan_score(const Meta& m, ScorePlan* p, bool widen = true) {
     }
     const int rc = rank_class(r);
     if (rc < 0) return PALU_ERR_UNSUPPORTED;
+    if (rank_class_half(rc)) p->max_slices = std::max(p->max_slices, 2);      // planes for either form below
+    if (rank_class_half(rc) && split16) {
+      // rank 288 .. 512 on the whole-head kernel: two slices of 128 .. 256 rows (multiples of 32), each a unit
+      // of its own rank class that writes one score plane
+      const int nh = std::min(4, m.head_off[j0 + 1] - h);
+      const int r0 = (r + 63) / 64 * 32;
+      for (int sl = 0; sl < 2; ++sl) {
+        u.nh = nh;
+        u.k_off0 = m.k_off[j0] + sl * r0;
+        u.bk_off0 = m.bk_off[j0] + (h - m.head_off[j0]) * u.head_stride + sl * r0 * PALU_D_HEAD;
+        u.head_off0 = h;                 // heads of the unit are counted from h0 inside one group
+        u.part0 = sl;
+        const int st = add_unit(rank_class(sl ? r - r0 : r0) * 3, u);
+        if (st != PALU_OK) return st;
+      }
+      for (int x = 0; x < nh; ++x) {
+        p->slices[h + x] = 2;
+        p->half_heads[h + x] = false;
+      }
+      h += nh;
+      continue;
+    }
     int nh, lg = 0;
     if (rank_class_half(rc)) {
       nh = std::min(2, m.head_off[j0 + 1] - h);
@@ -1069,7 +1091,11 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   ScorePlan sp;
   PvPlan pp;
   const bool k_lowbit = k_bits == 2 || k_bits == 3;        // their score kernels take one group per workgroup
-  if ((st = plan_score(m, &sp, !k_lowbit)) != PALU_OK) return st;
+  // unquantized latents, one query per wavefront's head: every head of rank 64 and more runs on the whole-head kernel
+  // (ranks above 256 in slices); the shared-key form, which leaves it, only takes layers without such ranks
+  // (not with option score_fp8, whose weights are laid out per whole head)
+  const bool split16 = !k_i4 && g_opt_score_waves == 0 && g_opt_score_fp8 == 0;
+  if ((st = plan_score(m, &sp, !k_lowbit, split16)) != PALU_OK) return st;
   if ((st = plan_pv(m, &pp)) != PALU_OK) return st;
   const int quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
   int split_tokens, n_split;
@@ -1260,7 +1286,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         fa.rev_lo[f] = (float)(rev - (double)fa.rev_hi[f]);
       }
       fa.meta = mk;
-      fa.layout16 = use16 ? 1 : 0;
+      fa.layout16 = use16 ? (split16 ? 2 : 1) : 0;
       int max_r = 0;
       for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
       const dim3 g((unsigned)(max_r / 16), (unsigned)mk.n_heads, 1u);
@@ -1452,7 +1478,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   int max_parts = 0;
   for (int h = 0; h < m.n_heads; ++h) {      // half-head wavefronts write two planes per rank slice
     const int rk = m.k_off[m.group_of_head[h] + 1] - m.k_off[m.group_of_head[h]];
-    const bool whole = used16 && (rank_class_16(rank_class(rk)) || rk > 512);      // one wavefront per head: one plane (per rank slice)
+    // one wavefront per head: one plane (per rank slice)
+    const bool whole = used16 && (split16 ? rk >= 64 : (rank_class_16(rank_class(rk)) || rk > 512));
     n_parts[h] = no_rope ? (uint8_t)1 : (uint8_t)(((waves8 || sp.half_heads[h]) && !whole) ? 2 * sp.slices[h] : sp.slices[h]);
     max_parts = std::max(max_parts, (int)n_parts[h]);
   }

@@ -224,7 +224,7 @@ struct FoldArgs {
   uint16_t* mfold;           // B_k transposed per head, in matrix-core operand order
   float rev_hi[kHalf];       // theta^(-2f/128) / (2 pi) from the host's float64 value, as a float pair hi + lo
   float rev_lo[kHalf];       // (read by the query items that ride in the same launch, see qfrag_body)
-  int layout16;              // heads of rank 64 .. 256 (and above 512, in slices of 256) in score16_kernel's operand order
+  int layout16;              // score16_kernel's operand order for: 1 = heads of rank 64 .. 256 and above 512 (slices of 256); 2 = every head of rank 64 and more
   Meta meta;
 };
 

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void rope_gather_tiles_kernel(RopeGatherArgs a
 // with coalesced 16-byte loads, transposed through LDS, and written as 256
 // 16-byte words in operand order: word (row tile rt, lane) = 8 consecutive k of
 // feature 32 rt + lane % 32, k-octet lane / 32.  The 16-bit values are copied as they are.
-// Heads of rank 64 .. 256 (and above 512: slices of 256) are laid out for score16_kernel instead when a.layout16 is set (16-feature
+// Heads of rank 64 and more are laid out for score16_kernel instead when a.layout16 is set (16-feature
 // operands of v_mfma_f32_16x16x32): per k-step of 32 rows, 512 words: word (feature tile ct, lane) =
 // 8 consecutive k (k-octet lane / 16 of the 32) of feature 16 ct + lane % 16; the workgroups of even ks
 // do two 16-row steps each.
@@ -76,7 +76,8 @@ __device__ __forceinline__ void fold_body(const FoldArgs& a, int ks, int h) {
   const int r = m.k_off[j + 1] - m.k_off[j];
   if (ks >= (r >> 4)) return;
   int width;
-  if (a.layout16 && ((r >= 64 && r <= 256) || r > 512)) {        // ranks above 512 are contracted in slices of 256 rows
+  // ranks above 256 are contracted in slices of up to 256 rows (layout16 == 1: only those above 512, the others by score_kernel)
+  if (a.layout16 && r >= 64 && (a.layout16 == 2 || r <= 256 || r > 512)) {
     if (ks & 1) return;
     const uint16_t* B = a.Bk + weight_block(m, j, h, m.bk_off[j], &width);
     const int lrow = tid >> 3, lcol = (tid & 7) * 16;             // thread = (row of 32, 16-column piece)
