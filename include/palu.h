@@ -137,13 +137,16 @@ int palu_probe_read(const void* src, size_t bytes, float* sink, void* stream);
 
 /*
  * RoPE angle table (Sec. 3.1.2: RoPE acts on queries and keys before their
- * product).  For position p and pair f < d_h/2 the table stores, as float16,
- * cos(p w_f) and sin(p w_f) with w_f = theta^(-2f/d_h), computed in float64;
+ * product).  For position p and pair f < d_h/2 the table stores cos(p w_f) and
+ * sin(p w_f) with w_f = theta^(-2f/d_h): as float32 (read by the default score
+ * kernels) and, beside them, as float16 (read by the opt-in shared-key form).
+ * The angle is reduced in revolutions with float32 pair arithmetic from the
+ * host's float64 frequencies (about 1e-7 absolute for positions up to 2^24);
  * the pairing is (f, f + d_h/2) as in the Huggingface Llama implementation the
- * paper builds on (Sec. 4.1).  The row order inside a position is private to
- * the library.  One table serves every layer and step of a model; build it
- * once for the longest position that will occur.  theta <= 0 fills the table
- * with cos = 1, sin = 0.
+ * paper builds on (Sec. 4.1).  The layout (tiles of 32 positions) is private to
+ * the library; its size is palu_rope_table_bytes.  One table serves every layer
+ * and step of a model; build it once for the longest position that will occur.
+ * theta <= 0 fills the table with cos = 1, sin = 0.
  *   n_pos     number of positions 0 .. n_pos-1
  *   table     DEVICE, palu_rope_table_bytes(...) bytes, 256-byte aligned
  */
