@@ -106,14 +106,16 @@ int palu_version(void);
  *                         (clamped to +-448, no scale), and the keys are rebuilt on the 8-bit matrix
  *                         instructions; rotation, scores, softmax and values as in the default path.  The
  *                         result is exact attention over keys rebuilt from the rounded operands (about 3 % noise
- *                         per key entry): a different numeric contract, 1.3x faster scores on a 7B-shaped layer.
+ *                         per key entry): a different numeric contract, 1.2x faster scores on a 7B-shaped layer.
  *                         Set it before querying the workspace size (it adds a region).  Default 0.
  *   "shared_key_fp16"     1: with 2 .. 16 queries per key/value head (grouped-query heads, several queries per
  *                         sequence), fp16 latents and ranks <= 256, rebuild each key once for the queries that
  *                         share it and contract it with them on the matrix cores after rounding the key and
- *                         its cos / sin products to fp16.  About 3x faster on a 4:1 grouped-query layer, but
- *                         the logit error is about 4e-4 of the logit (output error 2e-3 reached at logits of
- *                         about +-25).  Default 0: every query head rebuilds its keys in float32.
+ *                         its cos / sin products to fp16.  About 1.5x faster scores on a 4:1 grouped-query layer
+ *                         than the default, but the logit error is about 4e-4 of the logit (output error 2e-3
+ *                         reached at logits of about +-25).  Default 0: keys are rebuilt and rotated in float32,
+ *                         once per key/value head for its 2, 4 or 8 queries where every key rank of the layer is
+ *                         128 .. 256 (8 queries: 192 .. 256), else once per query head.
  *   "encode_tile_rows"    token rows per workgroup of the prompt-sized projection (64, 128 or 256, each
  *                         with 256 columns; 32 selects the narrow tile of 64 rows x 128 columns)
  * Unknown names and out-of-range values return PALU_ERR_INVALID_ARG.  Set

@@ -21,7 +21,9 @@ HIPCC_FLAGS = [
 # The matrix instructions of the attention kernels write ordinary vector registers, so their float32
 # epilogues read the accumulators without a copy per value; the prompt-sized projection keeps its 256
 # accumulators per lane in the accumulation registers and is compiled on its own without the option.
-VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+# (The shared-key forms of the whole-head score kernel unroll 64 matrix instructions with the vector work of up to
+# eight queries dealt out between them: beyond the default size limit of "#pragma unroll".)
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form", "-mllvm", "-pragma-unroll-threshold=200000"]
 BUILD_DIR = os.path.join(HERE, "_build")
 
 

@@ -502,6 +502,26 @@ ScoreFn score16_fn_t(int rc, int lg) {
   }
 }
 inline bool rank_class_16(int rc) { return rc >= 1 && rc <= 7; }
+// ... and 2, 4 or 8 queries per key/value head: the key rebuilt once per key/value head (ranks 128 .. 256; 8 queries: 192 .. 256)
+inline bool shared16_ok(int rc, int nq) { return rc >= 3 && rc <= 7 && (nq == 2 || nq == 4 || (nq == 8 && rc >= 5)); }
+template <typename T, int NK>
+ScoreFn score16q_fn_n(int nq) {
+  if (nq == 2) return score16_kernel<T, NK, 1, 2>;
+  if (nq == 4) return score16_kernel<T, NK, 1, 4>;
+  if constexpr (NK >= 6) { if (nq == 8) return score16_kernel<T, NK, 1, 8>; }
+  return nullptr;
+}
+template <typename T>
+ScoreFn score16q_fn_t(int rc, int nq) {
+  switch (rc) {
+    case 3: return score16q_fn_n<T, 4>(nq);
+    case 4: return score16q_fn_n<T, 5>(nq);
+    case 5: return score16q_fn_n<T, 6>(nq);
+    case 6: return score16q_fn_n<T, 7>(nq);
+    case 7: return score16q_fn_n<T, 8>(nq);
+    default: return nullptr;
+  }
+}
 
 // 3- and 2-bit key latents: one group per workgroup, 8 wavefronts up to rank 256, 4 half-head wavefronts above
 template <int NKS>
@@ -1257,10 +1277,15 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     // share it (shared-key form).  Otherwise every query head rebuilds its key/value head's keys (one-query form).
     bool shared_key = g_opt_shared_key_fp16 != 0 && m.qpk >= 2 && m.qpk <= 16 && act == PALU_F16 && !k_i4 && waves8;
     for (int j = 0; j < m.n_groups && shared_key; ++j) shared_key = m.k_off[j + 1] - m.k_off[j] <= 256;
-    const Meta mk = shared_key ? kv_head_meta(m) : m;
     // unquantized latents, one query per head: heads of rank 64 .. 256 run one whole head per wavefront
     // (option score_waves = 4 or 8 forces the half-head / ping-pong schedules of score_kernel)
     const bool use16 = !shared_key && !k_i4 && g_opt_score_waves == 0;
+    // ... and with 2, 4 or 8 queries per key/value head and ranks 128 .. 256 one whole key/value head per wavefront:
+    // the key is rebuilt and rotated once in float32 for the queries that share it (exact shared-key form)
+    bool shared16 = use16 && m.qpk > 1 && g_opt_score_fp8 == 0;
+    for (int j = 0; j < m.n_groups && shared16; ++j) shared16 = shared16_ok(rank_class(m.k_off[j + 1] - m.k_off[j]), m.qpk);
+    const bool kv_units = shared_key || shared16;            // the score units are key/value heads
+    const Meta mk = kv_units ? kv_head_meta(m) : m;
     used16 = use16;
     // option score_fp8: those heads rebuild their keys from E4M3-rounded latents and weights (fp16 layers)
     const bool use8 = use16 && g_opt_score_fp8 != 0 && act == PALU_F16;
@@ -1271,8 +1296,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         if (sp.cls_id[sp.unit_cls[i]] == kSlicedCls) sp.units[i].part0 /= 2;
     }
     static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)
-    if (shared_key && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
-    const ScorePlan& plan = shared_key ? spk : sp;
+    if (kv_units && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
+    const ScorePlan& plan = kv_units ? spk : sp;
 
     // 1. B_k in the score kernel's operand order (shared-key form: and the rotated queries beside it)
     static thread_local FoldArgs fa;
@@ -1440,9 +1465,11 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         size_t lds = (size_t)score_lds_bytes(width, dma, !shared_key, pingpong);
         const bool k16 = use16 && rank_class_16(rc);
         ScoreFn fn = shared_key ? (m.qpk <= 4 ? score_fn_shared<1>(rc) : score_fn_shared<2>(rc))
+                   : shared16 ? (act == PALU_F16 ? score16q_fn_t<F16>(rc, m.qpk) : score16q_fn_t<BF16>(rc, m.qpk))
                    : k16 ? (act == PALU_F16 ? score16_fn_t<F16>(rc, lg) : score16_fn_t<BF16>(rc, lg))
                    : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, rc * 3 + lg, waves8));
         if (k16) lds = (size_t)score16_lds_bytes(width);
+        if (!fn) return PALU_ERR_UNSUPPORTED;
         const bool k8 = k16 && use8 && !sliced;
         if (k8) {
           fn = score8_fn(rc, lg);

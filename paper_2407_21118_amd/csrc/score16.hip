@@ -15,6 +15,11 @@
 //
 // Per 32-token tile and CU this moves 160 KiB through the LDS where the ping-pong schedule moves 225,
 // and issues 0.75 as many vector instructions.
+//
+// Several queries per key/value head (grouped-query layers, several query tokens per sequence; NQ = 2, 4, 8): the
+// wavefront's head is a key/value head; its key tile is rebuilt once, each key pair rotated once in float32 and
+// multiplied by each of the NQ rotated queries (4 + 2 NQ operations per token and pair instead of 6 NQ), then one
+// lane exchange and one score row per query.
 
 #pragma once
 #include <type_traits>
@@ -46,13 +51,17 @@ __device__ __forceinline__ float sum_quad_over_row(const float (&p)[4], int lane
 //     latent row is G * 32 * NK columns wide
 // grid (sequence chunks, units, batch), 256 threads.  a.mfold: B_k^T in the operand order of
 // fold_body's 16-feature layout.
-template <typename T, int NK, int G>
+// NQ: queries that share the wavefront's key/value head (grouped-query layers, several query tokens per sequence):
+//     the unit's heads are then key/value heads, query row hc * NQ + i reads key/value head hc; the key tile is
+//     rebuilt once, rotated once in float32 and multiplied by each rotated query (NQ = 1: the head's own query)
+template <typename T, int NK, int G, int NQ = 1>
 __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   using Vec = typename T::vec8;
   constexpr int kRank = NK * 32;
   constexpr int kWidth = G * kRank;
   static_assert(kWidth <= 512 && NK >= 2 && NK <= 8, "latent tile row too wide / rank outside 64 .. 256");
+  static_assert(NQ == 1 || (G == 1 && NK * 8 >= 5 * NQ + 8), "shared keys: one group per workgroup, room for the queries' lane exchanges");
   constexpr int kCpr = kWidth / 8;                              // 16-byte chunks per tile row
   constexpr int kRowB = kWidth * 2 + kRowPad;
   constexpr int kTileB = kTile * kRowB;
@@ -158,19 +167,27 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
 
   // the first tile's requests, then the query and the weights (everything the first sub-tile waits for), then the other tiles
   dma_issue(0);
-  uint16_t q_raw[4][2];
+  uint16_t q_raw[NQ][4][2];
   float q_rev[4][2];
-  int q_position;
+  int q_position[NQ];
   {
     Meta mq;                                                    // only the fields q_row and q_token read
     mq.n_heads = a.n_heads; mq.qpk = a.m_qpk; mq.nq = a.m_nq;
-    const uint16_t* qp = a.q + q_row(mq, b, hc) * kDHead;
-    q_position = a.q_pos[b * a.m_nq + q_token(mq, hc)];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      const int hq = hc * NQ + i;                               // the query row (NQ = 1: the head itself)
+      const uint16_t* qp = a.q + q_row(mq, b, hq) * kDHead;
+      q_position[i] = a.q_pos[b * a.m_nq + q_token(mq, hq)];
+#pragma unroll
+      for (int pb = 0; pb < 4; ++pb) {
+        const int f = 16 * pb + n16;
+        q_raw[i][pb][0] = qp[f];
+        q_raw[i][pb][1] = qp[f + kHalf];
+      }
+    }
 #pragma unroll
     for (int pb = 0; pb < 4; ++pb) {
       const int f = 16 * pb + n16;
-      q_raw[pb][0] = qp[f];
-      q_raw[pb][1] = qp[f + kHalf];
       q_rev[pb][0] = a.rev_hi[f];
       q_rev[pb][1] = a.rev_lo[f];
     }
@@ -215,25 +232,27 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   };
   auto angle_tile = [&](int tile) __attribute__((always_inline)) { return lds + kCsRing + (size_t)(tile % kBufs) * kRopeTileBytes; };
 
-  float* out_row = a.scores + ((size_t)u.part0 * a.batch + b) * a.n_heads * (size_t)a.lpad + (size_t)hc * a.lpad + t_begin;
+  // the score row of query row hc * NQ (the others follow, lpad floats apart)
+  float* out_row = a.scores + ((size_t)u.part0 * a.batch + b) * a.n_heads * (size_t)a.lpad + (size_t)hc * NQ * a.lpad + t_begin;
   const int tok_of_lane = 4 * kq + 2 * ((lane >> 2) & 1) + (lane & 1);      // see sum_quad_over_row
 
   // ---- start-up: tile 0, the query and the weights have landed; tiles 1 .. kAheadTiles-1 stay in flight
   __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAheadTiles - 1) * kDmaOps));
   __syncthreads();
   // the rotated query, scaled by log2(e) / sqrt(d_h): qa = q'_f, qb = q'_{f+64} of pair f = 16 pb + n16
-  float qa[4], qb[4];
-  {
-    const float pos = (float)q_position;
+  float qa[NQ][4], qb[NQ][4];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const float pos = (float)q_position[i];
 #pragma unroll
     for (int pb = 0; pb < 4; ++pb) {
-      const float x0 = T::to_float(q_raw[pb][0]), x1 = T::to_float(q_raw[pb][1]);
+      const float x0 = T::to_float(q_raw[i][pb][0]), x1 = T::to_float(q_raw[i][pb][1]);
       const float ph = pos * q_rev[pb][0];
       const float pe = fmaf(pos, q_rev[pb][0], -ph);
       const float rev = (ph - floorf(ph)) + (pe + pos * q_rev[pb][1]);          // the angle in revolutions, see score.hip
       const float sn = __builtin_amdgcn_sinf(rev), cn = __builtin_amdgcn_cosf(rev);
-      qa[pb] = (x0 * cn - x1 * sn) * a.scale;
-      qb[pb] = (x1 * cn + x0 * sn) * a.scale;
+      qa[i][pb] = (x0 * cn - x1 * sn) * a.scale;
+      qb[i][pb] = (x1 * cn + x0 * sn) * a.scale;
     }
   }
 
@@ -246,8 +265,24 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   auto half_item = [&](const float4v (&ac)[8], float (&part)[4], int e2, const float4v& c, const float4v& s)
       __attribute__((always_inline)) {
     const int pb = e2 >> 3, j = (e2 >> 1) & 3, h2 = e2 & 1;
-    const float coef = h2 == 0 ? fmaf(s[j], qb[pb], c[j] * qa[pb]) : fmaf(-s[j], qa[pb], c[j] * qb[pb]);
+    const float coef = h2 == 0 ? fmaf(s[j], qb[0][pb], c[j] * qa[0][pb]) : fmaf(-s[j], qa[0][pb], c[j] * qb[0][pb]);
     part[j] = fmaf(ac[pb + 4 * h2][j], coef, part[j]);
+  };
+  // Shared keys (NQ > 1): pair block pb, token j in 1 + NQ / 2 steps of four operations: step 0 rotates the key pair,
+  //   r0 = k_f c - k_{f+64} s,  r1 = k_{f+64} c + k_f s,   step x > 0 adds r0 q'_f + r1 q'_{f+64} for queries 2x-2 and 2x-1
+  constexpr int kPairSteps = 1 + NQ / 2;
+  auto pair_step = [&](const float4v (&ac)[8], float (&part)[NQ][4], float (&rot)[2], int st, const float4v& c, const float4v& s)
+      __attribute__((always_inline)) {
+    const int it = st / kPairSteps, x = st % kPairSteps, pb = it >> 2, j = it & 3;
+    if (x == 0) {
+      const float kf = ac[pb][j], kg = ac[pb + 4][j];
+      rot[0] = fmaf(-kg, s[j], kf * c[j]);
+      rot[1] = fmaf(kf, s[j], kg * c[j]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NQ; ++i)
+        if (i / 2 == x - 1) part[i][j] = fmaf(rot[1], qb[i][pb], fmaf(rot[0], qa[i][pb], part[i][j]));
+    }
   };
   // the sum over the features of the 4 tokens a lane holds (sum_quad_over_row) in four steps of at most three operations
   struct RowSum {
@@ -266,14 +301,31 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   // the whole of it at once (the last sub-tile of the chunk)
   auto finish = [&](const float4v (&ac)[8], int tile, int tt) __attribute__((always_inline)) {
     const unsigned char* cst = angle_tile(tile);
-    float part[4] = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (NQ == 1) {
+      float part[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int pb = 0; pb < 4; ++pb) {
-      const float4v c = angle_piece(cst, pb, 4 * tt), s = angle_piece(cst, pb, 8 + 4 * tt);
+      for (int pb = 0; pb < 4; ++pb) {
+        const float4v c = angle_piece(cst, pb, 4 * tt), s = angle_piece(cst, pb, 8 + 4 * tt);
 #pragma unroll
-      for (int x = 0; x < 8; ++x) half_item(ac, part, 8 * pb + x, c, s);
+        for (int x = 0; x < 8; ++x) half_item(ac, part, 8 * pb + x, c, s);
+      }
+      out_row[tile * kTile + 16 * tt + tok_of_lane] = sum_quad_over_row(part, lane);
+    } else {
+      float part[NQ][4];
+      float rot[2];
+#pragma unroll
+      for (int i = 0; i < NQ; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) part[i][j] = 0.f;
+#pragma unroll
+      for (int pb = 0; pb < 4; ++pb) {
+        const float4v c = angle_piece(cst, pb, 4 * tt), s = angle_piece(cst, pb, 8 + 4 * tt);
+#pragma unroll
+        for (int x = 0; x < 4 * kPairSteps; ++x) pair_step(ac, part, rot, 4 * kPairSteps * pb + x, c, s);
+      }
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) out_row[(size_t)i * a.lpad + tile * kTile + 16 * tt + tok_of_lane] = sum_quad_over_row(part[i], lane);
     }
-    out_row[tile * kTile + 16 * tt + tok_of_lane] = sum_quad_over_row(part, lane);
   };
 
   // Sub-tile tt of tile k: its matrix instructions, each followed by at most a few vector operations of the previous
@@ -282,8 +334,9 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   // last quarter; in the second sub-tile of a tile also the tile hand-over: wait for this wavefront's share of tile
   // k+1, one barrier, request tile k + kAheadTiles into the buffers tile k-1 occupied (every reader of tile k-1, its
   // last sub-tile's items included, is past that barrier).
-  constexpr int kSumSlot0 = kMfmas - 5;                         // four lane-exchange steps and the store
+  constexpr int kSumSlot0 = kMfmas - 5 * NQ;                    // per query: four lane-exchange steps and the store
   constexpr int kItemSlots = kMfmas * 3 / 4 < kSumSlot0 ? kMfmas * 3 / 4 : kSumSlot0;
+  constexpr int kSteps = NQ == 1 ? 32 : 16 * kPairSteps;        // half-items, or steps of the shared-key pairs, per sub-tile
   static_assert(kItemSlots <= kSumSlot0, "the lane exchange follows the last half-item");
   // k-step before which the hand-over happens: the middle of the sub-tile where its last two k-steps (which already
   // read tile k+1) come after it, else its start
@@ -298,7 +351,12 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
     const int ptile = tt == 0 ? k - 1 : k;
     constexpr int ptt = 1 - tt;
     const unsigned char* cst = angle_tile(have_prev ? ptile : k);
-    float part[4] = {0.f, 0.f, 0.f, 0.f};
+    float part[NQ][4];
+    float rot[2];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) part[i][j] = 0.f;
     float4v csr[2][2];
     RowSum rs;
     DmaTile nxt;
@@ -328,20 +386,21 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
         else acc[tt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, W[ks][ct], prev, 0, 0, 0);
         if (have_prev) {
           if (mi < kItemSlots) {
-            // half-items [mi * 32 / kItemSlots, (mi + 1) * 32 / kItemSlots)
+            // steps [mi * kSteps / kItemSlots, (mi + 1) * kSteps / kItemSlots); a quarter of them per pair block
 #pragma unroll
-            for (int e2 = mi * 32 / kItemSlots; e2 < (mi + 1) * 32 / kItemSlots; ++e2) {
-              const int pb = e2 >> 3;
-              if ((e2 & 7) == 0 && pb + 1 < 4) {                // the next pair block's angles
+            for (int e2 = mi * kSteps / kItemSlots; e2 < (mi + 1) * kSteps / kItemSlots; ++e2) {
+              const int pb = e2 / (kSteps / 4);
+              if (e2 % (kSteps / 4) == 0 && pb + 1 < 4) {       // the next pair block's angles
                 csr[(pb + 1) & 1][0] = angle_piece(cst, pb + 1, 4 * ptt);
                 csr[(pb + 1) & 1][1] = angle_piece(cst, pb + 1, 8 + 4 * ptt);
               }
-              half_item(acc[ptt], part, e2, csr[pb & 1][0], csr[pb & 1][1]);
+              if constexpr (NQ == 1) half_item(acc[ptt], part[0], e2, csr[pb & 1][0], csr[pb & 1][1]);
+              else pair_step(acc[ptt], part, rot, e2, csr[pb & 1][0], csr[pb & 1][1]);
             }
-          } else if (mi >= kSumSlot0 && mi < kSumSlot0 + 4) {
-            row_sum_step(rs, part, mi - kSumSlot0);
-          } else if (mi == kSumSlot0 + 4) {
-            out_row[ptile * kTile + 16 * ptt + tok_of_lane] = rs.v;
+          } else if (mi >= kSumSlot0) {
+            const int i = (mi - kSumSlot0) / 5, x = (mi - kSumSlot0) % 5;      // query, step
+            if (x < 4) row_sum_step(rs, part[i], x);
+            else out_row[(size_t)i * a.lpad + ptile * kTile + 16 * ptt + tok_of_lane] = rs.v;
           }
         }
         if (tt == 1 && ks >= kHandK) {

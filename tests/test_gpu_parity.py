@@ -316,9 +316,9 @@ def test_random_layers_int4(seed):
 def test_grouped_query_attention(qpk, theta, dtype):
     """Grouped-query attention (the Llama-3 / Mistral models of Sec. 4.1): the latents and
     B matrices cover the key/value heads, q_per_kv query heads share each of them.  Groups
-    of unequal size and rank, ragged lengths, with and without RoPE.  With fp16 latents,
-    RoPE and up to 16 query heads per key/value head the score kernel rebuilds each key once
-    for the heads that share it; the other cases (bf16) run one folded matrix per query head."""
+    of unequal size and rank, ragged lengths, with and without RoPE.  The ranks here (64 .. 256 in
+    one layer) keep the score kernel on one query head per wavefront; test_shared_keys_exact_form
+    covers the layers whose keys are rebuilt once for the heads that share them."""
     n_kv = 8 if qpk <= 4 else 4
     sizes = [4, 2, 1, 1] if n_kv == 8 else [2, 1, 1]
     head_off = [0] + list(np.cumsum(sizes))
@@ -333,6 +333,30 @@ def test_grouped_query_attention(qpk, theta, dtype):
         case.k_pos = np.sort(np.random.default_rng(qpk).choice(4096, size=300, replace=False)).astype(np.int32)
         case.q_pos = np.array([4100, 2000], np.int32)
     case.name = f"gqa q_per_kv={qpk} kv_heads={n_kv} groups={sizes} theta={theta}"
+    check(case, TOL_FP)
+
+
+@pytest.mark.parametrize("rank,qpk,sizes,dtype,scale", [(256, 4, [4, 4], "f16", 8.0), (256, 8, [2, 4, 2], "f16", 1.0),
+                                                        (192, 8, [4], "bf16", 4.0), (224, 2, [4, 3, 2], "f16", 12.0),
+                                                        (160, 4, [2, 2], "f16", 1.0), (128, 2, [4, 4, 1], "bf16", 8.0)])
+def test_shared_keys_exact_form(rank, qpk, sizes, dtype, scale):
+    """Layers whose key ranks are all 128 .. 256 with 2, 4 or 8 query heads per key/value head: the score kernel
+    rebuilds and rotates each key once in float32 for the queries that share it.  Same tolerance as one query per
+    head, also at the large logits of scaled queries; ragged lengths, gathered positions in one case."""
+    n_kv = sum(sizes)
+    head_off = [0] + list(np.cumsum(sizes))
+    kr = [rank] * len(sizes)
+    vr = [128 if s == 1 else 192 for s in sizes]
+    layer = synth.Layer(n_kv, 128, head_off, [0] + list(np.cumsum(kr)), [0] + list(np.cumsum(vr)), rope_theta=500000.0,
+                        q_per_kv=qpk)
+    case = synth.make_case_orthonormal(layer, 2, 333, seed=700 + rank + qpk, dtype=dtype)
+    case.q = synth.round_to(case.q * scale, dtype)
+    case.seq_lens = np.array([333, 150], np.int32)
+    case.q_pos = np.array([340, 149], np.int32)
+    if qpk == 4:
+        case.k_pos = np.sort(np.random.default_rng(rank).choice(5000, size=333, replace=False)).astype(np.int32)
+        case.q_pos = np.array([5001, 3000], np.int32)
+    case.name = f"shared keys rank={rank} q_per_kv={qpk} groups={sizes} {dtype} q x{scale:g}"
     check(case, TOL_FP)
 
 
