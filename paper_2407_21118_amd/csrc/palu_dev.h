@@ -94,6 +94,46 @@ __device__ __forceinline__ NibblePairs nibbles_to_fp16_pairs(uint32_t w, uint32_
   return r;
 }
 
+// Dequantization of the 8 codes of a 32-bit word (code u in bits 4u .. 4u+3) to fp16, (c - z) * scale with one
+// rounding, in channel order.  Packed form: a code c in the low mantissa bits of 0x6400 is the fp16 number 1024 + c;
+// with an integer zero-point |z| <= 1000 the difference (1024 + c) - (1024 + z) is the exact integer c - z, and its
+// fp16 product with the scale is rounded once: the same number as ((float)c - z) * scale rounded to fp16.  Codes u and
+// u + 4 are 16 bits apart, i.e. in the two halves of one register: one shift and one masked merge per pair, two
+// packed operations, then four byte permutes back to channel order.  k1024 = per_lane_constant(0x64006400).
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bool zero_point_is_small_integer(uint16_t z16) {
+  const float zf = F16::to_float(z16);
+  return fabsf(zf) <= 1000.f && zf == rintf(zf);
+}
+__device__ __forceinline__ uint4v dequant8_packed(uint32_t w, uint16_t s16, uint16_t z16, uint32_t k1024) {
+  constexpr uint32_t kNib = 0x000f000fu;
+  const uint32_t zz = (uint32_t)z16 | ((uint32_t)z16 << 16), ss = (uint32_t)s16 | ((uint32_t)s16 << 16);
+  const half2v zc = __builtin_bit_cast(half2v, zz) + __builtin_bit_cast(half2v, (uint32_t)0x64006400u);     // 1024 + z, exact
+  const half2v sc = __builtin_bit_cast(half2v, ss);
+  uint32_t p[4];                                              // pair u: channels u and u + 4
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const uint32_t c = ((w >> (4 * u)) & kNib) | k1024;       // (1024 + c_u, 1024 + c_{u+4})
+    const half2v d = (__builtin_bit_cast(half2v, c) - zc) * sc;
+    p[u] = __builtin_bit_cast(uint32_t, d);
+  }
+  uint4v out;                                                 // perm: selector bytes 0-3 pick from the second operand
+  out.x = __builtin_amdgcn_perm(p[1], p[0], 0x05040100u);     // channels 0, 1
+  out.y = __builtin_amdgcn_perm(p[3], p[2], 0x05040100u);     // 2, 3
+  out.z = __builtin_amdgcn_perm(p[1], p[0], 0x07060302u);     // 4, 5
+  out.w = __builtin_amdgcn_perm(p[3], p[2], 0x07060302u);     // 6, 7
+  return out;
+}
+__device__ __forceinline__ uint4v dequant8_float(uint32_t w, uint16_t s16, uint16_t z16) {
+  const float sc = F16::to_float(s16), zf = F16::to_float(z16);
+  auto pair = [&](int e) __attribute__((always_inline)) {
+    const float lo = ((float)((w >> (8 * e)) & 15u) - zf) * sc;
+    const float hi = ((float)((w >> (8 * e + 4)) & 15u) - zf) * sc;
+    return (uint32_t)F16::from_float(lo) | ((uint32_t)F16::from_float(hi) << 16);
+  };
+  return uint4v{pair(0), pair(1), pair(2), pair(3)};
+}
+
 // 2- and 3-bit latents (the low-bit settings of Sec. 4.4): eight channels' codes, stored as 16 bits of
 // two-bit fields (channel u in bits 2u, 2u+1) and, for 3 bits, 8 third bits (channel u in bit u), spread
 // into the 4-bit layout the kernels work on (channel u in bits 4u .. 4u+3).

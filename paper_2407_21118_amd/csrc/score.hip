@@ -315,6 +315,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   };
 
   // =========================== staging through registers (bf16, int4) ===========================
+  const uint32_t k1024 = per_lane_constant(0x64006400u);
   int st_row[kPass], st_col[kPass];
 #pragma unroll
   for (int p = 0; p < kPass; ++p) {
@@ -366,21 +367,33 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
         *reinterpret_cast<uint4v*>(cb + f * 256 + ((piece ^ (f & 15)) * 16)) = s.cs[x];
       }
     }
+    // quantized latents: (code - zero) * scale, one rounding to fp16.  With integer zero-points of magnitude up to
+    // 1000 (what the quantizer produces for latents that are not far off centre) the packed fp16 form gives the same
+    // numbers in half the operations; the whole wavefront takes the float32 form for a tile in which any of its
+    // zero-points is something else (a uniform branch around two straight-line bodies).
+    bool packed = I4;
+    if constexpr (I4) {
 #pragma unroll
-    for (int p = 0; p < kPass; ++p) {
-      uint4v v = s.h[p];
-      if (I4) {            // dequantize: (code - zero) * scale in float32, one rounding to fp16
-        const uint32_t codes = !LB ? v.x : expand_low_bits(v.x, v.z, bits == 3);
-        const float sc = F16::to_float((uint16_t)(v.y & 0xffffu));
-        const float z = F16::to_float((uint16_t)(v.y >> 16));
+      for (int p = 0; p < kPass; ++p) packed = packed && zero_point_is_small_integer((uint16_t)(s.h[p].y >> 16));
+      packed = __builtin_amdgcn_ballot_w64(!packed) == 0;
+    }
+    if (packed) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float lo = ((float)((codes >> (8 * e)) & 15u) - z) * sc;
-          const float hi = ((float)((codes >> (8 * e + 4)) & 15u) - z) * sc;
-          v[e] = (uint32_t)F16::from_float(lo) | ((uint32_t)F16::from_float(hi) << 16);
-        }
+      for (int p = 0; p < kPass; ++p) {
+        const uint32_t codes = !LB ? s.h[p].x : expand_low_bits(s.h[p].x, s.h[p].z, bits == 3);
+        const uint4v v = dequant8_packed(codes, (uint16_t)(s.h[p].y & 0xffffu), (uint16_t)(s.h[p].y >> 16), k1024);
+        if (p * kThreads + tid < kChunks) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + st_col[p] * 16) = v;
       }
-      if (p * kThreads + tid < kChunks) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + st_col[p] * 16) = v;
+    } else {
+#pragma unroll
+      for (int p = 0; p < kPass; ++p) {
+        uint4v v = s.h[p];
+        if (I4) {
+          const uint32_t codes = !LB ? v.x : expand_low_bits(v.x, v.z, bits == 3);
+          v = dequant8_float(codes, (uint16_t)(v.y & 0xffffu), (uint16_t)(v.y >> 16));
+        }
+        if (p * kThreads + tid < kChunks) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + st_col[p] * 16) = v;
+      }
     }
   };
 

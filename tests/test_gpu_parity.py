@@ -291,6 +291,19 @@ def test_random_layers_and_lengths(seed):
     check(case, TOL_FP)
 
 
+@pytest.mark.parametrize("bits", [4, 3])
+def test_quantized_keys_far_off_centre(bits):
+    """Key latents with a large common offset and a small spread: zero-points in the thousands, outside the range in
+    which the score kernel dequantizes in packed fp16 arithmetic; it must take its float32 form and still agree."""
+    layer = synth.uniform_layer(8, 4, 256)
+    case = synth.make_case_orthonormal(layer, 2, 150, seed=41)
+    case.Hk = synth.round_to(0.01 * case.Hk + 12.0, "f16")
+    case.name = f"far-off-centre keys, {bits} bits"
+    quant = {"k": O.quant_latent(case.Hk, bits=bits), "v": O.quant_latent(case.Hv, bits=bits)}
+    assert np.abs(np.asarray(quant["k"][2], np.float32)).max() > 1000.0
+    check(case, TOL_I4, k_i4=True, v_i4=False, quant=quant, bits=bits)
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])
 def test_random_layers_int4(seed):
     """Random layers whose ranks are multiples of the 128-channel quantization block,
