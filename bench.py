@@ -103,6 +103,67 @@ def prompt_encode(args, P, torch) -> int:
     return 0
 
 
+def multi_query_decode(args, P, torch) -> int:
+    """palu_attn_decode_multi: N query tokens per sequence (a speculative-decoding check, a chunk of a prompt)
+    over the cache of the chosen configuration; attention only, timed with events around `steps` calls."""
+    import numpy as np
+    from workloads import device as wd, synth
+    cfg = args.config
+    layer = synth.config_layer(cfg.split("-")[0])
+    batch, seq = synth.FULL_SIZES[cfg]
+    n_q = args.query_tokens
+    case = wd.make_device_case(cfg, seed=0, dtype="f16", n_sets=2, layer=layer)
+    desc = P.LayerDesc(layer.n_heads, layer.d_head, layer.group_head_off, layer.k_rank_off, layer.v_rank_off,
+                       P.PALU_F16, P.PALU_F16, P.PALU_F16, layer.quant_block, layer.rope_theta, layer.q_per_kv)
+    table = P.palu_rope_table_init(layer.rope_theta, layer.d_head, seq)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    q = torch.randn((batch, n_q, layer.n_q_heads, layer.d_head), generator=g, device="cuda").half()
+    rows = seq - n_q + 1 + torch.arange(n_q, dtype=torch.int32, device="cuda")          # a causal block over the last n_q rows
+    q_len = rows[None].expand(batch, n_q).contiguous()
+    q_pos = (q_len - 1).contiguous()
+    out = torch.empty((batch, n_q, layer.n_q_heads, layer.d_head), dtype=torch.float32, device="cuda")
+    lib = P.load_library()
+    import ctypes
+    nbytes = ctypes.c_size_t(0)
+    if lib.palu_attn_decode_multi_workspace_bytes(desc.ref(), batch, n_q, seq, ctypes.byref(nbytes)) != 0:
+        print("unsupported configuration", file=sys.stderr)
+        return 2
+    ws = torch.empty(int(nbytes.value), dtype=torch.uint8, device="cuda")
+
+    def call(i):
+        s = i % 2
+        P.palu_attn_decode_multi(desc, batch, n_q, seq, seq, q, q_pos, case.Hk[s], case.Hv[s], case.Bk, case.Bv, table, seq,
+                                 q_len=q_len, out=out, workspace=ws)
+    for i in range(args.warmup):
+        call(i)
+    torch.cuda.synchronize()
+    kGroup, n_groups = 5, max(20, -(-args.steps // 5))
+    gev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_groups)]
+    it = 0
+    for a, b in gev:
+        a.record()
+        for _ in range(kGroup):
+            call(it)
+            it += 1
+        b.record()
+    torch.cuda.synchronize()
+    us = np.array([a.elapsed_time(b) for a, b in gev]) * 1e3 / kGroup
+    flops = 2.0 * batch * seq * 128 * sum((layer.k_rank_off[j + 1] - layer.k_rank_off[j]) *
+                                          (layer.group_head_off[j + 1] - layer.group_head_off[j]) for j in range(layer.n_groups))
+    med = float(np.median(us))
+    print(json.dumps({"metric": "decode_attn_multi_us_per_call", "value": med, "unit": "us/call", "n_gpus": 1,
+                      "steps": n_groups * kGroup, "warmup": args.warmup, "ms_per_step": med * 1e-3, "higher_is_better": False,
+                      "step_us_median": med, "step_us_min": float(np.min(us)), "dtype": "f16", "data": "synthetic",
+                      "config": {"workload": f"config {cfg}: {n_q} query tokens per sequence over batch {batch}, seq {seq} "
+                                             f"(palu_attn_decode_multi, attention only)"},
+                      "us_per_query_token": med / n_q,
+                      "roofline": {"bound": "mfma", "note": "key reconstruction FLOPs of ONE pass over the cache (shared by the query tokens)",
+                                   "achieved": flops / (med * 1e-6) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": flops / (med * 1e-6) / 1e12 / MFMA_F16_PEAK_TFLOPS, "traffic": None}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,6 +190,8 @@ def main() -> int:
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="after the timed region also run a plain device copy of this size three times: "
                          "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--query-tokens", type=int, default=0, metavar="N",
+                    help="time palu_attn_decode_multi with N query tokens per sequence (attention only) instead of the decode step")
     ap.add_argument("--prompt-tokens", type=int, default=0, metavar="N",
                     help="instead of the decode step, time the projection of an N-token prompt into both latent "
                          "caches (palu_encode_kv on its tiled-GEMM path) and print its own JSON line")
@@ -154,6 +217,8 @@ def main() -> int:
 
     if args.prompt_tokens > 0:
         return prompt_encode(args, P, torch)
+    if args.query_tokens > 0:
+        return multi_query_decode(args, P, torch)
 
     cfg = args.config
     v_only = cfg == "4v"

@@ -502,13 +502,15 @@ ScoreFn score16_fn_t(int rc, int lg) {
   }
 }
 inline bool rank_class_16(int rc) { return rc >= 1 && rc <= 7; }
-// ... and 2, 4 or 8 queries per key/value head: the key rebuilt once per key/value head (ranks 128 .. 256; 8 queries: 192 .. 256)
-inline bool shared16_ok(int rc, int nq) { return rc >= 3 && rc <= 7 && (nq == 2 || nq == 4 || (nq == 8 && rc >= 5)); }
+// ... and several queries per key/value head: the key rebuilt once per key/value head and pass of up to 8 query
+// rows (ranks 192 .. 256) or 4 (ranks 128, 160); the kernel is compiled for 2, 4 and 8 rows
+inline bool shared16_ok(int rc) { return rc >= 3 && rc <= 7; }
+inline int shared16_rows_per_pass(int rc) { return rc >= 5 ? 8 : 4; }
 template <typename T, int NK>
 ScoreFn score16q_fn_n(int nq) {
-  if (nq == 2) return score16_kernel<T, NK, 1, 2>;
-  if (nq == 4) return score16_kernel<T, NK, 1, 4>;
-  if constexpr (NK >= 6) { if (nq == 8) return score16_kernel<T, NK, 1, 8>; }
+  if (nq <= 2) return score16_kernel<T, NK, 1, 2>;
+  if (nq <= 4) return score16_kernel<T, NK, 1, 4>;
+  if constexpr (NK >= 6) { if (nq <= 8) return score16_kernel<T, NK, 1, 8>; }
   return nullptr;
 }
 template <typename T>
@@ -1283,7 +1285,12 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     // ... and with 2, 4 or 8 queries per key/value head and ranks 128 .. 256 one whole key/value head per wavefront:
     // the key is rebuilt and rotated once in float32 for the queries that share it (exact shared-key form)
     bool shared16 = use16 && m.qpk > 1 && g_opt_score_fp8 == 0;
-    for (int j = 0; j < m.n_groups && shared16; ++j) shared16 = shared16_ok(rank_class(m.k_off[j + 1] - m.k_off[j]), m.qpk);
+    int sk_pass_rows = 8;
+    for (int j = 0; j < m.n_groups && shared16; ++j) {
+      const int rcj = rank_class(m.k_off[j + 1] - m.k_off[j]);
+      shared16 = shared16_ok(rcj);
+      if (shared16) sk_pass_rows = std::min(sk_pass_rows, shared16_rows_per_pass(rcj));
+    }
     const bool kv_units = shared_key || shared16;            // the score units are key/value heads
     const Meta mk = kv_units ? kv_head_meta(m) : m;
     used16 = use16;
@@ -1465,10 +1472,39 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         size_t lds = (size_t)score_lds_bytes(width, dma, !shared_key, pingpong);
         const bool k16 = use16 && rank_class_16(rc);
         ScoreFn fn = shared_key ? (m.qpk <= 4 ? score_fn_shared<1>(rc) : score_fn_shared<2>(rc))
-                   : shared16 ? (act == PALU_F16 ? score16q_fn_t<F16>(rc, m.qpk) : score16q_fn_t<BF16>(rc, m.qpk))
+                   : shared16 ? nullptr            // chosen per pass below
                    : k16 ? (act == PALU_F16 ? score16_fn_t<F16>(rc, lg) : score16_fn_t<BF16>(rc, lg))
                    : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, rc * 3 + lg, waves8));
         if (k16) lds = (size_t)score16_lds_bytes(width);
+        if (shared16) {
+          // exact shared-key form: passes of up to sk_pass_rows query rows of every key/value head, each pass one
+          // launch per flush of units (the key tile is rebuilt once per pass)
+          for (int row0 = 0; row0 < m.qpk; row0 += sk_pass_rows) {
+            const int rows = std::min(sk_pass_rows, m.qpk - row0);
+            fn = act == PALU_F16 ? score16q_fn_t<F16>(rc, rows) : score16q_fn_t<BF16>(rc, rows);
+            if (!fn) return PALU_ERR_UNSUPPORTED;
+            if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
+            a.sk_row0 = row0;
+            a.sk_rows = rows;
+            a.mfold = reinterpret_cast<const uint16_t*>(ws + w.mfold);
+            a.units.n_units = 0;
+            auto flush_q = [&]() -> int {
+              if (a.units.n_units == 0) return PALU_OK;
+              set_chunks(a.units.n_units);
+              const dim3 grid((unsigned)a.n_chunks, (unsigned)a.units.n_units, (unsigned)batch);
+              hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, a);
+              a.units.n_units = 0;
+              return launch_ok();
+            };
+            for (int i = 0; i < plan.total_units; ++i) {
+              if (plan.unit_cls[i] != cls) continue;
+              a.units.u[a.units.n_units++] = plan.units[i];
+              if (a.units.n_units == kMaxScoreUnits && (st = flush_q()) != PALU_OK) return st;
+            }
+            if ((st = flush_q()) != PALU_OK) return st;
+          }
+          continue;
+        }
         if (!fn) return PALU_ERR_UNSUPPORTED;
         const bool k8 = k16 && use8 && !sliced;
         if (k8) {

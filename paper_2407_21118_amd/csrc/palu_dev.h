@@ -230,6 +230,7 @@ struct ScoreArgs {
   int n_kv;                  // key/value heads
   const float* w_scale;      // 8-bit weights (score8_kernel): the power-of-two scale of every feature column [heads][128]
   int m_qpk, m_nq;           // one-query form: Meta::qpk and Meta::nq of the call (layout of q, see q_row)
+  int sk_row0, sk_rows;      // exact shared-key form: the query rows of every key/value head this launch takes
   int rope_tile_stride;
   float rev_hi[kHalf];       // theta^(-2f/128) / (2 pi) from the host's float64 value, as a float pair hi + lo
   float rev_lo[kHalf];

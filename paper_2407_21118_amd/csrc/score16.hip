@@ -16,7 +16,8 @@
 // Per 32-token tile and CU this moves 160 KiB through the LDS where the ping-pong schedule moves 225,
 // and issues 0.75 as many vector instructions.
 //
-// Several queries per key/value head (grouped-query layers, several query tokens per sequence; NQ = 2, 4, 8): the
+// Several queries per key/value head (grouped-query layers, several query tokens per sequence; NQ = 2, 4, 8, other
+// counts in passes with idle rows): the
 // wavefront's head is a key/value head; its key tile is rebuilt once, each key pair rotated once in float32 and
 // multiplied by each of the NQ rotated queries (4 + 2 NQ operations per token and pair instead of 6 NQ), then one
 // lane exchange and one score row per query.
@@ -52,8 +53,9 @@ __device__ __forceinline__ float sum_quad_over_row(const float (&p)[4], int lane
 // grid (sequence chunks, units, batch), 256 threads.  a.mfold: B_k^T in the operand order of
 // fold_body's 16-feature layout.
 // NQ: queries that share the wavefront's key/value head (grouped-query layers, several query tokens per sequence):
-//     the unit's heads are then key/value heads, query row hc * NQ + i reads key/value head hc; the key tile is
-//     rebuilt once, rotated once in float32 and multiplied by each rotated query (NQ = 1: the head's own query)
+//     the unit's heads are then key/value heads with a.m_qpk query rows each; this launch takes rows a.sk_row0 ..
+//     + a.sk_rows - 1 (at most NQ) of every key/value head: the key tile is rebuilt once, rotated once in float32
+//     and multiplied by each rotated query (NQ = 1: the head's own query)
 template <typename T, int NK, int G, int NQ = 1>
 __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -175,7 +177,8 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
     mq.n_heads = a.n_heads; mq.qpk = a.m_qpk; mq.nq = a.m_nq;
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
-      const int hq = hc * NQ + i;                               // the query row (NQ = 1: the head itself)
+      // the query row (NQ = 1: the head itself); rows past the launch's share re-read its last row and count as zero
+      const int hq = NQ == 1 ? hc : hc * a.m_qpk + a.sk_row0 + min(i, a.sk_rows - 1);
       const uint16_t* qp = a.q + q_row(mq, b, hq) * kDHead;
       q_position[i] = a.q_pos[b * a.m_nq + q_token(mq, hq)];
 #pragma unroll
@@ -232,8 +235,9 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   };
   auto angle_tile = [&](int tile) __attribute__((always_inline)) { return lds + kCsRing + (size_t)(tile % kBufs) * kRopeTileBytes; };
 
-  // the score row of query row hc * NQ (the others follow, lpad floats apart)
-  float* out_row = a.scores + ((size_t)u.part0 * a.batch + b) * a.n_heads * (size_t)a.lpad + (size_t)hc * NQ * a.lpad + t_begin;
+  // the score row of the wavefront's first query row (the others follow, lpad floats apart)
+  float* out_row = a.scores + ((size_t)u.part0 * a.batch + b) * a.n_heads * (size_t)a.lpad +
+                   (size_t)(NQ == 1 ? hc : hc * a.m_qpk + a.sk_row0) * a.lpad + t_begin;
   const int tok_of_lane = 4 * kq + 2 * ((lane >> 2) & 1) + (lane & 1);      // see sum_quad_over_row
 
   // ---- start-up: tile 0, the query and the weights have landed; tiles 1 .. kAheadTiles-1 stay in flight
@@ -251,8 +255,9 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
       const float pe = fmaf(pos, q_rev[pb][0], -ph);
       const float rev = (ph - floorf(ph)) + (pe + pos * q_rev[pb][1]);          // the angle in revolutions, see score.hip
       const float sn = __builtin_amdgcn_sinf(rev), cn = __builtin_amdgcn_cosf(rev);
-      qa[i][pb] = (x0 * cn - x1 * sn) * a.scale;
-      qb[i][pb] = (x1 * cn + x0 * sn) * a.scale;
+      const float on = (NQ == 1 || i < a.sk_rows) ? a.scale : 0.f;
+      qa[i][pb] = (x0 * cn - x1 * sn) * on;
+      qb[i][pb] = (x1 * cn + x0 * sn) * on;
     }
   }
 
@@ -324,7 +329,10 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
         for (int x = 0; x < 4 * kPairSteps; ++x) pair_step(ac, part, rot, 4 * kPairSteps * pb + x, c, s);
       }
 #pragma unroll
-      for (int i = 0; i < NQ; ++i) out_row[(size_t)i * a.lpad + tile * kTile + 16 * tt + tok_of_lane] = sum_quad_over_row(part[i], lane);
+      for (int i = 0; i < NQ; ++i) {
+        const float v = sum_quad_over_row(part[i], lane);
+        if (i < a.sk_rows) out_row[(size_t)i * a.lpad + tile * kTile + 16 * tt + tok_of_lane] = v;
+      }
     }
   };
 
@@ -400,7 +408,7 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
           } else if (mi >= kSumSlot0) {
             const int i = (mi - kSumSlot0) / 5, x = (mi - kSumSlot0) % 5;      // query, step
             if (x < 4) row_sum_step(rs, part[i], x);
-            else out_row[(size_t)i * a.lpad + ptile * kTile + 16 * ptt + tok_of_lane] = rs.v;
+            else if (NQ == 1 || i < a.sk_rows) out_row[(size_t)i * a.lpad + ptile * kTile + 16 * ptt + tok_of_lane] = rs.v;
           }
         }
         if (tt == 1 && ks >= kHandK) {

@@ -351,11 +351,15 @@ def test_grouped_query_attention(qpk, theta, dtype):
 
 @pytest.mark.parametrize("rank,qpk,sizes,dtype,scale", [(256, 4, [4, 4], "f16", 8.0), (256, 8, [2, 4, 2], "f16", 1.0),
                                                         (192, 8, [4], "bf16", 4.0), (224, 2, [4, 3, 2], "f16", 12.0),
-                                                        (160, 4, [2, 2], "f16", 1.0), (128, 2, [4, 4, 1], "bf16", 8.0)])
+                                                        (160, 4, [2, 2], "f16", 1.0), (128, 2, [4, 4, 1], "bf16", 8.0),
+                                                        (256, 3, [4, 2], "f16", 8.0), (192, 5, [2, 2], "f16", 1.0),
+                                                        (128, 6, [4, 1], "bf16", 1.0), (256, 12, [2, 2], "f16", 4.0),
+                                                        (224, 16, [4], "f16", 1.0), (160, 7, [2], "f16", 12.0)])
 def test_shared_keys_exact_form(rank, qpk, sizes, dtype, scale):
-    """Layers whose key ranks are all 128 .. 256 with 2, 4 or 8 query heads per key/value head: the score kernel
-    rebuilds and rotates each key once in float32 for the queries that share it.  Same tolerance as one query per
-    head, also at the large logits of scaled queries; ragged lengths, gathered positions in one case."""
+    """Layers whose key ranks are all 128 .. 256 with several query heads per key/value head: the score kernel
+    rebuilds and rotates each key once in float32 for the queries that share it (in passes of up to 8 query rows, 4
+    at ranks below 192; a pass of 3 or 5 .. 7 rows runs the 4- or 8-row kernel with idle rows).  Same tolerance as one
+    query per head, also at the large logits of scaled queries; ragged lengths, gathered positions in one case."""
     n_kv = sum(sizes)
     head_off = [0] + list(np.cumsum(sizes))
     kr = [rank] * len(sizes)
