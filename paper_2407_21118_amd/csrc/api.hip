@@ -1287,9 +1287,15 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     bool shared16 = use16 && m.qpk > 1 && g_opt_score_fp8 == 0;
     int sk_pass_rows = 8;
     for (int j = 0; j < m.n_groups && shared16; ++j) {
-      const int rcj = rank_class(m.k_off[j + 1] - m.k_off[j]);
-      shared16 = shared16_ok(rcj);
-      if (shared16) sk_pass_rows = std::min(sk_pass_rows, shared16_rows_per_pass(rcj));
+      const int r = m.k_off[j + 1] - m.k_off[j];
+      // ranks 288 .. 512 run as two slices of 128 .. 256 rows (plan_score), each a unit of its own rank class
+      const int r0 = (r > 256 && r <= 512 && split16) ? (r + 63) / 64 * 32 : r;
+      for (int rs : {r0, r - r0}) {
+        if (rs == 0) continue;
+        const int rcj = rank_class(rs);
+        shared16 = shared16 && shared16_ok(rcj);
+        if (shared16) sk_pass_rows = std::min(sk_pass_rows, shared16_rows_per_pass(rcj));
+      }
     }
     const bool kv_units = shared_key || shared16;            // the score units are key/value heads
     const Meta mk = kv_units ? kv_head_meta(m) : m;
@@ -1303,7 +1309,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         if (sp.cls_id[sp.unit_cls[i]] == kSlicedCls) sp.units[i].part0 /= 2;
     }
     static thread_local ScorePlan spk;                 // units over key/value heads (shared-key form only)
-    if (kv_units && (st = plan_score(mk, &spk, false)) != PALU_OK) return st;
+    if (kv_units && (st = plan_score(mk, &spk, false, shared16 && split16)) != PALU_OK) return st;
     const ScorePlan& plan = kv_units ? spk : sp;
 
     // 1. B_k in the score kernel's operand order (shared-key form: and the rotated queries beside it)

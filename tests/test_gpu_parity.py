@@ -354,9 +354,11 @@ def test_grouped_query_attention(qpk, theta, dtype):
                                                         (160, 4, [2, 2], "f16", 1.0), (128, 2, [4, 4, 1], "bf16", 8.0),
                                                         (256, 3, [4, 2], "f16", 8.0), (192, 5, [2, 2], "f16", 1.0),
                                                         (128, 6, [4, 1], "bf16", 1.0), (256, 12, [2, 2], "f16", 4.0),
-                                                        (224, 16, [4], "f16", 1.0), (160, 7, [2], "f16", 12.0)])
+                                                        (224, 16, [4], "f16", 1.0), (160, 7, [2], "f16", 12.0),
+                                                        (384, 4, [4, 3], "f16", 8.0), (512, 2, [4], "bf16", 1.0),
+                                                        (288, 3, [3, 4], "f16", 4.0)])
 def test_shared_keys_exact_form(rank, qpk, sizes, dtype, scale):
-    """Layers whose key ranks are all 128 .. 256 with several query heads per key/value head: the score kernel
+    """Layers whose key ranks are all 128 .. 512 (above 256: two slices) with several query heads per key/value head: the score kernel
     rebuilds and rotates each key once in float32 for the queries that share it (in passes of up to 8 query rows, 4
     at ranks below 192; a pass of 3 or 5 .. 7 rows runs the 4- or 8-row kernel with idle rows).  Same tolerance as one
     query per head, also at the large logits of scaled queries; ragged lengths, gathered positions in one case."""
