@@ -503,8 +503,8 @@ ScoreFn score16_fn_t(int rc, int lg) {
 }
 inline bool rank_class_16(int rc) { return rc >= 1 && rc <= 7; }
 // ... and several queries per key/value head: the key rebuilt once per key/value head and pass of up to 8 query
-// rows (ranks 192 .. 256) or 4 (ranks 128, 160); the kernel is compiled for 2, 4 and 8 rows
-inline bool shared16_ok(int rc) { return rc >= 3 && rc <= 7; }
+// rows (ranks 192 .. 256) or 4 (ranks 64 .. 160); the kernel is compiled for 2, 4 and 8 rows
+inline bool shared16_ok(int rc) { return rc >= 1 && rc <= 7; }
 inline int shared16_rows_per_pass(int rc) { return rc >= 5 ? 8 : 4; }
 template <typename T, int NK>
 ScoreFn score16q_fn_n(int nq) {
@@ -516,6 +516,8 @@ ScoreFn score16q_fn_n(int nq) {
 template <typename T>
 ScoreFn score16q_fn_t(int rc, int nq) {
   switch (rc) {
+    case 1: return score16q_fn_n<T, 2>(nq);
+    case 2: return score16q_fn_n<T, 3>(nq);
     case 3: return score16q_fn_n<T, 4>(nq);
     case 4: return score16q_fn_n<T, 5>(nq);
     case 5: return score16q_fn_n<T, 6>(nq);

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   constexpr int kRank = NK * 32;
   constexpr int kWidth = G * kRank;
   static_assert(kWidth <= 512 && NK >= 2 && NK <= 8, "latent tile row too wide / rank outside 64 .. 256");
-  static_assert(NQ == 1 || (G == 1 && NK * 8 >= 5 * NQ + 8), "shared keys: one group per workgroup, room for the queries' lane exchanges");
+  static_assert(NQ == 1 || G == 1, "shared keys: one group per workgroup");
   constexpr int kCpr = kWidth / 8;                              // 16-byte chunks per tile row
   constexpr int kRowB = kWidth * 2 + kRowPad;
   constexpr int kTileB = kTile * kRowB;
@@ -342,7 +342,9 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   // last quarter; in the second sub-tile of a tile also the tile hand-over: wait for this wavefront's share of tile
   // k+1, one barrier, request tile k + kAheadTiles into the buffers tile k-1 occupied (every reader of tile k-1, its
   // last sub-tile's items included, is past that barrier).
-  constexpr int kSumSlot0 = kMfmas - 5 * NQ;                    // per query: four lane-exchange steps and the store
+  constexpr int kTail = 5 * NQ;                                 // per query: four lane-exchange steps and the store ...
+  constexpr int kSumSlot0 = kMfmas - kTail >= kMfmas / 2 ? kMfmas - kTail : kMfmas / 2;   // ... one per slot where the slots suffice
+  constexpr int kTailSlots = kMfmas - kSumSlot0;
   constexpr int kItemSlots = kMfmas * 3 / 4 < kSumSlot0 ? kMfmas * 3 / 4 : kSumSlot0;
   constexpr int kSteps = NQ == 1 ? 32 : 16 * kPairSteps;        // half-items, or steps of the shared-key pairs, per sub-tile
   static_assert(kItemSlots <= kSumSlot0, "the lane exchange follows the last half-item");
@@ -406,9 +408,12 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
               else pair_step(acc[ptt], part, rot, e2, csr[pb & 1][0], csr[pb & 1][1]);
             }
           } else if (mi >= kSumSlot0) {
-            const int i = (mi - kSumSlot0) / 5, x = (mi - kSumSlot0) % 5;      // query, step
-            if (x < 4) row_sum_step(rs, part[i], x);
-            else if (NQ == 1 || i < a.sk_rows) out_row[(size_t)i * a.lpad + ptile * kTile + 16 * ptt + tok_of_lane] = rs.v;
+#pragma unroll
+            for (int ts = (mi - kSumSlot0) * kTail / kTailSlots; ts < (mi - kSumSlot0 + 1) * kTail / kTailSlots; ++ts) {
+              const int i = ts / 5, x = ts % 5;                                // query, step
+              if (x < 4) row_sum_step(rs, part[i], x);
+              else if (NQ == 1 || i < a.sk_rows) out_row[(size_t)i * a.lpad + ptile * kTile + 16 * ptt + tok_of_lane] = rs.v;
+            }
           }
         }
         if (tt == 1 && ks >= kHandK) {

@@ -329,9 +329,8 @@ def test_random_layers_int4(seed):
 def test_grouped_query_attention(qpk, theta, dtype):
     """Grouped-query attention (the Llama-3 / Mistral models of Sec. 4.1): the latents and
     B matrices cover the key/value heads, q_per_kv query heads share each of them.  Groups
-    of unequal size and rank, ragged lengths, with and without RoPE.  The ranks here (64 .. 256 in
-    one layer) keep the score kernel on one query head per wavefront; test_shared_keys_exact_form
-    covers the layers whose keys are rebuilt once for the heads that share them."""
+    of unequal size and rank (64 .. 256 in one layer), ragged lengths, with and without RoPE; with RoPE
+    each key is rebuilt once for the query heads that share it (2 .. 12 of them: passes of 4 rows)."""
     n_kv = 8 if qpk <= 4 else 4
     sizes = [4, 2, 1, 1] if n_kv == 8 else [2, 1, 1]
     head_off = [0] + list(np.cumsum(sizes))
