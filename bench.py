@@ -375,6 +375,7 @@ def main() -> int:
     torch.cuda.synchronize()
     whole_us = float(np.mean([a.elapsed_time(b) for a, b in dec]) * 1e3)
     gap_us = max(0.0, (sum(bracket_us.values()) - whole_us) / (P.PALU_DECODE_STAGES - 1))
+    gap_us = min(gap_us, min(bracket_us.values()))         # no stage is shorter than nothing (a near-empty first stage)
     stage_us = {n: bracket_us[n] - gap_us for n in names}
     stage_us_med = {n: float(np.median(stage_ms[:, k]) * 1e3) - gap_us for k, n in enumerate(names)}
     log(f"[bench] stage brackets us: {bracket_us}; whole decode call {whole_us:.2f} us; marker gap {gap_us:.2f} us")
