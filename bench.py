@@ -169,7 +169,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="2", help="workload: 1, 2 (7B shape, seq 16K, headline), 2-4k, 2-64k, 3, 4, 4v, 5a, 5b, "
+    ap.add_argument("--config", default="2", help="workload: 1, 2 (7B shape, seq 16K, headline), 2-4k, 2-64k, 3, 4, 4v, gqa4, 5a, 5b, "
                          "2p / 2p-64k (the paper's latency allocation: K rank 128, V rank 384 per group), "
                          "gqa / gqa-64k (32 query heads on 8 key/value heads, the Llama-3-8B / Mistral-7B shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -222,9 +222,10 @@ def main() -> int:
 
     cfg = args.config
     v_only = cfg == "4v"
-    base_cfg = "4" if v_only else cfg
-    k_i4 = base_cfg == "4" and not v_only
-    v_i4 = base_cfg == "4"
+    gqa4 = cfg == "gqa4"                          # the grouped-query layer with quantized key and value latents
+    base_cfg = "4" if v_only else ("gqa" if gqa4 else cfg)
+    k_i4 = (base_cfg == "4" and not v_only) or gqa4
+    v_i4 = base_cfg == "4" or gqa4
 
     # ---- inputs -----------------------------------------------------------
     t0 = time.time()

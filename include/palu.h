@@ -115,7 +115,7 @@ int palu_version(void);
  *                         than the default, but the logit error is about 4e-4 of the logit (output error 2e-3
  *                         reached at logits of about +-25).  Default 0: keys are rebuilt and rotated in float32,
  *                         once per key/value head and pass of up to 8 of its queries where every key rank of
- *                         the layer is 64 .. 512, else once per query head.
+ *                         the layer is 64 .. 512 (4-bit keys: 128 or 256), else once per query head.
  *   "encode_tile_rows"    token rows per workgroup of the prompt-sized projection (64, 128 or 256, each
  *                         with 256 columns; 32 selects the narrow tile of 64 rows x 128 columns)
  * Unknown names and out-of-range values return PALU_ERR_INVALID_ARG.  Set

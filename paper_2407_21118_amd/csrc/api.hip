@@ -513,6 +513,13 @@ ScoreFn score16q_fn_n(int nq) {
   if constexpr (NK >= 6) { if (nq <= 8) return score16_kernel<T, NK, 1, 8>; }
   return nullptr;
 }
+// 4-bit key latents (ranks 128 and 256: whole quantization blocks) with several queries per key/value head
+ScoreFn score16q4_fn(int rc, int nq) {
+  if (rc == 3) return nq <= 2 ? score16_kernel<F16, 4, 1, 2, 4> : (nq <= 4 ? score16_kernel<F16, 4, 1, 4, 4> : nullptr);
+  if (rc == 7) return nq <= 2 ? score16_kernel<F16, 8, 1, 2, 4> : (nq <= 4 ? score16_kernel<F16, 8, 1, 4, 4> : score16_kernel<F16, 8, 1, 8, 4>);
+  return nullptr;
+}
+constexpr int score16q4_lds_bytes(int width) { return 3 * score_tile_bytes(width) + 3 * kRopeTileBytes; }
 template <typename T>
 ScoreFn score16q_fn_t(int rc, int nq) {
   switch (rc) {
@@ -1147,7 +1154,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       if (!stage_events[i]) return PALU_ERR_INVALID_ARG;
 
   bool enc_pending = enc != nullptr;
-  bool used16 = false;
+  bool used16 = false, used4 = false;
   if (enc_pending && enc->gemm) {
     if ((st = launch_encode(act, *enc, s)) != PALU_OK) return st;
     enc_pending = false;
@@ -1299,7 +1306,16 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         if (shared16) sk_pass_rows = std::min(sk_pass_rows, shared16_rows_per_pass(rcj));
       }
     }
-    const bool kv_units = shared_key || shared16;            // the score units are key/value heads
+    // the same with 4-bit keys (blocks of 128 channels, ranks 128 and 256): their tiles are dequantized once per pass
+    // for the queries that share them
+    bool shared4 = !shared_key && k_bits == 4 && quant_block == 128 && m.qpk > 1 && g_opt_score_waves == 0;
+    for (int j = 0; j < m.n_groups && shared4; ++j) {
+      const int r = m.k_off[j + 1] - m.k_off[j];
+      shared4 = r == 128 || r == 256;
+      if (shared4) sk_pass_rows = std::min(sk_pass_rows, r == 256 ? 8 : 4);
+    }
+    used4 = shared4;
+    const bool kv_units = shared_key || shared16 || shared4;   // the score units are key/value heads
     const Meta mk = kv_units ? kv_head_meta(m) : m;
     used16 = use16;
     // option score_fp8: those heads rebuild their keys from E4M3-rounded latents and weights (fp16 layers)
@@ -1326,7 +1342,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         fa.rev_lo[f] = (float)(rev - (double)fa.rev_hi[f]);
       }
       fa.meta = mk;
-      fa.layout16 = use16 ? (split16 ? 2 : 1) : 0;
+      fa.layout16 = use16 ? (split16 ? 2 : 1) : (shared4 ? 1 : 0);
       int max_r = 0;
       for (int j = 0; j < m.n_groups; ++j) max_r = std::max(max_r, m.k_off[j + 1] - m.k_off[j]);
       const dim3 g((unsigned)(max_r / 16), (unsigned)mk.n_heads, 1u);
@@ -1484,12 +1500,14 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
                    : k16 ? (act == PALU_F16 ? score16_fn_t<F16>(rc, lg) : score16_fn_t<BF16>(rc, lg))
                    : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, rc * 3 + lg, waves8));
         if (k16) lds = (size_t)score16_lds_bytes(width);
-        if (shared16) {
+        if (shared16 || shared4) {
+          if (shared4) lds = (size_t)score16q4_lds_bytes(width);
           // exact shared-key form: passes of up to sk_pass_rows query rows of every key/value head, each pass one
           // launch per flush of units (the key tile is rebuilt once per pass)
           for (int row0 = 0; row0 < m.qpk; row0 += sk_pass_rows) {
             const int rows = std::min(sk_pass_rows, m.qpk - row0);
-            fn = act == PALU_F16 ? score16q_fn_t<F16>(rc, rows) : score16q_fn_t<BF16>(rc, rows);
+            fn = shared4 ? score16q4_fn(rc, rows)
+                         : (act == PALU_F16 ? score16q_fn_t<F16>(rc, rows) : score16q_fn_t<BF16>(rc, rows));
             if (!fn) return PALU_ERR_UNSUPPORTED;
             if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
             a.sk_row0 = row0;
@@ -1550,7 +1568,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   for (int h = 0; h < m.n_heads; ++h) {      // half-head wavefronts write two planes per rank slice
     const int rk = m.k_off[m.group_of_head[h] + 1] - m.k_off[m.group_of_head[h]];
     // one wavefront per head: one plane (per rank slice)
-    const bool whole = used16 && (split16 ? rk >= 64 : (rank_class_16(rank_class(rk)) || rk > 512));
+    const bool whole = used4 || (used16 && (split16 ? rk >= 64 : (rank_class_16(rank_class(rk)) || rk > 512)));
     n_parts[h] = no_rope ? (uint8_t)1 : (uint8_t)(((waves8 || sp.half_heads[h]) && !whole) ? 2 * sp.slices[h] : sp.slices[h]);
     max_parts = std::max(max_parts, (int)n_parts[h]);
   }

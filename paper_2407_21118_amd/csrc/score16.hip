@@ -56,10 +56,17 @@ __device__ __forceinline__ float sum_quad_over_row(const float (&p)[4], int lane
 //     the unit's heads are then key/value heads with a.m_qpk query rows each; this launch takes rows a.sk_row0 ..
 //     + a.sk_rows - 1 (at most NQ) of every key/value head: the key tile is rebuilt once, rotated once in float32
 //     and multiplied by each rotated query (NQ = 1: the head's own query)
-template <typename T, int NK, int G, int NQ = 1>
+// QB: 4: the key latents are 4-bit codes (Sec. 3.4, Appendix A; fp16 layers).  Their tiles then go through registers:
+//     codes, scales and zero-points are requested a tile ahead, dequantized to fp16 at the tile hand-over ((code -
+//     zero) * scale, one rounding; see dequant8_packed) and written to LDS in the layout the matrix instructions
+//     read; only the angle tiles stay LDS-direct.  The hand-over's vector work is not hidden by matrix instructions,
+//     which is why this form is used where several queries share the key tile (NQ > 1) and score_kernel elsewhere.
+template <typename T, int NK, int G, int NQ = 1, int QB = 0>
 __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   using Vec = typename T::vec8;
+  constexpr bool kStaged = QB != 0;
+  static_assert(QB == 0 || (QB == 4 && __is_same(T, F16)), "quantized keys: 4-bit codes dequantized to fp16");
   constexpr int kRank = NK * 32;
   constexpr int kWidth = G * kRank;
   static_assert(kWidth <= 512 && NK >= 2 && NK <= 8, "latent tile row too wide / rank outside 64 .. 256");
@@ -67,14 +74,15 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   constexpr int kCpr = kWidth / 8;                              // 16-byte chunks per tile row
   constexpr int kRowB = kWidth * 2 + kRowPad;
   constexpr int kTileB = kTile * kRowB;
-  constexpr int kBufs = score_num_bufs(kWidth, true, true, false);
+  // staged tiles: three buffers (tile k+1 is written while stragglers may still read tile k-1)
+  constexpr int kBufs = kStaged ? 3 : score_num_bufs(kWidth, true, true, false);
   constexpr int kCsRing = kBufs * kTileB;                       // the angle tiles' ring behind the latent ring, kBufs tiles too
   constexpr int kAheadTiles = kBufs - 1;
   static_assert(kBufs >= 3, "the schedule keeps at least one tile in flight beyond the next");
-  constexpr bool kPair = kCpr == 32;                            // rows of 512 bytes are requested two per instruction (see score.hip)
+  constexpr bool kPair = !kStaged && kCpr == 32;                // rows of 512 bytes are requested two per instruction (see score.hip)
   constexpr int kPairB = 2 * kWidth * 2 + 2 * kRowPad;
   constexpr int kRowsPerWave = kTile / 4;
-  constexpr int kRowOps = kPair ? kRowsPerWave / 2 : kRowsPerWave;
+  constexpr int kRowOps = kStaged ? 0 : (kPair ? kRowsPerWave / 2 : kRowsPerWave);   // LDS-direct row requests per wavefront and tile
   constexpr int kCsPerWave = kRopeTileBytes / 1024 / 4;
   constexpr int kDmaOps = kRowOps + kCsPerWave;
   constexpr int kMfmas = NK * 8;                                // matrix instructions per 16-token sub-tile
@@ -99,14 +107,15 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   const int last_tile = n_tiles - 1;
   const int rel_last = L - 1 - t_begin;
 
-  const unsigned row_bytes = (unsigned)a.row_elems * 2u;
-  const unsigned char* hk_base = (const unsigned char*)a.hk + ((size_t)b * a.max_seq + t_begin) * row_bytes + u.k_off0 * 2;
+  const unsigned row_bytes = kStaged ? (unsigned)a.row_elems / 2u : (unsigned)a.row_elems * 2u;
+  const size_t row0 = (size_t)b * a.max_seq + t_begin;
+  const unsigned char* hk_base = (const unsigned char*)a.hk + row0 * row_bytes + (kStaged ? u.k_off0 / 2 : u.k_off0 * 2);
   const unsigned char* rope_base_u = uniform_ptr((const unsigned char*)a.rope_rows + (size_t)(t_begin >> 5) * a.rope_tile_stride);
   const unsigned lds_base = (unsigned)(size_t)lds;
 
   // ---- staging: LDS-direct requests, as in score_kernel (rows past the last attendable one re-read it, tiles past
   // the end of the chunk re-read its last tile, so that the number of requests in flight at every wait is a constant)
-  unsigned dma_row_off[kRowOps];
+  unsigned dma_row_off[kRowOps > 0 ? kRowOps : 1];
   unsigned dma_pair_col = 0;
 #pragma unroll
   for (int x = 0; x < kRowOps; ++x) {
@@ -160,6 +169,60 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
     for (int x = 0; x < kDmaOps; ++x) dma_issue_op(d, x);
   };
 
+  // ---- quantized keys: a tile's codes, scales and zero-points through registers (rows past the last attendable one
+  // re-read it); chunk = 8 channels of one token = 4 bytes of codes -> 16 bytes of fp16 in LDS
+  constexpr int kChunks = kTile * kCpr;
+  constexpr int kPass = kStaged ? (kChunks + 255) / 256 : 1;     // chunks per thread and tile
+  struct Staged {
+    uint32_t codes;
+    uint16_t scale, zero;
+  };
+  Staged stage[kPass];
+  int st_row[kPass], st_col[kPass], st_blk[kPass];
+  uint32_t k1024 = 0;
+  if constexpr (kStaged) {
+    k1024 = per_lane_constant(0x64006400u);
+#pragma unroll
+    for (int p = 0; p < kPass; ++p) {
+      const int id = min(p * 256 + tid, kChunks - 1);           // surplus threads repeat the last chunk
+      st_row[p] = id / kCpr;
+      st_col[p] = id - st_row[p] * kCpr;
+      st_blk[p] = (u.k_off0 + st_col[p] * 8) / a.quant_block;   // quantization block of the chunk's 8 channels
+    }
+  }
+  auto latent_loads = [&](int tile_unclamped) __attribute__((always_inline)) {
+    const int r0 = min(tile_unclamped, last_tile) * kTile;
+#pragma unroll
+    for (int p = 0; p < kPass; ++p) {
+      const unsigned rel = (unsigned)min(r0 + st_row[p], rel_last);
+      stage[p].codes = *reinterpret_cast<const uint32_t*>(hk_base + (size_t)rel * row_bytes + (unsigned)st_col[p] * 4u);
+      const size_t sb = (row0 + rel) * a.n_blocks_q + st_blk[p];
+      stage[p].scale = a.hk_scale[sb];
+      stage[p].zero = a.hk_zero[sb];
+    }
+  };
+  // the whole wavefront takes the float32 form for a tile in which any of its zero-points is not a small integer
+  // (a uniform branch around two straight-line bodies)
+  auto latent_store = [&](int tile) __attribute__((always_inline)) {
+    unsigned char* base = lds + (size_t)(tile % kBufs) * kTileB;
+    bool small = true;
+#pragma unroll
+    for (int p = 0; p < kPass; ++p) small = small && zero_point_is_small_integer(stage[p].zero);
+    if (__builtin_amdgcn_ballot_w64(!small) == 0) {
+#pragma unroll
+      for (int p = 0; p < kPass; ++p) {
+        const uint4v v = dequant8_packed(stage[p].codes, stage[p].scale, stage[p].zero, k1024);
+        if (p * 256 + tid < kChunks) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + st_col[p] * 16) = v;
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < kPass; ++p) {
+        const uint4v v = dequant8_float(stage[p].codes, stage[p].scale, stage[p].zero);
+        if (p * 256 + tid < kChunks) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + st_col[p] * 16) = v;
+      }
+    }
+  };
+
   // ---- this wavefront's head
   const bool active = wave < u.nh;
   const int hc = u.h0 + (active ? wave : 0);                    // idle wavefronts mirror head h0: same values, same stores
@@ -169,6 +232,7 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
 
   // the first tile's requests, then the query and the weights (everything the first sub-tile waits for), then the other tiles
   dma_issue(0);
+  if constexpr (kStaged) latent_loads(0);
   uint16_t q_raw[NQ][4][2];
   float q_rev[4][2];
   int q_position[NQ];
@@ -242,6 +306,10 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
 
   // ---- start-up: tile 0, the query and the weights have landed; tiles 1 .. kAheadTiles-1 stay in flight
   __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAheadTiles - 1) * kDmaOps));
+  if constexpr (kStaged) {                                      // tile 0 goes to LDS, tile 1 into the staging registers
+    latent_store(0);
+    latent_loads(1);
+  }
   __syncthreads();
   // the rotated query, scaled by log2(e) / sqrt(d_h): qa = q'_f, qb = q'_{f+64} of pair f = 16 pb + n16
   float qa[NQ][4], qb[NQ][4];
@@ -378,7 +446,9 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
     for (int ks = 0; ks < NK; ++ks) {
       if (tt == 1 && ks == kHandK) {
         __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAheadTiles - 2) * kDmaOps));         // tile k+1 has landed (this wavefront's share)
+        if constexpr (kStaged) latent_store(k + 1);             // ... in the staging registers: dequantized into buffer (k+1) % 3
         __syncthreads();
+        if constexpr (kStaged) latent_loads(k + 2);
         nxt = dma_tile(k + kAheadTiles);
         __builtin_amdgcn_sched_barrier(0);
       }

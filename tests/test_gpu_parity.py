@@ -378,6 +378,30 @@ def test_shared_keys_exact_form(rank, qpk, sizes, dtype, scale):
     check(case, TOL_FP)
 
 
+@pytest.mark.parametrize("rank,qpk,sizes,offset", [(128, 4, [2, 4, 1], 0.0), (256, 8, [4, 2], 0.0), (256, 3, [4], 0.0),
+                                                  (128, 6, [4, 4], 0.0), (256, 2, [2, 2], 12.0)])
+def test_shared_keys_quantized(rank, qpk, sizes, offset):
+    """4-bit key latents of rank 128 / 256 with several query heads per key/value head: a key tile is dequantized,
+    rebuilt and rotated once per pass for the queries that share it.  One case has key latents far off centre
+    (zero-points in the thousands: the float32 form of the dequantizer)."""
+    n_kv = sum(sizes)
+    head_off = [0] + list(np.cumsum(sizes))
+    kr = [rank] * len(sizes)
+    vr = [128] * len(sizes)
+    layer = synth.Layer(n_kv, 128, head_off, [0] + list(np.cumsum(kr)), [0] + list(np.cumsum(vr)), rope_theta=10000.0,
+                        q_per_kv=qpk)
+    case = synth.make_case_orthonormal(layer, 2, 211, seed=900 + rank + qpk)
+    if offset:
+        case.Hk = synth.round_to(0.01 * case.Hk + offset, "f16")
+    case.seq_lens = np.array([211, 70], np.int32)
+    case.q_pos = (case.seq_lens - 1).astype(np.int32)
+    case.name = f"shared keys, 4-bit, rank={rank} q_per_kv={qpk} groups={sizes} offset={offset:g}"
+    quant = {"k": O.quant_latent(case.Hk), "v": O.quant_latent(case.Hv)}
+    if offset:
+        assert np.abs(np.asarray(quant["k"][2], np.float32)).max() > 1000.0
+    check(case, TOL_I4, k_i4=True, v_i4=True, quant=quant)
+
+
 @pytest.mark.parametrize("k_i4,v_i4,theta", [(True, True, 500000.0), (True, True, 0.0)])
 def test_grouped_query_attention_int4(k_i4, v_i4, theta):
     import dataclasses
