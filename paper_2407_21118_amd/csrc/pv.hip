@@ -17,13 +17,22 @@
 // kernel stays bound by the latent stream for every head-group size, including
 // one latent shared by all 32 heads.
 //
-// 4-bit latents: while transposing, a code c becomes the exact fp16 number 1 + c/64
-// (the nibble placed in mantissa bits 4 .. 7, at most two operations per register);
-// the per-(token, 128-channel block) scale is folded into the probabilities
-// (one probability tile per block, a = p s) and the zero-points and the offset
-// into one scalar per (head, block): sum_t a (c - z) = 64 sum_t a (1 + c/64) - sum_t a (64 + z).
+// 4-bit latents: while transposing, a code c is masked in place into the low mantissa bits of an fp16 zero,
+// i.e. becomes the subnormal number c 2^-24 (codes in bits 0 .. 3) or c 2^-20 (bits 4 .. 7): the matrix cores
+// take subnormal fp16 operands exactly, so one AND per operand register (and one shift per four) dequantizes.
+// The per-(token, 128-channel block) scale is folded into the probabilities (one probability tile per block,
+// a = p s), the power of two into the write-out, and the zero-points into one scalar per (head, block):
+// sum_t a (c - z) = 2^24 sum_t a (c 2^-24) - sum_t a z.
+//
+// The running maximum is lazy: it only rises (and the accumulators are only rescaled) when a set's maximum
+// exceeds it by more than 8 (scores are base-2 logarithms), so probabilities reach 256 at most; the (max, sum)
+// pair a split reports is consistent with its accumulators, which is all the combination needs.
 
 #include "palu_dev.h"
+
+#ifndef PALU_PV_PAIR_DEPTH
+#define PALU_PV_PAIR_DEPTH 2
+#endif
 
 namespace palu {
 
@@ -140,9 +149,16 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   constexpr bool I4 = QB != 0;
   constexpr bool kIsBf16 = !__is_same(T, F16);
   constexpr int MT = HS > 8 ? 2 : 1;
-  constexpr int NA = I4 ? NG : 1;                  // probability tiles
+  constexpr int NA = I4 ? NG : 1;                  // scaled probabilities: one set per quantization block
+  // 4-bit codes, four heads, two blocks: a lane takes two neighbouring 8-channel chunks with one 8-byte load
+  // (a load instruction then covers whole 128-byte rows, and a set needs half the requests, which is what
+  // lets three sets be in flight under the 63 outstanding requests a wavefront can count).  The chunks of lanes
+  // n < 8 lie in block 0 and those of lanes n >= 8 in block 1, so one matrix instruction serves both blocks:
+  // the probability tile has rows (block, head) - 8 of its 16 - and a lane keeps the rows of its own block.
+  constexpr bool kPair = QB == 4 && NG == 2 && HS == 2;
+  constexpr int NT = kPair ? 1 : NA;               // probability tiles
   constexpr int kPitch = 40;                       // halfs per head row: 80-byte pitch, 16-byte reads of 16 rows hit distinct banks
-  __shared__ __attribute__((aligned(16))) _Float16 p_lds[4][NA][MT * 16 * kPitch];
+  __shared__ __attribute__((aligned(16))) _Float16 p_lds[4][NT][MT * 16 * kPitch];
   __shared__ __attribute__((aligned(16))) float x_lds[4][MT * 16 * NA];
 
   const int lane = threadIdx.x & 63;
@@ -182,6 +198,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   unsigned coff[NG];
 #pragma unroll
   for (int ng = 0; ng < NG; ++ng) coff[ng] = (unsigned)min(ng * 16 + n, lpt - 1) * (I4 ? (bits == 4 ? 4u : 2u) : 16u);
+  if constexpr (kPair) coff[0] = (unsigned)min(n, (lpt >> 1) - 1) * 8u;      // chunks 2n and 2n + 1 (a unit has a multiple of 4 chunks)
   // byte offset of the row of the lane's token j in set 0; a set further on is 32 rows further, clamped to the last row
   unsigned roff[8];
 #pragma unroll
@@ -215,11 +232,15 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   auto issue = [&](Set& st, int k) {
     const int tb = k * 32;
 #pragma unroll
-    for (int ng = 0; ng < NG; ++ng) {
+    for (int ng = 0; ng < (kPair ? 1 : NG); ++ng) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const unsigned char* p = base + (size_t)(min(roff[j] + (unsigned)k * set_bytes, last_off) + coff[ng]);
-        if constexpr (I4) {
+        if constexpr (kPair) {
+          const uint2v v = *reinterpret_cast<const uint2v*>(p);
+          st.blk[0].h[j][0] = v.x;
+          st.blk[1].h[j][0] = v.y;
+        } else if constexpr (I4) {
           if constexpr (bits == 4) {
             st.blk[ng].h[j][0] = *reinterpret_cast<const uint32_t*>(p);
           } else {
@@ -248,7 +269,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
     }
   };
 
-  const uint32_t fp16_ones = per_lane_constant(0x3c003c00u);
+  constexpr float kLazy = 8.f;
   float mx[HS], lsum[HS], lz[HS][NA];
 #pragma unroll
   for (int i = 0; i < HS; ++i) {
@@ -273,12 +294,21 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
     // ---- online softmax statistics of the 32 tokens
     float s[HS], bm[HS];
     bool grew = false;
+    // lazy maximum: probabilities up to 2^kLazy.  Quantized latents carry the scale in the fp16 weights a = p s:
+    // with a scale above 128 somewhere in the set the maximum is exact (p <= 1) and a stays in range as before.
+    float lazy = kLazy;
+    if constexpr (I4) {
+      bool big = false;
+#pragma unroll
+      for (int g = 0; g < NA; ++g) big |= st.qs[g] > (uint16_t)0x5800;          // fp16 bits of 128 (a negative or NaN scale also lands here)
+      if (__builtin_amdgcn_ballot_w64(big) != 0) lazy = 0.f;
+    }
 #pragma unroll
     for (int i = 0; i < HS; ++i) {
       const float v = st.sc[i][0] + (two[i] ? st.sc[i][1] : 0.f);
       s[i] = (tok_ok && hp + 2 * i < nh && k * 32 + tl < lim[i]) ? v : -INFINITY;
       bm[i] = half_wave_max(s[i]);
-      grew |= bm[i] > mx[i];
+      grew |= bm[i] > mx[i] + lazy;
     }
     if (__builtin_amdgcn_ballot_w64(grew) != 0) {             // uniform: some head's running maximum rises
 #pragma unroll
@@ -289,7 +319,10 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
         lsum[i] *= al;
 #pragma unroll
         for (int g = 0; g < NA; ++g) lz[i][g] *= al;
-        if (tl == 0) xw[hp + 2 * i] = al;
+        if (tl == 0) {
+          xw[hp + 2 * i] = al;
+          if constexpr (kPair) xw[4 + hp + 2 * i] = al;       // rows 4 .. 7: the same heads under block 1
+        }
       }
       wave_lds_fence();
 #pragma unroll
@@ -317,15 +350,15 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
           const float sc = F16::to_float(st.qs[g]);
           const float zp = F16::to_float(st.qz[g]);
           const _Float16 ah = (_Float16)(p * sc);
-          lz[i][g] = fmaf((float)ah, zp + 64.f, lz[i][g]);      // codes enter the product as 1 + c/64, see below
-          pw[g * (MT * 16 * kPitch) + slot] = ah;
+          lz[i][g] = fmaf((float)ah, zp, lz[i][g]);
+          pw[kPair ? slot + g * 4 * kPitch : g * (MT * 16 * kPitch) + slot] = ah;
         }
       }
     }
     wave_lds_fence();
-    half8 pa[NA][MT];
+    half8 pa[NT][MT];
 #pragma unroll
-    for (int g = 0; g < NA; ++g)
+    for (int g = 0; g < NT; ++g)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
         pa[g][mt] = *reinterpret_cast<const half8*>(pw + g * (MT * 16 * kPitch) + (mt * 16 + n) * kPitch + 8 * kq);
@@ -359,16 +392,17 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
             ca = expand_low_bits(ca, bl.h[2 * jp][QB == 3 ? 1 : 0], QB == 3);
             cb = expand_low_bits(cb, bl.h[2 * jp + 1][QB == 3 ? 1 : 0], QB == 3);
           }
-          // a code c in mantissa bits 4 .. 7 of 0x3c00 is the fp16 number 1 + c/64 (exact):
-          // sum_t a_t (1 + c_t/64) = sum a + (sum a c)/64, undone at the write-out together with the zero-points.
           // Four channels of both tokens side by side (token a's 16 bits of codes below token b's): the codes of
-          // channel u of the two tokens are then 16 bits apart, i.e. in the two halves of one operand register
-          // after one shift and one masked merge.
+          // channel u of the two tokens are then 16 bits apart, i.e. in the two halves of one operand register.
+          // Masked in place they are the subnormal fp16 numbers c 2^-24 (channels 0 and 2 of the four, after a
+          // shift by 8 for the latter) and c 2^-20 (channels 1 and 3); the powers of two are undone at the write-out.
 #pragma unroll
           for (int half = 0; half < 2; ++half) {
-            const NibblePairs np = nibbles_to_fp16_pairs(__builtin_amdgcn_perm(cb, ca, half ? 0x07060302u : 0x05040100u), fp16_ones);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) o[4 * half + u][jp] = np.p[u];                             // channel 4 half + u
+            const uint32_t x = __builtin_amdgcn_perm(cb, ca, half ? 0x07060302u : 0x05040100u), x8 = x >> 8;
+            o[4 * half + 0][jp] = x & 0x000f000fu;
+            o[4 * half + 1][jp] = x & 0x00f000f0u;
+            o[4 * half + 2][jp] = x8 & 0x000f000fu;
+            o[4 * half + 3][jp] = x8 & 0x00f000f0u;
           }
         }
       }
@@ -378,7 +412,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
         const half8 bop = __builtin_bit_cast(half8, bw);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          acc[mt][ng][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[I4 ? ng : 0][mt], bop, acc[mt][ng][e], 0, 0, 0);
+          acc[mt][ng][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[NT > 1 ? ng : 0][mt], bop, acc[mt][ng][e], 0, 0, 0);
       }
     }
   };
@@ -389,7 +423,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   // have to cover both ways of reaching it, i.e. every load in flight, and nothing would be prefetched.
   // (Three and four sets for quantized latents, whose sets are a quarter of the bytes, measured 5 - 10 % slower,
   // and 2-bit codes take as long as 4-bit ones: that kernel is bound by its instruction stream, not by bytes in flight.)
-  constexpr int kDepth = 2;
+  constexpr int kDepth = kPair ? PALU_PV_PAIR_DEPTH : 2;
   Set ring[kDepth];
 #pragma unroll
   for (int d = 0; d < kDepth - 1; ++d) issue(ring[d], d);
@@ -426,7 +460,8 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int hh = mt * 16 + 4 * kq + r;                    // accumulator row = head of the unit
+      if (kPair && kq != (n >> 3)) continue;                  // rows 4 kq + r: block kq's scale; the lane's chunks are in block n / 8
+      const int hh = kPair ? r : mt * 16 + 4 * kq + r;        // accumulator row = head of the unit
       if (hh >= nh) continue;
       const int h = h0 + hh;
       const int j = group_of(m, h);
@@ -434,17 +469,17 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
       float* oh = op + o_head_off(m, h) - lo;
 #pragma unroll
       for (int ng = 0; ng < NG; ++ng) {
-        const int chunk = ng * 16 + n;
+        const int chunk = kPair ? 2 * n + ng : ng * 16 + n;
         const int col = c0 + chunk * 8;
         if (chunk >= lpt || col < lo || col >= hi) continue;   // a head keeps the columns of its own group
-        // int4: acc = sum a (1 + c/64) and zt = sum a (64 + z), so sum a (c - z) = 64 acc - zt
-        const float zt = I4 ? xw[hh * NA + ng] : 0.f;
-        const float g = I4 ? 64.f : 1.f;
+        // quantized: acc = sum a c 2^-24 (even channels of the chunk) or sum a c 2^-20 (odd), zt = sum a z
+        const float zt = I4 ? xw[hh * NA + (kPair ? n >> 3 : ng)] : 0.f;
+        const float g0 = I4 ? 16777216.f : 1.f, g1 = I4 ? 1048576.f : 1.f;
         float4v v0, v1;
-        v0.x = fmaf(g, acc[mt][ng][0][r], -zt); v0.y = fmaf(g, acc[mt][ng][1][r], -zt);
-        v0.z = fmaf(g, acc[mt][ng][2][r], -zt); v0.w = fmaf(g, acc[mt][ng][3][r], -zt);
-        v1.x = fmaf(g, acc[mt][ng][4][r], -zt); v1.y = fmaf(g, acc[mt][ng][5][r], -zt);
-        v1.z = fmaf(g, acc[mt][ng][6][r], -zt); v1.w = fmaf(g, acc[mt][ng][7][r], -zt);
+        v0.x = fmaf(g0, acc[mt][ng][0][r], -zt); v0.y = fmaf(g1, acc[mt][ng][1][r], -zt);
+        v0.z = fmaf(g0, acc[mt][ng][2][r], -zt); v0.w = fmaf(g1, acc[mt][ng][3][r], -zt);
+        v1.x = fmaf(g0, acc[mt][ng][4][r], -zt); v1.y = fmaf(g1, acc[mt][ng][5][r], -zt);
+        v1.z = fmaf(g0, acc[mt][ng][6][r], -zt); v1.w = fmaf(g1, acc[mt][ng][7][r], -zt);
         *reinterpret_cast<float4v*>(oh + col) = v0;
         *reinterpret_cast<float4v*>(oh + col + 4) = v1;
       }
