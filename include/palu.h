@@ -95,10 +95,13 @@ const char* palu_status_string(int status);
 int palu_version(void);
 
 /*
- * Process-wide tuning knobs for experiments; every default (0) lets the library
+ * Process-wide tuning knobs for experiments; every default (0, where not stated otherwise) lets the library
  * choose.  Not thread-safe against concurrent decode calls.
  *   "score_waves"         4 or 8 wavefronts per score workgroup for ranks <= 256
  *   "score_chunks"        sequence chunks per (sequence, head block) in the score kernel
+ *   "score_mixed"         default 1: a layer whose groups have different ranks (all 64 .. 256 after slicing, fp16 or
+ *                         bf16 latents, one query per head) gets ONE score launch over all rank classes; 0: one
+ *                         launch per rank class
  *   "value_split_tokens"  tokens per sequence split in the value kernel (multiple of 32, <= 4096)
  *   "score_fp8"           1: low-precision key reconstruction (Sec. 4.5.2, last paragraph), for fp16 layers with RoPE,
  *                         unquantized key latents and ranks 64 .. 256: B_k is rounded to 8-bit floats (OCP E4M3)

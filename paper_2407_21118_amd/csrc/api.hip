@@ -11,6 +11,7 @@
 #include "qk.hip"
 #include "probe.hip"
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstring>
@@ -25,6 +26,7 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Tuning knobs (palu_set_option); 0 = automatic.
 std::atomic<int> g_opt_score_waves{0};        // 4 or 8 wavefronts per score workgroup (ranks <= 256)
+std::atomic<int> g_opt_score_mixed{1};        // 1: one score launch for a layer of several rank classes where the whole-head kernel takes them all
 std::atomic<int> g_opt_score_chunks{0};       // sequence chunks per (sequence, head block) of the score kernel
 std::atomic<int> g_opt_value_split{0};        // tokens per split of the value kernel
 std::atomic<int> g_opt_score_fp8{0};          // 1: keys rebuilt from E4M3-rounded latents and weights (score8_kernel)
@@ -752,6 +754,9 @@ int palu_set_option(const char* name, int value) {
   if (!std::strcmp(name, "score_waves")) {
     if (value != 0 && value != 4 && value != 8) return PALU_ERR_INVALID_ARG;
     g_opt_score_waves = value;
+  } else if (!std::strcmp(name, "score_mixed")) {
+    if (value > 16) return PALU_ERR_INVALID_ARG;
+    g_opt_score_mixed = value;
   } else if (!std::strcmp(name, "score_chunks")) {
     g_opt_score_chunks = value;
   } else if (!std::strcmp(name, "value_split_tokens")) {
@@ -1486,7 +1491,87 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         a.chunk_tokens = chunk_tiles * kTile;
         a.n_chunks = ceil_div(tiles, chunk_tiles);
       };
-      for (int cls = 0; cls < plan.n_cls; ++cls) {
+      // Groups of different ranks, every class on the whole-head kernel with one group per workgroup: ONE launch
+      // where one round of workgroups covers the layer.  Launches on one stream run one after the other and every
+      // workgroup start costs several microseconds (the head's weights go to registers, the tile ring fills), so
+      // a launch per class pays that once per class; here every workgroup has a compute unit to itself, starts
+      // once, and the chunk lengths per class are chosen so that all of them end at about the same time.
+      bool mixed = use16 && !shared16 && !shared4 && !use8 && g_opt_score_mixed != 0 && g_opt_score_chunks == 0 &&
+                   plan.n_cls > 1 && plan.n_cls <= kMaxMixClasses && plan.total_units <= kMaxScoreUnits;
+      for (int cls = 0; cls < plan.n_cls && mixed; ++cls) {
+        const int id = plan.cls_id[cls];
+        if (id == kSlicedCls || id % 3 != 0 || !rank_class_16(id / 3)) mixed = false;
+      }
+      int order[kMaxMixClasses], n_units_cls[kMaxMixClasses] = {}, one_round[kMaxMixClasses];
+      bool use_one_round = false;
+      double mix_per_wg = 0.0;
+      long long mix_chunk_limit_tiles = 1;
+      static const double kCost[9] = {0, 0, 30, 33, 36, 37, 51, 58, 56};   // measured: microseconds per 1000 tokens of one workgroup by rank / 32
+      auto weight = [](int nk) { return kCost[nk]; };
+      if (mixed) {
+        constexpr double kStartUs = 8.5;                         // measured: microseconds from a workgroup's start to its first tile and after its last
+        for (int cls = 0; cls < plan.n_cls; ++cls) order[cls] = cls;
+        std::sort(order, order + plan.n_cls, [&](int x, int y) { return plan.cls_id[x] > plan.cls_id[y]; });
+        for (int i = 0; i < plan.total_units; ++i) ++n_units_cls[plan.unit_cls[i]];
+        double work = 0.0;                                       // weighted tokens of the whole launch
+        for (int cls = 0; cls < plan.n_cls; ++cls) work += weight(plan.cls_id[cls] / 3 + 1) * n_units_cls[cls] * (double)batch * seq_len;
+        const int cus = device_cu_count();
+        mix_per_wg = work / ((g_opt_score_mixed > 1 ? (double)g_opt_score_mixed : 3.0) * cus);
+        const long long chunk_limit_tiles = mix_chunk_limit_tiles = std::max(1LL, std::min<long long>({(1LL << 31) / ((long long)Rk * 2 * kTile), (1LL << 24) / kTile,
+                                                                                 (1LL << 31) / kRopeTableStride}));
+        // One round where it fits: every workgroup has a compute unit to itself and starts once.  Chunks go, one at
+        // a time, to the class whose workgroups would run longest, while the launch still fits the chip.
+        if (g_opt_score_mixed == 1) {
+          long long total = 0;
+          for (int cls = 0; cls < plan.n_cls; ++cls) {
+            one_round[cls] = (int)ceil_div(tiles, (int)std::min<long long>(tiles, chunk_limit_tiles));
+            total += (long long)one_round[cls] * n_units_cls[cls] * batch;
+          }
+          auto wg_us = [&](int cls) { return kStartUs + ceil_div(tiles, one_round[cls]) * kTile * weight(plan.cls_id[cls] / 3 + 1) * 1e-3; };
+          while (total <= cus) {
+            int worst = 0;
+            for (int cls = 1; cls < plan.n_cls; ++cls) if (wg_us(cls) > wg_us(worst)) worst = cls;
+            const long long more = (long long)n_units_cls[worst] * batch;
+            if (one_round[worst] >= tiles || total + more > cus) break;
+            ++one_round[worst];
+            total += more;
+          }
+          double t1 = 0.0;
+          for (int cls = 0; cls < plan.n_cls; ++cls) t1 = std::max(t1, wg_us(cls));
+          const double t3 = 1.1 * (work * 1e-3 / cus + 3.0 * kStartUs);                     // three rounds of workgroups, some imbalance
+          use_one_round = total <= cus && t1 < t3;
+          if (!use_one_round) mixed = false;      // several rounds of mixed workgroups measured no faster than a launch per class
+        }
+      }
+      if (mixed) {
+        a.units.n_units = 0;
+        a.mix.n_cls = plan.n_cls;
+        long long first = 0;
+        size_t lds = 0;
+        for (int x = 0; x < plan.n_cls; ++x) {
+          const int cls = order[x], nk = plan.cls_id[cls] / 3 + 1;
+          int chunk_tiles = (int)std::min<long long>(std::max<long long>(1, std::llround(mix_per_wg / weight(nk) / kTile)), std::min<long long>(tiles, mix_chunk_limit_tiles));
+          const int n_chunks = use_one_round ? one_round[cls] : ceil_div(tiles, chunk_tiles);
+          chunk_tiles = ceil_div(tiles, n_chunks);               // chunks of equal length
+          a.mix.first[x] = (int)first;
+          a.mix.n_chunks[x] = ceil_div(tiles, chunk_tiles);
+          a.mix.chunk_tokens[x] = chunk_tiles * kTile;
+          a.mix.unit0[x] = a.units.n_units;
+          a.mix.n_units[x] = n_units_cls[cls];
+          a.mix.nk[x] = nk;
+          for (int i = 0; i < plan.total_units; ++i)
+            if (plan.unit_cls[i] == cls) a.units.u[a.units.n_units++] = plan.units[i];
+          first += (long long)a.mix.n_chunks[x] * n_units_cls[cls] * batch;
+          lds = std::max(lds, (size_t)score16_lds_bytes(32 * nk));
+        }
+        if (first >= (1LL << 31)) return PALU_ERR_UNSUPPORTED;
+        ScoreFn fn = act == PALU_F16 ? score16_mixed_kernel<F16> : score16_mixed_kernel<BF16>;
+        if ((st = allow_lds(fn, lds)) != PALU_OK) return st;
+        a.mfold = reinterpret_cast<const uint16_t*>(ws + w.mfold);
+        hipLaunchKernelGGL(fn, dim3((unsigned)first), dim3(256), lds, s, a);
+        if ((st = launch_ok()) != PALU_OK) return st;
+      }
+      for (int cls = 0; cls < plan.n_cls && !mixed; ++cls) {
         const int id = plan.cls_id[cls];
         const bool sliced = id == kSlicedCls;
         const int rc = sliced ? rank_class(kSliceRank) : id / 3, lg = sliced ? 0 : id % 3;

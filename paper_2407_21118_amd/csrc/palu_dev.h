@@ -194,6 +194,16 @@ struct ScoreUnit {
   int part0;                 // first partial-score plane the unit writes (2 per rank slice)
 };
 constexpr int kMaxScoreUnits = 64;      // per launch
+constexpr int kMaxMixClasses = 7;       // ranks 64, 96, .. 256
+struct ScoreMix {
+  int n_cls;
+  int first[kMaxMixClasses];            // first workgroup of the class
+  int n_chunks[kMaxMixClasses];         // sequence chunks per (unit, sequence)
+  int chunk_tokens[kMaxMixClasses];     // tokens per chunk (multiple of kTile)
+  int unit0[kMaxMixClasses];            // the class's units: unit0 .. unit0 + n_units - 1 of ScoreArgs.units
+  int n_units[kMaxMixClasses];
+  int nk[kMaxMixClasses];               // rank / 32
+};
 struct ScoreUnits {
   int n_units;
   ScoreUnit u[kMaxScoreUnits];
@@ -231,6 +241,7 @@ struct ScoreArgs {
   const float* w_scale;      // 8-bit weights (score8_kernel): the power-of-two scale of every feature column [heads][128]
   int m_qpk, m_nq;           // one-query form: Meta::qpk and Meta::nq of the call (layout of q, see q_row)
   int sk_row0, sk_rows;      // exact shared-key form: the query rows of every key/value head this launch takes
+  ScoreMix mix;              // one launch over several rank classes (score16_mixed_kernel)
   int rope_tile_stride;
   float rev_hi[kHalf];       // theta^(-2f/128) / (2 pi) from the host's float64 value, as a float pair hi + lo
   float rev_lo[kHalf];

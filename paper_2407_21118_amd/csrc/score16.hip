@@ -61,8 +61,10 @@ __device__ __forceinline__ float sum_quad_over_row(const float (&p)[4], int lane
 //     zero) * scale, one rounding; see dequant8_packed) and written to LDS in the layout the matrix instructions
 //     read; only the angle tiles stay LDS-direct.  The hand-over's vector work is not hidden by matrix instructions,
 //     which is why this form is used where several queries share the key tile (NQ > 1) and score_kernel elsewhere.
+// The body takes its place in the launch as arguments (sequence chunk of chunk_tokens tokens, unit, sequence), so
+// that a launch over several rank classes can hand each workgroup the body of its unit's class.
 template <typename T, int NK, int G, int NQ = 1, int QB = 0>
-__global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
+__device__ __forceinline__ void score16_body(const ScoreArgs& a, const int chunk, const int unit, const int b, const int chunk_tokens) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   using Vec = typename T::vec8;
   constexpr bool kStaged = QB != 0;
@@ -92,17 +94,16 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   const int lane = tid & 63;
   const int n16 = lane & 15, kq = lane >> 4;                    // feature column (B, D) or token row (A); k-octet (A, B) or token quad (D)
 
-  const int chunk = blockIdx.x, unit = blockIdx.y, b = blockIdx.z;
   const ScoreUnit u = a.units.u[unit];
-  asm volatile("" :: "s"(a.seq_lens), "s"(a.seq_len), "s"(a.chunk_tokens), "s"(a.hk), "s"(a.rope_rows), "s"(a.row_elems),
+  asm volatile("" :: "s"(a.seq_lens), "s"(a.seq_len), "s"(chunk_tokens), "s"(a.hk), "s"(a.rope_rows), "s"(a.row_elems),
                "s"(a.max_seq), "s"(a.mfold), "s"(a.scores), "s"(a.lpad), "s"(a.batch), "s"(a.n_heads), "s"(a.q), "s"(a.q_pos));
   asm volatile("" :: "s"(u.h0), "s"(u.nh), "s"(u.s), "s"(u.head_off0), "s"(u.k_off0), "s"(u.bk_off0), "s"(u.head_stride),
                "s"(u.part0));
 
   const int L = a.seq_lens ? min(a.seq_lens[b], a.seq_len) : a.seq_len;
-  const int t_begin = chunk * a.chunk_tokens;
+  const int t_begin = chunk * chunk_tokens;
   if (t_begin >= L) return;                                     // uniform for the workgroup
-  const int t_end = min(t_begin + a.chunk_tokens, L);
+  const int t_end = min(t_begin + chunk_tokens, L);
   const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
   const int last_tile = n_tiles - 1;
   const int rel_last = L - 1 - t_begin;
@@ -509,6 +510,38 @@ __global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
   }
   finish(acc[1], last_tile, 1);
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));     // no LDS-direct load may outlive the workgroup's LDS allocation
+}
+
+// grid (sequence chunks, units, batch), 256 threads: every unit of the launch has rank 32 * NK
+template <typename T, int NK, int G, int NQ = 1, int QB = 0>
+__global__ __launch_bounds__(256) void score16_kernel(ScoreArgs a) {
+  score16_body<T, NK, G, NQ, QB>(a, blockIdx.x, blockIdx.y, blockIdx.z, a.chunk_tokens);
+}
+
+// One launch for a layer whose groups have different ranks (the ranks a search assigns per group, Sec. 3.3):
+// a.mix lists the rank classes, heaviest first, each with its own chunk length (chosen by the host so that
+// workgroups of different classes take about as long) and its units, which lie side by side in a.units.
+// grid (sum over classes of chunks x units x batch), 256 threads; the workgroups of a class are consecutive.
+template <typename T>
+__global__ __launch_bounds__(256) void score16_mixed_kernel(ScoreArgs a) {
+  int c = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxMixClasses; ++i)
+    if (i < a.mix.n_cls && (int)blockIdx.x >= a.mix.first[i]) c = i;
+  const int local = (int)blockIdx.x - a.mix.first[c];
+  const int n_chunks = a.mix.n_chunks[c], n_units = a.mix.n_units[c];
+  const int chunk = local % n_chunks, rest = local / n_chunks;
+  const int unit = a.mix.unit0[c] + rest % n_units, b = rest / n_units;
+  const int ct = a.mix.chunk_tokens[c];
+  switch (a.mix.nk[c]) {
+    case 2: score16_body<T, 2, 1>(a, chunk, unit, b, ct); break;
+    case 3: score16_body<T, 3, 1>(a, chunk, unit, b, ct); break;
+    case 4: score16_body<T, 4, 1>(a, chunk, unit, b, ct); break;
+    case 5: score16_body<T, 5, 1>(a, chunk, unit, b, ct); break;
+    case 6: score16_body<T, 6, 1>(a, chunk, unit, b, ct); break;
+    case 7: score16_body<T, 7, 1>(a, chunk, unit, b, ct); break;
+    default: score16_body<T, 8, 1>(a, chunk, unit, b, ct); break;
+  }
 }
 
 }  // namespace palu

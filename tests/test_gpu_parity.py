@@ -255,6 +255,55 @@ def test_mixed_group_sizes_and_ranks():
     check(case, TOL_FP)
 
 
+@pytest.mark.parametrize("mode", [1, 0, 3])
+def test_rank_classes_in_one_score_launch(mode):
+    """A layer whose groups have different key ranks (the ranks a per-group search assigns, Sec. 3.3; above 256 in two
+    slices): by default ONE score launch covers all rank classes, each with its own chunk length (mode 1); the
+    option's other values give a launch per class (0) and several rounds of mixed workgroups (3).  Long enough for
+    several chunks per class, ragged lengths, bf16 in one case."""
+    k_ranks = [416, 352, 224, 256, 128, 64, 96]
+    v_ranks = [128, 256, 96, 128, 64, 128, 32]
+    sizes = [4, 4, 4, 2, 2, 1, 1]
+    layer = synth.Layer(sum(sizes), 128, [0] + list(np.cumsum(sizes)), [0] + list(np.cumsum(k_ranks)),
+                        [0] + list(np.cumsum(v_ranks)))
+    case = synth.make_case_orthonormal(layer, 3, 1500, seed=77 + mode, dtype="bf16" if mode == 3 else "f16")
+    case.seq_lens = np.array([1500, 1, 700], np.int32)
+    case.q_pos = np.array([1499, 5, 800], np.int32)
+    case.q = synth.round_to(case.q * 4.0, case.dtype)
+    case.name = f"rank classes in one launch, score_mixed={mode}"
+    import paper_2407_21118_amd as P
+    P.palu_set_option("score_mixed", mode)
+    try:
+        check(case, TOL_FP)
+    finally:
+        P.palu_set_option("score_mixed", 1)
+
+
+@pytest.mark.parametrize("kind", ["rising", "large-scale", "tiny-scale"])
+def test_value_kernel_lazy_maximum_4bit(kind):
+    """4-bit value latents under the value kernel's lazy running maximum: logits that keep rising along the sequence
+    (the maximum is raised again and again, in steps above and below its threshold), value latents whose quantization
+    scales exceed 128 (the kernel then keeps the exact maximum so that probability x scale stays inside fp16), and
+    tiny scales (weights near the bottom of the fp16 range)."""
+    layer = synth.uniform_layer(8, 4, 256)
+    case = synth.make_case_orthonormal(layer, 2, 700, seed=55)
+    case.seq_lens = np.array([700, 90], np.int32)
+    case.q_pos = (case.seq_lens - 1).astype(np.int32)
+    if kind == "rising":
+        # keys that grow along the sequence in the query's direction: scores rise by a fraction of a unit per token, with jumps
+        ramp = (1.0 + np.arange(700, dtype=np.float32) / 100.0 + 3.0 * (np.arange(700) % 97 == 0))[None, :, None]
+        case.Hk = synth.round_to(case.Hk * ramp, "f16")
+    elif kind == "large-scale":
+        case.Hv = synth.round_to(case.Hv * 3000.0, "f16")
+    else:
+        case.Hv = synth.round_to(case.Hv * 1e-3, "f16")
+    quant = {"k": O.quant_latent(case.Hk), "v": O.quant_latent(case.Hv)}
+    if kind == "large-scale":
+        assert np.asarray(quant["v"][1], np.float32).max() > 128.0
+    case.name = f"4-bit values, lazy maximum: {kind}"
+    check(case, TOL_I4, k_i4=False, v_i4=True, quant=quant)
+
+
 def _random_layer(rng, theta):
     """A random legal layer: groups of 1..8 heads, ranks in multiples of 32 up to
     min(512, width of the group), different for keys and values."""
