@@ -281,10 +281,14 @@ int plan_pv(const Meta& m, PvPlan* p) {
       j = j1;
       continue;
     }
-    const int hb = s <= 4 ? 4 : (s <= 16 ? 16 : 32);
-    const int cw = hb == 32 ? 128 : 256;       // two 16-row tiles of accumulators leave room for one column block
-    for (int u0 = 0; u0 < s; u0 += hb)
-      for (int cs = 0; cs < rv; cs += cw)
+    // Larger groups: blocks of 16 heads x 256 columns.  A wavefront then has 16 KiB of latents per set in flight (with
+    // 32 heads the accumulators leave room for 128 columns only, half of that, and the kernel is bound by
+    // latency).  The head blocks of the same columns are neighbours in the list: they run as wavefronts of one
+    // workgroup at the same time, so the second read of a latent row comes from the cache.
+    const int hb = s <= 4 ? 4 : 16;
+    const int cw = 256;
+    for (int cs = 0; cs < rv; cs += cw)
+      for (int u0 = 0; u0 < s; u0 += hb)
         if ((st = add(m.head_off[j] + u0, std::min(hb, s - u0), m.v_off[j] + cs, std::min(cw, rv - cs), cs == 0)) != PALU_OK)
           return st;
     ++j;
