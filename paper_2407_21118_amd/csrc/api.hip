@@ -245,10 +245,10 @@ int plan_score(const Meta& m, ScorePlan* p, bool widen = true, bool split16 = fa
 }
 
 // ---- value-path work units -----------------------------------------------------
-// Units of the matrix-core value kernel: at most 256 latent columns and 32 heads each.
+// Units of the matrix-core value kernel: at most 256 latent columns and 16 heads each.
 // Small adjacent groups are merged (up to 4 heads, 256 columns) so that a
 // wavefront's 64 lanes all stream; wide latents are cut into column slices.
-enum { kNumPvCls = 5 };            // class = 2 * (0: <=4 heads, 1: <=16, 2: <=32) + (units of up to 256 columns)
+enum { kNumPvCls = 4 };            // class = 2 * (0: <=4 heads, 1: <=16) + (units of up to 256 columns)
 struct PvPlan {
   int total_units;
   PvUnit units[kMaxPlanUnits];
@@ -259,7 +259,7 @@ int plan_pv(const Meta& m, PvPlan* p) {
   p->total_units = 0;
   auto add = [&](int h0, int nh, int c0, int ncols, int write_ml) -> int {
     if (p->total_units >= kMaxPlanUnits) return PALU_ERR_UNSUPPORTED;
-    const int hs = nh <= 4 ? 0 : (nh <= 16 ? 1 : 2);
+    const int hs = nh <= 4 ? 0 : 1;
     PvUnit& x = p->units[p->total_units];
     x.h0 = (uint16_t)h0; x.c0 = c0; x.ncols = (uint16_t)ncols; x.nh = (uint8_t)nh; x.write_ml = (uint8_t)write_ml;
     p->unit_cls[p->total_units++] = (uint8_t)(2 * hs + (ncols > 128 ? 1 : 0));
@@ -363,12 +363,14 @@ inline int value_waves_per_cu(const palu_layer_desc* d) { return latent_bits(d->
 
 // Tokens per value split and number of splits for a given attended length: a
 // split is one wavefront's share; aim at four wavefronts per compute unit,
-// splits of 64 to 512 tokens (more where the merge kernel's split limit asks for it).
+// splits of 64 to 512 tokens (more where the merge kernel's split limit asks for it).  Units of more than 4 heads
+// write larger partial results per split (heads x columns floats against tokens x columns latents read), which the
+// merge kernel reads again: their splits may be four times as long, where that still fills the chip.
 constexpr int kPvSplitMin = 64, kPvSplitMax = 512;
-void split_geometry(int total_units, int batch, int seq_len, int waves_per_cu, int* split_tokens, int* n_split) {
+void split_geometry(int total_units, int batch, int seq_len, int waves_per_cu, int max_unit_heads, int* split_tokens, int* n_split) {
   const long long items = std::max(1, total_units * batch);
   long long st = ceil_div((int)std::min<long long>(items * seq_len / ((long long)waves_per_cu * device_cu_count()) + 1, 1 << 30), 32) * 32LL;
-  st = std::min<long long>(std::max<long long>(st, kPvSplitMin), kPvSplitMax);
+  st = std::min<long long>(std::max<long long>(st, kPvSplitMin), max_unit_heads > 4 ? 4 * kPvSplitMax : kPvSplitMax);
   if (g_opt_value_split > 0) st = g_opt_value_split;
   st = std::max<long long>(st, ceil_div(ceil_div(seq_len, kMaxSplits), 32) * 32LL);
   *split_tokens = (int)st;
@@ -610,8 +612,7 @@ PvFn pv_fn_t(int cls) {
     case 0: return pv_kernel<T, 2, 1, QB>;
     case 1: return pv_kernel<T, 2, 2, QB>;
     case 2: return pv_kernel<T, 8, 1, QB>;
-    case 3: return pv_kernel<T, 8, 2, QB>;
-    default: return pv_kernel<T, 16, 1, QB>;
+    default: return pv_kernel<T, 8, 2, QB>;
   }
 }
 // bits: 4, 3 or 2 for quantized value latents, else 0
@@ -1139,7 +1140,9 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
   if ((st = plan_pv(m, &pp)) != PALU_OK) return st;
   const int quant_block = desc->quant_block > 0 ? desc->quant_block : 128;
   int split_tokens, n_split;
-  split_geometry(pp.total_units, batch, seq_len, value_waves_per_cu(desc), &split_tokens, &n_split);
+  int max_unit_heads = 0;
+  for (int i = 0; i < pp.total_units; ++i) max_unit_heads = std::max(max_unit_heads, (int)pp.units[i].nh);
+  split_geometry(pp.total_units, batch, seq_len, value_waves_per_cu(desc), max_unit_heads, &split_tokens, &n_split);
   if (n_split > kMaxSplits) return PALU_ERR_UNSUPPORTED;
   // the value and no-RoPE kernels address a split of the cache with 32-bit byte offsets
   if ((long long)split_tokens * std::max(Rk, Rv) * 2 >= (1LL << 32)) return PALU_ERR_UNSUPPORTED;

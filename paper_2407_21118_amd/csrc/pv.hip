@@ -14,8 +14,9 @@
 // permutes (one per operand register); channel e of every chunk then forms the
 // B operand of the e-th of 8 accumulator sets.  The vector ALU only does the
 // softmax (a few operations per token and head) and the transposes, so the
-// kernel stays bound by the latent stream for every head-group size, including
-// one latent shared by all 32 heads.
+// kernel stays bound by the latent stream for every head-group size (a latent
+// shared by all 32 heads goes in two blocks of 16 heads, side by side in a
+// workgroup, so that the second read of a row comes from the cache).
 //
 // 4-bit latents: while transposing, a code c is masked in place into the low mantissa bits of an fp16 zero,
 // i.e. becomes the subnormal number c 2^-24 (codes in bits 0 .. 3) or c 2^-20 (bits 4 .. 7): the matrix cores
@@ -40,7 +41,7 @@ struct PvUnit {
   int32_t c0;         // first column of the value-latent row
   uint16_t h0;        // first head
   uint16_t ncols;     // columns (multiple of 32, at most 128 * NG)
-  uint8_t nh;         // heads (at most 32); a head only keeps the columns of its own group
+  uint8_t nh;         // heads (at most 16 in the built forms); a head only keeps the columns of its own group
   uint8_t write_ml;   // this unit stores the (max, sum) pair of its heads
 };
 constexpr int kMaxPvUnits = 128;
@@ -139,7 +140,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 }
 
 // T:  storage type of unquantized latents (bfloat16 is converted to fp16 in registers: exact in the fp16 range)
-// HS: score slots per lane: the unit has at most 2*HS heads (HS = 16: two 16-row tiles)
+// HS: score slots per lane: the unit has at most 2*HS heads (built: 2 and 8; above 8 the code takes two 16-row tiles)
 // NG: 128-column blocks per unit (16 lanes x 8 channels each)
 // QB: latents are QB-bit codes (4, 3 or 2; 0: unquantized); every 128-column block of the unit is one
 //     quantization block.  In the body I4 = "quantized": 3- and 2-bit codes are spread into the
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   struct Set {
     Blk blk[NG];
     float sc[HS][2];
-    uint16_t qs[NA], qz[NA];                       // quantized: scale and zero-point of the lane's softmax token (as loaded: nothing waits on them at the request)
+    uint16_t sz[NA];                               // quantized: scales (lanes 0 .. 31) or zero-points (32 .. 63) of the lane's softmax token, as loaded
   };
 
   // every load is unconditional and in bounds (clamped to the last token / chunk / head);
@@ -260,12 +261,12 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
       st.sc[i][1] = sc_ptr[i][ts + a.part_stride];
     }
     if constexpr (I4) {
+      // the two lanes of a token split its scales and zero-points (2-byte requests cost the memory pipeline as much
+      // as the 8-byte latent ones) and swap them in process()
+      const uint16_t* arr = hp ? a.hv_zero : a.hv_scale;
 #pragma unroll
-      for (int ng = 0; ng < NG; ++ng) {
-        const size_t idx = sz_idx0 + (size_t)ts * a.n_blocks_q + min(ng, n_blk - 1);   // a narrow unit's idle block re-reads block 0
-        st.qs[ng] = a.hv_scale[idx];
-        st.qz[ng] = a.hv_zero[idx];
-      }
+      for (int ng = 0; ng < NG; ++ng)
+        st.sz[ng] = arr[sz_idx0 + (size_t)ts * a.n_blocks_q + min(ng, n_blk - 1)];     // a narrow unit's idle block re-reads block 0
     }
   };
 
@@ -297,10 +298,19 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
     // lazy maximum: probabilities up to 2^kLazy.  Quantized latents carry the scale in the fp16 weights a = p s:
     // with a scale above 128 somewhere in the set the maximum is exact (p <= 1) and a stays in range as before.
     float lazy = kLazy;
+    uint16_t qs[NA], qz[NA];                                   // scales and zero-points of the lane's token
     if constexpr (I4) {
+      uint32_t own = st.sz[0];
+      if constexpr (NA > 1) own |= (uint32_t)st.sz[1] << 16;
+      const uint32_t other = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) * 4, (int)own);
+      const uint32_t sv = hp ? other : own, zv = hp ? own : other;
       bool big = false;
 #pragma unroll
-      for (int g = 0; g < NA; ++g) big |= st.qs[g] > (uint16_t)0x5800;          // fp16 bits of 128 (a negative or NaN scale also lands here)
+      for (int g = 0; g < NA; ++g) {
+        qs[g] = (uint16_t)(sv >> (16 * g));
+        qz[g] = (uint16_t)(zv >> (16 * g));
+        big |= qs[g] > (uint16_t)0x5800;                       // fp16 bits of 128 (a negative or NaN scale also lands here)
+      }
       if (__builtin_amdgcn_ballot_w64(big) != 0) lazy = 0.f;
     }
 #pragma unroll
@@ -347,8 +357,8 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
         lsum[i] += p;
 #pragma unroll
         for (int g = 0; g < NA; ++g) {
-          const float sc = F16::to_float(st.qs[g]);
-          const float zp = F16::to_float(st.qz[g]);
+          const float sc = F16::to_float(qs[g]);
+          const float zp = F16::to_float(qz[g]);
           const _Float16 ah = (_Float16)(p * sc);
           lz[i][g] = fmaf((float)ah, zp, lz[i][g]);
           pw[kPair ? slot + g * 4 * kPitch : g * (MT * 16 * kPitch) + slot] = ah;
@@ -491,8 +501,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   template __global__ void pv_kernel<T, 2, 1, I4>(PvArgs);         \
   template __global__ void pv_kernel<T, 2, 2, I4>(PvArgs);         \
   template __global__ void pv_kernel<T, 8, 1, I4>(PvArgs);         \
-  template __global__ void pv_kernel<T, 8, 2, I4>(PvArgs);         \
-  template __global__ void pv_kernel<T, 16, 1, I4>(PvArgs);
+  template __global__ void pv_kernel<T, 8, 2, I4>(PvArgs);
 PALU_PV_INST(F16, 0)
 PALU_PV_INST(BF16, 0)
 PALU_PV_INST(F16, 4)

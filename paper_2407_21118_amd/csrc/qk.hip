@@ -244,10 +244,22 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
   constexpr int NL = I4 ? 2 : 8;                 // 16-byte loads per tile and chunk: int4 one per 128-column block, else one per 32 columns
   struct Step {
     uint4v h[2][NL];
-    uint16_t qs[2][I4 ? 2 : 1], qz[2][I4 ? 2 : 1];   // quantized: scale and zero-point of (tile token, block), as loaded
+    uint16_t sz[2];            // quantized: the lane's share of the step's scales and zero-points, as loaded (see issue())
   };
   // loads of (set, chunk); clamped to the last token / last valid columns (whose folded query is zero-padded)
   auto issue = [&](Step& st, int set, int chunk) {
+    if constexpr (I4) {
+      // Scales and zero-points of the step's 32 tokens x 2 blocks: the four lanes that share a token column split
+      // them (lane quarter kq: tile kq / 2, scales or zero-points by kq % 2; both blocks), two 2-byte requests per
+      // lane instead of eight, and hand them round in process().  These requests, 16 rows of 2 bytes each,
+      // cost the memory pipeline as much as a 16-byte-per-lane latent request: eight of them per step made the
+      // kernel half as slow again as the latent stream alone.
+      const unsigned t = (unsigned)min(set * 32 + (kq >> 1) * 16 + n, last);
+      const uint16_t* arr = (kq & 1) ? a.hk_zero : a.hk_scale;
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+        st.sz[x] = arr[sz_idx0 + (size_t)t * a.n_blocks_q + min(chunk * 2 + x, n_blk - 1)];
+    }
 #pragma unroll
     for (int tau = 0; tau < 2; ++tau) {
       const unsigned t = (unsigned)min(set * 32 + tau * 16 + n, last);
@@ -257,9 +269,6 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
         if (I4) {
           const int blkc = min(chunk * 2 + x, n_blk - 1);
           off = (unsigned)blkc * 64u + (unsigned)kq * 16u;
-          const size_t idx = sz_idx0 + (size_t)t * a.n_blocks_q + blkc;
-          st.qs[tau][x] = a.hk_scale[idx];
-          st.qz[tau][x] = a.hk_zero[idx];
         } else {
           const int col = min(chunk * 256 + x * 32 + kq * 8, ncols - 8);
           off = (unsigned)col * 2u;
@@ -319,6 +328,14 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
         }
       }
     } else {
+      // the step's scales and zero-points from the four lanes of this token column: [2 tau + (0: scales, 1: zero-points)],
+      // block x in bits 16 x .. 16 x + 15
+      uint32_t szv[4];
+      {
+        const int own = (int)((uint32_t)st.sz[0] | ((uint32_t)st.sz[1] << 16));
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) szv[k4] = (uint32_t)__builtin_amdgcn_ds_bpermute((n + 16 * k4) * 4, own);
+      }
 #pragma unroll
       for (int x = 0; x < 2; ++x) {                // quantization block chunk*2 + x
         const int blkc = min(chunk * 2 + x, n_blk - 1);
@@ -354,8 +371,8 @@ __global__ __launch_bounds__(256, 2) void qk_kernel(QkArgs a) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) d[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[mt][jj], bop, d[mt], 0, 0, 0);
           }
-          const float sc = chunk * 2 + x < n_blk ? F16::to_float(st.qs[tau][x]) : 0.f;
-          const float zp = F16::to_float(st.qz[tau][x]);
+          const float sc = chunk * 2 + x < n_blk ? F16::to_float((uint16_t)(szv[2 * tau] >> (16 * x))) : 0.f;
+          const float zp = F16::to_float((uint16_t)(szv[2 * tau + 1] >> (16 * x)));
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
