@@ -352,7 +352,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
           s.h[p].x = *reinterpret_cast<const uint16_t*>(hk_base + off);
           if (bits == 3) s.h[p].z = hk_base[off + hi_plane - (unsigned)st_col[p]];
         }
-        s.h[p].y = (uint32_t)a.hk_scale[sb] | ((uint32_t)a.hk_zero[sb] << 16);
+        // threads 2k and 2k + 1 hold chunks of the same row and quantization block: one requests the scale, one the
+        // zero-point (a 2-byte request costs the memory pipeline as much as the code request), swapped in store_stage
+        s.h[p].y = ((tid & 1) ? a.hk_zero : a.hk_scale)[sb];
       }
     }
   };
@@ -374,7 +376,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     bool packed = I4;
     if constexpr (I4) {
 #pragma unroll
-      for (int p = 0; p < kPass; ++p) packed = packed && zero_point_is_small_integer((uint16_t)(s.h[p].y >> 16));
+      for (int p = 0; p < kPass; ++p) {
+        const uint32_t own = s.h[p].y & 0xffffu;
+        const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1, 0xf, 0xf, false) & 0xffffu;   // quad_perm [1,0,3,2]
+        s.h[p].y = (tid & 1) ? (other | (own << 16)) : (own | (other << 16));                 // scale | zero-point << 16
+        packed = packed && zero_point_is_small_integer((uint16_t)(s.h[p].y >> 16));
+      }
       packed = __builtin_amdgcn_ballot_w64(!packed) == 0;
     }
     if (packed) {
