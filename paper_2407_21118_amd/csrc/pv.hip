@@ -151,12 +151,12 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   constexpr bool kIsBf16 = !__is_same(T, F16);
   constexpr int MT = HS > 8 ? 2 : 1;
   constexpr int NA = I4 ? NG : 1;                  // scaled probabilities: one set per quantization block
-  // 4-bit codes, four heads, two blocks: a lane takes two neighbouring 8-channel chunks with one 8-byte load
-  // (a load instruction then covers whole 128-byte rows, and a set needs half the requests, which is what
-  // lets three sets be in flight under the 63 outstanding requests a wavefront can count).  The chunks of lanes
+  // Quantized latents, four heads, two blocks: a lane takes two neighbouring 8-channel chunks with one load (8 bytes
+  // of 4-bit codes: a load instruction then covers whole 128-byte rows; 4 bytes of 2-bit fields, plus 2 bytes of
+  // third bits), and a set needs half the requests.  The chunks of lanes
   // n < 8 lie in block 0 and those of lanes n >= 8 in block 1, so one matrix instruction serves both blocks:
   // the probability tile has rows (block, head) - 8 of its 16 - and a lane keeps the rows of its own block.
-  constexpr bool kPair = QB == 4 && NG == 2 && HS == 2;
+  constexpr bool kPair = I4 && NG == 2 && HS == 2;
   constexpr int NT = kPair ? 1 : NA;               // probability tiles
   constexpr int kPitch = 40;                       // halfs per head row: 80-byte pitch, 16-byte reads of 16 rows hit distinct banks
   __shared__ __attribute__((aligned(16))) _Float16 p_lds[4][NT][MT * 16 * kPitch];
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   unsigned coff[NG];
 #pragma unroll
   for (int ng = 0; ng < NG; ++ng) coff[ng] = (unsigned)min(ng * 16 + n, lpt - 1) * (I4 ? (bits == 4 ? 4u : 2u) : 16u);
-  if constexpr (kPair) coff[0] = (unsigned)min(n, (lpt >> 1) - 1) * 8u;      // chunks 2n and 2n + 1 (a unit has a multiple of 4 chunks)
+  if constexpr (kPair) coff[0] = (unsigned)min(n, (lpt >> 1) - 1) * (bits == 4 ? 8u : 4u);      // chunks 2n and 2n + 1 (a unit has a multiple of 4 chunks)
   // byte offset of the row of the lane's token j in set 0; a set further on is 32 rows further, clamped to the last row
   unsigned roff[8];
 #pragma unroll
@@ -237,10 +237,19 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const unsigned char* p = base + (size_t)(min(roff[j] + (unsigned)k * set_bytes, last_off) + coff[ng]);
-        if constexpr (kPair) {
+        if constexpr (kPair && bits == 4) {
           const uint2v v = *reinterpret_cast<const uint2v*>(p);
           st.blk[0].h[j][0] = v.x;
           st.blk[1].h[j][0] = v.y;
+        } else if constexpr (kPair) {
+          const uint32_t v = *reinterpret_cast<const uint32_t*>(p);                 // two chunks' two-bit fields
+          st.blk[0].h[j][0] = v;
+          st.blk[1].h[j][0] = v >> 16;
+          if constexpr (QB == 3) {
+            const uint32_t pl = *reinterpret_cast<const uint16_t*>(p + hi_plane - (coff[0] >> 1));   // their two bytes of third bits
+            st.blk[0].h[j][1] = pl;
+            st.blk[1].h[j][1] = pl >> 8;
+          }
         } else if constexpr (I4) {
           if constexpr (bits == 4) {
             st.blk[ng].h[j][0] = *reinterpret_cast<const uint32_t*>(p);
