@@ -164,7 +164,11 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   constexpr int kCpr = kWidth / 8;                              // 16-byte chunks per tile row
   constexpr int kChunks = kTile * kCpr;                         // chunks per tile
   constexpr int kThreads = NW * 64;
-  constexpr int kPass = (kChunks + kThreads - 1) / kThreads;    // register staging: loads per thread and tile
+  // register staging: a thread takes kCh neighbouring chunks per pass (2- and 3-bit codes: two, i.e. 4 bytes of two-bit
+  // fields and 2 bytes of third bits per request instead of 2 and 1: requests cost per instruction, not per byte)
+  constexpr int kCh = LB ? 2 : 1;
+  static_assert(kCpr % (2 * kCh) == 0, "neighbouring threads stage chunks of one row and quantization block");
+  constexpr int kPass = (kChunks / kCh + kThreads - 1) / kThreads;    // loads per thread and tile
   constexpr int kCsPass = (kExact ? kRopeTileBytes / 16 : kTile * 16) / kThreads;   // register staging: angle chunks per thread and tile
   constexpr int kRowB = kWidth * 2 + kRowPad;                   // LDS row pitch in bytes
   constexpr int kTileB = kTile * kRowB;                         // latent tile bytes
@@ -319,9 +323,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
   int st_row[kPass], st_col[kPass];
 #pragma unroll
   for (int p = 0; p < kPass; ++p) {
-    const int id = min(p * kThreads + tid, kChunks - 1);        // surplus threads repeat the last chunk
-    st_row[p] = id / kCpr;
-    st_col[p] = id - st_row[p] * kCpr;
+    const int id = min(p * kThreads + tid, kChunks / kCh - 1);  // surplus threads repeat the last chunk (pair)
+    st_row[p] = id / (kCpr / kCh);
+    st_col[p] = (id - st_row[p] * (kCpr / kCh)) * kCh;
   }
   // the angle tile's 1024 chunks, chunk x * kThreads + tid per pass (row = chunk / 16, piece = chunk % 16)
   struct Stage {
@@ -349,8 +353,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
           s.h[p].x = *reinterpret_cast<const uint32_t*>(hk_base + off);
         } else {
           const unsigned off = __umul24(rel, row_bytes) + (unsigned)st_col[p] * 2u;
-          s.h[p].x = *reinterpret_cast<const uint16_t*>(hk_base + off);
-          if (bits == 3) s.h[p].z = hk_base[off + hi_plane - (unsigned)st_col[p]];
+          s.h[p].x = *reinterpret_cast<const uint32_t*>(hk_base + off);                                          // chunks st_col, st_col + 1
+          if (bits == 3) s.h[p].z = *reinterpret_cast<const uint16_t*>(hk_base + off + hi_plane - (unsigned)st_col[p]);
         }
         // threads 2k and 2k + 1 hold chunks of the same row and quantization block: one requests the scale, one the
         // zero-point (a 2-byte request costs the memory pipeline as much as the code request), swapped in store_stage
@@ -387,19 +391,25 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs a) {
     if (packed) {
 #pragma unroll
       for (int p = 0; p < kPass; ++p) {
-        const uint32_t codes = !LB ? s.h[p].x : expand_low_bits(s.h[p].x, s.h[p].z, bits == 3);
-        const uint4v v = dequant8_packed(codes, (uint16_t)(s.h[p].y & 0xffffu), (uint16_t)(s.h[p].y >> 16), k1024);
-        if (p * kThreads + tid < kChunks) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + st_col[p] * 16) = v;
+#pragma unroll
+        for (int c = 0; c < kCh; ++c) {
+          const uint32_t codes = !LB ? s.h[p].x : expand_low_bits(s.h[p].x >> (16 * c), s.h[p].z >> (8 * c), bits == 3);
+          const uint4v v = dequant8_packed(codes, (uint16_t)(s.h[p].y & 0xffffu), (uint16_t)(s.h[p].y >> 16), k1024);
+          if (p * kThreads + tid < kChunks / kCh) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + (st_col[p] + c) * 16) = v;
+        }
       }
     } else {
 #pragma unroll
       for (int p = 0; p < kPass; ++p) {
-        uint4v v = s.h[p];
-        if (I4) {
-          const uint32_t codes = !LB ? v.x : expand_low_bits(v.x, v.z, bits == 3);
-          v = dequant8_float(codes, (uint16_t)(v.y & 0xffffu), (uint16_t)(v.y >> 16));
+#pragma unroll
+        for (int c = 0; c < kCh; ++c) {
+          uint4v v = s.h[p];
+          if (I4) {
+            const uint32_t codes = !LB ? v.x : expand_low_bits(v.x >> (16 * c), v.z >> (8 * c), bits == 3);
+            v = dequant8_float(codes, (uint16_t)(v.y & 0xffffu), (uint16_t)(v.y >> 16));
+          }
+          if (p * kThreads + tid < kChunks / kCh) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + (st_col[p] + c) * 16) = v;
         }
-        if (p * kThreads + tid < kChunks) *reinterpret_cast<uint4v*>(base + st_row[p] * kRowB + st_col[p] * 16) = v;
       }
     }
   };
