@@ -115,3 +115,22 @@ def test_transposed_weight_entry_points_refuse_what_they_do_not_do():
     assert lib.palu_decode_step_t(d.ref(), 64, 8, 8, *args) == -2
     assert lib.palu_decode_step_t(d.ref(), 0, 8, 8, *args) == -1
     assert lib.palu_decode_step_t(dq.ref(), 1, 8, 8, *args) == -2
+
+
+def test_options_are_validated_on_the_host():
+    """palu_set_option: unknown names, NULL and out-of-range values are refused (-1) and leave the setting alone;
+    the documented values are accepted.  Every option is put back to its default."""
+    lib = P.load_library()
+    assert lib.palu_set_option(None, 0) == -1
+    assert lib.palu_set_option(b"no_such_option", 1) == -1
+    assert lib.palu_set_option(b"score_mixed", -1) == -1
+    for name, good, bad, default in ((b"score_mixed", (0, 1, 3, 16), (17,), 1), (b"score_waves", (0, 4, 8), (3, 16), 0),
+                                     (b"value_split_tokens", (0, 32, 4096), (48, 8192), 0), (b"score_fp8", (0, 1), (2,), 0),
+                                     (b"shared_key_fp16", (0, 1), (2,), 0), (b"encode_tile_rows", (0, 32, 256), (48,), 0)):
+        try:
+            for v in good:
+                assert lib.palu_set_option(name, v) == 0, (name, v)
+            for v in bad:
+                assert lib.palu_set_option(name, v) == -1, (name, v)
+        finally:
+            assert lib.palu_set_option(name, default) == 0
