@@ -606,21 +606,25 @@ Meta kv_head_meta(const Meta& m) {
 }
 
 using PvFn = void (*)(PvArgs);
-template <typename T, int QB>
+template <typename T, int QB, bool TWO>
 PvFn pv_fn_t(int cls) {
   switch (cls) {
-    case 0: return pv_kernel<T, 2, 1, QB>;
-    case 1: return pv_kernel<T, 2, 2, QB>;
-    case 2: return pv_kernel<T, 8, 1, QB>;
-    default: return pv_kernel<T, 8, 2, QB>;
+    case 0: return pv_kernel<T, 2, 1, QB, TWO>;
+    case 1: return pv_kernel<T, 2, 2, QB, TWO>;
+    case 2: return pv_kernel<T, 8, 1, QB, TWO>;
+    default: return pv_kernel<T, 8, 2, QB, TWO>;
   }
 }
-// bits: 4, 3 or 2 for quantized value latents, else 0
-PvFn pv_fn(int act, int bits, int cls) {
-  if (bits == 4) return pv_fn_t<F16, 4>(cls);
-  if (bits == 3) return pv_fn_t<F16, 3>(cls);
-  if (bits == 2) return pv_fn_t<F16, 2>(cls);
-  return act == PALU_F16 ? pv_fn_t<F16, 0>(cls) : pv_fn_t<BF16, 0>(cls);
+template <bool TWO>
+PvFn pv_fn_p(int act, int bits, int cls) {
+  if (bits == 4) return pv_fn_t<F16, 4, TWO>(cls);
+  if (bits == 3) return pv_fn_t<F16, 3, TWO>(cls);
+  if (bits == 2) return pv_fn_t<F16, 2, TWO>(cls);
+  return act == PALU_F16 ? pv_fn_t<F16, 0, TWO>(cls) : pv_fn_t<BF16, 0, TWO>(cls);
+}
+// bits: 4, 3 or 2 for quantized value latents, else 0; two_planes: some head's scores lie in two planes
+PvFn pv_fn(int act, int bits, int cls, bool two_planes) {
+  return two_planes ? pv_fn_p<true>(act, bits, cls) : pv_fn_p<false>(act, bits, cls);
 }
 
 // First launch of a fused decode step: the split-K partial products of the new token's down-projection
@@ -1697,7 +1701,11 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
     a.n_split = n_split;
     a.o_stride = w.o_stride;
     a.n_blocks_q = Rv / quant_block;
-    for (int h = 0; h < PALU_MAX_HEADS; ++h) a.n_parts[h] = (uint8_t)(n_parts[h] > 2 ? 1 : n_parts[h]);
+    bool two_planes = false;
+    for (int h = 0; h < PALU_MAX_HEADS; ++h) {
+      a.n_parts[h] = (uint8_t)(n_parts[h] > 2 ? 1 : n_parts[h]);
+      two_planes |= a.n_parts[h] == 2;
+    }
     a.meta = m;
     for (int cls = 0; cls < kNumPvCls; ++cls) {
       auto flush = [&]() -> int {
@@ -1705,7 +1713,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
         a.units_per_wg = a.units.n_units >= 4 ? 4 : (a.units.n_units >= 2 ? 2 : 1);
         const dim3 grid((unsigned)ceil_div(a.units.n_units, a.units_per_wg), (unsigned)ceil_div(n_split, 4 / a.units_per_wg),
                         (unsigned)batch);
-        hipLaunchKernelGGL(pv_fn(act, v_bits, cls), grid, dim3(256), 0, s, a);
+        hipLaunchKernelGGL(pv_fn(act, v_bits, cls, two_planes), grid, dim3(256), 0, s, a);
         a.units.n_units = 0;
         return launch_ok();
       };

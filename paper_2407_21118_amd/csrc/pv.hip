@@ -145,7 +145,9 @@ __device__ __forceinline__ void wave_lds_fence() {
 // QB: latents are QB-bit codes (4, 3 or 2; 0: unquantized); every 128-column block of the unit is one
 //     quantization block.  In the body I4 = "quantized": 3- and 2-bit codes are spread into the
 //     4-bit register layout when they are consumed and then follow the 4-bit arithmetic.
-template <typename T, int HS, int NG, int QB>
+// TWO: some head of the launch has two score planes (the kernel then requests both planes of every head; with one
+//     plane everywhere the second request, an instruction per head slot and set, is left out)
+template <typename T, int HS, int NG, int QB, bool TWO>
 __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(PvArgs a) {
   constexpr bool I4 = QB != 0;
   constexpr bool kIsBf16 = !__is_same(T, F16);
@@ -224,7 +226,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   };
   struct Set {
     Blk blk[NG];
-    float sc[HS][2];
+    float sc[HS][TWO ? 2 : 1];
     uint16_t sz[NA];                               // quantized: scales (lanes 0 .. 31) or zero-points (32 .. 63) of the lane's softmax token, as loaded
   };
 
@@ -267,7 +269,7 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
 #pragma unroll
     for (int i = 0; i < HS; ++i) {
       st.sc[i][0] = sc_ptr[i][ts];
-      st.sc[i][1] = sc_ptr[i][ts + a.part_stride];
+      if constexpr (TWO) st.sc[i][1] = sc_ptr[i][ts + a.part_stride];
     }
     if constexpr (I4) {
       // the two lanes of a token split its scales and zero-points (2-byte requests cost the memory pipeline as much
@@ -324,7 +326,8 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
     }
 #pragma unroll
     for (int i = 0; i < HS; ++i) {
-      const float v = st.sc[i][0] + (two[i] ? st.sc[i][1] : 0.f);
+      float v = st.sc[i][0];
+      if constexpr (TWO) v += two[i] ? st.sc[i][1] : 0.f;
       s[i] = (tok_ok && hp + 2 * i < nh && k * 32 + tl < lim[i]) ? v : -INFINITY;
       bm[i] = half_wave_max(s[i]);
       grew |= bm[i] > mx[i] + lazy;
@@ -506,11 +509,12 @@ __global__ __launch_bounds__(256, (QB != 0 && HS <= 2) ? 2 : 1) void pv_kernel(P
   }
 }
 
-#define PALU_PV_INST(T, I4)                                        \
-  template __global__ void pv_kernel<T, 2, 1, I4>(PvArgs);         \
-  template __global__ void pv_kernel<T, 2, 2, I4>(PvArgs);         \
-  template __global__ void pv_kernel<T, 8, 1, I4>(PvArgs);         \
-  template __global__ void pv_kernel<T, 8, 2, I4>(PvArgs);
+#define PALU_PV_INST2(T, I4, TWO)                                      \
+  template __global__ void pv_kernel<T, 2, 1, I4, TWO>(PvArgs);         \
+  template __global__ void pv_kernel<T, 2, 2, I4, TWO>(PvArgs);         \
+  template __global__ void pv_kernel<T, 8, 1, I4, TWO>(PvArgs);         \
+  template __global__ void pv_kernel<T, 8, 2, I4, TWO>(PvArgs);
+#define PALU_PV_INST(T, I4) PALU_PV_INST2(T, I4, true) PALU_PV_INST2(T, I4, false)
 PALU_PV_INST(F16, 0)
 PALU_PV_INST(BF16, 0)
 PALU_PV_INST(F16, 4)
