@@ -1517,10 +1517,13 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       bool use_one_round = false;
       double mix_per_wg = 0.0;
       long long mix_chunk_limit_tiles = 1;
-      static const double kCost[9] = {0, 0, 30, 33, 36, 37, 51, 58, 56};   // measured: microseconds per 1000 tokens of one workgroup by rank / 32
+      // measured (uniform layers of each rank, 2048- and 1024-token chunks with every compute unit busy): microseconds per
+      // 1000 tokens of one workgroup by rank / 32; ranks below 256 request their latent rows one per instruction, which
+      // is why 224 costs more than 256
+      static const double kCost[9] = {0, 0, 30, 34, 38, 47, 54, 63, 56};
       auto weight = [](int nk) { return kCost[nk]; };
       if (mixed) {
-        constexpr double kStartUs = 8.5;                         // measured: microseconds from a workgroup's start to its first tile and after its last
+        constexpr double kStartUs = 7.5;                         // measured: a launch's start plus a workgroup's own (weights into registers, tile ring filled, last tile drained)
         for (int cls = 0; cls < plan.n_cls; ++cls) order[cls] = cls;
         std::sort(order, order + plan.n_cls, [&](int x, int y) { return plan.cls_id[x] > plan.cls_id[y]; });
         for (int i = 0; i < plan.total_units; ++i) ++n_units_cls[plan.unit_cls[i]];
