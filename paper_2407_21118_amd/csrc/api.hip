@@ -1518,9 +1518,8 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
       double mix_per_wg = 0.0;
       long long mix_chunk_limit_tiles = 1;
       // measured (uniform layers of each rank, 2048- and 1024-token chunks with every compute unit busy): microseconds per
-      // 1000 tokens of one workgroup by rank / 32; ranks below 256 request their latent rows one per instruction, which
-      // is why 224 costs more than 256
-      static const double kCost[9] = {0, 0, 30, 34, 38, 47, 54, 63, 56};
+      // 1000 tokens of one workgroup by rank / 32
+      static const double kCost[9] = {0, 0, 30, 34, 38, 43, 47, 53, 56};
       auto weight = [](int nk) { return kCost[nk]; };
       if (mixed) {
         constexpr double kStartUs = 7.5;                         // measured: a launch's start plus a workgroup's own (weights into registers, tile ring filled, last tile drained)
@@ -1598,7 +1597,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
                    : shared16 ? nullptr            // chosen per pass below
                    : k16 ? (act == PALU_F16 ? score16_fn_t<F16>(rc, lg) : score16_fn_t<BF16>(rc, lg))
                    : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, rc * 3 + lg, waves8));
-        if (k16) lds = (size_t)score16_lds_bytes(width);
+        if (k16) lds = (size_t)score16_lds_bytes(width, 1 << lg);
         if (shared16 || shared4) {
           if (shared4) lds = (size_t)score16q4_lds_bytes(width);
           // exact shared-key form: passes of up to sk_pass_rows query rows of every key/value head, each pass one
