@@ -1597,7 +1597,7 @@ static int decode_impl(const palu_layer_desc* desc, int32_t batch, int32_t n_q, 
                    : shared16 ? nullptr            // chosen per pass below
                    : k16 ? (act == PALU_F16 ? score16_fn_t<F16>(rc, lg) : score16_fn_t<BF16>(rc, lg))
                    : (k_lowbit ? score_fn_lowbit(rc) : score_fn(act, k_i4, rc * 3 + lg, waves8));
-        if (k16) lds = (size_t)score16_lds_bytes(width, 1 << lg);
+        if (k16) lds = (size_t)score16_lds_bytes(width);
         if (shared16 || shared4) {
           if (shared4) lds = (size_t)score16q4_lds_bytes(width);
           // exact shared-key form: passes of up to sk_pass_rows query rows of every key/value head, each pass one

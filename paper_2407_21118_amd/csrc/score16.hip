@@ -29,13 +29,11 @@
 
 namespace palu {
 
-// Columns a latent tile row takes in LDS: `width` (= groups x rank), except that one group's row of 160 .. 224 columns
-// is laid out in the 32 slots of a 256-column row (its rows are requested two per instruction like those).
-constexpr int score16_lds_width(int width, int groups, bool staged) {
-  return (!staged && groups == 1 && width > 128 && width < 256) ? 256 : width;
-}
-// LDS bytes of score16_kernel for a tile row of `width` columns of `groups` groups (shared with the host)
-constexpr int score16_lds_bytes(int width, int groups = 1) { return score_lds_bytes(score16_lds_width(width, groups, false), true, true, false); }
+// Columns a latent tile row takes in LDS: the rows of unquantized latents (at most 256 columns: groups x rank) are
+// laid out in the 32 slots of a 256-column row, whatever their width, and requested two per instruction.
+constexpr int score16_lds_width(int width, bool staged) { return staged ? width : 256; }
+// LDS bytes of score16_kernel for unquantized latents (shared with the host)
+constexpr int score16_lds_bytes(int width) { return score_lds_bytes(score16_lds_width(width, false), true, true, false); }
 
 // part[j], j = 0..3, belongs to token 4 (lane / 16) + j of a 16-token sub-tile and to the feature this lane
 // owns (lane % 16).  Returns the sum over the 16 lanes of the row of ONE of the lane's tokens:
